@@ -1,0 +1,216 @@
+/*
+ * kge_mi355 — C ABI of one training step of a partitioned RGCN + DistMult
+ * knowledge-graph-embedding trainer on one AMD MI355X (gfx950).
+ *
+ * The calls follow the training procedure of "Scaling Knowledge Graph
+ * Embedding Models" (arXiv 2201.02791), Algorithm 1, for ONE trainer working
+ * on ONE self-sufficient partition:
+ *
+ *   kge_build_partition      Sec. 3.2.1 (core edges) + Sec. 3.2.2 (n-hop
+ *                            Neighborhood Expansion); once per partition
+ *   kge_rgcn_forward         Eq. 1 with the basis decomposition of Eq. 2
+ *   kge_sample_negatives     Sec. 2.1 (corrupt s or t) under the in-partition
+ *                            constraint of Sec. 3.3.1
+ *   kge_distmult_score_loss  Eq. 4 (DistMult) and Eq. 3 (cross entropy), with
+ *                            the gradients with respect to embeddings and M_r
+ *   kge_rgcn_backward        chain rule on Eq. 1-2 (Algorithm 1, "backward")
+ *
+ * General rules
+ *  - Every function returns KGE_OK (0) or a negative kge_status; on error no
+ *    output is valid and kge_last_error() holds a message for this thread.
+ *  - "device" pointers are HIP device memory on the partition's GPU, owned by
+ *    the caller; "host" pointers are ordinary host memory.  The library owns
+ *    only kge_partition objects.  The four per-step calls allocate nothing,
+ *    never synchronise with the host, and run asynchronously on `stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream).
+ *  - Row vectors: h is 1 x d, V_b is d_in x d_out, a projection is h V_b.
+ *  - Local vertex ids are ranks of global ids inside the partition.
+ *    Relation ids 0..R-1 are the given direction, R..2R-1 the inverses; the
+ *    self-loop is the dense W_0 term, not an edge.
+ *  - All matrices are dense row-major.  Feature widths must be multiples of 4
+ *    (of 8 when msg_dtype = KGE_MSG_BF16) and at most 256 (512 for bf16).
+ */
+#ifndef KGE_MI355_H
+#define KGE_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum kge_status {
+    KGE_OK = 0,
+    KGE_EINVAL = -1,  /* null pointer, bad shape, bad enum value            */
+    KGE_ENOMEM = -2,  /* allocation failed, or the workspace is too small    */
+    KGE_EHIP = -3,    /* a HIP call failed; see kge_last_error()             */
+    KGE_ERANGE = -4   /* an id is out of range, or a size exceeds 2^31-1     */
+} kge_status;
+
+enum { KGE_ACT_IDENTITY = 0, KGE_ACT_RELU = 1 };
+enum { KGE_MSG_F32 = 0, KGE_MSG_BF16 = 1 };      /* storage type of projected messages        */
+enum { KGE_NEG_TAIL = 0, KGE_NEG_HEAD_OR_TAIL = 1 };
+enum { KGE_DOMAIN_CORE = 0, KGE_DOMAIN_ALL = 1 };
+
+typedef struct kge_partition kge_partition;      /* opaque; device resident; library owned    */
+
+typedef struct kge_part_info {
+    int64_t n_vert;        /* N: vertices after expansion (numerator term of Eq. 7)            */
+    int64_t n_edge;        /* E: message edges kept                                             */
+    int64_t n_seg;         /* S: distinct (relation, destination) pairs                         */
+    int64_t n_core;        /* core edges = positive triples of this partition                   */
+    int64_t n_cand;        /* vertices negatives may be drawn from                              */
+    int64_t n_triples;     /* triples of the whole graph                                        */
+    int32_t n_entities, n_relations, n_parts, part_id, n_hops, neg_domain;
+    int32_t max_in_degree; /* largest number of message edges into one vertex                   */
+    int32_t max_out_degree;
+} kge_part_info;
+
+/* One RGCN layer (Eq. 1-2).  Device pointers, caller owned, never written. */
+typedef struct kge_layer {
+    int32_t d_in, d_out, n_bases, act;   /* act: KGE_ACT_*                                     */
+    const float *V;    /* [n_bases][d_in][d_out]   basis matrices V_b                          */
+    const float *a;    /* [2R][n_bases]            coefficients a_rb                           */
+    const float *W0;   /* [d_in][d_out]            self-loop weight                            */
+} kge_layer;
+
+/* Gradients of one layer; device pointers, caller owned, overwritten. */
+typedef struct kge_layer_grad {
+    float *dV;   /* [n_bases][d_in][d_out] */
+    float *da;   /* [2R][n_bases]          */
+    float *dW0;  /* [d_in][d_out]          */
+} kge_layer_grad;
+
+/* Arrays kge_partition_export can copy out (all 4-byte elements). */
+typedef enum kge_array {
+    KGE_ARR_VERT_GID = 0,  /* int32 [N]    global id of each local vertex, ascending           */
+    KGE_ARR_CORE_EID = 1,  /* int32 [n_core] index of each core triple in the input lists       */
+    KGE_ARR_CORE_H = 2,    /* int32 [n_core] local head                                        */
+    KGE_ARR_CORE_R = 3,    /* int32 [n_core] relation (0..R-1)                                 */
+    KGE_ARR_CORE_T = 4,    /* int32 [n_core] local tail                                        */
+    KGE_ARR_SEG_PTR = 5,   /* int32 [S+1]  edge range of each (relation, destination) run      */
+    KGE_ARR_SEG_REL = 6,   /* int32 [S]                                                        */
+    KGE_ARR_SEG_DST = 7,   /* int32 [S]    local destination                                   */
+    KGE_ARR_INV_C = 8,     /* float [S]    1 / c_{i,r} = 1.0f / run length                     */
+    KGE_ARR_COL_SRC = 9,   /* int32 [E]    local source, edges sorted by (rel, dst, src, id)   */
+    KGE_ARR_EDGE_ID = 10,  /* int32 [E]    message-edge id: triple i -> i, its inverse -> M+i  */
+    KGE_ARR_CAND = 11,     /* int32 [n_cand] local ids, ascending                              */
+    KGE_ARR_DM_PTR = 12,   /* int32 [N+1]  destination-major view: edge range per destination  */
+    KGE_ARR_DM_SRC = 13,   /* int32 [E]    source of each edge, ordered by (dst, rel, src, id) */
+    KGE_ARR_DM_REL = 14,   /* int32 [E]                                                        */
+    KGE_ARR_DM_INVC = 15,  /* float [E]    1 / c of the edge's run                             */
+    KGE_ARR_SM_PTR = 16,   /* int32 [N+1]  source-major view: edge range per source            */
+    KGE_ARR_SM_DST = 17,   /* int32 [E]    destination, ordered by (src, rel, dst, id)         */
+    KGE_ARR_SM_REL = 18,   /* int32 [E]                                                        */
+    KGE_ARR_SM_INVC = 19,  /* float [E]                                                        */
+    KGE_ARR_REL_PTR = 20   /* int32 [2R+1] run range of each relation                          */
+} kge_array;
+
+/*
+ * Build partition `part_id` of `n_parts` (Sec. 3.2).
+ *   head, rel, tail : HOST int32 [n_triples], the whole graph's training triples (s, r, t);
+ *                     entity ids in [0, n_entities), relation ids in [0, n_relations).
+ *   Core edges (the positives, Sec. 3.2.1) are the triples with
+ *       ((uint32)head * 0x9E3779B1u >> 8) mod n_parts == part_id
+ *   (a hash stands in for the paper's vertex-cut partitioner: disjoint cover of the edges).
+ *   Expansion (Sec. 3.2.2): S_0 = endpoints of core edges; S_k = S_{k-1} plus the sources of
+ *   all message edges into S_{k-1}; the partition keeps the vertices S_{n_hops} and every
+ *   message edge whose destination is in S_{n_hops-1}.  n_hops = number of GNN layers.
+ *   neg_domain: KGE_DOMAIN_CORE = negatives drawn from endpoints of core edges (Sec. 3.3.1),
+ *               KGE_DOMAIN_ALL  = from every vertex of the partition.
+ *   The edges are sorted on the GPU by (relation, destination, source, message-edge id);
+ *   c_{i,r} of Eq. 1 is the length of a (relation, destination) run, with multiplicity.
+ *   *out receives a new partition living on the current HIP device; free it with
+ *   kge_partition_destroy.  Synchronous.  KGE_ERANGE if an id is out of range or the packed
+ *   sort key (bits(2R) + 2 bits(N)) exceeds 64 bits.
+ */
+int kge_build_partition(const int32_t *head, const int32_t *rel, const int32_t *tail,
+                        int64_t n_triples, int32_t n_entities, int32_t n_relations,
+                        int32_t n_parts, int32_t part_id, int32_t n_hops, int32_t neg_domain,
+                        kge_partition **out);
+
+int kge_partition_info(const kge_partition *p, kge_part_info *out);
+
+/* Copy one array to HOST memory `host_dst` of `bytes` bytes (must equal 4 * its length).
+ * Synchronous. */
+int kge_partition_export(const kge_partition *p, int32_t which, void *host_dst, int64_t bytes);
+
+void kge_partition_destroy(kge_partition *p);
+
+/* Bytes of device workspace kge_rgcn_forward / kge_rgcn_backward need for these layers.
+ * Returns 0 on invalid arguments (kge_last_error explains). */
+size_t kge_workspace_bytes(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
+                           int32_t msg_dtype);
+
+/*
+ * Encoder forward over the whole partition (Eq. 1-2), for l = 1..n_layers:
+ *   P_l[j][b][:] = h_j V_b (stored as msg_dtype),  pre_i = sum_r sum_{j in N_i^r} (1/c_ir)
+ *   sum_b a_rb P_l[j][b][:] + h_i W_0,  h'_i = act(pre_i)   (fp32 accumulation throughout).
+ *   layers    : HOST array of n_layers descriptors (their pointers are device memory);
+ *               layers[l].d_in must equal layers[l-1].d_out.
+ *   H0        : device float [N][layers[0].d_in]
+ *   workspace : device, >= kge_workspace_bytes(...), 256-byte aligned; keeps what backward needs
+ *   H_out     : device float [N][layers[n_layers-1].d_out]
+ */
+int kge_rgcn_forward(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
+                     int32_t msg_dtype, const float *H0, void *workspace, size_t ws_bytes,
+                     float *H_out, void *stream);
+
+/*
+ * Encoder backward.  Must follow kge_rgcn_forward with the same arguments and the same,
+ * unmodified workspace.
+ *   dH_out : device float [N][d_out of last layer], dL/dH_out (e.g. from kge_distmult_score_loss);
+ *            left unchanged
+ *   grads  : HOST array of n_layers kge_layer_grad (device pointers); every array is overwritten
+ *   dH0    : device float [N][layers[0].d_in] or NULL (NULL when the layer-1 input is a fixed
+ *            feature matrix and needs no gradient)
+ */
+int kge_rgcn_backward(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
+                      int32_t msg_dtype, const float *H0, void *workspace, size_t ws_bytes,
+                      const float *dH_out, const kge_layer_grad *grads, float *dH0, void *stream);
+
+/*
+ * Negatives for a batch of positives (Sec. 2.1, Sec. 3.3.1).  For positive q (core-edge index
+ * c = pos_core_idx[q]) and slot k:
+ *   x = Philox4x32-10(counter = (c, k, step lo32, step hi32), key = (seed lo32, seed hi32))
+ *   neg_ent[q][k]  = cand[(x0 * n_cand) >> 32]                    (a local vertex id)
+ *   neg_side[q][k] = 1 (head replaced) if mode = KGE_NEG_HEAD_OR_TAIL and x1 >= 2^31,
+ *                    else 0 (tail replaced)
+ * No filtering against true triples.  pos_core_idx: device int32 [n_pos], values in
+ * [0, n_core) (not checked on the device; the draw only uses them as counter words).
+ * neg_ent: device int32 [n_pos][n_neg]; neg_side: device uint8 [n_pos][n_neg].
+ * KGE_EINVAL if the partition has no candidate vertex and n_pos * n_neg > 0.
+ */
+int kge_sample_negatives(const kge_partition *p, const int32_t *pos_core_idx, int64_t n_pos,
+                         int32_t n_neg, int32_t mode, uint64_t seed, uint64_t step,
+                         int32_t *neg_ent, uint8_t *neg_side, void *stream);
+
+/*
+ * DistMult score (Eq. 4), cross-entropy loss (Eq. 3, minimised form with the leading minus)
+ * and gradients, fused.  Scored triples are positive-major: row q = [positive, negative 0 ..
+ * n_neg-1]; |T| = n_pos (1 + n_neg).
+ *   g = sum_k h_s[k] M_r[k] h_t[k];  loss = (1/|T|) sum softplus(-g) [y=1] or softplus(g) [y=0]
+ *   delta = (sigmoid(g) - y)/|T|;  dH[s] += delta M_r*h_t;  dH[t] += delta M_r*h_s;
+ *   dM[r] += delta h_s*h_t
+ *   H      : device float [N][d]          M : device float [R][d]
+ *   pos_core_idx : device int32 [n_pos], each in [0, n_core)
+ *   neg_ent / neg_side : as written by kge_sample_negatives, entries in [0, N)
+ *   scores : device float [n_pos][1+n_neg] or NULL
+ *   loss   : device float [1]
+ *   dH     : device float [N][d], zeroed by this call, then accumulated
+ *   dM     : device float [R][d], zeroed by this call, then accumulated
+ * Accumulation uses fp32 atomics, so low-order bits can differ from run to run.
+ */
+int kge_distmult_score_loss(const kge_partition *p, const float *H, const float *M, int32_t d,
+                            const int32_t *pos_core_idx, int64_t n_pos, const int32_t *neg_ent,
+                            const uint8_t *neg_side, int32_t n_neg, float *scores, float *loss,
+                            float *dH, float *dM, void *stream);
+
+/* Message of the last failure on the calling thread ("" if none). */
+const char *kge_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KGE_MI355_H */

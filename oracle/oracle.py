@@ -195,9 +195,10 @@ def distmult_score_loss(part, H, M, pos_core_idx, neg_ent, neg_side):
     pos = np.ascontiguousarray(pos_core_idx, np.int64)
     ph = np.ascontiguousarray(part["core_h"][pos]); pr = np.ascontiguousarray(part["core_r"][pos])
     pt = np.ascontiguousarray(part["core_t"][pos])
-    neg_ent = np.ascontiguousarray(neg_ent, np.int32).reshape(len(pos), -1)
-    neg_side = np.ascontiguousarray(neg_side, np.uint8).reshape(len(pos), -1)
-    n_neg = neg_ent.shape[1]
+    neg_ent = np.ascontiguousarray(neg_ent, np.int32)
+    n_neg = neg_ent.shape[1] if neg_ent.ndim == 2 else neg_ent.size // max(len(pos), 1)
+    neg_ent = neg_ent.reshape(len(pos), n_neg)
+    neg_side = np.ascontiguousarray(neg_side, np.uint8).reshape(len(pos), n_neg)
     scores = np.zeros((len(pos), 1 + n_neg)); loss = np.zeros(1)
     dH = np.zeros((N, d)); dM = np.zeros_like(M)
     lib().orc_distmult_score_loss(C.c_int64(N), C.c_int32(d), C.c_int32(M.shape[0]), _p(H, _F64),

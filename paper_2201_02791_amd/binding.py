@@ -1,0 +1,204 @@
+"""Thin ctypes binding of ``libkge_mi355.so``: argument marshalling only.
+
+Function names mirror the C ABI (``include/kge_mi355.h``) without the ``kge_`` prefix.
+PyTorch is used for device memory and streams; every step of the training path runs in
+the library's HIP kernels.  There is no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libkge_mi355.so")
+_lib = None
+
+EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
+            "kge_partition_destroy", "kge_workspace_bytes", "kge_rgcn_forward",
+            "kge_rgcn_backward", "kge_sample_negatives", "kge_distmult_score_loss",
+            "kge_last_error"]
+
+ACT_IDENTITY, ACT_RELU = 0, 1
+MSG_F32, MSG_BF16 = 0, 1
+NEG_TAIL, NEG_HEAD_OR_TAIL = 0, 1
+DOMAIN_CORE, DOMAIN_ALL = 0, 1
+
+ARRAYS = {"vert_gid": (0, np.int32), "core_eid": (1, np.int32), "core_h": (2, np.int32),
+          "core_r": (3, np.int32), "core_t": (4, np.int32), "seg_ptr": (5, np.int32),
+          "seg_rel": (6, np.int32), "seg_dst": (7, np.int32), "inv_c": (8, np.float32),
+          "col_src": (9, np.int32), "edge_id": (10, np.int32), "cand": (11, np.int32),
+          "dm_ptr": (12, np.int32), "dm_src": (13, np.int32), "dm_rel": (14, np.int32),
+          "dm_invc": (15, np.float32), "sm_ptr": (16, np.int32), "sm_dst": (17, np.int32),
+          "sm_rel": (18, np.int32), "sm_invc": (19, np.float32), "rel_ptr": (20, np.int32)}
+
+
+class KgeError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__("kge status %d: %s" % (status, msg))
+        self.status = status
+
+
+class _PartInfo(C.Structure):
+    _fields_ = [("n_vert", C.c_int64), ("n_edge", C.c_int64), ("n_seg", C.c_int64),
+                ("n_core", C.c_int64), ("n_cand", C.c_int64), ("n_triples", C.c_int64),
+                ("n_entities", C.c_int32), ("n_relations", C.c_int32), ("n_parts", C.c_int32),
+                ("part_id", C.c_int32), ("n_hops", C.c_int32), ("neg_domain", C.c_int32),
+                ("max_in_degree", C.c_int32), ("max_out_degree", C.c_int32)]
+
+
+class _Layer(C.Structure):
+    _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("n_bases", C.c_int32), ("act", C.c_int32),
+                ("V", C.c_void_p), ("a", C.c_void_p), ("W0", C.c_void_p)]
+
+
+class _LayerGrad(C.Structure):
+    _fields_ = [("dV", C.c_void_p), ("da", C.c_void_p), ("dW0", C.c_void_p)]
+
+
+def load():
+    """Load the shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is missing: run `python -m paper_2201_02791_amd.build` "
+                              "(there is no CPU fallback)" % LIB_PATH)
+        lib = C.CDLL(LIB_PATH)
+        lib.kge_last_error.restype = C.c_char_p
+        lib.kge_workspace_bytes.restype = C.c_size_t
+        lib.kge_partition_destroy.restype = None
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise KgeError(rc, load().kge_last_error().decode())
+
+
+def _ptr(t) -> C.c_void_p:
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+class Partition:
+    """Owner of a ``kge_partition*``."""
+
+    def __init__(self, handle):
+        self._h = C.c_void_p(handle)
+        info = _PartInfo()
+        _check(load().kge_partition_info(self._h, C.byref(info)))
+        for name, _ in _PartInfo._fields_:
+            setattr(self, name, int(getattr(info, name)))
+
+    @property
+    def handle(self):
+        return self._h
+
+    def export(self, name: str) -> np.ndarray:
+        return partition_export(self, name)
+
+    def destroy(self):
+        if self._h is not None and self._h.value:
+            load().kge_partition_destroy(self._h)
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def build_partition(head, rel, tail, n_entities: int, n_relations: int, n_parts: int = 1,
+                    part_id: int = 0, n_hops: int = 2, neg_domain: int = DOMAIN_CORE) -> Partition:
+    head = np.ascontiguousarray(head, np.int32)
+    rel = np.ascontiguousarray(rel, np.int32)
+    tail = np.ascontiguousarray(tail, np.int32)
+    assert len(head) == len(rel) == len(tail)
+    out = C.c_void_p()
+    _check(load().kge_build_partition(head.ctypes.data_as(C.c_void_p), rel.ctypes.data_as(C.c_void_p),
+                                      tail.ctypes.data_as(C.c_void_p), C.c_int64(len(head)),
+                                      C.c_int32(n_entities), C.c_int32(n_relations), C.c_int32(n_parts),
+                                      C.c_int32(part_id), C.c_int32(n_hops), C.c_int32(neg_domain),
+                                      C.byref(out)))
+    return Partition(out.value)
+
+
+def partition_info(part: Partition) -> dict:
+    return {name: getattr(part, name) for name, _ in _PartInfo._fields_}
+
+
+def partition_export(part: Partition, name: str) -> np.ndarray:
+    which, dt = ARRAYS[name]
+    n = {"vert_gid": part.n_vert, "core_eid": part.n_core, "core_h": part.n_core, "core_r": part.n_core,
+         "core_t": part.n_core, "seg_ptr": part.n_seg + 1, "seg_rel": part.n_seg, "seg_dst": part.n_seg,
+         "inv_c": part.n_seg, "col_src": part.n_edge, "edge_id": part.n_edge, "cand": part.n_cand,
+         "dm_ptr": part.n_vert + 1, "dm_src": part.n_edge, "dm_rel": part.n_edge, "dm_invc": part.n_edge,
+         "sm_ptr": part.n_vert + 1, "sm_dst": part.n_edge, "sm_rel": part.n_edge, "sm_invc": part.n_edge,
+         "rel_ptr": 2 * part.n_relations + 1}[name]
+    arr = np.empty(n, dt)
+    _check(load().kge_partition_export(part.handle, C.c_int32(which), arr.ctypes.data_as(C.c_void_p),
+                                       C.c_int64(arr.nbytes)))
+    return arr
+
+
+def partition_destroy(part: Partition):
+    part.destroy()
+
+
+def _layers(layers: Sequence[dict]):
+    arr = (_Layer * len(layers))()
+    for i, l in enumerate(layers):
+        V, a, W0 = l["V"], l["a"], l["W0"]
+        arr[i].n_bases, arr[i].d_in, arr[i].d_out = V.shape
+        arr[i].act = int(l["act"])
+        arr[i].V, arr[i].a, arr[i].W0 = V.data_ptr(), a.data_ptr(), W0.data_ptr()
+    return arr
+
+
+def workspace_bytes(part: Partition, layers: Sequence[dict], msg_dtype: int = MSG_F32) -> int:
+    n = load().kge_workspace_bytes(part.handle, _layers(layers), C.c_int32(len(layers)), C.c_int32(msg_dtype))
+    if n == 0:
+        raise KgeError(-1, load().kge_last_error().decode())
+    return int(n)
+
+
+def rgcn_forward(part: Partition, layers: Sequence[dict], H0, workspace, H_out,
+                 msg_dtype: int = MSG_F32, stream=None):
+    _check(load().kge_rgcn_forward(part.handle, _layers(layers), C.c_int32(len(layers)), C.c_int32(msg_dtype),
+                                   _ptr(H0), _ptr(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
+                                   _ptr(H_out), _stream(stream)))
+
+
+def rgcn_backward(part: Partition, layers: Sequence[dict], H0, workspace, dH_out, grads: Sequence[dict],
+                  dH0=None, msg_dtype: int = MSG_F32, stream=None):
+    g = (_LayerGrad * len(layers))()
+    for i, gr in enumerate(grads):
+        g[i].dV, g[i].da, g[i].dW0 = gr["dV"].data_ptr(), gr["da"].data_ptr(), gr["dW0"].data_ptr()
+    _check(load().kge_rgcn_backward(part.handle, _layers(layers), C.c_int32(len(layers)), C.c_int32(msg_dtype),
+                                    _ptr(H0), _ptr(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
+                                    _ptr(dH_out), g, _ptr(dH0), _stream(stream)))
+
+
+def sample_negatives(part: Partition, pos_core_idx, n_neg: int, mode: int, seed: int, step: int,
+                     neg_ent, neg_side, stream=None):
+    _check(load().kge_sample_negatives(part.handle, _ptr(pos_core_idx), C.c_int64(pos_core_idx.numel()),
+                                       C.c_int32(n_neg), C.c_int32(mode), C.c_uint64(seed), C.c_uint64(step),
+                                       _ptr(neg_ent), _ptr(neg_side), _stream(stream)))
+
+
+def distmult_score_loss(part: Partition, H, M, pos_core_idx, neg_ent, neg_side, n_neg: int, scores, loss,
+                        dH, dM, stream=None):
+    _check(load().kge_distmult_score_loss(part.handle, _ptr(H), _ptr(M), C.c_int32(H.shape[1]),
+                                          _ptr(pos_core_idx), C.c_int64(pos_core_idx.numel()),
+                                          _ptr(neg_ent), _ptr(neg_side), C.c_int32(n_neg), _ptr(scores),
+                                          _ptr(loss), _ptr(dH), _ptr(dM), _stream(stream)))

@@ -1,0 +1,189 @@
+// Per-step entry points of the C ABI: argument checks, workspace carving and the launch
+// sequence of one training step (Algorithm 1: GNNmodel, loss, backward) on one stream.
+#include <vector>
+
+#include "common.h"
+
+namespace {
+
+struct WsLayout {
+    std::vector<size_t> off_P, off_H;   // per layer: projected messages, layer output
+    size_t off_self = 0, off_G = 0, off_dP = 0, off_dHa = 0, off_dHb = 0, off_seg = 0, total = 0;
+};
+
+int check_layers(const kge_partition *p, const kge_layer *layers, int32_t n_layers, int32_t msg_dtype)
+{
+    KGE_REQUIRE(p && layers, KGE_EINVAL, "NULL partition or layers");
+    KGE_REQUIRE(n_layers >= 1 && n_layers <= 16, KGE_EINVAL, "n_layers must be in [1, 16]");
+    KGE_REQUIRE(msg_dtype == KGE_MSG_F32 || msg_dtype == KGE_MSG_BF16, KGE_EINVAL, "bad msg_dtype");
+    const int mult = msg_dtype == KGE_MSG_BF16 ? 8 : 4;
+    const int dmax = msg_dtype == KGE_MSG_BF16 ? 512 : 256;
+    for (int l = 0; l < n_layers; ++l) {
+        const kge_layer &L = layers[l];
+        KGE_REQUIRE(L.V && L.a && L.W0, KGE_EINVAL, "layer %d has a NULL parameter pointer", l);
+        KGE_REQUIRE(L.d_in > 0 && L.d_out > 0 && L.n_bases > 0 && L.n_bases <= 256, KGE_EINVAL,
+                    "layer %d: d_in, d_out must be positive and n_bases in [1, 256]", l);
+        KGE_REQUIRE(L.d_in % 4 == 0 && L.d_out % mult == 0, KGE_EINVAL,
+                    "layer %d: d_in must be a multiple of 4 and d_out of %d", l, mult);
+        KGE_REQUIRE(L.d_out <= dmax && L.d_in <= 512, KGE_EINVAL,
+                    "layer %d: d_out must be at most %d and d_in at most 512", l, dmax);
+        KGE_REQUIRE(L.act == KGE_ACT_IDENTITY || L.act == KGE_ACT_RELU, KGE_EINVAL, "layer %d: bad act", l);
+        KGE_REQUIRE(l == 0 || L.d_in == layers[l - 1].d_out, KGE_EINVAL,
+                    "layer %d: d_in does not match the previous layer's d_out", l);
+        KGE_REQUIRE(((uintptr_t)L.V % 16) == 0 && ((uintptr_t)L.W0 % 16) == 0, KGE_EINVAL,
+                    "layer %d: V and W0 must be 16-byte aligned", l);
+    }
+    return KGE_OK;
+}
+
+void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, int32_t msg_dtype, WsLayout *w)
+{
+    const size_t N = (size_t)p->n_vert, ep = msg_dtype == KGE_MSG_BF16 ? 2 : 4;
+    size_t cur = 0, max_dout = 0, max_din = 0, max_bd = 0, max_B = 0;
+    w->off_P.resize(n_layers); w->off_H.resize(n_layers);
+    for (int l = 0; l < n_layers; ++l) {
+        const kge_layer &L = layers[l];
+        w->off_P[l] = cur; cur = align_up(cur + N * L.n_bases * L.d_out * ep, 256);
+        w->off_H[l] = cur; cur = align_up(cur + N * L.d_out * 4, 256);
+        if ((size_t)L.d_out > max_dout) max_dout = L.d_out;
+        if ((size_t)L.d_in > max_din) max_din = L.d_in;
+        if ((size_t)L.n_bases * L.d_out > max_bd) max_bd = (size_t)L.n_bases * L.d_out;
+        if ((size_t)L.n_bases > max_B) max_B = L.n_bases;
+    }
+    w->off_self = cur; cur = align_up(cur + N * max_dout * 4, 256);
+    w->off_G = cur; cur = align_up(cur + N * max_dout * 4, 256);
+    w->off_dP = cur; cur = align_up(cur + N * max_bd * ep, 256);
+    w->off_dHa = cur; cur = align_up(cur + N * max_din * 4, 256);
+    w->off_dHb = cur; cur = align_up(cur + N * max_din * 4, 256);
+    w->off_seg = cur; cur = align_up(cur + (size_t)p->n_seg * max_B * 4, 256);
+    w->total = cur > 0 ? cur : 256;
+}
+
+int check_ws(const kge_partition *p, const kge_layer *layers, int32_t n_layers, int32_t msg_dtype,
+             void *workspace, size_t ws_bytes, WsLayout *w)
+{
+    int rc = check_layers(p, layers, n_layers, msg_dtype);
+    if (rc != KGE_OK) return rc;
+    layout(p, layers, n_layers, msg_dtype, w);
+    KGE_REQUIRE(workspace && ((uintptr_t)workspace % 256) == 0, KGE_EINVAL, "workspace must be 256-byte aligned");
+    KGE_REQUIRE(ws_bytes >= w->total, KGE_ENOMEM, "workspace has %zu bytes, %zu needed", ws_bytes, w->total);
+    return KGE_OK;
+}
+
+}  // namespace
+
+extern "C" size_t kge_workspace_bytes(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
+                                      int32_t msg_dtype)
+{
+    if (check_layers(p, layers, n_layers, msg_dtype) != KGE_OK) return 0;
+    WsLayout w;
+    layout(p, layers, n_layers, msg_dtype, &w);
+    return w.total;
+}
+
+extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
+                                int32_t msg_dtype, const float *H0, void *workspace, size_t ws_bytes,
+                                float *H_out, void *stream)
+{
+    WsLayout w;
+    int rc = check_ws(p, layers, n_layers, msg_dtype, workspace, ws_bytes, &w);
+    if (rc != KGE_OK) return rc;
+    KGE_REQUIRE(H0 && H_out, KGE_EINVAL, "H0 or H_out is NULL");
+    KGE_REQUIRE(((uintptr_t)H0 % 16) == 0 && ((uintptr_t)H_out % 16) == 0, KGE_EINVAL, "H0 and H_out must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const int bf = msg_dtype == KGE_MSG_BF16;
+    const float *Hin = H0;
+    float *Self = (float *)(ws + w.off_self);
+    for (int l = 0; l < n_layers; ++l) {
+        const kge_layer &L = layers[l];
+        void *P = ws + w.off_P[l];
+        float *Hl = (float *)(ws + w.off_H[l]);
+        rc = launch_project(Hin, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, P, bf, Self, st);
+        if (rc != KGE_OK) return rc;
+        rc = launch_gather_forward(p, P, bf, L.a, L.n_bases, L.d_out, Self, L.act, Hl,
+                                   l == n_layers - 1 ? H_out : nullptr, st);
+        if (rc != KGE_OK) return rc;
+        Hin = Hl;
+    }
+    return KGE_OK;
+}
+
+extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
+                                 int32_t msg_dtype, const float *H0, void *workspace, size_t ws_bytes,
+                                 const float *dH_out, const kge_layer_grad *grads, float *dH0, void *stream)
+{
+    WsLayout w;
+    int rc = check_ws(p, layers, n_layers, msg_dtype, workspace, ws_bytes, &w);
+    if (rc != KGE_OK) return rc;
+    KGE_REQUIRE(H0 && dH_out && grads, KGE_EINVAL, "H0, dH_out or grads is NULL");
+    KGE_REQUIRE(((uintptr_t)H0 % 16) == 0 && ((uintptr_t)dH_out % 16) == 0 && ((uintptr_t)dH0 % 16) == 0,
+                KGE_EINVAL, "H0, dH_out and dH0 must be 16-byte aligned");
+    for (int l = 0; l < n_layers; ++l)
+        KGE_REQUIRE(grads[l].dV && grads[l].da && grads[l].dW0 && ((uintptr_t)grads[l].dV % 4) == 0 &&
+                        ((uintptr_t)grads[l].da % 4) == 0 && ((uintptr_t)grads[l].dW0 % 4) == 0,
+                    KGE_EINVAL, "layer %d: NULL or misaligned gradient pointer", l);
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const int bf = msg_dtype == KGE_MSG_BF16;
+    float *G = (float *)(ws + w.off_G);
+    void *dP = ws + w.off_dP;
+    float *dHbuf[2] = {(float *)(ws + w.off_dHa), (float *)(ws + w.off_dHb)};
+    float *seg = (float *)(ws + w.off_seg);
+    const float *gin = dH_out;
+    for (int l = n_layers - 1; l >= 0; --l) {
+        const kge_layer &L = layers[l];
+        const void *P = ws + w.off_P[l];
+        const float *Hl = (const float *)(ws + w.off_H[l]);
+        const float *Hprev = l > 0 ? (const float *)(ws + w.off_H[l - 1]) : H0;
+        const float *Gl = gin;
+        if (L.act != KGE_ACT_IDENTITY) {
+            rc = launch_act_backward(gin, Hl, L.act, p->n_vert * (int64_t)L.d_out, G, st);
+            if (rc != KGE_OK) return rc;
+            Gl = G;
+        }
+        rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, grads[l].da, st);
+        if (rc != KGE_OK) return rc;
+        rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf, st);
+        if (rc != KGE_OK) return rc;
+        rc = launch_weight_grad(Hprev, p->n_vert, L.d_in, L.d_out, L.n_bases, dP, bf, Gl, grads[l].dV,
+                                grads[l].dW0, st);
+        if (rc != KGE_OK) return rc;
+        if (l > 0 || dH0) {
+            float *dst = l > 0 ? dHbuf[l & 1] : dH0;
+            rc = launch_input_grad(dP, bf, Gl, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, dst, st);
+            if (rc != KGE_OK) return rc;
+            gin = dst;
+        }
+    }
+    return KGE_OK;
+}
+
+extern "C" int kge_sample_negatives(const kge_partition *p, const int32_t *pos_core_idx, int64_t n_pos,
+                                    int32_t n_neg, int32_t mode, uint64_t seed, uint64_t step,
+                                    int32_t *neg_ent, uint8_t *neg_side, void *stream)
+{
+    KGE_REQUIRE(p, KGE_EINVAL, "NULL partition");
+    KGE_REQUIRE(n_pos >= 0 && n_neg >= 0, KGE_EINVAL, "negative count");
+    KGE_REQUIRE(mode == KGE_NEG_TAIL || mode == KGE_NEG_HEAD_OR_TAIL, KGE_EINVAL, "bad mode");
+    KGE_REQUIRE(n_pos * (int64_t)n_neg == 0 || (pos_core_idx && neg_ent && neg_side), KGE_EINVAL, "NULL array");
+    return launch_sample_negatives(p, pos_core_idx, n_pos, n_neg, mode, seed, step, neg_ent, neg_side,
+                                   (hipStream_t)stream);
+}
+
+extern "C" int kge_distmult_score_loss(const kge_partition *p, const float *H, const float *M, int32_t d,
+                                       const int32_t *pos_core_idx, int64_t n_pos, const int32_t *neg_ent,
+                                       const uint8_t *neg_side, int32_t n_neg, float *scores, float *loss,
+                                       float *dH, float *dM, void *stream)
+{
+    KGE_REQUIRE(p && H && M && loss && dH && dM, KGE_EINVAL, "NULL argument");
+    KGE_REQUIRE(d > 0 && d <= 512 && d % 4 == 0, KGE_EINVAL, "d must be a multiple of 4 in [4, 512]");
+    KGE_REQUIRE(n_pos >= 0 && n_neg >= 0, KGE_EINVAL, "negative count");
+    KGE_REQUIRE(n_pos == 0 || pos_core_idx, KGE_EINVAL, "pos_core_idx is NULL");
+    KGE_REQUIRE(n_pos * (int64_t)n_neg == 0 || (neg_ent && neg_side), KGE_EINVAL, "negatives are NULL");
+    KGE_REQUIRE(n_pos == 0 || p->n_core > 0, KGE_EINVAL, "the partition has no core edge to score");
+    KGE_REQUIRE(((uintptr_t)dH % 4) == 0 && ((uintptr_t)dM % 4) == 0 && ((uintptr_t)loss % 4) == 0, KGE_EINVAL,
+                "misaligned output");
+    return launch_distmult(p, H, M, d, pos_core_idx, n_pos, neg_ent, neg_side, n_neg, scores, loss, dH, dM,
+                           (hipStream_t)stream);
+}

@@ -1,0 +1,91 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "kge_mi355.h"
+
+void kge_set_error(const char *fmt, ...);
+
+#define KGE_HIP(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e__ = (expr);                                                              \
+        if (e__ != hipSuccess) {                                                              \
+            kge_set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__,   \
+                          __LINE__);                                                          \
+            return KGE_EHIP;                                                                  \
+        }                                                                                     \
+    } while (0)
+
+#define KGE_REQUIRE(cond, code, ...)                                                          \
+    do {                                                                                      \
+        if (!(cond)) {                                                                        \
+            kge_set_error(__VA_ARGS__);                                                       \
+            return (code);                                                                    \
+        }                                                                                     \
+    } while (0)
+
+#define KGE_LAUNCH_CHECK() KGE_HIP(hipGetLastError())
+
+struct kge_partition {
+    int device;
+    int64_t n_vert, n_edge, n_seg, n_core, n_cand, n_triples;
+    int32_t n_entities, n_relations, n_parts, part_id, n_hops, neg_domain;
+    int32_t max_in_degree, max_out_degree;
+    // canonical arrays (bit-exact contract)
+    int32_t *vert_gid, *core_eid, *core_h, *core_r, *core_t;
+    int32_t *seg_ptr, *seg_rel, *seg_dst;
+    float *inv_c;
+    int32_t *col_src, *edge_id, *cand;
+    // destination-major and source-major views of the same edges
+    int32_t *dm_ptr, *dm_src, *dm_rel;
+    float *dm_invc;
+    int32_t *sm_ptr, *sm_dst, *sm_rel;
+    float *sm_invc;
+    int32_t *rel_ptr;   // [2R+1] run range per relation
+};
+
+static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- kernels' host launchers (implemented in the .hip files) ----
+
+// gemm.hip ---------------------------------------------------------------
+// P[N][B*d_out] (msg dtype) and Self[N][d_out] (fp32) = H[N][d_in] * [V_1 .. V_B | W0]
+int launch_project(const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
+                   const float *V, const float *W0, void *P, int msg_bf16, float *Self,
+                   hipStream_t st);
+// dV[B][d_in][d_out] = H^T dP_b ; dW0 = H^T G      (outputs zeroed inside, split over N)
+int launch_weight_grad(const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
+                       const void *dP, int msg_bf16, const float *G, float *dV, float *dW0,
+                       hipStream_t st);
+// dH[N][d_in] = sum_b dP_b V_b^T + G W0^T
+int launch_input_grad(const void *dP, int msg_bf16, const float *G, int64_t N, int32_t d_in,
+                      int32_t d_out, int32_t B, const float *V, const float *W0, float *dH,
+                      hipStream_t st);
+
+// gather.hip -------------------------------------------------------------
+// out[i] = act( sum_{e into i} invc_e sum_b a[rel_e][b] P[src_e][b][:] + Self[i] ); out2 optional copy
+int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, const float *a,
+                          int32_t B, int32_t d, const float *Self, int act, float *out, float *out2,
+                          hipStream_t st);
+// G = dHout * act'(Hout) (ReLU: Hout > 0)
+int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t n, float *G,
+                        hipStream_t st);
+// dP[j][b][:] = sum_{e out of j} a[rel_e][b] invc_e G[dst_e][:]
+int launch_gather_transpose(const kge_partition *p, const float *G, const float *a, int32_t B,
+                            int32_t d, void *dP, int msg_bf16, hipStream_t st);
+// da[r][b] = sum_{runs (r,i)} invc sum_{j in run} <P[j][b][:], G[i][:]> ; seg_scratch [S][B] floats
+int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const float *G,
+                      int32_t B, int32_t d, float *seg_scratch, float *da, hipStream_t st);
+
+// sampler_score.hip --------------------------------------------------------
+int launch_sample_negatives(const kge_partition *p, const int32_t *pos, int64_t n_pos, int32_t n_neg,
+                            int32_t mode, uint64_t seed, uint64_t step, int32_t *neg_ent,
+                            uint8_t *neg_side, hipStream_t st);
+int launch_distmult(const kge_partition *p, const float *H, const float *M, int32_t d,
+                    const int32_t *pos, int64_t n_pos, const int32_t *neg_ent,
+                    const uint8_t *neg_side, int32_t n_neg, float *scores, float *loss, float *dH,
+                    float *dM, hipStream_t st);
+int launch_fill_zero(void *ptr, size_t bytes, hipStream_t st);

@@ -1,0 +1,441 @@
+// Neighbour aggregation of the RGCN layer (Eq. 1 with W_r = sum_b a_rb V_b, Eq. 2) and
+// its backward counterparts.  All three kernels are bandwidth bound: they stream rows of
+// the projected messages P[j][b][:] (or of the upstream gradient G) with 128-bit loads, one
+// wavefront per destination / source / (relation, destination) run, and do a handful of
+// fp32 FMAs per loaded element.
+//
+// Lane layout shared by the kernels.  A row of `d` elements is covered by LPR lanes, each
+// holding VEC consecutive elements (VEC = 4 for fp32, 8 for bf16: one 16-byte load).  The
+// 64 / LPR lane groups of a wavefront work on different (edge, basis) pairs in parallel:
+// GB of them across bases, GE = groups / GB across edges.
+#include "common.h"
+
+namespace {
+
+constexpr int WPB = 4;                 // wavefronts per block
+
+template <bool BF16> struct MsgRow;
+template <> struct MsgRow<false> {
+    static constexpr int VEC = 4;
+    typedef float elem;
+    static __device__ __forceinline__ void load(const void *base, int64_t off, float (&v)[4])
+    {
+        float4 x = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(base) + off);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    }
+    static __device__ __forceinline__ void store(void *base, int64_t off, const float (&v)[4])
+    {
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(base) + off) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // round to nearest even
+{
+    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+    a = ((a & 0x7fffffffu) > 0x7f800000u) ? ((a >> 16) | 0x40u) : ((a + 0x7fffu + ((a >> 16) & 1u)) >> 16);
+    b = ((b & 0x7fffffffu) > 0x7f800000u) ? ((b >> 16) | 0x40u) : ((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
+    return (a & 0xffffu) | (b << 16);
+}
+template <> struct MsgRow<true> {
+    static constexpr int VEC = 8;
+    typedef uint16_t elem;
+    static __device__ __forceinline__ void load(const void *base, int64_t off, float (&v)[8])
+    {
+        uint4 x = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(base) + off);
+        v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xffff0000u);
+        v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
+        v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xffff0000u);
+        v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(void *base, int64_t off, const float (&v)[8])
+    {
+        uint4 x;
+        x.x = pack_bf16x2(v[0], v[1]); x.y = pack_bf16x2(v[2], v[3]);
+        x.z = pack_bf16x2(v[4], v[5]); x.w = pack_bf16x2(v[6], v[7]);
+        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(base) + off) = x;
+    }
+};
+
+__device__ __forceinline__ float act_apply(int act, float x) { return act == KGE_ACT_RELU ? fmaxf(x, 0.f) : x; }
+
+// ------------------------------------------------------------------ forward
+// One wavefront per destination i (destination-major view):
+//   out[i][:] = act( sum_e invc_e sum_b a[rel_e][b] P[src_e][b][:] + Self[i][:] )
+template <bool BF16, int LPR>
+__global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
+    const int32_t *__restrict__ dm_ptr, const int32_t *__restrict__ dm_src,
+    const int32_t *__restrict__ dm_rel, const float *__restrict__ dm_invc, int64_t N,
+    const void *__restrict__ P, const float *__restrict__ a, int32_t B, int32_t d, int32_t gb_count,
+    const float *__restrict__ Self, int act, float *__restrict__ out, float *__restrict__ out2)
+{
+    constexpr int VEC = MsgRow<BF16>::VEC;
+    constexpr int G = 64 / LPR;
+    constexpr int U = 4;
+    const int lane = threadIdx.x & 63;
+    const int64_t i = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+    if (i >= N) return;                                 // whole wavefront leaves together
+    const int kl = lane % LPR, g = lane / LPR;
+    const int GB = gb_count, GE = G / GB;
+    const int gb = g % GB, ge = g / GB;
+    const bool kact = kl * VEC < d;
+    const int nb = (B + GB - 1) / GB;                   // basis slots per edge for this group
+
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+
+    const int32_t beg = dm_ptr[i], end = dm_ptr[i + 1];
+    for (int32_t e0 = beg; e0 < end; e0 += 64) {
+        const int cnt = min(64, end - e0);
+        int32_t my_src = 0, my_rel = 0;
+        float my_w = 0.f;
+        if (lane < cnt) { my_src = dm_src[e0 + lane]; my_rel = dm_rel[e0 + lane]; my_w = dm_invc[e0 + lane]; }
+        const int erounds = (cnt + GE - 1) / GE;        // uniform trip counts for all lanes
+        const int items = erounds * nb;
+        int er = 0, bi = 0;                             // current (edge round, basis slot)
+        for (int q0 = 0; q0 < items; q0 += U) {
+            float coef[U];
+            float val[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int el = er * GE + ge;
+                const int b = bi * GB + gb;
+                const bool ok = (q0 + u < items) && el < cnt && b < B;
+                const int els = ok ? el : 0;
+                const int32_t src = __shfl(my_src, els, 64);
+                const int32_t rel = __shfl(my_rel, els, 64);
+                const float w = __shfl(my_w, els, 64);
+                coef[u] = 0.f;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) val[u][v] = 0.f;
+                if (ok) {
+                    coef[u] = a[(int64_t)rel * B + b] * w;
+                    if (kact) MsgRow<BF16>::load(P, ((int64_t)src * B + b) * d + kl * VEC, val[u]);
+                }
+                if (++bi == nb) { bi = 0; ++er; }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc[v] = fmaf(coef[u], val[u][v], acc[v]);
+        }
+    }
+    // fold the lane groups together (fixed order: deterministic)
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] += __shfl_xor(acc[v], off, 64);
+
+    if (g == 0 && kact) {
+        const int64_t o = i * d + kl * VEC;
+#pragma unroll
+        for (int v4 = 0; v4 < VEC; v4 += 4) {
+            float4 s = *reinterpret_cast<const float4 *>(Self + o + v4);
+            float4 r = make_float4(act_apply(act, acc[v4] + s.x), act_apply(act, acc[v4 + 1] + s.y),
+                                   act_apply(act, acc[v4 + 2] + s.z), act_apply(act, acc[v4 + 3] + s.w));
+            *reinterpret_cast<float4 *>(out + o + v4) = r;
+            if (out2) *reinterpret_cast<float4 *>(out2 + o + v4) = r;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ activation backward
+__global__ void k_act_backward(const float4 *__restrict__ dH, const float4 *__restrict__ Hout, int act,
+                               int64_t n4, float4 *__restrict__ G)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n4; i += stride) {
+        float4 g = dH[i];
+        if (act == KGE_ACT_RELU) {
+            float4 h = Hout[i];
+            g.x = h.x > 0.f ? g.x : 0.f; g.y = h.y > 0.f ? g.y : 0.f;
+            g.z = h.z > 0.f ? g.z : 0.f; g.w = h.w > 0.f ? g.w : 0.f;
+        }
+        G[i] = g;
+    }
+}
+
+// ------------------------------------------------------------------ transposed gather
+// One wavefront per (source j, chunk of bases) on the source-major view:
+//   dP[j][b][:] = sum_{e out of j} a[rel_e][b] invc_e G[dst_e][:]
+// A G row (fp32) is covered by LPR lanes x 4 floats; the 64/LPR lane groups take different
+// bases, NB bases each, so a chunk is (64/LPR)*NB bases.
+template <bool BF16, int LPR, int NB>
+__global__ __launch_bounds__(64 * WPB) void k_gather_t(
+    const int32_t *__restrict__ sm_ptr, const int32_t *__restrict__ sm_dst,
+    const int32_t *__restrict__ sm_rel, const float *__restrict__ sm_invc, int64_t N,
+    const float *__restrict__ G, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_chunks,
+    void *__restrict__ dP)
+{
+    constexpr int NG = 64 / LPR;
+    const int lane = threadIdx.x & 63;
+    const int64_t wid = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+    if (wid >= N * n_chunks) return;
+    const int64_t j = wid / n_chunks;
+    const int bc = (int)(wid - j * n_chunks);
+    const int kl = lane % LPR, g = lane / LPR;
+    const bool kact = kl * 4 < d;
+    const int b0 = (bc * NG + g) * NB;
+
+    float acc[NB][4];
+#pragma unroll
+    for (int n = 0; n < NB; ++n)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[n][v] = 0.f;
+
+    const int32_t beg = sm_ptr[j], end = sm_ptr[j + 1];
+    for (int32_t e0 = beg; e0 < end; e0 += 64) {
+        const int cnt = min(64, end - e0);
+        int32_t my_dst = 0, my_rel = 0;
+        float my_w = 0.f;
+        if (lane < cnt) { my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc[e0 + lane]; }
+        for (int el = 0; el < cnt; ++el) {
+            const int32_t dst = __builtin_amdgcn_readlane(my_dst, el);
+            const int32_t rel = __builtin_amdgcn_readlane(my_rel, el);
+            const float w = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), el));
+            float4 gv = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (kact) gv = *reinterpret_cast<const float4 *>(G + (int64_t)dst * d + kl * 4);
+            const float *arow = a + (int64_t)rel * B;
+#pragma unroll
+            for (int n = 0; n < NB; ++n) {
+                const float c = (b0 + n < B) ? arow[b0 + n] * w : 0.f;
+                acc[n][0] = fmaf(c, gv.x, acc[n][0]); acc[n][1] = fmaf(c, gv.y, acc[n][1]);
+                acc[n][2] = fmaf(c, gv.z, acc[n][2]); acc[n][3] = fmaf(c, gv.w, acc[n][3]);
+            }
+        }
+    }
+    if (kact) {
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+            if (b0 + n < B) {
+                const int64_t o = ((int64_t)j * B + b0 + n) * d + kl * 4;
+                if (BF16) {
+                    uint2 x;
+                    x.x = pack_bf16x2(acc[n][0], acc[n][1]); x.y = pack_bf16x2(acc[n][2], acc[n][3]);
+                    *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(dP) + o) = x;
+                } else {
+                    *reinterpret_cast<float4 *>(reinterpret_cast<float *>(dP) + o) =
+                        make_float4(acc[n][0], acc[n][1], acc[n][2], acc[n][3]);
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ coefficient gradient
+// One wavefront per (relation, destination) run s = (r, i):
+//   seg_out[s][b] = invc_s * sum_{j in run} < P[j][b][:], G[i][:] >
+// and da[r][b] is the sum of seg_out over the runs of relation r (second kernel).
+template <bool BF16, int LPR>
+__global__ __launch_bounds__(64 * WPB) void k_coeff_seg(
+    const int32_t *__restrict__ seg_ptr, const int32_t *__restrict__ seg_dst,
+    const float *__restrict__ inv_c, const int32_t *__restrict__ col_src, int64_t S,
+    const void *__restrict__ P, const float *__restrict__ G, int32_t B, int32_t d, int32_t gb_count,
+    float *__restrict__ seg_out)
+{
+    constexpr int VEC = MsgRow<BF16>::VEC;
+    constexpr int NG = 64 / LPR;
+    constexpr int U = 4;
+    const int lane = threadIdx.x & 63;
+    const int64_t s = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+    if (s >= S) return;
+    const int kl = lane % LPR, g = lane / LPR;
+    const int GB = gb_count, GE = NG / GB;
+    const int gb = g % GB, ge = g / GB;
+    const bool kact = kl * VEC < d;
+    const int nb = (B + GB - 1) / GB;
+
+    const int32_t beg = seg_ptr[s], end = seg_ptr[s + 1];
+    const int32_t i = seg_dst[s];
+    const float invc = inv_c[s];
+    float gv[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) gv[v] = 0.f;
+    if (kact) {
+#pragma unroll
+        for (int v4 = 0; v4 < VEC; v4 += 4) {
+            float4 x = *reinterpret_cast<const float4 *>(G + (int64_t)i * d + kl * VEC + v4);
+            gv[v4] = x.x; gv[v4 + 1] = x.y; gv[v4 + 2] = x.z; gv[v4 + 3] = x.w;
+        }
+    }
+    const int len = end - beg;
+    const int erounds = (len + GE - 1) / GE;
+    for (int bi0 = 0; bi0 < nb; bi0 += U) {
+        float part[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) part[u] = 0.f;
+        for (int er = 0; er < erounds; ++er) {
+            const int el = er * GE + ge;
+            const bool eok = el < len;
+            const int32_t src = eok ? col_src[beg + el] : 0;
+            float val[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int b = (bi0 + u) * GB + gb;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) val[u][v] = 0.f;
+                if (eok && kact && (bi0 + u) < nb && b < B)
+                    MsgRow<BF16>::load(P, ((int64_t)src * B + b) * d + kl * VEC, val[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) part[u] = fmaf(val[u][v], gv[v], part[u]);
+        }
+        // sum over the LPR lanes of a row and over the GE edge groups; skip the offsets that
+        // would mix different bases (LPR .. LPR*GB/2)
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int off = 1; off < LPR; off <<= 1) part[u] += __shfl_xor(part[u], off, 64);
+            for (int off = LPR * GB; off < 64; off <<= 1) part[u] += __shfl_xor(part[u], off, 64);
+        }
+        if (kl == 0 && ge == 0) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int b = (bi0 + u) * GB + gb;
+                if ((bi0 + u) < nb && b < B) seg_out[s * B + b] = invc * part[u];
+            }
+        }
+    }
+}
+
+// da[r][b] += sum of seg_out[s][b] over a strided share of relation r's runs.
+// grid = (2R, n_split); block = 256 threads laid out as (256 / BP) run slots x BP bases.
+__global__ __launch_bounds__(256) void k_coeff_reduce(const int32_t *__restrict__ rel_ptr,
+                                                      const float *__restrict__ seg_out, int32_t B,
+                                                      int32_t BP, float *__restrict__ da)
+{
+    __shared__ float red[256];
+    const int r = blockIdx.x;
+    const int slots = 256 / BP;
+    const int b = threadIdx.x % BP, slot = threadIdx.x / BP;
+    const int64_t beg = rel_ptr[r], end = rel_ptr[r + 1];
+    float acc = 0.f;
+    if (b < B && slot < slots)
+        for (int64_t s = beg + (int64_t)blockIdx.y * slots + slot; s < end; s += (int64_t)gridDim.y * slots)
+            acc += seg_out[s * B + b];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (slot == 0 && b < B) {
+        float t = 0.f;
+        for (int k = 0; k < slots; ++k) t += red[k * BP + b];
+        if (t != 0.f) unsafeAtomicAdd(&da[(int64_t)r * B + b], t);
+    }
+}
+
+int pow2_at_least(int x) { int p = 1; while (p < x) p <<= 1; return p; }
+int largest_pow2_dividing(int x, int cap) { int p = 1; while (p * 2 <= cap && x % (p * 2) == 0) p <<= 1; return p; }
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+#define DISPATCH_LPR(LPRV, CALL)                                                        \
+    switch (LPRV) {                                                                     \
+    case 1: { constexpr int L = 1; CALL; } break;                                       \
+    case 2: { constexpr int L = 2; CALL; } break;                                       \
+    case 4: { constexpr int L = 4; CALL; } break;                                       \
+    case 8: { constexpr int L = 8; CALL; } break;                                       \
+    case 16: { constexpr int L = 16; CALL; } break;                                     \
+    case 32: { constexpr int L = 32; CALL; } break;                                     \
+    default: { constexpr int L = 64; CALL; } break;                                     \
+    }
+
+int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, const float *a,
+                          int32_t B, int32_t d, const float *Self, int act, float *out, float *out2,
+                          hipStream_t st)
+{
+    const int64_t N = p->n_vert;
+    if (N == 0) return KGE_OK;
+    const int vec = msg_bf16 ? 8 : 4;
+    const int lpr = pow2_at_least((d + vec - 1) / vec);
+    KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the aggregation kernel", d);
+    const int gbc = largest_pow2_dividing(B, 64 / lpr);
+    const unsigned grid = (unsigned)cdiv(N, WPB);
+    if (msg_bf16) {
+        DISPATCH_LPR(lpr, (k_gather_fwd<true, L><<<grid, 64 * WPB, 0, st>>>(p->dm_ptr, p->dm_src, p->dm_rel, p->dm_invc, N, P, a, B, d, gbc, Self, act, out, out2)));
+    } else {
+        DISPATCH_LPR(lpr, (k_gather_fwd<false, L><<<grid, 64 * WPB, 0, st>>>(p->dm_ptr, p->dm_src, p->dm_rel, p->dm_invc, N, P, a, B, d, gbc, Self, act, out, out2)));
+    }
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t n, float *G, hipStream_t st)
+{
+    if (n == 0) return KGE_OK;
+    int64_t n4 = n / 4;
+    int64_t blocks = cdiv(n4, 256);
+    if (blocks > 65536) blocks = 65536;
+    k_act_backward<<<(unsigned)blocks, 256, 0, st>>>(reinterpret_cast<const float4 *>(dHout),
+                                                    reinterpret_cast<const float4 *>(Hout), act, n4,
+                                                    reinterpret_cast<float4 *>(G));
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+template <bool BF16, int LPR>
+static int launch_gather_t_nb(const kge_partition *p, const float *G, const float *a, int32_t B, int32_t d,
+                              void *dP, hipStream_t st)
+{
+    constexpr int NG = 64 / LPR;
+    const int64_t N = p->n_vert;
+    const int per_group = (B + NG - 1) / NG;
+#define GT_CALL(NBV)                                                                                  \
+    {                                                                                                 \
+        const int n_chunks = (B + NG * NBV - 1) / (NG * NBV);                                         \
+        const unsigned grid = (unsigned)cdiv(N * n_chunks, WPB);                                      \
+        k_gather_t<BF16, LPR, NBV><<<grid, 64 * WPB, 0, st>>>(p->sm_ptr, p->sm_dst, p->sm_rel,        \
+                                                             p->sm_invc, N, G, a, B, d, n_chunks, dP); \
+    }
+    if (per_group >= 16) GT_CALL(16)
+    else if (per_group >= 8) GT_CALL(8)
+    else if (per_group >= 4) GT_CALL(4)
+    else if (per_group >= 2) GT_CALL(2)
+    else GT_CALL(1)
+#undef GT_CALL
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+int launch_gather_transpose(const kge_partition *p, const float *G, const float *a, int32_t B, int32_t d,
+                            void *dP, int msg_bf16, hipStream_t st)
+{
+    if (p->n_vert == 0) return KGE_OK;
+    const int lpr = pow2_at_least((d + 3) / 4);
+    KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the transposed aggregation kernel", d);
+    KGE_REQUIRE(p->n_vert * (int64_t)B < 0x7fffffffLL * WPB, KGE_ERANGE, "grid too large");
+    int rc = KGE_OK;
+    if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(p, G, a, B, d, dP, st))); }
+    else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, L>(p, G, a, B, d, dP, st))); }
+    return rc;
+}
+
+int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const float *G, int32_t B,
+                      int32_t d, float *seg_scratch, float *da, hipStream_t st)
+{
+    const int64_t S = p->n_seg;
+    const int32_t R2 = 2 * p->n_relations;
+    int rc = launch_fill_zero(da, sizeof(float) * (size_t)R2 * B, st);
+    if (rc != KGE_OK) return rc;
+    if (S == 0) return KGE_OK;
+    const int vec = msg_bf16 ? 8 : 4;
+    const int lpr = pow2_at_least((d + vec - 1) / vec);
+    KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the coefficient-gradient kernel", d);
+    const int gbc = largest_pow2_dividing(B, 64 / lpr);
+    const unsigned grid = (unsigned)cdiv(S, WPB);
+    if (msg_bf16) {
+        DISPATCH_LPR(lpr, (k_coeff_seg<true, L><<<grid, 64 * WPB, 0, st>>>(p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, P, G, B, d, gbc, seg_scratch)));
+    } else {
+        DISPATCH_LPR(lpr, (k_coeff_seg<false, L><<<grid, 64 * WPB, 0, st>>>(p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, P, G, B, d, gbc, seg_scratch)));
+    }
+    KGE_LAUNCH_CHECK();
+    KGE_REQUIRE(B <= 256, KGE_EINVAL, "more than 256 bases are not supported");
+    const int BP = pow2_at_least(B);
+    int n_split = (int)(S / 65536) + 1;       // enough blocks for the most frequent relation
+    if (n_split > 256) n_split = 256;
+    dim3 rgrid((unsigned)R2, (unsigned)n_split, 1);
+    k_coeff_reduce<<<rgrid, 256, 0, st>>>(p->rel_ptr, seg_scratch, B, BP, da);
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}

@@ -1,0 +1,304 @@
+// Dense contractions of the encoder (Eq. 2 applied to every vertex, and its two
+// transposes for the backward pass) on the gfx950 matrix cores.
+//
+//   project      P = H [V_1 .. V_B | W_0]                      (N x d_in) (d_in x (B+1)d_out)
+//   weight_grad  d[V_1 .. V_B | W_0] = H^T [dP | G]            (d_in x N) (N x (B+1)d_out)
+//   input_grad   dH = [dP | G] [V_1 .. V_B | W_0]^T            (N x (B+1)d_out) ((B+1)d_out x d_in)
+//
+// One kernel template: 128x128 block tile, 4 wavefronts in a 2x2 grid, each wavefront owns a
+// 64x64 sub-tile as 2x2 v_mfma_f32_32x32x2_f32 accumulators.  Operands are staged through LDS
+// K-major (As[k][m], Bs[k][n]) so that the MFMA operand reads are 32 consecutive floats.
+// Operand loaders and the epilogue are small functors, so the concatenated operands
+// ([V|W0], [dP|G]) are never materialised.
+#include "common.h"
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, BN = 128, BK = 16, PADL = 4, GT = 256;
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)   // round to nearest even
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ---- operand sources: load4(row, col) returns 4 consecutive elements along the contiguous
+// dimension starting at (row, col); out-of-range -> zeros.  Contiguous extents are multiples of 4.
+
+struct SrcRowMajorF32 {          // X[r][c], c contiguous
+    const float *p; int64_t rows; int32_t cols;
+    __device__ __forceinline__ float4 load4(int64_t r, int32_t c) const
+    {
+        if (r >= rows || c >= cols) return make_float4(0.f, 0.f, 0.f, 0.f);
+        return *reinterpret_cast<const float4 *>(p + r * cols + c);
+    }
+};
+
+// [V_1 .. V_B | W0] viewed as a (d_in x (B+1) d_out) matrix, column index contiguous inside a block
+struct SrcWcat {
+    const float *V, *W0; int32_t d_in, d_out, B;
+    __device__ __forceinline__ float4 load4(int64_t k, int32_t c) const
+    {
+        int32_t nc = (B + 1) * d_out;
+        if (k >= d_in || c >= nc) return make_float4(0.f, 0.f, 0.f, 0.f);
+        int32_t b = c / d_out, cc = c - b * d_out;
+        const float *base = b < B ? V + ((int64_t)b * d_in + k) * d_out : W0 + k * d_out;
+        return *reinterpret_cast<const float4 *>(base + cc);
+    }
+};
+
+// [dP | G] viewed as an (N x (B+1) d_out) matrix; dP is fp32 or bf16, G is fp32
+template <bool BF16>
+struct SrcXcat {
+    const void *dP; const float *G; int64_t rows; int32_t d_out, B;
+    __device__ __forceinline__ float4 load4(int64_t r, int32_t c) const
+    {
+        int32_t bd = B * d_out;
+        if (r >= rows || c >= bd + d_out) return make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c >= bd) return *reinterpret_cast<const float4 *>(G + r * d_out + (c - bd));
+        if (BF16) {
+            const uint16_t *q = reinterpret_cast<const uint16_t *>(dP) + r * bd + c;
+            uint2 w = *reinterpret_cast<const uint2 *>(q);
+            return make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u),
+                               __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xffff0000u));
+        }
+        return *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(dP) + r * bd + c);
+    }
+};
+
+// ---- epilogues: store(m, n, value)
+template <bool BF16>
+struct EpiProject {             // columns < B*d_out go to P (msg dtype), the rest to Self
+    void *P; float *Self; int64_t rows; int32_t d_out, B;
+    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
+    {
+        int32_t bd = B * d_out;
+        if (m >= rows || n >= bd + d_out) return;
+        if (n >= bd) Self[m * d_out + (n - bd)] = v;
+        else if (BF16) reinterpret_cast<uint16_t *>(P)[m * bd + n] = f32_to_bf16(v);
+        else reinterpret_cast<float *>(P)[m * bd + n] = v;
+    }
+};
+
+struct EpiWeightGrad {          // atomic accumulation of split-K partial tiles
+    float *dV, *dW0; int32_t d_in, d_out, B;
+    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
+    {
+        int32_t bd = B * d_out;
+        if (m >= d_in || n >= bd + d_out) return;
+        int32_t b = n / d_out, c = n - b * d_out;
+        float *dst = b < B ? dV + ((int64_t)b * d_in + m) * d_out + c : dW0 + m * d_out + c;
+        unsafeAtomicAdd(dst, v);
+    }
+};
+
+struct EpiRowMajor {
+    float *out; int64_t rows; int32_t cols;
+    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
+    {
+        if (m < rows && n < cols) out[m * cols + n] = v;
+    }
+};
+
+// A(m,k): A_KCONTIG ? srcA.load4(m, k) along k : srcA.load4(k, m) along m
+// B(k,n): B_KCONTIG ? srcB.load4(n, k) along k : srcB.load4(k, n) along n
+template <class SA, bool A_KCONTIG, class SB, bool B_KCONTIG, class EPI>
+__global__ __launch_bounds__(GT) void k_gemm(SA srcA, SB srcB, EPI epi, int64_t K, int64_t kchunk)
+{
+    __shared__ __attribute__((aligned(16))) float As[BK][BM + PADL];
+    __shared__ __attribute__((aligned(16))) float Bs[BK][BN + PADL];
+
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int wm = w >> 1, wn = w & 1;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int32_t n0 = blockIdx.y * BN;
+    const int64_t kbeg = (int64_t)blockIdx.z * kchunk;
+    const int64_t kend = (kbeg + kchunk < K) ? kbeg + kchunk : K;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
+        // ---- global -> registers
+        float4 ra[2], rb[2];
+#pragma unroll
+        for (int ps = 0; ps < 2; ++ps) {
+            if (A_KCONTIG) {
+                int m = (t >> 2) + ps * 64, k4 = (t & 3) * 4;
+                ra[ps] = (k0 + k4 < kend) ? srcA.load4(m0 + m, (int32_t)(k0 + k4)) : make_float4(0.f, 0.f, 0.f, 0.f);
+            } else {
+                int k = (t >> 5) + ps * 8, m4 = (t & 31) * 4;
+                ra[ps] = (k0 + k < kend) ? srcA.load4(k0 + k, (int32_t)(m0 + m4)) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            if (B_KCONTIG) {
+                int n = (t >> 2) + ps * 64, k4 = (t & 3) * 4;
+                rb[ps] = (k0 + k4 < kend) ? srcB.load4(n0 + n, (int32_t)(k0 + k4)) : make_float4(0.f, 0.f, 0.f, 0.f);
+            } else {
+                int k = (t >> 5) + ps * 8, n4 = (t & 31) * 4;
+                rb[ps] = (k0 + k < kend) ? srcB.load4(k0 + k, n0 + n4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+        __syncthreads();      // previous tile fully consumed
+#pragma unroll
+        for (int ps = 0; ps < 2; ++ps) {
+            if (A_KCONTIG) {
+                int m = (t >> 2) + ps * 64, k4 = (t & 3) * 4;
+                As[k4 + 0][m] = ra[ps].x; As[k4 + 1][m] = ra[ps].y;
+                As[k4 + 2][m] = ra[ps].z; As[k4 + 3][m] = ra[ps].w;
+            } else {
+                int k = (t >> 5) + ps * 8, m4 = (t & 31) * 4;
+                *reinterpret_cast<float4 *>(&As[k][m4]) = ra[ps];
+            }
+            if (B_KCONTIG) {
+                int n = (t >> 2) + ps * 64, k4 = (t & 3) * 4;
+                Bs[k4 + 0][n] = rb[ps].x; Bs[k4 + 1][n] = rb[ps].y;
+                Bs[k4 + 2][n] = rb[ps].z; Bs[k4 + 3][n] = rb[ps].w;
+            } else {
+                int k = (t >> 5) + ps * 8, n4 = (t & 31) * 4;
+                *reinterpret_cast<float4 *>(&Bs[k][n4]) = rb[ps];
+            }
+        }
+        __syncthreads();
+        // ---- LDS -> matrix cores.  32x32x2: lane l supplies A[m = l%32][k = l/32], B[k = l/32][n = l%32]
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            int ka = kk + (lane >> 5);
+            float a0 = As[ka][wm * 64 + (lane & 31)];
+            float a1 = As[ka][wm * 64 + 32 + (lane & 31)];
+            float b0 = Bs[ka][wn * 64 + (lane & 31)];
+            float b1 = Bs[ka][wn * 64 + 32 + (lane & 31)];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+    }
+    // ---- epilogue.  D register v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int row = wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                int col = wn * 64 + j * 32 + (lane & 31);
+                epi.store(m0 + row, n0 + col, acc[i][j][v]);
+            }
+}
+
+__global__ void k_zero16(float4 *p, int64_t n4)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n4; i += stride) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+__global__ void k_zero4(uint32_t *p, int64_t n)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = 0u;
+}
+
+}  // namespace
+
+// Zero `bytes` bytes (a multiple of 4, 4-byte aligned) with a fill kernel; no memset nodes,
+// so callers may capture the step in a HIP graph.
+int launch_fill_zero(void *ptr, size_t bytes, hipStream_t st)
+{
+    if (bytes == 0) return KGE_OK;
+    KGE_REQUIRE(((uintptr_t)ptr % 4) == 0 && bytes % 4 == 0, KGE_EINVAL,
+                "zero fill needs a 4-byte aligned buffer and size");
+    if (((uintptr_t)ptr % 16) == 0 && bytes % 16 == 0) {
+        int64_t n4 = (int64_t)(bytes / 16);
+        int64_t blocks = cdiv(n4, 256);
+        if (blocks > 65536) blocks = 65536;
+        k_zero16<<<(unsigned)blocks, 256, 0, st>>>(reinterpret_cast<float4 *>(ptr), n4);
+    } else {
+        int64_t n = (int64_t)(bytes / 4);
+        int64_t blocks = cdiv(n, 256);
+        if (blocks > 65536) blocks = 65536;
+        k_zero4<<<(unsigned)blocks, 256, 0, st>>>(reinterpret_cast<uint32_t *>(ptr), n);
+    }
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+int launch_project(const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const float *V,
+                   const float *W0, void *P, int msg_bf16, float *Self, hipStream_t st)
+{
+    if (N == 0) return KGE_OK;
+    int32_t nc = (B + 1) * d_out;
+    dim3 grid((unsigned)cdiv(N, BM), (unsigned)cdiv(nc, BN), 1);
+    SrcRowMajorF32 sa{H, N, d_in};
+    SrcWcat sb{V, W0, d_in, d_out, B};
+    if (msg_bf16) {
+        EpiProject<true> ep{P, Self, N, d_out, B};
+        k_gemm<SrcRowMajorF32, true, SrcWcat, false, EpiProject<true>><<<grid, GT, 0, st>>>(sa, sb, ep, d_in, d_in);
+    } else {
+        EpiProject<false> ep{P, Self, N, d_out, B};
+        k_gemm<SrcRowMajorF32, true, SrcWcat, false, EpiProject<false>><<<grid, GT, 0, st>>>(sa, sb, ep, d_in, d_in);
+    }
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+int launch_weight_grad(const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
+                       const void *dP, int msg_bf16, const float *G, float *dV, float *dW0,
+                       hipStream_t st)
+{
+    int rc = launch_fill_zero(dV, sizeof(float) * (size_t)B * d_in * d_out, st);
+    if (rc != KGE_OK) return rc;
+    rc = launch_fill_zero(dW0, sizeof(float) * (size_t)d_in * d_out, st);
+    if (rc != KGE_OK) return rc;
+    if (N == 0) return KGE_OK;
+    int32_t nc = (B + 1) * d_out;
+    int64_t tiles = cdiv(d_in, BM) * cdiv(nc, BN);
+    // split the N-long contraction so that roughly 2048 blocks are in flight
+    int64_t splits = cdiv(2048, tiles);
+    int64_t kchunk = cdiv(cdiv(N, splits), BK) * BK;
+    if (kchunk < 4 * BK) kchunk = 4 * BK;
+    splits = cdiv(N, kchunk);
+    dim3 grid((unsigned)cdiv(d_in, BM), (unsigned)cdiv(nc, BN), (unsigned)splits);
+    SrcRowMajorF32 sa{H, N, d_in};
+    EpiWeightGrad ep{dV, dW0, d_in, d_out, B};
+    if (msg_bf16) {
+        SrcXcat<true> sb{dP, G, N, d_out, B};
+        k_gemm<SrcRowMajorF32, false, SrcXcat<true>, false, EpiWeightGrad><<<grid, GT, 0, st>>>(sa, sb, ep, N, kchunk);
+    } else {
+        SrcXcat<false> sb{dP, G, N, d_out, B};
+        k_gemm<SrcRowMajorF32, false, SrcXcat<false>, false, EpiWeightGrad><<<grid, GT, 0, st>>>(sa, sb, ep, N, kchunk);
+    }
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+int launch_input_grad(const void *dP, int msg_bf16, const float *G, int64_t N, int32_t d_in,
+                      int32_t d_out, int32_t B, const float *V, const float *W0, float *dH,
+                      hipStream_t st)
+{
+    if (N == 0) return KGE_OK;
+    int32_t nc = (B + 1) * d_out;
+    dim3 grid((unsigned)cdiv(N, BM), (unsigned)cdiv(d_in, BN), 1);
+    SrcWcat sb{V, W0, d_in, d_out, B};
+    EpiRowMajor ep{dH, N, d_in};
+    if (msg_bf16) {
+        SrcXcat<true> sa{dP, G, N, d_out, B};
+        k_gemm<SrcXcat<true>, true, SrcWcat, true, EpiRowMajor><<<grid, GT, 0, st>>>(sa, sb, ep, nc, nc);
+    } else {
+        SrcXcat<false> sa{dP, G, N, d_out, B};
+        k_gemm<SrcXcat<false>, true, SrcWcat, true, EpiRowMajor><<<grid, GT, 0, st>>>(sa, sb, ep, nc, nc);
+    }
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}

@@ -1,0 +1,724 @@
+// build_partition on the GPU: core-edge selection by head hash (Sec. 3.2.1), n-hop
+// Neighborhood Expansion by frontier marking (Sec. 3.2.2), local relabelling, and the
+// (relation, destination, source, id)-sorted edge list with its runs, by a hand-written
+// stable LSD radix sort.  Two more stable sorts give the destination-major and source-major
+// views the aggregation kernels walk.  Runs once per partition; nothing here is in the
+// timed training step.
+#include <stdarg.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+
+namespace {
+
+constexpr int TB = 256;              // threads per block (4 wavefronts of 64)
+constexpr int SCAN_ITEMS = 8;        // items per thread in the scan kernels
+constexpr int SCAN_TILE = TB * SCAN_ITEMS;
+constexpr int SORT_ROWS = 8;         // 64-element rows per wavefront in a sort tile
+constexpr int SORT_TILE = TB * SORT_ROWS;
+
+__device__ __forceinline__ uint32_t part_of_head(int32_t head, uint32_t n_parts)
+{
+    return (((uint32_t)head * 0x9E3779B1u) >> 8) % n_parts;
+}
+
+// ---------------------------------------------------------------- marking
+__global__ void k_check_ids(const int32_t *head, const int32_t *rel, const int32_t *tail, int64_t M,
+                            int32_t n_ent, int32_t n_rel, uint32_t *bad)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    uint32_t h = (uint32_t)head[i], r = (uint32_t)rel[i], t = (uint32_t)tail[i];
+    if (h >= (uint32_t)n_ent || t >= (uint32_t)n_ent || r >= (uint32_t)n_rel) *bad = 1u;
+}
+
+__global__ void k_mark_core(const int32_t *head, const int32_t *tail, int64_t M, uint32_t n_parts,
+                            uint32_t part_id, uint32_t *core_flag, uint32_t *s0)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    uint32_t c = part_of_head(head[i], n_parts) == part_id ? 1u : 0u;
+    core_flag[i] = c;
+    if (c) { s0[head[i]] = 1u; s0[tail[i]] = 1u; }
+}
+
+// One expansion hop: a triple (s,r,t) carries s->t and t->s, so each endpoint in the
+// previous set pulls in the other.  prev is read-only during the pass.
+__global__ void k_expand(const int32_t *head, const int32_t *tail, int64_t M, const uint32_t *prev,
+                         uint32_t *cur)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    int32_t s = head[i], t = tail[i];
+    if (prev[t]) cur[s] = 1u;
+    if (prev[s]) cur[t] = 1u;
+}
+
+// ---------------------------------------------------------------- scan
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
+{
+    int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        uint32_t o = __shfl_up(v, off, 64);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+// Inclusive scan of one value per thread across the block; returns the exclusive prefix of
+// this thread and the block total.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *total)
+{
+    __shared__ uint32_t wsum[TB / 64];
+    int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t inc = wave_incl_scan(v);
+    if (lane == 63) wsum[w] = inc;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int k = 0; k < TB / 64; ++k) {
+        uint32_t s = wsum[k];
+        if (k < w) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+__global__ void k_scan_reduce(const uint32_t *in, int64_t n, uint32_t *block_sums)
+{
+    int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    uint32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k)
+        if (base + k < n) s += in[base + k];
+    uint32_t tot;
+    block_excl_scan(s, &tot);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
+}
+
+__global__ void k_scan_apply(const uint32_t *in, int64_t n, const uint32_t *block_offs, uint32_t *out)
+{
+    int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    uint32_t v[SCAN_ITEMS], s = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        v[k] = (base + k < n) ? in[base + k] : 0u;
+        s += v[k];
+    }
+    uint32_t tot;
+    uint32_t run = block_excl_scan(s, &tot) + block_offs[blockIdx.x];
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        if (base + k < n) out[base + k] = run;
+        run += v[k];
+    }
+}
+
+// Single block: exclusive scan of up to any n (loops), writes total to out[n].
+__global__ void k_scan_small(const uint32_t *in, int64_t n, uint32_t *out)
+{
+    __shared__ uint32_t carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int64_t start = 0; start < n; start += SCAN_TILE) {
+        int64_t base = start + (int64_t)threadIdx.x * SCAN_ITEMS;
+        uint32_t v[SCAN_ITEMS], s = 0;
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) {
+            v[k] = (base + k < n) ? in[base + k] : 0u;
+            s += v[k];
+        }
+        uint32_t tot;
+        uint32_t run = block_excl_scan(s, &tot) + carry;
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) {
+            if (base + k < n) out[base + k] = run;
+            run += v[k];
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) carry += tot;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[n] = carry;
+}
+
+// out[0..n) = exclusive prefix sums of in[0..n), out[n] = total.  out has n+1 entries and may
+// not alias in.  Temporary block sums are allocated here (build time only).
+int exclusive_scan(const uint32_t *in, uint32_t *out, int64_t n, hipStream_t st)
+{
+    if (n <= 4 * SCAN_TILE) {
+        k_scan_small<<<1, TB, 0, st>>>(in, n, out);
+        KGE_LAUNCH_CHECK();
+        return KGE_OK;
+    }
+    int64_t nb = cdiv(n, SCAN_TILE);
+    uint32_t *sums = nullptr, *offs = nullptr;
+    KGE_HIP(hipMalloc(&sums, sizeof(uint32_t) * (nb + 1)));
+    KGE_HIP(hipMalloc(&offs, sizeof(uint32_t) * (nb + 1)));
+    k_scan_reduce<<<(unsigned)nb, TB, 0, st>>>(in, n, sums);
+    KGE_LAUNCH_CHECK();
+    int rc = exclusive_scan(sums, offs, nb, st);
+    if (rc == KGE_OK) {
+        k_scan_apply<<<(unsigned)nb, TB, 0, st>>>(in, n, offs, out);
+        KGE_LAUNCH_CHECK();
+        // total = offs[nb]
+        KGE_HIP(hipMemcpyAsync(out + n, offs + nb, sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
+    }
+    KGE_HIP(hipStreamSynchronize(st));
+    (void)hipFree(sums);
+    (void)hipFree(offs);
+    return rc;
+}
+
+// ---------------------------------------------------------------- compaction kernels
+__global__ void k_vert_compact(const uint32_t *flag, const uint32_t *pos, int32_t n_ent,
+                               int32_t *vert_gid, int32_t *lid)
+{
+    int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= n_ent) return;
+    if (flag[g]) { vert_gid[pos[g]] = (int32_t)g; lid[g] = (int32_t)pos[g]; }
+    else lid[g] = -1;
+}
+
+__global__ void k_cand_compact(const uint32_t *flag, const uint32_t *pos, int32_t n_ent,
+                               const int32_t *lid, int32_t *cand)
+{
+    int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= n_ent) return;
+    if (flag[g]) cand[pos[g]] = lid[g];
+}
+
+__global__ void k_core_compact(const uint32_t *flag, const uint32_t *pos, int64_t M,
+                               const int32_t *head, const int32_t *rel, const int32_t *tail,
+                               const int32_t *lid, int32_t *core_eid, int32_t *core_h,
+                               int32_t *core_r, int32_t *core_t)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M || !flag[i]) return;
+    uint32_t q = pos[i];
+    core_eid[q] = (int32_t)i;
+    core_h[q] = lid[head[i]];
+    core_r[q] = rel[i];
+    core_t[q] = lid[tail[i]];
+}
+
+// Message edge e in [0, 2M): e < M is triple e in the given direction (dst = tail),
+// e >= M is the inverse of triple e-M (dst = head).  Kept iff dst is in S_{L-1}.
+__global__ void k_edge_flag(const int32_t *head, const int32_t *tail, int64_t M,
+                            const uint32_t *dstset, uint32_t *eflag)
+{
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= 2 * M) return;
+    int32_t dst = e < M ? tail[e] : head[e - M];
+    eflag[e] = dstset[dst] ? 1u : 0u;
+}
+
+__global__ void k_edge_emit(const int32_t *head, const int32_t *rel, const int32_t *tail, int64_t M,
+                            int32_t n_rel, const uint32_t *eflag, const uint32_t *epos,
+                            const int32_t *lid, int vbits, uint64_t *keys, uint32_t *vals)
+{
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= 2 * M || !eflag[e]) return;
+    int64_t i = e < M ? e : e - M;
+    uint64_t r = e < M ? (uint64_t)rel[i] : (uint64_t)(rel[i] + n_rel);
+    uint64_t dst = (uint64_t)(e < M ? lid[tail[i]] : lid[head[i]]);
+    uint64_t src = (uint64_t)(e < M ? lid[head[i]] : lid[tail[i]]);
+    uint32_t q = epos[e];
+    keys[q] = (r << (2 * vbits)) | (dst << vbits) | src;
+    vals[q] = (uint32_t)e;
+}
+
+// ---------------------------------------------------------------- radix sort
+// Stable LSD radix sort, 8 bits per pass.  A tile of SORT_TILE elements is split so that
+// wavefront w owns the contiguous chunk [w*512, (w+1)*512): ascending index order is then
+// (wavefront, row, lane), which is the order ranks are handed out in.
+template <typename K>
+__global__ void k_radix_hist(const K *keys, int64_t n, int shift, uint32_t *hist, int64_t nblk)
+{
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    int64_t base = (int64_t)blockIdx.x * SORT_TILE;
+#pragma unroll
+    for (int k = 0; k < SORT_ROWS; ++k) {
+        int64_t idx = base + (int64_t)k * TB + threadIdx.x;
+        if (idx < n) atomicAdd(&h[(uint32_t)(keys[idx] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+}
+
+template <typename K>
+__global__ void k_radix_scatter(const K *keys_in, const uint32_t *vals_in, K *keys_out,
+                                uint32_t *vals_out, int64_t n, int shift, const uint32_t *offs,
+                                int64_t nblk)
+{
+    __shared__ uint32_t cnt[TB / 64][256];
+    __shared__ uint32_t base[TB / 64][256];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+    for (int k = 0; k < TB / 64; ++k) cnt[k][threadIdx.x] = 0;
+    __syncthreads();
+
+    const int64_t start = (int64_t)blockIdx.x * SORT_TILE + (int64_t)w * (64 * SORT_ROWS);
+    K key[SORT_ROWS];
+    uint32_t val[SORT_ROWS], rank[SORT_ROWS];
+#pragma unroll
+    for (int it = 0; it < SORT_ROWS; ++it) {
+        int64_t idx = start + it * 64 + lane;
+        bool valid = idx < n;
+        key[it] = valid ? keys_in[idx] : (K)0;
+        val[it] = valid ? vals_in[idx] : 0u;
+        uint32_t digit = (uint32_t)(key[it] >> shift) & 255u;
+        unsigned long long mask = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            bool bit = (digit >> b) & 1u;
+            unsigned long long bal = __ballot(valid && bit);
+            mask &= bit ? bal : ~bal;
+        }
+        // mask: valid lanes of this row holding the same digit as this lane
+        uint32_t below = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+        uint32_t same = (uint32_t)__popcll(mask);
+        uint32_t prev = 0;
+        if (valid && below == 0) {          // lowest lane of its digit group updates the counter
+            prev = cnt[w][digit];
+            cnt[w][digit] = prev + same;
+        }
+        int leader = valid ? (__ffsll((long long)mask) - 1) : lane;
+        prev = __shfl(prev, leader, 64);
+        rank[it] = prev + below;
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+    {
+        uint32_t run = offs[(int64_t)threadIdx.x * nblk + blockIdx.x];
+#pragma unroll
+        for (int k = 0; k < TB / 64; ++k) {
+            base[k][threadIdx.x] = run;
+            run += cnt[k][threadIdx.x];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < SORT_ROWS; ++it) {
+        int64_t idx = start + it * 64 + lane;
+        if (idx < n) {
+            uint32_t digit = (uint32_t)(key[it] >> shift) & 255u;
+            uint32_t pos = base[w][digit] + rank[it];
+            keys_out[pos] = key[it];
+            vals_out[pos] = val[it];
+        }
+    }
+}
+
+// Sort (keys, vals) by the low `bits` bits of the key, stable.  Buffers ping-pong; on return
+// *keys / *vals point at the sorted data (either the original or the alternate buffers).
+template <typename K>
+int radix_sort(K **keys, uint32_t **vals, K **keys_alt, uint32_t **vals_alt, int64_t n, int bits,
+               hipStream_t st)
+{
+    if (n == 0) return KGE_OK;
+    int64_t nblk = cdiv(n, SORT_TILE);
+    uint32_t *hist = nullptr, *offs = nullptr;
+    KGE_HIP(hipMalloc(&hist, sizeof(uint32_t) * (256 * nblk + 1)));
+    KGE_HIP(hipMalloc(&offs, sizeof(uint32_t) * (256 * nblk + 1)));
+    int rc = KGE_OK;
+    for (int shift = 0; shift < bits && rc == KGE_OK; shift += 8) {
+        k_radix_hist<K><<<(unsigned)nblk, TB, 0, st>>>(*keys, n, shift, hist, nblk);
+        rc = exclusive_scan(hist, offs, 256 * nblk, st);
+        if (rc != KGE_OK) break;
+        k_radix_scatter<K><<<(unsigned)nblk, TB, 0, st>>>(*keys, *vals, *keys_alt, *vals_alt, n,
+                                                         shift, offs, nblk);
+        if (hipGetLastError() != hipSuccess) { kge_set_error("radix scatter launch failed"); rc = KGE_EHIP; }
+        K *tk = *keys; *keys = *keys_alt; *keys_alt = tk;
+        uint32_t *tv = *vals; *vals = *vals_alt; *vals_alt = tv;
+    }
+    (void)hipStreamSynchronize(st);
+    (void)hipFree(hist);
+    (void)hipFree(offs);
+    return rc;
+}
+
+// ---------------------------------------------------------------- runs and views
+__global__ void k_seg_flag(const uint64_t *keys, int64_t E, int vbits, uint32_t *flag)
+{
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    flag[e] = (e == 0 || (keys[e] >> vbits) != (keys[e - 1] >> vbits)) ? 1u : 0u;
+}
+
+__global__ void k_seg_emit(const uint64_t *keys, const uint32_t *vals, int64_t E, int vbits,
+                           const uint32_t *flag, const uint32_t *fpos, int32_t *seg_ptr,
+                           int32_t *seg_rel, int32_t *seg_dst, int32_t *col_src, int32_t *edge_id,
+                           uint32_t *edge_seg)
+{
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    uint64_t k = keys[e], vmask = (1ull << vbits) - 1ull;
+    col_src[e] = (int32_t)(k & vmask);
+    edge_id[e] = (int32_t)vals[e];
+    uint32_t s = fpos[e] + flag[e] - 1u;    // index of the run this edge belongs to
+    edge_seg[e] = s;
+    if (flag[e]) {
+        seg_ptr[s] = (int32_t)e;
+        seg_rel[s] = (int32_t)(k >> (2 * vbits));
+        seg_dst[s] = (int32_t)((k >> vbits) & vmask);
+    }
+}
+
+__global__ void k_inv_c(const int32_t *seg_ptr, int64_t S, float *inv_c)
+{
+    int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= S) return;
+    inv_c[s] = 1.0f / (float)(seg_ptr[s + 1] - seg_ptr[s]);
+}
+
+// keys2[e] = field of the sorted key selected by (shift, mask); vals2[e] = e
+__global__ void k_view_keys(const uint64_t *keys, int64_t E, int shift, uint64_t mask, uint32_t *k2,
+                            uint32_t *v2)
+{
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    k2[e] = (uint32_t)((keys[e] >> shift) & mask);
+    v2[e] = (uint32_t)e;
+}
+
+// After sorting positions by one endpoint: other endpoint, relation and 1/c of every edge.
+__global__ void k_view_emit(const uint32_t *pos_sorted, int64_t E, const uint64_t *keys, int vbits,
+                            int other_shift, const uint32_t *edge_seg, const float *inv_c,
+                            int32_t *o_vert, int32_t *o_rel, float *o_invc)
+{
+    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= E) return;
+    uint32_t e = pos_sorted[q];
+    uint64_t k = keys[e], vmask = (1ull << vbits) - 1ull;
+    o_vert[q] = (int32_t)((k >> other_shift) & vmask);
+    o_rel[q] = (int32_t)(k >> (2 * vbits));
+    o_invc[q] = inv_c[edge_seg[e]];
+}
+
+// ptr[v] = first position q with sorted[q] >= v, for v in [0, nv]; ptr[nv] = n.
+template <typename T>
+__global__ void k_ptr_from_sorted(const T *sorted, int64_t n, int64_t nv, int32_t *ptr)
+{
+    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q > n) return;
+    int64_t lo = (q == 0) ? 0 : (int64_t)sorted[q - 1] + 1;
+    int64_t hi = (q == n) ? nv : (int64_t)sorted[q];
+    for (int64_t v = lo; v <= hi; ++v) ptr[v] = (int32_t)q;
+}
+
+__global__ void k_max_degree(const int32_t *ptr, int64_t nv, int32_t *out)
+{
+    int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= nv) return;
+    atomicMax(out, ptr[v + 1] - ptr[v]);
+}
+
+__global__ void k_iota(int32_t *a, int64_t n)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) a[i] = (int32_t)i;
+}
+
+int bits_for(uint64_t n_values)   // bits to hold ids 0..n_values-1 (at least 1)
+{
+    int b = 1;
+    while ((1ull << b) < n_values) ++b;
+    return b;
+}
+
+struct TempBufs {
+    std::vector<void *> ptrs;
+    ~TempBufs() { for (void *q : ptrs) (void)hipFree(q); }
+    template <typename T> int alloc(T **out, size_t count)
+    {
+        void *q = nullptr;
+        hipError_t e = hipMalloc(&q, sizeof(T) * (count ? count : 1));
+        if (e != hipSuccess) { kge_set_error("hipMalloc of %zu bytes failed: %s", sizeof(T) * count, hipGetErrorString(e)); return KGE_ENOMEM; }
+        ptrs.push_back(q);
+        *out = (T *)q;
+        return KGE_OK;
+    }
+};
+
+template <typename T> int palloc(T **out, size_t count)
+{
+    void *q = nullptr;
+    hipError_t e = hipMalloc(&q, sizeof(T) * (count ? count : 1));
+    if (e != hipSuccess) { kge_set_error("hipMalloc of %zu bytes failed: %s", sizeof(T) * count, hipGetErrorString(e)); return KGE_ENOMEM; }
+    *out = (T *)q;
+    return KGE_OK;
+}
+
+#define TRY(x) do { int rc__ = (x); if (rc__ != KGE_OK) return rc__; } while (0)
+inline unsigned grid_for(int64_t n) { return (unsigned)(n > 0 ? cdiv(n, TB) : 1); }
+
+int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tail, int64_t M,
+               int32_t n_ent, int32_t n_rel, int32_t n_parts, int32_t part_id, int32_t n_hops,
+               int32_t neg_domain, kge_partition *p)
+{
+    hipStream_t st = nullptr;
+    TempBufs tmp;
+    int32_t *head, *rel, *tail;
+    TRY(tmp.alloc(&head, M)); TRY(tmp.alloc(&rel, M)); TRY(tmp.alloc(&tail, M));
+    KGE_HIP(hipMemcpy(head, h_head, sizeof(int32_t) * M, hipMemcpyHostToDevice));
+    KGE_HIP(hipMemcpy(rel, h_rel, sizeof(int32_t) * M, hipMemcpyHostToDevice));
+    KGE_HIP(hipMemcpy(tail, h_tail, sizeof(int32_t) * M, hipMemcpyHostToDevice));
+
+    uint32_t *bad;
+    TRY(tmp.alloc(&bad, 1));
+    KGE_HIP(hipMemsetAsync(bad, 0, sizeof(uint32_t), st));
+    if (M > 0) { k_check_ids<<<grid_for(M), TB, 0, st>>>(head, rel, tail, M, n_ent, n_rel, bad); KGE_LAUNCH_CHECK(); }
+    uint32_t h_bad = 0;
+    KGE_HIP(hipMemcpy(&h_bad, bad, sizeof(uint32_t), hipMemcpyDeviceToHost));
+    KGE_REQUIRE(!h_bad, KGE_ERANGE, "a triple has an entity or relation id out of range");
+
+    // --- core edges and S_0
+    uint32_t *core_flag, *s0, *prev, *cur, *dstset;
+    TRY(tmp.alloc(&core_flag, M)); TRY(tmp.alloc(&s0, n_ent)); TRY(tmp.alloc(&prev, n_ent));
+    TRY(tmp.alloc(&cur, n_ent)); TRY(tmp.alloc(&dstset, n_ent));
+    KGE_HIP(hipMemsetAsync(s0, 0, sizeof(uint32_t) * n_ent, st));
+    KGE_HIP(hipMemsetAsync(dstset, 0, sizeof(uint32_t) * n_ent, st));
+    if (M > 0) { k_mark_core<<<grid_for(M), TB, 0, st>>>(head, tail, M, (uint32_t)n_parts, (uint32_t)part_id, core_flag, s0); KGE_LAUNCH_CHECK(); }
+    KGE_HIP(hipMemcpyAsync(cur, s0, sizeof(uint32_t) * n_ent, hipMemcpyDeviceToDevice, st));
+    // --- expansion
+    for (int k = 1; k <= n_hops; ++k) {
+        KGE_HIP(hipMemcpyAsync(prev, cur, sizeof(uint32_t) * n_ent, hipMemcpyDeviceToDevice, st));
+        if (M > 0) { k_expand<<<grid_for(M), TB, 0, st>>>(head, tail, M, prev, cur); KGE_LAUNCH_CHECK(); }
+    }
+    if (n_hops >= 1) KGE_HIP(hipMemcpyAsync(dstset, prev, sizeof(uint32_t) * n_ent, hipMemcpyDeviceToDevice, st));
+
+    // --- local ids
+    uint32_t *vpos;
+    int32_t *lid;
+    TRY(tmp.alloc(&vpos, (size_t)n_ent + 1)); TRY(tmp.alloc(&lid, n_ent));
+    TRY(exclusive_scan(cur, vpos, n_ent, st));
+    uint32_t N32 = 0;
+    KGE_HIP(hipMemcpy(&N32, vpos + n_ent, sizeof(uint32_t), hipMemcpyDeviceToHost));
+    const int64_t N = N32;
+    p->n_vert = N;
+    TRY(palloc(&p->vert_gid, N));
+    k_vert_compact<<<grid_for(n_ent), TB, 0, st>>>(cur, vpos, n_ent, p->vert_gid, lid);
+    KGE_LAUNCH_CHECK();
+
+    // --- negative candidates
+    if (neg_domain == KGE_DOMAIN_CORE) {
+        uint32_t *cpos;
+        TRY(tmp.alloc(&cpos, (size_t)n_ent + 1));
+        TRY(exclusive_scan(s0, cpos, n_ent, st));
+        uint32_t nc = 0;
+        KGE_HIP(hipMemcpy(&nc, cpos + n_ent, sizeof(uint32_t), hipMemcpyDeviceToHost));
+        p->n_cand = nc;
+        TRY(palloc(&p->cand, nc));
+        k_cand_compact<<<grid_for(n_ent), TB, 0, st>>>(s0, cpos, n_ent, lid, p->cand);
+        KGE_LAUNCH_CHECK();
+    } else {
+        p->n_cand = N;
+        TRY(palloc(&p->cand, N));
+        if (N > 0) { k_iota<<<grid_for(N), TB, 0, st>>>(p->cand, N); KGE_LAUNCH_CHECK(); }
+    }
+
+    // --- core triples
+    {
+        uint32_t *kpos;
+        TRY(tmp.alloc(&kpos, (size_t)M + 1));
+        TRY(exclusive_scan(core_flag, kpos, M, st));
+        uint32_t nk = 0;
+        KGE_HIP(hipMemcpy(&nk, kpos + M, sizeof(uint32_t), hipMemcpyDeviceToHost));
+        p->n_core = nk;
+        TRY(palloc(&p->core_eid, nk)); TRY(palloc(&p->core_h, nk));
+        TRY(palloc(&p->core_r, nk)); TRY(palloc(&p->core_t, nk));
+        if (M > 0) {
+            k_core_compact<<<grid_for(M), TB, 0, st>>>(core_flag, kpos, M, head, rel, tail, lid,
+                                                      p->core_eid, p->core_h, p->core_r, p->core_t);
+            KGE_LAUNCH_CHECK();
+        }
+    }
+
+    // --- message edges into S_{L-1}
+    const int vbits = bits_for((uint64_t)(N > 0 ? N : 1));
+    const int rbits = bits_for((uint64_t)2 * n_rel);
+    KGE_REQUIRE(rbits + 2 * vbits <= 64, KGE_ERANGE,
+                "sort key needs %d bits (> 64): too many vertices or relations", rbits + 2 * vbits);
+    uint32_t *eflag, *epos;
+    TRY(tmp.alloc(&eflag, (size_t)2 * M)); TRY(tmp.alloc(&epos, (size_t)2 * M + 1));
+    if (M > 0) { k_edge_flag<<<grid_for(2 * M), TB, 0, st>>>(head, tail, M, dstset, eflag); KGE_LAUNCH_CHECK(); }
+    TRY(exclusive_scan(eflag, epos, 2 * M, st));
+    uint32_t E32 = 0;
+    KGE_HIP(hipMemcpy(&E32, epos + 2 * M, sizeof(uint32_t), hipMemcpyDeviceToHost));
+    const int64_t E = E32;
+    KGE_REQUIRE(E < 0x7fffffffLL, KGE_ERANGE, "too many message edges");
+    p->n_edge = E;
+
+    uint64_t *keys, *keys_alt;
+    uint32_t *vals, *vals_alt;
+    TRY(tmp.alloc(&keys, E)); TRY(tmp.alloc(&keys_alt, E));
+    TRY(tmp.alloc(&vals, E)); TRY(tmp.alloc(&vals_alt, E));
+    if (M > 0) {
+        k_edge_emit<<<grid_for(2 * M), TB, 0, st>>>(head, rel, tail, M, n_rel, eflag, epos, lid, vbits, keys, vals);
+        KGE_LAUNCH_CHECK();
+    }
+    TRY(radix_sort<uint64_t>(&keys, &vals, &keys_alt, &vals_alt, E, rbits + 2 * vbits, st));
+
+    // --- runs
+    uint32_t *sflag, *spos, *edge_seg;
+    TRY(tmp.alloc(&sflag, E)); TRY(tmp.alloc(&spos, (size_t)E + 1)); TRY(tmp.alloc(&edge_seg, E));
+    if (E > 0) { k_seg_flag<<<grid_for(E), TB, 0, st>>>(keys, E, vbits, sflag); KGE_LAUNCH_CHECK(); }
+    TRY(exclusive_scan(sflag, spos, E, st));
+    uint32_t S32 = 0;
+    KGE_HIP(hipMemcpy(&S32, spos + E, sizeof(uint32_t), hipMemcpyDeviceToHost));
+    const int64_t S = S32;
+    p->n_seg = S;
+    TRY(palloc(&p->seg_ptr, S + 1)); TRY(palloc(&p->seg_rel, S)); TRY(palloc(&p->seg_dst, S));
+    TRY(palloc(&p->inv_c, S)); TRY(palloc(&p->col_src, E)); TRY(palloc(&p->edge_id, E));
+    if (E > 0) {
+        k_seg_emit<<<grid_for(E), TB, 0, st>>>(keys, vals, E, vbits, sflag, spos, p->seg_ptr, p->seg_rel,
+                                              p->seg_dst, p->col_src, p->edge_id, edge_seg);
+        KGE_LAUNCH_CHECK();
+    }
+    int32_t E_i32 = (int32_t)E;
+    KGE_HIP(hipMemcpyAsync(p->seg_ptr + S, &E_i32, sizeof(int32_t), hipMemcpyHostToDevice, st));
+    KGE_HIP(hipStreamSynchronize(st));
+    if (S > 0) { k_inv_c<<<grid_for(S), TB, 0, st>>>(p->seg_ptr, S, p->inv_c); KGE_LAUNCH_CHECK(); }
+    TRY(palloc(&p->rel_ptr, (size_t)2 * n_rel + 1));
+    k_ptr_from_sorted<int32_t><<<grid_for(S + 1), TB, 0, st>>>(p->seg_rel, S, 2 * (int64_t)n_rel, p->rel_ptr);
+    KGE_LAUNCH_CHECK();
+
+    // --- destination-major and source-major views: stable sorts of edge positions
+    TRY(palloc(&p->dm_ptr, N + 1)); TRY(palloc(&p->dm_src, E)); TRY(palloc(&p->dm_rel, E)); TRY(palloc(&p->dm_invc, E));
+    TRY(palloc(&p->sm_ptr, N + 1)); TRY(palloc(&p->sm_dst, E)); TRY(palloc(&p->sm_rel, E)); TRY(palloc(&p->sm_invc, E));
+    uint32_t *k2, *k2_alt, *v2, *v2_alt;
+    TRY(tmp.alloc(&k2, E)); TRY(tmp.alloc(&k2_alt, E)); TRY(tmp.alloc(&v2, E)); TRY(tmp.alloc(&v2_alt, E));
+    int32_t *maxdeg;
+    TRY(tmp.alloc(&maxdeg, 2));
+    KGE_HIP(hipMemsetAsync(maxdeg, 0, 2 * sizeof(int32_t), st));
+    const uint64_t vmask = (1ull << vbits) - 1ull;
+    for (int view = 0; view < 2; ++view) {
+        const int key_shift = view == 0 ? vbits : 0;       // sort by dst (view 0) or src (view 1)
+        const int other_shift = view == 0 ? 0 : vbits;
+        int32_t *ptr = view == 0 ? p->dm_ptr : p->sm_ptr;
+        if (E > 0) { k_view_keys<<<grid_for(E), TB, 0, st>>>(keys, E, key_shift, vmask, k2, v2); KGE_LAUNCH_CHECK(); }
+        TRY(radix_sort<uint32_t>(&k2, &v2, &k2_alt, &v2_alt, E, vbits, st));
+        if (E > 0) {
+            k_view_emit<<<grid_for(E), TB, 0, st>>>(v2, E, keys, vbits, other_shift, edge_seg, p->inv_c,
+                                                   view == 0 ? p->dm_src : p->sm_dst,
+                                                   view == 0 ? p->dm_rel : p->sm_rel,
+                                                   view == 0 ? p->dm_invc : p->sm_invc);
+            KGE_LAUNCH_CHECK();
+        }
+        k_ptr_from_sorted<uint32_t><<<grid_for(E + 1), TB, 0, st>>>(k2, E, N, ptr);
+        KGE_LAUNCH_CHECK();
+        if (N > 0) { k_max_degree<<<grid_for(N), TB, 0, st>>>(ptr, N, maxdeg + view); KGE_LAUNCH_CHECK(); }
+    }
+    int32_t h_maxdeg[2] = {0, 0};
+    KGE_HIP(hipMemcpy(h_maxdeg, maxdeg, sizeof(h_maxdeg), hipMemcpyDeviceToHost));
+    p->max_in_degree = h_maxdeg[0];
+    p->max_out_degree = h_maxdeg[1];
+    KGE_HIP(hipStreamSynchronize(st));
+    return KGE_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ ABI
+static thread_local char g_err[512] = "";
+
+void kge_set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char *kge_last_error(void) { return g_err; }
+
+extern "C" void kge_partition_destroy(kge_partition *p)
+{
+    if (!p) return;
+    void *arrs[] = {p->vert_gid, p->core_eid, p->core_h, p->core_r, p->core_t, p->seg_ptr, p->seg_rel,
+                    p->seg_dst, p->inv_c, p->col_src, p->edge_id, p->cand, p->dm_ptr, p->dm_src,
+                    p->dm_rel, p->dm_invc, p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, p->rel_ptr};
+    for (void *q : arrs) if (q) (void)hipFree(q);
+    delete p;
+}
+
+extern "C" int kge_build_partition(const int32_t *head, const int32_t *rel, const int32_t *tail,
+                                   int64_t n_triples, int32_t n_entities, int32_t n_relations,
+                                   int32_t n_parts, int32_t part_id, int32_t n_hops,
+                                   int32_t neg_domain, kge_partition **out)
+{
+    KGE_REQUIRE(out, KGE_EINVAL, "out is NULL");
+    *out = nullptr;
+    KGE_REQUIRE(n_triples >= 0 && (n_triples == 0 || (head && rel && tail)), KGE_EINVAL,
+                "triple arrays are NULL or n_triples < 0");
+    KGE_REQUIRE(n_entities > 0 && n_relations > 0, KGE_EINVAL, "n_entities and n_relations must be positive");
+    KGE_REQUIRE(n_parts > 0 && part_id >= 0 && part_id < n_parts, KGE_EINVAL, "bad n_parts / part_id");
+    KGE_REQUIRE(n_hops >= 0 && n_hops <= 16, KGE_EINVAL, "n_hops must be in [0, 16]");
+    KGE_REQUIRE(neg_domain == KGE_DOMAIN_CORE || neg_domain == KGE_DOMAIN_ALL, KGE_EINVAL, "bad neg_domain");
+    KGE_REQUIRE(n_triples < 0x3fffffffLL, KGE_ERANGE, "n_triples must be below 2^30");
+    KGE_REQUIRE(n_relations < 0x3fffffff, KGE_ERANGE, "n_relations too large");
+    kge_partition *p = new kge_partition();
+    memset(p, 0, sizeof *p);
+    KGE_HIP(hipGetDevice(&p->device));
+    p->n_triples = n_triples; p->n_entities = n_entities; p->n_relations = n_relations;
+    p->n_parts = n_parts; p->part_id = part_id; p->n_hops = n_hops; p->neg_domain = neg_domain;
+    int rc = build_impl(head, rel, tail, n_triples, n_entities, n_relations, n_parts, part_id,
+                        n_hops, neg_domain, p);
+    if (rc != KGE_OK) { kge_partition_destroy(p); return rc; }
+    *out = p;
+    return KGE_OK;
+}
+
+extern "C" int kge_partition_info(const kge_partition *p, kge_part_info *o)
+{
+    KGE_REQUIRE(p && o, KGE_EINVAL, "NULL argument");
+    o->n_vert = p->n_vert; o->n_edge = p->n_edge; o->n_seg = p->n_seg; o->n_core = p->n_core;
+    o->n_cand = p->n_cand; o->n_triples = p->n_triples; o->n_entities = p->n_entities;
+    o->n_relations = p->n_relations; o->n_parts = p->n_parts; o->part_id = p->part_id;
+    o->n_hops = p->n_hops; o->neg_domain = p->neg_domain; o->max_in_degree = p->max_in_degree;
+    o->max_out_degree = p->max_out_degree;
+    return KGE_OK;
+}
+
+extern "C" int kge_partition_export(const kge_partition *p, int32_t which, void *host_dst, int64_t bytes)
+{
+    KGE_REQUIRE(p && (host_dst || bytes == 0), KGE_EINVAL, "NULL argument");
+    const void *src = nullptr;
+    int64_t n = 0;
+    switch (which) {
+    case KGE_ARR_VERT_GID: src = p->vert_gid; n = p->n_vert; break;
+    case KGE_ARR_CORE_EID: src = p->core_eid; n = p->n_core; break;
+    case KGE_ARR_CORE_H: src = p->core_h; n = p->n_core; break;
+    case KGE_ARR_CORE_R: src = p->core_r; n = p->n_core; break;
+    case KGE_ARR_CORE_T: src = p->core_t; n = p->n_core; break;
+    case KGE_ARR_SEG_PTR: src = p->seg_ptr; n = p->n_seg + 1; break;
+    case KGE_ARR_SEG_REL: src = p->seg_rel; n = p->n_seg; break;
+    case KGE_ARR_SEG_DST: src = p->seg_dst; n = p->n_seg; break;
+    case KGE_ARR_INV_C: src = p->inv_c; n = p->n_seg; break;
+    case KGE_ARR_COL_SRC: src = p->col_src; n = p->n_edge; break;
+    case KGE_ARR_EDGE_ID: src = p->edge_id; n = p->n_edge; break;
+    case KGE_ARR_CAND: src = p->cand; n = p->n_cand; break;
+    case KGE_ARR_DM_PTR: src = p->dm_ptr; n = p->n_vert + 1; break;
+    case KGE_ARR_DM_SRC: src = p->dm_src; n = p->n_edge; break;
+    case KGE_ARR_DM_REL: src = p->dm_rel; n = p->n_edge; break;
+    case KGE_ARR_DM_INVC: src = p->dm_invc; n = p->n_edge; break;
+    case KGE_ARR_SM_PTR: src = p->sm_ptr; n = p->n_vert + 1; break;
+    case KGE_ARR_SM_DST: src = p->sm_dst; n = p->n_edge; break;
+    case KGE_ARR_SM_REL: src = p->sm_rel; n = p->n_edge; break;
+    case KGE_ARR_SM_INVC: src = p->sm_invc; n = p->n_edge; break;
+    case KGE_ARR_REL_PTR: src = p->rel_ptr; n = 2 * (int64_t)p->n_relations + 1; break;
+    default: KGE_REQUIRE(false, KGE_EINVAL, "unknown array id %d", which);
+    }
+    KGE_REQUIRE(bytes == 4 * n, KGE_EINVAL, "array %d has %lld bytes, caller gave %lld", which,
+                (long long)(4 * n), (long long)bytes);
+    if (n > 0) KGE_HIP(hipMemcpy(host_dst, src, (size_t)bytes, hipMemcpyDeviceToHost));
+    return KGE_OK;
+}

@@ -1,0 +1,78 @@
+"""One training step of Algorithm 1 on one partition: buffer ownership and call order.
+
+Holds the torch tensors (device memory only) and issues the library calls in order on one
+stream: encoder forward -> negatives -> score/loss -> encoder backward.  No arithmetic of
+the method happens in Python or torch.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+from . import binding as kb
+
+
+class TrainStep:
+    def __init__(self, part: kb.Partition, params: Dict[str, object], acts: Sequence[int],
+                 msg_dtype: int = kb.MSG_F32, need_dH0: bool = True, device: str = "cuda:0",
+                 keep_scores: bool = True):
+        import torch
+        self.torch = torch
+        self.part = part
+        self.dev = torch.device(device)
+        self.msg_dtype = msg_dtype
+        t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(self.dev)
+        self.layers: List[dict] = []
+        for V, a, W0, act in zip(params["V"], params["a"], params["W0"], acts):
+            self.layers.append(dict(V=t(V), a=t(a), W0=t(W0), act=int(act)))
+        self.M = t(params["M"])
+        self.H0 = t(params["H0"])
+        N = part.n_vert
+        assert self.H0.shape[0] == N
+        d_out = self.layers[-1]["V"].shape[2]
+        self.H_out = torch.empty((N, d_out), dtype=torch.float32, device=self.dev)
+        self.dH_out = torch.empty_like(self.H_out)
+        self.dM = torch.empty_like(self.M)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=self.dev)
+        self.grads = [dict(dV=torch.empty_like(l["V"]), da=torch.empty_like(l["a"]),
+                           dW0=torch.empty_like(l["W0"])) for l in self.layers]
+        self.dH0 = torch.empty_like(self.H0) if need_dH0 else None
+        self.ws_bytes = kb.workspace_bytes(part, self.layers, msg_dtype)
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.keep_scores = keep_scores
+        self.pos = None
+        self.neg_ent = self.neg_side = self.scores = None
+        self.n_neg = 0
+
+    def set_batch(self, pos_core_idx: np.ndarray, n_neg: int):
+        torch = self.torch
+        self.pos = torch.from_numpy(np.ascontiguousarray(pos_core_idx, np.int32)).to(self.dev)
+        n_pos = self.pos.numel()
+        self.n_neg = int(n_neg)
+        self.neg_ent = torch.empty((n_pos, max(n_neg, 1)), dtype=torch.int32, device=self.dev)
+        self.neg_side = torch.empty((n_pos, max(n_neg, 1)), dtype=torch.uint8, device=self.dev)
+        self.scores = (torch.empty((n_pos, 1 + n_neg), dtype=torch.float32, device=self.dev)
+                       if self.keep_scores else None)
+
+    # --- the four per-step calls, in Algorithm 1's order
+    def forward(self, stream=None):
+        kb.rgcn_forward(self.part, self.layers, self.H0, self.workspace, self.H_out, self.msg_dtype, stream)
+
+    def sample(self, mode: int, seed: int, step: int, stream=None):
+        kb.sample_negatives(self.part, self.pos, self.n_neg, mode, seed, step, self.neg_ent, self.neg_side, stream)
+
+    def score_loss(self, stream=None):
+        kb.distmult_score_loss(self.part, self.H_out, self.M, self.pos, self.neg_ent, self.neg_side,
+                               self.n_neg, self.scores, self.loss, self.dH_out, self.dM, stream)
+
+    def backward(self, stream=None):
+        kb.rgcn_backward(self.part, self.layers, self.H0, self.workspace, self.dH_out, self.grads,
+                         self.dH0, self.msg_dtype, stream)
+
+    def run(self, mode: int, seed: int, step: int, stream=None):
+        self.forward(stream)
+        self.sample(mode, seed, step, stream)
+        self.score_loss(stream)
+        self.backward(stream)

@@ -1,0 +1,86 @@
+"""Helpers of the GPU parity tests: run the HIP library and the CPU oracle on the same
+seeded inputs and compare."""
+import numpy as np
+
+from paper_2201_02791_amd import synth
+
+SEED, STEP = 0x5EEDC0DE12345, 3
+
+
+def rel_err(x, y):
+    """Per-tensor relative error: max|x - y| / max|y| (y is the oracle)."""
+    x = np.asarray(x, np.float64); y = np.asarray(y, np.float64)
+    if y.size == 0:
+        return 0.0
+    scale = max(np.abs(y).max(), 1e-30)
+    return float(np.abs(x - y).max() / scale)
+
+
+def layers_of(params, acts):
+    return [dict(V=params["V"][l], a=params["a"][l], W0=params["W0"][l], act=acts[l])
+            for l in range(len(acts))]
+
+
+def gpu_step(spec, head, rel, tail, params=None, pos=None, need_dH0=True):
+    """Build the partition and run one step on the GPU. Returns (part, step object, params, pos)."""
+    from paper_2201_02791_amd import binding as kb
+    from paper_2201_02791_amd.step import TrainStep
+    import torch
+    part = kb.build_partition(head, rel, tail, spec.n_entities, spec.n_relations, spec.n_parts,
+                              spec.part_id, spec.n_hops, spec.neg_domain)
+    if params is None:
+        params = synth.make_params(spec, part.n_vert)
+    if pos is None:
+        pos = synth.make_batch(spec, part.n_core)
+    msg = kb.MSG_BF16 if spec.msg_dtype == "bf16" else kb.MSG_F32
+    ts = TrainStep(part, params, spec.acts, msg, need_dH0=need_dH0)
+    ts.set_batch(pos, spec.n_neg)
+    ts.run(spec.neg_mode, SEED, STEP)
+    torch.cuda.synchronize()
+    return part, ts, params, pos
+
+
+def oracle_step(orc, spec, head, rel, tail, params, pos, need_dH0=True):
+    part = orc.build_partition(head, rel, tail, spec.n_entities, spec.n_relations, spec.n_parts,
+                               spec.part_id, spec.n_hops, spec.neg_domain)
+    res = orc.train_step(part, layers_of(params, spec.acts), params["H0"], params["M"], pos,
+                         spec.n_neg, spec.neg_mode, SEED, STEP, need_dH0)
+    return part, res
+
+
+PART_ARRAYS = ["vert_gid", "core_eid", "core_h", "core_r", "core_t", "seg_ptr", "seg_rel", "seg_dst",
+               "inv_c", "col_src", "edge_id", "cand"]
+
+
+def assert_partition_equal(gpart, opart):
+    for k in ("n_vert", "n_edge", "n_seg", "n_core", "n_cand"):
+        assert getattr(gpart, k) == opart[k], k
+    for name in PART_ARRAYS:
+        got = gpart.export(name)
+        want = opart[name]
+        assert got.dtype == want.dtype, name
+        if name == "inv_c":       # compared as bit patterns
+            np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32), err_msg=name)
+        else:
+            np.testing.assert_array_equal(got, want, err_msg=name)
+
+
+def assert_step_close(ts, res, tol_val, tol_grad, need_dH0=True):
+    """Compare every output of a GPU step with the oracle's."""
+    c = lambda t: t.detach().cpu().numpy()
+    errs = {}
+    np.testing.assert_array_equal(c(ts.neg_ent)[:, :ts.n_neg], res["neg_ent"])
+    np.testing.assert_array_equal(c(ts.neg_side)[:, :ts.n_neg], res["neg_side"])
+    errs["H_out"] = (rel_err(c(ts.H_out), res["Hs"][-1]), tol_val)
+    errs["scores"] = (rel_err(c(ts.scores), res["scores"]), tol_val)
+    errs["loss"] = (abs(float(c(ts.loss)[0]) - res["loss"]) / abs(res["loss"]), tol_val)
+    errs["dH_out"] = (rel_err(c(ts.dH_out), res["dH_out"]), tol_grad)
+    errs["dM"] = (rel_err(c(ts.dM), res["dM"]), tol_grad)
+    for l, g in enumerate(ts.grads):
+        for k in ("dV", "da", "dW0"):
+            errs["%s%d" % (k, l)] = (rel_err(c(g[k]), res["grads"][l][k]), tol_grad)
+    if need_dH0:
+        errs["dH0"] = (rel_err(c(ts.dH0), res["dH0"]), tol_grad)
+    bad = {k: v for k, v in errs.items() if not (v[0] <= v[1])}
+    assert not bad, "relative errors above tolerance: %s (all: %s)" % (bad, errs)
+    return errs
