@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark: one training step (RGCN forward + in-partition negatives + DistMult/BCE +
+RGCN backward) on one self-sufficient partition, on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C]
+
+Prints ONE JSON line: whole-step throughput in message edges per second (inputs resident in
+HBM), the roofline figures of the kernel that takes most of the step (HIP events recorded by
+the library on the launch stream during the timed steps), and the CPU oracle timed on this
+host as a baseline.  Data is synthetic and seeded (paper_2201_02791_amd/synth.py).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_F32_MFMA_TFLOPS = 157.3
+PEAK_BF16_MFMA_TFLOPS = 2500.0
+
+
+def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg):
+    """Algorithmic bytes / flops of ONE launch of a kernel (what the method itself must move
+    or compute in this formulation).  Returns (bound, work, unit_is_bytes)."""
+    N, E, S = part.n_vert, part.n_edge, part.n_seg
+    R2 = 2 * part.n_relations
+    gemm_flops = 2.0 * N * d * (B + 1) * d
+    if name == "gather_fwd":   # per edge: P row + (src, rel, 1/c); per vertex: ptr + Self read + output write
+        return "hbm", E * (B * d * ep + 12.0) + N * (4.0 + 8.0 * d) + R2 * B * 4.0
+    if name == "coeff_seg":    # per edge: P row + src; per run: ptr/dst/1/c + G row + B outputs
+        return "hbm", E * (B * d * ep + 4.0) + S * (12.0 + 4.0 * d + 4.0 * B)
+    if name == "gather_t":     # per edge: G row + (dst, rel, 1/c); per vertex: ptr + dP row write
+        return "hbm", E * (4.0 * d + 12.0) + N * (4.0 + B * d * ep) + R2 * B * 4.0
+    if name == "distmult":     # per scored group: h_s, h_t, M_r + one row per negative, read and atomically updated
+        return "hbm", n_pos * (3.0 + n_neg) * d * 4.0 * 2.0 + n_pos * n_neg * 5.0
+    if name == "project":
+        return "mfma", gemm_flops
+    if name == "weight_grad":
+        return "mfma", gemm_flops
+    if name == "input_grad":
+        return "mfma", gemm_flops
+    if name == "act_bwd":
+        return "hbm", 12.0 * N * d
+    if name == "coeff_reduce":
+        return "hbm", 4.0 * S * B
+    return "hbm", 0.0
+
+
+def cpu_baseline(spec, cfg_index):
+    """The oracle as it stands, timed on this host (1 thread), on a bounded sample: the whole
+    step on the same generator recipe, scaled down so that it takes roughly 10-30 s."""
+    from paper_2201_02791_amd import synth
+    from oracle import oracle as orc
+    # oracle cost ~ 8 N B d^2 (projections, fwd+bwd, 2 layers) + 6 E B d  FMAs at roughly 1.5e9 FMA/s
+    budget = 25e9
+    per_vertex = 8.0 * spec.n_bases * spec.d * spec.d + 6.0 * 2.0 * (spec.n_triples / spec.n_entities) * spec.n_bases * spec.d
+    n = int(min(spec.n_entities, max(200, budget / per_vertex)))
+    scale = n / spec.n_entities
+    m = max(400, int(spec.n_triples * scale))
+    small = synth.scaled(spec, n_entities=n, n_triples=m, n_parts=1, part_id=0,
+                         n_pos=max(16, int(spec.n_pos * scale)))
+    head, rel, tail = synth.make_triples(small)
+    part = orc.build_partition(head, rel, tail, small.n_entities, small.n_relations, 1, 0, small.n_hops,
+                               small.neg_domain)
+    params = synth.make_params(small, part["n_vert"])
+    layers = [dict(V=params["V"][l], a=params["a"][l], W0=params["W0"][l], act=small.acts[l])
+              for l in range(small.n_layers)]
+    pos = synth.make_batch(small, part["n_core"])
+    t0 = time.perf_counter()
+    orc.train_step(part, layers, params["H0"], params["M"], pos, small.n_neg, small.neg_mode, 1, 0,
+                   need_dH0=not small.fixed_features)
+    dt = time.perf_counter() - t0
+    return {"value": part["n_edge"] / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
+            "host_cores": os.cpu_count(),
+            "sample": "whole oracle step on the same recipe scaled to %d entities / %d triples "
+                      "(%d message edges, d=%d, %d bases), %.1f s" % (n, m, part["n_edge"], small.d,
+                                                                      small.n_bases, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3, help="index into the workload list (0..4)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one partition per GPU, no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2201_02791_amd import binding as kb, synth
+    from paper_2201_02791_amd.step import TrainStep
+    kb.load()
+    assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU fallback)"
+    spec = synth.WORKLOADS[args.config]
+    log = lambda *a: print("[bench]", *a, file=sys.stderr, flush=True)
+
+    t0 = time.time()
+    head, rel, tail = synth.make_triples(spec)
+    log("graph %s: %d entities, %d triples (%.1f s)" % (spec.name, spec.n_entities, len(head), time.time() - t0))
+    t0 = time.time()
+    part = kb.build_partition(head, rel, tail, spec.n_entities, spec.n_relations, spec.n_parts, spec.part_id,
+                              spec.n_hops, spec.neg_domain)
+    log("partition %d/%d: N=%d E=%d S=%d core=%d cand=%d max_in=%d max_out=%d (%.1f s)" % (
+        spec.part_id, spec.n_parts, part.n_vert, part.n_edge, part.n_seg, part.n_core, part.n_cand,
+        part.max_in_degree, part.max_out_degree, time.time() - t0))
+    del head, rel, tail
+    params = synth.make_params(spec, part.n_vert)
+    pos = synth.make_batch(spec, part.n_core)
+    msg = kb.MSG_BF16 if spec.msg_dtype == "bf16" else kb.MSG_F32
+    ts = TrainStep(part, params, spec.acts, msg, need_dH0=not spec.fixed_features, keep_scores=True)
+    ts.set_batch(pos, spec.n_neg)
+    log("workspace %.2f GB" % (ts.ws_bytes / 1e9))
+
+    stream = torch.cuda.current_stream()
+    for w in range(args.warmup):
+        ts.run(spec.neg_mode, 1234, w)
+    torch.cuda.synchronize()
+    kb.profile_enable(True)
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ts.run(spec.neg_mode, 1234, args.warmup + k)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kb.profile_enable(False)
+    prof = kb.profile_collect()
+    loss = float(ts.loss.cpu()[0])
+
+    ms_per_step = 1e3 * dt / args.steps
+    E = part.n_edge
+    n_pos, n_neg = len(pos), spec.n_neg
+    T = n_pos * (1 + n_neg)
+    ep = 2 if spec.msg_dtype == "bf16" else 4
+    kernels = {}
+    for name, (tot_ms, calls) in prof.items():
+        bound, work = kernel_work(name, part, spec, spec.d, spec.n_bases, ep, n_pos, n_neg)
+        avg_ms = tot_ms / max(calls, 1)
+        if bound == "hbm":
+            ach, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+        else:
+            ach, peak, unit = work / (avg_ms * 1e-3) / 1e12, PEAK_F32_MFMA_TFLOPS, "TFLOP/s"
+        kernels[name] = {"ms_per_step": tot_ms / args.steps, "launches_per_step": calls / args.steps,
+                         "avg_ms": avg_ms, "bound": bound, "achieved": ach, "peak": peak, "unit": unit,
+                         "frac": ach / peak if peak else None}
+    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"]) if kernels else None
+    roof = None
+    if dominant:
+        kd = kernels[dominant]
+        roof = {"kernel": dominant, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
+                "unit": kd["unit"], "frac": kd["frac"], "traffic": None, "avg_launch_ms": kd["avg_ms"]}
+    for name in sorted(kernels, key=lambda k: -kernels[k]["ms_per_step"]):
+        kd = kernels[name]
+        log("%-13s %8.3f ms/step  %5.1f launches  %9.1f %s  (%.1f%% of peak)" % (
+            name, kd["ms_per_step"], kd["launches_per_step"], kd["achieved"], kd["unit"], 100 * kd["frac"]))
+
+    base = None
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample ...")
+        base = cpu_baseline(spec, args.config)
+
+    out = {"metric": "train-step edges/s (RGCN fwd+bwd + DistMult) on 1 GPU",
+           "value": E / (dt / args.steps), "unit": "edges/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16 messages, f32 accumulate" if ep == 2 else "f32",
+           "data": "synthetic",
+           "config": {"workload": "configs[%d] %s" % (args.config, spec.name), "n_vertices": part.n_vert,
+                      "message_edges": E, "runs": part.n_seg, "d": spec.d, "bases": spec.n_bases,
+                      "relations_with_inverses": 2 * spec.n_relations, "layers": spec.n_layers,
+                      "positives": n_pos, "negatives_per_positive": n_neg, "parallelism": "1 partition on 1 GPU"},
+           "triples_per_s": T / (dt / args.steps), "loss": loss,
+           "roofline": roof, "cpu_baseline": base, "kernels": kernels}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

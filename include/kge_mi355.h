@@ -207,6 +207,21 @@ int kge_distmult_score_loss(const kge_partition *p, const float *H, const float 
                             const uint8_t *neg_side, int32_t n_neg, float *scores, float *loss,
                             float *dH, float *dM, void *stream);
 
+/*
+ * Per-kernel timing for benchmarks (not part of the training path).  While enabled, every
+ * kernel launch of the per-step calls is bracketed by two HIP events recorded on the launch
+ * stream.  kge_profile_collect waits for the recorded events, sums the elapsed time per
+ * kernel name into out[0..*n_entries) (at most max_entries), and clears the records.
+ * Not thread safe; enabling allocates events, so keep it off in allocation-free callers.
+ */
+typedef struct kge_prof_entry {
+    char name[32];
+    double total_ms;
+    int64_t calls;
+} kge_prof_entry;
+int kge_profile_enable(int32_t on);
+int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_entries);
+
 /* Message of the last failure on the calling thread ("" if none). */
 const char *kge_last_error(void);
 

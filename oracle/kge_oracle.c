@@ -220,9 +220,24 @@ void orc_partition_copy(const orc_partition *p, int32_t which, void *dst)
 static double act_fwd(int act, double x) { return act == 1 ? (x > 0.0 ? x : 0.0) : x; }
 static double act_grad(int act, double pre) { return act == 1 ? (pre > 0.0 ? 1.0 : 0.0) : 1.0; }
 
+/* Storage rounding of a projected message when the workload keeps messages in bfloat16:
+ * to float, then to the nearest bfloat16 (ties to even).  Everything else stays double. */
+static double round_msg(double x, int32_t msg_bf16)
+{
+    if (!msg_bf16) return x;
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return x;            /* NaN */
+    uint32_t lower = u & 0xffffu, keep = u & 0xffff0000u;
+    if (lower > 0x8000u || (lower == 0x8000u && (keep & 0x10000u))) keep += 0x10000u;
+    memcpy(&f, &keep, 4);
+    return (double)f;
+}
+
 /* P[j][b][:] = h_j V_b  — the B projections of every vertex (Eq. 2 applied to h_j). */
 static void project_all(int64_t N, int32_t d_in, int32_t d_out, int32_t B,
-                        const double *V, const double *H, double *P)
+                        const double *V, const double *H, double *P, int32_t msg_bf16)
 {
     memset(P, 0, sizeof(double) * (size_t)N * (size_t)B * (size_t)d_out);
     for (int64_t j = 0; j < N; ++j)
@@ -234,6 +249,7 @@ static void project_all(int64_t N, int32_t d_in, int32_t d_out, int32_t B,
                 const double *vrow = Vb + (size_t)k * d_out;
                 for (int32_t o = 0; o < d_out; ++o) out[o] += h * vrow[o];
             }
+            if (msg_bf16) for (int32_t o = 0; o < d_out; ++o) out[o] = round_msg(out[o], 1);
         }
 }
 
@@ -241,15 +257,17 @@ static void project_all(int64_t N, int32_t d_in, int32_t d_out, int32_t B,
  * One layer forward over the whole partition:
  *   pre_i = sum_r sum_{j in N_i^r} (1/c_{i,r}) h_j W_r + h_i W_0,   W_r = sum_b a_rb V_b
  *   h'_i  = act(pre_i)                        act: 0 identity, 1 ReLU
- * P_scratch is [N][B][d_out] doubles.
+ * P_scratch is [N][B][d_out] doubles.  msg_bf16 != 0 models a workload that stores the
+ * projected messages in bfloat16 (they are rounded once, when written); 0 keeps them exact.
  */
 void orc_rgcn_layer_forward(int64_t N, int64_t S, const int32_t *seg_ptr, const int32_t *seg_rel,
                             const int32_t *seg_dst, const int32_t *col_src,
                             int32_t d_in, int32_t d_out, int32_t B,
                             const double *V, const double *a, const double *W0, int32_t act,
+                            int32_t msg_bf16,
                             const double *H, double *P_scratch, double *pre, double *Hout)
 {
-    project_all(N, d_in, d_out, B, V, H, P_scratch);
+    project_all(N, d_in, d_out, B, V, H, P_scratch, msg_bf16);
     /* self-loop: h_i W_0 */
     for (int64_t i = 0; i < N; ++i) {
         double *o = pre + (size_t)i * d_out;
@@ -287,6 +305,7 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
                          const int64_t *row_seg, const int32_t *seg_ptr, const int32_t *seg_rel,
                          const int32_t *col_src, int32_t d_in, int32_t d_out, int32_t B,
                          const double *V, const double *a, const double *W0, int32_t act,
+                         int32_t msg_bf16,
                          const float *H /* [N][d_in], the layer input as stored */,
                          double *pre_rows, double *out_rows)
 {
@@ -313,7 +332,7 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
                         for (int32_t c = 0; c < d_out; ++c) pj[c] += h * Vb[(size_t)k * d_out + c];
                     }
                     double w = a[(size_t)r * B + b] * invc;
-                    for (int32_t c = 0; c < d_out; ++c) o[c] += w * pj[c];
+                    for (int32_t c = 0; c < d_out; ++c) o[c] += w * round_msg(pj[c], msg_bf16);
                 }
             }
         }
@@ -336,13 +355,14 @@ void orc_rgcn_layer_backward(int64_t N, int64_t S, const int32_t *seg_ptr, const
                              const int32_t *seg_dst, const int32_t *col_src,
                              int32_t d_in, int32_t d_out, int32_t B, int32_t n_rel2,
                              const double *V, const double *a, const double *W0, int32_t act,
+                             int32_t msg_bf16,
                              const double *H, const double *pre, const double *dHout,
                              double *P_scratch, double *dP_scratch, double *Gpre,
                              double *dV, double *da, double *dW0, double *dH_in)
 {
     size_t nd_out = (size_t)N * d_out;
     for (size_t q = 0; q < nd_out; ++q) Gpre[q] = dHout[q] * act_grad(act, pre[q]);
-    project_all(N, d_in, d_out, B, V, H, P_scratch);
+    project_all(N, d_in, d_out, B, V, H, P_scratch, msg_bf16);
     memset(dP_scratch, 0, sizeof(double) * (size_t)N * B * d_out);
     memset(dV, 0, sizeof(double) * (size_t)B * d_in * d_out);
     memset(da, 0, sizeof(double) * (size_t)n_rel2 * B);

@@ -85,7 +85,7 @@ def _d(x):
     return np.ascontiguousarray(x, np.float64)
 
 
-def layer_forward(part, V, a, W0, act, H):
+def layer_forward(part, V, a, W0, act, H, msg_bf16=False):
     """One RGCN layer over the whole partition (Eq. 1-2). Returns (pre, H') in float64."""
     L = lib()
     V, a, W0, H = _d(V), _d(a), _d(W0), _d(H)
@@ -99,22 +99,23 @@ def layer_forward(part, V, a, W0, act, H):
                              _p(part["seg_rel"], _I32), _p(part["seg_dst"], _I32),
                              _p(part["col_src"], _I32), C.c_int32(d_in), C.c_int32(d_out),
                              C.c_int32(B), _p(V, _F64), _p(a, _F64), _p(W0, _F64), C.c_int32(act),
+                             C.c_int32(1 if msg_bf16 else 0),
                              _p(H, _F64), _p(P, _F64), _p(pre, _F64), _p(out, _F64))
     return pre, out
 
 
-def rgcn_forward(part, layers: Sequence[dict], H0):
+def rgcn_forward(part, layers: Sequence[dict], H0, msg_bf16=False):
     """All layers.  ``layers[l]`` has V [B,d,d], a [2R,B], W0 [d,d], act.  Returns the list of
     layer inputs/outputs ``Hs`` (len L+1, Hs[0] = H0) and pre-activations ``pres`` (len L)."""
     Hs, pres = [_d(H0)], []
     for lay in layers:
-        pre, out = layer_forward(part, lay["V"], lay["a"], lay["W0"], lay["act"], Hs[-1])
+        pre, out = layer_forward(part, lay["V"], lay["a"], lay["W0"], lay["act"], Hs[-1], msg_bf16)
         pres.append(pre)
         Hs.append(out)
     return Hs, pres
 
 
-def layer_backward(part, V, a, W0, act, H, pre, dHout, need_dH=True):
+def layer_backward(part, V, a, W0, act, H, pre, dHout, need_dH=True, msg_bf16=False):
     L = lib()
     V, a, W0, H, pre, dHout = _d(V), _d(a), _d(W0), _d(H), _d(pre), _d(dHout)
     B, d_in, d_out = V.shape
@@ -126,27 +127,28 @@ def layer_backward(part, V, a, W0, act, H, pre, dHout, need_dH=True):
                               _p(part["seg_rel"], _I32), _p(part["seg_dst"], _I32),
                               _p(part["col_src"], _I32), C.c_int32(d_in), C.c_int32(d_out),
                               C.c_int32(B), C.c_int32(a.shape[0]), _p(V, _F64), _p(a, _F64),
-                              _p(W0, _F64), C.c_int32(act), _p(H, _F64), _p(pre, _F64),
+                              _p(W0, _F64), C.c_int32(act), C.c_int32(1 if msg_bf16 else 0),
+                              _p(H, _F64), _p(pre, _F64),
                               _p(dHout, _F64), _p(P, _F64), _p(dP, _F64), _p(G, _F64),
                               _p(dV, _F64), _p(da, _F64), _p(dW0, _F64),
                               _p(dH, _F64) if need_dH else None)
     return dict(dV=dV, da=da, dW0=dW0, dH=dH, dP=dP, Gpre=G)
 
 
-def rgcn_backward(part, layers, Hs, pres, dH_out, need_dH0=True):
+def rgcn_backward(part, layers, Hs, pres, dH_out, need_dH0=True, msg_bf16=False):
     """Reverse of :func:`rgcn_forward`. Returns per-layer grads (list) and dH0 (or None)."""
     grads: List[Optional[dict]] = [None] * len(layers)
     g = _d(dH_out)
     for l in range(len(layers) - 1, -1, -1):
         lay = layers[l]
         need = need_dH0 or l > 0
-        r = layer_backward(part, lay["V"], lay["a"], lay["W0"], lay["act"], Hs[l], pres[l], g, need)
+        r = layer_backward(part, lay["V"], lay["a"], lay["W0"], lay["act"], Hs[l], pres[l], g, need, msg_bf16)
         grads[l] = r
         g = r["dH"]
     return grads, g
 
 
-def layer_rows(part, rows, V, a, W0, act, H_f32):
+def layer_rows(part, rows, V, a, W0, act, H_f32, msg_bf16=False):
     """Layer output for the listed destination rows only, from the stored float32 input."""
     L = lib()
     rows = np.ascontiguousarray(rows, np.int32)
@@ -165,7 +167,8 @@ def layer_rows(part, rows, V, a, W0, act, H_f32):
     L.orc_rgcn_layer_rows(C.c_int64(len(rows)), _p(rows, _I32), _p(ptr, _I64), _p(segs, _I64),
                           _p(part["seg_ptr"], _I32), _p(part["seg_rel"], _I32),
                           _p(part["col_src"], _I32), C.c_int32(d_in), C.c_int32(d_out), C.c_int32(B),
-                          _p(V, _F64), _p(a, _F64), _p(W0, _F64), C.c_int32(act), _p(H_f32, _F32),
+                          _p(V, _F64), _p(a, _F64), _p(W0, _F64), C.c_int32(act),
+                          C.c_int32(1 if msg_bf16 else 0), _p(H_f32, _F32),
                           _p(pre, _F64), _p(out, _F64))
     return pre, out
 
@@ -208,11 +211,12 @@ def distmult_score_loss(part, H, M, pos_core_idx, neg_ent, neg_side):
     return dict(scores=scores, loss=float(loss[0]), dH=dH, dM=dM)
 
 
-def train_step(part, layers, H0, M, pos_core_idx, n_neg, mode, seed, step, need_dH0=True):
+def train_step(part, layers, H0, M, pos_core_idx, n_neg, mode, seed, step, need_dH0=True,
+               msg_bf16=False):
     """One whole step: encoder forward, negatives, score + loss, encoder backward."""
-    Hs, pres = rgcn_forward(part, layers, H0)
+    Hs, pres = rgcn_forward(part, layers, H0, msg_bf16)
     ne, ns = sample_negatives(part, pos_core_idx, n_neg, mode, seed, step)
     sl = distmult_score_loss(part, Hs[-1], M, pos_core_idx, ne, ns)
-    grads, dH0 = rgcn_backward(part, layers, Hs, pres, sl["dH"], need_dH0)
+    grads, dH0 = rgcn_backward(part, layers, Hs, pres, sl["dH"], need_dH0, msg_bf16)
     return dict(Hs=Hs, pres=pres, neg_ent=ne, neg_side=ns, scores=sl["scores"], loss=sl["loss"],
                 dH_out=sl["dH"], dM=sl["dM"], grads=grads, dH0=dH0)

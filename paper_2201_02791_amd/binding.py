@@ -19,7 +19,7 @@ _lib = None
 EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_partition_destroy", "kge_workspace_bytes", "kge_rgcn_forward",
             "kge_rgcn_backward", "kge_sample_negatives", "kge_distmult_score_loss",
-            "kge_last_error"]
+            "kge_profile_enable", "kge_profile_collect", "kge_last_error"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
 MSG_F32, MSG_BF16 = 0, 1
@@ -56,6 +56,10 @@ class _Layer(C.Structure):
 
 class _LayerGrad(C.Structure):
     _fields_ = [("dV", C.c_void_p), ("da", C.c_void_p), ("dW0", C.c_void_p)]
+
+
+class _ProfEntry(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("total_ms", C.c_double), ("calls", C.c_int64)]
 
 
 def load():
@@ -202,3 +206,15 @@ def distmult_score_loss(part: Partition, H, M, pos_core_idx, neg_ent, neg_side, 
                                           _ptr(pos_core_idx), C.c_int64(pos_core_idx.numel()),
                                           _ptr(neg_ent), _ptr(neg_side), C.c_int32(n_neg), _ptr(scores),
                                           _ptr(loss), _ptr(dH), _ptr(dM), _stream(stream)))
+
+
+def profile_enable(on: bool):
+    _check(load().kge_profile_enable(C.c_int32(1 if on else 0)))
+
+
+def profile_collect() -> dict:
+    """{kernel name: (total milliseconds, launches)} since profiling was enabled / last collected."""
+    arr = (_ProfEntry * 64)()
+    n = C.c_int32(0)
+    _check(load().kge_profile_collect(arr, C.c_int32(64), C.byref(n)))
+    return {arr[i].name.decode(): (float(arr[i].total_ms), int(arr[i].calls)) for i in range(n.value)}

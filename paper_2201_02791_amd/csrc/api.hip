@@ -1,8 +1,71 @@
 // Per-step entry points of the C ABI: argument checks, workspace carving and the launch
 // sequence of one training step (Algorithm 1: GNNmodel, loss, backward) on one stream.
+#include <string.h>
+
 #include <vector>
 
 #include "common.h"
+
+// ------------------------------------------------------------------ event profiling
+namespace {
+struct ProfRec { const char *name; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof_recs;
+std::vector<hipEvent_t> g_prof_pool;
+hipEvent_t prof_event()
+{
+    if (!g_prof_pool.empty()) { hipEvent_t e = g_prof_pool.back(); g_prof_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+}  // namespace
+
+KgeProfScope::KgeProfScope(const char *name, hipStream_t s) : slot(-1), st(s)
+{
+    if (!g_prof_on) return;
+    ProfRec r{name, prof_event(), prof_event()};
+    if (!r.a || !r.b) return;
+    (void)hipEventRecord(r.a, st);
+    slot = (int)g_prof_recs.size();
+    g_prof_recs.push_back(r);
+}
+KgeProfScope::~KgeProfScope()
+{
+    if (slot >= 0) (void)hipEventRecord(g_prof_recs[slot].b, st);
+}
+
+extern "C" int kge_profile_enable(int32_t on)
+{
+    g_prof_on = on != 0;
+    return KGE_OK;
+}
+
+extern "C" int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_entries)
+{
+    KGE_REQUIRE(out && n_entries && max_entries > 0, KGE_EINVAL, "NULL argument");
+    int n = 0;
+    for (const ProfRec &r : g_prof_recs) {
+        float ms = 0.f;
+        KGE_HIP(hipEventSynchronize(r.b));
+        KGE_HIP(hipEventElapsedTime(&ms, r.a, r.b));
+        int k = 0;
+        for (; k < n; ++k) if (strncmp(out[k].name, r.name, sizeof out[k].name) == 0) break;
+        if (k == n) {
+            if (n == max_entries) continue;
+            memset(&out[n], 0, sizeof out[n]);
+            strncpy(out[n].name, r.name, sizeof(out[n].name) - 1);
+            ++n;
+        }
+        out[k].total_ms += ms;
+        out[k].calls += 1;
+        g_prof_pool.push_back(r.a);
+        g_prof_pool.push_back(r.b);
+    }
+    g_prof_recs.clear();
+    *n_entries = n;
+    return KGE_OK;
+}
 
 namespace {
 

@@ -46,6 +46,15 @@ struct kge_partition {
     int32_t *rel_ptr;   // [2R+1] run range per relation
 };
 
+// Optional per-kernel timing with HIP events on the launch stream (kge_profile_enable).
+struct KgeProfScope {
+    KgeProfScope(const char *name, hipStream_t st);
+    ~KgeProfScope();
+    int slot;
+    hipStream_t st;
+};
+#define KGE_PROF(name, st) KgeProfScope prof_scope__(name, st)
+
 static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -352,6 +352,7 @@ int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, c
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the aggregation kernel", d);
     const int gbc = largest_pow2_dividing(B, 64 / lpr);
     const unsigned grid = (unsigned)cdiv(N, WPB);
+    KGE_PROF("gather_fwd", st);
     if (msg_bf16) {
         DISPATCH_LPR(lpr, (k_gather_fwd<true, L><<<grid, 64 * WPB, 0, st>>>(p->dm_ptr, p->dm_src, p->dm_rel, p->dm_invc, N, P, a, B, d, gbc, Self, act, out, out2)));
     } else {
@@ -367,6 +368,7 @@ int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t 
     int64_t n4 = n / 4;
     int64_t blocks = cdiv(n4, 256);
     if (blocks > 65536) blocks = 65536;
+    KGE_PROF("act_bwd", st);
     k_act_backward<<<(unsigned)blocks, 256, 0, st>>>(reinterpret_cast<const float4 *>(dHout),
                                                     reinterpret_cast<const float4 *>(Hout), act, n4,
                                                     reinterpret_cast<float4 *>(G));
@@ -381,6 +383,7 @@ static int launch_gather_t_nb(const kge_partition *p, const float *G, const floa
     constexpr int NG = 64 / LPR;
     const int64_t N = p->n_vert;
     const int per_group = (B + NG - 1) / NG;
+    KGE_PROF("gather_t", st);
 #define GT_CALL(NBV)                                                                                  \
     {                                                                                                 \
         const int n_chunks = (B + NG * NBV - 1) / (NG * NBV);                                         \
@@ -424,10 +427,13 @@ int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the coefficient-gradient kernel", d);
     const int gbc = largest_pow2_dividing(B, 64 / lpr);
     const unsigned grid = (unsigned)cdiv(S, WPB);
+    {
+    KGE_PROF("coeff_seg", st);
     if (msg_bf16) {
         DISPATCH_LPR(lpr, (k_coeff_seg<true, L><<<grid, 64 * WPB, 0, st>>>(p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, P, G, B, d, gbc, seg_scratch)));
     } else {
         DISPATCH_LPR(lpr, (k_coeff_seg<false, L><<<grid, 64 * WPB, 0, st>>>(p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, P, G, B, d, gbc, seg_scratch)));
+    }
     }
     KGE_LAUNCH_CHECK();
     KGE_REQUIRE(B <= 256, KGE_EINVAL, "more than 256 bases are not supported");
@@ -435,6 +441,7 @@ int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const
     int n_split = (int)(S / 65536) + 1;       // enough blocks for the most frequent relation
     if (n_split > 256) n_split = 256;
     dim3 rgrid((unsigned)R2, (unsigned)n_split, 1);
+    KGE_PROF("coeff_reduce", st);
     k_coeff_reduce<<<rgrid, 256, 0, st>>>(p->rel_ptr, seg_scratch, B, BP, da);
     KGE_LAUNCH_CHECK();
     return KGE_OK;

@@ -219,6 +219,7 @@ int launch_fill_zero(void *ptr, size_t bytes, hipStream_t st)
     if (bytes == 0) return KGE_OK;
     KGE_REQUIRE(((uintptr_t)ptr % 4) == 0 && bytes % 4 == 0, KGE_EINVAL,
                 "zero fill needs a 4-byte aligned buffer and size");
+    KGE_PROF("zero", st);
     if (((uintptr_t)ptr % 16) == 0 && bytes % 16 == 0) {
         int64_t n4 = (int64_t)(bytes / 16);
         int64_t blocks = cdiv(n4, 256);
@@ -242,6 +243,7 @@ int launch_project(const float *H, int64_t N, int32_t d_in, int32_t d_out, int32
     dim3 grid((unsigned)cdiv(N, BM), (unsigned)cdiv(nc, BN), 1);
     SrcRowMajorF32 sa{H, N, d_in};
     SrcWcat sb{V, W0, d_in, d_out, B};
+    KGE_PROF("project", st);
     if (msg_bf16) {
         EpiProject<true> ep{P, Self, N, d_out, B};
         k_gemm<SrcRowMajorF32, true, SrcWcat, false, EpiProject<true>><<<grid, GT, 0, st>>>(sa, sb, ep, d_in, d_in);
@@ -272,6 +274,7 @@ int launch_weight_grad(const float *H, int64_t N, int32_t d_in, int32_t d_out, i
     dim3 grid((unsigned)cdiv(d_in, BM), (unsigned)cdiv(nc, BN), (unsigned)splits);
     SrcRowMajorF32 sa{H, N, d_in};
     EpiWeightGrad ep{dV, dW0, d_in, d_out, B};
+    KGE_PROF("weight_grad", st);
     if (msg_bf16) {
         SrcXcat<true> sb{dP, G, N, d_out, B};
         k_gemm<SrcRowMajorF32, false, SrcXcat<true>, false, EpiWeightGrad><<<grid, GT, 0, st>>>(sa, sb, ep, N, kchunk);
@@ -292,6 +295,7 @@ int launch_input_grad(const void *dP, int msg_bf16, const float *G, int64_t N, i
     dim3 grid((unsigned)cdiv(N, BM), (unsigned)cdiv(d_in, BN), 1);
     SrcWcat sb{V, W0, d_in, d_out, B};
     EpiRowMajor ep{dH, N, d_in};
+    KGE_PROF("input_grad", st);
     if (msg_bf16) {
         SrcXcat<true> sa{dP, G, N, d_out, B};
         k_gemm<SrcXcat<true>, true, SrcWcat, true, EpiRowMajor><<<grid, GT, 0, st>>>(sa, sb, ep, nc, nc);

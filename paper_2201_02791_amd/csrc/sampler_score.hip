@@ -156,6 +156,7 @@ int launch_sample_negatives(const kge_partition *p, const int32_t *pos, int64_t 
     if (total == 0) return KGE_OK;
     KGE_REQUIRE(p->n_cand > 0, KGE_EINVAL, "the partition has no vertex to draw negatives from");
     KGE_REQUIRE(cdiv(total, 256) < 0x7fffffffLL, KGE_ERANGE, "too many negatives for one launch");
+    KGE_PROF("sample_neg", st);
     k_sample_negatives<<<(unsigned)cdiv(total, 256), 256, 0, st>>>(
         p->cand, (uint32_t)p->n_cand, pos, n_pos, n_neg, mode, (uint32_t)seed, (uint32_t)(seed >> 32),
         (uint32_t)step, (uint32_t)(step >> 32), neg_ent, neg_side);
@@ -176,6 +177,7 @@ int launch_distmult(const kge_partition *p, const float *H, const float *M, int3
     if (n_pos == 0) return KGE_OK;
     const float inv_T = (float)(1.0 / ((double)n_pos * (1.0 + (double)n_neg)));
     const unsigned grid = (unsigned)cdiv(n_pos, 4);
+    KGE_PROF("distmult", st);
 #define DM_CALL(NCHV)                                                                               \
     k_distmult<NCHV><<<grid, 256, 0, st>>>(H, M, d, p->core_h, p->core_r, p->core_t, pos, n_pos,    \
                                           neg_ent, neg_side, n_neg, inv_T, scores, loss, dH, dM)

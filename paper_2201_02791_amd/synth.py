@@ -93,11 +93,13 @@ def _powerlaw_weights(rng, n, exponent, cap):
 
 
 def _categorical(rng, weights, size):
-    cdf = np.cumsum(weights)
-    cdf /= cdf[-1]
-    x = rng.random(size)
-    idx = np.searchsorted(cdf, x, side="right")
-    return np.minimum(idx, len(weights) - 1).astype(np.int32)
+    # `size` i.i.d. draws from Categorical(weights), as per-category counts (one multinomial
+    # draw) expanded and shuffled: same distribution as drawing one by one, much faster.
+    p = np.asarray(weights, np.float64)
+    counts = rng.multinomial(size, p / p.sum())
+    out = np.repeat(np.arange(len(p), dtype=np.int32), counts)
+    rng.shuffle(out)
+    return out
 
 
 def make_triples(spec: WorkloadSpec):

@@ -40,11 +40,13 @@ def gpu_step(spec, head, rel, tail, params=None, pos=None, need_dH0=True):
     return part, ts, params, pos
 
 
-def oracle_step(orc, spec, head, rel, tail, params, pos, need_dH0=True):
+def oracle_step(orc, spec, head, rel, tail, params, pos, need_dH0=True, msg_bf16=None):
+    """msg_bf16 None: the oracle stores messages the way the workload says (bf16 or exact)."""
     part = orc.build_partition(head, rel, tail, spec.n_entities, spec.n_relations, spec.n_parts,
                                spec.part_id, spec.n_hops, spec.neg_domain)
     res = orc.train_step(part, layers_of(params, spec.acts), params["H0"], params["M"], pos,
-                         spec.n_neg, spec.neg_mode, SEED, STEP, need_dH0)
+                         spec.n_neg, spec.neg_mode, SEED, STEP, need_dH0,
+                         msg_bf16=(spec.msg_dtype == "bf16") if msg_bf16 is None else msg_bf16)
     return part, res
 
 

@@ -137,9 +137,12 @@ def test_hub_vertex_and_isolated_rows(kb, orc):
 @pytest.mark.parametrize("acts,n,m", [([0, 0], 600, 6000), ([1, 0], 6000, 90000)],
                          ids=["identity", "relu"])
 def test_bf16_messages_small(kb, orc, acts, n, m):
-    """Messages stored as bf16 (fp32 accumulation).  With ReLU a pre-activation within bf16
-    rounding of zero can flip its mask, so that case uses a graph large enough for single
-    flips not to dominate a max-norm; the identity case checks the arithmetic alone."""
+    """Messages stored as bf16 (fp32 accumulation), tolerance 2e-2.
+    The ReLU mask of layer 1 is a decision taken from floating-point values: a pre-activation
+    within bf16 rounding of zero flips it, and each flip changes layer-1 gradients by whole
+    terms.  So the full comparison is against the oracle that stores messages in bf16 as the
+    workload specifies (both sides then take the mask decision in the same precision), and the
+    outputs that do not depend on that decision are also held to 2e-2 against the exact oracle."""
     say("bf16 small", acts, n, m)
     spec = synth.scaled(synth.WORKLOADS[4], name="bf16-small", seed=3, n_entities=n, n_relations=20,
                         n_triples=m, d=64, n_bases=8, n_pos=256, n_neg=4, n_parts=2, part_id=0, acts=acts)
@@ -148,7 +151,17 @@ def test_bf16_messages_small(kb, orc, acts, n, m):
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
     assert_partition_equal(gp, op)
     errs = assert_step_close(ts, res, TOL_BF16, TOL_BF16)
-    say("bf16 errs", errs)
+    say("bf16 errs vs bf16-storage oracle", errs)
+    _, exact = oracle_step(orc, spec, head, rel, tail, params, pos, msg_bf16=False)
+    c = lambda t: t.detach().cpu().numpy()
+    assert rel_err(c(ts.H_out), exact["Hs"][-1]) <= TOL_BF16
+    assert rel_err(c(ts.scores), exact["scores"]) <= TOL_BF16
+    assert abs(float(c(ts.loss)[0]) - exact["loss"]) <= TOL_BF16 * exact["loss"]
+    last = len(acts) - 1
+    for k in ("dV", "da", "dW0"):
+        assert rel_err(c(ts.grads[last][k]), exact["grads"][last][k]) <= TOL_BF16, k
+    if acts == [0, 0]:       # no mask anywhere: everything also matches the exact oracle
+        assert_step_close(ts, exact, TOL_BF16, TOL_BF16)
 
 
 def test_zero_negatives_and_empty_batch(kb, orc):

@@ -153,3 +153,24 @@ def test_layer_rows_matches_whole_layer(orc):
     rpre, rout = orc.layer_rows(part, rows, lay["V"], lay["a"], lay["W0"], 1, H)
     np.testing.assert_allclose(rpre, pre[rows], rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(rout, out[rows], rtol=1e-12, atol=1e-13)
+
+
+def test_bf16_message_storage_rounds_like_a_library_conversion(orc):
+    """msg_bf16 rounds each projected message once to bfloat16 (nearest, ties to even).  With one
+    basis, V = I, a = 1, W_0 = 0 and a single in-edge, the layer output IS the rounded message,
+    which must equal PyTorch's float32 -> bfloat16 conversion, ties included."""
+    import torch
+    d = 256
+    head = np.array([0], np.int32); rel = np.array([0], np.int32); tail = np.array([1], np.int32)
+    part = orc.build_partition(head, rel, tail, 2, 1, 1, 0, 1, 0)
+    rng = np.random.default_rng(0)
+    h = (rng.standard_normal(d) * 10.0 ** rng.integers(-6, 6, d)).astype(np.float32)
+    # exact ties: low 16 bits = 0x8000 with even and odd kept parts
+    ties = np.array([0x3F808000, 0x3F818000, 0xBF808000, 0x40FF8000, 0x3F807FFF, 0x3F808001], np.uint32)
+    h[:len(ties)] = ties.view(np.float32)
+    H = np.zeros((2, d)); H[0] = h
+    _, out = orc.layer_forward(part, np.eye(d)[None], np.ones((2, 1)), np.zeros((d, d)), 0, H, msg_bf16=True)
+    want = torch.from_numpy(h).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(out[1], want)
+    _, exact = orc.layer_forward(part, np.eye(d)[None], np.ones((2, 1)), np.zeros((d, d)), 0, H)
+    np.testing.assert_array_equal(exact[1], h.astype(np.float64))
