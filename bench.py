@@ -57,8 +57,8 @@ def cpu_baseline(spec, cfg_index):
     step on the same generator recipe, scaled down so that it takes roughly 10-30 s."""
     from paper_2201_02791_amd import synth
     from oracle import oracle as orc
-    # oracle cost ~ 8 N B d^2 (projections, fwd+bwd, 2 layers) + 6 E B d  FMAs at roughly 1.5e9 FMA/s
-    budget = 25e9
+    # oracle cost ~ 8 N B d^2 (projections, fwd+bwd, 2 layers) + 6 E B d  FMAs at roughly 5e9 FMA/s
+    budget = 100e9
     per_vertex = 8.0 * spec.n_bases * spec.d * spec.d + 6.0 * 2.0 * (spec.n_triples / spec.n_entities) * spec.n_bases * spec.d
     n = int(min(spec.n_entities, max(200, budget / per_vertex)))
     scale = n / spec.n_entities
