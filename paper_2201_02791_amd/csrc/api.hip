@@ -71,7 +71,7 @@ namespace {
 
 struct WsLayout {
     std::vector<size_t> off_P, off_H;   // per layer: projected messages, layer output
-    size_t off_self = 0, off_G = 0, off_dP = 0, off_dHa = 0, off_dHb = 0, off_seg = 0, total = 0;
+    size_t off_self = 0, off_G = 0, off_dP = 0, off_dHa = 0, off_dHb = 0, off_seg = 0, off_part = 0, total = 0;
 };
 
 int check_layers(const kge_partition *p, const kge_layer *layers, int32_t n_layers, int32_t msg_dtype)
@@ -119,6 +119,11 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
     w->off_dHa = cur; cur = align_up(cur + N * max_din * 4, 256);
     w->off_dHb = cur; cur = align_up(cur + N * max_din * 4, 256);
     w->off_seg = cur; cur = align_up(cur + (size_t)p->n_seg * max_B * 4, 256);
+    // partial results of the units of heavy rows; the three users never overlap in time
+    size_t part = (size_t)p->hv_dm.n_units * max_dout;
+    if ((size_t)p->hv_sm.n_units * max_bd > part) part = (size_t)p->hv_sm.n_units * max_bd;
+    if ((size_t)p->hv_seg.n_units * max_B > part) part = (size_t)p->hv_seg.n_units * max_B;
+    w->off_part = cur; cur = align_up(cur + part * 4, 256);
     w->total = cur > 0 ? cur : 256;
 }
 
@@ -158,6 +163,7 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_layer *layers,
     const int bf = msg_dtype == KGE_MSG_BF16;
     const float *Hin = H0;
     float *Self = (float *)(ws + w.off_self);
+    float *part = (float *)(ws + w.off_part);
     for (int l = 0; l < n_layers; ++l) {
         const kge_layer &L = layers[l];
         void *P = ws + w.off_P[l];
@@ -165,7 +171,7 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_layer *layers,
         rc = launch_project(Hin, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, P, bf, Self, st);
         if (rc != KGE_OK) return rc;
         rc = launch_gather_forward(p, P, bf, L.a, L.n_bases, L.d_out, Self, L.act, Hl,
-                                   l == n_layers - 1 ? H_out : nullptr, st);
+                                   l == n_layers - 1 ? H_out : nullptr, part, st);
         if (rc != KGE_OK) return rc;
         Hin = Hl;
     }
@@ -193,6 +199,7 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_layer *layers
     void *dP = ws + w.off_dP;
     float *dHbuf[2] = {(float *)(ws + w.off_dHa), (float *)(ws + w.off_dHb)};
     float *seg = (float *)(ws + w.off_seg);
+    float *part = (float *)(ws + w.off_part);
     const float *gin = dH_out;
     for (int l = n_layers - 1; l >= 0; --l) {
         const kge_layer &L = layers[l];
@@ -205,9 +212,9 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_layer *layers
             if (rc != KGE_OK) return rc;
             Gl = G;
         }
-        rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, grads[l].da, st);
+        rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, part, grads[l].da, st);
         if (rc != KGE_OK) return rc;
-        rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf, st);
+        rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf, part, st);
         if (rc != KGE_OK) return rc;
         rc = launch_weight_grad(Hprev, p->n_vert, L.d_in, L.d_out, L.n_bases, dP, bf, Gl, grads[l].dV,
                                 grads[l].dW0, st);

@@ -28,6 +28,18 @@ void kge_set_error(const char *fmt, ...);
 
 #define KGE_LAUNCH_CHECK() KGE_HIP(hipGetLastError())
 
+// Rows (destinations, sources or runs) with at least KGE_HEAVY edges are cut into units of at most
+// KGE_HEAVY edges; each unit is handled by its own wavefront and writes a partial result that a
+// small finishing kernel sums in unit order (deterministic).  Power-law graphs put a large share
+// of all edges into such rows.
+#define KGE_HEAVY 256
+struct kge_heavy_index {
+    int32_t n_hv, n_units;
+    int32_t *hv_row;        // [n_hv]    row id of each heavy row, ascending
+    int32_t *hv_unit_ptr;   // [n_hv+1]  first unit of each heavy row
+    int32_t *unit_hv;       // [n_units] heavy-row index of each unit
+};
+
 struct kge_partition {
     int device;
     int64_t n_vert, n_edge, n_seg, n_core, n_cand, n_triples;
@@ -44,6 +56,7 @@ struct kge_partition {
     int32_t *sm_ptr, *sm_dst, *sm_rel;
     float *sm_invc;
     int32_t *rel_ptr;   // [2R+1] run range per relation
+    kge_heavy_index hv_dm, hv_sm, hv_seg;   // heavy destinations, sources, runs
 };
 
 // Optional per-kernel timing with HIP events on the launch stream (kge_profile_enable).
@@ -76,18 +89,22 @@ int launch_input_grad(const void *dP, int msg_bf16, const float *G, int64_t N, i
 
 // gather.hip -------------------------------------------------------------
 // out[i] = act( sum_{e into i} invc_e sum_b a[rel_e][b] P[src_e][b][:] + Self[i] ); out2 optional copy
+// `partial`: [hv_dm.n_units][d] floats of scratch
 int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, const float *a,
                           int32_t B, int32_t d, const float *Self, int act, float *out, float *out2,
-                          hipStream_t st);
+                          float *partial, hipStream_t st);
 // G = dHout * act'(Hout) (ReLU: Hout > 0)
 int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t n, float *G,
                         hipStream_t st);
 // dP[j][b][:] = sum_{e out of j} a[rel_e][b] invc_e G[dst_e][:]
+// `partial`: [hv_sm.n_units][B*d] floats of scratch
 int launch_gather_transpose(const kge_partition *p, const float *G, const float *a, int32_t B,
-                            int32_t d, void *dP, int msg_bf16, hipStream_t st);
+                            int32_t d, void *dP, int msg_bf16, float *partial, hipStream_t st);
 // da[r][b] = sum_{runs (r,i)} invc sum_{j in run} <P[j][b][:], G[i][:]> ; seg_scratch [S][B] floats
+// seg_scratch [S][B] floats; `partial`: [hv_seg.n_units][B] floats
 int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const float *G,
-                      int32_t B, int32_t d, float *seg_scratch, float *da, hipStream_t st);
+                      int32_t B, int32_t d, float *seg_scratch, float *partial, float *da,
+                      hipStream_t st);
 
 // sampler_score.hip --------------------------------------------------------
 int launch_sample_negatives(const kge_partition *p, const int32_t *pos, int64_t n_pos, int32_t n_neg,

@@ -1,13 +1,17 @@
 // Neighbour aggregation of the RGCN layer (Eq. 1 with W_r = sum_b a_rb V_b, Eq. 2) and
-// its backward counterparts.  All three kernels are bandwidth bound: they stream rows of
-// the projected messages P[j][b][:] (or of the upstream gradient G) with 128-bit loads, one
-// wavefront per destination / source / (relation, destination) run, and do a handful of
-// fp32 FMAs per loaded element.
+// its backward counterparts.  All kernels here are bandwidth bound: they stream rows of
+// the projected messages P[j][b][:] (or of the upstream gradient G) with 128-bit loads and do
+// a handful of fp32 FMAs per loaded element.
 //
-// Lane layout shared by the kernels.  A row of `d` elements is covered by LPR lanes, each
-// holding VEC consecutive elements (VEC = 4 for fp32, 8 for bf16: one 16-byte load).  The
-// 64 / LPR lane groups of a wavefront work on different (edge, basis) pairs in parallel:
-// GB of them across bases, GE = groups / GB across edges.
+// Work decomposition.  One wavefront per row (destination, source, or (relation, destination)
+// run).  Rows with >= KGE_HEAVY edges are cut into units of KGE_HEAVY edges, one wavefront
+// each, placed first in the grid; a unit writes a partial sum and a small finishing kernel adds
+// the partials of a row in unit order.  No atomics: results are bit-reproducible.
+//
+// Lane layout.  A row of `d` elements is covered by LPR lanes, each holding VEC consecutive
+// elements (VEC = 4 for fp32, 8 for bf16: one 16-byte load).  The 64 / LPR lane groups of a
+// wavefront work on different (edge, basis) pairs in parallel: GB of them across bases,
+// GE = groups / GB across edges.
 #include "common.h"
 
 namespace {
@@ -17,17 +21,31 @@ constexpr int WPB = 4;                 // wavefronts per block
 template <bool BF16> struct MsgRow;
 template <> struct MsgRow<false> {
     static constexpr int VEC = 4;
-    typedef float elem;
-    static __device__ __forceinline__ void load(const void *base, int64_t off, float (&v)[4])
+    static __device__ __forceinline__ uint4 load_raw(const void *base, int64_t off)
     {
-        float4 x = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(base) + off);
-        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+        return *reinterpret_cast<const uint4 *>(reinterpret_cast<const float *>(base) + off);
     }
-    static __device__ __forceinline__ void store(void *base, int64_t off, const float (&v)[4])
+    static __device__ __forceinline__ void unpack(const uint4 &x, float (&v)[4])
     {
-        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(base) + off) = make_float4(v[0], v[1], v[2], v[3]);
+        v[0] = __uint_as_float(x.x); v[1] = __uint_as_float(x.y);
+        v[2] = __uint_as_float(x.z); v[3] = __uint_as_float(x.w);
     }
 };
+template <> struct MsgRow<true> {
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ uint4 load_raw(const void *base, int64_t off)
+    {
+        return *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(base) + off);
+    }
+    static __device__ __forceinline__ void unpack(const uint4 &x, float (&v)[8])
+    {
+        v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xffff0000u);
+        v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
+        v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xffff0000u);
+        v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xffff0000u);
+    }
+};
+
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // round to nearest even
 {
     uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
@@ -35,44 +53,58 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // round t
     b = ((b & 0x7fffffffu) > 0x7f800000u) ? ((b >> 16) | 0x40u) : ((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
     return (a & 0xffffu) | (b << 16);
 }
-template <> struct MsgRow<true> {
-    static constexpr int VEC = 8;
-    typedef uint16_t elem;
-    static __device__ __forceinline__ void load(const void *base, int64_t off, float (&v)[8])
-    {
-        uint4 x = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(base) + off);
-        v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xffff0000u);
-        v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
-        v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xffff0000u);
-        v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xffff0000u);
-    }
-    static __device__ __forceinline__ void store(void *base, int64_t off, const float (&v)[8])
-    {
-        uint4 x;
-        x.x = pack_bf16x2(v[0], v[1]); x.y = pack_bf16x2(v[2], v[3]);
-        x.z = pack_bf16x2(v[4], v[5]); x.w = pack_bf16x2(v[6], v[7]);
-        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(base) + off) = x;
-    }
-};
 
 __device__ __forceinline__ float act_apply(int act, float x) { return act == KGE_ACT_RELU ? fmaxf(x, 0.f) : x; }
 
+// Which row and edge range a wavefront works on.  Wavefronts [0, n_units) take the units of heavy
+// rows; wavefront n_units + r takes light row r (and leaves at once if r is heavy).
+struct RowWork {
+    int64_t row;       // row id, or -1: nothing to do
+    int32_t beg, end;  // edge range
+    int32_t unit;      // >= 0: partial result goes to slot `unit`; -1: the row is finished here
+};
+__device__ __forceinline__ RowWork row_work(int64_t wid, const int32_t *__restrict__ ptr, int64_t n_rows,
+                                            int32_t n_units, const int32_t *__restrict__ hv_row,
+                                            const int32_t *__restrict__ hv_unit_ptr,
+                                            const int32_t *__restrict__ unit_hv)
+{
+    RowWork w;
+    if (wid < n_units) {
+        const int32_t h = unit_hv[wid];
+        w.row = hv_row[h];
+        w.unit = (int32_t)wid;
+        w.beg = ptr[w.row] + (int32_t)(wid - hv_unit_ptr[h]) * KGE_HEAVY;
+        w.end = min(w.beg + KGE_HEAVY, ptr[w.row + 1]);
+        return w;
+    }
+    w.row = wid - n_units;
+    w.unit = -1;
+    if (w.row >= n_rows) { w.row = -1; w.beg = w.end = 0; return w; }
+    w.beg = ptr[w.row];
+    w.end = ptr[w.row + 1];
+    if (w.end - w.beg >= KGE_HEAVY) w.row = -1;
+    return w;
+}
+
 // ------------------------------------------------------------------ forward
-// One wavefront per destination i (destination-major view):
 //   out[i][:] = act( sum_e invc_e sum_b a[rel_e][b] P[src_e][b][:] + Self[i][:] )
 template <bool BF16, int LPR>
 __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
     const int32_t *__restrict__ dm_ptr, const int32_t *__restrict__ dm_src,
     const int32_t *__restrict__ dm_rel, const float *__restrict__ dm_invc, int64_t N,
+    int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
+    const int32_t *__restrict__ unit_hv,
     const void *__restrict__ P, const float *__restrict__ a, int32_t B, int32_t d, int32_t gb_count,
-    const float *__restrict__ Self, int act, float *__restrict__ out, float *__restrict__ out2)
+    const float *__restrict__ Self, int act, float *__restrict__ out, float *__restrict__ out2,
+    float *__restrict__ partial)
 {
     constexpr int VEC = MsgRow<BF16>::VEC;
     constexpr int G = 64 / LPR;
-    constexpr int U = 4;
+    constexpr int U = 8;
     const int lane = threadIdx.x & 63;
-    const int64_t i = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
-    if (i >= N) return;                                 // whole wavefront leaves together
+    const int64_t wid = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+    const RowWork rw = row_work(wid, dm_ptr, N, n_units, hv_row, hv_unit_ptr, unit_hv);
+    if (rw.row < 0) return;                             // whole wavefront leaves together
     const int kl = lane % LPR, g = lane / LPR;
     const int GB = gb_count, GE = G / GB;
     const int gb = g % GB, ge = g / GB;
@@ -83,9 +115,8 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
 
-    const int32_t beg = dm_ptr[i], end = dm_ptr[i + 1];
-    for (int32_t e0 = beg; e0 < end; e0 += 64) {
-        const int cnt = min(64, end - e0);
+    for (int32_t e0 = rw.beg; e0 < rw.end; e0 += 64) {
+        const int cnt = min(64, rw.end - e0);
         int32_t my_src = 0, my_rel = 0;
         float my_w = 0.f;
         if (lane < cnt) { my_src = dm_src[e0 + lane]; my_rel = dm_rel[e0 + lane]; my_w = dm_invc[e0 + lane]; }
@@ -94,7 +125,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
         int er = 0, bi = 0;                             // current (edge round, basis slot)
         for (int q0 = 0; q0 < items; q0 += U) {
             float coef[U];
-            float val[U][VEC];
+            uint4 raw[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int el = er * GE + ge;
@@ -105,18 +136,20 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
                 const int32_t rel = __shfl(my_rel, els, 64);
                 const float w = __shfl(my_w, els, 64);
                 coef[u] = 0.f;
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) val[u][v] = 0.f;
+                raw[u] = make_uint4(0u, 0u, 0u, 0u);
                 if (ok) {
                     coef[u] = a[(int64_t)rel * B + b] * w;
-                    if (kact) MsgRow<BF16>::load(P, ((int64_t)src * B + b) * d + kl * VEC, val[u]);
+                    if (kact) raw[u] = MsgRow<BF16>::load_raw(P, ((int64_t)src * B + b) * d + kl * VEC);
                 }
                 if (++bi == nb) { bi = 0; ++er; }
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u) {
+                float val[VEC];
+                MsgRow<BF16>::unpack(raw[u], val);
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) acc[v] = fmaf(coef[u], val[u][v], acc[v]);
+                for (int v = 0; v < VEC; ++v) acc[v] = fmaf(coef[u], val[v], acc[v]);
+            }
         }
     }
     // fold the lane groups together (fixed order: deterministic)
@@ -126,7 +159,14 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
         for (int v = 0; v < VEC; ++v) acc[v] += __shfl_xor(acc[v], off, 64);
 
     if (g == 0 && kact) {
-        const int64_t o = i * d + kl * VEC;
+        if (rw.unit >= 0) {
+            float *q = partial + (int64_t)rw.unit * d + kl * VEC;
+#pragma unroll
+            for (int v4 = 0; v4 < VEC; v4 += 4)
+                *reinterpret_cast<float4 *>(q + v4) = make_float4(acc[v4], acc[v4 + 1], acc[v4 + 2], acc[v4 + 3]);
+            return;
+        }
+        const int64_t o = rw.row * d + kl * VEC;
 #pragma unroll
         for (int v4 = 0; v4 < VEC; v4 += 4) {
             float4 s = *reinterpret_cast<const float4 *>(Self + o + v4);
@@ -136,6 +176,30 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
             if (out2) *reinterpret_cast<float4 *>(out2 + o + v4) = r;
         }
     }
+}
+
+// Heavy destinations: out[i] = act(sum of the row's unit partials + Self[i]).  One thread per float4.
+__global__ void k_gather_fwd_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
+                                    const int32_t *__restrict__ hv_unit_ptr, const float *__restrict__ partial,
+                                    int32_t d, const float *__restrict__ Self, int act,
+                                    float *__restrict__ out, float *__restrict__ out2)
+{
+    const int d4 = d >> 2;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)n_hv * d4) return;
+    const int32_t h = (int32_t)(idx / d4);
+    const int k4 = (int)(idx - (int64_t)h * d4) * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int32_t u = hv_unit_ptr[h]; u < hv_unit_ptr[h + 1]; ++u) {
+        const float4 x = *reinterpret_cast<const float4 *>(partial + (int64_t)u * d + k4);
+        s.x += x.x; s.y += x.y; s.z += x.z; s.w += x.w;
+    }
+    const int64_t o = (int64_t)hv_row[h] * d + k4;
+    const float4 sf = *reinterpret_cast<const float4 *>(Self + o);
+    const float4 r = make_float4(act_apply(act, s.x + sf.x), act_apply(act, s.y + sf.y),
+                                 act_apply(act, s.z + sf.z), act_apply(act, s.w + sf.w));
+    *reinterpret_cast<float4 *>(out + o) = r;
+    if (out2) *reinterpret_cast<float4 *>(out2 + o) = r;
 }
 
 // ------------------------------------------------------------------ activation backward
@@ -156,23 +220,26 @@ __global__ void k_act_backward(const float4 *__restrict__ dH, const float4 *__re
 }
 
 // ------------------------------------------------------------------ transposed gather
-// One wavefront per (source j, chunk of bases) on the source-major view:
+// One wavefront per (source row work, chunk of bases) on the source-major view:
 //   dP[j][b][:] = sum_{e out of j} a[rel_e][b] invc_e G[dst_e][:]
 // A G row (fp32) is covered by LPR lanes x 4 floats; the 64/LPR lane groups take different
-// bases, NB bases each, so a chunk is (64/LPR)*NB bases.
-template <bool BF16, int LPR, int NB>
+// bases, NB bases each, so a chunk is (64/LPR)*NB bases.  UE edges are in flight at a time.
+template <bool BF16, int LPR, int NB, int UE>
 __global__ __launch_bounds__(64 * WPB) void k_gather_t(
     const int32_t *__restrict__ sm_ptr, const int32_t *__restrict__ sm_dst,
     const int32_t *__restrict__ sm_rel, const float *__restrict__ sm_invc, int64_t N,
+    int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
+    const int32_t *__restrict__ unit_hv,
     const float *__restrict__ G, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_chunks,
-    void *__restrict__ dP)
+    void *__restrict__ dP, float *__restrict__ partial)
 {
     constexpr int NG = 64 / LPR;
     const int lane = threadIdx.x & 63;
-    const int64_t wid = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
-    if (wid >= N * n_chunks) return;
-    const int64_t j = wid / n_chunks;
-    const int bc = (int)(wid - j * n_chunks);
+    const int64_t wid_all = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+    const int64_t wid = wid_all / n_chunks;
+    const int bc = (int)(wid_all - wid * n_chunks);
+    const RowWork rw = row_work(wid, sm_ptr, N, n_units, hv_row, hv_unit_ptr, unit_hv);
+    if (rw.row < 0) return;
     const int kl = lane % LPR, g = lane / LPR;
     const bool kact = kl * 4 < d;
     const int b0 = (bc * NG + g) * NB;
@@ -183,71 +250,111 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
 #pragma unroll
         for (int v = 0; v < 4; ++v) acc[n][v] = 0.f;
 
-    const int32_t beg = sm_ptr[j], end = sm_ptr[j + 1];
-    for (int32_t e0 = beg; e0 < end; e0 += 64) {
-        const int cnt = min(64, end - e0);
+    for (int32_t e0 = rw.beg; e0 < rw.end; e0 += 64) {
+        const int cnt = min(64, rw.end - e0);
         int32_t my_dst = 0, my_rel = 0;
         float my_w = 0.f;
         if (lane < cnt) { my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc[e0 + lane]; }
-        for (int el = 0; el < cnt; ++el) {
-            const int32_t dst = __builtin_amdgcn_readlane(my_dst, el);
-            const int32_t rel = __builtin_amdgcn_readlane(my_rel, el);
-            const float w = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), el));
-            float4 gv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (kact) gv = *reinterpret_cast<const float4 *>(G + (int64_t)dst * d + kl * 4);
-            const float *arow = a + (int64_t)rel * B;
+        for (int el0 = 0; el0 < cnt; el0 += UE) {
+            float4 gv[UE];
+            float w[UE];
+            const float *arow[UE];
 #pragma unroll
-            for (int n = 0; n < NB; ++n) {
-                const float c = (b0 + n < B) ? arow[b0 + n] * w : 0.f;
-                acc[n][0] = fmaf(c, gv.x, acc[n][0]); acc[n][1] = fmaf(c, gv.y, acc[n][1]);
-                acc[n][2] = fmaf(c, gv.z, acc[n][2]); acc[n][3] = fmaf(c, gv.w, acc[n][3]);
+            for (int u = 0; u < UE; ++u) {
+                const bool ok = el0 + u < cnt;
+                const int el = ok ? el0 + u : el0;
+                const int32_t dst = __builtin_amdgcn_readlane(my_dst, el);
+                const int32_t rel = __builtin_amdgcn_readlane(my_rel, el);
+                w[u] = ok ? __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), el)) : 0.f;
+                arow[u] = a + (int64_t)rel * B;
+                gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (kact) gv[u] = *reinterpret_cast<const float4 *>(G + (int64_t)dst * d + kl * 4);
             }
+#pragma unroll
+            for (int u = 0; u < UE; ++u)
+#pragma unroll
+                for (int n = 0; n < NB; ++n) {
+                    const float c = (b0 + n < B) ? arow[u][b0 + n] * w[u] : 0.f;
+                    acc[n][0] = fmaf(c, gv[u].x, acc[n][0]); acc[n][1] = fmaf(c, gv[u].y, acc[n][1]);
+                    acc[n][2] = fmaf(c, gv[u].z, acc[n][2]); acc[n][3] = fmaf(c, gv[u].w, acc[n][3]);
+                }
         }
     }
-    if (kact) {
+    if (!kact) return;
 #pragma unroll
-        for (int n = 0; n < NB; ++n) {
-            if (b0 + n < B) {
-                const int64_t o = ((int64_t)j * B + b0 + n) * d + kl * 4;
-                if (BF16) {
-                    uint2 x;
-                    x.x = pack_bf16x2(acc[n][0], acc[n][1]); x.y = pack_bf16x2(acc[n][2], acc[n][3]);
-                    *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(dP) + o) = x;
-                } else {
-                    *reinterpret_cast<float4 *>(reinterpret_cast<float *>(dP) + o) =
-                        make_float4(acc[n][0], acc[n][1], acc[n][2], acc[n][3]);
-                }
+    for (int n = 0; n < NB; ++n) {
+        if (b0 + n >= B) continue;
+        if (rw.unit >= 0) {
+            *reinterpret_cast<float4 *>(partial + ((int64_t)rw.unit * B + b0 + n) * d + kl * 4) =
+                make_float4(acc[n][0], acc[n][1], acc[n][2], acc[n][3]);
+        } else {
+            const int64_t o = ((int64_t)rw.row * B + b0 + n) * d + kl * 4;
+            if (BF16) {
+                uint2 x;
+                x.x = pack_bf16x2(acc[n][0], acc[n][1]); x.y = pack_bf16x2(acc[n][2], acc[n][3]);
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(dP) + o) = x;
+            } else {
+                *reinterpret_cast<float4 *>(reinterpret_cast<float *>(dP) + o) =
+                    make_float4(acc[n][0], acc[n][1], acc[n][2], acc[n][3]);
             }
         }
     }
 }
 
+// Heavy sources: dP[j] = sum of the row's unit partials.  One thread per float4 of a [B*d] row.
+template <bool BF16>
+__global__ void k_gather_t_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
+                                  const int32_t *__restrict__ hv_unit_ptr, const float *__restrict__ partial,
+                                  int32_t bd, void *__restrict__ dP)
+{
+    const int bd4 = bd >> 2;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)n_hv * bd4) return;
+    const int32_t h = (int32_t)(idx / bd4);
+    const int k4 = (int)(idx - (int64_t)h * bd4) * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int32_t u = hv_unit_ptr[h]; u < hv_unit_ptr[h + 1]; ++u) {
+        const float4 x = *reinterpret_cast<const float4 *>(partial + (int64_t)u * bd + k4);
+        s.x += x.x; s.y += x.y; s.z += x.z; s.w += x.w;
+    }
+    const int64_t o = (int64_t)hv_row[h] * bd + k4;
+    if (BF16) {
+        uint2 x;
+        x.x = pack_bf16x2(s.x, s.y); x.y = pack_bf16x2(s.z, s.w);
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(dP) + o) = x;
+    } else {
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(dP) + o) = s;
+    }
+}
+
 // ------------------------------------------------------------------ coefficient gradient
-// One wavefront per (relation, destination) run s = (r, i):
+// One wavefront per (relation, destination) run s = (r, i) (or per unit of a long run):
 //   seg_out[s][b] = invc_s * sum_{j in run} < P[j][b][:], G[i][:] >
-// and da[r][b] is the sum of seg_out over the runs of relation r (second kernel).
-template <bool BF16, int LPR>
+// and da[r][b] is the sum of seg_out over the runs of relation r (k_coeff_reduce).
+// UB basis slots x UE edge rounds are in flight at a time.
+template <bool BF16, int LPR, int UB, int UE>
 __global__ __launch_bounds__(64 * WPB) void k_coeff_seg(
     const int32_t *__restrict__ seg_ptr, const int32_t *__restrict__ seg_dst,
     const float *__restrict__ inv_c, const int32_t *__restrict__ col_src, int64_t S,
+    int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
+    const int32_t *__restrict__ unit_hv,
     const void *__restrict__ P, const float *__restrict__ G, int32_t B, int32_t d, int32_t gb_count,
-    float *__restrict__ seg_out)
+    float *__restrict__ seg_out, float *__restrict__ partial)
 {
     constexpr int VEC = MsgRow<BF16>::VEC;
     constexpr int NG = 64 / LPR;
-    constexpr int U = 4;
     const int lane = threadIdx.x & 63;
-    const int64_t s = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
-    if (s >= S) return;
+    const int64_t wid = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+    const RowWork rw = row_work(wid, seg_ptr, S, n_units, hv_row, hv_unit_ptr, unit_hv);
+    if (rw.row < 0) return;
     const int kl = lane % LPR, g = lane / LPR;
     const int GB = gb_count, GE = NG / GB;
     const int gb = g % GB, ge = g / GB;
     const bool kact = kl * VEC < d;
     const int nb = (B + GB - 1) / GB;
 
-    const int32_t beg = seg_ptr[s], end = seg_ptr[s + 1];
-    const int32_t i = seg_dst[s];
-    const float invc = inv_c[s];
+    const int32_t i = seg_dst[rw.row];
+    const float scale = rw.unit >= 0 ? 1.f : inv_c[rw.row];
     float gv[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) gv[v] = 0.f;
@@ -258,46 +365,69 @@ __global__ __launch_bounds__(64 * WPB) void k_coeff_seg(
             gv[v4] = x.x; gv[v4 + 1] = x.y; gv[v4 + 2] = x.z; gv[v4 + 3] = x.w;
         }
     }
-    const int len = end - beg;
+    const int len = rw.end - rw.beg;
     const int erounds = (len + GE - 1) / GE;
-    for (int bi0 = 0; bi0 < nb; bi0 += U) {
-        float part[U];
+    float *dst_out = rw.unit >= 0 ? partial + (int64_t)rw.unit * B : seg_out + rw.row * B;
+    for (int bi0 = 0; bi0 < nb; bi0 += UB) {
+        float part[UB];
 #pragma unroll
-        for (int u = 0; u < U; ++u) part[u] = 0.f;
-        for (int er = 0; er < erounds; ++er) {
-            const int el = er * GE + ge;
-            const bool eok = el < len;
-            const int32_t src = eok ? col_src[beg + el] : 0;
-            float val[U][VEC];
+        for (int u = 0; u < UB; ++u) part[u] = 0.f;
+        for (int er0 = 0; er0 < erounds; er0 += UE) {
+            uint4 raw[UE][UB];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int b = (bi0 + u) * GB + gb;
+            for (int x = 0; x < UE; ++x) {
+                const int el = (er0 + x) * GE + ge;
+                const bool eok = el < len;
+                const int32_t src = eok ? col_src[rw.beg + el] : 0;
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) val[u][v] = 0.f;
-                if (eok && kact && (bi0 + u) < nb && b < B)
-                    MsgRow<BF16>::load(P, ((int64_t)src * B + b) * d + kl * VEC, val[u]);
+                for (int u = 0; u < UB; ++u) {
+                    const int b = (bi0 + u) * GB + gb;
+                    raw[x][u] = make_uint4(0u, 0u, 0u, 0u);
+                    if (eok && kact && (bi0 + u) < nb && b < B)
+                        raw[x][u] = MsgRow<BF16>::load_raw(P, ((int64_t)src * B + b) * d + kl * VEC);
+                }
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int x = 0; x < UE; ++x)
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) part[u] = fmaf(val[u][v], gv[v], part[u]);
+                for (int u = 0; u < UB; ++u) {
+                    float val[VEC];
+                    MsgRow<BF16>::unpack(raw[x][u], val);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) part[u] = fmaf(val[v], gv[v], part[u]);
+                }
         }
         // sum over the LPR lanes of a row and over the GE edge groups; skip the offsets that
         // would mix different bases (LPR .. LPR*GB/2)
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
+        for (int u = 0; u < UB; ++u) {
 #pragma unroll
             for (int off = 1; off < LPR; off <<= 1) part[u] += __shfl_xor(part[u], off, 64);
             for (int off = LPR * GB; off < 64; off <<= 1) part[u] += __shfl_xor(part[u], off, 64);
         }
         if (kl == 0 && ge == 0) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
+            for (int u = 0; u < UB; ++u) {
                 const int b = (bi0 + u) * GB + gb;
-                if ((bi0 + u) < nb && b < B) seg_out[s * B + b] = invc * part[u];
+                if ((bi0 + u) < nb && b < B) dst_out[b] = scale * part[u];
             }
         }
     }
+}
+
+// Long runs: seg_out[s][b] = invc_s * sum of the run's unit partials.
+__global__ void k_coeff_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
+                               const int32_t *__restrict__ hv_unit_ptr, const float *__restrict__ partial,
+                               const float *__restrict__ inv_c, int32_t B, float *__restrict__ seg_out)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)n_hv * B) return;
+    const int32_t h = (int32_t)(idx / B);
+    const int b = (int)(idx - (int64_t)h * B);
+    float s = 0.f;
+    for (int32_t u = hv_unit_ptr[h]; u < hv_unit_ptr[h + 1]; ++u) s += partial[(int64_t)u * B + b];
+    const int64_t row = hv_row[h];
+    seg_out[row * B + b] = inv_c[row] * s;
 }
 
 // da[r][b] += sum of seg_out[s][b] over a strided share of relation r's runs.
@@ -312,7 +442,7 @@ __global__ __launch_bounds__(256) void k_coeff_reduce(const int32_t *__restrict_
     const int b = threadIdx.x % BP, slot = threadIdx.x / BP;
     const int64_t beg = rel_ptr[r], end = rel_ptr[r + 1];
     float acc = 0.f;
-    if (b < B && slot < slots)
+    if (b < B)
         for (int64_t s = beg + (int64_t)blockIdx.y * slots + slot; s < end; s += (int64_t)gridDim.y * slots)
             acc += seg_out[s * B + b];
     red[threadIdx.x] = acc;
@@ -343,7 +473,7 @@ int largest_pow2_dividing(int x, int cap) { int p = 1; while (p * 2 <= cap && x 
 
 int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, const float *a,
                           int32_t B, int32_t d, const float *Self, int act, float *out, float *out2,
-                          hipStream_t st)
+                          float *partial, hipStream_t st)
 {
     const int64_t N = p->n_vert;
     if (N == 0) return KGE_OK;
@@ -351,14 +481,24 @@ int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, c
     const int lpr = pow2_at_least((d + vec - 1) / vec);
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the aggregation kernel", d);
     const int gbc = largest_pow2_dividing(B, 64 / lpr);
-    const unsigned grid = (unsigned)cdiv(N, WPB);
-    KGE_PROF("gather_fwd", st);
-    if (msg_bf16) {
-        DISPATCH_LPR(lpr, (k_gather_fwd<true, L><<<grid, 64 * WPB, 0, st>>>(p->dm_ptr, p->dm_src, p->dm_rel, p->dm_invc, N, P, a, B, d, gbc, Self, act, out, out2)));
-    } else {
-        DISPATCH_LPR(lpr, (k_gather_fwd<false, L><<<grid, 64 * WPB, 0, st>>>(p->dm_ptr, p->dm_src, p->dm_rel, p->dm_invc, N, P, a, B, d, gbc, Self, act, out, out2)));
+    const kge_heavy_index &hx = p->hv_dm;
+    const unsigned grid = (unsigned)cdiv(N + hx.n_units, WPB);
+    {
+        KGE_PROF("gather_fwd", st);
+#define GF_ARGS p->dm_ptr, p->dm_src, p->dm_rel, p->dm_invc, N, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, \
+                P, a, B, d, gbc, Self, act, out, out2, partial
+        if (msg_bf16) { DISPATCH_LPR(lpr, (k_gather_fwd<true, L><<<grid, 64 * WPB, 0, st>>>(GF_ARGS))); }
+        else { DISPATCH_LPR(lpr, (k_gather_fwd<false, L><<<grid, 64 * WPB, 0, st>>>(GF_ARGS))); }
+#undef GF_ARGS
     }
     KGE_LAUNCH_CHECK();
+    if (hx.n_hv > 0) {
+        KGE_PROF("gather_fwd_fin", st);
+        const int64_t n = (int64_t)hx.n_hv * (d / 4);
+        k_gather_fwd_finish<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, d,
+                                                                   Self, act, out, out2);
+        KGE_LAUNCH_CHECK();
+    }
     return KGE_OK;
 }
 
@@ -378,65 +518,98 @@ int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t 
 
 template <bool BF16, int LPR>
 static int launch_gather_t_nb(const kge_partition *p, const float *G, const float *a, int32_t B, int32_t d,
-                              void *dP, hipStream_t st)
+                              void *dP, float *partial, hipStream_t st)
 {
     constexpr int NG = 64 / LPR;
     const int64_t N = p->n_vert;
+    const kge_heavy_index &hx = p->hv_sm;
     const int per_group = (B + NG - 1) / NG;
     KGE_PROF("gather_t", st);
-#define GT_CALL(NBV)                                                                                  \
+#define GT_CALL(NBV, UEV)                                                                             \
     {                                                                                                 \
         const int n_chunks = (B + NG * NBV - 1) / (NG * NBV);                                         \
-        const unsigned grid = (unsigned)cdiv(N * n_chunks, WPB);                                      \
-        k_gather_t<BF16, LPR, NBV><<<grid, 64 * WPB, 0, st>>>(p->sm_ptr, p->sm_dst, p->sm_rel,        \
-                                                             p->sm_invc, N, G, a, B, d, n_chunks, dP); \
+        const int64_t waves = (N + hx.n_units) * n_chunks;                                            \
+        KGE_REQUIRE(cdiv(waves, WPB) < 0x7fffffffLL, KGE_ERANGE, "grid too large");                   \
+        k_gather_t<BF16, LPR, NBV, UEV><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(              \
+            p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, N, hx.n_units, hx.hv_row, hx.hv_unit_ptr,    \
+            hx.unit_hv, G, a, B, d, n_chunks, dP, partial);                                           \
     }
-    if (per_group >= 16) GT_CALL(16)
-    else if (per_group >= 8) GT_CALL(8)
-    else if (per_group >= 4) GT_CALL(4)
-    else if (per_group >= 2) GT_CALL(2)
-    else GT_CALL(1)
+    if (per_group >= 16) GT_CALL(16, 1)
+    else if (per_group >= 8) GT_CALL(8, 2)
+    else if (per_group >= 4) GT_CALL(4, 4)
+    else if (per_group >= 2) GT_CALL(2, 4)
+    else GT_CALL(1, 8)
 #undef GT_CALL
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
 
 int launch_gather_transpose(const kge_partition *p, const float *G, const float *a, int32_t B, int32_t d,
-                            void *dP, int msg_bf16, hipStream_t st)
+                            void *dP, int msg_bf16, float *partial, hipStream_t st)
 {
     if (p->n_vert == 0) return KGE_OK;
     const int lpr = pow2_at_least((d + 3) / 4);
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the transposed aggregation kernel", d);
-    KGE_REQUIRE(p->n_vert * (int64_t)B < 0x7fffffffLL * WPB, KGE_ERANGE, "grid too large");
     int rc = KGE_OK;
-    if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(p, G, a, B, d, dP, st))); }
-    else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, L>(p, G, a, B, d, dP, st))); }
-    return rc;
+    if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(p, G, a, B, d, dP, partial, st))); }
+    else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, L>(p, G, a, B, d, dP, partial, st))); }
+    if (rc != KGE_OK) return rc;
+    const kge_heavy_index &hx = p->hv_sm;
+    if (hx.n_hv > 0) {
+        KGE_PROF("gather_t_fin", st);
+        const int bd = B * d;
+        const int64_t n = (int64_t)hx.n_hv * (bd / 4);
+        if (msg_bf16) k_gather_t_finish<true><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, bd, dP);
+        else k_gather_t_finish<false><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, bd, dP);
+        KGE_LAUNCH_CHECK();
+    }
+    return KGE_OK;
+}
+
+template <bool BF16, int LPR>
+static int launch_coeff_seg(const kge_partition *p, const void *P, const float *G, int32_t B, int32_t d,
+                            int gbc, float *seg_scratch, float *partial, hipStream_t st)
+{
+    const int64_t S = p->n_seg;
+    const kge_heavy_index &hx = p->hv_seg;
+    const unsigned grid = (unsigned)cdiv(S + hx.n_units, WPB);
+    const int nb = (B + gbc - 1) / gbc;
+#define CS_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, \
+                P, G, B, d, gbc, seg_scratch, partial
+    if (nb >= 4) k_coeff_seg<BF16, LPR, 4, 2><<<grid, 64 * WPB, 0, st>>>(CS_ARGS);
+    else if (nb >= 2) k_coeff_seg<BF16, LPR, 2, 4><<<grid, 64 * WPB, 0, st>>>(CS_ARGS);
+    else k_coeff_seg<BF16, LPR, 1, 8><<<grid, 64 * WPB, 0, st>>>(CS_ARGS);
+#undef CS_ARGS
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
 }
 
 int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const float *G, int32_t B,
-                      int32_t d, float *seg_scratch, float *da, hipStream_t st)
+                      int32_t d, float *seg_scratch, float *partial, float *da, hipStream_t st)
 {
     const int64_t S = p->n_seg;
     const int32_t R2 = 2 * p->n_relations;
     int rc = launch_fill_zero(da, sizeof(float) * (size_t)R2 * B, st);
     if (rc != KGE_OK) return rc;
     if (S == 0) return KGE_OK;
+    KGE_REQUIRE(B <= 256, KGE_EINVAL, "more than 256 bases are not supported");
     const int vec = msg_bf16 ? 8 : 4;
     const int lpr = pow2_at_least((d + vec - 1) / vec);
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the coefficient-gradient kernel", d);
     const int gbc = largest_pow2_dividing(B, 64 / lpr);
-    const unsigned grid = (unsigned)cdiv(S, WPB);
     {
-    KGE_PROF("coeff_seg", st);
-    if (msg_bf16) {
-        DISPATCH_LPR(lpr, (k_coeff_seg<true, L><<<grid, 64 * WPB, 0, st>>>(p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, P, G, B, d, gbc, seg_scratch)));
-    } else {
-        DISPATCH_LPR(lpr, (k_coeff_seg<false, L><<<grid, 64 * WPB, 0, st>>>(p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, P, G, B, d, gbc, seg_scratch)));
+        KGE_PROF("coeff_seg", st);
+        if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_coeff_seg<true, L>(p, P, G, B, d, gbc, seg_scratch, partial, st))); }
+        else { DISPATCH_LPR(lpr, (rc = launch_coeff_seg<false, L>(p, P, G, B, d, gbc, seg_scratch, partial, st))); }
     }
+    if (rc != KGE_OK) return rc;
+    const kge_heavy_index &hx = p->hv_seg;
+    if (hx.n_hv > 0) {
+        KGE_PROF("coeff_fin", st);
+        const int64_t n = (int64_t)hx.n_hv * B;
+        k_coeff_finish<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, p->inv_c, B, seg_scratch);
+        KGE_LAUNCH_CHECK();
     }
-    KGE_LAUNCH_CHECK();
-    KGE_REQUIRE(B <= 256, KGE_EINVAL, "more than 256 bases are not supported");
     const int BP = pow2_at_least(B);
     int n_split = (int)(S / 65536) + 1;       // enough blocks for the most frequent relation
     if (n_split > 256) n_split = 256;

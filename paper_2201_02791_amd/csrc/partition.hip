@@ -421,6 +421,29 @@ __global__ void k_max_degree(const int32_t *ptr, int64_t nv, int32_t *out)
     atomicMax(out, ptr[v + 1] - ptr[v]);
 }
 
+// Heavy-row index: rows with at least KGE_HEAVY edges, cut into units of KGE_HEAVY edges.
+__global__ void k_heavy_flag(const int32_t *ptr, int64_t n_rows, uint32_t *flag, uint32_t *units)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_rows) return;
+    int32_t deg = ptr[i + 1] - ptr[i];
+    uint32_t f = deg >= KGE_HEAVY ? 1u : 0u;
+    flag[i] = f;
+    units[i] = f ? (uint32_t)((deg + KGE_HEAVY - 1) / KGE_HEAVY) : 0u;
+}
+
+__global__ void k_heavy_emit(int64_t n_rows, const uint32_t *flag, const uint32_t *hpos,
+                             const uint32_t *units, const uint32_t *upos, int32_t *hv_row,
+                             int32_t *hv_unit_ptr, int32_t *unit_hv)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_rows || !flag[i]) return;
+    uint32_t h = hpos[i], u0 = upos[i], n = units[i];
+    hv_row[h] = (int32_t)i;
+    hv_unit_ptr[h] = (int32_t)u0;
+    for (uint32_t k = 0; k < n; ++k) unit_hv[u0 + k] = (int32_t)h;
+}
+
 __global__ void k_iota(int32_t *a, int64_t n)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -459,6 +482,31 @@ template <typename T> int palloc(T **out, size_t count)
 
 #define TRY(x) do { int rc__ = (x); if (rc__ != KGE_OK) return rc__; } while (0)
 inline unsigned grid_for(int64_t n) { return (unsigned)(n > 0 ? cdiv(n, TB) : 1); }
+
+int build_heavy_index(const int32_t *ptr, int64_t n_rows, kge_heavy_index *hx, hipStream_t st)
+{
+    TempBufs tmp;
+    uint32_t *flag, *units, *hpos, *upos;
+    TRY(tmp.alloc(&flag, n_rows)); TRY(tmp.alloc(&units, n_rows));
+    TRY(tmp.alloc(&hpos, (size_t)n_rows + 1)); TRY(tmp.alloc(&upos, (size_t)n_rows + 1));
+    if (n_rows > 0) { k_heavy_flag<<<grid_for(n_rows), TB, 0, st>>>(ptr, n_rows, flag, units); KGE_LAUNCH_CHECK(); }
+    TRY(exclusive_scan(flag, hpos, n_rows, st));
+    TRY(exclusive_scan(units, upos, n_rows, st));
+    uint32_t nh = 0, nu = 0;
+    KGE_HIP(hipMemcpy(&nh, hpos + n_rows, sizeof(uint32_t), hipMemcpyDeviceToHost));
+    KGE_HIP(hipMemcpy(&nu, upos + n_rows, sizeof(uint32_t), hipMemcpyDeviceToHost));
+    hx->n_hv = (int32_t)nh; hx->n_units = (int32_t)nu;
+    TRY(palloc(&hx->hv_row, nh)); TRY(palloc(&hx->hv_unit_ptr, (size_t)nh + 1)); TRY(palloc(&hx->unit_hv, nu));
+    if (n_rows > 0) {
+        k_heavy_emit<<<grid_for(n_rows), TB, 0, st>>>(n_rows, flag, hpos, units, upos, hx->hv_row,
+                                                     hx->hv_unit_ptr, hx->unit_hv);
+        KGE_LAUNCH_CHECK();
+    }
+    int32_t nu_i = (int32_t)nu;
+    KGE_HIP(hipMemcpyAsync(hx->hv_unit_ptr + nh, &nu_i, sizeof(int32_t), hipMemcpyHostToDevice, st));
+    KGE_HIP(hipStreamSynchronize(st));
+    return KGE_OK;
+}
 
 int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tail, int64_t M,
                int32_t n_ent, int32_t n_rel, int32_t n_parts, int32_t part_id, int32_t n_hops,
@@ -617,6 +665,9 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
         KGE_LAUNCH_CHECK();
         if (N > 0) { k_max_degree<<<grid_for(N), TB, 0, st>>>(ptr, N, maxdeg + view); KGE_LAUNCH_CHECK(); }
     }
+    TRY(build_heavy_index(p->dm_ptr, N, &p->hv_dm, st));
+    TRY(build_heavy_index(p->sm_ptr, N, &p->hv_sm, st));
+    TRY(build_heavy_index(p->seg_ptr, S, &p->hv_seg, st));
     int32_t h_maxdeg[2] = {0, 0};
     KGE_HIP(hipMemcpy(h_maxdeg, maxdeg, sizeof(h_maxdeg), hipMemcpyDeviceToHost));
     p->max_in_degree = h_maxdeg[0];
@@ -645,7 +696,10 @@ extern "C" void kge_partition_destroy(kge_partition *p)
     if (!p) return;
     void *arrs[] = {p->vert_gid, p->core_eid, p->core_h, p->core_r, p->core_t, p->seg_ptr, p->seg_rel,
                     p->seg_dst, p->inv_c, p->col_src, p->edge_id, p->cand, p->dm_ptr, p->dm_src,
-                    p->dm_rel, p->dm_invc, p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, p->rel_ptr};
+                    p->dm_rel, p->dm_invc, p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, p->rel_ptr,
+                    p->hv_dm.hv_row, p->hv_dm.hv_unit_ptr, p->hv_dm.unit_hv,
+                    p->hv_sm.hv_row, p->hv_sm.hv_unit_ptr, p->hv_sm.unit_hv,
+                    p->hv_seg.hv_row, p->hv_seg.hv_unit_ptr, p->hv_seg.unit_hv};
     for (void *q : arrs) if (q) (void)hipFree(q);
     delete p;
 }
