@@ -147,7 +147,8 @@ def main():
         if bound == "hbm":
             ach, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
         else:
-            ach, peak, unit = work / (avg_ms * 1e-3) / 1e12, PEAK_F32_MFMA_TFLOPS, "TFLOP/s"
+            peak = PEAK_BF16_MFMA_TFLOPS if ep == 2 else PEAK_F32_MFMA_TFLOPS
+            ach, unit = work / (avg_ms * 1e-3) / 1e12, "TFLOP/s"
         kernels[name] = {"ms_per_step": tot_ms / args.steps, "launches_per_step": calls / args.steps,
                          "avg_ms": avg_ms, "bound": bound, "achieved": ach, "peak": peak, "unit": unit,
                          "frac": ach / peak if peak else None}

@@ -220,8 +220,10 @@ void orc_partition_copy(const orc_partition *p, int32_t which, void *dst)
 static double act_fwd(int act, double x) { return act == 1 ? (x > 0.0 ? x : 0.0) : x; }
 static double act_grad(int act, double pre) { return act == 1 ? (pre > 0.0 ? 1.0 : 0.0) : 1.0; }
 
-/* Storage rounding of a projected message when the workload keeps messages in bfloat16:
- * to float, then to the nearest bfloat16 (ties to even).  Everything else stays double. */
+/* Rounding to bfloat16 for workloads that run the projections as a bf16 contraction and keep
+ * the projected messages in bf16: the operands (layer input, V_b, W_0) are rounded before they
+ * are multiplied, products are summed exactly (double), and a message is rounded once more when
+ * it is stored.  To float first, then to the nearest bfloat16, ties to even. */
 static double round_msg(double x, int32_t msg_bf16)
 {
     if (!msg_bf16) return x;
@@ -245,9 +247,9 @@ static void project_all(int64_t N, int32_t d_in, int32_t d_out, int32_t B,
             double *out = P + ((size_t)j * B + b) * d_out;
             const double *Vb = V + (size_t)b * d_in * d_out;
             for (int32_t k = 0; k < d_in; ++k) {
-                double h = H[(size_t)j * d_in + k];
+                double h = round_msg(H[(size_t)j * d_in + k], msg_bf16);
                 const double *vrow = Vb + (size_t)k * d_out;
-                for (int32_t o = 0; o < d_out; ++o) out[o] += h * vrow[o];
+                for (int32_t o = 0; o < d_out; ++o) out[o] += h * round_msg(vrow[o], msg_bf16);
             }
             if (msg_bf16) for (int32_t o = 0; o < d_out; ++o) out[o] = round_msg(out[o], 1);
         }
@@ -257,8 +259,8 @@ static void project_all(int64_t N, int32_t d_in, int32_t d_out, int32_t B,
  * One layer forward over the whole partition:
  *   pre_i = sum_r sum_{j in N_i^r} (1/c_{i,r}) h_j W_r + h_i W_0,   W_r = sum_b a_rb V_b
  *   h'_i  = act(pre_i)                        act: 0 identity, 1 ReLU
- * P_scratch is [N][B][d_out] doubles.  msg_bf16 != 0 models a workload that stores the
- * projected messages in bfloat16 (they are rounded once, when written); 0 keeps them exact.
+ * P_scratch is [N][B][d_out] doubles.  msg_bf16 != 0 models a workload whose projections are
+ * a bf16 contraction with bf16 message storage (see round_msg); 0 keeps everything exact.
  */
 void orc_rgcn_layer_forward(int64_t N, int64_t S, const int32_t *seg_ptr, const int32_t *seg_rel,
                             const int32_t *seg_dst, const int32_t *col_src,
@@ -273,9 +275,9 @@ void orc_rgcn_layer_forward(int64_t N, int64_t S, const int32_t *seg_ptr, const 
         double *o = pre + (size_t)i * d_out;
         for (int32_t c = 0; c < d_out; ++c) o[c] = 0.0;
         for (int32_t k = 0; k < d_in; ++k) {
-            double h = H[(size_t)i * d_in + k];
+            double h = round_msg(H[(size_t)i * d_in + k], msg_bf16);
             const double *w = W0 + (size_t)k * d_out;
-            for (int32_t c = 0; c < d_out; ++c) o[c] += h * w[c];
+            for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(w[c], msg_bf16);
         }
     }
     /* neighbours, one (relation, destination) run at a time */
@@ -315,8 +317,8 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
         double *o = pre_rows + (size_t)q * d_out;
         for (int32_t c = 0; c < d_out; ++c) o[c] = 0.0;
         for (int32_t k = 0; k < d_in; ++k) {
-            double h = (double)H[(size_t)i * d_in + k];
-            for (int32_t c = 0; c < d_out; ++c) o[c] += h * W0[(size_t)k * d_out + c];
+            double h = round_msg((double)H[(size_t)i * d_in + k], msg_bf16);
+            for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(W0[(size_t)k * d_out + c], msg_bf16);
         }
         for (int64_t t = row_seg_ptr[q]; t < row_seg_ptr[q + 1]; ++t) {
             int64_t s = row_seg[t];
@@ -328,8 +330,9 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
                     const double *Vb = V + (size_t)b * d_in * d_out;
                     for (int32_t c = 0; c < d_out; ++c) pj[c] = 0.0;
                     for (int32_t k = 0; k < d_in; ++k) {
-                        double h = (double)H[(size_t)j * d_in + k];
-                        for (int32_t c = 0; c < d_out; ++c) pj[c] += h * Vb[(size_t)k * d_out + c];
+                        double h = round_msg((double)H[(size_t)j * d_in + k], msg_bf16);
+                        for (int32_t c = 0; c < d_out; ++c)
+                            pj[c] += h * round_msg(Vb[(size_t)k * d_out + c], msg_bf16);
                     }
                     double w = a[(size_t)r * B + b] * invc;
                     for (int32_t c = 0; c < d_out; ++c) o[c] += w * round_msg(pj[c], msg_bf16);

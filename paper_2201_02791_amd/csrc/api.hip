@@ -71,6 +71,7 @@ namespace {
 
 struct WsLayout {
     std::vector<size_t> off_P, off_H;   // per layer: projected messages, layer output
+    std::vector<size_t> off_Hbf, off_Wbf, off_WbfT;   // bf16 workloads: bf16 copies of layer input and weights
     size_t off_self = 0, off_G = 0, off_dP = 0, off_dHa = 0, off_dHb = 0, off_seg = 0, off_part = 0, total = 0;
 };
 
@@ -86,8 +87,8 @@ int check_layers(const kge_partition *p, const kge_layer *layers, int32_t n_laye
         KGE_REQUIRE(L.V && L.a && L.W0, KGE_EINVAL, "layer %d has a NULL parameter pointer", l);
         KGE_REQUIRE(L.d_in > 0 && L.d_out > 0 && L.n_bases > 0 && L.n_bases <= 256, KGE_EINVAL,
                     "layer %d: d_in, d_out must be positive and n_bases in [1, 256]", l);
-        KGE_REQUIRE(L.d_in % 4 == 0 && L.d_out % mult == 0, KGE_EINVAL,
-                    "layer %d: d_in must be a multiple of 4 and d_out of %d", l, mult);
+        KGE_REQUIRE(L.d_in % mult == 0 && L.d_out % mult == 0, KGE_EINVAL,
+                    "layer %d: d_in and d_out must be multiples of %d", l, mult);
         KGE_REQUIRE(L.d_out <= dmax && L.d_in <= 512, KGE_EINVAL,
                     "layer %d: d_out must be at most %d and d_in at most 512", l, dmax);
         KGE_REQUIRE(L.act == KGE_ACT_IDENTITY || L.act == KGE_ACT_RELU, KGE_EINVAL, "layer %d: bad act", l);
@@ -103,7 +104,10 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
 {
     const size_t N = (size_t)p->n_vert, ep = msg_dtype == KGE_MSG_BF16 ? 2 : 4;
     size_t cur = 0, max_dout = 0, max_din = 0, max_bd = 0, max_B = 0;
+    const bool bf = msg_dtype == KGE_MSG_BF16;
+    size_t max_nc = 0;
     w->off_P.resize(n_layers); w->off_H.resize(n_layers);
+    w->off_Hbf.assign(n_layers, 0); w->off_Wbf.assign(n_layers, 0); w->off_WbfT.assign(n_layers, 0);
     for (int l = 0; l < n_layers; ++l) {
         const kge_layer &L = layers[l];
         w->off_P[l] = cur; cur = align_up(cur + N * L.n_bases * L.d_out * ep, 256);
@@ -112,10 +116,18 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
         if ((size_t)L.d_in > max_din) max_din = L.d_in;
         if ((size_t)L.n_bases * L.d_out > max_bd) max_bd = (size_t)L.n_bases * L.d_out;
         if ((size_t)L.n_bases > max_B) max_B = L.n_bases;
+        const size_t nc = (size_t)(L.n_bases + 1) * L.d_out;
+        if (nc > max_nc) max_nc = nc;
+        if (bf) {
+            w->off_Hbf[l] = cur; cur = align_up(cur + N * L.d_in * 2, 256);
+            w->off_Wbf[l] = cur; cur = align_up(cur + nc * L.d_in * 2, 256);
+            w->off_WbfT[l] = cur; cur = align_up(cur + nc * L.d_in * 2, 256);
+        }
     }
     w->off_self = cur; cur = align_up(cur + N * max_dout * 4, 256);
     w->off_G = cur; cur = align_up(cur + N * max_dout * 4, 256);
-    w->off_dP = cur; cur = align_up(cur + N * max_bd * ep, 256);
+    // dP; bf16 workloads append G behind it so that X = [dP | G] is one bf16 matrix
+    w->off_dP = cur; cur = align_up(cur + (bf ? N * max_nc * 2 : N * max_bd * ep), 256);
     w->off_dHa = cur; cur = align_up(cur + N * max_din * 4, 256);
     w->off_dHb = cur; cur = align_up(cur + N * max_din * 4, 256);
     w->off_seg = cur; cur = align_up(cur + (size_t)p->n_seg * max_B * 4, 256);
@@ -168,7 +180,16 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_layer *layers,
         const kge_layer &L = layers[l];
         void *P = ws + w.off_P[l];
         float *Hl = (float *)(ws + w.off_H[l]);
-        rc = launch_project(Hin, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, P, bf, Self, st);
+        if (bf) {
+            void *Hbf = ws + w.off_Hbf[l], *Wbf = ws + w.off_Wbf[l], *WbfT = ws + w.off_WbfT[l];
+            rc = launch_cvt_rows_bf16(Hin, p->n_vert * (int64_t)L.d_in, Hbf, st);
+            if (rc != KGE_OK) return rc;
+            rc = launch_cvt_weights_bf16(L.V, L.W0, L.d_in, L.d_out, L.n_bases, Wbf, WbfT, st);
+            if (rc != KGE_OK) return rc;
+            rc = launch_project_bf16(Hbf, p->n_vert, L.d_in, L.d_out, L.n_bases, WbfT, P, Self, st);
+        } else {
+            rc = launch_project(Hin, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, (float *)P, Self, st);
+        }
         if (rc != KGE_OK) return rc;
         rc = launch_gather_forward(p, P, bf, L.a, L.n_bases, L.d_out, Self, L.act, Hl,
                                    l == n_layers - 1 ? H_out : nullptr, part, st);
@@ -214,14 +235,23 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_layer *layers
         }
         rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, part, grads[l].da, st);
         if (rc != KGE_OK) return rc;
-        rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf, part, st);
+        const int64_t bd = (int64_t)L.n_bases * L.d_out;
+        rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf ? bd + L.d_out : bd, bf, part, st);
         if (rc != KGE_OK) return rc;
-        rc = launch_weight_grad(Hprev, p->n_vert, L.d_in, L.d_out, L.n_bases, dP, bf, Gl, grads[l].dV,
-                                grads[l].dW0, st);
+        if (bf) {
+            rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, L.n_bases, dP, st);
+            if (rc != KGE_OK) return rc;
+            rc = launch_weight_grad_bf16(ws + w.off_Hbf[l], p->n_vert, L.d_in, L.d_out, L.n_bases, dP,
+                                         grads[l].dV, grads[l].dW0, st);
+        } else {
+            rc = launch_weight_grad(Hprev, p->n_vert, L.d_in, L.d_out, L.n_bases, (const float *)dP, Gl,
+                                    grads[l].dV, grads[l].dW0, st);
+        }
         if (rc != KGE_OK) return rc;
         if (l > 0 || dH0) {
             float *dst = l > 0 ? dHbuf[l & 1] : dH0;
-            rc = launch_input_grad(dP, bf, Gl, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, dst, st);
+            if (bf) rc = launch_input_grad_bf16(dP, p->n_vert, L.d_in, L.d_out, L.n_bases, ws + w.off_Wbf[l], dst, st);
+            else rc = launch_input_grad((const float *)dP, Gl, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, dst, st);
             if (rc != KGE_OK) return rc;
             gin = dst;
         }

@@ -73,19 +73,29 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 
 // ---- kernels' host launchers (implemented in the .hip files) ----
 
-// gemm.hip ---------------------------------------------------------------
-// P[N][B*d_out] (msg dtype) and Self[N][d_out] (fp32) = H[N][d_in] * [V_1 .. V_B | W0]
+// gemm.hip (fp32 messages) -------------------------------------------------
+// P[N][B*d_out] and Self[N][d_out] = H[N][d_in] * [V_1 .. V_B | W0]
 int launch_project(const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
-                   const float *V, const float *W0, void *P, int msg_bf16, float *Self,
-                   hipStream_t st);
+                   const float *V, const float *W0, float *P, float *Self, hipStream_t st);
 // dV[B][d_in][d_out] = H^T dP_b ; dW0 = H^T G      (outputs zeroed inside, split over N)
 int launch_weight_grad(const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
-                       const void *dP, int msg_bf16, const float *G, float *dV, float *dW0,
-                       hipStream_t st);
+                       const float *dP, const float *G, float *dV, float *dW0, hipStream_t st);
 // dH[N][d_in] = sum_b dP_b V_b^T + G W0^T
-int launch_input_grad(const void *dP, int msg_bf16, const float *G, int64_t N, int32_t d_in,
-                      int32_t d_out, int32_t B, const float *V, const float *W0, float *dH,
-                      hipStream_t st);
+int launch_input_grad(const float *dP, const float *G, int64_t N, int32_t d_in, int32_t d_out,
+                      int32_t B, const float *V, const float *W0, float *dH, hipStream_t st);
+
+// gemm_bf16.hip (bf16 messages): every operand is a row-major bf16 matrix ----
+int launch_cvt_rows_bf16(const float *src, int64_t n, void *dst, hipStream_t st);
+int launch_cvt_weights_bf16(const float *V, const float *W0, int32_t d_in, int32_t d_out, int32_t B,
+                            void *Wbf /*[d_in][nc]*/, void *WbfT /*[nc][d_in]*/, hipStream_t st);
+// G (fp32 [N][d_out]) -> last d_out columns of X (bf16 [N][(B+1) d_out])
+int launch_append_g_bf16(const float *G, int64_t N, int32_t d_out, int32_t B, void *X, hipStream_t st);
+int launch_project_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
+                        const void *WbfT, void *P, float *Self, hipStream_t st);
+int launch_weight_grad_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
+                            const void *X, float *dV, float *dW0, hipStream_t st);
+int launch_input_grad_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
+                           const void *Wbf, float *dH, hipStream_t st);
 
 // gather.hip -------------------------------------------------------------
 // out[i] = act( sum_{e into i} invc_e sum_b a[rel_e][b] P[src_e][b][:] + Self[i] ); out2 optional copy
@@ -98,8 +108,10 @@ int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t 
                         hipStream_t st);
 // dP[j][b][:] = sum_{e out of j} a[rel_e][b] invc_e G[dst_e][:]
 // `partial`: [hv_sm.n_units][B*d] floats of scratch
+// dP rows are `ld` elements apart (B*d, or (B+1)*d when G is appended behind them)
 int launch_gather_transpose(const kge_partition *p, const float *G, const float *a, int32_t B,
-                            int32_t d, void *dP, int msg_bf16, float *partial, hipStream_t st);
+                            int32_t d, void *dP, int64_t ld, int msg_bf16, float *partial,
+                            hipStream_t st);
 // da[r][b] = sum_{runs (r,i)} invc sum_{j in run} <P[j][b][:], G[i][:]> ; seg_scratch [S][B] floats
 // seg_scratch [S][B] floats; `partial`: [hv_seg.n_units][B] floats
 int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const float *G,

@@ -231,7 +231,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
     int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
     const int32_t *__restrict__ unit_hv,
     const float *__restrict__ G, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_chunks,
-    void *__restrict__ dP, float *__restrict__ partial)
+    void *__restrict__ dP, int64_t ld, float *__restrict__ partial)
 {
     constexpr int NG = 64 / LPR;
     const int lane = threadIdx.x & 63;
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
             *reinterpret_cast<float4 *>(partial + ((int64_t)rw.unit * B + b0 + n) * d + kl * 4) =
                 make_float4(acc[n][0], acc[n][1], acc[n][2], acc[n][3]);
         } else {
-            const int64_t o = ((int64_t)rw.row * B + b0 + n) * d + kl * 4;
+            const int64_t o = (int64_t)rw.row * ld + (int64_t)(b0 + n) * d + kl * 4;
             if (BF16) {
                 uint2 x;
                 x.x = pack_bf16x2(acc[n][0], acc[n][1]); x.y = pack_bf16x2(acc[n][2], acc[n][3]);
@@ -305,7 +305,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
 template <bool BF16>
 __global__ void k_gather_t_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
                                   const int32_t *__restrict__ hv_unit_ptr, const float *__restrict__ partial,
-                                  int32_t bd, void *__restrict__ dP)
+                                  int32_t bd, void *__restrict__ dP, int64_t ld)
 {
     const int bd4 = bd >> 2;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -317,7 +317,7 @@ __global__ void k_gather_t_finish(int32_t n_hv, const int32_t *__restrict__ hv_r
         const float4 x = *reinterpret_cast<const float4 *>(partial + (int64_t)u * bd + k4);
         s.x += x.x; s.y += x.y; s.z += x.z; s.w += x.w;
     }
-    const int64_t o = (int64_t)hv_row[h] * bd + k4;
+    const int64_t o = (int64_t)hv_row[h] * ld + k4;
     if (BF16) {
         uint2 x;
         x.x = pack_bf16x2(s.x, s.y); x.y = pack_bf16x2(s.z, s.w);
@@ -518,7 +518,7 @@ int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t 
 
 template <bool BF16, int LPR>
 static int launch_gather_t_nb(const kge_partition *p, const float *G, const float *a, int32_t B, int32_t d,
-                              void *dP, float *partial, hipStream_t st)
+                              void *dP, int64_t ld, float *partial, hipStream_t st)
 {
     constexpr int NG = 64 / LPR;
     const int64_t N = p->n_vert;
@@ -532,7 +532,7 @@ static int launch_gather_t_nb(const kge_partition *p, const float *G, const floa
         KGE_REQUIRE(cdiv(waves, WPB) < 0x7fffffffLL, KGE_ERANGE, "grid too large");                   \
         k_gather_t<BF16, LPR, NBV, UEV><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(              \
             p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, N, hx.n_units, hx.hv_row, hx.hv_unit_ptr,    \
-            hx.unit_hv, G, a, B, d, n_chunks, dP, partial);                                           \
+            hx.unit_hv, G, a, B, d, n_chunks, dP, ld, partial);                                           \
     }
     if (per_group >= 16) GT_CALL(16, 1)
     else if (per_group >= 8) GT_CALL(8, 2)
@@ -545,22 +545,22 @@ static int launch_gather_t_nb(const kge_partition *p, const float *G, const floa
 }
 
 int launch_gather_transpose(const kge_partition *p, const float *G, const float *a, int32_t B, int32_t d,
-                            void *dP, int msg_bf16, float *partial, hipStream_t st)
+                            void *dP, int64_t ld, int msg_bf16, float *partial, hipStream_t st)
 {
     if (p->n_vert == 0) return KGE_OK;
     const int lpr = pow2_at_least((d + 3) / 4);
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the transposed aggregation kernel", d);
     int rc = KGE_OK;
-    if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(p, G, a, B, d, dP, partial, st))); }
-    else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, L>(p, G, a, B, d, dP, partial, st))); }
+    if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(p, G, a, B, d, dP, ld, partial, st))); }
+    else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, L>(p, G, a, B, d, dP, ld, partial, st))); }
     if (rc != KGE_OK) return rc;
     const kge_heavy_index &hx = p->hv_sm;
     if (hx.n_hv > 0) {
         KGE_PROF("gather_t_fin", st);
         const int bd = B * d;
         const int64_t n = (int64_t)hx.n_hv * (bd / 4);
-        if (msg_bf16) k_gather_t_finish<true><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, bd, dP);
-        else k_gather_t_finish<false><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, bd, dP);
+        if (msg_bf16) k_gather_t_finish<true><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, bd, dP, ld);
+        else k_gather_t_finish<false><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, bd, dP, ld);
         KGE_LAUNCH_CHECK();
     }
     return KGE_OK;

@@ -9,7 +9,8 @@
 // 64x64 sub-tile as 2x2 v_mfma_f32_32x32x2_f32 accumulators.  Operands are staged through LDS
 // K-major (As[k][m], Bs[k][n]) so that the MFMA operand reads are 32 consecutive floats.
 // Operand loaders and the epilogue are small functors, so the concatenated operands
-// ([V|W0], [dP|G]) are never materialised.
+// ([V|W0], [dP|G]) are never materialised.  This file is the fp32 path; workloads with bf16
+// messages use the bf16 matrix-core kernels of gemm_bf16.hip.
 #include "common.h"
 
 namespace {
@@ -17,15 +18,6 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 128, BN = 128, BK = 16, PADL = 4, GT = 256;
-
-__device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16(float f)   // round to nearest even
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
 
 // ---- operand sources: load4(row, col) returns 4 consecutive elements along the contiguous
 // dimension starting at (row, col); out-of-range -> zeros.  Contiguous extents are multiples of 4.
@@ -52,36 +44,27 @@ struct SrcWcat {
     }
 };
 
-// [dP | G] viewed as an (N x (B+1) d_out) matrix; dP is fp32 or bf16, G is fp32
-template <bool BF16>
+// [dP | G] viewed as an (N x (B+1) d_out) matrix, both fp32
 struct SrcXcat {
-    const void *dP; const float *G; int64_t rows; int32_t d_out, B;
+    const float *dP; const float *G; int64_t rows; int32_t d_out, B;
     __device__ __forceinline__ float4 load4(int64_t r, int32_t c) const
     {
         int32_t bd = B * d_out;
         if (r >= rows || c >= bd + d_out) return make_float4(0.f, 0.f, 0.f, 0.f);
         if (c >= bd) return *reinterpret_cast<const float4 *>(G + r * d_out + (c - bd));
-        if (BF16) {
-            const uint16_t *q = reinterpret_cast<const uint16_t *>(dP) + r * bd + c;
-            uint2 w = *reinterpret_cast<const uint2 *>(q);
-            return make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u),
-                               __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xffff0000u));
-        }
-        return *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(dP) + r * bd + c);
+        return *reinterpret_cast<const float4 *>(dP + r * bd + c);
     }
 };
 
 // ---- epilogues: store(m, n, value)
-template <bool BF16>
-struct EpiProject {             // columns < B*d_out go to P (msg dtype), the rest to Self
-    void *P; float *Self; int64_t rows; int32_t d_out, B;
+struct EpiProject {             // columns < B*d_out go to P, the rest to Self
+    float *P; float *Self; int64_t rows; int32_t d_out, B;
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         int32_t bd = B * d_out;
         if (m >= rows || n >= bd + d_out) return;
         if (n >= bd) Self[m * d_out + (n - bd)] = v;
-        else if (BF16) reinterpret_cast<uint16_t *>(P)[m * bd + n] = f32_to_bf16(v);
-        else reinterpret_cast<float *>(P)[m * bd + n] = v;
+        else P[m * bd + n] = v;
     }
 };
 
@@ -236,7 +219,7 @@ int launch_fill_zero(void *ptr, size_t bytes, hipStream_t st)
 }
 
 int launch_project(const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const float *V,
-                   const float *W0, void *P, int msg_bf16, float *Self, hipStream_t st)
+                   const float *W0, float *P, float *Self, hipStream_t st)
 {
     if (N == 0) return KGE_OK;
     int32_t nc = (B + 1) * d_out;
@@ -244,20 +227,14 @@ int launch_project(const float *H, int64_t N, int32_t d_in, int32_t d_out, int32
     SrcRowMajorF32 sa{H, N, d_in};
     SrcWcat sb{V, W0, d_in, d_out, B};
     KGE_PROF("project", st);
-    if (msg_bf16) {
-        EpiProject<true> ep{P, Self, N, d_out, B};
-        k_gemm<SrcRowMajorF32, true, SrcWcat, false, EpiProject<true>><<<grid, GT, 0, st>>>(sa, sb, ep, d_in, d_in);
-    } else {
-        EpiProject<false> ep{P, Self, N, d_out, B};
-        k_gemm<SrcRowMajorF32, true, SrcWcat, false, EpiProject<false>><<<grid, GT, 0, st>>>(sa, sb, ep, d_in, d_in);
-    }
+    EpiProject ep{P, Self, N, d_out, B};
+    k_gemm<SrcRowMajorF32, true, SrcWcat, false, EpiProject><<<grid, GT, 0, st>>>(sa, sb, ep, d_in, d_in);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
 
 int launch_weight_grad(const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
-                       const void *dP, int msg_bf16, const float *G, float *dV, float *dW0,
-                       hipStream_t st)
+                       const float *dP, const float *G, float *dV, float *dW0, hipStream_t st)
 {
     int rc = launch_fill_zero(dV, sizeof(float) * (size_t)B * d_in * d_out, st);
     if (rc != KGE_OK) return rc;
@@ -275,18 +252,13 @@ int launch_weight_grad(const float *H, int64_t N, int32_t d_in, int32_t d_out, i
     SrcRowMajorF32 sa{H, N, d_in};
     EpiWeightGrad ep{dV, dW0, d_in, d_out, B};
     KGE_PROF("weight_grad", st);
-    if (msg_bf16) {
-        SrcXcat<true> sb{dP, G, N, d_out, B};
-        k_gemm<SrcRowMajorF32, false, SrcXcat<true>, false, EpiWeightGrad><<<grid, GT, 0, st>>>(sa, sb, ep, N, kchunk);
-    } else {
-        SrcXcat<false> sb{dP, G, N, d_out, B};
-        k_gemm<SrcRowMajorF32, false, SrcXcat<false>, false, EpiWeightGrad><<<grid, GT, 0, st>>>(sa, sb, ep, N, kchunk);
-    }
+    SrcXcat sb{dP, G, N, d_out, B};
+    k_gemm<SrcRowMajorF32, false, SrcXcat, false, EpiWeightGrad><<<grid, GT, 0, st>>>(sa, sb, ep, N, kchunk);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
 
-int launch_input_grad(const void *dP, int msg_bf16, const float *G, int64_t N, int32_t d_in,
+int launch_input_grad(const float *dP, const float *G, int64_t N, int32_t d_in,
                       int32_t d_out, int32_t B, const float *V, const float *W0, float *dH,
                       hipStream_t st)
 {
@@ -296,13 +268,8 @@ int launch_input_grad(const void *dP, int msg_bf16, const float *G, int64_t N, i
     SrcWcat sb{V, W0, d_in, d_out, B};
     EpiRowMajor ep{dH, N, d_in};
     KGE_PROF("input_grad", st);
-    if (msg_bf16) {
-        SrcXcat<true> sa{dP, G, N, d_out, B};
-        k_gemm<SrcXcat<true>, true, SrcWcat, true, EpiRowMajor><<<grid, GT, 0, st>>>(sa, sb, ep, nc, nc);
-    } else {
-        SrcXcat<false> sa{dP, G, N, d_out, B};
-        k_gemm<SrcXcat<false>, true, SrcWcat, true, EpiRowMajor><<<grid, GT, 0, st>>>(sa, sb, ep, nc, nc);
-    }
+    SrcXcat sa{dP, G, N, d_out, B};
+    k_gemm<SrcXcat, true, SrcWcat, true, EpiRowMajor><<<grid, GT, 0, st>>>(sa, sb, ep, nc, nc);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }

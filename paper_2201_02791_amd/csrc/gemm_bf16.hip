@@ -1,0 +1,381 @@
+// The three dense contractions of the encoder (see gemm.hip) for workloads that keep messages
+// in bf16, on v_mfma_f32_32x32x16_bf16 (fp32 accumulation).
+//
+// Every operand is a plain row-major bf16 matrix by the time it reaches a GEMM: small
+// conversion kernels write a bf16 copy of the layer input, of [V_1..V_B | W_0] (row-major and
+// transposed), and append the upstream gradient G to the dP buffer, so that X = [dP | G] is one
+// matrix.  The GEMM loaders are then bare 16-byte (or 4-byte) loads.
+//
+//   project      [P | Self] = Hbf  (N x K)  *  WbfT^T   both operands k-contiguous
+//   input_grad   dH         = X    (N x nc) *  Wbf^T    both operands k-contiguous
+//   weight_grad  d[V | W0]  = Hbf^T * X                 both operands k-strided (k = vertex)
+//
+// Block tile 128 x 256 x 32, 4 wavefronts in a 2 x 2 grid, each owning 64 x 128 = 2 x 4 MFMA
+// tiles (128 accumulator registers, two blocks per CU).  LDS holds A as [m][k] and B as [n][k],
+// k contiguous, rows padded to 80 bytes so the 16-byte operand reads of a half-wavefront touch
+// every bank once.  A lane feeds the matrix core 8 consecutive k values of one row; k-strided
+// sources are transposed in registers (8 k x 2 columns per thread) before the LDS write.  The
+// next tile's global loads are issued before the MFMA loop of the current tile.  The projection's
+// epilogue goes through LDS so that P is written as 16-byte bf16 vectors, 256 bytes per row.
+#include "common.h"
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int TM = 128, TN = 256, TK = 32, LDK = TK + 8, NT = 256;
+constexpr int EPI_LD = 128;                           // floats per staged row: 4 x 32 x 128 x 4 B = 64 KB
+constexpr int LDS_MAIN = (TM + TN) * LDK * 2;         // bytes
+constexpr int LDS_EPI = 4 * 32 * EPI_LD * 4;          // bytes: 4 wavefronts x 32 rows
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi)   // two fp32 -> packed bf16x2, nearest even
+{
+    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+    a = ((a & 0x7fffffffu) > 0x7f800000u) ? ((a >> 16) | 0x40u) : ((a + 0x7fffu + ((a >> 16) & 1u)) >> 16);
+    b = ((b & 0x7fffffffu) > 0x7f800000u) ? ((b >> 16) | 0x40u) : ((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
+    return (a & 0xffffu) | (b << 16);
+}
+
+// Row-major bf16 matrix.  oct: 8 consecutive elements (16 bytes); pair: 2 (4 bytes).  Out of range -> 0.
+struct MatBF {
+    const uint16_t *p; int64_t rows; int32_t cols; int64_t ld;
+    __device__ __forceinline__ uint4 oct(int64_t r, int32_t c) const
+    {
+        if (r >= rows || c >= cols) return make_uint4(0u, 0u, 0u, 0u);
+        return *reinterpret_cast<const uint4 *>(p + r * ld + c);
+    }
+    __device__ __forceinline__ uint32_t pair(int64_t r, int32_t c) const
+    {
+        if (r >= rows || c >= cols) return 0u;
+        return *reinterpret_cast<const uint32_t *>(p + r * ld + c);
+    }
+};
+
+struct EpiProjectStaged {     // columns < bd -> P (bf16), the rest -> Self (fp32); through LDS
+    static constexpr bool staged = true;
+    uint16_t *P; float *Self; int64_t rows; int32_t d_out, bd;
+    __device__ __forceinline__ void store8(int64_t m, int32_t n, const float4 &x, const float4 &y) const
+    {
+        if (m >= rows || n >= bd + d_out) return;
+        if (n < bd) {
+            *reinterpret_cast<uint4 *>(P + m * bd + n) =
+                make_uint4(pack2(x.x, x.y), pack2(x.z, x.w), pack2(y.x, y.y), pack2(y.z, y.w));
+        } else {
+            float *q = Self + m * d_out + (n - bd);
+            *reinterpret_cast<float4 *>(q) = x;
+            *reinterpret_cast<float4 *>(q + 4) = y;
+        }
+    }
+    __device__ __forceinline__ void store(int64_t, int32_t, float) const {}
+};
+struct EpiWeightGradAtomic {
+    static constexpr bool staged = false;
+    float *dV, *dW0; int32_t d_in, d_out, B;
+    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
+    {
+        const int32_t bd = B * d_out;
+        if (m >= d_in || n >= bd + d_out) return;
+        const int32_t b = n / d_out, c = n - b * d_out;
+        float *dst = b < B ? dV + ((int64_t)b * d_in + m) * d_out + c : dW0 + m * d_out + c;
+        unsafeAtomicAdd(dst, v);
+    }
+    __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
+};
+struct EpiRowMajorF32 {
+    static constexpr bool staged = false;
+    float *out; int64_t rows; int32_t cols;
+    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
+    {
+        if (m < rows && n < cols) out[m * cols + n] = v;
+    }
+    __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
+};
+
+// eight packed pairs (k = 0..7, columns x and x+1) -> the k-octets of column x and of column x+1
+__device__ __forceinline__ void transpose_pairs(const uint32_t (&pr)[8], uint4 &c0, uint4 &c1)
+{
+    c0.x = (pr[0] & 0xffffu) | (pr[1] << 16); c0.y = (pr[2] & 0xffffu) | (pr[3] << 16);
+    c0.z = (pr[4] & 0xffffu) | (pr[5] << 16); c0.w = (pr[6] & 0xffffu) | (pr[7] << 16);
+    c1.x = (pr[0] >> 16) | (pr[1] & 0xffff0000u); c1.y = (pr[2] >> 16) | (pr[3] & 0xffff0000u);
+    c1.z = (pr[4] >> 16) | (pr[5] & 0xffff0000u); c1.w = (pr[6] >> 16) | (pr[7] & 0xffff0000u);
+}
+
+// KC = true : C[m][n] = sum_k A[m][k] B[n][k]   (A.oct(m, k), B.oct(n, k))
+// KC = false: C[m][n] = sum_k A[k][m] B[k][n]   (A.pair(k, m), B.pair(k, n))
+template <bool KC, class EPI>
+__global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, int64_t K, int64_t kchunk,
+                                                     int32_t tiles_m, int32_t tiles_n)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    uint16_t (*As)[LDK] = reinterpret_cast<uint16_t (*)[LDK]>(smem);
+    uint16_t (*Bs)[LDK] = reinterpret_cast<uint16_t (*)[LDK]>(smem + TM * LDK * 2);
+
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int wm = w >> 1, wn = w & 1;
+    // block id -> (split, row tile, column tile), column tiles fastest so that neighbouring
+    // blocks share their A rows in L2
+    int64_t bid = blockIdx.x;
+    const int32_t tn = (int32_t)(bid % tiles_n); bid /= tiles_n;
+    const int32_t tm = (int32_t)(bid % tiles_m); bid /= tiles_m;
+    const int64_t m0 = (int64_t)tm * TM;
+    const int32_t n0 = tn * TN;
+    const int64_t kbeg = bid * kchunk;
+    const int64_t kend = (kbeg + kchunk < K) ? kbeg + kchunk : K;
+
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    uint4 ra[2], rb[4];       // the next tile, staged in registers
+
+    auto load_tile = [&](int64_t k0) {
+        if (KC) {
+            const int row = t >> 2, ko = (t & 3) * 8;
+            const bool kok = k0 + ko < kend;
+#pragma unroll
+            for (int ps = 0; ps < 2; ++ps)
+                ra[ps] = kok ? A.oct(m0 + row + ps * 64, (int32_t)(k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int ps = 0; ps < 4; ++ps)
+                rb[ps] = kok ? B.oct(n0 + row + ps * 64, (int32_t)(k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
+        } else {
+            const int cp = t & 63, ko = (t >> 6) * 8;
+            uint32_t pr[8];
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+                pr[kk] = (k0 + ko + kk < kend) ? A.pair(k0 + ko + kk, (int32_t)(m0 + 2 * cp)) : 0u;
+            transpose_pairs(pr, ra[0], ra[1]);
+#pragma unroll
+            for (int ps = 0; ps < 2; ++ps) {
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk)
+                    pr[kk] = (k0 + ko + kk < kend) ? B.pair(k0 + ko + kk, n0 + 2 * (cp + ps * 64)) : 0u;
+                transpose_pairs(pr, rb[2 * ps], rb[2 * ps + 1]);
+            }
+        }
+    };
+    auto store_tile = [&]() {
+        if (KC) {
+            const int row = t >> 2, ko = (t & 3) * 8;
+#pragma unroll
+            for (int ps = 0; ps < 2; ++ps) *reinterpret_cast<uint4 *>(&As[row + ps * 64][ko]) = ra[ps];
+#pragma unroll
+            for (int ps = 0; ps < 4; ++ps) *reinterpret_cast<uint4 *>(&Bs[row + ps * 64][ko]) = rb[ps];
+        } else {
+            const int cp = t & 63, ko = (t >> 6) * 8;
+            *reinterpret_cast<uint4 *>(&As[2 * cp][ko]) = ra[0];
+            *reinterpret_cast<uint4 *>(&As[2 * cp + 1][ko]) = ra[1];
+#pragma unroll
+            for (int ps = 0; ps < 2; ++ps) {
+                *reinterpret_cast<uint4 *>(&Bs[2 * (cp + ps * 64)][ko]) = rb[2 * ps];
+                *reinterpret_cast<uint4 *>(&Bs[2 * (cp + ps * 64) + 1][ko]) = rb[2 * ps + 1];
+            }
+        }
+    };
+
+    if (kbeg < kend) load_tile(kbeg);
+    for (int64_t k0 = kbeg; k0 < kend; k0 += TK) {
+        __syncthreads();                 // previous tile fully consumed
+        store_tile();
+        __syncthreads();
+        if (k0 + TK < kend) load_tile(k0 + TK);      // in flight during the MFMA loop
+#pragma unroll
+        for (int ks = 0; ks < TK; ks += 16) {
+            const int kc = ks + 8 * (lane >> 5);
+            bf16x8 af[2], bfr[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[wm * 64 + i * 32 + (lane & 31)][kc]));
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                bfr[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[wn * 128 + j * 32 + (lane & 31)][kc]));
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    // D register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 tile
+    if (EPI::staged) {
+        float *stage = reinterpret_cast<float *>(smem) + w * 32 * EPI_LD;   // 32 rows x 128 columns per wavefront
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            __syncthreads();             // operand tiles (or the previous row group) no longer needed
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    stage[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * EPI_LD + j * 32 + (lane & 31)] = acc[i][j][v];
+            __syncthreads();
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int row = it * 4 + (lane >> 4), c8 = (lane & 15) * 8;
+                const float4 x = *reinterpret_cast<const float4 *>(&stage[row * EPI_LD + c8]);
+                const float4 y = *reinterpret_cast<const float4 *>(&stage[row * EPI_LD + c8 + 4]);
+                epi.store8(m0 + wm * 64 + i * 32 + row, n0 + wn * 128 + c8, x, y);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    const int col = wn * 128 + j * 32 + (lane & 31);
+                    epi.store(m0 + row, n0 + col, acc[i][j][v]);
+                }
+    }
+}
+
+// ---- conversion kernels
+__global__ void k_cvt_rows(const float4 *__restrict__ src, int64_t n4, uint2 *__restrict__ dst)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n4; i += stride) {
+        const float4 x = src[i];
+        dst[i] = make_uint2(pack2(x.x, x.y), pack2(x.z, x.w));
+    }
+}
+
+// G (fp32 [N][d_out]) -> columns [bd, bd + d_out) of X (bf16 [N][nc])
+__global__ void k_append_g(const float4 *__restrict__ G, int64_t N, int32_t d_out, int32_t bd, int32_t nc,
+                           uint16_t *__restrict__ X)
+{
+    const int d4 = d_out >> 2;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x, n4 = N * d4;
+    for (; i < n4; i += stride) {
+        const int64_t r = i / d4;
+        const int c = (int)(i - r * d4) * 4;
+        const float4 x = G[i];
+        *reinterpret_cast<uint2 *>(X + r * nc + bd + c) = make_uint2(pack2(x.x, x.y), pack2(x.z, x.w));
+    }
+}
+
+// [V_1 .. V_B | W0] (fp32) -> Wbf [d_in][nc] and WbfT [nc][d_in], bf16
+__global__ void k_cvt_weights(const float *__restrict__ V, const float *__restrict__ W0, int32_t d_in,
+                              int32_t d_out, int32_t B, uint16_t *__restrict__ Wbf, uint16_t *__restrict__ WbfT)
+{
+    const int32_t nc = (B + 1) * d_out;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)d_in * nc) return;
+    const int32_t k = (int32_t)(idx / nc), n = (int32_t)(idx - (int64_t)k * nc);
+    const int32_t b = n / d_out, c = n - b * d_out;
+    const float v = b < B ? V[((int64_t)b * d_in + k) * d_out + c] : W0[(int64_t)k * d_out + c];
+    const uint16_t h = (uint16_t)(pack2(v, 0.f) & 0xffffu);
+    Wbf[idx] = h;
+    WbfT[(int64_t)n * d_in + k] = h;
+}
+
+template <bool KC, class EPI>
+int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64_t kchunk, int32_t tiles_m,
+                int32_t tiles_n, int64_t splits, hipStream_t st)
+{
+    const int64_t blocks = splits * tiles_m * tiles_n;
+    KGE_REQUIRE(blocks < 0x7fffffffLL, KGE_ERANGE, "grid too large");
+    const size_t lds = EPI::staged ? (LDS_EPI > LDS_MAIN ? LDS_EPI : LDS_MAIN) : LDS_MAIN;
+    static bool attr_set = false;
+    if (!attr_set) {
+        KGE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<KC, EPI>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    k_gemm_bf16<KC, EPI><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n);
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+}  // namespace
+
+int launch_cvt_rows_bf16(const float *src, int64_t n, void *dst, hipStream_t st)
+{
+    if (n == 0) return KGE_OK;
+    int64_t n4 = n / 4, blocks = cdiv(n4, 256);
+    if (blocks > 65536) blocks = 65536;
+    KGE_PROF("cvt_rows", st);
+    k_cvt_rows<<<(unsigned)blocks, 256, 0, st>>>(reinterpret_cast<const float4 *>(src), n4, reinterpret_cast<uint2 *>(dst));
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+int launch_append_g_bf16(const float *G, int64_t N, int32_t d_out, int32_t B, void *X, hipStream_t st)
+{
+    if (N == 0) return KGE_OK;
+    int64_t blocks = cdiv(N * (d_out / 4), 256);
+    if (blocks > 65536) blocks = 65536;
+    KGE_PROF("append_g", st);
+    k_append_g<<<(unsigned)blocks, 256, 0, st>>>(reinterpret_cast<const float4 *>(G), N, d_out, B * d_out,
+                                                 (B + 1) * d_out, reinterpret_cast<uint16_t *>(X));
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+int launch_cvt_weights_bf16(const float *V, const float *W0, int32_t d_in, int32_t d_out, int32_t B, void *Wbf,
+                            void *WbfT, hipStream_t st)
+{
+    const int64_t n = (int64_t)d_in * (B + 1) * d_out;
+    KGE_PROF("cvt_weights", st);
+    k_cvt_weights<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(V, W0, d_in, d_out, B, reinterpret_cast<uint16_t *>(Wbf),
+                                                         reinterpret_cast<uint16_t *>(WbfT));
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+// [P | Self] = Hbf * [V | W0]      Hbf: bf16 [N][d_in]; WbfT: bf16 [nc][d_in]
+int launch_project_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const void *WbfT,
+                        void *P, float *Self, hipStream_t st)
+{
+    if (N == 0) return KGE_OK;
+    const int32_t nc = (B + 1) * d_out;
+    const int32_t tiles_m = (int32_t)cdiv(N, TM), tiles_n = (int32_t)cdiv(nc, TN);
+    MatBF A{reinterpret_cast<const uint16_t *>(Hbf), N, d_in, d_in};
+    MatBF Bm{reinterpret_cast<const uint16_t *>(WbfT), nc, d_in, d_in};
+    EpiProjectStaged ep{reinterpret_cast<uint16_t *>(P), Self, N, d_out, B * d_out};
+    KGE_PROF("project", st);
+    return launch_gemm<true, EpiProjectStaged>(A, Bm, ep, d_in, cdiv(d_in, TK) * TK, tiles_m, tiles_n, 1, st);
+}
+
+// d[V | W0] = Hbf^T X     X: bf16 [N][nc] = [dP | G]
+int launch_weight_grad_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const void *X,
+                            float *dV, float *dW0, hipStream_t st)
+{
+    int rc = launch_fill_zero(dV, sizeof(float) * (size_t)B * d_in * d_out, st);
+    if (rc != KGE_OK) return rc;
+    rc = launch_fill_zero(dW0, sizeof(float) * (size_t)d_in * d_out, st);
+    if (rc != KGE_OK) return rc;
+    if (N == 0) return KGE_OK;
+    const int32_t nc = (B + 1) * d_out;
+    const int32_t tiles_m = (int32_t)cdiv(d_in, TM), tiles_n = (int32_t)cdiv(nc, TN);
+    int64_t splits = cdiv(2048, (int64_t)tiles_m * tiles_n);
+    int64_t kchunk = cdiv(cdiv(N, splits), TK) * TK;
+    if (kchunk < 8 * TK) kchunk = 8 * TK;
+    splits = cdiv(N, kchunk);
+    MatBF A{reinterpret_cast<const uint16_t *>(Hbf), N, d_in, d_in};
+    MatBF Bm{reinterpret_cast<const uint16_t *>(X), N, nc, nc};
+    EpiWeightGradAtomic ep{dV, dW0, d_in, d_out, B};
+    KGE_PROF("weight_grad", st);
+    return launch_gemm<false, EpiWeightGradAtomic>(A, Bm, ep, N, kchunk, tiles_m, tiles_n, splits, st);
+}
+
+// dH = X [V | W0]^T        Wbf: bf16 [d_in][nc]
+int launch_input_grad_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const void *Wbf,
+                           float *dH, hipStream_t st)
+{
+    if (N == 0) return KGE_OK;
+    const int32_t nc = (B + 1) * d_out;
+    const int32_t tiles_m = (int32_t)cdiv(N, TM), tiles_n = (int32_t)cdiv(d_in, TN);
+    MatBF A{reinterpret_cast<const uint16_t *>(X), N, nc, nc};
+    MatBF Bm{reinterpret_cast<const uint16_t *>(Wbf), d_in, nc, nc};
+    EpiRowMajorF32 ep{dH, N, d_in};
+    KGE_PROF("input_grad", st);
+    return launch_gemm<true, EpiRowMajorF32>(A, Bm, ep, nc, cdiv(nc, TK) * TK, tiles_m, tiles_n, 1, st);
+}
