@@ -222,6 +222,24 @@ typedef struct kge_prof_entry {
 int kge_profile_enable(int32_t on);
 int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_entries);
 
+/*
+ * Where the intermediates of a step live inside the caller-owned workspace (for inspection and
+ * tests; the layout is fixed by the partition, the layer list and msg_dtype).  Writes the byte
+ * offset and size of one slice:
+ *   KGE_WS_P    layer l's projected messages P_l [N][B*d_out], msg_dtype (valid after forward)
+ *   KGE_WS_H    layer l's output H_l [N][d_out] float (valid after forward)
+ *   KGE_WS_G    G = dL/d(pre) [N][d_out] float of the last ReLU layer backward has processed
+ *               (a layer with identity activation uses its incoming gradient in place)
+ *   KGE_WS_DP   dP of the last layer backward has processed: [N][ld] msg_dtype with
+ *               ld = B*d_out (fp32 messages) or (B+1)*d_out (bf16 messages: G, rounded to
+ *               bf16, is appended behind the B blocks)
+ *   KGE_WS_DH   gradient with respect to layer l's INPUT, l >= 1, [N][d_in] float (after backward)
+ */
+enum { KGE_WS_P = 0, KGE_WS_H = 1, KGE_WS_G = 2, KGE_WS_DP = 3, KGE_WS_DH = 4 };
+int kge_workspace_slice(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
+                        int32_t msg_dtype, int32_t which, int32_t layer, size_t *offset,
+                        size_t *bytes);
+
 /* Message of the last failure on the calling thread ("" if none). */
 const char *kge_last_error(void);
 

@@ -1,0 +1,110 @@
+"""Row-sampled and any-size checks of the training step (TEST INFRASTRUCTURE ONLY).
+
+For partitions too large for the whole-step oracle, each function here evaluates the paper's
+definition (Eq. 1-2 and the chain rule on them) for a handful of rows, columns or relations,
+in float64 NumPy, from given layer inputs.  A dense matmul is the only library step.  Every
+function is pinned against the whole-step C oracle on a small graph (tests/test_oracle_sampled.py).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+class EdgeView:
+    """Per-edge arrays of a partition in its sorted order: destination, relation, 1/c_{i,r}."""
+
+    def __init__(self, part):
+        lens = np.diff(part["seg_ptr"])
+        seg = np.repeat(np.arange(part["n_seg"]), lens)
+        self.src = part["col_src"]
+        self.dst = part["seg_dst"][seg]
+        self.rel = part["seg_rel"][seg]
+        self.invc = (1.0 / lens.astype(np.float64))[seg]
+        self.n_vert = part["n_vert"]
+
+    def into(self, rows):
+        """Edge indices whose destination is in `rows`."""
+        mask = np.zeros(self.n_vert, bool); mask[np.asarray(rows)] = True
+        return np.nonzero(mask[self.dst])[0]
+
+    def out_of(self, rows):
+        mask = np.zeros(self.n_vert, bool); mask[np.asarray(rows)] = True
+        return np.nonzero(mask[self.src])[0]
+
+
+def project_rows(H_rows, V):
+    """P[j][b][:] = h_j V_b for the given rows (Eq. 2 applied to h_j).  H_rows [n, d_in]."""
+    return np.einsum("nk,bko->nbo", np.asarray(H_rows, np.float64), np.asarray(V, np.float64))
+
+
+def transposed_rows(ev: EdgeView, rows, a, G):
+    """dP[j][b][:] = sum over edges j -> i under r of a_rb (1/c_{i,r}) G_i, for sources `rows`.
+    G is the full [N, d] gradient with respect to the pre-activations (any float dtype)."""
+    a = np.asarray(a, np.float64)
+    rows = np.asarray(rows)
+    B, d = a.shape[1], G.shape[1]
+    out = np.zeros((len(rows), B, d))
+    e = ev.out_of(rows)
+    slot = {int(j): k for k, j in enumerate(rows)}
+    for idx in e:
+        g = np.asarray(G[ev.dst[idx]], np.float64)
+        out[slot[int(ev.src[idx])]] += (a[ev.rel[idx]] * ev.invc[idx])[:, None] * g[None, :]
+    return out
+
+
+def input_grad_rows(dP_rows, G_rows, V, W0):
+    """dH_j = sum_b dP[j][b][:] V_b^T + G_j W_0^T  (chain rule on h_j V_b and h_j W_0)."""
+    V = np.asarray(V, np.float64); W0 = np.asarray(W0, np.float64)
+    return (np.einsum("nbo,bko->nk", np.asarray(dP_rows, np.float64), V)
+            + np.asarray(G_rows, np.float64) @ W0.T)
+
+
+def self_weight_grad(H_in, G, chunk=1 << 18):
+    """dW_0 = H^T G over all vertices, accumulated in float64 chunk by chunk."""
+    d_in, d_out = H_in.shape[1], G.shape[1]
+    out = np.zeros((d_in, d_out))
+    for s in range(0, H_in.shape[0], chunk):
+        g = np.asarray(G[s:s + chunk], np.float64)
+        nz = np.nonzero(np.abs(g).max(axis=1) > 0)[0]
+        if len(nz):
+            out += np.asarray(H_in[s:s + chunk][nz], np.float64).T @ g[nz]
+    return out
+
+
+def basis_weight_grad_column(H_in, dP_col, chunk=1 << 20):
+    """dV_b[:, c] = H^T dP[:, b, c]: one column of one basis gradient, from that column of dP."""
+    out = np.zeros(H_in.shape[1])
+    for s in range(0, H_in.shape[0], chunk):
+        out += np.asarray(H_in[s:s + chunk], np.float64).T @ np.asarray(dP_col[s:s + chunk], np.float64)
+    return out
+
+
+def coeff_grad_relations(ev: EdgeView, rels, P_of, G, B):
+    """da[r][b] = sum over edges j -> i under r of (1/c_{i,r}) <P[j][b][:], G_i>, for the listed
+    relations.  P_of(src_ids) returns the projected rows [n, B, d] of those sources."""
+    out = {}
+    for r in rels:
+        e = np.nonzero(ev.rel == r)[0]
+        acc = np.zeros(B)
+        for s in range(0, len(e), 256):
+            ee = e[s:s + 256]
+            P = np.asarray(P_of(ev.src[ee]), np.float64)
+            g = np.asarray(G[ev.dst[ee]], np.float64)
+            acc += np.einsum("e,ebo,eo->b", ev.invc[ee], P, g)
+        out[int(r)] = acc
+    return out
+
+
+def euler_quantity(pre, H_in, W0, G, chunk=1 << 18):
+    """Q = sum_i <pre_i - h_i W_0, G_i>.  Because the aggregate is linear in the coefficients and in
+    the bases, Q = sum_{r,b} a_rb da_rb = sum_b <dV_b, V_b>  at any size.  `pre` only has to be
+    right where G is non-zero (so ReLU outputs serve as pre-activations there)."""
+    q = 0.0
+    W0 = np.asarray(W0, np.float64)
+    for s in range(0, G.shape[0], chunk):
+        g = np.asarray(G[s:s + chunk], np.float64)
+        nz = np.nonzero(np.abs(g).max(axis=1) > 0)[0]
+        if len(nz):
+            agg = np.asarray(pre[s:s + chunk][nz], np.float64) - np.asarray(H_in[s:s + chunk][nz], np.float64) @ W0
+            q += float(np.sum(agg * g[nz]))
+    return q

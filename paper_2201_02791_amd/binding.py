@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libkge_mi355.so")
 _lib = None
 
 EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
-            "kge_partition_destroy", "kge_workspace_bytes", "kge_rgcn_forward",
+            "kge_partition_destroy", "kge_workspace_bytes", "kge_workspace_slice", "kge_rgcn_forward",
             "kge_rgcn_backward", "kge_sample_negatives", "kge_distmult_score_loss",
             "kge_profile_enable", "kge_profile_collect", "kge_last_error"]
 
@@ -218,3 +218,15 @@ def profile_collect() -> dict:
     n = C.c_int32(0)
     _check(load().kge_profile_collect(arr, C.c_int32(64), C.byref(n)))
     return {arr[i].name.decode(): (float(arr[i].total_ms), int(arr[i].calls)) for i in range(n.value)}
+
+
+WS_P, WS_H, WS_G, WS_DP, WS_DH = 0, 1, 2, 3, 4
+
+
+def workspace_slice(part: Partition, layers: Sequence[dict], which: int, layer: int,
+                    msg_dtype: int = MSG_F32):
+    """(byte offset, byte size) of one intermediate inside the workspace."""
+    off, nbytes = C.c_size_t(0), C.c_size_t(0)
+    _check(load().kge_workspace_slice(part.handle, _layers(layers), C.c_int32(len(layers)), C.c_int32(msg_dtype),
+                                      C.c_int32(which), C.c_int32(layer), C.byref(off), C.byref(nbytes)))
+    return int(off.value), int(nbytes.value)

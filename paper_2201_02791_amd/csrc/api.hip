@@ -161,6 +161,34 @@ extern "C" size_t kge_workspace_bytes(const kge_partition *p, const kge_layer *l
     return w.total;
 }
 
+extern "C" int kge_workspace_slice(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
+                                   int32_t msg_dtype, int32_t which, int32_t layer, size_t *offset,
+                                   size_t *bytes)
+{
+    int rc = check_layers(p, layers, n_layers, msg_dtype);
+    if (rc != KGE_OK) return rc;
+    KGE_REQUIRE(offset && bytes, KGE_EINVAL, "NULL argument");
+    KGE_REQUIRE(layer >= 0 && layer < n_layers, KGE_EINVAL, "layer out of range");
+    WsLayout w;
+    layout(p, layers, n_layers, msg_dtype, &w);
+    const size_t N = (size_t)p->n_vert, ep = msg_dtype == KGE_MSG_BF16 ? 2 : 4;
+    const kge_layer &L = layers[layer];
+    switch (which) {
+    case KGE_WS_P: *offset = w.off_P[layer]; *bytes = N * L.n_bases * L.d_out * ep; break;
+    case KGE_WS_H: *offset = w.off_H[layer]; *bytes = N * L.d_out * 4; break;
+    case KGE_WS_G: *offset = w.off_G; *bytes = N * L.d_out * 4; break;
+    case KGE_WS_DP:
+        *offset = w.off_dP;
+        *bytes = N * (size_t)(msg_dtype == KGE_MSG_BF16 ? L.n_bases + 1 : L.n_bases) * L.d_out * ep;
+        break;
+    case KGE_WS_DH:
+        KGE_REQUIRE(layer >= 1, KGE_EINVAL, "layer 0's input gradient is the caller's dH0");
+        *offset = (layer & 1) ? w.off_dHb : w.off_dHa; *bytes = N * L.d_in * 4; break;
+    default: KGE_REQUIRE(false, KGE_EINVAL, "unknown workspace slice %d", which);
+    }
+    return KGE_OK;
+}
+
 extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
                                 int32_t msg_dtype, const float *H0, void *workspace, size_t ws_bytes,
                                 float *H_out, void *stream)

@@ -56,6 +56,15 @@ class TrainStep:
         self.scores = (torch.empty((n_pos, 1 + n_neg), dtype=torch.float32, device=self.dev)
                        if self.keep_scores else None)
 
+    def view(self, which: int, layer: int):
+        """Torch view [N, width] of one intermediate inside the workspace (see kge_workspace_slice)."""
+        torch = self.torch
+        off, nbytes = kb.workspace_slice(self.part, self.layers, which, layer, self.msg_dtype)
+        raw = self.workspace[off:off + nbytes]
+        bf = self.msg_dtype == kb.MSG_BF16 and which in (kb.WS_P, kb.WS_DP)
+        t = raw.view(torch.bfloat16 if bf else torch.float32)
+        return t.view(self.part.n_vert, -1)
+
     # --- the four per-step calls, in Algorithm 1's order
     def forward(self, stream=None):
         kb.rgcn_forward(self.part, self.layers, self.H0, self.workspace, self.H_out, self.msg_dtype, stream)

@@ -1,0 +1,184 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The whole-step oracle is too slow there, so every kernel's output is checked on samples the
+oracle can compute one by one (rows, columns, rare relations) or through properties that hold
+at any size, all evaluated from the GPU's own stored layer inputs:
+
+  build_partition   every array, bit-exact          sample_negatives   every draw, bit-exact
+  project           sampled rows of P               gather (forward)   sampled rows of H_1, H_out
+  distmult          all scores, loss, dH_out, dM    activation bwd     sampled rows of G (bit-exact)
+  transposed gather sampled rows of dP              input_grad         sampled rows of dH_1 (and dH0)
+  weight_grad       dW0 whole; dV sampled columns; Euler identity     coefficients  rare relations; Euler
+"""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+from paper_2201_02791_amd import synth
+from gpu_util import SEED, STEP, assert_partition_equal, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print("[gpu-case]", *a, file=sys.stderr, flush=True)
+
+
+def pick_rows(rng, deg, edge_budget, n_max):
+    """Random rows within an edge budget, plus one row that is cut into units (degree >= 256) and
+    the heaviest row if they fit."""
+    order = rng.permutation(len(deg))
+    rows, used = [], 0
+    for v in order[:20000]:
+        if deg[v] <= 200 and used + deg[v] <= 0.5 * edge_budget and len(rows) < n_max:
+            rows.append(int(v)); used += int(deg[v])
+    heavy = np.nonzero(deg >= 256)[0]
+    if len(heavy):
+        h = int(heavy[np.argmin(deg[heavy])])
+        if deg[h] <= 0.25 * edge_budget:
+            rows.append(h); used += int(deg[h])
+        top = int(np.argmax(deg))
+        if deg[top] <= 0.25 * edge_budget and top not in rows:
+            rows.append(top)
+    zero = np.nonzero(deg == 0)[0]
+    if len(zero):
+        rows.append(int(zero[0]))
+    return np.array(sorted(set(rows)), np.int64)
+
+
+def run_full_size(kb, orc, cfg):
+    import torch
+    from oracle import sampled
+    from paper_2201_02791_amd.step import TrainStep
+    spec = synth.WORKLOADS[cfg]
+    bf = spec.msg_dtype == "bf16"
+    tol_v, tol_g = (2e-2, 2e-2) if bf else (1e-4, 1e-3)
+    t0 = time.time()
+    head, rel, tail = synth.make_triples(spec)
+    gp = kb.build_partition(head, rel, tail, spec.n_entities, spec.n_relations, spec.n_parts, spec.part_id,
+                            spec.n_hops, spec.neg_domain)
+    say("config", cfg, "gpu partition N=%d E=%d S=%d (%.0f s)" % (gp.n_vert, gp.n_edge, gp.n_seg, time.time() - t0))
+    op = orc.build_partition(head, rel, tail, spec.n_entities, spec.n_relations, spec.n_parts, spec.part_id,
+                             spec.n_hops, spec.neg_domain)
+    say("oracle partition done (%.0f s)" % (time.time() - t0))
+    assert_partition_equal(gp, op)
+    del head, rel, tail
+    N, d, B = gp.n_vert, spec.d, spec.n_bases
+    params = synth.make_params(spec, N)
+    pos = synth.make_batch(spec, gp.n_core)
+    need_dH0 = not spec.fixed_features
+    ts = TrainStep(gp, params, spec.acts, kb.MSG_BF16 if bf else kb.MSG_F32, need_dH0=need_dH0)
+    ts.set_batch(pos, spec.n_neg)
+    ts.run(spec.neg_mode, SEED, STEP)
+    torch.cuda.synchronize()
+    say("gpu step done (%.0f s)" % (time.time() - t0))
+    c = lambda t: t.detach().float().cpu().numpy()
+    L = [dict(V=params["V"][l], a=params["a"][l], W0=params["W0"][l], act=spec.acts[l]) for l in range(2)]
+    H0 = params["H0"]
+    H1 = c(ts.view(kb.WS_H, 0)); Hout = c(ts.H_out)
+    ev = sampled.EdgeView(op)
+    rng = np.random.default_rng(123)
+    deg_in = np.diff(gp.export("dm_ptr")); deg_out = np.diff(gp.export("sm_ptr"))
+    errs = {}
+
+    # ---- forward: sampled destination rows of both layers, and of P
+    budget = 1.4e10 / (B * d * d)      # oracle cost per edge: B d^2 multiply-adds
+    rows = pick_rows(rng, deg_in, budget, 300)
+    say("forward rows:", len(rows), "edges:", int(deg_in[rows].sum()), "max deg:", int(deg_in[rows].max()))
+    _, want1 = orc.layer_rows(op, rows, L[0]["V"], L[0]["a"], L[0]["W0"], L[0]["act"], H0, msg_bf16=bf)
+    errs["H1 rows"] = (rel_err(H1[rows], want1), tol_v)
+    _, want2 = orc.layer_rows(op, rows, L[1]["V"], L[1]["a"], L[1]["W0"], L[1]["act"], H1, msg_bf16=bf)
+    errs["H_out rows"] = (rel_err(Hout[rows], want2), tol_v)
+    trows = torch.from_numpy(rows).to(ts.dev)
+    P1 = c(ts.view(kb.WS_P, 0)[trows]).reshape(len(rows), B, d)
+    errs["P1 rows"] = (rel_err(P1, sampled.project_rows(H0[rows], L[0]["V"])), tol_v)
+    P2 = c(ts.view(kb.WS_P, 1)[trows]).reshape(len(rows), B, d)
+    errs["P2 rows"] = (rel_err(P2, sampled.project_rows(H1[rows], L[1]["V"])), tol_v)
+    say("forward checked (%.0f s)" % (time.time() - t0), errs)
+
+    # ---- negatives and scoring: everything
+    ne, ns = orc.sample_negatives(op, pos, spec.n_neg, spec.neg_mode, SEED, STEP)
+    np.testing.assert_array_equal(ts.neg_ent.cpu().numpy()[:, :spec.n_neg], ne)
+    np.testing.assert_array_equal(ts.neg_side.cpu().numpy()[:, :spec.n_neg], ns)
+    sl = orc.distmult_score_loss(op, Hout, params["M"], pos, ne, ns)
+    errs["scores"] = (rel_err(c(ts.scores), sl["scores"]), 1e-4)
+    errs["loss"] = (abs(float(ts.loss.cpu()[0]) - sl["loss"]) / sl["loss"], 1e-4)
+    G2 = c(ts.dH_out)
+    errs["dH_out"] = (rel_err(G2, sl["dH"]), 1e-3)
+    errs["dM"] = (rel_err(c(ts.dM), sl["dM"]), 1e-3)
+    del sl
+    say("scoring checked (%.0f s)" % (time.time() - t0))
+
+    # ---- backward
+    srows = pick_rows(rng, deg_out, 40000, 60)
+    tsrows = torch.from_numpy(srows).to(ts.dev)
+    # layer 2 input gradient (dH_1) by definition from G2, and the activation backward
+    dP2 = sampled.transposed_rows(ev, srows, L[1]["a"], G2)
+    want = sampled.input_grad_rows(dP2, G2[srows], L[1]["V"], L[1]["W0"])
+    dH1 = c(ts.view(kb.WS_DH, 1)[tsrows])
+    errs["dH_1 rows"] = (rel_err(dH1, want), tol_g)
+    G1 = c(ts.view(kb.WS_G, 0))
+    np.testing.assert_array_equal(G1[srows], dH1 * (H1[srows] > 0))
+    # layer 1 transposed gather from the GPU's own G1
+    X1 = ts.view(kb.WS_DP, 0)
+    dP1 = c(X1[tsrows])[:, :B * d].reshape(len(srows), B, d)
+    errs["dP_1 rows"] = (rel_err(dP1, sampled.transposed_rows(ev, srows, L[0]["a"], G1)), tol_g)
+    if need_dH0:
+        errs["dH0 rows"] = (rel_err(c(ts.dH0[tsrows]), sampled.input_grad_rows(dP1, G1[srows], L[0]["V"], L[0]["W0"])), tol_g)
+    # self-loop weight gradients, whole
+    errs["dW0_2"] = (rel_err(c(ts.grads[1]["dW0"]), sampled.self_weight_grad(H1, G2)), tol_g)
+    errs["dW0_1"] = (rel_err(c(ts.grads[0]["dW0"]), sampled.self_weight_grad(H0, G1)), tol_g)
+    # basis gradients of layer 1: sampled columns
+    dV1 = c(ts.grads[0]["dV"])
+    for (b, col) in [(0, 0), (B - 1, d - 1), (B // 2, d // 3)]:
+        colv = c(X1[:, b * d + col])
+        want = sampled.basis_weight_grad_column(H0, colv)
+        errs["dV_1[%d][:,%d]" % (b, col)] = (float(np.abs(dV1[b][:, col] - want).max() / np.abs(dV1[b]).max()), tol_g)
+    # Euler identity for both layers: sum a*da = sum V*dV = sum <pre - h W0, G>
+    tol_q = 5e-2 if bf else 2e-3
+    for l, (pre, Hin, G) in enumerate([(H1, H0, G1), (Hout, H1, G2)]):
+        q = sampled.euler_quantity(pre, Hin, L[l]["W0"], G)
+        qa = float(np.sum(L[l]["a"].astype(np.float64) * c(ts.grads[l]["da"])))
+        qv = float(np.sum(L[l]["V"].astype(np.float64) * c(ts.grads[l]["dV"])))
+        scale = max(abs(q), 1e-30)
+        errs["euler da layer %d" % (l + 1)] = (abs(qa - q) / scale, tol_q)
+        errs["euler dV layer %d" % (l + 1)] = (abs(qv - q) / scale, tol_q)
+    # coefficient gradients of rare relations, exactly
+    if 2 * spec.n_relations > 8:
+        cnt = np.bincount(ev.rel, minlength=2 * spec.n_relations)
+        cand = np.nonzero((cnt > 0) & (cnt <= 3000))[0]
+        rels = cand[np.argsort(cnt[cand])][-3:] if len(cand) else []
+        for l, G in ((0, G1), (1, G2)):
+            Pv = ts.view(kb.WS_P, l)
+            P_of = lambda ids: c(Pv[torch.from_numpy(np.asarray(ids, np.int64)).to(ts.dev)]).reshape(len(ids), B, d)
+            want = sampled.coeff_grad_relations(ev, rels, P_of, G, B)
+            da = c(ts.grads[l]["da"])
+            for r, v in want.items():
+                errs["da_%d[rel %d]" % (l + 1, r)] = (float(np.abs(da[r] - v).max() / max(np.abs(v).max(), 1e-30)), tol_g)
+    say("backward checked (%.0f s)" % (time.time() - t0))
+    for k, v in errs.items():
+        say("  %-22s %.3e (tol %.0e)" % (k, v[0], v[1]))
+    bad = {k: v for k, v in errs.items() if not (v[0] <= v[1])}
+    assert not bad, bad
+
+
+@pytest.fixture(scope="module")
+def kb():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2201_02791_amd import binding
+    binding.load()
+    return binding
+
+
+def test_config3_full_size(kb, orc):
+    """Partition 0 of 16 of the 2.9 M-vertex / 30 M-edge graph, d = 128, 2 bases, fp32."""
+    run_full_size(kb, orc, 3)
+
+
+def test_config4_full_size(kb, orc):
+    """Partition 0 of 4 of the 1 M-entity / 20 M-triple / 1,000-relation graph, d = 256, 64 bases,
+    bf16 messages (the oracle stores messages the way the workload says)."""
+    run_full_size(kb, orc, 4)

@@ -1,0 +1,46 @@
+"""The row-sampled / any-size checks used at full benchmark sizes, pinned here against the
+whole-step C oracle on a small graph (which is itself pinned by brute force and finite differences)."""
+import numpy as np
+import pytest
+
+from test_oracle_partition import tiny_graph
+from test_oracle_rgcn import rand_layer
+
+
+@pytest.fixture(scope="module")
+def case(orc):
+    from oracle import sampled
+    head, rel, tail, n, R = tiny_graph(77, n=80, R=3, m=500)
+    part = orc.build_partition(head, rel, tail, n, R, 2, 0, 2, 0)
+    rng = np.random.default_rng(0)
+    d, B = 8, 3
+    layers = [rand_layer(rng, 2 * R, B, d, d, 1), rand_layer(rng, 2 * R, B, d, d, 0)]
+    H0 = rng.normal(0, 1, (part["n_vert"], d)); M = rng.normal(0, 1, (R, d))
+    pos = rng.permutation(part["n_core"])[:40].astype(np.int32)
+    res = orc.train_step(part, layers, H0, M, pos, 3, 1, 5, 0)
+    return sampled, part, layers, H0, res, sampled.EdgeView(part)
+
+
+def test_sampled_rows_match_the_whole_step(case):
+    sampled, part, layers, H0, res, ev = case
+    rows = np.array([0, 3, 11, part["n_vert"] - 1])
+    for l in (1, 0):
+        lay, g = layers[l], res["grads"][l]
+        Hin = res["Hs"][l]
+        P = sampled.project_rows(Hin[rows], lay["V"])
+        dP = sampled.transposed_rows(ev, rows, lay["a"], g["Gpre"])
+        np.testing.assert_allclose(dP, g["dP"][rows], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(sampled.input_grad_rows(g["dP"][rows], g["Gpre"][rows], lay["V"], lay["W0"]),
+                                   g["dH"][rows], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(sampled.self_weight_grad(Hin, g["Gpre"], chunk=16), g["dW0"], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(sampled.basis_weight_grad_column(Hin, g["dP"][:, 1, 2], chunk=16),
+                                   g["dV"][1][:, 2], rtol=1e-11, atol=1e-13)
+        Pfull = sampled.project_rows(Hin, lay["V"])
+        da = sampled.coeff_grad_relations(ev, [0, 4], lambda ids: Pfull[ids], g["Gpre"], P.shape[1])
+        for r, v in da.items():
+            np.testing.assert_allclose(v, g["da"][r], rtol=1e-10, atol=1e-13)
+        # pre-activations: exact ones, and ReLU outputs (equal wherever the gradient is non-zero)
+        for pre in (res["pres"][l], res["Hs"][l + 1]):
+            q = sampled.euler_quantity(pre, Hin, lay["W0"], g["Gpre"], chunk=16)
+            assert q == pytest.approx(float(np.sum(lay["a"] * g["da"])), rel=1e-10)
+            assert q == pytest.approx(float(np.sum(lay["V"] * g["dV"])), rel=1e-10)
