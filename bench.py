@@ -52,6 +52,16 @@ def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg):
     return "hbm", 0.0
 
 
+def measured_traffic(cfg_index, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    runs of this same benchmark (profiles/hbm_traffic.json), or None if not recorded."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    rec = json.load(open(path)).get("configs[%d]" % cfg_index, {}).get(kernel)
+    return None if rec is None else rec["bytes_per_launch"]
+
+
 def cpu_baseline(spec, cfg_index):
     """The oracle as it stands, timed on this host (1 thread), on a bounded sample: the whole
     step on the same generator recipe, scaled down so that it takes roughly 10-30 s."""
@@ -90,6 +100,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="index into the workload list (0..4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain 1 GiB device copy (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one partition per GPU, no collectives); "
@@ -121,7 +133,13 @@ def main():
     ts.set_batch(pos, spec.n_neg)
     log("workspace %.2f GB" % (ts.ws_bytes / 1e9))
 
-    stream = torch.cuda.current_stream()
+    if args.calibrate:     # known traffic: reads 1 GiB, writes 1 GiB
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for w in range(args.warmup):
         ts.run(spec.neg_mode, 1234, w)
     torch.cuda.synchronize()
@@ -157,7 +175,8 @@ def main():
     if dominant:
         kd = kernels[dominant]
         roof = {"kernel": dominant, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
-                "unit": kd["unit"], "frac": kd["frac"], "traffic": None, "avg_launch_ms": kd["avg_ms"]}
+                "unit": kd["unit"], "frac": kd["frac"], "traffic": measured_traffic(args.config, dominant),
+                "avg_launch_ms": kd["avg_ms"]}
     for name in sorted(kernels, key=lambda k: -kernels[k]["ms_per_step"]):
         kd = kernels[name]
         log("%-13s %8.3f ms/step  %5.1f launches  %9.1f %s  (%.1f%% of peak)" % (
