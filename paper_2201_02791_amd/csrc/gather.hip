@@ -222,8 +222,9 @@ __global__ void k_act_backward(const float4 *__restrict__ dH, const float4 *__re
 // ------------------------------------------------------------------ transposed gather
 // One wavefront per (source row work, chunk of bases) on the source-major view:
 //   dP[j][b][:] = sum_{e out of j} a[rel_e][b] invc_e G[dst_e][:]
-// A G row (fp32) is covered by LPR lanes x 4 floats; the 64/LPR lane groups take different
-// bases, NB bases each, so a chunk is (64/LPR)*NB bases.  UE edges are in flight at a time.
+// A G row (fp32) is covered by LPR lanes x 4 floats.  Of the 64/LPR lane groups, GBT take
+// different bases (NB bases each, so a chunk is GBT*NB bases) and the other 64/(LPR*GBT) take
+// different edges; UE rounds of edges are in flight at a time.
 template <bool BF16, int LPR, int NB, int UE>
 __global__ __launch_bounds__(64 * WPB) void k_gather_t(
     const int32_t *__restrict__ sm_ptr, const int32_t *__restrict__ sm_dst,
@@ -231,7 +232,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
     int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
     const int32_t *__restrict__ unit_hv,
     const float *__restrict__ G, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_chunks,
-    void *__restrict__ dP, int64_t ld, float *__restrict__ partial)
+    int32_t gbt_count, void *__restrict__ dP, int64_t ld, float *__restrict__ partial)
 {
     constexpr int NG = 64 / LPR;
     const int lane = threadIdx.x & 63;
@@ -241,8 +242,10 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
     const RowWork rw = row_work(wid, sm_ptr, N, n_units, hv_row, hv_unit_ptr, unit_hv);
     if (rw.row < 0) return;
     const int kl = lane % LPR, g = lane / LPR;
+    const int GBT = gbt_count, GET = NG / GBT;
+    const int gbt = g % GBT, get = g / GBT;
     const bool kact = kl * 4 < d;
-    const int b0 = (bc * NG + g) * NB;
+    const int b0 = (bc * GBT + gbt) * NB;
 
     float acc[NB][4];
 #pragma unroll
@@ -255,20 +258,31 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
         int32_t my_dst = 0, my_rel = 0;
         float my_w = 0.f;
         if (lane < cnt) { my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc[e0 + lane]; }
-        for (int el0 = 0; el0 < cnt; el0 += UE) {
+        const int rounds = (cnt + GET - 1) / GET;       // uniform trip count
+        for (int r0 = 0; r0 < rounds; r0 += UE) {
             float4 gv[UE];
             float w[UE];
             const float *arow[UE];
 #pragma unroll
             for (int u = 0; u < UE; ++u) {
-                const bool ok = el0 + u < cnt;
-                const int el = ok ? el0 + u : el0;
-                const int32_t dst = __builtin_amdgcn_readlane(my_dst, el);
-                const int32_t rel = __builtin_amdgcn_readlane(my_rel, el);
-                w[u] = ok ? __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), el)) : 0.f;
+                const int el = (r0 + u) * GET + get;
+                const bool ok = (r0 + u < rounds) && el < cnt;
+                const int els = ok ? el : 0;
+                int32_t dst, rel;
+                float ww;
+                if (NG == 1) {            // one lane group: the edge is wavefront-uniform (scalar path)
+                    dst = __builtin_amdgcn_readlane(my_dst, els);
+                    rel = __builtin_amdgcn_readlane(my_rel, els);
+                    ww = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), els));
+                } else {
+                    dst = __shfl(my_dst, els, 64);
+                    rel = __shfl(my_rel, els, 64);
+                    ww = __shfl(my_w, els, 64);
+                }
+                w[u] = ok ? ww : 0.f;
                 arow[u] = a + (int64_t)rel * B;
                 gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (kact) gv[u] = *reinterpret_cast<const float4 *>(G + (int64_t)dst * d + kl * 4);
+                if (ok && kact) gv[u] = *reinterpret_cast<const float4 *>(G + (int64_t)dst * d + kl * 4);
             }
 #pragma unroll
             for (int u = 0; u < UE; ++u)
@@ -280,7 +294,13 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
                 }
         }
     }
-    if (!kact) return;
+    // fold the edge groups together (fixed order)
+    for (int off = LPR * GBT; off < 64; off <<= 1)
+#pragma unroll
+        for (int n = 0; n < NB; ++n)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[n][v] += __shfl_xor(acc[n][v], off, 64);
+    if (!kact || get != 0) return;
 #pragma unroll
     for (int n = 0; n < NB; ++n) {
         if (b0 + n >= B) continue;
@@ -299,6 +319,119 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
             }
         }
     }
+}
+
+// The same transposed gather for many bases (B >= 32) on the matrix cores: for one source,
+//   dP[j] (B x d) = W^T (B x deg) * Gg (deg x d),  W[e][b] = a[rel_e][b] invc_e,  Gg[e] = G[dst_e],
+// a small dense product whose inner dimension is the source's out-degree.  v_mfma_f32_32x32x2_f32
+// keeps fp32 inputs; one wavefront owns a (32 bases x 128 columns) block = 1 x 4 tiles and walks
+// the edges two at a time (lane half h supplies edge k+h: 32 coefficients and 32 columns of G).
+typedef float gt_floatx16 __attribute__((ext_vector_type(16)));
+
+template <bool BF16, int NBT>
+__global__ __launch_bounds__(64 * WPB) void k_gather_t_mfma(
+    const int32_t *__restrict__ sm_ptr, const int32_t *__restrict__ sm_dst,
+    const int32_t *__restrict__ sm_rel, const float *__restrict__ sm_invc, int64_t N,
+    int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
+    const int32_t *__restrict__ unit_hv,
+    const float *__restrict__ G, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_bchunks,
+    int32_t n_cchunks, void *__restrict__ dP, int64_t ld, float *__restrict__ partial)
+{
+    constexpr int UK = 4;                                  // edge pairs in flight
+    __shared__ float stage[WPB][32][36];                   // one 32x32 tile per wavefront (bf16 epilogue)
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int64_t wid_all = (int64_t)blockIdx.x * WPB + wv;
+    const int n_chunks = n_bchunks * n_cchunks;
+    const int64_t wid = wid_all / n_chunks;
+    const int chunk = (int)(wid_all - wid * n_chunks);
+    const int bchunk = chunk / n_cchunks, cchunk = chunk - bchunk * n_cchunks;
+    const RowWork rw = row_work(wid, sm_ptr, N, n_units, hv_row, hv_unit_ptr, unit_hv);
+    if (rw.row < 0) return;
+    const int h = lane >> 5, l32 = lane & 31;
+    const int bbase = bchunk * 32 * NBT, cbase = cchunk * 128;
+
+    gt_floatx16 acc[NBT][4];
+#pragma unroll
+    for (int t = 0; t < NBT; ++t)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][c][v] = 0.f;
+
+    for (int32_t e0 = rw.beg; e0 < rw.end; e0 += 64) {
+        const int cnt = min(64, rw.end - e0);
+        int32_t my_dst = 0, my_rel = 0;
+        float my_w = 0.f;
+        if (lane < cnt) { my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc[e0 + lane]; }
+        for (int k0 = 0; k0 < cnt; k0 += 2 * UK) {
+            float wa[UK][NBT], gb[UK][4];
+#pragma unroll
+            for (int u = 0; u < UK; ++u) {
+                const int el = k0 + 2 * u + h;
+                const bool ok = el < cnt;
+                const int els = ok ? el : 0;
+                const int32_t dst = __shfl(my_dst, els, 64);
+                const int32_t rel = __shfl(my_rel, els, 64);
+                const float wsh = __shfl(my_w, els, 64);       // every lane takes part: a shuffle under a
+                const float ww = ok ? wsh : 0.f;               // condition would read zeros from idle lanes
+#pragma unroll
+                for (int t = 0; t < NBT; ++t) {
+                    const int b = bbase + t * 32 + l32;
+                    wa[u][t] = (ok && b < B) ? a[(int64_t)rel * B + b] * ww : 0.f;
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int col = cbase + c * 32 + l32;
+                    gb[u][c] = (ok && col < d) ? G[(int64_t)dst * d + col] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UK; ++u)
+#pragma unroll
+                for (int t = 0; t < NBT; ++t)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[u][t], gb[u][c], acc[t][c], 0, 0, 0);
+        }
+    }
+    // D register v of lane l: base 8*(v/4) + 4*(l/32) + v%4, column l%32 of its tile
+#pragma unroll
+    for (int t = 0; t < NBT; ++t)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int tb = bbase + t * 32, tc = cbase + c * 32;
+            if (tb >= B || tc >= d) continue;              // uniform
+            if (rw.unit >= 0 || !BF16) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int b = tb + 8 * (v >> 2) + 4 * h + (v & 3), col = tc + l32;
+                    if (b < B && col < d) {
+                        if (rw.unit >= 0) partial[((int64_t)rw.unit * B + b) * d + col] = acc[t][c][v];
+                        else reinterpret_cast<float *>(dP)[(int64_t)rw.row * ld + (int64_t)b * d + col] = acc[t][c][v];
+                    }
+                }
+            } else {
+                // through LDS so that each lane writes 16 consecutive bf16 of one base row
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int v = 0; v < 16; ++v) stage[wv][8 * (v >> 2) + 4 * h + (v & 3)][l32] = acc[t][c][v];
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                const int br = lane >> 1, c16 = (lane & 1) * 16;
+                const float4 x0 = *reinterpret_cast<const float4 *>(&stage[wv][br][c16]);
+                const float4 x1 = *reinterpret_cast<const float4 *>(&stage[wv][br][c16 + 4]);
+                const float4 x2 = *reinterpret_cast<const float4 *>(&stage[wv][br][c16 + 8]);
+                const float4 x3 = *reinterpret_cast<const float4 *>(&stage[wv][br][c16 + 12]);
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                if (tb + br < B) {
+                    uint16_t *q = reinterpret_cast<uint16_t *>(dP) + (int64_t)rw.row * ld + (int64_t)(tb + br) * d + tc + c16;
+                    *reinterpret_cast<uint4 *>(q) = make_uint4(pack_bf16x2(x0.x, x0.y), pack_bf16x2(x0.z, x0.w),
+                                                               pack_bf16x2(x1.x, x1.y), pack_bf16x2(x1.z, x1.w));
+                    *reinterpret_cast<uint4 *>(q + 8) = make_uint4(pack_bf16x2(x2.x, x2.y), pack_bf16x2(x2.z, x2.w),
+                                                                   pack_bf16x2(x3.x, x3.y), pack_bf16x2(x3.z, x3.w));
+                }
+            }
+        }
 }
 
 // Heavy sources: dP[j] = sum of the row's unit partials.  One thread per float4 of a [B*d] row.
@@ -523,21 +656,24 @@ static int launch_gather_t_nb(const kge_partition *p, const float *G, const floa
     constexpr int NG = 64 / LPR;
     const int64_t N = p->n_vert;
     const kge_heavy_index &hx = p->hv_sm;
-    const int per_group = (B + NG - 1) / NG;
     KGE_PROF("gather_t", st);
+    // NB bases per lane (a power of two, at most 16); lane groups first cover the bases of a row,
+    // the remaining groups split the edges
 #define GT_CALL(NBV, UEV)                                                                             \
     {                                                                                                 \
-        const int n_chunks = (B + NG * NBV - 1) / (NG * NBV);                                         \
+        int gbt = 1;                                                                                  \
+        while (gbt * 2 <= NG && gbt * NBV < B) gbt *= 2;                                              \
+        const int n_chunks = (B + gbt * NBV - 1) / (gbt * NBV);                                       \
         const int64_t waves = (N + hx.n_units) * n_chunks;                                            \
         KGE_REQUIRE(cdiv(waves, WPB) < 0x7fffffffLL, KGE_ERANGE, "grid too large");                   \
         k_gather_t<BF16, LPR, NBV, UEV><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(              \
             p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, N, hx.n_units, hx.hv_row, hx.hv_unit_ptr,    \
-            hx.unit_hv, G, a, B, d, n_chunks, dP, ld, partial);                                           \
+            hx.unit_hv, G, a, B, d, n_chunks, gbt, dP, ld, partial);                                  \
     }
-    if (per_group >= 16) GT_CALL(16, 1)
-    else if (per_group >= 8) GT_CALL(8, 2)
-    else if (per_group >= 4) GT_CALL(4, 4)
-    else if (per_group >= 2) GT_CALL(2, 4)
+    if (B >= 16) GT_CALL(16, 2)
+    else if (B >= 8) GT_CALL(8, 4)
+    else if (B >= 4) GT_CALL(4, 4)
+    else if (B >= 2) GT_CALL(2, 8)
     else GT_CALL(1, 8)
 #undef GT_CALL
     KGE_LAUNCH_CHECK();
@@ -551,7 +687,20 @@ int launch_gather_transpose(const kge_partition *p, const float *G, const float 
     const int lpr = pow2_at_least((d + 3) / 4);
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the transposed aggregation kernel", d);
     int rc = KGE_OK;
-    if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(p, G, a, B, d, dP, ld, partial, st))); }
+    if (B >= 32 && d % 32 == 0) {
+        // many bases: the per-source product runs on the matrix cores
+        const kge_heavy_index &hxm = p->hv_sm;
+        const int n_bchunks = (B + 31) / 32, n_cchunks = (d + 127) / 128;
+        const int64_t waves = (p->n_vert + hxm.n_units) * n_bchunks * n_cchunks;
+        KGE_REQUIRE(cdiv(waves, WPB) < 0x7fffffffLL, KGE_ERANGE, "grid too large");
+        KGE_PROF("gather_t", st);
+#define GTM_ARGS p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, p->n_vert, hxm.n_units, hxm.hv_row, hxm.hv_unit_ptr, \
+                 hxm.unit_hv, G, a, B, d, n_bchunks, n_cchunks, dP, ld, partial
+        if (msg_bf16) k_gather_t_mfma<true, 1><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(GTM_ARGS);
+        else k_gather_t_mfma<false, 1><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(GTM_ARGS);
+#undef GTM_ARGS
+        KGE_LAUNCH_CHECK();
+    } else if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(p, G, a, B, d, dP, ld, partial, st))); }
     else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, L>(p, G, a, B, d, dP, ld, partial, st))); }
     if (rc != KGE_OK) return rc;
     const kge_heavy_index &hx = p->hv_sm;

@@ -105,7 +105,7 @@ __device__ __forceinline__ void transpose_pairs(const uint32_t (&pr)[8], uint4 &
 // KC = false: C[m][n] = sum_k A[k][m] B[k][n]   (A.pair(k, m), B.pair(k, n))
 template <bool KC, class EPI>
 __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, int64_t K, int64_t kchunk,
-                                                     int32_t tiles_m, int32_t tiles_n)
+                                                     int32_t tiles_m, int32_t tiles_n, int32_t n_splits)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint16_t (*As)[LDK] = reinterpret_cast<uint16_t (*)[LDK]>(smem);
@@ -113,11 +113,22 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
 
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int wm = w >> 1, wn = w & 1;
-    // block id -> (split, row tile, column tile), column tiles fastest so that neighbouring
-    // blocks share their A rows in L2
-    int64_t bid = blockIdx.x;
-    const int32_t tn = (int32_t)(bid % tiles_n); bid /= tiles_n;
-    const int32_t tm = (int32_t)(bid % tiles_m); bid /= tiles_m;
+    // block id -> (split, row tile, column tile).  Workgroup i is dispatched to XCD i % 8, each with
+    // its own L2.  The (split x row tile, column tile) space is cut into patches of 64 tiles (8 x 8 when there are
+    // at least 8 column tiles); a patch goes
+    // to one XCD and the 64 blocks that XCD runs at a time are one patch, so every A row tile and B
+    // column tile that enters an L2 is used by 8 blocks.
+    const int64_t rows_total = (int64_t)n_splits * tiles_m;
+    const int pn = tiles_n >= 8 ? 8 : (tiles_n >= 4 ? 4 : (tiles_n >= 2 ? 2 : 1)), pm = 64 / pn;   // patch shape
+    const int64_t patches_n = (tiles_n + pn - 1) / pn;
+    const int64_t q = blockIdx.x / 8, xcd = blockIdx.x % 8;
+    const int64_t patch = (q / 64) * 8 + xcd;
+    const int r64 = (int)(q % 64);
+    const int64_t prow = (patch / patches_n) * pm + r64 / pn;
+    const int32_t tn = (int32_t)((patch % patches_n) * pn + r64 % pn);
+    if (prow >= rows_total || tn >= tiles_n) return;          // padding blocks of the last patches
+    const int32_t tm = (int32_t)(prow % tiles_m);
+    const int64_t bid = prow / tiles_m;                        // split index
     const int64_t m0 = (int64_t)tm * TM;
     const int32_t n0 = tn * TN;
     const int64_t kbeg = bid * kchunk;
@@ -280,7 +291,9 @@ template <bool KC, class EPI>
 int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64_t kchunk, int32_t tiles_m,
                 int32_t tiles_n, int64_t splits, hipStream_t st)
 {
-    const int64_t blocks = splits * tiles_m * tiles_n;
+    const int pn = tiles_n >= 8 ? 8 : (tiles_n >= 4 ? 4 : (tiles_n >= 2 ? 2 : 1)), pm = 64 / pn;
+    const int64_t n_patches = cdiv(splits * tiles_m, pm) * cdiv(tiles_n, pn);
+    const int64_t blocks = cdiv(n_patches, 8) * 8 * 64;
     KGE_REQUIRE(blocks < 0x7fffffffLL, KGE_ERANGE, "grid too large");
     const size_t lds = EPI::staged ? (LDS_EPI > LDS_MAIN ? LDS_EPI : LDS_MAIN) : LDS_MAIN;
     static bool attr_set = false;
@@ -289,7 +302,7 @@ int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    k_gemm_bf16<KC, EPI><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n);
+    k_gemm_bf16<KC, EPI><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n, (int32_t)splits);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }

@@ -99,6 +99,8 @@ SHAPES = [
     ("d8_B1", 100, 2, 700, 8, 1, 64, 4, 1, 1, [0, 0]),
     ("d256_B5", 200, 3, 1500, 256, 5, 90, 7, 1, 1, [1, 0]),
     ("d16_B20", 250, 9, 2200, 16, 20, 128, 2, 0, 2, [1, 0]),
+    ("d96_B40_matrix_core_transpose", 300, 12, 2600, 96, 40, 150, 3, 1, 1, [1, 0]),
+    ("d160_B70", 200, 5, 1500, 160, 70, 64, 2, 1, 2, [1, 1]),
 ]
 
 
@@ -134,18 +136,19 @@ def test_hub_vertex_and_isolated_rows(kb, orc):
     assert_step_close(ts, res, TOL_VAL, TOL_GRAD)
 
 
-@pytest.mark.parametrize("acts,n,m", [([0, 0], 600, 6000), ([1, 0], 6000, 90000)],
-                         ids=["identity", "relu"])
-def test_bf16_messages_small(kb, orc, acts, n, m):
+@pytest.mark.parametrize("acts,n,m,d,B", [([0, 0], 600, 6000, 64, 8), ([1, 0], 6000, 90000, 64, 8),
+                                          ([0, 0], 900, 9000, 96, 40)],
+                         ids=["identity", "relu", "identity_B40_d96"])
+def test_bf16_messages_small(kb, orc, acts, n, m, d, B):
     """Messages stored as bf16 (fp32 accumulation), tolerance 2e-2.
     The ReLU mask of layer 1 is a decision taken from floating-point values: a pre-activation
     within bf16 rounding of zero flips it, and each flip changes layer-1 gradients by whole
     terms.  So the full comparison is against the oracle that stores messages in bf16 as the
     workload specifies (both sides then take the mask decision in the same precision), and the
     outputs that do not depend on that decision are also held to 2e-2 against the exact oracle."""
-    say("bf16 small", acts, n, m)
+    say("bf16 small", acts, n, m, d, B)
     spec = synth.scaled(synth.WORKLOADS[4], name="bf16-small", seed=3, n_entities=n, n_relations=20,
-                        n_triples=m, d=64, n_bases=8, n_pos=256, n_neg=4, n_parts=2, part_id=0, acts=acts)
+                        n_triples=m, d=d, n_bases=B, n_pos=256, n_neg=4, n_parts=2, part_id=0, acts=acts)
     head, rel, tail = synth.make_triples(spec)
     gp, ts, params, pos = gpu_step(spec, head, rel, tail)
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
