@@ -515,3 +515,33 @@ void orc_distmult_score_loss(int64_t N, int32_t d, int32_t n_rel, const double *
         }
     *loss = T > 0 ? total / (double)T : 0.0;
 }
+
+/* ------------------------------------------------------------------ */
+/* Computational sub-graph of one edge batch (Sec. 3.3, Algorithm 1)   */
+/* ------------------------------------------------------------------ */
+/*
+ * The embeddings of a batch's vertices after layer L depend only on the vertices within L hops
+ * along incoming message edges.  active[l][i] = 1 if layer l+1 (l = 0 .. L-1) has to produce an
+ * output row for vertex i:
+ *   active[L-1] = the batch's vertices (heads and tails of the positives, corrupting entities),
+ *   active[l-1] = active[l]  united with  the sources of every message edge whose destination is
+ *                 in active[l]   (a vertex also needs its own previous row: the self-loop).
+ * `active` is [n_layers][N], overwritten.
+ */
+void orc_compute_graph(int64_t N, int64_t S, const int32_t *seg_ptr, const int32_t *seg_dst,
+                       const int32_t *col_src, int64_t n_batch, const int32_t *batch_vertices,
+                       int32_t n_layers, uint8_t *active)
+{
+    memset(active, 0, (size_t)n_layers * (size_t)N);
+    if (n_layers <= 0) return;
+    uint8_t *top = active + (size_t)(n_layers - 1) * N;
+    for (int64_t k = 0; k < n_batch; ++k) top[batch_vertices[k]] = 1;
+    for (int32_t l = n_layers - 1; l >= 1; --l) {
+        const uint8_t *cur = active + (size_t)l * N;
+        uint8_t *below = active + (size_t)(l - 1) * N;
+        for (int64_t i = 0; i < N; ++i) if (cur[i]) below[i] = 1;
+        for (int64_t s = 0; s < S; ++s)
+            if (cur[seg_dst[s]])
+                for (int32_t e = seg_ptr[s]; e < seg_ptr[s + 1]; ++e) below[col_src[e]] = 1;
+    }
+}

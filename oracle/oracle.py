@@ -211,6 +211,25 @@ def distmult_score_loss(part, H, M, pos_core_idx, neg_ent, neg_side):
     return dict(scores=scores, loss=float(loss[0]), dH=dH, dM=dM)
 
 
+def batch_vertices(part, pos_core_idx, neg_ent):
+    """Local ids of every vertex a scored triple of the batch touches."""
+    pos = np.ascontiguousarray(pos_core_idx, np.int64)
+    return np.concatenate([part["core_h"][pos], part["core_t"][pos],
+                           np.ascontiguousarray(neg_ent, np.int32).reshape(-1)]).astype(np.int32)
+
+
+def compute_graph(part, pos_core_idx, neg_ent, n_layers):
+    """Computational sub-graph of one edge batch (Sec. 3.3, Algorithm 1): uint8 [n_layers][N],
+    row l = the vertices layer l+1 must produce an output for."""
+    bv = np.ascontiguousarray(batch_vertices(part, pos_core_idx, neg_ent), np.int32)
+    N = part["n_vert"]
+    active = np.zeros((n_layers, N), np.uint8)
+    lib().orc_compute_graph(C.c_int64(N), C.c_int64(part["n_seg"]), _p(part["seg_ptr"], _I32),
+                            _p(part["seg_dst"], _I32), _p(part["col_src"], _I32), C.c_int64(len(bv)),
+                            _p(bv, _I32), C.c_int32(n_layers), _p(active, _U8))
+    return active
+
+
 def train_step(part, layers, H0, M, pos_core_idx, n_neg, mode, seed, step, need_dH0=True,
                msg_bf16=False):
     """One whole step: encoder forward, negatives, score + loss, encoder backward."""
