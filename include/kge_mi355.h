@@ -9,6 +9,8 @@
  *   kge_build_partition      Sec. 3.2.1 (core edges) + Sec. 3.2.2 (n-hop
  *                            Neighborhood Expansion); once per partition
  *   kge_rgcn_forward         Eq. 1 with the basis decomposition of Eq. 2
+ *   kge_compute_graph        Sec. 3.3 / Algorithm 1 "getComputeGraph": the
+ *                            vertices within n_layers hops of an edge batch
  *   kge_sample_negatives     Sec. 2.1 (corrupt s or t) under the in-partition
  *                            constraint of Sec. 3.3.1
  *   kge_distmult_score_loss  Eq. 4 (DistMult) and Eq. 3 (cross entropy), with
@@ -54,6 +56,7 @@ enum { KGE_NEG_TAIL = 0, KGE_NEG_HEAD_OR_TAIL = 1 };
 enum { KGE_DOMAIN_CORE = 0, KGE_DOMAIN_ALL = 1 };
 
 typedef struct kge_partition kge_partition;      /* opaque; device resident; library owned    */
+typedef struct kge_cgraph kge_cgraph;            /* opaque; one batch's computational sub-graph */
 
 typedef struct kge_part_info {
     int64_t n_vert;        /* N: vertices after expansion (numerator term of Eq. 7)            */
@@ -144,7 +147,32 @@ size_t kge_workspace_bytes(const kge_partition *p, const kge_layer *layers, int3
                            int32_t msg_dtype);
 
 /*
- * Encoder forward over the whole partition (Eq. 1-2), for l = 1..n_layers:
+ * Computational sub-graph of one edge batch (Sec. 3.3; Algorithm 1, "getComputeGraph").
+ * With L layers the batch's final embeddings depend only on vertices within L hops along
+ * incoming message edges.  For l = L-1 .. 0 (0-based layer index) the object holds one byte per
+ * vertex, active_l[i] = 1 iff layer l has to produce a row for vertex i:
+ *   active_{L-1} = heads and tails of the batch's positives and every corrupting entity,
+ *   active_{l-1} = active_l united with the sources of all message edges into active_l.
+ * A self-sufficient partition (n_hops >= L) contains every such vertex and edge.
+ *
+ * kge_cgraph_create allocates the flags for a partition and a layer count (once per trainer;
+ * synchronous); kge_cgraph_destroy frees them.  kge_compute_graph fills them for one batch:
+ * asynchronous on `stream`, no allocation, no host synchronisation.
+ *   pos_core_idx : device int32 [n_pos], each in [0, n_core)
+ *   neg_ent      : device int32 [n_neg_entries] local vertex ids (as written by
+ *                  kge_sample_negatives, n_neg_entries = n_pos * n_neg), or NULL with 0
+ * kge_cgraph_export (synchronises the device) copies the flags to HOST uint8 [L][N] and/or, per
+ * layer, three counts to HOST int64 [L][3]: active vertices, message edges into them, and
+ * (relation, destination) runs into them; either pointer may be NULL.
+ */
+int kge_cgraph_create(const kge_partition *p, int32_t n_layers, kge_cgraph **out);
+void kge_cgraph_destroy(kge_cgraph *cg);
+int kge_compute_graph(const kge_partition *p, kge_cgraph *cg, const int32_t *pos_core_idx,
+                      int64_t n_pos, const int32_t *neg_ent, int64_t n_neg_entries, void *stream);
+int kge_cgraph_export(const kge_cgraph *cg, uint8_t *host_active, int64_t *host_stats);
+
+/*
+ * Encoder forward (Eq. 1-2), for l = 1..n_layers:
  *   P_l[j][b][:] = h_j V_b (stored as msg_dtype),  pre_i = sum_r sum_{j in N_i^r} (1/c_ir)
  *   sum_b a_rb P_l[j][b][:] + h_i W_0,  h'_i = act(pre_i)   (fp32 accumulation throughout).
  *   layers    : HOST array of n_layers descriptors (their pointers are device memory);
@@ -152,10 +180,15 @@ size_t kge_workspace_bytes(const kge_partition *p, const kge_layer *layers, int3
  *   H0        : device float [N][layers[0].d_in]
  *   workspace : device, >= kge_workspace_bytes(...), 256-byte aligned; keeps what backward needs
  *   H_out     : device float [N][layers[n_layers-1].d_out]
+ *   cg        : NULL = propagate the whole partition.  Otherwise a sub-graph filled by
+ *               kge_compute_graph for the batch that will be scored: each layer aggregates only
+ *               into its active destinations and writes zero rows elsewhere.  The rows of H_out
+ *               on the batch's vertices, the loss and every gradient are the same as with NULL
+ *               (rows outside cannot reach the batch); H_out rows of other vertices are zero.
  */
-int kge_rgcn_forward(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
-                     int32_t msg_dtype, const float *H0, void *workspace, size_t ws_bytes,
-                     float *H_out, void *stream);
+int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, const kge_layer *layers,
+                     int32_t n_layers, int32_t msg_dtype, const float *H0, void *workspace,
+                     size_t ws_bytes, float *H_out, void *stream);
 
 /*
  * Encoder backward.  Must follow kge_rgcn_forward with the same arguments and the same,
@@ -165,10 +198,13 @@ int kge_rgcn_forward(const kge_partition *p, const kge_layer *layers, int32_t n_
  *   grads  : HOST array of n_layers kge_layer_grad (device pointers); every array is overwritten
  *   dH0    : device float [N][layers[0].d_in] or NULL (NULL when the layer-1 input is a fixed
  *            feature matrix and needs no gradient)
+ *   cg     : the same object (or NULL) the forward call got; dH_out must then be zero outside
+ *            the batch's vertices, as kge_distmult_score_loss writes it
  */
-int kge_rgcn_backward(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
-                      int32_t msg_dtype, const float *H0, void *workspace, size_t ws_bytes,
-                      const float *dH_out, const kge_layer_grad *grads, float *dH0, void *stream);
+int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, const kge_layer *layers,
+                      int32_t n_layers, int32_t msg_dtype, const float *H0, void *workspace,
+                      size_t ws_bytes, const float *dH_out, const kge_layer_grad *grads, float *dH0,
+                      void *stream);
 
 /*
  * Negatives for a batch of positives (Sec. 2.1, Sec. 3.3.1).  For positive q (core-edge index

@@ -19,7 +19,8 @@ _lib = None
 EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_partition_destroy", "kge_workspace_bytes", "kge_workspace_slice", "kge_rgcn_forward",
             "kge_rgcn_backward", "kge_sample_negatives", "kge_distmult_score_loss",
-            "kge_profile_enable", "kge_profile_collect", "kge_last_error"]
+            "kge_profile_enable", "kge_profile_collect", "kge_last_error", "kge_cgraph_create",
+            "kge_cgraph_destroy", "kge_compute_graph", "kge_cgraph_export"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
 MSG_F32, MSG_BF16 = 0, 1
@@ -69,10 +70,14 @@ def load():
         if not os.path.exists(LIB_PATH):
             raise ImportError("%s is missing: run `python -m paper_2201_02791_amd.build` "
                               "(there is no CPU fallback)" % LIB_PATH)
+        # torch first: its bundled HIP runtime must be the one this process initialises; loading
+        # the library before it brings in a second runtime that then finds no device
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         lib.kge_last_error.restype = C.c_char_p
         lib.kge_workspace_bytes.restype = C.c_size_t
         lib.kge_partition_destroy.restype = None
+        lib.kge_cgraph_destroy.restype = None
         _lib = lib
     return _lib
 
@@ -176,19 +181,63 @@ def workspace_bytes(part: Partition, layers: Sequence[dict], msg_dtype: int = MS
     return int(n)
 
 
+class ComputeGraph:
+    """Owner of a ``kge_cgraph*``: the flags of one batch's computational sub-graph."""
+
+    def __init__(self, part: Partition, n_layers: int):
+        out = C.c_void_p()
+        _check(load().kge_cgraph_create(part.handle, C.c_int32(n_layers), C.byref(out)))
+        self._h = C.c_void_p(out.value)
+        self.n_layers, self.n_vert = n_layers, part.n_vert
+
+    @property
+    def handle(self):
+        return self._h
+
+    def export(self):
+        """(active uint8 [n_layers][N], counts int64 [n_layers][3] = vertices, edges, runs)."""
+        active = np.zeros((self.n_layers, self.n_vert), np.uint8)
+        stats = np.zeros((self.n_layers, 3), np.int64)
+        _check(load().kge_cgraph_export(self._h, active.ctypes.data_as(C.c_void_p),
+                                        stats.ctypes.data_as(C.c_void_p)))
+        return active, stats
+
+    def destroy(self):
+        if self._h is not None and self._h.value:
+            load().kge_cgraph_destroy(self._h)
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _cg(cg) -> C.c_void_p:
+    return C.c_void_p(0) if cg is None else cg.handle
+
+
+def compute_graph(part: Partition, cg: ComputeGraph, pos_core_idx, neg_ent=None, stream=None):
+    n_neg_entries = 0 if neg_ent is None else neg_ent.numel()
+    _check(load().kge_compute_graph(part.handle, cg.handle, _ptr(pos_core_idx), C.c_int64(pos_core_idx.numel()),
+                                    _ptr(neg_ent if n_neg_entries else None), C.c_int64(n_neg_entries),
+                                    _stream(stream)))
+
+
 def rgcn_forward(part: Partition, layers: Sequence[dict], H0, workspace, H_out,
-                 msg_dtype: int = MSG_F32, stream=None):
-    _check(load().kge_rgcn_forward(part.handle, _layers(layers), C.c_int32(len(layers)), C.c_int32(msg_dtype),
+                 msg_dtype: int = MSG_F32, stream=None, cg: ComputeGraph = None):
+    _check(load().kge_rgcn_forward(part.handle, _cg(cg), _layers(layers), C.c_int32(len(layers)), C.c_int32(msg_dtype),
                                    _ptr(H0), _ptr(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
                                    _ptr(H_out), _stream(stream)))
 
 
 def rgcn_backward(part: Partition, layers: Sequence[dict], H0, workspace, dH_out, grads: Sequence[dict],
-                  dH0=None, msg_dtype: int = MSG_F32, stream=None):
+                  dH0=None, msg_dtype: int = MSG_F32, stream=None, cg: ComputeGraph = None):
     g = (_LayerGrad * len(layers))()
     for i, gr in enumerate(grads):
         g[i].dV, g[i].da, g[i].dW0 = gr["dV"].data_ptr(), gr["da"].data_ptr(), gr["dW0"].data_ptr()
-    _check(load().kge_rgcn_backward(part.handle, _layers(layers), C.c_int32(len(layers)), C.c_int32(msg_dtype),
+    _check(load().kge_rgcn_backward(part.handle, _cg(cg), _layers(layers), C.c_int32(len(layers)), C.c_int32(msg_dtype),
                                     _ptr(H0), _ptr(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
                                     _ptr(dH_out), g, _ptr(dH0), _stream(stream)))
 

@@ -189,12 +189,14 @@ extern "C" int kge_workspace_slice(const kge_partition *p, const kge_layer *laye
     return KGE_OK;
 }
 
-extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
-                                int32_t msg_dtype, const float *H0, void *workspace, size_t ws_bytes,
-                                float *H_out, void *stream)
+extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, const kge_layer *layers,
+                                int32_t n_layers, int32_t msg_dtype, const float *H0, void *workspace,
+                                size_t ws_bytes, float *H_out, void *stream)
 {
     WsLayout w;
     int rc = check_ws(p, layers, n_layers, msg_dtype, workspace, ws_bytes, &w);
+    if (rc != KGE_OK) return rc;
+    rc = kge_cgraph_check(p, cg, n_layers);
     if (rc != KGE_OK) return rc;
     KGE_REQUIRE(H0 && H_out, KGE_EINVAL, "H0 or H_out is NULL");
     KGE_REQUIRE(((uintptr_t)H0 % 16) == 0 && ((uintptr_t)H_out % 16) == 0, KGE_EINVAL, "H0 and H_out must be 16-byte aligned");
@@ -220,19 +222,22 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_layer *layers,
         }
         if (rc != KGE_OK) return rc;
         rc = launch_gather_forward(p, P, bf, L.a, L.n_bases, L.d_out, Self, L.act, Hl,
-                                   l == n_layers - 1 ? H_out : nullptr, part, st);
+                                   l == n_layers - 1 ? H_out : nullptr, part, kge_cgraph_layer(cg, l), st);
         if (rc != KGE_OK) return rc;
         Hin = Hl;
     }
     return KGE_OK;
 }
 
-extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
-                                 int32_t msg_dtype, const float *H0, void *workspace, size_t ws_bytes,
-                                 const float *dH_out, const kge_layer_grad *grads, float *dH0, void *stream)
+extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, const kge_layer *layers,
+                                 int32_t n_layers, int32_t msg_dtype, const float *H0, void *workspace,
+                                 size_t ws_bytes, const float *dH_out, const kge_layer_grad *grads, float *dH0,
+                                 void *stream)
 {
     WsLayout w;
     int rc = check_ws(p, layers, n_layers, msg_dtype, workspace, ws_bytes, &w);
+    if (rc != KGE_OK) return rc;
+    rc = kge_cgraph_check(p, cg, n_layers);
     if (rc != KGE_OK) return rc;
     KGE_REQUIRE(H0 && dH_out && grads, KGE_EINVAL, "H0, dH_out or grads is NULL");
     KGE_REQUIRE(((uintptr_t)H0 % 16) == 0 && ((uintptr_t)dH_out % 16) == 0 && ((uintptr_t)dH0 % 16) == 0,
@@ -261,10 +266,11 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_layer *layers
             if (rc != KGE_OK) return rc;
             Gl = G;
         }
-        rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, part, grads[l].da, st);
+        rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, part, grads[l].da, kge_cgraph_layer(cg, l), st);
         if (rc != KGE_OK) return rc;
         const int64_t bd = (int64_t)L.n_bases * L.d_out;
-        rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf ? bd + L.d_out : bd, bf, part, st);
+        rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf ? bd + L.d_out : bd, bf, part,
+                                     kge_cgraph_layer(cg, l), st);
         if (rc != KGE_OK) return rc;
         if (bf) {
             rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, L.n_bases, dP, st);

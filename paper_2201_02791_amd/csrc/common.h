@@ -98,11 +98,14 @@ int launch_input_grad_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out
                            const void *Wbf, float *dH, hipStream_t st);
 
 // gather.hip -------------------------------------------------------------
+// `active` (may be null = every vertex): one byte per vertex, the destinations inside the batch's
+// computational sub-graph for this layer.  Rows outside it are written as zeros (forward) and
+// edges into them are skipped (backward: their upstream gradient is zero).
 // out[i] = act( sum_{e into i} invc_e sum_b a[rel_e][b] P[src_e][b][:] + Self[i] ); out2 optional copy
 // `partial`: [hv_dm.n_units][d] floats of scratch
 int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, const float *a,
                           int32_t B, int32_t d, const float *Self, int act, float *out, float *out2,
-                          float *partial, hipStream_t st);
+                          float *partial, const uint8_t *active, hipStream_t st);
 // G = dHout * act'(Hout) (ReLU: Hout > 0)
 int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t n, float *G,
                         hipStream_t st);
@@ -111,12 +114,17 @@ int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t 
 // dP rows are `ld` elements apart (B*d, or (B+1)*d when G is appended behind them)
 int launch_gather_transpose(const kge_partition *p, const float *G, const float *a, int32_t B,
                             int32_t d, void *dP, int64_t ld, int msg_bf16, float *partial,
-                            hipStream_t st);
+                            const uint8_t *active, hipStream_t st);
 // da[r][b] = sum_{runs (r,i)} invc sum_{j in run} <P[j][b][:], G[i][:]> ; seg_scratch [S][B] floats
 // seg_scratch [S][B] floats; `partial`: [hv_seg.n_units][B] floats
 int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const float *G,
                       int32_t B, int32_t d, float *seg_scratch, float *partial, float *da,
-                      hipStream_t st);
+                      const uint8_t *active, hipStream_t st);
+
+// cgraph.hip: per-batch computational sub-graph ------------------------------
+// flag row of layer `layer` (device pointer), or null when cg is null
+const uint8_t *kge_cgraph_layer(const kge_cgraph *cg, int32_t layer);
+int kge_cgraph_check(const kge_partition *p, const kge_cgraph *cg, int32_t n_layers);
 
 // sampler_score.hip --------------------------------------------------------
 int launch_sample_negatives(const kge_partition *p, const int32_t *pos, int64_t n_pos, int32_t n_neg,

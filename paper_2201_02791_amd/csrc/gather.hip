@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
     const int32_t *__restrict__ unit_hv,
     const void *__restrict__ P, const float *__restrict__ a, int32_t B, int32_t d, int32_t gb_count,
     const float *__restrict__ Self, int act, float *__restrict__ out, float *__restrict__ out2,
-    float *__restrict__ partial)
+    float *__restrict__ partial, const uint8_t *__restrict__ active)
 {
     constexpr int VEC = MsgRow<BF16>::VEC;
     constexpr int G = 64 / LPR;
@@ -106,6 +106,17 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
     const RowWork rw = row_work(wid, dm_ptr, N, n_units, hv_row, hv_unit_ptr, unit_hv);
     if (rw.row < 0) return;                             // whole wavefront leaves together
     const int kl = lane % LPR, g = lane / LPR;
+    if (active && !active[rw.row]) {                    // outside the batch's sub-graph: a zero row
+        if (rw.unit < 0 && g == 0 && kl * VEC < d) {
+            const int64_t o = rw.row * d + kl * VEC;
+#pragma unroll
+            for (int v4 = 0; v4 < VEC; v4 += 4) {
+                *reinterpret_cast<float4 *>(out + o + v4) = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (out2) *reinterpret_cast<float4 *>(out2 + o + v4) = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+        return;
+    }
     const int GB = gb_count, GE = G / GB;
     const int gb = g % GB, ge = g / GB;
     const bool kact = kl * VEC < d;
@@ -182,7 +193,8 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
 __global__ void k_gather_fwd_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
                                     const int32_t *__restrict__ hv_unit_ptr, const float *__restrict__ partial,
                                     int32_t d, const float *__restrict__ Self, int act,
-                                    float *__restrict__ out, float *__restrict__ out2)
+                                    float *__restrict__ out, float *__restrict__ out2,
+                                    const uint8_t *__restrict__ active)
 {
     const int d4 = d >> 2;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -190,6 +202,12 @@ __global__ void k_gather_fwd_finish(int32_t n_hv, const int32_t *__restrict__ hv
     const int32_t h = (int32_t)(idx / d4);
     const int k4 = (int)(idx - (int64_t)h * d4) * 4;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (active && !active[hv_row[h]]) {
+        const int64_t oz = (int64_t)hv_row[h] * d + k4;
+        *reinterpret_cast<float4 *>(out + oz) = s;
+        if (out2) *reinterpret_cast<float4 *>(out2 + oz) = s;
+        return;
+    }
     for (int32_t u = hv_unit_ptr[h]; u < hv_unit_ptr[h + 1]; ++u) {
         const float4 x = *reinterpret_cast<const float4 *>(partial + (int64_t)u * d + k4);
         s.x += x.x; s.y += x.y; s.z += x.z; s.w += x.w;
@@ -232,7 +250,8 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
     int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
     const int32_t *__restrict__ unit_hv,
     const float *__restrict__ G, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_chunks,
-    int32_t gbt_count, void *__restrict__ dP, int64_t ld, float *__restrict__ partial)
+    int32_t gbt_count, void *__restrict__ dP, int64_t ld, float *__restrict__ partial,
+    const uint8_t *__restrict__ active)
 {
     constexpr int NG = 64 / LPR;
     const int lane = threadIdx.x & 63;
@@ -257,7 +276,10 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
         const int cnt = min(64, rw.end - e0);
         int32_t my_dst = 0, my_rel = 0;
         float my_w = 0.f;
-        if (lane < cnt) { my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc[e0 + lane]; }
+        if (lane < cnt) {
+            my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc[e0 + lane];
+            if (active && !active[my_dst]) my_dst = -1;   // destination outside the sub-graph: G row is zero
+        }
         const int rounds = (cnt + GET - 1) / GET;       // uniform trip count
         for (int r0 = 0; r0 < rounds; r0 += UE) {
             float4 gv[UE];
@@ -279,10 +301,11 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
                     rel = __shfl(my_rel, els, 64);
                     ww = __shfl(my_w, els, 64);
                 }
-                w[u] = ok ? ww : 0.f;
+                const bool live = ok && dst >= 0;
+                w[u] = live ? ww : 0.f;
                 arow[u] = a + (int64_t)rel * B;
                 gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (ok && kact) gv[u] = *reinterpret_cast<const float4 *>(G + (int64_t)dst * d + kl * 4);
+                if (live && kact) gv[u] = *reinterpret_cast<const float4 *>(G + (int64_t)dst * d + kl * 4);
             }
 #pragma unroll
             for (int u = 0; u < UE; ++u)
@@ -335,7 +358,8 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t_mfma(
     int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
     const int32_t *__restrict__ unit_hv,
     const float *__restrict__ G, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_bchunks,
-    int32_t n_cchunks, void *__restrict__ dP, int64_t ld, float *__restrict__ partial)
+    int32_t n_cchunks, void *__restrict__ dP, int64_t ld, float *__restrict__ partial,
+    const uint8_t *__restrict__ active)
 {
     constexpr int UK = 4;                                  // edge pairs in flight
     __shared__ float stage[WPB][32][36];                   // one 32x32 tile per wavefront (bf16 epilogue)
@@ -362,7 +386,10 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t_mfma(
         const int cnt = min(64, rw.end - e0);
         int32_t my_dst = 0, my_rel = 0;
         float my_w = 0.f;
-        if (lane < cnt) { my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc[e0 + lane]; }
+        if (lane < cnt) {
+            my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc[e0 + lane];
+            if (active && !active[my_dst]) my_dst = -1;   // destination outside the sub-graph: G row is zero
+        }
         for (int k0 = 0; k0 < cnt; k0 += 2 * UK) {
             float wa[UK][NBT], gb[UK][4];
 #pragma unroll
@@ -373,16 +400,17 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t_mfma(
                 const int32_t dst = __shfl(my_dst, els, 64);
                 const int32_t rel = __shfl(my_rel, els, 64);
                 const float wsh = __shfl(my_w, els, 64);       // every lane takes part: a shuffle under a
-                const float ww = ok ? wsh : 0.f;               // condition would read zeros from idle lanes
+                const bool live = ok && dst >= 0;              // condition would read zeros from idle lanes
+                const float ww = live ? wsh : 0.f;
 #pragma unroll
                 for (int t = 0; t < NBT; ++t) {
                     const int b = bbase + t * 32 + l32;
-                    wa[u][t] = (ok && b < B) ? a[(int64_t)rel * B + b] * ww : 0.f;
+                    wa[u][t] = (live && b < B) ? a[(int64_t)rel * B + b] * ww : 0.f;
                 }
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const int col = cbase + c * 32 + l32;
-                    gb[u][c] = (ok && col < d) ? G[(int64_t)dst * d + col] : 0.f;
+                    gb[u][c] = (live && col < d) ? G[(int64_t)dst * d + col] : 0.f;
                 }
             }
 #pragma unroll
@@ -472,7 +500,7 @@ __global__ __launch_bounds__(64 * WPB) void k_coeff_seg(
     int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
     const int32_t *__restrict__ unit_hv,
     const void *__restrict__ P, const float *__restrict__ G, int32_t B, int32_t d, int32_t gb_count,
-    float *__restrict__ seg_out, float *__restrict__ partial)
+    float *__restrict__ seg_out, float *__restrict__ partial, const uint8_t *__restrict__ active)
 {
     constexpr int VEC = MsgRow<BF16>::VEC;
     constexpr int NG = 64 / LPR;
@@ -480,6 +508,11 @@ __global__ __launch_bounds__(64 * WPB) void k_coeff_seg(
     const int64_t wid = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
     const RowWork rw = row_work(wid, seg_ptr, S, n_units, hv_row, hv_unit_ptr, unit_hv);
     if (rw.row < 0) return;
+    if (active && !active[seg_dst[rw.row]]) {           // destination outside the sub-graph: G row is zero
+        if (rw.unit < 0)
+            for (int b = lane; b < B; b += 64) seg_out[rw.row * B + b] = 0.f;
+        return;
+    }
     const int kl = lane % LPR, g = lane / LPR;
     const int GB = gb_count, GE = NG / GB;
     const int gb = g % GB, ge = g / GB;
@@ -551,15 +584,17 @@ __global__ __launch_bounds__(64 * WPB) void k_coeff_seg(
 // Long runs: seg_out[s][b] = invc_s * sum of the run's unit partials.
 __global__ void k_coeff_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
                                const int32_t *__restrict__ hv_unit_ptr, const float *__restrict__ partial,
-                               const float *__restrict__ inv_c, int32_t B, float *__restrict__ seg_out)
+                               const float *__restrict__ inv_c, int32_t B, float *__restrict__ seg_out,
+                               const int32_t *__restrict__ seg_dst, const uint8_t *__restrict__ active)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (int64_t)n_hv * B) return;
     const int32_t h = (int32_t)(idx / B);
     const int b = (int)(idx - (int64_t)h * B);
+    const int64_t row = hv_row[h];
+    if (active && !active[seg_dst[row]]) { seg_out[row * B + b] = 0.f; return; }
     float s = 0.f;
     for (int32_t u = hv_unit_ptr[h]; u < hv_unit_ptr[h + 1]; ++u) s += partial[(int64_t)u * B + b];
-    const int64_t row = hv_row[h];
     seg_out[row * B + b] = inv_c[row] * s;
 }
 
@@ -606,7 +641,7 @@ int largest_pow2_dividing(int x, int cap) { int p = 1; while (p * 2 <= cap && x 
 
 int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, const float *a,
                           int32_t B, int32_t d, const float *Self, int act, float *out, float *out2,
-                          float *partial, hipStream_t st)
+                          float *partial, const uint8_t *active, hipStream_t st)
 {
     const int64_t N = p->n_vert;
     if (N == 0) return KGE_OK;
@@ -619,7 +654,7 @@ int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, c
     {
         KGE_PROF("gather_fwd", st);
 #define GF_ARGS p->dm_ptr, p->dm_src, p->dm_rel, p->dm_invc, N, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, \
-                P, a, B, d, gbc, Self, act, out, out2, partial
+                P, a, B, d, gbc, Self, act, out, out2, partial, active
         if (msg_bf16) { DISPATCH_LPR(lpr, (k_gather_fwd<true, L><<<grid, 64 * WPB, 0, st>>>(GF_ARGS))); }
         else { DISPATCH_LPR(lpr, (k_gather_fwd<false, L><<<grid, 64 * WPB, 0, st>>>(GF_ARGS))); }
 #undef GF_ARGS
@@ -629,7 +664,7 @@ int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, c
         KGE_PROF("gather_fwd_fin", st);
         const int64_t n = (int64_t)hx.n_hv * (d / 4);
         k_gather_fwd_finish<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, d,
-                                                                   Self, act, out, out2);
+                                                                   Self, act, out, out2, active);
         KGE_LAUNCH_CHECK();
     }
     return KGE_OK;
@@ -651,7 +686,7 @@ int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t 
 
 template <bool BF16, int LPR>
 static int launch_gather_t_nb(const kge_partition *p, const float *G, const float *a, int32_t B, int32_t d,
-                              void *dP, int64_t ld, float *partial, hipStream_t st)
+                              void *dP, int64_t ld, float *partial, const uint8_t *active, hipStream_t st)
 {
     constexpr int NG = 64 / LPR;
     const int64_t N = p->n_vert;
@@ -668,7 +703,7 @@ static int launch_gather_t_nb(const kge_partition *p, const float *G, const floa
         KGE_REQUIRE(cdiv(waves, WPB) < 0x7fffffffLL, KGE_ERANGE, "grid too large");                   \
         k_gather_t<BF16, LPR, NBV, UEV><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(              \
             p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, N, hx.n_units, hx.hv_row, hx.hv_unit_ptr,    \
-            hx.unit_hv, G, a, B, d, n_chunks, gbt, dP, ld, partial);                                  \
+            hx.unit_hv, G, a, B, d, n_chunks, gbt, dP, ld, partial, active);                                  \
     }
     if (B >= 16) GT_CALL(16, 2)
     else if (B >= 8) GT_CALL(8, 4)
@@ -681,7 +716,8 @@ static int launch_gather_t_nb(const kge_partition *p, const float *G, const floa
 }
 
 int launch_gather_transpose(const kge_partition *p, const float *G, const float *a, int32_t B, int32_t d,
-                            void *dP, int64_t ld, int msg_bf16, float *partial, hipStream_t st)
+                            void *dP, int64_t ld, int msg_bf16, float *partial, const uint8_t *active,
+                            hipStream_t st)
 {
     if (p->n_vert == 0) return KGE_OK;
     const int lpr = pow2_at_least((d + 3) / 4);
@@ -695,13 +731,13 @@ int launch_gather_transpose(const kge_partition *p, const float *G, const float 
         KGE_REQUIRE(cdiv(waves, WPB) < 0x7fffffffLL, KGE_ERANGE, "grid too large");
         KGE_PROF("gather_t", st);
 #define GTM_ARGS p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, p->n_vert, hxm.n_units, hxm.hv_row, hxm.hv_unit_ptr, \
-                 hxm.unit_hv, G, a, B, d, n_bchunks, n_cchunks, dP, ld, partial
+                 hxm.unit_hv, G, a, B, d, n_bchunks, n_cchunks, dP, ld, partial, active
         if (msg_bf16) k_gather_t_mfma<true, 1><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(GTM_ARGS);
         else k_gather_t_mfma<false, 1><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(GTM_ARGS);
 #undef GTM_ARGS
         KGE_LAUNCH_CHECK();
-    } else if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(p, G, a, B, d, dP, ld, partial, st))); }
-    else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, L>(p, G, a, B, d, dP, ld, partial, st))); }
+    } else if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(p, G, a, B, d, dP, ld, partial, active, st))); }
+    else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, L>(p, G, a, B, d, dP, ld, partial, active, st))); }
     if (rc != KGE_OK) return rc;
     const kge_heavy_index &hx = p->hv_sm;
     if (hx.n_hv > 0) {
@@ -717,14 +753,14 @@ int launch_gather_transpose(const kge_partition *p, const float *G, const float 
 
 template <bool BF16, int LPR>
 static int launch_coeff_seg(const kge_partition *p, const void *P, const float *G, int32_t B, int32_t d,
-                            int gbc, float *seg_scratch, float *partial, hipStream_t st)
+                            int gbc, float *seg_scratch, float *partial, const uint8_t *active, hipStream_t st)
 {
     const int64_t S = p->n_seg;
     const kge_heavy_index &hx = p->hv_seg;
     const unsigned grid = (unsigned)cdiv(S + hx.n_units, WPB);
     const int nb = (B + gbc - 1) / gbc;
 #define CS_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, \
-                P, G, B, d, gbc, seg_scratch, partial
+                P, G, B, d, gbc, seg_scratch, partial, active
     if (nb >= 4) k_coeff_seg<BF16, LPR, 4, 2><<<grid, 64 * WPB, 0, st>>>(CS_ARGS);
     else if (nb >= 2) k_coeff_seg<BF16, LPR, 2, 4><<<grid, 64 * WPB, 0, st>>>(CS_ARGS);
     else k_coeff_seg<BF16, LPR, 1, 8><<<grid, 64 * WPB, 0, st>>>(CS_ARGS);
@@ -734,7 +770,8 @@ static int launch_coeff_seg(const kge_partition *p, const void *P, const float *
 }
 
 int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const float *G, int32_t B,
-                      int32_t d, float *seg_scratch, float *partial, float *da, hipStream_t st)
+                      int32_t d, float *seg_scratch, float *partial, float *da, const uint8_t *active,
+                      hipStream_t st)
 {
     const int64_t S = p->n_seg;
     const int32_t R2 = 2 * p->n_relations;
@@ -748,15 +785,15 @@ int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const
     const int gbc = largest_pow2_dividing(B, 64 / lpr);
     {
         KGE_PROF("coeff_seg", st);
-        if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_coeff_seg<true, L>(p, P, G, B, d, gbc, seg_scratch, partial, st))); }
-        else { DISPATCH_LPR(lpr, (rc = launch_coeff_seg<false, L>(p, P, G, B, d, gbc, seg_scratch, partial, st))); }
+        if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_coeff_seg<true, L>(p, P, G, B, d, gbc, seg_scratch, partial, active, st))); }
+        else { DISPATCH_LPR(lpr, (rc = launch_coeff_seg<false, L>(p, P, G, B, d, gbc, seg_scratch, partial, active, st))); }
     }
     if (rc != KGE_OK) return rc;
     const kge_heavy_index &hx = p->hv_seg;
     if (hx.n_hv > 0) {
         KGE_PROF("coeff_fin", st);
         const int64_t n = (int64_t)hx.n_hv * B;
-        k_coeff_finish<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, p->inv_c, B, seg_scratch);
+        k_coeff_finish<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, p->inv_c, B, seg_scratch, p->seg_dst, active);
         KGE_LAUNCH_CHECK();
     }
     const int BP = pow2_at_least(B);

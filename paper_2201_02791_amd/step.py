@@ -1,8 +1,8 @@
 """One training step of Algorithm 1 on one partition: buffer ownership and call order.
 
 Holds the torch tensors (device memory only) and issues the library calls in order on one
-stream: encoder forward -> negatives -> score/loss -> encoder backward.  No arithmetic of
-the method happens in Python or torch.
+stream: negatives -> [computational sub-graph of the batch] -> encoder forward -> score/loss ->
+encoder backward.  No arithmetic of the method happens in Python or torch.
 """
 from __future__ import annotations
 
@@ -16,7 +16,7 @@ from . import binding as kb
 class TrainStep:
     def __init__(self, part: kb.Partition, params: Dict[str, object], acts: Sequence[int],
                  msg_dtype: int = kb.MSG_F32, need_dH0: bool = True, device: str = "cuda:0",
-                 keep_scores: bool = True):
+                 keep_scores: bool = True, cone: bool = False):
         import torch
         self.torch = torch
         self.part = part
@@ -42,6 +42,8 @@ class TrainStep:
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
         assert self.workspace.data_ptr() % 256 == 0
         self.keep_scores = keep_scores
+        # cone: propagate only the batch's computational sub-graph (Algorithm 1, getComputeGraph)
+        self.cg = kb.ComputeGraph(part, len(self.layers)) if cone else None
         self.pos = None
         self.neg_ent = self.neg_side = self.scores = None
         self.n_neg = 0
@@ -66,8 +68,13 @@ class TrainStep:
         return t.view(self.part.n_vert, -1)
 
     # --- the four per-step calls, in Algorithm 1's order
+    def compute_graph(self, stream=None):
+        if self.cg is not None:
+            kb.compute_graph(self.part, self.cg, self.pos, self.neg_ent if self.n_neg > 0 else None, stream)
+
     def forward(self, stream=None):
-        kb.rgcn_forward(self.part, self.layers, self.H0, self.workspace, self.H_out, self.msg_dtype, stream)
+        kb.rgcn_forward(self.part, self.layers, self.H0, self.workspace, self.H_out, self.msg_dtype, stream,
+                        self.cg)
 
     def sample(self, mode: int, seed: int, step: int, stream=None):
         kb.sample_negatives(self.part, self.pos, self.n_neg, mode, seed, step, self.neg_ent, self.neg_side, stream)
@@ -78,10 +85,11 @@ class TrainStep:
 
     def backward(self, stream=None):
         kb.rgcn_backward(self.part, self.layers, self.H0, self.workspace, self.dH_out, self.grads,
-                         self.dH0, self.msg_dtype, stream)
+                         self.dH0, self.msg_dtype, stream, self.cg)
 
     def run(self, mode: int, seed: int, step: int, stream=None):
-        self.forward(stream)
         self.sample(mode, seed, step, stream)
+        self.compute_graph(stream)
+        self.forward(stream)
         self.score_loss(stream)
         self.backward(stream)

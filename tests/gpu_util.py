@@ -21,7 +21,7 @@ def layers_of(params, acts):
             for l in range(len(acts))]
 
 
-def gpu_step(spec, head, rel, tail, params=None, pos=None, need_dH0=True):
+def gpu_step(spec, head, rel, tail, params=None, pos=None, need_dH0=True, cone=False):
     """Build the partition and run one step on the GPU. Returns (part, step object, params, pos)."""
     from paper_2201_02791_amd import binding as kb
     from paper_2201_02791_amd.step import TrainStep
@@ -33,7 +33,7 @@ def gpu_step(spec, head, rel, tail, params=None, pos=None, need_dH0=True):
     if pos is None:
         pos = synth.make_batch(spec, part.n_core)
     msg = kb.MSG_BF16 if spec.msg_dtype == "bf16" else kb.MSG_F32
-    ts = TrainStep(part, params, spec.acts, msg, need_dH0=need_dH0)
+    ts = TrainStep(part, params, spec.acts, msg, need_dH0=need_dH0, cone=cone)
     ts.set_batch(pos, spec.n_neg)
     ts.run(spec.neg_mode, SEED, STEP)
     torch.cuda.synchronize()
@@ -67,13 +67,23 @@ def assert_partition_equal(gpart, opart):
             np.testing.assert_array_equal(got, want, err_msg=name)
 
 
-def assert_step_close(ts, res, tol_val, tol_grad, need_dH0=True):
-    """Compare every output of a GPU step with the oracle's."""
+def assert_step_close(ts, res, tol_val, tol_grad, need_dH0=True, batch_rows=None):
+    """Compare every output of a GPU step with the oracle's.  batch_rows: the step propagated only
+    the batch's computational sub-graph, so H_out is compared on these rows and must be exactly
+    zero on all others."""
     c = lambda t: t.detach().cpu().numpy()
     errs = {}
     np.testing.assert_array_equal(c(ts.neg_ent)[:, :ts.n_neg], res["neg_ent"])
     np.testing.assert_array_equal(c(ts.neg_side)[:, :ts.n_neg], res["neg_side"])
-    errs["H_out"] = (rel_err(c(ts.H_out), res["Hs"][-1]), tol_val)
+    if batch_rows is None:
+        errs["H_out"] = (rel_err(c(ts.H_out), res["Hs"][-1]), tol_val)
+    else:
+        rows = np.unique(batch_rows)
+        h = c(ts.H_out)
+        scale = max(np.abs(res["Hs"][-1]).max(), 1e-30)
+        errs["H_out"] = (float(np.abs(h[rows] - res["Hs"][-1][rows]).max() / scale) if len(rows) else 0.0, tol_val)
+        mask = np.ones(h.shape[0], bool); mask[rows] = False
+        assert not h[mask].any(), "rows outside the batch must be zero"
     errs["scores"] = (rel_err(c(ts.scores), res["scores"]), tol_val)
     errs["loss"] = (abs(float(c(ts.loss)[0]) - res["loss"]) / abs(res["loss"]), tol_val)
     errs["dH_out"] = (rel_err(c(ts.dH_out), res["dH_out"]), tol_grad)
