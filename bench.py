@@ -25,12 +25,24 @@ PEAK_F32_MFMA_TFLOPS = 157.3
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 
 
-def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg):
+def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None):
     """Algorithmic bytes / flops of ONE launch of a kernel (what the method itself must move
-    or compute in this formulation).  Returns (bound, work, unit_is_bytes)."""
+    or compute in this formulation).  Returns (bound, work).  cone: None, or the per-layer counts
+    (active vertices, edges into them, runs into them) of the batch's computational sub-graph;
+    the figure is then the mean over the layers' launches."""
     N, E, S = part.n_vert, part.n_edge, part.n_seg
     R2 = 2 * part.n_relations
     gemm_flops = 2.0 * N * d * (B + 1) * d
+    if cone is not None and name in ("gather_fwd", "coeff_seg", "gather_t"):
+        tot = 0.0
+        for nv, ne, ns in cone:
+            if name == "gather_fwd":   # inactive rows: flag + ptr read, zero row written
+                tot += ne * (B * d * ep + 12.0) + N * (5.0 + 4.0 * d) + nv * 4.0 * d + R2 * B * 4.0
+            elif name == "coeff_seg":  # inactive runs: dst + flag read, B zeros written
+                tot += ne * (B * d * ep + 4.0) + ns * (8.0 + 4.0 * d) + S * (5.0 + 4.0 * B)
+            else:                      # every edge's metadata and flag, G rows of active destinations only
+                tot += ne * 4.0 * d + E * 13.0 + N * (4.0 + B * d * ep) + R2 * B * 4.0
+        return "hbm", tot / len(cone)
     if name == "gather_fwd":   # per edge: P row + (src, rel, 1/c); per vertex: ptr + Self read + output write
         return "hbm", E * (B * d * ep + 12.0) + N * (4.0 + 8.0 * d) + R2 * B * 4.0
     if name == "coeff_seg":    # per edge: P row + src; per run: ptr/dst/1/c + G row + B outputs
@@ -100,6 +112,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="index into the workload list (0..4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--whole-partition", action="store_true",
+                    help="propagate every vertex of the partition instead of the batch's computational sub-graph")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -129,7 +143,8 @@ def main():
     params = synth.make_params(spec, part.n_vert)
     pos = synth.make_batch(spec, part.n_core)
     msg = kb.MSG_BF16 if spec.msg_dtype == "bf16" else kb.MSG_F32
-    ts = TrainStep(part, params, spec.acts, msg, need_dH0=not spec.fixed_features, keep_scores=True)
+    ts = TrainStep(part, params, spec.acts, msg, need_dH0=not spec.fixed_features, keep_scores=True,
+                   cone=not args.whole_partition)
     ts.set_batch(pos, spec.n_neg)
     log("workspace %.2f GB" % (ts.ws_bytes / 1e9))
 
@@ -152,6 +167,10 @@ def main():
     kb.profile_enable(False)
     prof = kb.profile_collect()
     loss = float(ts.loss.cpu()[0])
+    cone = None
+    if ts.cg is not None:
+        cone = [tuple(int(x) for x in row) for row in ts.cg.export()[1]]
+        log("computational sub-graph (vertices, edges, runs) per layer:", cone)
 
     ms_per_step = 1e3 * dt / args.steps
     E = part.n_edge
@@ -160,7 +179,7 @@ def main():
     ep = 2 if spec.msg_dtype == "bf16" else 4
     kernels = {}
     for name, (tot_ms, calls) in prof.items():
-        bound, work = kernel_work(name, part, spec, spec.d, spec.n_bases, ep, n_pos, n_neg)
+        bound, work = kernel_work(name, part, spec, spec.d, spec.n_bases, ep, n_pos, n_neg, cone)
         avg_ms = tot_ms / max(calls, 1)
         if bound == "hbm":
             ach, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
@@ -195,7 +214,9 @@ def main():
            "config": {"workload": "configs[%d] %s" % (args.config, spec.name), "n_vertices": part.n_vert,
                       "message_edges": E, "runs": part.n_seg, "d": spec.d, "bases": spec.n_bases,
                       "relations_with_inverses": 2 * spec.n_relations, "layers": spec.n_layers,
-                      "positives": n_pos, "negatives_per_positive": n_neg, "parallelism": "1 partition on 1 GPU"},
+                      "positives": n_pos, "negatives_per_positive": n_neg, "parallelism": "1 partition on 1 GPU",
+                      "propagation": "whole partition" if cone is None else "batch computational sub-graph",
+                      "subgraph_vertices_edges_runs_per_layer": cone},
            "triples_per_s": T / (dt / args.steps), "loss": loss,
            "roofline": roof, "cpu_baseline": base, "kernels": kernels}
     print(json.dumps(out))
