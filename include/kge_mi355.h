@@ -54,6 +54,13 @@ enum { KGE_ACT_IDENTITY = 0, KGE_ACT_RELU = 1 };
 enum { KGE_MSG_F32 = 0, KGE_MSG_BF16 = 1 };      /* storage type of projected messages        */
 enum { KGE_NEG_TAIL = 0, KGE_NEG_HEAD_OR_TAIL = 1 };
 enum { KGE_DOMAIN_CORE = 0, KGE_DOMAIN_ALL = 1 };
+/* Order in which a layer applies Eq. 1-2 (the results are the same up to rounding):
+ *   KGE_ORDER_PROJECT_FIRST    P[j][b] = h_j V_b for every vertex, then the neighbour sum over
+ *                              projected messages: (B+1) d_out values move per edge.
+ *   KGE_ORDER_AGGREGATE_FIRST  z_{i,r} = (1/c_ir) sum_{j in N_i^r} h_j per (relation,
+ *                              destination) run, y_{i,b} = sum_r a_rb z_{i,r}, then
+ *                              pre_i = sum_b y_{i,b} V_b + h_i W_0: d_in values move per edge. */
+enum { KGE_ORDER_PROJECT_FIRST = 0, KGE_ORDER_AGGREGATE_FIRST = 1 };
 
 typedef struct kge_partition kge_partition;      /* opaque; device resident; library owned    */
 typedef struct kge_cgraph kge_cgraph;            /* opaque; one batch's computational sub-graph */
@@ -73,6 +80,7 @@ typedef struct kge_part_info {
 /* One RGCN layer (Eq. 1-2).  Device pointers, caller owned, never written. */
 typedef struct kge_layer {
     int32_t d_in, d_out, n_bases, act;   /* act: KGE_ACT_*                                     */
+    int32_t order;     /* KGE_ORDER_*                                                           */
     const float *V;    /* [n_bases][d_in][d_out]   basis matrices V_b                          */
     const float *a;    /* [2R][n_bases]            coefficients a_rb                           */
     const float *W0;   /* [d_in][d_out]            self-loop weight                            */
@@ -107,7 +115,10 @@ typedef enum kge_array {
     KGE_ARR_SM_DST = 17,   /* int32 [E]    destination, ordered by (src, rel, dst, id)         */
     KGE_ARR_SM_REL = 18,   /* int32 [E]                                                        */
     KGE_ARR_SM_INVC = 19,  /* float [E]                                                        */
-    KGE_ARR_REL_PTR = 20   /* int32 [2R+1] run range of each relation                          */
+    KGE_ARR_REL_PTR = 20,  /* int32 [2R+1] run range of each relation                          */
+    KGE_ARR_DR_PTR = 21,   /* int32 [N+1]  runs grouped by destination: run range per vertex   */
+    KGE_ARR_DR_SEG = 22,   /* int32 [S]    run id, ordered by (dst, rel)                       */
+    KGE_ARR_DR_REL = 23    /* int32 [S]    relation of that run                                */
 } kge_array;
 
 /*
@@ -270,8 +281,13 @@ int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_ent
  *               ld = B*d_out (fp32 messages) or (B+1)*d_out (bf16 messages: G, rounded to
  *               bf16, is appended behind the B blocks)
  *   KGE_WS_DH   gradient with respect to layer l's INPUT, l >= 1, [N][d_in] float (after backward)
+ *   KGE_WS_Z    aggregate-first layer l: run means z [S][d_in] float, one row per (relation,
+ *               destination) run in the partition's run order (valid after forward)
+ *   KGE_WS_Y    aggregate-first layer l: y [N][B*d_in] float of the last such layer forward has
+ *               processed (the buffer is shared between layers)
+ * KGE_WS_P exists only for project-first layers, KGE_WS_Z / KGE_WS_Y only for aggregate-first ones.
  */
-enum { KGE_WS_P = 0, KGE_WS_H = 1, KGE_WS_G = 2, KGE_WS_DP = 3, KGE_WS_DH = 4 };
+enum { KGE_WS_P = 0, KGE_WS_H = 1, KGE_WS_G = 2, KGE_WS_DP = 3, KGE_WS_DH = 4, KGE_WS_Z = 5, KGE_WS_Y = 6 };
 int kge_workspace_slice(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
                         int32_t msg_dtype, int32_t which, int32_t layer, size_t *offset,
                         size_t *bytes);

@@ -23,6 +23,7 @@ EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_cgraph_destroy", "kge_compute_graph", "kge_cgraph_export"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
+ORDER_PROJECT_FIRST, ORDER_AGGREGATE_FIRST = 0, 1
 MSG_F32, MSG_BF16 = 0, 1
 NEG_TAIL, NEG_HEAD_OR_TAIL = 0, 1
 DOMAIN_CORE, DOMAIN_ALL = 0, 1
@@ -33,7 +34,8 @@ ARRAYS = {"vert_gid": (0, np.int32), "core_eid": (1, np.int32), "core_h": (2, np
           "col_src": (9, np.int32), "edge_id": (10, np.int32), "cand": (11, np.int32),
           "dm_ptr": (12, np.int32), "dm_src": (13, np.int32), "dm_rel": (14, np.int32),
           "dm_invc": (15, np.float32), "sm_ptr": (16, np.int32), "sm_dst": (17, np.int32),
-          "sm_rel": (18, np.int32), "sm_invc": (19, np.float32), "rel_ptr": (20, np.int32)}
+          "sm_rel": (18, np.int32), "sm_invc": (19, np.float32), "rel_ptr": (20, np.int32),
+          "dr_ptr": (21, np.int32), "dr_seg": (22, np.int32), "dr_rel": (23, np.int32)}
 
 
 class KgeError(RuntimeError):
@@ -52,7 +54,7 @@ class _PartInfo(C.Structure):
 
 class _Layer(C.Structure):
     _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("n_bases", C.c_int32), ("act", C.c_int32),
-                ("V", C.c_void_p), ("a", C.c_void_p), ("W0", C.c_void_p)]
+                ("order", C.c_int32), ("V", C.c_void_p), ("a", C.c_void_p), ("W0", C.c_void_p)]
 
 
 class _LayerGrad(C.Structure):
@@ -153,7 +155,8 @@ def partition_export(part: Partition, name: str) -> np.ndarray:
          "inv_c": part.n_seg, "col_src": part.n_edge, "edge_id": part.n_edge, "cand": part.n_cand,
          "dm_ptr": part.n_vert + 1, "dm_src": part.n_edge, "dm_rel": part.n_edge, "dm_invc": part.n_edge,
          "sm_ptr": part.n_vert + 1, "sm_dst": part.n_edge, "sm_rel": part.n_edge, "sm_invc": part.n_edge,
-         "rel_ptr": 2 * part.n_relations + 1}[name]
+         "rel_ptr": 2 * part.n_relations + 1, "dr_ptr": part.n_vert + 1, "dr_seg": part.n_seg,
+         "dr_rel": part.n_seg}[name]
     arr = np.empty(n, dt)
     _check(load().kge_partition_export(part.handle, C.c_int32(which), arr.ctypes.data_as(C.c_void_p),
                                        C.c_int64(arr.nbytes)))
@@ -170,6 +173,7 @@ def _layers(layers: Sequence[dict]):
         V, a, W0 = l["V"], l["a"], l["W0"]
         arr[i].n_bases, arr[i].d_in, arr[i].d_out = V.shape
         arr[i].act = int(l["act"])
+        arr[i].order = int(l.get("order", ORDER_PROJECT_FIRST))
         arr[i].V, arr[i].a, arr[i].W0 = V.data_ptr(), a.data_ptr(), W0.data_ptr()
     return arr
 
@@ -269,7 +273,7 @@ def profile_collect() -> dict:
     return {arr[i].name.decode(): (float(arr[i].total_ms), int(arr[i].calls)) for i in range(n.value)}
 
 
-WS_P, WS_H, WS_G, WS_DP, WS_DH = 0, 1, 2, 3, 4
+WS_P, WS_H, WS_G, WS_DP, WS_DH, WS_Z, WS_Y = 0, 1, 2, 3, 4, 5, 6
 
 
 def workspace_slice(part: Partition, layers: Sequence[dict], which: int, layer: int,

@@ -72,6 +72,8 @@ namespace {
 struct WsLayout {
     std::vector<size_t> off_P, off_H;   // per layer: projected messages, layer output
     std::vector<size_t> off_Hbf, off_Wbf, off_WbfT;   // bf16 workloads: bf16 copies of layer input and weights
+    std::vector<size_t> off_Z;          // aggregate-first layers: run means [S][d_in]
+    size_t off_Y = 0, off_C = 0;        // aggregate-first layers: Y [N][B*d_in], C [2R][d_in*d_out] (shared)
     size_t off_self = 0, off_G = 0, off_dP = 0, off_dHa = 0, off_dHb = 0, off_seg = 0, off_part = 0, total = 0;
 };
 
@@ -92,6 +94,10 @@ int check_layers(const kge_partition *p, const kge_layer *layers, int32_t n_laye
         KGE_REQUIRE(L.d_out <= dmax && L.d_in <= 512, KGE_EINVAL,
                     "layer %d: d_out must be at most %d and d_in at most 512", l, dmax);
         KGE_REQUIRE(L.act == KGE_ACT_IDENTITY || L.act == KGE_ACT_RELU, KGE_EINVAL, "layer %d: bad act", l);
+        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.order == KGE_ORDER_AGGREGATE_FIRST, KGE_EINVAL,
+                    "layer %d: bad order", l);
+        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || (msg_dtype == KGE_MSG_F32 && L.d_in <= 256), KGE_EINVAL,
+                    "layer %d: the aggregate-first order needs fp32 messages and d_in <= 256", l);
         KGE_REQUIRE(l == 0 || L.d_in == layers[l - 1].d_out, KGE_EINVAL,
                     "layer %d: d_in does not match the previous layer's d_out", l);
         KGE_REQUIRE(((uintptr_t)L.V % 16) == 0 && ((uintptr_t)L.W0 % 16) == 0, KGE_EINVAL,
@@ -106,11 +112,22 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
     size_t cur = 0, max_dout = 0, max_din = 0, max_bd = 0, max_B = 0;
     const bool bf = msg_dtype == KGE_MSG_BF16;
     size_t max_nc = 0;
-    w->off_P.resize(n_layers); w->off_H.resize(n_layers);
+    w->off_P.assign(n_layers, 0); w->off_H.resize(n_layers); w->off_Z.assign(n_layers, 0);
+    size_t max_y = 0, max_c = 0, max_zd = 0;
     w->off_Hbf.assign(n_layers, 0); w->off_Wbf.assign(n_layers, 0); w->off_WbfT.assign(n_layers, 0);
     for (int l = 0; l < n_layers; ++l) {
         const kge_layer &L = layers[l];
-        w->off_P[l] = cur; cur = align_up(cur + N * L.n_bases * L.d_out * ep, 256);
+        const bool agg = L.order == KGE_ORDER_AGGREGATE_FIRST;
+        if (agg) {
+            w->off_Z[l] = cur; cur = align_up(cur + (size_t)p->n_seg * L.d_in * 4, 256);
+            if (N * L.n_bases * L.d_in * 4 > max_y) max_y = N * L.n_bases * L.d_in * 4;
+            const size_t cb = (size_t)2 * p->n_relations * L.d_in * L.d_out * 4;
+            if (cb > max_c) max_c = cb;
+            if ((size_t)L.d_in > max_zd) max_zd = L.d_in;
+            if ((size_t)L.n_bases * L.d_in > max_bd) max_bd = (size_t)L.n_bases * L.d_in;   // partials of Y
+        } else {
+            w->off_P[l] = cur; cur = align_up(cur + N * L.n_bases * L.d_out * ep, 256);
+        }
         w->off_H[l] = cur; cur = align_up(cur + N * L.d_out * 4, 256);
         if ((size_t)L.d_out > max_dout) max_dout = L.d_out;
         if ((size_t)L.d_in > max_din) max_din = L.d_in;
@@ -124,6 +141,8 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
             w->off_WbfT[l] = cur; cur = align_up(cur + nc * L.d_in * 2, 256);
         }
     }
+    w->off_Y = cur; cur = align_up(cur + max_y, 256);
+    w->off_C = cur; cur = align_up(cur + max_c, 256);
     w->off_self = cur; cur = align_up(cur + N * max_dout * 4, 256);
     w->off_G = cur; cur = align_up(cur + N * max_dout * 4, 256);
     // dP; bf16 workloads append G behind it so that X = [dP | G] is one bf16 matrix
@@ -135,6 +154,8 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
     size_t part = (size_t)p->hv_dm.n_units * max_dout;
     if ((size_t)p->hv_sm.n_units * max_bd > part) part = (size_t)p->hv_sm.n_units * max_bd;
     if ((size_t)p->hv_seg.n_units * max_B > part) part = (size_t)p->hv_seg.n_units * max_B;
+    if ((size_t)p->hv_seg.n_units * max_zd > part) part = (size_t)p->hv_seg.n_units * max_zd;
+    if (max_y > 0 && (size_t)p->hv_dr.n_units * max_bd > part) part = (size_t)p->hv_dr.n_units * max_bd;
     w->off_part = cur; cur = align_up(cur + part * 4, 256);
     w->total = cur > 0 ? cur : 256;
 }
@@ -174,7 +195,15 @@ extern "C" int kge_workspace_slice(const kge_partition *p, const kge_layer *laye
     const size_t N = (size_t)p->n_vert, ep = msg_dtype == KGE_MSG_BF16 ? 2 : 4;
     const kge_layer &L = layers[layer];
     switch (which) {
-    case KGE_WS_P: *offset = w.off_P[layer]; *bytes = N * L.n_bases * L.d_out * ep; break;
+    case KGE_WS_P:
+        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST, KGE_EINVAL, "an aggregate-first layer keeps no projected messages");
+        *offset = w.off_P[layer]; *bytes = N * L.n_bases * L.d_out * ep; break;
+    case KGE_WS_Z:
+        KGE_REQUIRE(L.order == KGE_ORDER_AGGREGATE_FIRST, KGE_EINVAL, "only aggregate-first layers keep run means");
+        *offset = w.off_Z[layer]; *bytes = (size_t)p->n_seg * L.d_in * 4; break;
+    case KGE_WS_Y:
+        KGE_REQUIRE(L.order == KGE_ORDER_AGGREGATE_FIRST, KGE_EINVAL, "only aggregate-first layers have Y");
+        *offset = w.off_Y; *bytes = N * L.n_bases * L.d_in * 4; break;
     case KGE_WS_H: *offset = w.off_H[layer]; *bytes = N * L.d_out * 4; break;
     case KGE_WS_G: *offset = w.off_G; *bytes = N * L.d_out * 4; break;
     case KGE_WS_DP:
@@ -210,6 +239,20 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
         const kge_layer &L = layers[l];
         void *P = ws + w.off_P[l];
         float *Hl = (float *)(ws + w.off_H[l]);
+        if (L.order == KGE_ORDER_AGGREGATE_FIRST) {
+            float *Z = (float *)(ws + w.off_Z[l]);
+            float *Y = (float *)(ws + w.off_Y);
+            const uint8_t *act_l = kge_cgraph_layer(cg, l);
+            rc = launch_run_mean(p, Hin, L.d_in, Z, part, act_l, st);
+            if (rc != KGE_OK) return rc;
+            rc = launch_aggregate_runs(p, Z, L.a, L.n_bases, L.d_in, Y, (int64_t)L.n_bases * L.d_in, 0, part, act_l, st);
+            if (rc != KGE_OK) return rc;
+            rc = launch_combine(Y, Hin, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, L.act, act_l, Hl,
+                                l == n_layers - 1 ? H_out : nullptr, st);
+            if (rc != KGE_OK) return rc;
+            Hin = Hl;
+            continue;
+        }
         if (bf) {
             void *Hbf = ws + w.off_Hbf[l], *Wbf = ws + w.off_Wbf[l], *WbfT = ws + w.off_WbfT[l];
             rc = launch_cvt_rows_bf16(Hin, p->n_vert * (int64_t)L.d_in, Hbf, st);
@@ -266,7 +309,11 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
             if (rc != KGE_OK) return rc;
             Gl = G;
         }
-        rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, part, grads[l].da, kge_cgraph_layer(cg, l), st);
+        if (L.order == KGE_ORDER_AGGREGATE_FIRST)
+            rc = launch_coeff_grad_runs(p, (const float *)(ws + w.off_Z[l]), Gl, L.d_in, L.d_out, L.n_bases, L.V,
+                                        (float *)(ws + w.off_C), grads[l].da, st);
+        else
+            rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, part, grads[l].da, kge_cgraph_layer(cg, l), st);
         if (rc != KGE_OK) return rc;
         const int64_t bd = (int64_t)L.n_bases * L.d_out;
         rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf ? bd + L.d_out : bd, bf, part,

@@ -57,7 +57,14 @@ struct kge_partition {
     float *sm_invc;
     int32_t *rel_ptr;   // [2R+1] run range per relation
     kge_heavy_index hv_dm, hv_sm, hv_seg;   // heavy destinations, sources, runs
+    // the runs grouped by destination (order dst, rel): dr_seg = run id, dr_rel = its relation
+    int32_t *dr_ptr, *dr_seg, *dr_rel;
+    kge_heavy_index hv_dr;
+    // each relation's run range cut into chunks of at most KGE_REL_CHUNK runs
+    int32_t n_relc;
+    int32_t *relc_rel, *relc_beg, *relc_end;
 };
+#define KGE_REL_CHUNK 2048
 
 // Optional per-kernel timing with HIP events on the launch stream (kge_profile_enable).
 struct KgeProfScope {
@@ -125,6 +132,27 @@ int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const
 // flag row of layer `layer` (device pointer), or null when cg is null
 const uint8_t *kge_cgraph_layer(const kge_cgraph *cg, int32_t layer);
 int kge_cgraph_check(const kge_partition *p, const kge_cgraph *cg, int32_t n_layers);
+
+// gather.hip, aggregate-first order ------------------------------------------
+// Z[s][:] = invc_s sum_{j in run s} H[j][:]  (fp32 [S][d]); runs into inactive destinations get zeros;
+// `partial`: [hv_seg.n_units][d] floats
+int launch_run_mean(const kge_partition *p, const float *H, int32_t d, float *Z, float *partial,
+                    const uint8_t *active, hipStream_t st);
+// Y[i][b][:] = sum_{runs (r,i) of i} a[r][b] Z[run][:]; rows are `ld` elements apart; rows with
+// row_active[i] == 0 are left unwritten; `partial`: [hv_dr.n_units][B*d] floats
+int launch_aggregate_runs(const kge_partition *p, const float *Z, const float *a, int32_t B, int32_t d,
+                          void *Y, int64_t ld, int msg_bf16, float *partial, const uint8_t *row_active,
+                          hipStream_t st);
+
+// gemm.hip, aggregate-first order ---------------------------------------------
+// out[i][:] = act( sum_b Y[i][b][:] V_b + H[i][:] W0 ), zero rows where row_active[i] == 0; out2 optional copy
+int launch_combine(const float *Y, const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
+                   const float *V, const float *W0, int act, const uint8_t *row_active, float *out,
+                   float *out2, hipStream_t st);
+// C[r] (d_in x d_out) = sum_{runs s of relation r} Z[s]^T G[seg_dst[s]];  da[r][b] = <C[r], V_b>
+// C: [2R][d_in*d_out] floats of scratch
+int launch_coeff_grad_runs(const kge_partition *p, const float *Z, const float *G, int32_t d_in,
+                           int32_t d_out, int32_t B, const float *V, float *C, float *da, hipStream_t st);
 
 // sampler_score.hip --------------------------------------------------------
 int launch_sample_negatives(const kge_partition *p, const int32_t *pos, int64_t n_pos, int32_t n_neg,

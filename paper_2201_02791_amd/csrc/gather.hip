@@ -251,7 +251,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
     const int32_t *__restrict__ unit_hv,
     const float *__restrict__ G, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_chunks,
     int32_t gbt_count, void *__restrict__ dP, int64_t ld, float *__restrict__ partial,
-    const uint8_t *__restrict__ active)
+    const uint8_t *__restrict__ active, const uint8_t *__restrict__ row_active)
 {
     constexpr int NG = 64 / LPR;
     const int lane = threadIdx.x & 63;
@@ -260,6 +260,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
     const int bc = (int)(wid_all - wid * n_chunks);
     const RowWork rw = row_work(wid, sm_ptr, N, n_units, hv_row, hv_unit_ptr, unit_hv);
     if (rw.row < 0) return;
+    if (row_active && !row_active[rw.row]) return;       // the row is not needed: left unwritten
     const int kl = lane % LPR, g = lane / LPR;
     const int GBT = gbt_count, GET = NG / GBT;
     const int gbt = g % GBT, get = g / GBT;
@@ -277,7 +278,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
         int32_t my_dst = 0, my_rel = 0;
         float my_w = 0.f;
         if (lane < cnt) {
-            my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc[e0 + lane];
+            my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc ? sm_invc[e0 + lane] : 1.f;
             if (active && !active[my_dst]) my_dst = -1;   // destination outside the sub-graph: G row is zero
         }
         const int rounds = (cnt + GET - 1) / GET;       // uniform trip count
@@ -359,7 +360,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t_mfma(
     const int32_t *__restrict__ unit_hv,
     const float *__restrict__ G, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_bchunks,
     int32_t n_cchunks, void *__restrict__ dP, int64_t ld, float *__restrict__ partial,
-    const uint8_t *__restrict__ active)
+    const uint8_t *__restrict__ active, const uint8_t *__restrict__ row_active)
 {
     constexpr int UK = 4;                                  // edge pairs in flight
     __shared__ float stage[WPB][32][36];                   // one 32x32 tile per wavefront (bf16 epilogue)
@@ -371,6 +372,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t_mfma(
     const int bchunk = chunk / n_cchunks, cchunk = chunk - bchunk * n_cchunks;
     const RowWork rw = row_work(wid, sm_ptr, N, n_units, hv_row, hv_unit_ptr, unit_hv);
     if (rw.row < 0) return;
+    if (row_active && !row_active[rw.row]) return;
     const int h = lane >> 5, l32 = lane & 31;
     const int bbase = bchunk * 32 * NBT, cbase = cchunk * 128;
 
@@ -387,7 +389,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t_mfma(
         int32_t my_dst = 0, my_rel = 0;
         float my_w = 0.f;
         if (lane < cnt) {
-            my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc[e0 + lane];
+            my_dst = sm_dst[e0 + lane]; my_rel = sm_rel[e0 + lane]; my_w = sm_invc ? sm_invc[e0 + lane] : 1.f;
             if (active && !active[my_dst]) my_dst = -1;   // destination outside the sub-graph: G row is zero
         }
         for (int k0 = 0; k0 < cnt; k0 += 2 * UK) {
@@ -466,12 +468,14 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t_mfma(
 template <bool BF16>
 __global__ void k_gather_t_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
                                   const int32_t *__restrict__ hv_unit_ptr, const float *__restrict__ partial,
-                                  int32_t bd, void *__restrict__ dP, int64_t ld)
+                                  int32_t bd, void *__restrict__ dP, int64_t ld,
+                                  const uint8_t *__restrict__ row_active)
 {
     const int bd4 = bd >> 2;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (int64_t)n_hv * bd4) return;
     const int32_t h = (int32_t)(idx / bd4);
+    if (row_active && !row_active[hv_row[h]]) return;
     const int k4 = (int)(idx - (int64_t)h * bd4) * 4;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int32_t u = hv_unit_ptr[h]; u < hv_unit_ptr[h + 1]; ++u) {
@@ -486,6 +490,85 @@ __global__ void k_gather_t_finish(int32_t n_hv, const int32_t *__restrict__ hv_r
     } else {
         *reinterpret_cast<float4 *>(reinterpret_cast<float *>(dP) + o) = s;
     }
+}
+
+// ------------------------------------------------------------------ run means
+// One wavefront per (relation, destination) run s (or per unit of a long run):
+//   Z[s][:] = invc_s * sum_{j in run s} H[j][:]
+// the normalised neighbour sum of Eq. 1 for one relation, before any weight is applied.
+template <int LPR>
+__global__ __launch_bounds__(64 * WPB) void k_run_mean(
+    const int32_t *__restrict__ seg_ptr, const int32_t *__restrict__ seg_dst,
+    const float *__restrict__ inv_c, const int32_t *__restrict__ col_src, int64_t S,
+    int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
+    const int32_t *__restrict__ unit_hv, const float *__restrict__ H, int32_t d,
+    float *__restrict__ Z, float *__restrict__ partial, const uint8_t *__restrict__ active)
+{
+    constexpr int NG = 64 / LPR;
+    constexpr int U = (NG >= 8) ? 2 : (NG >= 2 ? 4 : 8);     // row loads in flight per lane
+    const int lane = threadIdx.x & 63;
+    const int64_t wid = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+    const RowWork rw = row_work(wid, seg_ptr, S, n_units, hv_row, hv_unit_ptr, unit_hv);
+    if (rw.row < 0) return;
+    const int kl = lane % LPR, g = lane / LPR;
+    const bool kact = kl * 4 < d;
+    if (active && !active[seg_dst[rw.row]]) {           // destination outside the sub-graph
+        if (rw.unit < 0 && g == 0 && kact)
+            *reinterpret_cast<float4 *>(Z + rw.row * d + kl * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+        return;
+    }
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int len = rw.end - rw.beg;
+    for (int e0 = 0; e0 < len; e0 += NG * U) {
+        float4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int el = e0 + u * NG + g;
+            x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (el < len && kact) {
+                const int32_t src = col_src[rw.beg + el];
+                x[u] = *reinterpret_cast<const float4 *>(H + (int64_t)src * d + kl * 4);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) { acc.x += x[u].x; acc.y += x[u].y; acc.z += x[u].z; acc.w += x[u].w; }
+    }
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+        acc.x += __shfl_xor(acc.x, off, 64); acc.y += __shfl_xor(acc.y, off, 64);
+        acc.z += __shfl_xor(acc.z, off, 64); acc.w += __shfl_xor(acc.w, off, 64);
+    }
+    if (g != 0 || !kact) return;
+    if (rw.unit >= 0) {
+        *reinterpret_cast<float4 *>(partial + (int64_t)rw.unit * d + kl * 4) = acc;
+    } else {
+        const float w = inv_c[rw.row];
+        *reinterpret_cast<float4 *>(Z + rw.row * d + kl * 4) = make_float4(w * acc.x, w * acc.y, w * acc.z, w * acc.w);
+    }
+}
+
+// Long runs: Z[s] = invc_s * sum of the run's unit partials.  One thread per float4.
+__global__ void k_run_mean_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
+                                  const int32_t *__restrict__ hv_unit_ptr, const float *__restrict__ partial,
+                                  const float *__restrict__ inv_c, int32_t d, float *__restrict__ Z,
+                                  const int32_t *__restrict__ seg_dst, const uint8_t *__restrict__ active)
+{
+    const int d4 = d >> 2;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)n_hv * d4) return;
+    const int32_t h = (int32_t)(idx / d4);
+    const int k4 = (int)(idx - (int64_t)h * d4) * 4;
+    const int64_t row = hv_row[h];
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!(active && !active[seg_dst[row]])) {
+        for (int32_t u = hv_unit_ptr[h]; u < hv_unit_ptr[h + 1]; ++u) {
+            const float4 x = *reinterpret_cast<const float4 *>(partial + (int64_t)u * d + k4);
+            s.x += x.x; s.y += x.y; s.z += x.z; s.w += x.w;
+        }
+        const float w = inv_c[row];
+        s.x *= w; s.y *= w; s.z *= w; s.w *= w;
+    }
+    *reinterpret_cast<float4 *>(Z + row * d + k4) = s;
 }
 
 // ------------------------------------------------------------------ coefficient gradient
@@ -684,14 +767,25 @@ int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t 
     return KGE_OK;
 }
 
+// A CSR view whose rows each sum coefficient-weighted rows of another matrix:
+//   out[row][b][:] = sum_{q in row} a[rel[q]][b] * w[q] * X[idx[q]][:]       (w = 1 if null)
+struct TView {
+    const int32_t *ptr, *idx, *rel;
+    const float *w;
+    int64_t n_rows;
+    const kge_heavy_index *hx;
+    const char *name;
+};
+
 template <bool BF16, int LPR>
-static int launch_gather_t_nb(const kge_partition *p, const float *G, const float *a, int32_t B, int32_t d,
-                              void *dP, int64_t ld, float *partial, const uint8_t *active, hipStream_t st)
+static int launch_gather_t_nb(const TView &vw, const float *G, const float *a, int32_t B, int32_t d,
+                              void *dP, int64_t ld, float *partial, const uint8_t *active,
+                              const uint8_t *row_active, hipStream_t st)
 {
     constexpr int NG = 64 / LPR;
-    const int64_t N = p->n_vert;
-    const kge_heavy_index &hx = p->hv_sm;
-    KGE_PROF("gather_t", st);
+    const int64_t N = vw.n_rows;
+    const kge_heavy_index &hx = *vw.hx;
+    KGE_PROF(vw.name, st);
     // NB bases per lane (a power of two, at most 16); lane groups first cover the bases of a row,
     // the remaining groups split the edges
 #define GT_CALL(NBV, UEV)                                                                             \
@@ -702,8 +796,8 @@ static int launch_gather_t_nb(const kge_partition *p, const float *G, const floa
         const int64_t waves = (N + hx.n_units) * n_chunks;                                            \
         KGE_REQUIRE(cdiv(waves, WPB) < 0x7fffffffLL, KGE_ERANGE, "grid too large");                   \
         k_gather_t<BF16, LPR, NBV, UEV><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(              \
-            p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, N, hx.n_units, hx.hv_row, hx.hv_unit_ptr,    \
-            hx.unit_hv, G, a, B, d, n_chunks, gbt, dP, ld, partial, active);                                  \
+            vw.ptr, vw.idx, vw.rel, vw.w, N, hx.n_units, hx.hv_row, hx.hv_unit_ptr,                   \
+            hx.unit_hv, G, a, B, d, n_chunks, gbt, dP, ld, partial, active, row_active);              \
     }
     if (B >= 16) GT_CALL(16, 2)
     else if (B >= 8) GT_CALL(8, 4)
@@ -715,40 +809,57 @@ static int launch_gather_t_nb(const kge_partition *p, const float *G, const floa
     return KGE_OK;
 }
 
-int launch_gather_transpose(const kge_partition *p, const float *G, const float *a, int32_t B, int32_t d,
-                            void *dP, int64_t ld, int msg_bf16, float *partial, const uint8_t *active,
-                            hipStream_t st)
+static int launch_tview(const TView &vw, const float *G, const float *a, int32_t B, int32_t d,
+                        void *dP, int64_t ld, int msg_bf16, float *partial, const uint8_t *active,
+                        const uint8_t *row_active, hipStream_t st)
 {
-    if (p->n_vert == 0) return KGE_OK;
+    if (vw.n_rows == 0) return KGE_OK;
     const int lpr = pow2_at_least((d + 3) / 4);
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the transposed aggregation kernel", d);
     int rc = KGE_OK;
     if (B >= 32 && d % 32 == 0) {
         // many bases: the per-source product runs on the matrix cores
-        const kge_heavy_index &hxm = p->hv_sm;
+        const kge_heavy_index &hxm = *vw.hx;
         const int n_bchunks = (B + 31) / 32, n_cchunks = (d + 127) / 128;
-        const int64_t waves = (p->n_vert + hxm.n_units) * n_bchunks * n_cchunks;
+        const int64_t waves = (vw.n_rows + hxm.n_units) * n_bchunks * n_cchunks;
         KGE_REQUIRE(cdiv(waves, WPB) < 0x7fffffffLL, KGE_ERANGE, "grid too large");
-        KGE_PROF("gather_t", st);
-#define GTM_ARGS p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, p->n_vert, hxm.n_units, hxm.hv_row, hxm.hv_unit_ptr, \
-                 hxm.unit_hv, G, a, B, d, n_bchunks, n_cchunks, dP, ld, partial, active
+        KGE_PROF(vw.name, st);
+#define GTM_ARGS vw.ptr, vw.idx, vw.rel, vw.w, vw.n_rows, hxm.n_units, hxm.hv_row, hxm.hv_unit_ptr, \
+                 hxm.unit_hv, G, a, B, d, n_bchunks, n_cchunks, dP, ld, partial, active, row_active
         if (msg_bf16) k_gather_t_mfma<true, 1><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(GTM_ARGS);
         else k_gather_t_mfma<false, 1><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(GTM_ARGS);
 #undef GTM_ARGS
         KGE_LAUNCH_CHECK();
-    } else if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(p, G, a, B, d, dP, ld, partial, active, st))); }
-    else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, L>(p, G, a, B, d, dP, ld, partial, active, st))); }
+    } else if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(vw, G, a, B, d, dP, ld, partial, active, row_active, st))); }
+    else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, L>(vw, G, a, B, d, dP, ld, partial, active, row_active, st))); }
     if (rc != KGE_OK) return rc;
-    const kge_heavy_index &hx = p->hv_sm;
+    const kge_heavy_index &hx = *vw.hx;
     if (hx.n_hv > 0) {
         KGE_PROF("gather_t_fin", st);
         const int bd = B * d;
         const int64_t n = (int64_t)hx.n_hv * (bd / 4);
-        if (msg_bf16) k_gather_t_finish<true><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, bd, dP, ld);
-        else k_gather_t_finish<false><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, bd, dP, ld);
+        if (msg_bf16) k_gather_t_finish<true><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, bd, dP, ld, row_active);
+        else k_gather_t_finish<false><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, bd, dP, ld, row_active);
         KGE_LAUNCH_CHECK();
     }
     return KGE_OK;
+}
+
+int launch_gather_transpose(const kge_partition *p, const float *G, const float *a, int32_t B, int32_t d,
+                            void *dP, int64_t ld, int msg_bf16, float *partial, const uint8_t *active,
+                            hipStream_t st)
+{
+    const TView vw{p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, p->n_vert, &p->hv_sm, "gather_t"};
+    return launch_tview(vw, G, a, B, d, dP, ld, msg_bf16, partial, active, nullptr, st);
+}
+
+// Y[i][b][:] = sum over the runs (r, i) of destination i of a[r][b] Z[run][:]
+int launch_aggregate_runs(const kge_partition *p, const float *Z, const float *a, int32_t B, int32_t d,
+                          void *Y, int64_t ld, int msg_bf16, float *partial, const uint8_t *row_active,
+                          hipStream_t st)
+{
+    const TView vw{p->dr_ptr, p->dr_seg, p->dr_rel, nullptr, p->n_vert, &p->hv_dr, "aggregate"};
+    return launch_tview(vw, Z, a, B, d, Y, ld, msg_bf16, partial, nullptr, row_active, st);
 }
 
 template <bool BF16, int LPR>
@@ -803,5 +914,32 @@ int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const
     KGE_PROF("coeff_reduce", st);
     k_coeff_reduce<<<rgrid, 256, 0, st>>>(p->rel_ptr, seg_scratch, B, BP, da);
     KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+// Z[s][:] = invc_s * sum_{j in run s} H[j][:]   (fp32 [S][d]); `partial`: [hv_seg.n_units][d] floats
+int launch_run_mean(const kge_partition *p, const float *H, int32_t d, float *Z, float *partial,
+                    const uint8_t *active, hipStream_t st)
+{
+    const int64_t S = p->n_seg;
+    if (S == 0) return KGE_OK;
+    const int lpr = pow2_at_least((d + 3) / 4);
+    KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the run-mean kernel", d);
+    const kge_heavy_index &hx = p->hv_seg;
+    const unsigned grid = (unsigned)cdiv(S + hx.n_units, WPB);
+    {
+        KGE_PROF("run_mean", st);
+        DISPATCH_LPR(lpr, (k_run_mean<L><<<grid, 64 * WPB, 0, st>>>(p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S,
+                                                                    hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv,
+                                                                    H, d, Z, partial, active)));
+    }
+    KGE_LAUNCH_CHECK();
+    if (hx.n_hv > 0) {
+        KGE_PROF("run_mean_fin", st);
+        const int64_t n = (int64_t)hx.n_hv * (d / 4);
+        k_run_mean_finish<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial,
+                                                                 p->inv_c, d, Z, p->seg_dst, active);
+        KGE_LAUNCH_CHECK();
+    }
     return KGE_OK;
 }

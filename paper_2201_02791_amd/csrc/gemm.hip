@@ -5,6 +5,12 @@
 //   weight_grad  d[V_1 .. V_B | W_0] = H^T [dP | G]            (d_in x N) (N x (B+1)d_out)
 //   input_grad   dH = [dP | G] [V_1 .. V_B | W_0]^T            (N x (B+1)d_out) ((B+1)d_out x d_in)
 //
+// and, for layers that aggregate before they project,
+//
+//   combine      H' = act([Y | H] [V_1; ..; V_B; W_0])          (N x (B+1)d_in) ((B+1)d_in x d_out)
+//   rel_outer    C_r = sum_{runs s of r} Z_s^T G_{dst(s)}        grouped over relations, (d_in x d_out) each
+//   coeff        da = C Vflat^T                                  (2R x d_in d_out) (d_in d_out x B)
+//
 // One kernel template: 128x128 block tile, 4 wavefronts in a 2x2 grid, each wavefront owns a
 // 64x64 sub-tile as 2x2 v_mfma_f32_32x32x2_f32 accumulators.  Operands are staged through LDS
 // K-major (As[k][m], Bs[k][n]) so that the MFMA operand reads are 32 consecutive floats.
@@ -56,9 +62,32 @@ struct SrcXcat {
     }
 };
 
-// ---- epilogues: store(m, n, value)
+// [V_1; ..; V_B; W0] viewed as a ((B+1) d_in x d_out) matrix (V's own memory order, then W0)
+struct SrcWstack {
+    const float *V, *W0; int32_t d_in, d_out, B;
+    __device__ __forceinline__ float4 load4(int64_t k, int32_t c) const
+    {
+        const int64_t bk = (int64_t)B * d_in;
+        if (k >= bk + d_in || c >= d_out) return make_float4(0.f, 0.f, 0.f, 0.f);
+        const float *base = k < bk ? V + k * d_out : W0 + (k - bk) * d_out;
+        return *reinterpret_cast<const float4 *>(base + c);
+    }
+};
+
+// rows of X picked through an index list: row k is X[idx[k]]
+struct SrcGatherRows {
+    const float *X; const int32_t *idx; int64_t n_idx; int32_t cols;
+    __device__ __forceinline__ float4 load4(int64_t k, int32_t c) const
+    {
+        if (k >= n_idx || c >= cols) return make_float4(0.f, 0.f, 0.f, 0.f);
+        return *reinterpret_cast<const float4 *>(X + (int64_t)idx[k] * cols + c);
+    }
+};
+
+// ---- epilogues: store(m, n, value); bind(g) tells a grouped launch which group the block works on
 struct EpiProject {             // columns < B*d_out go to P, the rest to Self
     float *P; float *Self; int64_t rows; int32_t d_out, B;
+    __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         int32_t bd = B * d_out;
@@ -70,6 +99,7 @@ struct EpiProject {             // columns < B*d_out go to P, the rest to Self
 
 struct EpiWeightGrad {          // atomic accumulation of split-K partial tiles
     float *dV, *dW0; int32_t d_in, d_out, B;
+    __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         int32_t bd = B * d_out;
@@ -82,16 +112,53 @@ struct EpiWeightGrad {          // atomic accumulation of split-K partial tiles
 
 struct EpiRowMajor {
     float *out; int64_t rows; int32_t cols;
+    __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         if (m < rows && n < cols) out[m * cols + n] = v;
     }
 };
 
+struct EpiRowMajorAtomic {      // split-K partial tiles
+    float *out; int64_t rows; int32_t cols;
+    __device__ __forceinline__ void bind(int32_t) {}
+    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
+    {
+        if (m < rows && n < cols) unsafeAtomicAdd(out + m * cols + n, v);
+    }
+};
+
+struct EpiAct {                 // activation, zero rows outside the sub-graph, optional second copy
+    float *out, *out2; int64_t rows; int32_t cols; int act; const uint8_t *row_active;
+    __device__ __forceinline__ void bind(int32_t) {}
+    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
+    {
+        if (m >= rows || n >= cols) return;
+        float r = act == KGE_ACT_RELU ? fmaxf(v, 0.f) : v;
+        if (row_active && !row_active[m]) r = 0.f;
+        out[m * cols + n] = r;
+        if (out2) out2[m * cols + n] = r;
+    }
+};
+
+struct EpiRelOuter {            // C[group] (d_in x d_out) accumulates the chunks of one relation
+    float *C; int32_t d_in, d_out; int32_t group;
+    __device__ __forceinline__ void bind(int32_t g) { group = g; }
+    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
+    {
+        if (m < d_in && n < d_out) unsafeAtomicAdd(C + ((int64_t)group * d_in + m) * d_out + n, v);
+    }
+};
+
 // A(m,k): A_KCONTIG ? srcA.load4(m, k) along k : srcA.load4(k, m) along m
 // B(k,n): B_KCONTIG ? srcB.load4(n, k) along k : srcB.load4(k, n) along n
+// The contraction range of block z is [z*kchunk, min((z+1)*kchunk, K)), or, in a grouped launch
+// (g_beg non-null), [g_beg[z], g_end[z]) with the epilogue bound to group g_id[z].
 template <class SA, bool A_KCONTIG, class SB, bool B_KCONTIG, class EPI>
-__global__ __launch_bounds__(GT) void k_gemm(SA srcA, SB srcB, EPI epi, int64_t K, int64_t kchunk)
+__global__ __launch_bounds__(GT) void k_gemm(SA srcA, SB srcB, EPI epi, int64_t K, int64_t kchunk,
+                                             const int32_t *__restrict__ g_id = nullptr,
+                                             const int32_t *__restrict__ g_beg = nullptr,
+                                             const int32_t *__restrict__ g_end = nullptr)
 {
     __shared__ __attribute__((aligned(16))) float As[BK][BM + PADL];
     __shared__ __attribute__((aligned(16))) float Bs[BK][BN + PADL];
@@ -100,8 +167,9 @@ __global__ __launch_bounds__(GT) void k_gemm(SA srcA, SB srcB, EPI epi, int64_t 
     const int wm = w >> 1, wn = w & 1;
     const int64_t m0 = (int64_t)blockIdx.x * BM;
     const int32_t n0 = blockIdx.y * BN;
-    const int64_t kbeg = (int64_t)blockIdx.z * kchunk;
-    const int64_t kend = (kbeg + kchunk < K) ? kbeg + kchunk : K;
+    int64_t kbeg = (int64_t)blockIdx.z * kchunk;
+    int64_t kend = (kbeg + kchunk < K) ? kbeg + kchunk : K;
+    if (g_beg) { kbeg = g_beg[blockIdx.z]; kend = g_end[blockIdx.z]; epi.bind(g_id[blockIdx.z]); }
 
     floatx16 acc[2][2];
 #pragma unroll
@@ -271,5 +339,59 @@ int launch_input_grad(const float *dP, const float *G, int64_t N, int32_t d_in,
     SrcXcat sa{dP, G, N, d_out, B};
     k_gemm<SrcXcat, true, SrcWcat, true, EpiRowMajor><<<grid, GT, 0, st>>>(sa, sb, ep, nc, nc);
     KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+int launch_combine(const float *Y, const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
+                   const float *V, const float *W0, int act, const uint8_t *row_active, float *out,
+                   float *out2, hipStream_t st)
+{
+    if (N == 0) return KGE_OK;
+    const int64_t K = (int64_t)(B + 1) * d_in;
+    dim3 grid((unsigned)cdiv(N, BM), (unsigned)cdiv(d_out, BN), 1);
+    SrcXcat sa{Y, H, N, d_in, B};                 // [Y | H]: B blocks of d_in columns, then d_in more
+    SrcWstack sb{V, W0, d_in, d_out, B};
+    EpiAct ep{out, out2, N, d_out, act, row_active};
+    KGE_PROF("combine", st);
+    k_gemm<SrcXcat, true, SrcWstack, false, EpiAct><<<grid, GT, 0, st>>>(sa, sb, ep, K, K);
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+int launch_coeff_grad_runs(const kge_partition *p, const float *Z, const float *G, int32_t d_in,
+                           int32_t d_out, int32_t B, const float *V, float *C, float *da, hipStream_t st)
+{
+    const int64_t R2 = 2 * (int64_t)p->n_relations;
+    const int64_t dd = (int64_t)d_in * d_out;
+    int rc = launch_fill_zero(da, sizeof(float) * (size_t)R2 * B, st);
+    if (rc != KGE_OK) return rc;
+    if (p->n_seg == 0) return KGE_OK;
+    rc = launch_fill_zero(C, sizeof(float) * (size_t)R2 * dd, st);
+    if (rc != KGE_OK) return rc;
+    KGE_REQUIRE(p->n_relc <= 65535, KGE_ERANGE, "too many relation chunks (%d) for one launch", p->n_relc);
+    {
+        dim3 grid((unsigned)cdiv(d_in, BM), (unsigned)cdiv(d_out, BN), (unsigned)p->n_relc);
+        SrcRowMajorF32 sa{Z, p->n_seg, d_in};
+        SrcGatherRows sb{G, p->seg_dst, p->n_seg, d_out};
+        EpiRelOuter ep{C, d_in, d_out, 0};
+        KGE_PROF("rel_outer", st);
+        k_gemm<SrcRowMajorF32, false, SrcGatherRows, false, EpiRelOuter><<<grid, GT, 0, st>>>(
+            sa, sb, ep, p->n_seg, 0, p->relc_rel, p->relc_beg, p->relc_end);
+        KGE_LAUNCH_CHECK();
+    }
+    {
+        const int64_t tiles = cdiv(R2, BM) * cdiv(B, BN);
+        int64_t splits = cdiv(512, tiles);
+        int64_t kchunk = cdiv(cdiv(dd, splits), BK) * BK;
+        if (kchunk < 4 * BK) kchunk = 4 * BK;
+        splits = cdiv(dd, kchunk);
+        dim3 grid((unsigned)cdiv(R2, BM), (unsigned)cdiv(B, BN), (unsigned)splits);
+        SrcRowMajorF32 sa{C, R2, (int32_t)dd};
+        SrcRowMajorF32 sb{V, B, (int32_t)dd};
+        EpiRowMajorAtomic ep{da, R2, B};
+        KGE_PROF("coeff_contract", st);
+        k_gemm<SrcRowMajorF32, true, SrcRowMajorF32, true, EpiRowMajorAtomic><<<grid, GT, 0, st>>>(sa, sb, ep, dd, kchunk);
+        KGE_LAUNCH_CHECK();
+    }
     return KGE_OK;
 }

@@ -414,6 +414,25 @@ __global__ void k_ptr_from_sorted(const T *sorted, int64_t n, int64_t nv, int32_
     for (int64_t v = lo; v <= hi; ++v) ptr[v] = (int32_t)q;
 }
 
+// keys[s] = destination of run s, vals[s] = s
+__global__ void k_run_keys(const int32_t *seg_dst, int64_t S, uint32_t *k, uint32_t *v)
+{
+    int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= S) return;
+    k[s] = (uint32_t)seg_dst[s];
+    v[s] = (uint32_t)s;
+}
+
+__global__ void k_run_emit(const uint32_t *sorted_run, int64_t S, const int32_t *seg_rel, int32_t *dr_seg,
+                           int32_t *dr_rel)
+{
+    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= S) return;
+    const uint32_t s = sorted_run[q];
+    dr_seg[q] = (int32_t)s;
+    dr_rel[q] = seg_rel[s];
+}
+
 __global__ void k_max_degree(const int32_t *ptr, int64_t nv, int32_t *out)
 {
     int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -668,6 +687,39 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
     TRY(build_heavy_index(p->dm_ptr, N, &p->hv_dm, st));
     TRY(build_heavy_index(p->sm_ptr, N, &p->hv_sm, st));
     TRY(build_heavy_index(p->seg_ptr, S, &p->hv_seg, st));
+
+    // --- the runs grouped by destination: a stable sort of run ids by destination keeps the
+    // relation order inside a destination
+    TRY(palloc(&p->dr_ptr, N + 1)); TRY(palloc(&p->dr_seg, S)); TRY(palloc(&p->dr_rel, S));
+    {
+        uint32_t *rk, *rk_alt, *rv, *rv_alt;
+        TRY(tmp.alloc(&rk, S)); TRY(tmp.alloc(&rk_alt, S)); TRY(tmp.alloc(&rv, S)); TRY(tmp.alloc(&rv_alt, S));
+        if (S > 0) { k_run_keys<<<grid_for(S), TB, 0, st>>>(p->seg_dst, S, rk, rv); KGE_LAUNCH_CHECK(); }
+        TRY(radix_sort<uint32_t>(&rk, &rv, &rk_alt, &rv_alt, S, vbits, st));
+        if (S > 0) { k_run_emit<<<grid_for(S), TB, 0, st>>>(rv, S, p->seg_rel, p->dr_seg, p->dr_rel); KGE_LAUNCH_CHECK(); }
+        k_ptr_from_sorted<uint32_t><<<grid_for(S + 1), TB, 0, st>>>(rk, S, N, p->dr_ptr);
+        KGE_LAUNCH_CHECK();
+    }
+    TRY(build_heavy_index(p->dr_ptr, N, &p->hv_dr, st));
+
+    // --- chunks of each relation's run range (host side: 2R+1 offsets)
+    {
+        const int64_t R2 = 2 * (int64_t)n_rel;
+        std::vector<int32_t> h_rel_ptr((size_t)R2 + 1), c_rel, c_beg, c_end;
+        KGE_HIP(hipMemcpy(h_rel_ptr.data(), p->rel_ptr, sizeof(int32_t) * (size_t)(R2 + 1), hipMemcpyDeviceToHost));
+        for (int64_t r = 0; r < R2; ++r)
+            for (int32_t b = h_rel_ptr[r]; b < h_rel_ptr[r + 1]; b += KGE_REL_CHUNK) {
+                c_rel.push_back((int32_t)r); c_beg.push_back(b);
+                c_end.push_back(b + KGE_REL_CHUNK < h_rel_ptr[r + 1] ? b + KGE_REL_CHUNK : h_rel_ptr[r + 1]);
+            }
+        p->n_relc = (int32_t)c_rel.size();
+        TRY(palloc(&p->relc_rel, c_rel.size())); TRY(palloc(&p->relc_beg, c_rel.size())); TRY(palloc(&p->relc_end, c_rel.size()));
+        if (!c_rel.empty()) {
+            KGE_HIP(hipMemcpy(p->relc_rel, c_rel.data(), sizeof(int32_t) * c_rel.size(), hipMemcpyHostToDevice));
+            KGE_HIP(hipMemcpy(p->relc_beg, c_beg.data(), sizeof(int32_t) * c_beg.size(), hipMemcpyHostToDevice));
+            KGE_HIP(hipMemcpy(p->relc_end, c_end.data(), sizeof(int32_t) * c_end.size(), hipMemcpyHostToDevice));
+        }
+    }
     int32_t h_maxdeg[2] = {0, 0};
     KGE_HIP(hipMemcpy(h_maxdeg, maxdeg, sizeof(h_maxdeg), hipMemcpyDeviceToHost));
     p->max_in_degree = h_maxdeg[0];
@@ -699,7 +751,9 @@ extern "C" void kge_partition_destroy(kge_partition *p)
                     p->dm_rel, p->dm_invc, p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, p->rel_ptr,
                     p->hv_dm.hv_row, p->hv_dm.hv_unit_ptr, p->hv_dm.unit_hv,
                     p->hv_sm.hv_row, p->hv_sm.hv_unit_ptr, p->hv_sm.unit_hv,
-                    p->hv_seg.hv_row, p->hv_seg.hv_unit_ptr, p->hv_seg.unit_hv};
+                    p->hv_seg.hv_row, p->hv_seg.hv_unit_ptr, p->hv_seg.unit_hv,
+                    p->dr_ptr, p->dr_seg, p->dr_rel, p->hv_dr.hv_row, p->hv_dr.hv_unit_ptr, p->hv_dr.unit_hv,
+                    p->relc_rel, p->relc_beg, p->relc_end};
     for (void *q : arrs) if (q) (void)hipFree(q);
     delete p;
 }
@@ -769,6 +823,9 @@ extern "C" int kge_partition_export(const kge_partition *p, int32_t which, void 
     case KGE_ARR_SM_REL: src = p->sm_rel; n = p->n_edge; break;
     case KGE_ARR_SM_INVC: src = p->sm_invc; n = p->n_edge; break;
     case KGE_ARR_REL_PTR: src = p->rel_ptr; n = 2 * (int64_t)p->n_relations + 1; break;
+    case KGE_ARR_DR_PTR: src = p->dr_ptr; n = p->n_vert + 1; break;
+    case KGE_ARR_DR_SEG: src = p->dr_seg; n = p->n_seg; break;
+    case KGE_ARR_DR_REL: src = p->dr_rel; n = p->n_seg; break;
     default: KGE_REQUIRE(false, KGE_EINVAL, "unknown array id %d", which);
     }
     KGE_REQUIRE(bytes == 4 * n, KGE_EINVAL, "array %d has %lld bytes, caller gave %lld", which,

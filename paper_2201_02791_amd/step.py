@@ -16,7 +16,7 @@ from . import binding as kb
 class TrainStep:
     def __init__(self, part: kb.Partition, params: Dict[str, object], acts: Sequence[int],
                  msg_dtype: int = kb.MSG_F32, need_dH0: bool = True, device: str = "cuda:0",
-                 keep_scores: bool = True, cone: bool = False):
+                 keep_scores: bool = True, cone: bool = False, order: int = kb.ORDER_PROJECT_FIRST):
         import torch
         self.torch = torch
         self.part = part
@@ -25,7 +25,7 @@ class TrainStep:
         t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(self.dev)
         self.layers: List[dict] = []
         for V, a, W0, act in zip(params["V"], params["a"], params["W0"], acts):
-            self.layers.append(dict(V=t(V), a=t(a), W0=t(W0), act=int(act)))
+            self.layers.append(dict(V=t(V), a=t(a), W0=t(W0), act=int(act), order=int(order)))
         self.M = t(params["M"])
         self.H0 = t(params["H0"])
         N = part.n_vert
@@ -65,7 +65,7 @@ class TrainStep:
         raw = self.workspace[off:off + nbytes]
         bf = self.msg_dtype == kb.MSG_BF16 and which in (kb.WS_P, kb.WS_DP)
         t = raw.view(torch.bfloat16 if bf else torch.float32)
-        return t.view(self.part.n_vert, -1)
+        return t.view(self.part.n_seg if which == kb.WS_Z else self.part.n_vert, -1)
 
     # --- the four per-step calls, in Algorithm 1's order
     def compute_graph(self, stream=None):

@@ -1,0 +1,154 @@
+"""GPU parity of the aggregate-first order of Eq. 1-2 (run means z, per-basis sums y, one
+contraction with [V_1; ..; V_B; W_0]) against the same oracle as the project-first order: the
+two orders are algebraically identical, so every output is held to the same tolerances."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2201_02791_amd import synth
+from gpu_util import (SEED, STEP, assert_partition_equal, assert_step_close, gpu_step, oracle_step, rel_err)
+
+pytestmark = pytest.mark.gpu
+TOL_VAL, TOL_GRAD = 1e-4, 1e-3
+AGG = 1
+
+
+def say(*a):
+    print("[case]", *a, file=sys.stderr, flush=True)
+
+
+@pytest.fixture(scope="module")
+def kb():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2201_02791_amd import binding
+    binding.load()
+    return binding
+
+
+def random_graph(seed, n, R, m):
+    rng = np.random.default_rng(seed)
+    return (rng.integers(0, n, m).astype(np.int32), rng.integers(0, R, m).astype(np.int32),
+            rng.integers(0, n, m).astype(np.int32))
+
+
+def test_runs_grouped_by_destination(kb, orc):
+    say("dr view")
+    head, rel, tail = random_graph(3, 500, 7, 6000)
+    gp = kb.build_partition(head, rel, tail, 500, 7, 2, 1, 2, 0)
+    op = orc.build_partition(head, rel, tail, 500, 7, 2, 1, 2, 0)
+    S, N = op["n_seg"], op["n_vert"]
+    order = np.lexsort((op["seg_rel"], op["seg_dst"]))            # by destination, then relation
+    np.testing.assert_array_equal(gp.export("dr_seg"), order.astype(np.int32))
+    np.testing.assert_array_equal(gp.export("dr_rel"), op["seg_rel"][order])
+    want_ptr = np.searchsorted(op["seg_dst"][order], np.arange(N + 1)).astype(np.int32)
+    np.testing.assert_array_equal(gp.export("dr_ptr"), want_ptr)
+    assert gp.export("dr_ptr")[-1] == S
+
+
+SHAPES = [
+    # name, n, R, m, d, B, n_pos, n_neg, mode, P, acts
+    ("d32_B4", 300, 5, 2500, 32, 4, 200, 3, 1, 1, [1, 0]),
+    ("d200_B10_ragged_lanes", 400, 6, 3000, 200, 10, 333, 5, 1, 1, [1, 0]),
+    ("d128_B2", 500, 1, 4000, 128, 2, 257, 1, 0, 2, [1, 0]),
+    ("d64_B3_odd_bases", 300, 4, 2000, 64, 3, 100, 2, 1, 3, [1, 1]),
+    ("d8_B1", 100, 2, 700, 8, 1, 64, 4, 1, 1, [0, 0]),
+    ("d256_B5", 200, 3, 1500, 256, 5, 90, 7, 1, 1, [1, 0]),
+    ("d16_B20", 250, 9, 2200, 16, 20, 128, 2, 0, 2, [1, 0]),
+    ("d96_B40_matrix_core_sum", 300, 12, 2600, 96, 40, 150, 3, 1, 1, [1, 0]),
+    ("d160_B70", 200, 5, 1500, 160, 70, 64, 2, 1, 2, [1, 1]),
+    ("many_relations_few_runs", 400, 300, 3000, 32, 6, 100, 2, 1, 1, [1, 0]),
+    ("one_relation_many_chunks", 9000, 1, 40000, 16, 2, 300, 1, 1, 1, [1, 0]),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=[s[0] for s in SHAPES])
+def test_step_aggregate_first(kb, orc, shape):
+    name, n, R, m, d, B, n_pos, n_neg, mode, P, acts = shape
+    say("aggregate-first step", shape)
+    spec = synth.scaled(synth.WORKLOADS[0], name=name, seed=17, n_entities=n, n_relations=R, n_triples=m,
+                        d=d, n_bases=B, n_pos=n_pos, n_neg=n_neg, neg_mode=mode, n_parts=P, part_id=P - 1,
+                        acts=acts, feature_std=0.5)
+    head, rel, tail = random_graph(len(name) + n, n, R, m)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=AGG)
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
+    assert_partition_equal(gp, op)
+    assert_step_close(ts, res, TOL_VAL, TOL_GRAD)
+
+
+def test_intermediates_z_and_y(kb, orc):
+    """z (run means) and y (per-basis sums) of the LAST layer against their definitions in fp64."""
+    say("z / y")
+    n, R, m, d, B = 600, 6, 7000, 64, 5
+    spec = synth.scaled(synth.WORKLOADS[0], name="zy", seed=3, n_entities=n, n_relations=R, n_triples=m,
+                        d=d, n_bases=B, n_pos=50, n_neg=1, feature_std=0.5)
+    head, rel, tail = random_graph(77, n, R, m)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=AGG)
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
+    H1 = res["Hs"][1]                       # input of the last layer
+    lens = np.diff(op["seg_ptr"])
+    run_of_edge = np.repeat(np.arange(op["n_seg"]), lens)
+    Z = np.zeros((op["n_seg"], d))
+    np.add.at(Z, run_of_edge, H1[op["col_src"]])
+    Z /= lens[:, None]
+    assert rel_err(ts.view(kb.WS_Z, 1).cpu().numpy(), Z) <= TOL_VAL
+    a = np.asarray(params["a"][1], np.float64)
+    Y = np.zeros((op["n_vert"], B, d))
+    np.add.at(Y, op["seg_dst"], a[op["seg_rel"]][:, :, None] * Z[:, None, :])
+    assert rel_err(ts.view(kb.WS_Y, 1).cpu().numpy().reshape(-1, B, d), Y) <= TOL_VAL
+
+
+def test_hub_rows_aggregate_first(kb, orc):
+    """A run of 600 edges (split into units), a destination and a source with > 256 edges."""
+    say("aggregate-first hub")
+    n, R = 700, 2
+    leaves = np.arange(1, 601, dtype=np.int32)
+    head = np.concatenate([leaves, leaves[:50], np.array([650, 651], np.int32)])
+    tail = np.concatenate([np.zeros(600, np.int32), np.zeros(50, np.int32), np.array([651, 652], np.int32)])
+    rel = np.concatenate([np.zeros(600, np.int32), np.ones(50, np.int32), np.array([0, 1], np.int32)])
+    spec = synth.scaled(synth.WORKLOADS[0], name="hub", seed=5, n_entities=n, n_relations=R,
+                        n_triples=len(head), d=64, n_bases=4, n_pos=300, n_neg=2, neg_mode=1)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=AGG)
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
+    assert_step_close(ts, res, TOL_VAL, TOL_GRAD)
+
+
+def test_many_runs_per_destination(kb, orc):
+    """One destination reached under 700 different relations: its list of runs is itself split."""
+    say("aggregate-first, heavy run list")
+    n, R = 900, 700
+    head = np.arange(1, 701, dtype=np.int32)
+    tail = np.zeros(700, np.int32)
+    rel = np.arange(700, dtype=np.int32)
+    extra = random_graph(9, n, R, 1500)
+    head = np.concatenate([head, extra[0]]); rel = np.concatenate([rel, extra[1]]); tail = np.concatenate([tail, extra[2]])
+    spec = synth.scaled(synth.WORKLOADS[0], name="manyruns", seed=5, n_entities=n, n_relations=R,
+                        n_triples=len(head), d=32, n_bases=3, n_pos=200, n_neg=1, neg_mode=1)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=AGG)
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
+    assert np.diff(gp.export("dr_ptr")).max() >= 700
+    assert_step_close(ts, res, TOL_VAL, TOL_GRAD)
+
+
+def test_aggregate_first_with_compute_graph(kb, orc):
+    say("aggregate-first + sub-graph")
+    n, R, m = 4000, 5, 14000
+    spec = synth.scaled(synth.WORKLOADS[0], name="aggcone", seed=23, n_entities=n, n_relations=R, n_triples=m,
+                        d=64, n_bases=4, n_pos=9, n_neg=2, neg_mode=1, feature_std=0.5)
+    head, rel, tail = random_graph(31, n, R, m)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, cone=True, order=AGG)
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
+    active, stats = ts.cg.export()
+    np.testing.assert_array_equal(active, orc.compute_graph(op, pos, res["neg_ent"], 2))
+    assert stats[1, 0] < stats[0, 0] < gp.n_vert
+    assert_step_close(ts, res, TOL_VAL, TOL_GRAD, batch_rows=orc.batch_vertices(op, pos, res["neg_ent"]))
+
+
+def test_aggregate_first_needs_fp32_messages(kb):
+    head, rel, tail = random_graph(1, 100, 2, 500)
+    gp = kb.build_partition(head, rel, tail, 100, 2)
+    import torch
+    V = torch.zeros((2, 16, 16), device="cuda"); a = torch.zeros((4, 2), device="cuda"); W0 = torch.zeros((16, 16), device="cuda")
+    with pytest.raises(kb.KgeError):
+        kb.workspace_bytes(gp, [dict(V=V, a=a, W0=W0, act=0, order=AGG)], kb.MSG_BF16)
