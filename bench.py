@@ -51,6 +51,19 @@ def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None):
         return "hbm", E * (4.0 * d + 12.0) + N * (4.0 + B * d * ep) + R2 * B * 4.0
     if name == "distmult":     # per scored group: h_s, h_t, M_r + one row per negative, read and atomically updated
         return "hbm", n_pos * (3.0 + n_neg) * d * 4.0 * 2.0 + n_pos * n_neg * 5.0
+    ne_mean = E if cone is None else sum(c[1] for c in cone) / len(cone)
+    ns_mean = S if cone is None else sum(c[2] for c in cone) / len(cone)
+    nv_mean = N if cone is None else sum(c[0] for c in cone) / len(cone)
+    if name == "run_mean":     # per edge: source id + input row; per run: ptr/dst/1/c + z row written
+        return "hbm", ne_mean * (4.0 * d + 4.0) + S * 12.0 + S * 4.0 * d
+    if name == "aggregate":    # per run: z row + (run id, relation); per vertex: ptr + y row written
+        return "hbm", ns_mean * (4.0 * d + 8.0) + N * 4.0 + nv_mean * B * d * 4.0 + R2 * B * 4.0
+    if name == "combine":
+        return "mfma", gemm_flops
+    if name == "rel_outer":    # C_r = sum_runs z^T G: 2 S d^2 flops; bytes S (2 d) 4
+        return "mfma", 2.0 * S * d * d
+    if name == "coeff_contract":
+        return "mfma", 2.0 * R2 * d * d * B
     if name == "project":
         return "mfma", gemm_flops
     if name == "weight_grad":
@@ -112,6 +125,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="index into the workload list (0..4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--order", choices=["project", "aggregate"], default="project",
+                    help="project-first (P = H V_b, then the neighbour sum) or aggregate-first order of Eq. 1-2")
     ap.add_argument("--whole-partition", action="store_true",
                     help="propagate every vertex of the partition instead of the batch's computational sub-graph")
     ap.add_argument("--calibrate", action="store_true",
@@ -144,7 +159,8 @@ def main():
     pos = synth.make_batch(spec, part.n_core)
     msg = kb.MSG_BF16 if spec.msg_dtype == "bf16" else kb.MSG_F32
     ts = TrainStep(part, params, spec.acts, msg, need_dH0=not spec.fixed_features, keep_scores=True,
-                   cone=not args.whole_partition)
+                   cone=not args.whole_partition,
+                   order=kb.ORDER_AGGREGATE_FIRST if args.order == "aggregate" else kb.ORDER_PROJECT_FIRST)
     ts.set_batch(pos, spec.n_neg)
     log("workspace %.2f GB" % (ts.ws_bytes / 1e9))
 
@@ -216,6 +232,7 @@ def main():
                       "relations_with_inverses": 2 * spec.n_relations, "layers": spec.n_layers,
                       "positives": n_pos, "negatives_per_positive": n_neg, "parallelism": "1 partition on 1 GPU",
                       "propagation": "whole partition" if cone is None else "batch computational sub-graph",
+                      "order": args.order + "-first",
                       "subgraph_vertices_edges_runs_per_layer": cone},
            "triples_per_s": T / (dt / args.steps), "loss": loss,
            "roofline": roof, "cpu_baseline": base, "kernels": kernels}

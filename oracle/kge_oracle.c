@@ -256,11 +256,64 @@ static void project_all(int64_t N, int32_t d_in, int32_t d_out, int32_t B,
 }
 
 /*
+ * The rounding points of a bf16 pipeline that sums neighbours before it applies weights
+ * (msg_bf16 == 2).  Eq. 1-2 regrouped, nothing else:
+ *   z_{i,r} = (1/c_{i,r}) sum_{j in N_i^r} h_j          per (relation, destination) run
+ *   y_{i,b} = sum_r a_rb z_{i,r}
+ *   pre_i   = sum_b y_{i,b} V_b + h_i W_0
+ * with h, z, y, V_b, W_0 each rounded to bf16 where they enter the next step and every sum exact.
+ * zq_out (optional) receives the rounded z, [S][d_in].
+ */
+static void forward_aggregate_first_bf16(int64_t N, int64_t S, const int32_t *seg_ptr,
+                                         const int32_t *seg_rel, const int32_t *seg_dst,
+                                         const int32_t *col_src, int32_t d_in, int32_t d_out, int32_t B,
+                                         const double *V, const double *a, const double *W0,
+                                         const double *H, double *pre, double *zq_out)
+{
+    double *y = (double *)calloc((size_t)N * B * d_in, sizeof(double));
+    double *z = (double *)malloc(sizeof(double) * (size_t)d_in);
+    for (int64_t s = 0; s < S; ++s) {
+        int32_t r = seg_rel[s], i = seg_dst[s];
+        double c = (double)(seg_ptr[s + 1] - seg_ptr[s]);
+        for (int32_t k = 0; k < d_in; ++k) z[k] = 0.0;
+        for (int32_t e = seg_ptr[s]; e < seg_ptr[s + 1]; ++e) {
+            const double *hj = H + (size_t)col_src[e] * d_in;
+            for (int32_t k = 0; k < d_in; ++k) z[k] += round_msg(hj[k], 1);
+        }
+        for (int32_t k = 0; k < d_in; ++k) z[k] = round_msg(z[k] / c, 1);
+        if (zq_out) memcpy(zq_out + (size_t)s * d_in, z, sizeof(double) * (size_t)d_in);
+        for (int32_t b = 0; b < B; ++b) {
+            double w = a[(size_t)r * B + b];
+            double *yb = y + ((size_t)i * B + b) * d_in;
+            for (int32_t k = 0; k < d_in; ++k) yb[k] += w * z[k];
+        }
+    }
+    for (int64_t i = 0; i < N; ++i) {
+        double *o = pre + (size_t)i * d_out;
+        for (int32_t c = 0; c < d_out; ++c) o[c] = 0.0;
+        for (int32_t k = 0; k < d_in; ++k) {
+            double h = round_msg(H[(size_t)i * d_in + k], 1);
+            const double *w = W0 + (size_t)k * d_out;
+            for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(w[c], 1);
+        }
+        for (int32_t b = 0; b < B; ++b)
+            for (int32_t k = 0; k < d_in; ++k) {
+                double yq = round_msg(y[((size_t)i * B + b) * d_in + k], 1);
+                const double *v = V + ((size_t)b * d_in + k) * d_out;
+                for (int32_t c = 0; c < d_out; ++c) o[c] += yq * round_msg(v[c], 1);
+            }
+    }
+    free(z);
+    free(y);
+}
+
+/*
  * One layer forward over the whole partition:
  *   pre_i = sum_r sum_{j in N_i^r} (1/c_{i,r}) h_j W_r + h_i W_0,   W_r = sum_b a_rb V_b
  *   h'_i  = act(pre_i)                        act: 0 identity, 1 ReLU
  * P_scratch is [N][B][d_out] doubles.  msg_bf16 != 0 models a workload whose projections are
- * a bf16 contraction with bf16 message storage (see round_msg); 0 keeps everything exact.
+ * a bf16 contraction with bf16 message storage (see round_msg); 2 models the bf16 pipeline that
+ * sums neighbours first (forward_aggregate_first_bf16); 0 keeps everything exact.
  */
 void orc_rgcn_layer_forward(int64_t N, int64_t S, const int32_t *seg_ptr, const int32_t *seg_rel,
                             const int32_t *seg_dst, const int32_t *col_src,
@@ -269,6 +322,11 @@ void orc_rgcn_layer_forward(int64_t N, int64_t S, const int32_t *seg_ptr, const 
                             int32_t msg_bf16,
                             const double *H, double *P_scratch, double *pre, double *Hout)
 {
+    if (msg_bf16 == 2) {
+        forward_aggregate_first_bf16(N, S, seg_ptr, seg_rel, seg_dst, col_src, d_in, d_out, B, V, a, W0, H, pre, NULL);
+        for (size_t q = 0; q < (size_t)N * d_out; ++q) Hout[q] = act_fwd(act, pre[q]);
+        return;
+    }
     project_all(N, d_in, d_out, B, V, H, P_scratch, msg_bf16);
     /* self-loop: h_i W_0 */
     for (int64_t i = 0; i < N; ++i) {
@@ -312,10 +370,39 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
                          double *pre_rows, double *out_rows)
 {
     double *pj = (double *)malloc(sizeof(double) * (size_t)d_out);
+    double *yrow = (double *)malloc(sizeof(double) * (size_t)B * d_in);
+    double *zrow = (double *)malloc(sizeof(double) * (size_t)d_in);
     for (int64_t q = 0; q < n_rows; ++q) {
         int32_t i = rows[q];
         double *o = pre_rows + (size_t)q * d_out;
         for (int32_t c = 0; c < d_out; ++c) o[c] = 0.0;
+        if (msg_bf16 == 2) {      /* the regrouped evaluation, see forward_aggregate_first_bf16 */
+            for (size_t x = 0; x < (size_t)B * d_in; ++x) yrow[x] = 0.0;
+            for (int64_t t = row_seg_ptr[q]; t < row_seg_ptr[q + 1]; ++t) {
+                int64_t s = row_seg[t];
+                double cnt = (double)(seg_ptr[s + 1] - seg_ptr[s]);
+                for (int32_t k = 0; k < d_in; ++k) zrow[k] = 0.0;
+                for (int32_t e = seg_ptr[s]; e < seg_ptr[s + 1]; ++e)
+                    for (int32_t k = 0; k < d_in; ++k)
+                        zrow[k] += round_msg((double)H[(size_t)col_src[e] * d_in + k], 1);
+                for (int32_t k = 0; k < d_in; ++k) zrow[k] = round_msg(zrow[k] / cnt, 1);
+                for (int32_t b = 0; b < B; ++b)
+                    for (int32_t k = 0; k < d_in; ++k)
+                        yrow[(size_t)b * d_in + k] += a[(size_t)seg_rel[s] * B + b] * zrow[k];
+            }
+            for (int32_t k = 0; k < d_in; ++k) {
+                double h = round_msg((double)H[(size_t)i * d_in + k], 1);
+                for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(W0[(size_t)k * d_out + c], 1);
+            }
+            for (int32_t b = 0; b < B; ++b)
+                for (int32_t k = 0; k < d_in; ++k) {
+                    double yq = round_msg(yrow[(size_t)b * d_in + k], 1);
+                    for (int32_t c = 0; c < d_out; ++c)
+                        o[c] += yq * round_msg(V[((size_t)b * d_in + k) * d_out + c], 1);
+                }
+            for (int32_t c = 0; c < d_out; ++c) out_rows[(size_t)q * d_out + c] = act_fwd(act, o[c]);
+            continue;
+        }
         for (int32_t k = 0; k < d_in; ++k) {
             double h = round_msg((double)H[(size_t)i * d_in + k], msg_bf16);
             for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(W0[(size_t)k * d_out + c], msg_bf16);
@@ -342,6 +429,8 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
         for (int32_t c = 0; c < d_out; ++c) out_rows[(size_t)q * d_out + c] = act_fwd(act, o[c]);
     }
     free(pj);
+    free(yrow);
+    free(zrow);
 }
 
 /*
@@ -353,6 +442,9 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
  *       dP[j][b][:] += a_rb w Gpre_i
  *   dV_b = H^T dP_b,                dH_j  += sum_b dP[j][b][:] V_b^T
  * P_scratch and dP_scratch are [N][B][d_out]; dH_in may be NULL.
+ * msg_bf16 == 1: the projected messages h_j V_b in da are the rounded ones the forward pass kept.
+ * msg_bf16 == 2: da_rb = sum_runs <z_{i,r} V_b, Gpre_i> with the rounded run means z the regrouped
+ * forward pass kept (the same sum, since sum_j (1/c) h_j V_b = z V_b).  All else is exact.
  */
 void orc_rgcn_layer_backward(int64_t N, int64_t S, const int32_t *seg_ptr, const int32_t *seg_rel,
                              const int32_t *seg_dst, const int32_t *col_src,
@@ -365,7 +457,7 @@ void orc_rgcn_layer_backward(int64_t N, int64_t S, const int32_t *seg_ptr, const
 {
     size_t nd_out = (size_t)N * d_out;
     for (size_t q = 0; q < nd_out; ++q) Gpre[q] = dHout[q] * act_grad(act, pre[q]);
-    project_all(N, d_in, d_out, B, V, H, P_scratch, msg_bf16);
+    project_all(N, d_in, d_out, B, V, H, P_scratch, msg_bf16 == 2 ? 0 : msg_bf16);
     memset(dP_scratch, 0, sizeof(double) * (size_t)N * B * d_out);
     memset(dV, 0, sizeof(double) * (size_t)B * d_in * d_out);
     memset(da, 0, sizeof(double) * (size_t)n_rel2 * B);
@@ -395,9 +487,31 @@ void orc_rgcn_layer_backward(int64_t N, int64_t S, const int32_t *seg_ptr, const
                 double *dpj = dP_scratch + ((size_t)j * B + b) * d_out;
                 double dot = 0.0, w = a[(size_t)r * B + b] * invc;
                 for (int32_t c = 0; c < d_out; ++c) { dot += pj[c] * g[c]; dpj[c] += w * g[c]; }
-                da[(size_t)r * B + b] += invc * dot;
+                if (msg_bf16 != 2) da[(size_t)r * B + b] += invc * dot;
             }
         }
+    }
+    if (msg_bf16 == 2) {
+        double *zq = (double *)malloc(sizeof(double) * (size_t)(S > 0 ? S : 1) * d_in);
+        double *scratch_pre = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1) * d_out);
+        forward_aggregate_first_bf16(N, S, seg_ptr, seg_rel, seg_dst, col_src, d_in, d_out, B, V, a, W0, H,
+                                     scratch_pre, zq);
+        for (int64_t s = 0; s < S; ++s) {
+            const double *g = Gpre + (size_t)seg_dst[s] * d_out;
+            const double *z = zq + (size_t)s * d_in;
+            for (int32_t b = 0; b < B; ++b) {
+                double dot = 0.0;
+                for (int32_t k = 0; k < d_in; ++k) {
+                    const double *v = V + ((size_t)b * d_in + k) * d_out;
+                    double t = 0.0;
+                    for (int32_t c = 0; c < d_out; ++c) t += v[c] * g[c];
+                    dot += z[k] * t;
+                }
+                da[(size_t)seg_rel[s] * B + b] += dot;
+            }
+        }
+        free(scratch_pre);
+        free(zq);
     }
     for (int64_t j = 0; j < N; ++j)
         for (int32_t b = 0; b < B; ++b) {

@@ -85,6 +85,8 @@ def _d(x):
     return np.ascontiguousarray(x, np.float64)
 
 
+# msg_bf16: False/0 exact; True/1 bf16 projections with bf16 message storage (project-first pipeline);
+# 2 the bf16 pipeline that sums neighbours first (run means, per-basis sums and weights rounded).
 def layer_forward(part, V, a, W0, act, H, msg_bf16=False):
     """One RGCN layer over the whole partition (Eq. 1-2). Returns (pre, H') in float64."""
     L = lib()
@@ -99,7 +101,7 @@ def layer_forward(part, V, a, W0, act, H, msg_bf16=False):
                              _p(part["seg_rel"], _I32), _p(part["seg_dst"], _I32),
                              _p(part["col_src"], _I32), C.c_int32(d_in), C.c_int32(d_out),
                              C.c_int32(B), _p(V, _F64), _p(a, _F64), _p(W0, _F64), C.c_int32(act),
-                             C.c_int32(1 if msg_bf16 else 0),
+                             C.c_int32(int(msg_bf16)),
                              _p(H, _F64), _p(P, _F64), _p(pre, _F64), _p(out, _F64))
     return pre, out
 
@@ -127,7 +129,7 @@ def layer_backward(part, V, a, W0, act, H, pre, dHout, need_dH=True, msg_bf16=Fa
                               _p(part["seg_rel"], _I32), _p(part["seg_dst"], _I32),
                               _p(part["col_src"], _I32), C.c_int32(d_in), C.c_int32(d_out),
                               C.c_int32(B), C.c_int32(a.shape[0]), _p(V, _F64), _p(a, _F64),
-                              _p(W0, _F64), C.c_int32(act), C.c_int32(1 if msg_bf16 else 0),
+                              _p(W0, _F64), C.c_int32(act), C.c_int32(int(msg_bf16)),
                               _p(H, _F64), _p(pre, _F64),
                               _p(dHout, _F64), _p(P, _F64), _p(dP, _F64), _p(G, _F64),
                               _p(dV, _F64), _p(da, _F64), _p(dW0, _F64),
@@ -168,7 +170,7 @@ def layer_rows(part, rows, V, a, W0, act, H_f32, msg_bf16=False):
                           _p(part["seg_ptr"], _I32), _p(part["seg_rel"], _I32),
                           _p(part["col_src"], _I32), C.c_int32(d_in), C.c_int32(d_out), C.c_int32(B),
                           _p(V, _F64), _p(a, _F64), _p(W0, _F64), C.c_int32(act),
-                          C.c_int32(1 if msg_bf16 else 0), _p(H_f32, _F32),
+                          C.c_int32(int(msg_bf16)), _p(H_f32, _F32),
                           _p(pre, _F64), _p(out, _F64))
     return pre, out
 

@@ -108,3 +108,57 @@ def euler_quantity(pre, H_in, W0, G, chunk=1 << 18):
             agg = np.asarray(pre[s:s + chunk][nz], np.float64) - np.asarray(H_in[s:s + chunk][nz], np.float64) @ W0
             q += float(np.sum(agg * g[nz]))
     return q
+
+
+# ---- the regrouped evaluation of Eq. 1-2 (run means z, per-basis sums y), sampled ----------------
+def round_bf16(x):
+    """float -> nearest bfloat16 (ties to even), returned as float64.  Bit arithmetic on the float32
+    pattern: add half a unit of the kept part, plus its lowest bit for ties, and drop 16 bits."""
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7fff + ((u >> 16) & 1)) & 0xffff0000).astype(np.uint32)
+    return r.view(np.float32).astype(np.float64).reshape(np.shape(x))
+
+
+def run_mean_rows(part, runs, H, bf16=False):
+    """z_s = (1/c_s) sum_{j in run s} h_j for the listed runs; with bf16, inputs are rounded first."""
+    out = np.zeros((len(runs), H.shape[1]))
+    for k, s in enumerate(runs):
+        src = part["col_src"][part["seg_ptr"][s]:part["seg_ptr"][s + 1]]
+        rows = np.asarray(H[src], np.float64)
+        if bf16:
+            rows = round_bf16(rows)
+        out[k] = rows.sum(0) / len(src)
+    return out
+
+
+def basis_sum_rows(part, rows, a, Z_of):
+    """y_{i,b} = sum over the runs (r, i) of destination i of a_rb z_{(r,i)}, for destinations `rows`.
+    Z_of(run_ids) returns the stored run means of those runs [n, d]."""
+    a = np.asarray(a, np.float64)
+    order = np.argsort(part["seg_dst"], kind="stable")
+    first = np.searchsorted(part["seg_dst"][order], rows, "left")
+    last = np.searchsorted(part["seg_dst"][order], rows, "right")
+    out = []
+    for f, l in zip(first, last):
+        runs = order[f:l]
+        z = np.asarray(Z_of(runs), np.float64) if len(runs) else np.zeros((0, 1))
+        out.append(np.einsum("sb,sk->bk", a[part["seg_rel"][runs]], z) if len(runs) else None)
+    d = next((o.shape[1] for o in out if o is not None), 1)
+    return np.stack([o if o is not None else np.zeros((a.shape[1], d)) for o in out])
+
+
+def coeff_grad_relations_runs(part, rels, Z_of, V, G):
+    """da[r][b] = sum over the runs s = (r, i) of relation r of <z_s V_b, G_i>  (the chain rule on
+    y_{i,b} = sum_r a_rb z_{i,r}, pre_i = sum_b y_{i,b} V_b + ...), for the listed relations."""
+    V = np.asarray(V, np.float64)
+    out = {}
+    for r in rels:
+        runs = np.nonzero(part["seg_rel"] == r)[0]
+        acc = np.zeros(V.shape[0])
+        for s in range(0, len(runs), 512):
+            rr = runs[s:s + 512]
+            z = np.asarray(Z_of(rr), np.float64)
+            g = np.asarray(G[part["seg_dst"][rr]], np.float64)
+            acc += np.einsum("sk,bkc,sc->b", z, V, g)
+        out[int(r)] = acc
+    return out

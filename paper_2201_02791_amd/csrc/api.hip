@@ -72,7 +72,7 @@ namespace {
 struct WsLayout {
     std::vector<size_t> off_P, off_H;   // per layer: projected messages, layer output
     std::vector<size_t> off_Hbf, off_Wbf, off_WbfT;   // bf16 workloads: bf16 copies of layer input and weights
-    std::vector<size_t> off_Z;          // aggregate-first layers: run means [S][d_in]
+    std::vector<size_t> off_Z, off_Wst; // aggregate-first layers: run means [S][d_in]; bf16: stacked weights, transposed
     size_t off_Y = 0, off_C = 0;        // aggregate-first layers: Y [N][B*d_in], C [2R][d_in*d_out] (shared)
     size_t off_self = 0, off_G = 0, off_dP = 0, off_dHa = 0, off_dHb = 0, off_seg = 0, off_part = 0, total = 0;
 };
@@ -96,8 +96,8 @@ int check_layers(const kge_partition *p, const kge_layer *layers, int32_t n_laye
         KGE_REQUIRE(L.act == KGE_ACT_IDENTITY || L.act == KGE_ACT_RELU, KGE_EINVAL, "layer %d: bad act", l);
         KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.order == KGE_ORDER_AGGREGATE_FIRST, KGE_EINVAL,
                     "layer %d: bad order", l);
-        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || (msg_dtype == KGE_MSG_F32 && L.d_in <= 256), KGE_EINVAL,
-                    "layer %d: the aggregate-first order needs fp32 messages and d_in <= 256", l);
+        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.d_in <= dmax, KGE_EINVAL,
+                    "layer %d: the aggregate-first order needs d_in <= %d", l, dmax);
         KGE_REQUIRE(l == 0 || L.d_in == layers[l - 1].d_out, KGE_EINVAL,
                     "layer %d: d_in does not match the previous layer's d_out", l);
         KGE_REQUIRE(((uintptr_t)L.V % 16) == 0 && ((uintptr_t)L.W0 % 16) == 0, KGE_EINVAL,
@@ -113,14 +113,18 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
     const bool bf = msg_dtype == KGE_MSG_BF16;
     size_t max_nc = 0;
     w->off_P.assign(n_layers, 0); w->off_H.resize(n_layers); w->off_Z.assign(n_layers, 0);
+    w->off_Wst.assign(n_layers, 0);
     size_t max_y = 0, max_c = 0, max_zd = 0;
     w->off_Hbf.assign(n_layers, 0); w->off_Wbf.assign(n_layers, 0); w->off_WbfT.assign(n_layers, 0);
     for (int l = 0; l < n_layers; ++l) {
         const kge_layer &L = layers[l];
         const bool agg = L.order == KGE_ORDER_AGGREGATE_FIRST;
         if (agg) {
-            w->off_Z[l] = cur; cur = align_up(cur + (size_t)p->n_seg * L.d_in * 4, 256);
-            if (N * L.n_bases * L.d_in * 4 > max_y) max_y = N * L.n_bases * L.d_in * 4;
+            w->off_Z[l] = cur; cur = align_up(cur + (size_t)p->n_seg * L.d_in * ep, 256);
+            // fp32: Y [N][B d_in]; bf16: X = [Y | Hbf] [N][(B+1) d_in]
+            const size_t yb = bf ? N * (L.n_bases + 1) * L.d_in * 2 : N * L.n_bases * L.d_in * 4;
+            if (yb > max_y) max_y = yb;
+            if (bf) { w->off_Wst[l] = cur; cur = align_up(cur + (size_t)(L.n_bases + 1) * L.d_in * L.d_out * 2, 256); }
             const size_t cb = (size_t)2 * p->n_relations * L.d_in * L.d_out * 4;
             if (cb > max_c) max_c = cb;
             if ((size_t)L.d_in > max_zd) max_zd = L.d_in;
@@ -200,10 +204,12 @@ extern "C" int kge_workspace_slice(const kge_partition *p, const kge_layer *laye
         *offset = w.off_P[layer]; *bytes = N * L.n_bases * L.d_out * ep; break;
     case KGE_WS_Z:
         KGE_REQUIRE(L.order == KGE_ORDER_AGGREGATE_FIRST, KGE_EINVAL, "only aggregate-first layers keep run means");
-        *offset = w.off_Z[layer]; *bytes = (size_t)p->n_seg * L.d_in * 4; break;
+        *offset = w.off_Z[layer]; *bytes = (size_t)p->n_seg * L.d_in * ep; break;
     case KGE_WS_Y:
         KGE_REQUIRE(L.order == KGE_ORDER_AGGREGATE_FIRST, KGE_EINVAL, "only aggregate-first layers have Y");
-        *offset = w.off_Y; *bytes = N * L.n_bases * L.d_in * 4; break;
+        *offset = w.off_Y;
+        *bytes = msg_dtype == KGE_MSG_BF16 ? N * (size_t)(L.n_bases + 1) * L.d_in * 2 : N * (size_t)L.n_bases * L.d_in * 4;
+        break;
     case KGE_WS_H: *offset = w.off_H[layer]; *bytes = N * L.d_out * 4; break;
     case KGE_WS_G: *offset = w.off_G; *bytes = N * L.d_out * 4; break;
     case KGE_WS_DP:
@@ -240,15 +246,33 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
         void *P = ws + w.off_P[l];
         float *Hl = (float *)(ws + w.off_H[l]);
         if (L.order == KGE_ORDER_AGGREGATE_FIRST) {
-            float *Z = (float *)(ws + w.off_Z[l]);
-            float *Y = (float *)(ws + w.off_Y);
+            void *Z = ws + w.off_Z[l];
+            void *Y = ws + w.off_Y;
+            float *out2 = l == n_layers - 1 ? H_out : nullptr;
             const uint8_t *act_l = kge_cgraph_layer(cg, l);
-            rc = launch_run_mean(p, Hin, L.d_in, Z, part, act_l, st);
-            if (rc != KGE_OK) return rc;
-            rc = launch_aggregate_runs(p, Z, L.a, L.n_bases, L.d_in, Y, (int64_t)L.n_bases * L.d_in, 0, part, act_l, st);
-            if (rc != KGE_OK) return rc;
-            rc = launch_combine(Y, Hin, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, L.act, act_l, Hl,
-                                l == n_layers - 1 ? H_out : nullptr, st);
+            if (bf) {
+                void *Hbf = ws + w.off_Hbf[l], *Wbf = ws + w.off_Wbf[l], *WbfT = ws + w.off_WbfT[l], *WstT = ws + w.off_Wst[l];
+                rc = launch_cvt_rows_bf16(Hin, p->n_vert * (int64_t)L.d_in, Hbf, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_cvt_weights_bf16(L.V, L.W0, L.d_in, L.d_out, L.n_bases, Wbf, WbfT, st);   // backward reads Wbf
+                if (rc != KGE_OK) return rc;
+                rc = launch_cvt_wstack_bf16(L.V, L.W0, L.d_in, L.d_out, L.n_bases, WstT, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_run_mean(p, Hbf, L.d_in, Z, 1, part, act_l, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_aggregate_runs(p, Z, L.a, L.n_bases, L.d_in, Y, (int64_t)(L.n_bases + 1) * L.d_in, 1, part, act_l, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_append_g_bf16(Hin, p->n_vert, L.d_in, L.n_bases, Y, st);      // X = [Y | Hbf]
+                if (rc != KGE_OK) return rc;
+                rc = launch_combine_bf16(Y, p->n_vert, L.d_in, L.d_out, L.n_bases, WstT, L.act, act_l, Hl, out2, st);
+            } else {
+                rc = launch_run_mean(p, Hin, L.d_in, Z, 0, part, act_l, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_aggregate_runs(p, Z, L.a, L.n_bases, L.d_in, Y, (int64_t)L.n_bases * L.d_in, 0, part, act_l, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_combine((const float *)Y, Hin, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, L.act, act_l,
+                                    Hl, out2, st);
+            }
             if (rc != KGE_OK) return rc;
             Hin = Hl;
             continue;
@@ -309,11 +333,15 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
             if (rc != KGE_OK) return rc;
             Gl = G;
         }
-        if (L.order == KGE_ORDER_AGGREGATE_FIRST)
-            rc = launch_coeff_grad_runs(p, (const float *)(ws + w.off_Z[l]), Gl, L.d_in, L.d_out, L.n_bases, L.V,
-                                        (float *)(ws + w.off_C), grads[l].da, st);
-        else
+        const bool agg = L.order == KGE_ORDER_AGGREGATE_FIRST;
+        float *C = (float *)(ws + w.off_C);
+        if (agg && !bf) {
+            rc = launch_rel_outer(p, (const float *)(ws + w.off_Z[l]), Gl, L.d_in, L.d_out, C, st);
+            if (rc != KGE_OK) return rc;
+            rc = launch_coeff_contract(p, C, L.V, L.d_in, L.d_out, L.n_bases, grads[l].da, st);
+        } else if (!agg) {
             rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, part, grads[l].da, kge_cgraph_layer(cg, l), st);
+        }
         if (rc != KGE_OK) return rc;
         const int64_t bd = (int64_t)L.n_bases * L.d_out;
         rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf ? bd + L.d_out : bd, bf, part,
@@ -322,6 +350,12 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
         if (bf) {
             rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, L.n_bases, dP, st);
             if (rc != KGE_OK) return rc;
+            if (agg) {       // the coefficient gradient reads the bf16 copy of G that was just appended
+                rc = launch_rel_outer_bf16(p, ws + w.off_Z[l], (const uint16_t *)dP + bd, bd + L.d_out, L.d_in, L.d_out, C, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_coeff_contract(p, C, L.V, L.d_in, L.d_out, L.n_bases, grads[l].da, st);
+                if (rc != KGE_OK) return rc;
+            }
             rc = launch_weight_grad_bf16(ws + w.off_Hbf[l], p->n_vert, L.d_in, L.d_out, L.n_bases, dP,
                                          grads[l].dV, grads[l].dW0, st);
         } else {

@@ -134,13 +134,14 @@ const uint8_t *kge_cgraph_layer(const kge_cgraph *cg, int32_t layer);
 int kge_cgraph_check(const kge_partition *p, const kge_cgraph *cg, int32_t n_layers);
 
 // gather.hip, aggregate-first order ------------------------------------------
-// Z[s][:] = invc_s sum_{j in run s} H[j][:]  (fp32 [S][d]); runs into inactive destinations get zeros;
-// `partial`: [hv_seg.n_units][d] floats
-int launch_run_mean(const kge_partition *p, const float *H, int32_t d, float *Z, float *partial,
+// Z[s][:] = invc_s sum_{j in run s} H[j][:]  ([S][d]; H and Z both fp32 or, with bf16 != 0, both bf16;
+// sums in fp32); runs into inactive destinations get zeros; `partial`: [hv_seg.n_units][d] floats
+int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, int bf16, float *partial,
                     const uint8_t *active, hipStream_t st);
 // Y[i][b][:] = sum_{runs (r,i) of i} a[r][b] Z[run][:]; rows are `ld` elements apart; rows with
 // row_active[i] == 0 are left unwritten; `partial`: [hv_dr.n_units][B*d] floats
-int launch_aggregate_runs(const kge_partition *p, const float *Z, const float *a, int32_t B, int32_t d,
+// (Z and Y are fp32, or both bf16 when msg_bf16 != 0)
+int launch_aggregate_runs(const kge_partition *p, const void *Z, const float *a, int32_t B, int32_t d,
                           void *Y, int64_t ld, int msg_bf16, float *partial, const uint8_t *row_active,
                           hipStream_t st);
 
@@ -149,10 +150,23 @@ int launch_aggregate_runs(const kge_partition *p, const float *Z, const float *a
 int launch_combine(const float *Y, const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
                    const float *V, const float *W0, int act, const uint8_t *row_active, float *out,
                    float *out2, hipStream_t st);
-// C[r] (d_in x d_out) = sum_{runs s of relation r} Z[s]^T G[seg_dst[s]];  da[r][b] = <C[r], V_b>
-// C: [2R][d_in*d_out] floats of scratch
-int launch_coeff_grad_runs(const kge_partition *p, const float *Z, const float *G, int32_t d_in,
-                           int32_t d_out, int32_t B, const float *V, float *C, float *da, hipStream_t st);
+// C[r] (d_in x d_out; [2R][d_in*d_out] floats, zeroed inside) = sum_{runs s of relation r} Z[s]^T G[seg_dst[s]]
+int launch_rel_outer(const kge_partition *p, const float *Z, const float *G, int32_t d_in, int32_t d_out,
+                     float *C, hipStream_t st);
+// da[r][b] = <C[r], V_b>   (fp32)
+int launch_coeff_contract(const kge_partition *p, const float *C, const float *V, int32_t d_in, int32_t d_out,
+                          int32_t B, float *da, hipStream_t st);
+
+// gemm_bf16.hip, aggregate-first order ----------------------------------------
+// [V_1; ..; V_B; W0] -> WstT bf16 [d_out][(B+1) d_in]
+int launch_cvt_wstack_bf16(const float *V, const float *W0, int32_t d_in, int32_t d_out, int32_t B, void *WstT,
+                           hipStream_t st);
+// out = act(X WstT^T), X = [Y | Hbf] bf16 [N][(B+1) d_in]; zero rows where row_active[i] == 0
+int launch_combine_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const void *WstT,
+                        int act, const uint8_t *row_active, float *out, float *out2, hipStream_t st);
+// the same C from bf16 operands: Zbf [S][d_in]; Gbf rows of d_out elements, ldg elements apart
+int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const void *Gbf, int64_t ldg, int32_t d_in,
+                          int32_t d_out, float *C, hipStream_t st);
 
 // sampler_score.hip --------------------------------------------------------
 int launch_sample_negatives(const kge_partition *p, const int32_t *pos, int64_t n_pos, int32_t n_neg,

@@ -243,13 +243,14 @@ __global__ void k_act_backward(const float4 *__restrict__ dH, const float4 *__re
 // A G row (fp32) is covered by LPR lanes x 4 floats.  Of the 64/LPR lane groups, GBT take
 // different bases (NB bases each, so a chunk is GBT*NB bases) and the other 64/(LPR*GBT) take
 // different edges; UE rounds of edges are in flight at a time.
-template <bool BF16, int LPR, int NB, int UE>
+// GIN: the gathered rows are bf16 instead of fp32.
+template <bool BF16, bool GIN, int LPR, int NB, int UE>
 __global__ __launch_bounds__(64 * WPB) void k_gather_t(
     const int32_t *__restrict__ sm_ptr, const int32_t *__restrict__ sm_dst,
     const int32_t *__restrict__ sm_rel, const float *__restrict__ sm_invc, int64_t N,
     int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
     const int32_t *__restrict__ unit_hv,
-    const float *__restrict__ G, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_chunks,
+    const void *__restrict__ Gv, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_chunks,
     int32_t gbt_count, void *__restrict__ dP, int64_t ld, float *__restrict__ partial,
     const uint8_t *__restrict__ active, const uint8_t *__restrict__ row_active)
 {
@@ -306,7 +307,15 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
                 w[u] = live ? ww : 0.f;
                 arow[u] = a + (int64_t)rel * B;
                 gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (live && kact) gv[u] = *reinterpret_cast<const float4 *>(G + (int64_t)dst * d + kl * 4);
+                if (live && kact) {
+                    if (GIN) {
+                        const uint2 x = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(Gv) + (int64_t)dst * d + kl * 4);
+                        gv[u] = make_float4(__uint_as_float(x.x << 16), __uint_as_float(x.x & 0xffff0000u),
+                                            __uint_as_float(x.y << 16), __uint_as_float(x.y & 0xffff0000u));
+                    } else {
+                        gv[u] = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(Gv) + (int64_t)dst * d + kl * 4);
+                    }
+                }
             }
 #pragma unroll
             for (int u = 0; u < UE; ++u)
@@ -352,13 +361,13 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
 // the edges two at a time (lane half h supplies edge k+h: 32 coefficients and 32 columns of G).
 typedef float gt_floatx16 __attribute__((ext_vector_type(16)));
 
-template <bool BF16, int NBT>
+template <bool BF16, bool GIN, int NBT>
 __global__ __launch_bounds__(64 * WPB) void k_gather_t_mfma(
     const int32_t *__restrict__ sm_ptr, const int32_t *__restrict__ sm_dst,
     const int32_t *__restrict__ sm_rel, const float *__restrict__ sm_invc, int64_t N,
     int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
     const int32_t *__restrict__ unit_hv,
-    const float *__restrict__ G, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_bchunks,
+    const void *__restrict__ Gv, const float *__restrict__ a, int32_t B, int32_t d, int32_t n_bchunks,
     int32_t n_cchunks, void *__restrict__ dP, int64_t ld, float *__restrict__ partial,
     const uint8_t *__restrict__ active, const uint8_t *__restrict__ row_active)
 {
@@ -412,7 +421,10 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t_mfma(
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const int col = cbase + c * 32 + l32;
-                    gb[u][c] = (live && col < d) ? G[(int64_t)dst * d + col] : 0.f;
+                    gb[u][c] = 0.f;
+                    if (live && col < d)
+                        gb[u][c] = GIN ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(Gv)[(int64_t)dst * d + col] << 16)
+                                       : reinterpret_cast<const float *>(Gv)[(int64_t)dst * d + col];
                 }
             }
 #pragma unroll
@@ -496,14 +508,16 @@ __global__ void k_gather_t_finish(int32_t n_hv, const int32_t *__restrict__ hv_r
 // One wavefront per (relation, destination) run s (or per unit of a long run):
 //   Z[s][:] = invc_s * sum_{j in run s} H[j][:]
 // the normalised neighbour sum of Eq. 1 for one relation, before any weight is applied.
-template <int LPR>
+// BF16: the input rows and Z are bf16 (sums stay fp32).
+template <bool BF16, int LPR>
 __global__ __launch_bounds__(64 * WPB) void k_run_mean(
     const int32_t *__restrict__ seg_ptr, const int32_t *__restrict__ seg_dst,
     const float *__restrict__ inv_c, const int32_t *__restrict__ col_src, int64_t S,
     int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
-    const int32_t *__restrict__ unit_hv, const float *__restrict__ H, int32_t d,
-    float *__restrict__ Z, float *__restrict__ partial, const uint8_t *__restrict__ active)
+    const int32_t *__restrict__ unit_hv, const void *__restrict__ H, int32_t d,
+    void *__restrict__ Z, float *__restrict__ partial, const uint8_t *__restrict__ active)
 {
+    constexpr int VEC = MsgRow<BF16>::VEC;
     constexpr int NG = 64 / LPR;
     constexpr int U = (NG >= 8) ? 2 : (NG >= 2 ? 4 : 8);     // row loads in flight per lane
     const int lane = threadIdx.x & 63;
@@ -511,46 +525,62 @@ __global__ __launch_bounds__(64 * WPB) void k_run_mean(
     const RowWork rw = row_work(wid, seg_ptr, S, n_units, hv_row, hv_unit_ptr, unit_hv);
     if (rw.row < 0) return;
     const int kl = lane % LPR, g = lane / LPR;
-    const bool kact = kl * 4 < d;
-    if (active && !active[seg_dst[rw.row]]) {           // destination outside the sub-graph
-        if (rw.unit < 0 && g == 0 && kact)
-            *reinterpret_cast<float4 *>(Z + rw.row * d + kl * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
-        return;
-    }
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    const int len = rw.end - rw.beg;
+    const bool kact = kl * VEC < d;
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+    const bool skip = active && !active[seg_dst[rw.row]];     // destination outside the sub-graph: zeros
+    if (skip && rw.unit >= 0) return;
+    const int len = skip ? 0 : rw.end - rw.beg;
     for (int e0 = 0; e0 < len; e0 += NG * U) {
-        float4 x[U];
+        uint4 x[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int el = e0 + u * NG + g;
-            x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            x[u] = make_uint4(0u, 0u, 0u, 0u);
             if (el < len && kact) {
                 const int32_t src = col_src[rw.beg + el];
-                x[u] = *reinterpret_cast<const float4 *>(H + (int64_t)src * d + kl * 4);
+                x[u] = MsgRow<BF16>::load_raw(H, (int64_t)src * d + kl * VEC);
             }
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) { acc.x += x[u].x; acc.y += x[u].y; acc.z += x[u].z; acc.w += x[u].w; }
+        for (int u = 0; u < U; ++u) {
+            float val[VEC];
+            MsgRow<BF16>::unpack(x[u], val);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] += val[v];
+        }
     }
 #pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) {
-        acc.x += __shfl_xor(acc.x, off, 64); acc.y += __shfl_xor(acc.y, off, 64);
-        acc.z += __shfl_xor(acc.z, off, 64); acc.w += __shfl_xor(acc.w, off, 64);
-    }
+    for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] += __shfl_xor(acc[v], off, 64);
     if (g != 0 || !kact) return;
     if (rw.unit >= 0) {
-        *reinterpret_cast<float4 *>(partial + (int64_t)rw.unit * d + kl * 4) = acc;
+#pragma unroll
+        for (int v4 = 0; v4 < VEC; v4 += 4)
+            *reinterpret_cast<float4 *>(partial + (int64_t)rw.unit * d + kl * VEC + v4) =
+                make_float4(acc[v4], acc[v4 + 1], acc[v4 + 2], acc[v4 + 3]);
+        return;
+    }
+    const float w = skip ? 0.f : inv_c[rw.row];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] *= w;
+    if (BF16) {
+        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(Z) + rw.row * d + kl * VEC) =
+            make_uint4(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
+                       pack_bf16x2(acc[4 % VEC], acc[5 % VEC]), pack_bf16x2(acc[6 % VEC], acc[7 % VEC]));
     } else {
-        const float w = inv_c[rw.row];
-        *reinterpret_cast<float4 *>(Z + rw.row * d + kl * 4) = make_float4(w * acc.x, w * acc.y, w * acc.z, w * acc.w);
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(Z) + rw.row * d + kl * VEC) =
+            make_float4(acc[0], acc[1], acc[2], acc[3]);
     }
 }
 
 // Long runs: Z[s] = invc_s * sum of the run's unit partials.  One thread per float4.
+template <bool BF16>
 __global__ void k_run_mean_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
                                   const int32_t *__restrict__ hv_unit_ptr, const float *__restrict__ partial,
-                                  const float *__restrict__ inv_c, int32_t d, float *__restrict__ Z,
+                                  const float *__restrict__ inv_c, int32_t d, void *__restrict__ Z,
                                   const int32_t *__restrict__ seg_dst, const uint8_t *__restrict__ active)
 {
     const int d4 = d >> 2;
@@ -568,7 +598,11 @@ __global__ void k_run_mean_finish(int32_t n_hv, const int32_t *__restrict__ hv_r
         const float w = inv_c[row];
         s.x *= w; s.y *= w; s.z *= w; s.w *= w;
     }
-    *reinterpret_cast<float4 *>(Z + row * d + k4) = s;
+    if (BF16)
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(Z) + row * d + k4) =
+            make_uint2(pack_bf16x2(s.x, s.y), pack_bf16x2(s.z, s.w));
+    else
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(Z) + row * d + k4) = s;
 }
 
 // ------------------------------------------------------------------ coefficient gradient
@@ -777,8 +811,8 @@ struct TView {
     const char *name;
 };
 
-template <bool BF16, int LPR>
-static int launch_gather_t_nb(const TView &vw, const float *G, const float *a, int32_t B, int32_t d,
+template <bool BF16, bool GIN, int LPR>
+static int launch_gather_t_nb(const TView &vw, const void *G, const float *a, int32_t B, int32_t d,
                               void *dP, int64_t ld, float *partial, const uint8_t *active,
                               const uint8_t *row_active, hipStream_t st)
 {
@@ -795,7 +829,7 @@ static int launch_gather_t_nb(const TView &vw, const float *G, const float *a, i
         const int n_chunks = (B + gbt * NBV - 1) / (gbt * NBV);                                       \
         const int64_t waves = (N + hx.n_units) * n_chunks;                                            \
         KGE_REQUIRE(cdiv(waves, WPB) < 0x7fffffffLL, KGE_ERANGE, "grid too large");                   \
-        k_gather_t<BF16, LPR, NBV, UEV><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(              \
+        k_gather_t<BF16, GIN, LPR, NBV, UEV><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(              \
             vw.ptr, vw.idx, vw.rel, vw.w, N, hx.n_units, hx.hv_row, hx.hv_unit_ptr,                   \
             hx.unit_hv, G, a, B, d, n_chunks, gbt, dP, ld, partial, active, row_active);              \
     }
@@ -809,10 +843,11 @@ static int launch_gather_t_nb(const TView &vw, const float *G, const float *a, i
     return KGE_OK;
 }
 
-static int launch_tview(const TView &vw, const float *G, const float *a, int32_t B, int32_t d,
+static int launch_tview(const TView &vw, const void *G, int g_bf16, const float *a, int32_t B, int32_t d,
                         void *dP, int64_t ld, int msg_bf16, float *partial, const uint8_t *active,
                         const uint8_t *row_active, hipStream_t st)
 {
+    KGE_REQUIRE(!g_bf16 || msg_bf16, KGE_EINVAL, "bf16 input rows are only used with bf16 output");
     if (vw.n_rows == 0) return KGE_OK;
     const int lpr = pow2_at_least((d + 3) / 4);
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the transposed aggregation kernel", d);
@@ -826,12 +861,14 @@ static int launch_tview(const TView &vw, const float *G, const float *a, int32_t
         KGE_PROF(vw.name, st);
 #define GTM_ARGS vw.ptr, vw.idx, vw.rel, vw.w, vw.n_rows, hxm.n_units, hxm.hv_row, hxm.hv_unit_ptr, \
                  hxm.unit_hv, G, a, B, d, n_bchunks, n_cchunks, dP, ld, partial, active, row_active
-        if (msg_bf16) k_gather_t_mfma<true, 1><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(GTM_ARGS);
-        else k_gather_t_mfma<false, 1><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(GTM_ARGS);
+        if (g_bf16) k_gather_t_mfma<true, true, 1><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(GTM_ARGS);
+        else if (msg_bf16) k_gather_t_mfma<true, false, 1><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(GTM_ARGS);
+        else k_gather_t_mfma<false, false, 1><<<(unsigned)cdiv(waves, WPB), 64 * WPB, 0, st>>>(GTM_ARGS);
 #undef GTM_ARGS
         KGE_LAUNCH_CHECK();
-    } else if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, L>(vw, G, a, B, d, dP, ld, partial, active, row_active, st))); }
-    else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, L>(vw, G, a, B, d, dP, ld, partial, active, row_active, st))); }
+    } else if (g_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, true, L>(vw, G, a, B, d, dP, ld, partial, active, row_active, st))); }
+    else if (msg_bf16) { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<true, false, L>(vw, G, a, B, d, dP, ld, partial, active, row_active, st))); }
+    else { DISPATCH_LPR(lpr, (rc = launch_gather_t_nb<false, false, L>(vw, G, a, B, d, dP, ld, partial, active, row_active, st))); }
     if (rc != KGE_OK) return rc;
     const kge_heavy_index &hx = *vw.hx;
     if (hx.n_hv > 0) {
@@ -850,16 +887,16 @@ int launch_gather_transpose(const kge_partition *p, const float *G, const float 
                             hipStream_t st)
 {
     const TView vw{p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, p->n_vert, &p->hv_sm, "gather_t"};
-    return launch_tview(vw, G, a, B, d, dP, ld, msg_bf16, partial, active, nullptr, st);
+    return launch_tview(vw, G, 0, a, B, d, dP, ld, msg_bf16, partial, active, nullptr, st);
 }
 
 // Y[i][b][:] = sum over the runs (r, i) of destination i of a[r][b] Z[run][:]
-int launch_aggregate_runs(const kge_partition *p, const float *Z, const float *a, int32_t B, int32_t d,
+int launch_aggregate_runs(const kge_partition *p, const void *Z, const float *a, int32_t B, int32_t d,
                           void *Y, int64_t ld, int msg_bf16, float *partial, const uint8_t *row_active,
                           hipStream_t st)
 {
     const TView vw{p->dr_ptr, p->dr_seg, p->dr_rel, nullptr, p->n_vert, &p->hv_dr, "aggregate"};
-    return launch_tview(vw, Z, a, B, d, Y, ld, msg_bf16, partial, nullptr, row_active, st);
+    return launch_tview(vw, Z, msg_bf16, a, B, d, Y, ld, msg_bf16, partial, nullptr, row_active, st);
 }
 
 template <bool BF16, int LPR>
@@ -917,28 +954,33 @@ int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const
     return KGE_OK;
 }
 
-// Z[s][:] = invc_s * sum_{j in run s} H[j][:]   (fp32 [S][d]); `partial`: [hv_seg.n_units][d] floats
-int launch_run_mean(const kge_partition *p, const float *H, int32_t d, float *Z, float *partial,
+// Z[s][:] = invc_s * sum_{j in run s} H[j][:]; H and Z fp32, or both bf16; `partial`: [hv_seg.n_units][d] floats
+int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, int bf16, float *partial,
                     const uint8_t *active, hipStream_t st)
 {
     const int64_t S = p->n_seg;
     if (S == 0) return KGE_OK;
-    const int lpr = pow2_at_least((d + 3) / 4);
+    const int vec = bf16 ? 8 : 4;
+    const int lpr = pow2_at_least((d + vec - 1) / vec);
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the run-mean kernel", d);
     const kge_heavy_index &hx = p->hv_seg;
     const unsigned grid = (unsigned)cdiv(S + hx.n_units, WPB);
     {
         KGE_PROF("run_mean", st);
-        DISPATCH_LPR(lpr, (k_run_mean<L><<<grid, 64 * WPB, 0, st>>>(p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S,
-                                                                    hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv,
-                                                                    H, d, Z, partial, active)));
+#define RM_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, \
+                H, d, Z, partial, active
+        if (bf16) { DISPATCH_LPR(lpr, (k_run_mean<true, L><<<grid, 64 * WPB, 0, st>>>(RM_ARGS))); }
+        else { DISPATCH_LPR(lpr, (k_run_mean<false, L><<<grid, 64 * WPB, 0, st>>>(RM_ARGS))); }
+#undef RM_ARGS
     }
     KGE_LAUNCH_CHECK();
     if (hx.n_hv > 0) {
         KGE_PROF("run_mean_fin", st);
         const int64_t n = (int64_t)hx.n_hv * (d / 4);
-        k_run_mean_finish<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial,
-                                                                 p->inv_c, d, Z, p->seg_dst, active);
+        if (bf16) k_run_mean_finish<true><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial,
+                                                                                p->inv_c, d, Z, p->seg_dst, active);
+        else k_run_mean_finish<false><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial,
+                                                                             p->inv_c, d, Z, p->seg_dst, active);
         KGE_LAUNCH_CHECK();
     }
     return KGE_OK;

@@ -358,16 +358,14 @@ int launch_combine(const float *Y, const float *H, int64_t N, int32_t d_in, int3
     return KGE_OK;
 }
 
-int launch_coeff_grad_runs(const kge_partition *p, const float *Z, const float *G, int32_t d_in,
-                           int32_t d_out, int32_t B, const float *V, float *C, float *da, hipStream_t st)
+int launch_rel_outer(const kge_partition *p, const float *Z, const float *G, int32_t d_in, int32_t d_out,
+                     float *C, hipStream_t st)
 {
     const int64_t R2 = 2 * (int64_t)p->n_relations;
     const int64_t dd = (int64_t)d_in * d_out;
-    int rc = launch_fill_zero(da, sizeof(float) * (size_t)R2 * B, st);
+    int rc = launch_fill_zero(C, sizeof(float) * (size_t)R2 * dd, st);
     if (rc != KGE_OK) return rc;
-    if (p->n_seg == 0) return KGE_OK;
-    rc = launch_fill_zero(C, sizeof(float) * (size_t)R2 * dd, st);
-    if (rc != KGE_OK) return rc;
+    if (p->n_seg == 0 || p->n_relc == 0) return KGE_OK;
     KGE_REQUIRE(p->n_relc <= 65535, KGE_ERANGE, "too many relation chunks (%d) for one launch", p->n_relc);
     {
         dim3 grid((unsigned)cdiv(d_in, BM), (unsigned)cdiv(d_out, BN), (unsigned)p->n_relc);
@@ -379,6 +377,17 @@ int launch_coeff_grad_runs(const kge_partition *p, const float *Z, const float *
             sa, sb, ep, p->n_seg, 0, p->relc_rel, p->relc_beg, p->relc_end);
         KGE_LAUNCH_CHECK();
     }
+    return KGE_OK;
+}
+
+int launch_coeff_contract(const kge_partition *p, const float *C, const float *V, int32_t d_in, int32_t d_out,
+                          int32_t B, float *da, hipStream_t st)
+{
+    const int64_t R2 = 2 * (int64_t)p->n_relations;
+    const int64_t dd = (int64_t)d_in * d_out;
+    int rc = launch_fill_zero(da, sizeof(float) * (size_t)R2 * B, st);
+    if (rc != KGE_OK) return rc;
+    if (p->n_seg == 0) return KGE_OK;
     {
         const int64_t tiles = cdiv(R2, BM) * cdiv(B, BN);
         int64_t splits = cdiv(512, tiles);

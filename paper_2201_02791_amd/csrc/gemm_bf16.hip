@@ -10,6 +10,12 @@
 //   input_grad   dH         = X    (N x nc) *  Wbf^T    both operands k-contiguous
 //   weight_grad  d[V | W0]  = Hbf^T * X                 both operands k-strided (k = vertex)
 //
+// and for layers that aggregate before they project:
+//
+//   combine      H' = act([Y | Hbf] * WstT^T)             both operands k-contiguous, K = (B+1) d_in
+//   rel_outer    C_r = sum_{runs s of r} Zbf[s]^T Gbf[dst(s)]   k-strided (k = run), grouped by relation,
+//                                                        B rows picked through the run -> destination list
+//
 // Block tile 128 x 256 x 32, 4 wavefronts in a 2 x 2 grid, each owning 64 x 128 = 2 x 4 MFMA
 // tiles (128 accumulator registers, two blocks per CU).  LDS holds A as [m][k] and B as [n][k],
 // k contiguous, rows padded to 80 bytes so the 16-byte operand reads of a half-wavefront touch
@@ -38,8 +44,9 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)   // two fp32 -> p
 }
 
 // Row-major bf16 matrix.  oct: 8 consecutive elements (16 bytes); pair: 2 (4 bytes).  Out of range -> 0.
+// `idx` (optional): logical row r is stored row idx[r].
 struct MatBF {
-    const uint16_t *p; int64_t rows; int32_t cols; int64_t ld;
+    const uint16_t *p; int64_t rows; int32_t cols; int64_t ld; const int32_t *idx;
     __device__ __forceinline__ uint4 oct(int64_t r, int32_t c) const
     {
         if (r >= rows || c >= cols) return make_uint4(0u, 0u, 0u, 0u);
@@ -48,13 +55,15 @@ struct MatBF {
     __device__ __forceinline__ uint32_t pair(int64_t r, int32_t c) const
     {
         if (r >= rows || c >= cols) return 0u;
-        return *reinterpret_cast<const uint32_t *>(p + r * ld + c);
+        const int64_t rr = idx ? (int64_t)idx[r] : r;
+        return *reinterpret_cast<const uint32_t *>(p + rr * ld + c);
     }
 };
 
 struct EpiProjectStaged {     // columns < bd -> P (bf16), the rest -> Self (fp32); through LDS
     static constexpr bool staged = true;
     uint16_t *P; float *Self; int64_t rows; int32_t d_out, bd;
+    __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store8(int64_t m, int32_t n, const float4 &x, const float4 &y) const
     {
         if (m >= rows || n >= bd + d_out) return;
@@ -72,6 +81,7 @@ struct EpiProjectStaged {     // columns < bd -> P (bf16), the rest -> Self (fp3
 struct EpiWeightGradAtomic {
     static constexpr bool staged = false;
     float *dV, *dW0; int32_t d_in, d_out, B;
+    __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         const int32_t bd = B * d_out;
@@ -85,9 +95,34 @@ struct EpiWeightGradAtomic {
 struct EpiRowMajorF32 {
     static constexpr bool staged = false;
     float *out; int64_t rows; int32_t cols;
+    __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         if (m < rows && n < cols) out[m * cols + n] = v;
+    }
+    __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
+};
+struct EpiActF32 {            // activation, zero rows outside the sub-graph, optional second copy
+    static constexpr bool staged = false;
+    float *out, *out2; int64_t rows; int32_t cols; int act; const uint8_t *row_active;
+    __device__ __forceinline__ void bind(int32_t) {}
+    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
+    {
+        if (m >= rows || n >= cols) return;
+        float r = act == KGE_ACT_RELU ? fmaxf(v, 0.f) : v;
+        if (row_active && !row_active[m]) r = 0.f;
+        out[m * cols + n] = r;
+        if (out2) out2[m * cols + n] = r;
+    }
+    __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
+};
+struct EpiRelOuterAtomic {    // C[group] (d_in x d_out) accumulates the chunks of one relation
+    static constexpr bool staged = false;
+    float *C; int32_t d_in, d_out; int32_t group;
+    __device__ __forceinline__ void bind(int32_t g) { group = g; }
+    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
+    {
+        if (m < d_in && n < d_out) unsafeAtomicAdd(C + ((int64_t)group * d_in + m) * d_out + n, v);
     }
     __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
 };
@@ -104,8 +139,13 @@ __device__ __forceinline__ void transpose_pairs(const uint32_t (&pr)[8], uint4 &
 // KC = true : C[m][n] = sum_k A[m][k] B[n][k]   (A.oct(m, k), B.oct(n, k))
 // KC = false: C[m][n] = sum_k A[k][m] B[k][n]   (A.pair(k, m), B.pair(k, n))
 template <bool KC, class EPI>
+// Split s contracts [s*kchunk, min((s+1)*kchunk, K)), or, in a grouped launch (g_beg non-null),
+// [g_beg[s], g_end[s]) with the epilogue bound to group g_id[s].
 __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, int64_t K, int64_t kchunk,
-                                                     int32_t tiles_m, int32_t tiles_n, int32_t n_splits)
+                                                     int32_t tiles_m, int32_t tiles_n, int32_t n_splits,
+                                                     const int32_t *__restrict__ g_id,
+                                                     const int32_t *__restrict__ g_beg,
+                                                     const int32_t *__restrict__ g_end)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint16_t (*As)[LDK] = reinterpret_cast<uint16_t (*)[LDK]>(smem);
@@ -131,8 +171,9 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
     const int64_t bid = prow / tiles_m;                        // split index
     const int64_t m0 = (int64_t)tm * TM;
     const int32_t n0 = tn * TN;
-    const int64_t kbeg = bid * kchunk;
-    const int64_t kend = (kbeg + kchunk < K) ? kbeg + kchunk : K;
+    int64_t kbeg = bid * kchunk;
+    int64_t kend = (kbeg + kchunk < K) ? kbeg + kchunk : K;
+    if (g_beg) { kbeg = g_beg[bid]; kend = g_end[bid]; epi.bind(g_id[bid]); }
 
     floatx16 acc[2][4];
 #pragma unroll
@@ -287,9 +328,23 @@ __global__ void k_cvt_weights(const float *__restrict__ V, const float *__restri
     WbfT[(int64_t)n * d_in + k] = h;
 }
 
+// [V_1; ..; V_B; W0] (fp32, ((B+1) d_in x d_out)) -> WstT [d_out][(B+1) d_in], bf16
+__global__ void k_cvt_wstack_t(const float *__restrict__ V, const float *__restrict__ W0, int32_t d_in,
+                               int32_t d_out, int32_t B, uint16_t *__restrict__ WstT)
+{
+    const int64_t K = (int64_t)(B + 1) * d_in;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // = kk * d_out + c (coalesced reads)
+    if (idx >= K * d_out) return;
+    const int64_t kk = idx / d_out;
+    const int32_t c = (int32_t)(idx - kk * d_out);
+    const float v = kk < (int64_t)B * d_in ? V[idx] : W0[(kk - (int64_t)B * d_in) * d_out + c];
+    WstT[(int64_t)c * K + kk] = (uint16_t)(pack2(v, 0.f) & 0xffffu);
+}
+
 template <bool KC, class EPI>
 int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64_t kchunk, int32_t tiles_m,
-                int32_t tiles_n, int64_t splits, hipStream_t st)
+                int32_t tiles_n, int64_t splits, hipStream_t st, const int32_t *g_id = nullptr,
+                const int32_t *g_beg = nullptr, const int32_t *g_end = nullptr)
 {
     const int pn = tiles_n >= 8 ? 8 : (tiles_n >= 4 ? 4 : (tiles_n >= 2 ? 2 : 1)), pm = 64 / pn;
     const int64_t n_patches = cdiv(splits * tiles_m, pm) * cdiv(tiles_n, pn);
@@ -302,7 +357,8 @@ int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    k_gemm_bf16<KC, EPI><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n, (int32_t)splits);
+    k_gemm_bf16<KC, EPI><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n, (int32_t)splits,
+                                                            g_id, g_beg, g_end);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
@@ -350,8 +406,8 @@ int launch_project_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out,
     if (N == 0) return KGE_OK;
     const int32_t nc = (B + 1) * d_out;
     const int32_t tiles_m = (int32_t)cdiv(N, TM), tiles_n = (int32_t)cdiv(nc, TN);
-    MatBF A{reinterpret_cast<const uint16_t *>(Hbf), N, d_in, d_in};
-    MatBF Bm{reinterpret_cast<const uint16_t *>(WbfT), nc, d_in, d_in};
+    MatBF A{reinterpret_cast<const uint16_t *>(Hbf), N, d_in, d_in, nullptr};
+    MatBF Bm{reinterpret_cast<const uint16_t *>(WbfT), nc, d_in, d_in, nullptr};
     EpiProjectStaged ep{reinterpret_cast<uint16_t *>(P), Self, N, d_out, B * d_out};
     KGE_PROF("project", st);
     return launch_gemm<true, EpiProjectStaged>(A, Bm, ep, d_in, cdiv(d_in, TK) * TK, tiles_m, tiles_n, 1, st);
@@ -372,8 +428,8 @@ int launch_weight_grad_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_
     int64_t kchunk = cdiv(cdiv(N, splits), TK) * TK;
     if (kchunk < 8 * TK) kchunk = 8 * TK;
     splits = cdiv(N, kchunk);
-    MatBF A{reinterpret_cast<const uint16_t *>(Hbf), N, d_in, d_in};
-    MatBF Bm{reinterpret_cast<const uint16_t *>(X), N, nc, nc};
+    MatBF A{reinterpret_cast<const uint16_t *>(Hbf), N, d_in, d_in, nullptr};
+    MatBF Bm{reinterpret_cast<const uint16_t *>(X), N, nc, nc, nullptr};
     EpiWeightGradAtomic ep{dV, dW0, d_in, d_out, B};
     KGE_PROF("weight_grad", st);
     return launch_gemm<false, EpiWeightGradAtomic>(A, Bm, ep, N, kchunk, tiles_m, tiles_n, splits, st);
@@ -386,9 +442,51 @@ int launch_input_grad_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out
     if (N == 0) return KGE_OK;
     const int32_t nc = (B + 1) * d_out;
     const int32_t tiles_m = (int32_t)cdiv(N, TM), tiles_n = (int32_t)cdiv(d_in, TN);
-    MatBF A{reinterpret_cast<const uint16_t *>(X), N, nc, nc};
-    MatBF Bm{reinterpret_cast<const uint16_t *>(Wbf), d_in, nc, nc};
+    MatBF A{reinterpret_cast<const uint16_t *>(X), N, nc, nc, nullptr};
+    MatBF Bm{reinterpret_cast<const uint16_t *>(Wbf), d_in, nc, nc, nullptr};
     EpiRowMajorF32 ep{dH, N, d_in};
     KGE_PROF("input_grad", st);
     return launch_gemm<true, EpiRowMajorF32>(A, Bm, ep, nc, cdiv(nc, TK) * TK, tiles_m, tiles_n, 1, st);
+}
+
+int launch_cvt_wstack_bf16(const float *V, const float *W0, int32_t d_in, int32_t d_out, int32_t B, void *WstT,
+                           hipStream_t st)
+{
+    const int64_t n = (int64_t)(B + 1) * d_in * d_out;
+    KGE_PROF("cvt_weights", st);
+    k_cvt_wstack_t<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(V, W0, d_in, d_out, B, reinterpret_cast<uint16_t *>(WstT));
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+// out = act(X WstT^T)      X: bf16 [N][(B+1) d_in] = [Y | Hbf]; WstT: bf16 [d_out][(B+1) d_in]
+int launch_combine_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const void *WstT,
+                        int act, const uint8_t *row_active, float *out, float *out2, hipStream_t st)
+{
+    if (N == 0) return KGE_OK;
+    const int32_t K = (B + 1) * d_in;
+    const int32_t tiles_m = (int32_t)cdiv(N, TM), tiles_n = (int32_t)cdiv(d_out, TN);
+    MatBF A{reinterpret_cast<const uint16_t *>(X), N, K, K, nullptr};
+    MatBF Bm{reinterpret_cast<const uint16_t *>(WstT), d_out, K, K, nullptr};
+    EpiActF32 ep{out, out2, N, d_out, act, row_active};
+    KGE_PROF("combine", st);
+    return launch_gemm<true, EpiActF32>(A, Bm, ep, K, cdiv(K, TK) * TK, tiles_m, tiles_n, 1, st);
+}
+
+// C[r] (d_in x d_out, fp32, zeroed here) = sum_{runs s of relation r} Zbf[s]^T Gbf[seg_dst[s]]
+// Gbf: bf16 rows of d_out elements, `ldg` elements apart (the G block appended behind dP)
+int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const void *Gbf, int64_t ldg, int32_t d_in,
+                          int32_t d_out, float *C, hipStream_t st)
+{
+    const int64_t R2 = 2 * (int64_t)p->n_relations;
+    int rc = launch_fill_zero(C, sizeof(float) * (size_t)R2 * d_in * d_out, st);
+    if (rc != KGE_OK) return rc;
+    if (p->n_seg == 0 || p->n_relc == 0) return KGE_OK;
+    const int32_t tiles_m = (int32_t)cdiv(d_in, TM), tiles_n = (int32_t)cdiv(d_out, TN);
+    MatBF A{reinterpret_cast<const uint16_t *>(Zbf), p->n_seg, d_in, d_in, nullptr};
+    MatBF Bm{reinterpret_cast<const uint16_t *>(Gbf), p->n_seg, d_out, ldg, p->seg_dst};
+    EpiRelOuterAtomic ep{C, d_in, d_out, 0};
+    KGE_PROF("rel_outer", st);
+    return launch_gemm<false, EpiRelOuterAtomic>(A, Bm, ep, p->n_seg, 0, tiles_m, tiles_n, p->n_relc, st,
+                                                 p->relc_rel, p->relc_beg, p->relc_end);
 }

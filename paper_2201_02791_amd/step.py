@@ -63,7 +63,7 @@ class TrainStep:
         torch = self.torch
         off, nbytes = kb.workspace_slice(self.part, self.layers, which, layer, self.msg_dtype)
         raw = self.workspace[off:off + nbytes]
-        bf = self.msg_dtype == kb.MSG_BF16 and which in (kb.WS_P, kb.WS_DP)
+        bf = self.msg_dtype == kb.MSG_BF16 and which in (kb.WS_P, kb.WS_DP, kb.WS_Z, kb.WS_Y)
         t = raw.view(torch.bfloat16 if bf else torch.float32)
         return t.view(self.part.n_seg if which == kb.WS_Z else self.part.n_vert, -1)
 

@@ -96,3 +96,32 @@ def assert_step_close(ts, res, tol_val, tol_grad, need_dH0=True, batch_rows=None
     bad = {k: v for k, v in errs.items() if not (v[0] <= v[1])}
     assert not bad, "relative errors above tolerance: %s (all: %s)" % (bad, errs)
     return errs
+
+
+def align_mask_decisions(orc, ts, opart, res, params, acts, need_dH0, msg_bf16, rows=None, thresh=1e-4):
+    """ReLU masks are decisions taken from floating-point values; a pre-activation within rounding
+    noise of zero can fall on different sides in fp32 sums (GPU) and fp64 sums (oracle).  Where that
+    happens - and only where |pre| <= thresh * max|pre| - adopt the kernel's decision and recompute
+    the oracle's backward pass.  Returns (number of adopted decisions, res with updated gradients).
+    rows: boolean [n_layers][N] of the rows that were propagated (None = all)."""
+    from paper_2201_02791_amd import binding as kb
+    pres = [p.copy() for p in res["pres"]]
+    n_flip = 0
+    for l, act in enumerate(acts):
+        if act != 1:
+            continue
+        hg = ts.view(kb.WS_H, l).cpu().numpy()
+        flip = (hg > 0) != (pres[l] > 0)
+        if rows is not None:
+            flip &= rows[l].astype(bool)[:, None]
+        if not flip.any():
+            continue
+        assert np.abs(pres[l][flip]).max() <= thresh * np.abs(pres[l]).max(), "mask differs away from zero"
+        n_flip += int(flip.sum())
+        tiny = np.finfo(np.float64).tiny
+        pres[l][flip] = np.where(hg[flip] > 0, tiny, -tiny)
+    if n_flip == 0:
+        return 0, res
+    grads, dH0 = orc.rgcn_backward(opart, layers_of(params, acts), res["Hs"], pres, res["dH_out"], need_dH0, msg_bf16)
+    out = dict(res); out["grads"] = grads; out["dH0"] = dH0
+    return n_flip, out

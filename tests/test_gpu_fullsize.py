@@ -9,6 +9,10 @@ at any size, all evaluated from the GPU's own stored layer inputs:
   distmult          all scores, loss, dH_out, dM    activation bwd     sampled rows of G (bit-exact)
   transposed gather sampled rows of dP              input_grad         sampled rows of dH_1 (and dH0)
   weight_grad       dW0 whole; dV sampled columns; Euler identity     coefficients  rare relations; Euler
+
+The aggregate-first variants run on the batch's computational sub-graph, as bench.py does by default:
+sampled run means z and per-basis sums y replace the projected rows, forward rows are sampled from
+the active sets, and the sub-graph flags and counts are compared bit-exactly.
 """
 import sys
 import time
@@ -26,10 +30,13 @@ def say(*a):
     print("[gpu-case]", *a, file=sys.stderr, flush=True)
 
 
-def pick_rows(rng, deg, edge_budget, n_max):
+def pick_rows(rng, deg, edge_budget, n_max, allowed=None):
     """Random rows within an edge budget, plus one row that is cut into units (degree >= 256) and
-    the heaviest row if they fit."""
+    the heaviest row if they fit.  allowed: boolean mask of the rows that may be picked."""
+    if allowed is not None:
+        deg = np.where(allowed, deg, -1)
     order = rng.permutation(len(deg))
+    order = order[deg[order] >= 0]
     rows, used = [], 0
     for v in order[:20000]:
         if deg[v] <= 200 and used + deg[v] <= 0.5 * edge_budget and len(rows) < n_max:
@@ -48,7 +55,7 @@ def pick_rows(rng, deg, edge_budget, n_max):
     return np.array(sorted(set(rows)), np.int64)
 
 
-def run_full_size(kb, orc, cfg):
+def run_full_size(kb, orc, cfg, agg=False):
     import torch
     from oracle import sampled
     from paper_2201_02791_amd.step import TrainStep
@@ -69,7 +76,9 @@ def run_full_size(kb, orc, cfg):
     params = synth.make_params(spec, N)
     pos = synth.make_batch(spec, gp.n_core)
     need_dH0 = not spec.fixed_features
-    ts = TrainStep(gp, params, spec.acts, kb.MSG_BF16 if bf else kb.MSG_F32, need_dH0=need_dH0)
+    ts = TrainStep(gp, params, spec.acts, kb.MSG_BF16 if bf else kb.MSG_F32, need_dH0=need_dH0, cone=agg,
+                   order=kb.ORDER_AGGREGATE_FIRST if agg else kb.ORDER_PROJECT_FIRST)
+    mode = (2 if agg else 1) if bf else 0          # the oracle's rounding points for this pipeline
     ts.set_batch(pos, spec.n_neg)
     ts.run(spec.neg_mode, SEED, STEP)
     torch.cuda.synchronize()
@@ -84,24 +93,58 @@ def run_full_size(kb, orc, cfg):
     errs = {}
 
     # ---- forward: sampled destination rows of both layers, and of P
-    budget = 1.4e10 / (B * d * d)      # oracle cost per edge: B d^2 multiply-adds
-    rows = pick_rows(rng, deg_in, budget, 300)
-    say("forward rows:", len(rows), "edges:", int(deg_in[rows].sum()), "max deg:", int(deg_in[rows].max()))
-    _, want1 = orc.layer_rows(op, rows, L[0]["V"], L[0]["a"], L[0]["W0"], L[0]["act"], H0, msg_bf16=bf)
-    errs["H1 rows"] = (rel_err(H1[rows], want1), tol_v)
-    _, want2 = orc.layer_rows(op, rows, L[1]["V"], L[1]["a"], L[1]["W0"], L[1]["act"], H1, msg_bf16=bf)
-    errs["H_out rows"] = (rel_err(Hout[rows], want2), tol_v)
-    trows = torch.from_numpy(rows).to(ts.dev)
-    P1 = c(ts.view(kb.WS_P, 0)[trows]).reshape(len(rows), B, d)
-    errs["P1 rows"] = (rel_err(P1, sampled.project_rows(H0[rows], L[0]["V"])), tol_v)
-    P2 = c(ts.view(kb.WS_P, 1)[trows]).reshape(len(rows), B, d)
-    errs["P2 rows"] = (rel_err(P2, sampled.project_rows(H1[rows], L[1]["V"])), tol_v)
-    say("forward checked (%.0f s)" % (time.time() - t0), errs)
-
-    # ---- negatives and scoring: everything
     ne, ns = orc.sample_negatives(op, pos, spec.n_neg, spec.neg_mode, SEED, STEP)
     np.testing.assert_array_equal(ts.neg_ent.cpu().numpy()[:, :spec.n_neg], ne)
     np.testing.assert_array_equal(ts.neg_side.cpu().numpy()[:, :spec.n_neg], ns)
+    active = None
+    if agg:            # the batch's computational sub-graph: flags and counts, bit-exact
+        active = orc.compute_graph(op, pos, ne, 2).astype(bool)
+        got_active, stats = ts.cg.export()
+        np.testing.assert_array_equal(got_active.astype(bool), active)
+        for l in range(2):
+            assert stats[l, 0] == int(active[l].sum()) and stats[l, 1] == int(deg_in[active[l]].sum())
+        say("sub-graph (vertices, edges, runs) per layer:", stats.tolist())
+        assert not Hout[~active[1]].any() and not H1[~active[0]].any()
+    if mode == 2:      # the oracle's regrouped evaluation costs (B + 1) d^2 per ROW and d per edge
+        budget = 4e6
+    else:
+        budget = 1.4e10 / (B * d * d)      # oracle cost per edge: B d^2 multiply-adds
+    rows1 = pick_rows(rng, deg_in, budget, 300, None if active is None else active[0])
+    rows2 = pick_rows(rng, deg_in, budget, 300, None if active is None else active[1])
+    say("forward rows:", len(rows1), len(rows2), "edges:", int(deg_in[rows1].sum()), int(deg_in[rows2].sum()),
+        "max deg:", int(deg_in[rows1].max()), int(deg_in[rows2].max()))
+    _, want1 = orc.layer_rows(op, rows1, L[0]["V"], L[0]["a"], L[0]["W0"], L[0]["act"], H0, msg_bf16=mode)
+    errs["H1 rows"] = (rel_err(H1[rows1], want1), tol_v)
+    _, want2 = orc.layer_rows(op, rows2, L[1]["V"], L[1]["a"], L[1]["W0"], L[1]["act"], H1, msg_bf16=mode)
+    errs["H_out rows"] = (rel_err(Hout[rows2], want2), tol_v)
+    if agg:
+        # run means of both layers on sampled runs into active destinations, and the per-basis sums
+        # of the last layer (the y buffer is shared) on its sampled rows, from the GPU's own z
+        run_len = np.diff(op["seg_ptr"])
+        for l, Hin in ((0, H0), (1, H1)):
+            ok = active[l][op["seg_dst"]] & (run_len <= 2000)
+            runs = rng.permutation(np.nonzero(ok)[0])[:400]
+            runs = np.concatenate([runs, np.nonzero(ok & (run_len >= 256))[0][:2]]).astype(np.int64)
+            zg = c(ts.view(kb.WS_Z, l)[torch.from_numpy(runs).to(ts.dev)])
+            zw = sampled.run_mean_rows(op, runs, Hin, bf16=bf)
+            errs["z_%d runs" % (l + 1)] = (rel_err(zg, zw), tol_v)
+            gone = np.nonzero(~active[l][op["seg_dst"]])[0][:50]          # runs outside the sub-graph: zero rows
+            if len(gone):
+                assert not c(ts.view(kb.WS_Z, l)[torch.from_numpy(gone).to(ts.dev)]).any()
+        Zv = ts.view(kb.WS_Z, 1)
+        Z_of = lambda ids: c(Zv[torch.from_numpy(np.asarray(ids, np.int64)).to(ts.dev)])
+        yw = sampled.basis_sum_rows(op, rows2, L[1]["a"], Z_of)
+        yg = c(ts.view(kb.WS_Y, 1)[torch.from_numpy(rows2).to(ts.dev)])[:, :B * d].reshape(len(rows2), B, d)
+        errs["y_2 rows"] = (rel_err(yg, yw), tol_v)
+    else:
+        trows = torch.from_numpy(rows1).to(ts.dev)
+        P1 = c(ts.view(kb.WS_P, 0)[trows]).reshape(len(rows1), B, d)
+        errs["P1 rows"] = (rel_err(P1, sampled.project_rows(H0[rows1], L[0]["V"])), tol_v)
+        P2 = c(ts.view(kb.WS_P, 1)[trows]).reshape(len(rows1), B, d)
+        errs["P2 rows"] = (rel_err(P2, sampled.project_rows(H1[rows1], L[1]["V"])), tol_v)
+    say("forward checked (%.0f s)" % (time.time() - t0), errs)
+
+    # ---- scoring: everything
     sl = orc.distmult_score_loss(op, Hout, params["M"], pos, ne, ns)
     errs["scores"] = (rel_err(c(ts.scores), sl["scores"]), 1e-4)
     errs["loss"] = (abs(float(ts.loss.cpu()[0]) - sl["loss"]) / sl["loss"], 1e-4)
@@ -151,9 +194,14 @@ def run_full_size(kb, orc, cfg):
         cand = np.nonzero((cnt > 0) & (cnt <= 3000))[0]
         rels = cand[np.argsort(cnt[cand])][-3:] if len(cand) else []
         for l, G in ((0, G1), (1, G2)):
-            Pv = ts.view(kb.WS_P, l)
-            P_of = lambda ids: c(Pv[torch.from_numpy(np.asarray(ids, np.int64)).to(ts.dev)]).reshape(len(ids), B, d)
-            want = sampled.coeff_grad_relations(ev, rels, P_of, G, B)
+            if agg:
+                Zl = ts.view(kb.WS_Z, l)
+                Zl_of = lambda ids: c(Zl[torch.from_numpy(np.asarray(ids, np.int64)).to(ts.dev)])
+                want = sampled.coeff_grad_relations_runs(op, rels, Zl_of, L[l]["V"], G)
+            else:
+                Pv = ts.view(kb.WS_P, l)
+                P_of = lambda ids: c(Pv[torch.from_numpy(np.asarray(ids, np.int64)).to(ts.dev)]).reshape(len(ids), B, d)
+                want = sampled.coeff_grad_relations(ev, rels, P_of, G, B)
             da = c(ts.grads[l]["da"])
             for r, v in want.items():
                 errs["da_%d[rel %d]" % (l + 1, r)] = (float(np.abs(da[r] - v).max() / max(np.abs(v).max(), 1e-30)), tol_g)
@@ -176,6 +224,17 @@ def kb():
 def test_config3_full_size(kb, orc):
     """Partition 0 of 16 of the 2.9 M-vertex / 30 M-edge graph, d = 128, 2 bases, fp32."""
     run_full_size(kb, orc, 3)
+
+
+def test_config3_full_size_aggregate_first_subgraph(kb, orc):
+    """The same workload in the aggregate-first order on the batch's computational sub-graph."""
+    run_full_size(kb, orc, 3, agg=True)
+
+
+def test_config4_full_size_aggregate_first_subgraph(kb, orc):
+    """configs[4] as a bf16 pipeline in the aggregate-first order (the oracle rounds at the same
+    points: inputs, run means, per-basis sums, weights) on the batch's computational sub-graph."""
+    run_full_size(kb, orc, 4, agg=True)
 
 
 def test_config4_full_size(kb, orc):

@@ -44,3 +44,29 @@ def test_sampled_rows_match_the_whole_step(case):
             q = sampled.euler_quantity(pre, Hin, lay["W0"], g["Gpre"], chunk=16)
             assert q == pytest.approx(float(np.sum(lay["a"] * g["da"])), rel=1e-10)
             assert q == pytest.approx(float(np.sum(lay["V"] * g["dV"])), rel=1e-10)
+
+
+def test_regrouped_helpers_match_the_whole_step(case, orc):
+    """Run means, per-basis sums and the coefficient gradient from run means reproduce the C oracle:
+    exact mode against the exact layer, bf16 rounding against torch's conversion and mode 2."""
+    import torch
+    sampled, part, layers, H0, res, ev = case
+    lay, g = layers[0], res["grads"][0]
+    S = part["n_seg"]
+    runs = np.arange(S)
+    Z = sampled.run_mean_rows(part, runs, H0)
+    rows = np.arange(part["n_vert"])
+    Y = sampled.basis_sum_rows(part, rows, lay["a"], lambda ids: Z[ids])
+    pre = np.einsum("nbk,bkc->nc", Y, lay["V"]) + H0 @ lay["W0"]
+    np.testing.assert_allclose(pre, res["pres"][0], rtol=1e-10, atol=1e-12)
+    da = sampled.coeff_grad_relations_runs(part, [0, 1, 4], lambda ids: Z[ids], lay["V"], g["Gpre"])
+    for r, v in da.items():
+        np.testing.assert_allclose(v, g["da"][r], rtol=1e-9, atol=1e-12)
+    x = np.random.default_rng(5).normal(0, 3, 4000).astype(np.float32)
+    x[:4] = np.array([0x3F808000, 0x3F818000, 0xBF808000, 0x3F807FFF], np.uint32).view(np.float32)
+    np.testing.assert_array_equal(sampled.round_bf16(x), torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy())
+    Zq = sampled.round_bf16(sampled.run_mean_rows(part, runs, H0, bf16=True))
+    Yq = sampled.round_bf16(sampled.basis_sum_rows(part, rows, lay["a"], lambda ids: Zq[ids]))
+    pre_q = np.einsum("nbk,bkc->nc", Yq, sampled.round_bf16(lay["V"])) + sampled.round_bf16(H0) @ sampled.round_bf16(lay["W0"])
+    want, _ = orc.layer_forward(part, lay["V"], lay["a"], lay["W0"], 1, H0, msg_bf16=2)
+    np.testing.assert_allclose(pre_q, want, rtol=1e-10, atol=1e-12)
