@@ -55,9 +55,9 @@ def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None):
     ns_mean = S if cone is None else sum(c[2] for c in cone) / len(cone)
     nv_mean = N if cone is None else sum(c[0] for c in cone) / len(cone)
     if name == "run_mean":     # per edge: source id + input row; per run: ptr/dst/1/c + z row written
-        return "hbm", ne_mean * (4.0 * d + 4.0) + S * 12.0 + S * 4.0 * d
+        return "hbm", ne_mean * (ep * d + 4.0) + S * 12.0 + S * ep * d
     if name == "aggregate":    # per run: z row + (run id, relation); per vertex: ptr + y row written
-        return "hbm", ns_mean * (4.0 * d + 8.0) + N * 4.0 + nv_mean * B * d * 4.0 + R2 * B * 4.0
+        return "hbm", ns_mean * (ep * d + 8.0) + N * 4.0 + nv_mean * B * d * ep + R2 * B * 4.0
     if name == "combine":
         return "mfma", gemm_flops
     if name == "rel_outer":    # C_r = sum_runs z^T G: 2 S d^2 flops; bytes S (2 d) 4
@@ -125,7 +125,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="index into the workload list (0..4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--order", choices=["project", "aggregate"], default="project",
+    ap.add_argument("--order", choices=["project", "aggregate"], default="aggregate",
                     help="project-first (P = H V_b, then the neighbour sum) or aggregate-first order of Eq. 1-2")
     ap.add_argument("--whole-partition", action="store_true",
                     help="propagate every vertex of the partition instead of the batch's computational sub-graph")
