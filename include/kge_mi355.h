@@ -59,8 +59,13 @@ enum { KGE_DOMAIN_CORE = 0, KGE_DOMAIN_ALL = 1 };
  *                              projected messages: (B+1) d_out values move per edge.
  *   KGE_ORDER_AGGREGATE_FIRST  z_{i,r} = (1/c_ir) sum_{j in N_i^r} h_j per (relation,
  *                              destination) run, y_{i,b} = sum_r a_rb z_{i,r}, then
- *                              pre_i = sum_b y_{i,b} V_b + h_i W_0: d_in values move per edge. */
-enum { KGE_ORDER_PROJECT_FIRST = 0, KGE_ORDER_AGGREGATE_FIRST = 1 };
+ *                              pre_i = sum_b y_{i,b} V_b + h_i W_0: d_in values move per edge.
+ *   KGE_ORDER_RELATION_WEIGHTS the same run means z_{i,r}, then Eq. 2 written out, W_r = sum_b a_rb
+ *                              V_b for every relation, and pre_i = sum_r z_{i,r} W_r + h_i W_0 as one
+ *                              product per (relation, destination) run, grouped by relation over the
+ *                              (relation, destination)-sorted runs.  S d_in d_out multiply-adds instead
+ *                              of N B d_in d_out: cheaper when a vertex has fewer runs than bases. */
+enum { KGE_ORDER_PROJECT_FIRST = 0, KGE_ORDER_AGGREGATE_FIRST = 1, KGE_ORDER_RELATION_WEIGHTS = 2 };
 
 typedef struct kge_partition kge_partition;      /* opaque; device resident; library owned    */
 typedef struct kge_cgraph kge_cgraph;            /* opaque; one batch's computational sub-graph */
@@ -118,7 +123,8 @@ typedef enum kge_array {
     KGE_ARR_REL_PTR = 20,  /* int32 [2R+1] run range of each relation                          */
     KGE_ARR_DR_PTR = 21,   /* int32 [N+1]  runs grouped by destination: run range per vertex   */
     KGE_ARR_DR_SEG = 22,   /* int32 [S]    run id, ordered by (dst, rel)                       */
-    KGE_ARR_DR_REL = 23    /* int32 [S]    relation of that run                                */
+    KGE_ARR_DR_REL = 23,   /* int32 [S]    relation of that run                                */
+    KGE_ARR_SM_SEG = 24    /* int32 [E]    run id of each edge in source-major order           */
 } kge_array;
 
 /*
@@ -281,7 +287,7 @@ int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_ent
  *               ld = B*d_out (fp32 messages) or (B+1)*d_out (bf16 messages: G, rounded to
  *               bf16, is appended behind the B blocks)
  *   KGE_WS_DH   gradient with respect to layer l's INPUT, l >= 1, [N][d_in] float (after backward)
- *   KGE_WS_Z    aggregate-first layer l: run means z [S][d_in] float, one row per (relation,
+ *   KGE_WS_Z    aggregate-first or relation-weight layer l: run means z [S][d_in], one row per (relation,
  *               destination) run in the partition's run order (valid after forward)
  *   KGE_WS_Y    aggregate-first layer l: y [N][B*d_in] float of the last such layer forward has
  *               processed (the buffer is shared between layers)

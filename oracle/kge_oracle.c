@@ -308,12 +308,68 @@ static void forward_aggregate_first_bf16(int64_t N, int64_t S, const int32_t *se
 }
 
 /*
+ * The rounding points of a bf16 pipeline that writes Eq. 2 out per relation (msg_bf16 == 3):
+ *   W_r     = sum_b a_rb V_b                            (Eq. 2), rounded to bf16
+ *   z_{i,r} = (1/c_{i,r}) sum_{j in N_i^r} h_j          h and z rounded to bf16
+ *   u_{i,r} = z_{i,r} W_r                               rounded to bf16 when stored
+ *   pre_i   = sum_r u_{i,r} + h_i W_0                   W_0 rounded to bf16
+ * every sum exact.  zq_out (optional) receives the rounded z, [S][d_in].
+ */
+static void forward_relation_weights_bf16(int64_t N, int64_t S, const int32_t *seg_ptr,
+                                          const int32_t *seg_rel, const int32_t *seg_dst,
+                                          const int32_t *col_src, int32_t d_in, int32_t d_out, int32_t B,
+                                          int32_t n_rel2, const double *V, const double *a, const double *W0,
+                                          const double *H, double *pre, double *zq_out)
+{
+    size_t dd = (size_t)d_in * d_out;
+    double *Wr = (double *)calloc((size_t)n_rel2 * dd, sizeof(double));
+    double *z = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *u = (double *)malloc(sizeof(double) * (size_t)d_out);
+    for (int32_t r = 0; r < n_rel2; ++r) {
+        for (int32_t b = 0; b < B; ++b)
+            for (size_t x = 0; x < dd; ++x) Wr[(size_t)r * dd + x] += a[(size_t)r * B + b] * V[(size_t)b * dd + x];
+        for (size_t x = 0; x < dd; ++x) Wr[(size_t)r * dd + x] = round_msg(Wr[(size_t)r * dd + x], 1);
+    }
+    for (int64_t i = 0; i < N; ++i) {
+        double *o = pre + (size_t)i * d_out;
+        for (int32_t c = 0; c < d_out; ++c) o[c] = 0.0;
+        for (int32_t k = 0; k < d_in; ++k) {
+            double h = round_msg(H[(size_t)i * d_in + k], 1);
+            const double *w = W0 + (size_t)k * d_out;
+            for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(w[c], 1);
+        }
+    }
+    for (int64_t s = 0; s < S; ++s) {
+        int32_t r = seg_rel[s], i = seg_dst[s];
+        double cnt = (double)(seg_ptr[s + 1] - seg_ptr[s]);
+        for (int32_t k = 0; k < d_in; ++k) z[k] = 0.0;
+        for (int32_t e = seg_ptr[s]; e < seg_ptr[s + 1]; ++e) {
+            const double *hj = H + (size_t)col_src[e] * d_in;
+            for (int32_t k = 0; k < d_in; ++k) z[k] += round_msg(hj[k], 1);
+        }
+        for (int32_t k = 0; k < d_in; ++k) z[k] = round_msg(z[k] / cnt, 1);
+        if (zq_out) memcpy(zq_out + (size_t)s * d_in, z, sizeof(double) * (size_t)d_in);
+        for (int32_t c = 0; c < d_out; ++c) u[c] = 0.0;
+        for (int32_t k = 0; k < d_in; ++k) {
+            const double *w = Wr + (size_t)r * dd + (size_t)k * d_out;
+            for (int32_t c = 0; c < d_out; ++c) u[c] += z[k] * w[c];
+        }
+        double *o = pre + (size_t)i * d_out;
+        for (int32_t c = 0; c < d_out; ++c) o[c] += round_msg(u[c], 1);
+    }
+    free(u);
+    free(z);
+    free(Wr);
+}
+
+/*
  * One layer forward over the whole partition:
  *   pre_i = sum_r sum_{j in N_i^r} (1/c_{i,r}) h_j W_r + h_i W_0,   W_r = sum_b a_rb V_b
  *   h'_i  = act(pre_i)                        act: 0 identity, 1 ReLU
  * P_scratch is [N][B][d_out] doubles.  msg_bf16 != 0 models a workload whose projections are
  * a bf16 contraction with bf16 message storage (see round_msg); 2 models the bf16 pipeline that
- * sums neighbours first (forward_aggregate_first_bf16); 0 keeps everything exact.
+ * sums neighbours first (forward_aggregate_first_bf16); 3 the one that writes Eq. 2 out per relation
+ * (forward_relation_weights_bf16); 0 keeps everything exact.
  */
 void orc_rgcn_layer_forward(int64_t N, int64_t S, const int32_t *seg_ptr, const int32_t *seg_rel,
                             const int32_t *seg_dst, const int32_t *col_src,
@@ -322,6 +378,14 @@ void orc_rgcn_layer_forward(int64_t N, int64_t S, const int32_t *seg_ptr, const 
                             int32_t msg_bf16,
                             const double *H, double *P_scratch, double *pre, double *Hout)
 {
+    if (msg_bf16 == 3) {
+        int32_t n_rel2 = 0;
+        for (int64_t s = 0; s < S; ++s) if (seg_rel[s] + 1 > n_rel2) n_rel2 = seg_rel[s] + 1;
+        forward_relation_weights_bf16(N, S, seg_ptr, seg_rel, seg_dst, col_src, d_in, d_out, B, n_rel2, V, a, W0, H,
+                                      pre, NULL);
+        for (size_t q = 0; q < (size_t)N * d_out; ++q) Hout[q] = act_fwd(act, pre[q]);
+        return;
+    }
     if (msg_bf16 == 2) {
         forward_aggregate_first_bf16(N, S, seg_ptr, seg_rel, seg_dst, col_src, d_in, d_out, B, V, a, W0, H, pre, NULL);
         for (size_t q = 0; q < (size_t)N * d_out; ++q) Hout[q] = act_fwd(act, pre[q]);
@@ -376,6 +440,33 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
         int32_t i = rows[q];
         double *o = pre_rows + (size_t)q * d_out;
         for (int32_t c = 0; c < d_out; ++c) o[c] = 0.0;
+        if (msg_bf16 == 3) {      /* Eq. 2 written out per relation, see forward_relation_weights_bf16 */
+            for (int32_t k = 0; k < d_in; ++k) {
+                double h = round_msg((double)H[(size_t)i * d_in + k], 1);
+                for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(W0[(size_t)k * d_out + c], 1);
+            }
+            for (int64_t t = row_seg_ptr[q]; t < row_seg_ptr[q + 1]; ++t) {
+                int64_t s = row_seg[t];
+                int32_t r = seg_rel[s];
+                double cnt = (double)(seg_ptr[s + 1] - seg_ptr[s]);
+                for (int32_t k = 0; k < d_in; ++k) zrow[k] = 0.0;
+                for (int32_t e = seg_ptr[s]; e < seg_ptr[s + 1]; ++e)
+                    for (int32_t k = 0; k < d_in; ++k)
+                        zrow[k] += round_msg((double)H[(size_t)col_src[e] * d_in + k], 1);
+                for (int32_t k = 0; k < d_in; ++k) zrow[k] = round_msg(zrow[k] / cnt, 1);
+                for (int32_t c = 0; c < d_out; ++c) pj[c] = 0.0;
+                for (int32_t k = 0; k < d_in; ++k)
+                    for (int32_t c = 0; c < d_out; ++c) {
+                        double wr = 0.0;                       /* W_r[k][c], rounded */
+                        for (int32_t b = 0; b < B; ++b)
+                            wr += a[(size_t)r * B + b] * V[((size_t)b * d_in + k) * d_out + c];
+                        pj[c] += zrow[k] * round_msg(wr, 1);
+                    }
+                for (int32_t c = 0; c < d_out; ++c) o[c] += round_msg(pj[c], 1);
+            }
+            for (int32_t c = 0; c < d_out; ++c) out_rows[(size_t)q * d_out + c] = act_fwd(act, o[c]);
+            continue;
+        }
         if (msg_bf16 == 2) {      /* the regrouped evaluation, see forward_aggregate_first_bf16 */
             for (size_t x = 0; x < (size_t)B * d_in; ++x) yrow[x] = 0.0;
             for (int64_t t = row_seg_ptr[q]; t < row_seg_ptr[q + 1]; ++t) {
@@ -444,7 +535,8 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
  * P_scratch and dP_scratch are [N][B][d_out]; dH_in may be NULL.
  * msg_bf16 == 1: the projected messages h_j V_b in da are the rounded ones the forward pass kept.
  * msg_bf16 == 2: da_rb = sum_runs <z_{i,r} V_b, Gpre_i> with the rounded run means z the regrouped
- * forward pass kept (the same sum, since sum_j (1/c) h_j V_b = z V_b).  All else is exact.
+ * forward pass kept (the same sum, since sum_j (1/c) h_j V_b = z V_b); msg_bf16 == 3 likewise.
+ * All else is exact.
  */
 void orc_rgcn_layer_backward(int64_t N, int64_t S, const int32_t *seg_ptr, const int32_t *seg_rel,
                              const int32_t *seg_dst, const int32_t *col_src,
@@ -457,7 +549,7 @@ void orc_rgcn_layer_backward(int64_t N, int64_t S, const int32_t *seg_ptr, const
 {
     size_t nd_out = (size_t)N * d_out;
     for (size_t q = 0; q < nd_out; ++q) Gpre[q] = dHout[q] * act_grad(act, pre[q]);
-    project_all(N, d_in, d_out, B, V, H, P_scratch, msg_bf16 == 2 ? 0 : msg_bf16);
+    project_all(N, d_in, d_out, B, V, H, P_scratch, msg_bf16 >= 2 ? 0 : msg_bf16);
     memset(dP_scratch, 0, sizeof(double) * (size_t)N * B * d_out);
     memset(dV, 0, sizeof(double) * (size_t)B * d_in * d_out);
     memset(da, 0, sizeof(double) * (size_t)n_rel2 * B);
@@ -487,11 +579,11 @@ void orc_rgcn_layer_backward(int64_t N, int64_t S, const int32_t *seg_ptr, const
                 double *dpj = dP_scratch + ((size_t)j * B + b) * d_out;
                 double dot = 0.0, w = a[(size_t)r * B + b] * invc;
                 for (int32_t c = 0; c < d_out; ++c) { dot += pj[c] * g[c]; dpj[c] += w * g[c]; }
-                if (msg_bf16 != 2) da[(size_t)r * B + b] += invc * dot;
+                if (msg_bf16 < 2) da[(size_t)r * B + b] += invc * dot;
             }
         }
     }
-    if (msg_bf16 == 2) {
+    if (msg_bf16 >= 2) {
         double *zq = (double *)malloc(sizeof(double) * (size_t)(S > 0 ? S : 1) * d_in);
         double *scratch_pre = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1) * d_out);
         forward_aggregate_first_bf16(N, S, seg_ptr, seg_rel, seg_dst, col_src, d_in, d_out, B, V, a, W0, H,

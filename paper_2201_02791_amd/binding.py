@@ -23,7 +23,7 @@ EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_cgraph_destroy", "kge_compute_graph", "kge_cgraph_export"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
-ORDER_PROJECT_FIRST, ORDER_AGGREGATE_FIRST = 0, 1
+ORDER_PROJECT_FIRST, ORDER_AGGREGATE_FIRST, ORDER_RELATION_WEIGHTS = 0, 1, 2
 MSG_F32, MSG_BF16 = 0, 1
 NEG_TAIL, NEG_HEAD_OR_TAIL = 0, 1
 DOMAIN_CORE, DOMAIN_ALL = 0, 1
@@ -35,7 +35,8 @@ ARRAYS = {"vert_gid": (0, np.int32), "core_eid": (1, np.int32), "core_h": (2, np
           "dm_ptr": (12, np.int32), "dm_src": (13, np.int32), "dm_rel": (14, np.int32),
           "dm_invc": (15, np.float32), "sm_ptr": (16, np.int32), "sm_dst": (17, np.int32),
           "sm_rel": (18, np.int32), "sm_invc": (19, np.float32), "rel_ptr": (20, np.int32),
-          "dr_ptr": (21, np.int32), "dr_seg": (22, np.int32), "dr_rel": (23, np.int32)}
+          "dr_ptr": (21, np.int32), "dr_seg": (22, np.int32), "dr_rel": (23, np.int32),
+          "sm_seg": (24, np.int32)}
 
 
 class KgeError(RuntimeError):
@@ -156,7 +157,7 @@ def partition_export(part: Partition, name: str) -> np.ndarray:
          "dm_ptr": part.n_vert + 1, "dm_src": part.n_edge, "dm_rel": part.n_edge, "dm_invc": part.n_edge,
          "sm_ptr": part.n_vert + 1, "sm_dst": part.n_edge, "sm_rel": part.n_edge, "sm_invc": part.n_edge,
          "rel_ptr": 2 * part.n_relations + 1, "dr_ptr": part.n_vert + 1, "dr_seg": part.n_seg,
-         "dr_rel": part.n_seg}[name]
+         "dr_rel": part.n_seg, "sm_seg": part.n_edge}[name]
     arr = np.empty(n, dt)
     _check(load().kge_partition_export(part.handle, C.c_int32(which), arr.ctypes.data_as(C.c_void_p),
                                        C.c_int64(arr.nbytes)))

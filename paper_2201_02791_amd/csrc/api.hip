@@ -74,6 +74,10 @@ struct WsLayout {
     std::vector<size_t> off_Hbf, off_Wbf, off_WbfT;   // bf16 workloads: bf16 copies of layer input and weights
     std::vector<size_t> off_Z, off_Wst; // aggregate-first layers: run means [S][d_in]; bf16: stacked weights, transposed
     size_t off_Y = 0, off_C = 0;        // aggregate-first layers: Y [N][B*d_in], C [2R][d_in*d_out] (shared)
+    // relation-weight layers: W_r fp32 [2R][d_in*d_out] and, for bf16 workloads, its bf16 copies in both
+    // orientations; U / dZ [S][max(d_in, d_out)] (shared)
+    std::vector<size_t> off_Wrel, off_Wrb, off_WrbT;
+    size_t off_U = 0;
     size_t off_self = 0, off_G = 0, off_dP = 0, off_dHa = 0, off_dHb = 0, off_seg = 0, off_part = 0, total = 0;
 };
 
@@ -94,8 +98,8 @@ int check_layers(const kge_partition *p, const kge_layer *layers, int32_t n_laye
         KGE_REQUIRE(L.d_out <= dmax && L.d_in <= 512, KGE_EINVAL,
                     "layer %d: d_out must be at most %d and d_in at most 512", l, dmax);
         KGE_REQUIRE(L.act == KGE_ACT_IDENTITY || L.act == KGE_ACT_RELU, KGE_EINVAL, "layer %d: bad act", l);
-        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.order == KGE_ORDER_AGGREGATE_FIRST, KGE_EINVAL,
-                    "layer %d: bad order", l);
+        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.order == KGE_ORDER_AGGREGATE_FIRST ||
+                        L.order == KGE_ORDER_RELATION_WEIGHTS, KGE_EINVAL, "layer %d: bad order", l);
         KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.d_in <= dmax, KGE_EINVAL,
                     "layer %d: the aggregate-first order needs d_in <= %d", l, dmax);
         KGE_REQUIRE(l == 0 || L.d_in == layers[l - 1].d_out, KGE_EINVAL,
@@ -114,12 +118,27 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
     size_t max_nc = 0;
     w->off_P.assign(n_layers, 0); w->off_H.resize(n_layers); w->off_Z.assign(n_layers, 0);
     w->off_Wst.assign(n_layers, 0);
+    w->off_Wrel.assign(n_layers, 0); w->off_Wrb.assign(n_layers, 0); w->off_WrbT.assign(n_layers, 0);
+    size_t max_u = 0;
     size_t max_y = 0, max_c = 0, max_zd = 0;
     w->off_Hbf.assign(n_layers, 0); w->off_Wbf.assign(n_layers, 0); w->off_WbfT.assign(n_layers, 0);
     for (int l = 0; l < n_layers; ++l) {
         const kge_layer &L = layers[l];
         const bool agg = L.order == KGE_ORDER_AGGREGATE_FIRST;
-        if (agg) {
+        if (L.order == KGE_ORDER_RELATION_WEIGHTS) {
+            const size_t dd = (size_t)L.d_in * L.d_out, R2 = (size_t)2 * p->n_relations;
+            w->off_Z[l] = cur; cur = align_up(cur + (size_t)p->n_seg * L.d_in * ep, 256);
+            w->off_Wrel[l] = cur; cur = align_up(cur + R2 * dd * 4, 256);
+            if (bf) {
+                w->off_Wrb[l] = cur; cur = align_up(cur + R2 * dd * 2, 256);
+                w->off_WrbT[l] = cur; cur = align_up(cur + R2 * dd * 2, 256);
+            }
+            const size_t dm = (size_t)(L.d_in > L.d_out ? L.d_in : L.d_out);
+            if ((size_t)p->n_seg * dm * ep > max_u) max_u = (size_t)p->n_seg * dm * ep;
+            if (R2 * dd * 4 > max_c) max_c = R2 * dd * 4;
+            if ((size_t)L.d_in > max_zd) max_zd = L.d_in;
+            if ((size_t)L.d_in > max_dout) max_dout = L.d_in;      // Self also holds the self-loop part of dH
+        } else if (agg) {
             w->off_Z[l] = cur; cur = align_up(cur + (size_t)p->n_seg * L.d_in * ep, 256);
             // fp32: Y [N][B d_in]; bf16: X = [Y | Hbf] [N][(B+1) d_in]
             const size_t yb = bf ? N * (L.n_bases + 1) * L.d_in * 2 : N * L.n_bases * L.d_in * 4;
@@ -147,6 +166,7 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
     }
     w->off_Y = cur; cur = align_up(cur + max_y, 256);
     w->off_C = cur; cur = align_up(cur + max_c, 256);
+    w->off_U = cur; cur = align_up(cur + max_u, 256);
     w->off_self = cur; cur = align_up(cur + N * max_dout * 4, 256);
     w->off_G = cur; cur = align_up(cur + N * max_dout * 4, 256);
     // dP; bf16 workloads append G behind it so that X = [dP | G] is one bf16 matrix
@@ -160,6 +180,8 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
     if ((size_t)p->hv_seg.n_units * max_B > part) part = (size_t)p->hv_seg.n_units * max_B;
     if ((size_t)p->hv_seg.n_units * max_zd > part) part = (size_t)p->hv_seg.n_units * max_zd;
     if (max_y > 0 && (size_t)p->hv_dr.n_units * max_bd > part) part = (size_t)p->hv_dr.n_units * max_bd;
+    if (max_u > 0 && (size_t)p->hv_dr.n_units * max_dout > part) part = (size_t)p->hv_dr.n_units * max_dout;
+    if (max_u > 0 && (size_t)p->hv_sm.n_units * max_dout > part) part = (size_t)p->hv_sm.n_units * max_dout;
     w->off_part = cur; cur = align_up(cur + part * 4, 256);
     w->total = cur > 0 ? cur : 256;
 }
@@ -203,7 +225,7 @@ extern "C" int kge_workspace_slice(const kge_partition *p, const kge_layer *laye
         KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST, KGE_EINVAL, "an aggregate-first layer keeps no projected messages");
         *offset = w.off_P[layer]; *bytes = N * L.n_bases * L.d_out * ep; break;
     case KGE_WS_Z:
-        KGE_REQUIRE(L.order == KGE_ORDER_AGGREGATE_FIRST, KGE_EINVAL, "only aggregate-first layers keep run means");
+        KGE_REQUIRE(L.order != KGE_ORDER_PROJECT_FIRST, KGE_EINVAL, "a project-first layer keeps no run means");
         *offset = w.off_Z[layer]; *bytes = (size_t)p->n_seg * L.d_in * ep; break;
     case KGE_WS_Y:
         KGE_REQUIRE(L.order == KGE_ORDER_AGGREGATE_FIRST, KGE_EINVAL, "only aggregate-first layers have Y");
@@ -245,6 +267,40 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
         const kge_layer &L = layers[l];
         void *P = ws + w.off_P[l];
         float *Hl = (float *)(ws + w.off_H[l]);
+        if (L.order == KGE_ORDER_RELATION_WEIGHTS) {
+            void *Z = ws + w.off_Z[l], *U = ws + w.off_U;
+            float *Wrel = (float *)(ws + w.off_Wrel[l]);
+            float *out2 = l == n_layers - 1 ? H_out : nullptr;
+            const uint8_t *act_l = kge_cgraph_layer(cg, l);
+            const int32_t R2 = 2 * p->n_relations;
+            rc = launch_relation_weights(L.a, R2, L.n_bases, L.V, (int64_t)L.d_in * L.d_out, Wrel, st);
+            if (rc != KGE_OK) return rc;
+            if (bf) {
+                void *Hbf = ws + w.off_Hbf[l], *Wbf = ws + w.off_Wbf[l], *WbfT = ws + w.off_WbfT[l];
+                rc = launch_cvt_rows_bf16(Hin, p->n_vert * (int64_t)L.d_in, Hbf, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_cvt_weights_bf16(L.V, L.W0, L.d_in, L.d_out, 0, Wbf, WbfT, st);     // W0 alone, both orientations
+                if (rc != KGE_OK) return rc;
+                rc = launch_cvt_relation_weights_bf16(Wrel, R2, L.d_in, L.d_out, ws + w.off_Wrb[l], ws + w.off_WrbT[l], st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_run_mean(p, Hbf, L.d_in, Z, 1, part, act_l, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_apply_relation_weights_bf16(p, Z, ws + w.off_WrbT[l], L.d_in, L.d_out, U, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_project_bf16(Hbf, p->n_vert, L.d_in, L.d_out, 0, WbfT, nullptr, Self, st);
+            } else {
+                rc = launch_run_mean(p, Hin, L.d_in, Z, 0, part, act_l, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_apply_relation_weights(p, (const float *)Z, Wrel, L.d_in, L.d_out, (float *)U, st);
+                if (rc != KGE_OK) return rc;
+                rc = launch_project(Hin, p->n_vert, L.d_in, L.d_out, 0, L.V, L.W0, nullptr, Self, st);
+            }
+            if (rc != KGE_OK) return rc;
+            rc = launch_sum_runs(p, U, bf, L.d_out, Self, L.act, Hl, out2, part, act_l, st);
+            if (rc != KGE_OK) return rc;
+            Hin = Hl;
+            continue;
+        }
         if (L.order == KGE_ORDER_AGGREGATE_FIRST) {
             void *Z = ws + w.off_Z[l];
             void *Y = ws + w.off_Y;
@@ -335,6 +391,49 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
         }
         const bool agg = L.order == KGE_ORDER_AGGREGATE_FIRST;
         float *C = (float *)(ws + w.off_C);
+        if (L.order == KGE_ORDER_RELATION_WEIGHTS) {
+            // W_r = sum_b a_rb V_b was applied per (relation, destination) run: dW_r = C_r = sum_runs z^T G,
+            // da_rb = <C_r, V_b>, dV_b = sum_r a_rb C_r, dz_s = G_dst W_r^T, dh_j = sum_{e out of j} dz/c + G_j W_0^T
+            const int32_t R2 = 2 * p->n_relations;
+            const int64_t dd = (int64_t)L.d_in * L.d_out;
+            const void *Z = ws + w.off_Z[l];
+            void *dZ = ws + w.off_U;
+            float *Self = (float *)(ws + w.off_self);
+            const bool need_in = l > 0 || dH0;
+            float *dst = l > 0 ? dHbuf[l & 1] : dH0;
+            if (bf) {
+                rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, 0, dP, st);          // Gbf [N][d_out]
+                if (rc != KGE_OK) return rc;
+                rc = launch_rel_outer_bf16(p, Z, dP, L.d_out, L.d_in, L.d_out, C, st);
+            } else {
+                rc = launch_rel_outer(p, (const float *)Z, Gl, L.d_in, L.d_out, C, st);
+            }
+            if (rc != KGE_OK) return rc;
+            rc = launch_coeff_contract(p, C, L.V, L.d_in, L.d_out, L.n_bases, grads[l].da, st);
+            if (rc != KGE_OK) return rc;
+            rc = launch_basis_grad_from_relations(L.a, R2, L.n_bases, C, dd, grads[l].dV, st);
+            if (rc != KGE_OK) return rc;
+            if (bf) rc = launch_weight_grad_bf16(ws + w.off_Hbf[l], p->n_vert, L.d_in, L.d_out, 0, dP, grads[l].dV, grads[l].dW0, st);
+            else rc = launch_weight_grad(Hprev, p->n_vert, L.d_in, L.d_out, 0, nullptr, Gl, grads[l].dV, grads[l].dW0, st);
+            if (rc != KGE_OK) return rc;
+            if (need_in) {
+                if (bf) {
+                    rc = launch_input_grad_bf16(dP, p->n_vert, L.d_in, L.d_out, 0, ws + w.off_Wbf[l], Self, st);
+                    if (rc != KGE_OK) return rc;
+                    rc = launch_apply_relation_weights_t_bf16(p, dP, L.d_out, ws + w.off_Wrb[l], L.d_in, L.d_out, dZ, st);
+                } else {
+                    rc = launch_input_grad(nullptr, Gl, p->n_vert, L.d_in, L.d_out, 0, L.V, L.W0, Self, st);
+                    if (rc != KGE_OK) return rc;
+                    rc = launch_apply_relation_weights_t(p, Gl, (const float *)(ws + w.off_Wrel[l]), L.d_in, L.d_out,
+                                                         (float *)dZ, st);
+                }
+                if (rc != KGE_OK) return rc;
+                rc = launch_sum_edges_out(p, dZ, bf, L.d_in, Self, dst, part, l > 0 ? kge_cgraph_layer(cg, l - 1) : nullptr, st);
+                if (rc != KGE_OK) return rc;
+                gin = dst;
+            }
+            continue;
+        }
         if (agg && !bf) {
             rc = launch_rel_outer(p, (const float *)(ws + w.off_Z[l]), Gl, L.d_in, L.d_out, C, st);
             if (rc != KGE_OK) return rc;

@@ -55,6 +55,7 @@ struct kge_partition {
     float *dm_invc;
     int32_t *sm_ptr, *sm_dst, *sm_rel;
     float *sm_invc;
+    int32_t *sm_seg;    // [E] run id of each edge in source-major order
     int32_t *rel_ptr;   // [2R+1] run range per relation
     kge_heavy_index hv_dm, hv_sm, hv_seg;   // heavy destinations, sources, runs
     // the runs grouped by destination (order dst, rel): dr_seg = run id, dr_rel = its relation
@@ -63,8 +64,12 @@ struct kge_partition {
     // each relation's run range cut into chunks of at most KGE_REL_CHUNK runs
     int32_t n_relc;
     int32_t *relc_rel, *relc_beg, *relc_end;
+    // and into row tiles of at most KGE_REL_TILE runs
+    int32_t n_relt;
+    int32_t *relt_rel, *relt_beg, *relt_end;
 };
 #define KGE_REL_CHUNK 2048
+#define KGE_REL_TILE 128
 
 // Optional per-kernel timing with HIP events on the launch stream (kge_profile_enable).
 struct KgeProfScope {
@@ -144,6 +149,36 @@ int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, i
 int launch_aggregate_runs(const kge_partition *p, const void *Z, const float *a, int32_t B, int32_t d,
                           void *Y, int64_t ld, int msg_bf16, float *partial, const uint8_t *row_active,
                           hipStream_t st);
+
+// gather.hip, relation-weight order ------------------------------------------
+// out[i] = act( sum over the runs (r, i) of destination i of U[run][:] + Self[i] ); U [S][d] fp32 or bf16;
+// zero rows where active[i] == 0; `partial`: [hv_dr.n_units][d] floats
+int launch_sum_runs(const kge_partition *p, const void *U, int u_bf16, int32_t d, const float *Self, int act,
+                    float *out, float *out2, float *partial, const uint8_t *active, hipStream_t st);
+// out[j] = sum over the edges e out of j of (1/c_e) dZ[run(e)][:] + Self[j]; `partial`: [hv_sm.n_units][d] floats
+int launch_sum_edges_out(const kge_partition *p, const void *dZ, int z_bf16, int32_t d, const float *Self,
+                         float *out, float *partial, const uint8_t *active, hipStream_t st);
+
+// gemm.hip / gemm_bf16.hip, relation-weight order -----------------------------
+// Wrel[r] = sum_b a[r][b] V_b ([2R][d_in*d_out] floats)
+int launch_relation_weights(const float *a, int32_t R2, int32_t B, const float *V, int64_t dd, float *Wrel,
+                            hipStream_t st);
+// dV[b] = sum_r a[r][b] C[r]   (overwrites dV)
+int launch_basis_grad_from_relations(const float *a, int32_t R2, int32_t B, const float *C, int64_t dd, float *dV,
+                                     hipStream_t st);
+// U[s] = Z[s] Wrel[rel(s)]  and  dZ[s] = G[dst(s)] Wrel[rel(s)]^T   (fp32)
+int launch_apply_relation_weights(const kge_partition *p, const float *Z, const float *Wrel, int32_t d_in,
+                                  int32_t d_out, float *U, hipStream_t st);
+int launch_apply_relation_weights_t(const kge_partition *p, const float *G, const float *Wrel, int32_t d_in,
+                                    int32_t d_out, float *dZ, hipStream_t st);
+// bf16 copies of Wrel: Wb [2R][d_in][d_out] and WbT [2R][d_out][d_in]
+int launch_cvt_relation_weights_bf16(const float *Wrel, int32_t R2, int32_t d_in, int32_t d_out, void *Wb, void *WbT,
+                                     hipStream_t st);
+// the same two products from bf16 operands, bf16 results; Gbf rows are ldg elements apart
+int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, const void *WbT, int32_t d_in,
+                                       int32_t d_out, void *U, hipStream_t st);
+int launch_apply_relation_weights_t_bf16(const kge_partition *p, const void *Gbf, int64_t ldg, const void *Wb,
+                                         int32_t d_in, int32_t d_out, void *dZ, hipStream_t st);
 
 // gemm.hip, aggregate-first order ---------------------------------------------
 // out[i][:] = act( sum_b Y[i][b][:] V_b + H[i][:] W0 ), zero rows where row_active[i] == 0; out2 optional copy

@@ -88,6 +88,8 @@ __device__ __forceinline__ RowWork row_work(int64_t wid, const int32_t *__restri
 
 // ------------------------------------------------------------------ forward
 //   out[i][:] = act( sum_e invc_e sum_b a[rel_e][b] P[src_e][b][:] + Self[i][:] )
+// With a == null (and B = 1) the sum is plain: out[i] = act( sum_e w_e P[idx_e] + Self[i] ), w = 1 if
+// dm_invc is null; dm_rel may then be null too.
 template <bool BF16, int LPR>
 __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
     const int32_t *__restrict__ dm_ptr, const int32_t *__restrict__ dm_src,
@@ -130,7 +132,11 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
         const int cnt = min(64, rw.end - e0);
         int32_t my_src = 0, my_rel = 0;
         float my_w = 0.f;
-        if (lane < cnt) { my_src = dm_src[e0 + lane]; my_rel = dm_rel[e0 + lane]; my_w = dm_invc[e0 + lane]; }
+        if (lane < cnt) {
+            my_src = dm_src[e0 + lane];
+            my_rel = dm_rel ? dm_rel[e0 + lane] : 0;
+            my_w = dm_invc ? dm_invc[e0 + lane] : 1.f;
+        }
         const int erounds = (cnt + GE - 1) / GE;        // uniform trip counts for all lanes
         const int items = erounds * nb;
         int er = 0, bi = 0;                             // current (edge round, basis slot)
@@ -149,7 +155,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
                 coef[u] = 0.f;
                 raw[u] = make_uint4(0u, 0u, 0u, 0u);
                 if (ok) {
-                    coef[u] = a[(int64_t)rel * B + b] * w;
+                    coef[u] = a ? a[(int64_t)rel * B + b] * w : w;
                     if (kact) raw[u] = MsgRow<BF16>::load_raw(P, ((int64_t)src * B + b) * d + kl * VEC);
                 }
                 if (++bi == nb) { bi = 0; ++er; }
@@ -785,6 +791,52 @@ int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, c
         KGE_LAUNCH_CHECK();
     }
     return KGE_OK;
+}
+
+// out[i] = act( sum_{q in row i of the view} w_q X[idx_q][:] + Self[i] ),  X rows of d elements (fp32 or bf16)
+static int launch_row_sum(const int32_t *ptr, const int32_t *idx, const float *w, int64_t n_rows,
+                          const kge_heavy_index &hx, const char *name, const void *X, int x_bf16, int32_t d,
+                          const float *Self, int act, float *out, float *out2, float *partial,
+                          const uint8_t *active, hipStream_t st)
+{
+    if (n_rows == 0) return KGE_OK;
+    const int vec = x_bf16 ? 8 : 4;
+    const int lpr = pow2_at_least((d + vec - 1) / vec);
+    KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the aggregation kernel", d);
+    const unsigned grid = (unsigned)cdiv(n_rows + hx.n_units, WPB);
+    {
+        KGE_PROF(name, st);
+#define RS_ARGS ptr, idx, nullptr, w, n_rows, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, X, nullptr, 1, d, 1, \
+                Self, act, out, out2, partial, active
+        if (x_bf16) { DISPATCH_LPR(lpr, (k_gather_fwd<true, L><<<grid, 64 * WPB, 0, st>>>(RS_ARGS))); }
+        else { DISPATCH_LPR(lpr, (k_gather_fwd<false, L><<<grid, 64 * WPB, 0, st>>>(RS_ARGS))); }
+#undef RS_ARGS
+    }
+    KGE_LAUNCH_CHECK();
+    if (hx.n_hv > 0) {
+        KGE_PROF("gather_fwd_fin", st);
+        const int64_t n = (int64_t)hx.n_hv * (d / 4);
+        k_gather_fwd_finish<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, d,
+                                                                   Self, act, out, out2, active);
+        KGE_LAUNCH_CHECK();
+    }
+    return KGE_OK;
+}
+
+// out[i] = act( sum over the runs (r, i) of destination i of U[run][:] + Self[i] )
+int launch_sum_runs(const kge_partition *p, const void *U, int u_bf16, int32_t d, const float *Self, int act,
+                    float *out, float *out2, float *partial, const uint8_t *active, hipStream_t st)
+{
+    return launch_row_sum(p->dr_ptr, p->dr_seg, nullptr, p->n_vert, p->hv_dr, "sum_runs", U, u_bf16, d, Self, act,
+                          out, out2, partial, active, st);
+}
+
+// dH[j] = sum over the edges e out of j of invc_e dZ[run(e)][:] + Self[j]
+int launch_sum_edges_out(const kge_partition *p, const void *dZ, int z_bf16, int32_t d, const float *Self,
+                         float *out, float *partial, const uint8_t *active, hipStream_t st)
+{
+    return launch_row_sum(p->sm_ptr, p->sm_seg, p->sm_invc, p->n_vert, p->hv_sm, "sum_edges_out", dZ, z_bf16, d, Self,
+                          KGE_ACT_IDENTITY, out, nullptr, partial, active, st);
 }
 
 int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t n, float *G, hipStream_t st)

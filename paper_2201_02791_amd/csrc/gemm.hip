@@ -28,8 +28,12 @@ constexpr int BM = 128, BN = 128, BK = 16, PADL = 4, GT = 256;
 // ---- operand sources: load4(row, col) returns 4 consecutive elements along the contiguous
 // dimension starting at (row, col); out-of-range -> zeros.  Contiguous extents are multiples of 4.
 
+// Hooks every source and epilogue has: limit_rows(e) hides rows >= e (a row tile that ends inside the
+// block), bind(g) selects group g's matrix or output.  No-ops where they mean nothing.
 struct SrcRowMajorF32 {          // X[r][c], c contiguous
     const float *p; int64_t rows; int32_t cols;
+    __device__ __forceinline__ void limit_rows(int64_t e) { if (e < rows) rows = e; }
+    __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ float4 load4(int64_t r, int32_t c) const
     {
         if (r >= rows || c >= cols) return make_float4(0.f, 0.f, 0.f, 0.f);
@@ -40,6 +44,8 @@ struct SrcRowMajorF32 {          // X[r][c], c contiguous
 // [V_1 .. V_B | W0] viewed as a (d_in x (B+1) d_out) matrix, column index contiguous inside a block
 struct SrcWcat {
     const float *V, *W0; int32_t d_in, d_out, B;
+    __device__ __forceinline__ void limit_rows(int64_t) {}
+    __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ float4 load4(int64_t k, int32_t c) const
     {
         int32_t nc = (B + 1) * d_out;
@@ -53,6 +59,8 @@ struct SrcWcat {
 // [dP | G] viewed as an (N x (B+1) d_out) matrix, both fp32
 struct SrcXcat {
     const float *dP; const float *G; int64_t rows; int32_t d_out, B;
+    __device__ __forceinline__ void limit_rows(int64_t) {}
+    __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ float4 load4(int64_t r, int32_t c) const
     {
         int32_t bd = B * d_out;
@@ -65,6 +73,8 @@ struct SrcXcat {
 // [V_1; ..; V_B; W0] viewed as a ((B+1) d_in x d_out) matrix (V's own memory order, then W0)
 struct SrcWstack {
     const float *V, *W0; int32_t d_in, d_out, B;
+    __device__ __forceinline__ void limit_rows(int64_t) {}
+    __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ float4 load4(int64_t k, int32_t c) const
     {
         const int64_t bk = (int64_t)B * d_in;
@@ -77,6 +87,8 @@ struct SrcWstack {
 // rows of X picked through an index list: row k is X[idx[k]]
 struct SrcGatherRows {
     const float *X; const int32_t *idx; int64_t n_idx; int32_t cols;
+    __device__ __forceinline__ void limit_rows(int64_t e) { if (e < n_idx) n_idx = e; }
+    __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ float4 load4(int64_t k, int32_t c) const
     {
         if (k >= n_idx || c >= cols) return make_float4(0.f, 0.f, 0.f, 0.f);
@@ -84,10 +96,23 @@ struct SrcGatherRows {
     }
 };
 
+// one (rows x cols) matrix per group, W[g][r][c]
+struct SrcGroupMat {
+    const float *W; int32_t rows, cols;
+    __device__ __forceinline__ void limit_rows(int64_t) {}
+    __device__ __forceinline__ void bind(int32_t g) { W += (int64_t)g * rows * cols; }
+    __device__ __forceinline__ float4 load4(int64_t r, int32_t c) const
+    {
+        if (r >= rows || c >= cols) return make_float4(0.f, 0.f, 0.f, 0.f);
+        return *reinterpret_cast<const float4 *>(W + r * cols + c);
+    }
+};
+
 // ---- epilogues: store(m, n, value); bind(g) tells a grouped launch which group the block works on
 struct EpiProject {             // columns < B*d_out go to P, the rest to Self
     float *P; float *Self; int64_t rows; int32_t d_out, B;
     __device__ __forceinline__ void bind(int32_t) {}
+    __device__ __forceinline__ void limit_rows(int64_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         int32_t bd = B * d_out;
@@ -100,6 +125,7 @@ struct EpiProject {             // columns < B*d_out go to P, the rest to Self
 struct EpiWeightGrad {          // atomic accumulation of split-K partial tiles
     float *dV, *dW0; int32_t d_in, d_out, B;
     __device__ __forceinline__ void bind(int32_t) {}
+    __device__ __forceinline__ void limit_rows(int64_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         int32_t bd = B * d_out;
@@ -113,6 +139,7 @@ struct EpiWeightGrad {          // atomic accumulation of split-K partial tiles
 struct EpiRowMajor {
     float *out; int64_t rows; int32_t cols;
     __device__ __forceinline__ void bind(int32_t) {}
+    __device__ __forceinline__ void limit_rows(int64_t e) { if (e < rows) rows = e; }
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         if (m < rows && n < cols) out[m * cols + n] = v;
@@ -122,6 +149,7 @@ struct EpiRowMajor {
 struct EpiRowMajorAtomic {      // split-K partial tiles
     float *out; int64_t rows; int32_t cols;
     __device__ __forceinline__ void bind(int32_t) {}
+    __device__ __forceinline__ void limit_rows(int64_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         if (m < rows && n < cols) unsafeAtomicAdd(out + m * cols + n, v);
@@ -131,6 +159,7 @@ struct EpiRowMajorAtomic {      // split-K partial tiles
 struct EpiAct {                 // activation, zero rows outside the sub-graph, optional second copy
     float *out, *out2; int64_t rows; int32_t cols; int act; const uint8_t *row_active;
     __device__ __forceinline__ void bind(int32_t) {}
+    __device__ __forceinline__ void limit_rows(int64_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         if (m >= rows || n >= cols) return;
@@ -144,6 +173,7 @@ struct EpiAct {                 // activation, zero rows outside the sub-graph, 
 struct EpiRelOuter {            // C[group] (d_in x d_out) accumulates the chunks of one relation
     float *C; int32_t d_in, d_out; int32_t group;
     __device__ __forceinline__ void bind(int32_t g) { group = g; }
+    __device__ __forceinline__ void limit_rows(int64_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         if (m < d_in && n < d_out) unsafeAtomicAdd(C + ((int64_t)group * d_in + m) * d_out + n, v);
@@ -158,14 +188,24 @@ template <class SA, bool A_KCONTIG, class SB, bool B_KCONTIG, class EPI>
 __global__ __launch_bounds__(GT) void k_gemm(SA srcA, SB srcB, EPI epi, int64_t K, int64_t kchunk,
                                              const int32_t *__restrict__ g_id = nullptr,
                                              const int32_t *__restrict__ g_beg = nullptr,
-                                             const int32_t *__restrict__ g_end = nullptr)
+                                             const int32_t *__restrict__ g_end = nullptr,
+                                             const int32_t *__restrict__ mt_id = nullptr,
+                                             const int32_t *__restrict__ mt_beg = nullptr,
+                                             const int32_t *__restrict__ mt_end = nullptr)
 {
     __shared__ __attribute__((aligned(16))) float As[BK][BM + PADL];
     __shared__ __attribute__((aligned(16))) float Bs[BK][BN + PADL];
 
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int wm = w >> 1, wn = w & 1;
-    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    // row tiles: blockIdx.x * BM, or, with a tile list (mt_beg non-null), rows [mt_beg[x], mt_end[x]) of
+    // group mt_id[x] (at most BM rows): A and the output are cut at the tile's end, B is the group's matrix
+    int64_t m0 = (int64_t)blockIdx.x * BM;
+    if (mt_beg) {
+        m0 = mt_beg[blockIdx.x];
+        const int64_t me = mt_end[blockIdx.x];
+        srcA.limit_rows(me); epi.limit_rows(me); srcB.bind(mt_id[blockIdx.x]);
+    }
     const int32_t n0 = blockIdx.y * BN;
     int64_t kbeg = (int64_t)blockIdx.z * kchunk;
     int64_t kend = (kbeg + kchunk < K) ? kbeg + kchunk : K;
@@ -402,5 +442,104 @@ int launch_coeff_contract(const kge_partition *p, const float *C, const float *V
         k_gemm<SrcRowMajorF32, true, SrcRowMajorF32, true, EpiRowMajorAtomic><<<grid, GT, 0, st>>>(sa, sb, ep, dd, kchunk);
         KGE_LAUNCH_CHECK();
     }
+    return KGE_OK;
+}
+
+// ---- relation-weight order ------------------------------------------------------------------
+namespace {
+
+// out[i][x] = sum_k coef(i, k) M[k][x],  coef(i, k) = TRANS ? c[k][i] : c[i][k]   (c is [ni][nk], or [nk][ni])
+// One block: 16 rows i, 1024 columns x; M is read once per 16 rows.
+template <bool TRANS>
+__global__ __launch_bounds__(256) void k_lincomb(const float *__restrict__ c, int32_t ni, int32_t nk,
+                                                 const float *__restrict__ M, int64_t nx, float *__restrict__ out)
+{
+    __shared__ float sc[16][64];
+    const int i0 = blockIdx.y * 16;
+    const int64_t x = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    float4 acc[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int k0 = 0; k0 < nk; k0 += 64) {
+        __syncthreads();
+        for (int q = threadIdx.x; q < 16 * 64; q += 256) {
+            const int j = q >> 6, kk = q & 63;
+            const int i = i0 + j, k = k0 + kk;
+            sc[j][kk] = (i < ni && k < nk) ? (TRANS ? c[(int64_t)k * ni + i] : c[(int64_t)i * nk + k]) : 0.f;
+        }
+        __syncthreads();
+        const int kn = min(64, nk - k0);
+        if (x < nx)
+            for (int kk = 0; kk < kn; ++kk) {
+                const float4 m = *reinterpret_cast<const float4 *>(M + (int64_t)(k0 + kk) * nx + x);
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const float w = sc[j][kk];
+                    acc[j].x = fmaf(w, m.x, acc[j].x); acc[j].y = fmaf(w, m.y, acc[j].y);
+                    acc[j].z = fmaf(w, m.z, acc[j].z); acc[j].w = fmaf(w, m.w, acc[j].w);
+                }
+            }
+    }
+    if (x < nx)
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if (i0 + j < ni) *reinterpret_cast<float4 *>(out + (int64_t)(i0 + j) * nx + x) = acc[j];
+}
+
+}  // namespace
+
+// Wrel[r] = sum_b a[r][b] V_b   ([2R][d_in*d_out] floats): Eq. 2 written out for every relation
+int launch_relation_weights(const float *a, int32_t R2, int32_t B, const float *V, int64_t dd, float *Wrel,
+                            hipStream_t st)
+{
+    if (R2 == 0) return KGE_OK;
+    dim3 grid((unsigned)cdiv(dd, 1024), (unsigned)cdiv(R2, 16), 1);
+    KGE_PROF("rel_weights", st);
+    k_lincomb<false><<<grid, 256, 0, st>>>(a, R2, B, V, dd, Wrel);
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+// dV_b = sum_r a[r][b] C[r]   (the chain rule on Wrel[r] = sum_b a[r][b] V_b with dWrel = C)
+int launch_basis_grad_from_relations(const float *a, int32_t R2, int32_t B, const float *C, int64_t dd, float *dV,
+                                     hipStream_t st)
+{
+    dim3 grid((unsigned)cdiv(dd, 1024), (unsigned)cdiv(B, 16), 1);
+    KGE_PROF("basis_grad", st);
+    k_lincomb<true><<<grid, 256, 0, st>>>(a, B, R2, C, dd, dV);
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+// U[s] = Z[s] Wrel[rel(s)]   (S x d_in) -> (S x d_out), one row tile per (relation, <= 128 runs)
+int launch_apply_relation_weights(const kge_partition *p, const float *Z, const float *Wrel, int32_t d_in,
+                                  int32_t d_out, float *U, hipStream_t st)
+{
+    if (p->n_relt == 0) return KGE_OK;
+    KGE_REQUIRE(cdiv(d_out, BN) <= 65535, KGE_ERANGE, "d_out too large");
+    dim3 grid((unsigned)p->n_relt, (unsigned)cdiv(d_out, BN), 1);
+    SrcRowMajorF32 sa{Z, p->n_seg, d_in};
+    SrcGroupMat sb{Wrel, d_in, d_out};
+    EpiRowMajor ep{U, p->n_seg, d_out};
+    KGE_PROF("apply_rel", st);
+    k_gemm<SrcRowMajorF32, true, SrcGroupMat, false, EpiRowMajor><<<grid, GT, 0, st>>>(
+        sa, sb, ep, d_in, d_in, nullptr, nullptr, nullptr, p->relt_rel, p->relt_beg, p->relt_end);
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+// dZ[s] = G[dst(s)] Wrel[rel(s)]^T   (S x d_out) -> (S x d_in)
+int launch_apply_relation_weights_t(const kge_partition *p, const float *G, const float *Wrel, int32_t d_in,
+                                    int32_t d_out, float *dZ, hipStream_t st)
+{
+    if (p->n_relt == 0) return KGE_OK;
+    dim3 grid((unsigned)p->n_relt, (unsigned)cdiv(d_in, BN), 1);
+    SrcGatherRows sa{G, p->seg_dst, p->n_seg, d_out};
+    SrcGroupMat sb{Wrel, d_in, d_out};
+    EpiRowMajor ep{dZ, p->n_seg, d_in};
+    KGE_PROF("apply_rel_t", st);
+    k_gemm<SrcGatherRows, true, SrcGroupMat, true, EpiRowMajor><<<grid, GT, 0, st>>>(
+        sa, sb, ep, d_out, d_out, nullptr, nullptr, nullptr, p->relt_rel, p->relt_beg, p->relt_end);
+    KGE_LAUNCH_CHECK();
     return KGE_OK;
 }

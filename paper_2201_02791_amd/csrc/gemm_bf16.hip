@@ -50,7 +50,8 @@ struct MatBF {
     __device__ __forceinline__ uint4 oct(int64_t r, int32_t c) const
     {
         if (r >= rows || c >= cols) return make_uint4(0u, 0u, 0u, 0u);
-        return *reinterpret_cast<const uint4 *>(p + r * ld + c);
+        const int64_t rr = idx ? (int64_t)idx[r] : r;
+        return *reinterpret_cast<const uint4 *>(p + rr * ld + c);
     }
     __device__ __forceinline__ uint32_t pair(int64_t r, int32_t c) const
     {
@@ -102,6 +103,18 @@ struct EpiRowMajorF32 {
     }
     __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
 };
+struct EpiRowsBF16Staged {    // out[m][n] as bf16, rows below `rows` only; through LDS for 16-byte stores
+    static constexpr bool staged = true;
+    uint16_t *out; int64_t rows; int32_t cols;
+    __device__ __forceinline__ void bind(int32_t) {}
+    __device__ __forceinline__ void store8(int64_t m, int32_t n, const float4 &x, const float4 &y) const
+    {
+        if (m >= rows || n >= cols) return;
+        *reinterpret_cast<uint4 *>(out + m * cols + n) =
+            make_uint4(pack2(x.x, x.y), pack2(x.z, x.w), pack2(y.x, y.y), pack2(y.z, y.w));
+    }
+    __device__ __forceinline__ void store(int64_t, int32_t, float) const {}
+};
 struct EpiActF32 {            // activation, zero rows outside the sub-graph, optional second copy
     static constexpr bool staged = false;
     float *out, *out2; int64_t rows; int32_t cols; int act; const uint8_t *row_active;
@@ -145,7 +158,10 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
                                                      int32_t tiles_m, int32_t tiles_n, int32_t n_splits,
                                                      const int32_t *__restrict__ g_id,
                                                      const int32_t *__restrict__ g_beg,
-                                                     const int32_t *__restrict__ g_end)
+                                                     const int32_t *__restrict__ g_end,
+                                                     const int32_t *__restrict__ mt_id,
+                                                     const int32_t *__restrict__ mt_beg,
+                                                     const int32_t *__restrict__ mt_end, int64_t b_group_stride)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint16_t (*As)[LDK] = reinterpret_cast<uint16_t (*)[LDK]>(smem);
@@ -169,7 +185,17 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
     if (prow >= rows_total || tn >= tiles_n) return;          // padding blocks of the last patches
     const int32_t tm = (int32_t)(prow % tiles_m);
     const int64_t bid = prow / tiles_m;                        // split index
-    const int64_t m0 = (int64_t)tm * TM;
+    // row tiles: tm * TM, or, with a tile list (mt_beg non-null), rows [mt_beg[tm], mt_end[tm]) of group
+    // mt_id[tm] (at most TM rows): A is cut at the tile's end, B is the group's matrix, and the
+    // epilogue must not write past the tile (its own row bound is set by the launcher's EPI type)
+    int64_t m0 = (int64_t)tm * TM;
+    int64_t m_end = A.rows;
+    if (mt_beg) {
+        m0 = mt_beg[tm];
+        m_end = mt_end[tm];
+        if (KC) A.rows = m_end;
+        B.p += (int64_t)mt_id[tm] * b_group_stride;
+    }
     const int32_t n0 = tn * TN;
     int64_t kbeg = bid * kchunk;
     int64_t kend = (kbeg + kchunk < K) ? kbeg + kchunk : K;
@@ -270,7 +296,8 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
                 const int row = it * 4 + (lane >> 4), c8 = (lane & 15) * 8;
                 const float4 x = *reinterpret_cast<const float4 *>(&stage[row * EPI_LD + c8]);
                 const float4 y = *reinterpret_cast<const float4 *>(&stage[row * EPI_LD + c8 + 4]);
-                epi.store8(m0 + wm * 64 + i * 32 + row, n0 + wn * 128 + c8, x, y);
+                if (m0 + wm * 64 + i * 32 + row < m_end || !mt_beg)
+                    epi.store8(m0 + wm * 64 + i * 32 + row, n0 + wn * 128 + c8, x, y);
             }
         }
     } else {
@@ -282,7 +309,7 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
                 for (int v = 0; v < 16; ++v) {
                     const int row = wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                     const int col = wn * 128 + j * 32 + (lane & 31);
-                    epi.store(m0 + row, n0 + col, acc[i][j][v]);
+                    if (m0 + row < m_end || !mt_beg) epi.store(m0 + row, n0 + col, acc[i][j][v]);
                 }
     }
 }
@@ -341,10 +368,36 @@ __global__ void k_cvt_wstack_t(const float *__restrict__ V, const float *__restr
     WstT[(int64_t)c * K + kk] = (uint16_t)(pack2(v, 0.f) & 0xffffu);
 }
 
+// Wrel (fp32 [G][rows][cols]) -> bf16 copies in both orientations: Wb[g][r][c] and WbT[g][c][r]
+__global__ __launch_bounds__(256) void k_cvt_group_mats(const float *__restrict__ W, int32_t rows, int32_t cols,
+                                                        uint16_t *__restrict__ Wb, uint16_t *__restrict__ WbT)
+{
+    __shared__ uint16_t tile[32][33];
+    const int64_t g = blockIdx.z;
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 x 8
+    const float *Wg = W + g * rows * cols;
+    for (int rr = ty; rr < 32; rr += 8) {
+        const int r = r0 + rr, c = c0 + tx;
+        uint16_t h = 0;
+        if (r < rows && c < cols) {
+            h = (uint16_t)(pack2(Wg[(int64_t)r * cols + c], 0.f) & 0xffffu);
+            Wb[g * rows * cols + (int64_t)r * cols + c] = h;
+        }
+        tile[rr][tx] = h;
+    }
+    __syncthreads();
+    for (int cc = ty; cc < 32; cc += 8) {
+        const int c = c0 + cc, r = r0 + tx;
+        if (r < rows && c < cols) WbT[g * rows * cols + (int64_t)c * rows + r] = tile[tx][cc];
+    }
+}
+
 template <bool KC, class EPI>
 int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64_t kchunk, int32_t tiles_m,
                 int32_t tiles_n, int64_t splits, hipStream_t st, const int32_t *g_id = nullptr,
-                const int32_t *g_beg = nullptr, const int32_t *g_end = nullptr)
+                const int32_t *g_beg = nullptr, const int32_t *g_end = nullptr, const int32_t *mt_id = nullptr,
+                const int32_t *mt_beg = nullptr, const int32_t *mt_end = nullptr, int64_t b_group_stride = 0)
 {
     const int pn = tiles_n >= 8 ? 8 : (tiles_n >= 4 ? 4 : (tiles_n >= 2 ? 2 : 1)), pm = 64 / pn;
     const int64_t n_patches = cdiv(splits * tiles_m, pm) * cdiv(tiles_n, pn);
@@ -358,7 +411,7 @@ int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64
         attr_set = true;
     }
     k_gemm_bf16<KC, EPI><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n, (int32_t)splits,
-                                                            g_id, g_beg, g_end);
+                                                            g_id, g_beg, g_end, mt_id, mt_beg, mt_end, b_group_stride);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
@@ -489,4 +542,47 @@ int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const void *G
     KGE_PROF("rel_outer", st);
     return launch_gemm<false, EpiRelOuterAtomic>(A, Bm, ep, p->n_seg, 0, tiles_m, tiles_n, p->n_relc, st,
                                                  p->relc_rel, p->relc_beg, p->relc_end);
+}
+
+int launch_cvt_relation_weights_bf16(const float *Wrel, int32_t R2, int32_t d_in, int32_t d_out, void *Wb, void *WbT,
+                                     hipStream_t st)
+{
+    if (R2 == 0) return KGE_OK;
+    KGE_REQUIRE(R2 <= 65535, KGE_ERANGE, "too many relations for one conversion launch");
+    dim3 grid((unsigned)cdiv(d_out, 32), (unsigned)cdiv(d_in, 32), (unsigned)R2);
+    KGE_PROF("cvt_weights", st);
+    k_cvt_group_mats<<<grid, 256, 0, st>>>(Wrel, d_in, d_out, reinterpret_cast<uint16_t *>(Wb),
+                                          reinterpret_cast<uint16_t *>(WbT));
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+// U[s] = Zbf[s] Wrel[rel(s)]   bf16 in, bf16 out; WbT: bf16 [2R][d_out][d_in]
+int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, const void *WbT, int32_t d_in,
+                                       int32_t d_out, void *U, hipStream_t st)
+{
+    if (p->n_relt == 0) return KGE_OK;
+    const int32_t tiles_n = (int32_t)cdiv(d_out, TN);
+    MatBF A{reinterpret_cast<const uint16_t *>(Zbf), p->n_seg, d_in, d_in, nullptr};
+    MatBF Bm{reinterpret_cast<const uint16_t *>(WbT), d_out, d_in, d_in, nullptr};
+    EpiRowsBF16Staged ep{reinterpret_cast<uint16_t *>(U), p->n_seg, d_out};
+    KGE_PROF("apply_rel", st);
+    return launch_gemm<true, EpiRowsBF16Staged>(A, Bm, ep, d_in, cdiv(d_in, TK) * TK, p->n_relt, tiles_n, 1, st, nullptr,
+                                                nullptr, nullptr, p->relt_rel, p->relt_beg, p->relt_end,
+                                                (int64_t)d_in * d_out);
+}
+
+// dZ[s] = Gbf[dst(s)] Wrel[rel(s)]^T   Gbf rows of d_out elements, ldg apart; Wb: bf16 [2R][d_in][d_out]
+int launch_apply_relation_weights_t_bf16(const kge_partition *p, const void *Gbf, int64_t ldg, const void *Wb,
+                                         int32_t d_in, int32_t d_out, void *dZ, hipStream_t st)
+{
+    if (p->n_relt == 0) return KGE_OK;
+    const int32_t tiles_n = (int32_t)cdiv(d_in, TN);
+    MatBF A{reinterpret_cast<const uint16_t *>(Gbf), p->n_seg, d_out, ldg, p->seg_dst};
+    MatBF Bm{reinterpret_cast<const uint16_t *>(Wb), d_in, d_out, d_out, nullptr};
+    EpiRowsBF16Staged ep{reinterpret_cast<uint16_t *>(dZ), p->n_seg, d_in};
+    KGE_PROF("apply_rel_t", st);
+    return launch_gemm<true, EpiRowsBF16Staged>(A, Bm, ep, d_out, cdiv(d_out, TK) * TK, p->n_relt, tiles_n, 1, st, nullptr,
+                                                nullptr, nullptr, p->relt_rel, p->relt_beg, p->relt_end,
+                                                (int64_t)d_in * d_out);
 }

@@ -392,7 +392,7 @@ __global__ void k_view_keys(const uint64_t *keys, int64_t E, int shift, uint64_t
 // After sorting positions by one endpoint: other endpoint, relation and 1/c of every edge.
 __global__ void k_view_emit(const uint32_t *pos_sorted, int64_t E, const uint64_t *keys, int vbits,
                             int other_shift, const uint32_t *edge_seg, const float *inv_c,
-                            int32_t *o_vert, int32_t *o_rel, float *o_invc)
+                            int32_t *o_vert, int32_t *o_rel, float *o_invc, int32_t *o_seg)
 {
     int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= E) return;
@@ -401,6 +401,7 @@ __global__ void k_view_emit(const uint32_t *pos_sorted, int64_t E, const uint64_
     o_vert[q] = (int32_t)((k >> other_shift) & vmask);
     o_rel[q] = (int32_t)(k >> (2 * vbits));
     o_invc[q] = inv_c[edge_seg[e]];
+    if (o_seg) o_seg[q] = (int32_t)edge_seg[e];
 }
 
 // ptr[v] = first position q with sorted[q] >= v, for v in [0, nv]; ptr[nv] = n.
@@ -661,6 +662,7 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
     // --- destination-major and source-major views: stable sorts of edge positions
     TRY(palloc(&p->dm_ptr, N + 1)); TRY(palloc(&p->dm_src, E)); TRY(palloc(&p->dm_rel, E)); TRY(palloc(&p->dm_invc, E));
     TRY(palloc(&p->sm_ptr, N + 1)); TRY(palloc(&p->sm_dst, E)); TRY(palloc(&p->sm_rel, E)); TRY(palloc(&p->sm_invc, E));
+    TRY(palloc(&p->sm_seg, E));
     uint32_t *k2, *k2_alt, *v2, *v2_alt;
     TRY(tmp.alloc(&k2, E)); TRY(tmp.alloc(&k2_alt, E)); TRY(tmp.alloc(&v2, E)); TRY(tmp.alloc(&v2_alt, E));
     int32_t *maxdeg;
@@ -677,7 +679,8 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
             k_view_emit<<<grid_for(E), TB, 0, st>>>(v2, E, keys, vbits, other_shift, edge_seg, p->inv_c,
                                                    view == 0 ? p->dm_src : p->sm_dst,
                                                    view == 0 ? p->dm_rel : p->sm_rel,
-                                                   view == 0 ? p->dm_invc : p->sm_invc);
+                                                   view == 0 ? p->dm_invc : p->sm_invc,
+                                                   view == 0 ? nullptr : p->sm_seg);
             KGE_LAUNCH_CHECK();
         }
         k_ptr_from_sorted<uint32_t><<<grid_for(E + 1), TB, 0, st>>>(k2, E, N, ptr);
@@ -705,13 +708,26 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
     // --- chunks of each relation's run range (host side: 2R+1 offsets)
     {
         const int64_t R2 = 2 * (int64_t)n_rel;
-        std::vector<int32_t> h_rel_ptr((size_t)R2 + 1), c_rel, c_beg, c_end;
+        std::vector<int32_t> h_rel_ptr((size_t)R2 + 1), c_rel, c_beg, c_end, t_rel, t_beg, t_end;
         KGE_HIP(hipMemcpy(h_rel_ptr.data(), p->rel_ptr, sizeof(int32_t) * (size_t)(R2 + 1), hipMemcpyDeviceToHost));
         for (int64_t r = 0; r < R2; ++r)
             for (int32_t b = h_rel_ptr[r]; b < h_rel_ptr[r + 1]; b += KGE_REL_CHUNK) {
                 c_rel.push_back((int32_t)r); c_beg.push_back(b);
                 c_end.push_back(b + KGE_REL_CHUNK < h_rel_ptr[r + 1] ? b + KGE_REL_CHUNK : h_rel_ptr[r + 1]);
             }
+        // and into row tiles of at most KGE_REL_TILE runs (one output tile of the per-relation products)
+        for (int64_t r = 0; r < R2; ++r)
+            for (int32_t b = h_rel_ptr[r]; b < h_rel_ptr[r + 1]; b += KGE_REL_TILE) {
+                t_rel.push_back((int32_t)r); t_beg.push_back(b);
+                t_end.push_back(b + KGE_REL_TILE < h_rel_ptr[r + 1] ? b + KGE_REL_TILE : h_rel_ptr[r + 1]);
+            }
+        p->n_relt = (int32_t)t_rel.size();
+        TRY(palloc(&p->relt_rel, t_rel.size())); TRY(palloc(&p->relt_beg, t_rel.size())); TRY(palloc(&p->relt_end, t_rel.size()));
+        if (!t_rel.empty()) {
+            KGE_HIP(hipMemcpy(p->relt_rel, t_rel.data(), sizeof(int32_t) * t_rel.size(), hipMemcpyHostToDevice));
+            KGE_HIP(hipMemcpy(p->relt_beg, t_beg.data(), sizeof(int32_t) * t_beg.size(), hipMemcpyHostToDevice));
+            KGE_HIP(hipMemcpy(p->relt_end, t_end.data(), sizeof(int32_t) * t_end.size(), hipMemcpyHostToDevice));
+        }
         p->n_relc = (int32_t)c_rel.size();
         TRY(palloc(&p->relc_rel, c_rel.size())); TRY(palloc(&p->relc_beg, c_rel.size())); TRY(palloc(&p->relc_end, c_rel.size()));
         if (!c_rel.empty()) {
@@ -753,7 +769,7 @@ extern "C" void kge_partition_destroy(kge_partition *p)
                     p->hv_sm.hv_row, p->hv_sm.hv_unit_ptr, p->hv_sm.unit_hv,
                     p->hv_seg.hv_row, p->hv_seg.hv_unit_ptr, p->hv_seg.unit_hv,
                     p->dr_ptr, p->dr_seg, p->dr_rel, p->hv_dr.hv_row, p->hv_dr.hv_unit_ptr, p->hv_dr.unit_hv,
-                    p->relc_rel, p->relc_beg, p->relc_end};
+                    p->relc_rel, p->relc_beg, p->relc_end, p->sm_seg, p->relt_rel, p->relt_beg, p->relt_end};
     for (void *q : arrs) if (q) (void)hipFree(q);
     delete p;
 }
@@ -826,6 +842,7 @@ extern "C" int kge_partition_export(const kge_partition *p, int32_t which, void 
     case KGE_ARR_DR_PTR: src = p->dr_ptr; n = p->n_vert + 1; break;
     case KGE_ARR_DR_SEG: src = p->dr_seg; n = p->n_seg; break;
     case KGE_ARR_DR_REL: src = p->dr_rel; n = p->n_seg; break;
+    case KGE_ARR_SM_SEG: src = p->sm_seg; n = p->n_edge; break;
     default: KGE_REQUIRE(false, KGE_EINVAL, "unknown array id %d", which);
     }
     KGE_REQUIRE(bytes == 4 * n, KGE_EINVAL, "array %d has %lld bytes, caller gave %lld", which,

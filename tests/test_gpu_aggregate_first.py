@@ -1,6 +1,8 @@
-"""GPU parity of the aggregate-first order of Eq. 1-2 (run means z, per-basis sums y, one
-contraction with [V_1; ..; V_B; W_0]) against the same oracle as the project-first order: the
-two orders are algebraically identical, so every output is held to the same tolerances."""
+"""GPU parity of the two orders of Eq. 1-2 that sum neighbours before they apply weights -
+aggregate-first (run means z, per-basis sums y, one contraction with [V_1; ..; V_B; W_0]) and
+relation-weight (run means z, W_r = sum_b a_rb V_b written out, one product z W_r per run) -
+against the same oracle as the project-first order: the orders are algebraically identical, so
+every output is held to the same tolerances."""
 import sys
 
 import numpy as np
@@ -12,7 +14,9 @@ from gpu_util import (SEED, STEP, align_mask_decisions, assert_partition_equal, 
 
 pytestmark = pytest.mark.gpu
 TOL_VAL, TOL_GRAD = 1e-4, 1e-3
-AGG = 1
+AGG, RELW = 1, 2
+ORDERS = [pytest.param(AGG, id="aggregate_first"), pytest.param(RELW, id="relation_weights")]
+BF16_MODE = {AGG: 2, RELW: 3}      # the oracle's rounding points for each bf16 pipeline
 
 
 def say(*a):
@@ -46,6 +50,12 @@ def test_runs_grouped_by_destination(kb, orc):
     want_ptr = np.searchsorted(op["seg_dst"][order], np.arange(N + 1)).astype(np.int32)
     np.testing.assert_array_equal(gp.export("dr_ptr"), want_ptr)
     assert gp.export("dr_ptr")[-1] == S
+    # run id of every edge in source-major order (src, rel, dst, id)
+    lens = np.diff(op["seg_ptr"])
+    run_of_edge = np.repeat(np.arange(S), lens)
+    dst_of_edge = op["seg_dst"][run_of_edge]; rel_of_edge = op["seg_rel"][run_of_edge]
+    sm_order = np.lexsort((op["edge_id"], dst_of_edge, rel_of_edge, op["col_src"]))
+    np.testing.assert_array_equal(gp.export("sm_seg"), run_of_edge[sm_order].astype(np.int32))
 
 
 SHAPES = [
@@ -64,15 +74,16 @@ SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("shape", SHAPES, ids=[s[0] for s in SHAPES])
-def test_step_aggregate_first(kb, orc, shape):
+def test_step_aggregate_first(kb, orc, shape, order):
     name, n, R, m, d, B, n_pos, n_neg, mode, P, acts = shape
-    say("aggregate-first step", shape)
+    say("step, order", order, shape)
     spec = synth.scaled(synth.WORKLOADS[0], name=name, seed=17, n_entities=n, n_relations=R, n_triples=m,
                         d=d, n_bases=B, n_pos=n_pos, n_neg=n_neg, neg_mode=mode, n_parts=P, part_id=P - 1,
                         acts=acts, feature_std=0.5)
     head, rel, tail = random_graph(len(name) + n, n, R, m)
-    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=AGG)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=order)
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
     assert_partition_equal(gp, op)
     assert_step_close(ts, res, TOL_VAL, TOL_GRAD)
@@ -100,9 +111,10 @@ def test_intermediates_z_and_y(kb, orc):
     assert rel_err(ts.view(kb.WS_Y, 1).cpu().numpy().reshape(-1, B, d), Y) <= TOL_VAL
 
 
-def test_hub_rows_aggregate_first(kb, orc):
+@pytest.mark.parametrize("order", ORDERS)
+def test_hub_rows_aggregate_first(kb, orc, order):
     """A run of 600 edges (split into units), a destination and a source with > 256 edges."""
-    say("aggregate-first hub")
+    say("hub, order", order)
     n, R = 700, 2
     leaves = np.arange(1, 601, dtype=np.int32)
     head = np.concatenate([leaves, leaves[:50], np.array([650, 651], np.int32)])
@@ -110,14 +122,15 @@ def test_hub_rows_aggregate_first(kb, orc):
     rel = np.concatenate([np.zeros(600, np.int32), np.ones(50, np.int32), np.array([0, 1], np.int32)])
     spec = synth.scaled(synth.WORKLOADS[0], name="hub", seed=5, n_entities=n, n_relations=R,
                         n_triples=len(head), d=64, n_bases=4, n_pos=300, n_neg=2, neg_mode=1)
-    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=AGG)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=order)
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
     assert_step_close(ts, res, TOL_VAL, TOL_GRAD)
 
 
-def test_many_runs_per_destination(kb, orc):
+@pytest.mark.parametrize("order", ORDERS)
+def test_many_runs_per_destination(kb, orc, order):
     """One destination reached under 700 different relations: its list of runs is itself split."""
-    say("aggregate-first, heavy run list")
+    say("heavy run list, order", order)
     n, R = 900, 700
     head = np.arange(1, 701, dtype=np.int32)
     tail = np.zeros(700, np.int32)
@@ -126,19 +139,20 @@ def test_many_runs_per_destination(kb, orc):
     head = np.concatenate([head, extra[0]]); rel = np.concatenate([rel, extra[1]]); tail = np.concatenate([tail, extra[2]])
     spec = synth.scaled(synth.WORKLOADS[0], name="manyruns", seed=5, n_entities=n, n_relations=R,
                         n_triples=len(head), d=32, n_bases=3, n_pos=200, n_neg=1, neg_mode=1)
-    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=AGG)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=order)
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
     assert np.diff(gp.export("dr_ptr")).max() >= 700
     assert_step_close(ts, res, TOL_VAL, TOL_GRAD)
 
 
-def test_aggregate_first_with_compute_graph(kb, orc):
-    say("aggregate-first + sub-graph")
+@pytest.mark.parametrize("order", ORDERS)
+def test_aggregate_first_with_compute_graph(kb, orc, order):
+    say("sub-graph, order", order)
     n, R, m = 4000, 5, 14000
     spec = synth.scaled(synth.WORKLOADS[0], name="aggcone", seed=23, n_entities=n, n_relations=R, n_triples=m,
                         d=64, n_bases=4, n_pos=9, n_neg=2, neg_mode=1, feature_std=0.5)
     head, rel, tail = random_graph(31, n, R, m)
-    gp, ts, params, pos = gpu_step(spec, head, rel, tail, cone=True, order=AGG)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, cone=True, order=order)
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
     active, stats = ts.cg.export()
     np.testing.assert_array_equal(active, orc.compute_graph(op, pos, res["neg_ent"], 2))
@@ -149,24 +163,26 @@ def test_aggregate_first_with_compute_graph(kb, orc):
 TOL_BF16 = 2e-2
 
 
+@pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("acts,n,m,d,B,cone", [([0, 0], 600, 6000, 64, 8, False), ([1, 0], 6000, 90000, 64, 8, False),
                                                ([0, 0], 900, 9000, 96, 40, False), ([1, 0], 5000, 60000, 128, 6, True)],
                          ids=["identity", "relu", "identity_B40_d96", "relu_subgraph"])
-def test_bf16_aggregate_first(kb, orc, acts, n, m, d, B, cone):
+def test_bf16_aggregate_first(kb, orc, acts, n, m, d, B, cone, order):
     """bf16 pipeline in the aggregate-first order: inputs, run means, per-basis sums and weights are
     bf16 operands, sums fp32.  As in the project-first bf16 tests the ReLU mask is a decision taken
     from rounded values, so the full comparison is against the oracle evaluated with the same
-    rounding points (mode 2); mask-independent outputs are also held to 2e-2 against the exact one."""
-    say("bf16 aggregate-first", acts, n, m, d, B, cone)
+    rounding points (mode 2; mode 3 for the relation-weight order: inputs, run means, W_r, the per-run
+    products and W_0); mask-independent outputs are also held to 2e-2 against the exact one."""
+    say("bf16, order", order, acts, n, m, d, B, cone)
     spec = synth.scaled(synth.WORKLOADS[4], name="bf16-agg", seed=3, n_entities=n, n_relations=20,
                         n_triples=m, d=d, n_bases=B, n_pos=24 if cone else 256, n_neg=4, n_parts=2, part_id=0, acts=acts)
     head, rel, tail = synth.make_triples(spec)
-    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=AGG, cone=cone)
-    op, res = oracle_step(orc, spec, head, rel, tail, params, pos, msg_bf16=2)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=order, cone=cone)
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos, msg_bf16=BF16_MODE[order])
     assert_partition_equal(gp, op)
     rows = orc.batch_vertices(op, pos, res["neg_ent"]) if cone else None
     active = orc.compute_graph(op, pos, res["neg_ent"], len(acts)) if cone else None
-    n_adopted, res = align_mask_decisions(orc, ts, op, res, params, acts, True, 2, rows=active)
+    n_adopted, res = align_mask_decisions(orc, ts, op, res, params, acts, True, BF16_MODE[order], rows=active)
     say("mask decisions adopted from the kernel:", n_adopted)
     assert n_adopted <= 8
     errs = assert_step_close(ts, res, TOL_BF16, TOL_BF16, batch_rows=rows)

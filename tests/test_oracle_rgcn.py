@@ -259,3 +259,53 @@ def test_aggregate_first_bf16_backward(orc):
     want = np.zeros_like(a); np.add.at(want, part["seg_rel"], per_run)
     np.testing.assert_allclose(g2["da"], want, rtol=1e-10, atol=1e-12)
     assert 0 < np.abs(g2["da"] - g0["da"]).max() / np.abs(g0["da"]).max() < 2e-2
+
+
+# ------------------------------------------------------------------ relation-weight bf16 rounding (msg_bf16 = 3)
+def test_relation_weight_bf16_mode_matches_a_numpy_emulation(orc):
+    """Eq. 2 written out (W_r = sum_b a_rb V_b, rounded), run means z (rounded), one product z W_r per
+    run (rounded when stored), summed per destination with the self-loop term."""
+    part, V, a, W0, H = _small_case(orc, 14)
+    S, N = part["n_seg"], part["n_vert"]
+    lens = np.diff(part["seg_ptr"])
+    run = np.repeat(np.arange(S), lens)
+    Hq = _bf(H)
+    Z = np.zeros((S, H.shape[1])); np.add.at(Z, run, Hq[part["col_src"]])
+    Zq = _bf(Z / lens[:, None])
+    Wr = _bf(np.einsum("rb,bkc->rkc", a, V))
+    U = _bf(np.einsum("sk,skc->sc", Zq, Wr[part["seg_rel"]]))
+    want = Hq @ _bf(W0)
+    np.add.at(want, part["seg_dst"], U)
+    pre, out = orc.layer_forward(part, V, a, W0, 1, H, msg_bf16=3)
+    np.testing.assert_allclose(pre, want, rtol=1e-11, atol=1e-12)
+    np.testing.assert_array_equal(out, np.maximum(pre, 0))
+    exact, _ = orc.layer_forward(part, V, a, W0, 1, H)
+    assert 0 < np.abs(pre - exact).max() / np.abs(exact).max() < 2e-2
+    rows = np.array([0, 7, N - 1], np.int32)
+    rpre, _ = orc.layer_rows(part, rows, V, a, W0, 1, H.astype(np.float32), msg_bf16=3)
+    np.testing.assert_allclose(rpre, pre[rows], rtol=1e-11, atol=1e-12)
+    # backward: only da differs from the exact one, and it is the mode-2 value (same rounded run means)
+    dH = np.random.default_rng(3).normal(0, 1, out.shape)
+    g3 = orc.layer_backward(part, V, a, W0, 1, H, pre, dH, True, msg_bf16=3)
+    g2 = orc.layer_backward(part, V, a, W0, 1, H, pre, dH, True, msg_bf16=2)
+    for k in ("dV", "dW0", "dH", "dP", "Gpre", "da"):
+        np.testing.assert_array_equal(g3[k], g2[k])
+
+
+def test_relation_weight_bf16_mode_is_exact_on_bf16_representable_inputs(orc):
+    n, R, d_in, d_out, B = 20, 2, 4, 4, 2
+    rng = np.random.default_rng(1)
+    head, rel, tail = [], [], []
+    for t in range(n):
+        for r in range(R):
+            for j in rng.choice(n, size=int(rng.choice([1, 2, 4])), replace=False):
+                head.append(j); rel.append(r); tail.append(t)
+    head, rel, tail = (np.asarray(x, np.int32) for x in (head, rel, tail))
+    part = orc.build_partition(head, rel, tail, n, R, 1, 0, 1, 0)
+    a = np.zeros((2 * R, B)); a[:R] = rng.integers(-2, 3, (R, B))      # inverse runs (any length) get weight 0
+    V = rng.integers(-2, 3, (B, d_in, d_out)).astype(np.float64)
+    W0 = rng.integers(-2, 3, (d_in, d_out)).astype(np.float64)
+    H = rng.integers(-4, 5, (part["n_vert"], d_in)).astype(np.float64)
+    exact, _ = orc.layer_forward(part, V, a, W0, 0, H)
+    got, _ = orc.layer_forward(part, V, a, W0, 0, H, msg_bf16=3)
+    np.testing.assert_array_equal(got, exact)
