@@ -25,7 +25,7 @@ PEAK_F32_MFMA_TFLOPS = 157.3
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 
 
-def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None):
+def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None, spec_order="project"):
     """Algorithmic bytes / flops of ONE launch of a kernel (what the method itself must move
     or compute in this formulation).  Returns (bound, work).  cone: None, or the per-layer counts
     (active vertices, edges into them, runs into them) of the batch's computational sub-graph;
@@ -58,12 +58,22 @@ def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None):
         return "hbm", ne_mean * (ep * d + 4.0) + S * 12.0 + S * ep * d
     if name == "aggregate":    # per run: z row + (run id, relation); per vertex: ptr + y row written
         return "hbm", ns_mean * (ep * d + 8.0) + N * 4.0 + nv_mean * B * d * ep + R2 * B * 4.0
+    if name == "sum_runs":     # per run: u row + run id; per vertex: ptr + Self read + output write
+        return "hbm", ns_mean * (ep * d + 4.0) + N * (5.0 + 4.0 * d) + nv_mean * 4.0 * d
+    if name == "sum_edges_out":  # per edge: dz row + (run id, 1/c); per vertex: ptr + Self read + output write
+        return "hbm", E * (ep * d + 8.0) + N * (4.0 + 8.0 * d)
+    if name in ("apply_rel", "apply_rel_t"):    # one (d x d) product per run
+        return "mfma", 2.0 * S * d * d
+    if name == "rel_weights" or name == "basis_grad":
+        return "alu", 2.0 * R2 * B * d * d
     if name == "combine":
         return "mfma", gemm_flops
     if name == "rel_outer":    # C_r = sum_runs z^T G: 2 S d^2 flops; bytes S (2 d) 4
         return "mfma", 2.0 * S * d * d
     if name == "coeff_contract":
         return "mfma", 2.0 * R2 * d * d * B
+    if spec_order == "relation":      # only the self-loop term W_0 goes through these
+        gemm_flops = 2.0 * N * d * d
     if name == "project":
         return "mfma", gemm_flops
     if name == "weight_grad":
@@ -125,8 +135,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="index into the workload list (0..4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--order", choices=["project", "aggregate"], default="aggregate",
-                    help="project-first (P = H V_b, then the neighbour sum) or aggregate-first order of Eq. 1-2")
+    ap.add_argument("--order", choices=["project", "aggregate", "relation"], default="relation",
+                    help="order of Eq. 1-2: project-first (P = H V_b, then the neighbour sum), aggregate-first "
+                         "(run means, per-basis sums, one contraction) or relation-weight (run means times W_r)")
     ap.add_argument("--whole-partition", action="store_true",
                     help="propagate every vertex of the partition instead of the batch's computational sub-graph")
     ap.add_argument("--calibrate", action="store_true",
@@ -160,7 +171,8 @@ def main():
     msg = kb.MSG_BF16 if spec.msg_dtype == "bf16" else kb.MSG_F32
     ts = TrainStep(part, params, spec.acts, msg, need_dH0=not spec.fixed_features, keep_scores=True,
                    cone=not args.whole_partition,
-                   order=kb.ORDER_AGGREGATE_FIRST if args.order == "aggregate" else kb.ORDER_PROJECT_FIRST)
+                   order={"project": kb.ORDER_PROJECT_FIRST, "aggregate": kb.ORDER_AGGREGATE_FIRST,
+                          "relation": kb.ORDER_RELATION_WEIGHTS}[args.order])
     ts.set_batch(pos, spec.n_neg)
     log("workspace %.2f GB" % (ts.ws_bytes / 1e9))
 
@@ -195,10 +207,12 @@ def main():
     ep = 2 if spec.msg_dtype == "bf16" else 4
     kernels = {}
     for name, (tot_ms, calls) in prof.items():
-        bound, work = kernel_work(name, part, spec, spec.d, spec.n_bases, ep, n_pos, n_neg, cone)
+        bound, work = kernel_work(name, part, spec, spec.d, spec.n_bases, ep, n_pos, n_neg, cone, args.order)
         avg_ms = tot_ms / max(calls, 1)
         if bound == "hbm":
             ach, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+        elif bound == "alu":
+            ach, peak, unit = work / (avg_ms * 1e-3) / 1e12, PEAK_F32_MFMA_TFLOPS, "TFLOP/s"
         else:
             peak = PEAK_BF16_MFMA_TFLOPS if ep == 2 else PEAK_F32_MFMA_TFLOPS
             ach, unit = work / (avg_ms * 1e-3) / 1e12, "TFLOP/s"
@@ -232,7 +246,7 @@ def main():
                       "relations_with_inverses": 2 * spec.n_relations, "layers": spec.n_layers,
                       "positives": n_pos, "negatives_per_positive": n_neg, "parallelism": "1 partition on 1 GPU",
                       "propagation": "whole partition" if cone is None else "batch computational sub-graph",
-                      "order": args.order + "-first",
+                      "order": {"project": "project-first", "aggregate": "aggregate-first", "relation": "relation-weight"}[args.order],
                       "subgraph_vertices_edges_runs_per_layer": cone},
            "triples_per_s": T / (dt / args.steps), "loss": loss,
            "roofline": roof, "cpu_baseline": base, "kernels": kernels}

@@ -209,59 +209,72 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    uint4 ra[2], rb[4];       // the next tile, staged in registers
+    // Two tiles are in flight in registers while a third is multiplied out of LDS (24 registers per
+    // tile): k-contiguous operands as 16-byte octets, k-strided ones as raw 4-byte pairs that are
+    // transposed only when they are written to LDS, so that nothing waits for a load before the
+    // matrix-core loop.  Rows picked through an index list have their indices fetched one tile
+    // earlier still, which keeps the row loads themselves independent.
+    struct Regs { uint4 a[2], b[4]; uint32_t pa[8], pb[2][8]; };
+    Regs rg[2];
+    int32_t brow[8];          // KC = false: stored rows of B for the tile that is loaded next
 
-    auto load_tile = [&](int64_t k0) {
+    auto load_rows = [&](int64_t k0) {
+        if (!KC) {
+            const int ko = (t >> 6) * 8;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                const int64_t r = k0 + ko + kk;
+                brow[kk] = (r < kend && r < B.rows) ? (B.idx ? B.idx[r] : (int32_t)r) : -1;
+            }
+        }
+    };
+    auto load_tile = [&](int64_t k0, Regs &R) {
         if (KC) {
             const int row = t >> 2, ko = (t & 3) * 8;
             const bool kok = k0 + ko < kend;
 #pragma unroll
             for (int ps = 0; ps < 2; ++ps)
-                ra[ps] = kok ? A.oct(m0 + row + ps * 64, (int32_t)(k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
+                R.a[ps] = kok ? A.oct(m0 + row + ps * 64, (int32_t)(k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
             for (int ps = 0; ps < 4; ++ps)
-                rb[ps] = kok ? B.oct(n0 + row + ps * 64, (int32_t)(k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
+                R.b[ps] = kok ? B.oct(n0 + row + ps * 64, (int32_t)(k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
         } else {
             const int cp = t & 63, ko = (t >> 6) * 8;
-            uint32_t pr[8];
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk)
-                pr[kk] = (k0 + ko + kk < kend) ? A.pair(k0 + ko + kk, (int32_t)(m0 + 2 * cp)) : 0u;
-            transpose_pairs(pr, ra[0], ra[1]);
+                R.pa[kk] = (k0 + ko + kk < kend) ? A.pair(k0 + ko + kk, (int32_t)(m0 + 2 * cp)) : 0u;
 #pragma unroll
-            for (int ps = 0; ps < 2; ++ps) {
+            for (int ps = 0; ps < 2; ++ps)
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk)
-                    pr[kk] = (k0 + ko + kk < kend) ? B.pair(k0 + ko + kk, n0 + 2 * (cp + ps * 64)) : 0u;
-                transpose_pairs(pr, rb[2 * ps], rb[2 * ps + 1]);
-            }
+                for (int kk = 0; kk < 8; ++kk) {
+                    const int32_t c = n0 + 2 * (cp + ps * 64);
+                    R.pb[ps][kk] = (brow[kk] >= 0 && c < B.cols)
+                                       ? *reinterpret_cast<const uint32_t *>(B.p + (int64_t)brow[kk] * B.ld + c) : 0u;
+                }
         }
     };
-    auto store_tile = [&]() {
+    auto store_tile = [&](Regs &R) {
         if (KC) {
             const int row = t >> 2, ko = (t & 3) * 8;
 #pragma unroll
-            for (int ps = 0; ps < 2; ++ps) *reinterpret_cast<uint4 *>(&As[row + ps * 64][ko]) = ra[ps];
+            for (int ps = 0; ps < 2; ++ps) *reinterpret_cast<uint4 *>(&As[row + ps * 64][ko]) = R.a[ps];
 #pragma unroll
-            for (int ps = 0; ps < 4; ++ps) *reinterpret_cast<uint4 *>(&Bs[row + ps * 64][ko]) = rb[ps];
+            for (int ps = 0; ps < 4; ++ps) *reinterpret_cast<uint4 *>(&Bs[row + ps * 64][ko]) = R.b[ps];
         } else {
             const int cp = t & 63, ko = (t >> 6) * 8;
-            *reinterpret_cast<uint4 *>(&As[2 * cp][ko]) = ra[0];
-            *reinterpret_cast<uint4 *>(&As[2 * cp + 1][ko]) = ra[1];
+            uint4 c0, c1;
+            transpose_pairs(R.pa, c0, c1);
+            *reinterpret_cast<uint4 *>(&As[2 * cp][ko]) = c0;
+            *reinterpret_cast<uint4 *>(&As[2 * cp + 1][ko]) = c1;
 #pragma unroll
             for (int ps = 0; ps < 2; ++ps) {
-                *reinterpret_cast<uint4 *>(&Bs[2 * (cp + ps * 64)][ko]) = rb[2 * ps];
-                *reinterpret_cast<uint4 *>(&Bs[2 * (cp + ps * 64) + 1][ko]) = rb[2 * ps + 1];
+                transpose_pairs(R.pb[ps], c0, c1);
+                *reinterpret_cast<uint4 *>(&Bs[2 * (cp + ps * 64)][ko]) = c0;
+                *reinterpret_cast<uint4 *>(&Bs[2 * (cp + ps * 64) + 1][ko]) = c1;
             }
         }
     };
-
-    if (kbeg < kend) load_tile(kbeg);
-    for (int64_t k0 = kbeg; k0 < kend; k0 += TK) {
-        __syncthreads();                 // previous tile fully consumed
-        store_tile();
-        __syncthreads();
-        if (k0 + TK < kend) load_tile(k0 + TK);      // in flight during the MFMA loop
+    auto mma_tile = [&]() {
 #pragma unroll
         for (int ks = 0; ks < TK; ks += 16) {
             const int kc = ks + 8 * (lane >> 5);
@@ -278,6 +291,25 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
                 for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
         }
+    };
+    // one step of the pipeline: tile k0 (held in R) goes to LDS and is multiplied; R is refilled with tile k0 + 2 TK
+    auto step = [&](int64_t k0, Regs &R) {
+        __syncthreads();                 // previous tile fully consumed
+        store_tile(R);
+        __syncthreads();
+        if (k0 + 2 * TK < kend) { load_tile(k0 + 2 * TK, R); load_rows(k0 + 3 * TK); }
+        mma_tile();
+    };
+
+    if (kbeg < kend) {
+        load_rows(kbeg);
+        load_tile(kbeg, rg[0]);
+        load_rows(kbeg + TK);
+        if (kbeg + TK < kend) { load_tile(kbeg + TK, rg[1]); load_rows(kbeg + 2 * TK); }
+    }
+    for (int64_t k0 = kbeg; k0 < kend; k0 += 2 * TK) {
+        step(k0, rg[0]);
+        if (k0 + TK < kend) step(k0 + TK, rg[1]);
     }
     // D register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 tile
     if (EPI::staged) {
