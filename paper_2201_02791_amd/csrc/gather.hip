@@ -582,6 +582,84 @@ __global__ __launch_bounds__(64 * WPB) void k_run_mean(
     }
 }
 
+// The same run means when most runs are very short (many relations: a run is often a single edge).
+// One wavefront takes RPW consecutive runs; each lane group owns every NG-th of them and has the
+// first source row of all its runs in flight at once, which is the whole sum for most.  Runs of
+// KGE_HEAVY edges or more are left to the unit wavefronts of k_run_mean and k_run_mean_finish.
+template <bool BF16, int LPR, int RPW>
+__global__ __launch_bounds__(64 * WPB) void k_run_mean_multi(
+    const int32_t *__restrict__ seg_ptr, const int32_t *__restrict__ seg_dst,
+    const float *__restrict__ inv_c, const int32_t *__restrict__ col_src, int64_t S,
+    const void *__restrict__ H, int32_t d, void *__restrict__ Z, const uint8_t *__restrict__ active)
+{
+    constexpr int VEC = MsgRow<BF16>::VEC;
+    constexpr int NG = 64 / LPR;
+    constexpr int PER = RPW / NG;                          // runs per lane group
+    static_assert(RPW % NG == 0 && RPW < 64, "runs per wavefront must be a multiple of the lane groups");
+    const int lane = threadIdx.x & 63;
+    const int64_t s0 = ((int64_t)blockIdx.x * WPB + (threadIdx.x >> 6)) * RPW;
+    if (s0 >= S) return;
+    const int kl = lane % LPR, g = lane / LPR;
+    const bool kact = kl * VEC < d;
+    // bounds of the RPW runs: lanes 0 .. RPW hold seg_ptr[s0 + lane]
+    int32_t pv = 0;
+    if (lane <= RPW) pv = seg_ptr[min(s0 + lane, S)];
+    int32_t beg[PER], len[PER], src0[PER];
+    float w[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int r = i * NG + g;
+        const int32_t b = __shfl(pv, r, 64), e = __shfl(pv, r + 1, 64);
+        const int64_t sr = s0 + r;
+        beg[i] = b;
+        len[i] = sr < S ? e - b : -1;                      // -1: no such run
+        w[i] = 0.f;
+        src0[i] = 0;
+        if (len[i] >= KGE_HEAVY) len[i] = -1;              // written by the finishing kernel
+        if (len[i] > 0) {
+            if (active && !active[seg_dst[sr]]) len[i] = 0;            // outside the sub-graph: a zero row
+            else { w[i] = inv_c[sr]; src0[i] = col_src[b]; }
+        }
+    }
+    uint4 x0[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        x0[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (len[i] > 0 && kact) x0[i] = MsgRow<BF16>::load_raw(H, (int64_t)src0[i] * d + kl * VEC);
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        if (len[i] < 0) continue;
+        float acc[VEC];
+        MsgRow<BF16>::unpack(x0[i], acc);
+        for (int el = 1; el < len[i]; el += 2) {           // the rest of a longer run, two rows at a time
+            const bool two = el + 1 < len[i];
+            uint4 xa = make_uint4(0u, 0u, 0u, 0u), xb = make_uint4(0u, 0u, 0u, 0u);
+            const int32_t sa = col_src[beg[i] + el], sb = two ? col_src[beg[i] + el + 1] : 0;
+            if (kact) {
+                xa = MsgRow<BF16>::load_raw(H, (int64_t)sa * d + kl * VEC);
+                if (two) xb = MsgRow<BF16>::load_raw(H, (int64_t)sb * d + kl * VEC);
+            }
+            float va[VEC], vb[VEC];
+            MsgRow<BF16>::unpack(xa, va);
+            MsgRow<BF16>::unpack(xb, vb);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] += va[v] + vb[v];
+        }
+        if (!kact) continue;
+        const int64_t o = (s0 + i * NG + g) * d + kl * VEC;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] *= w[i];
+        if (BF16) {
+            *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(Z) + o) =
+                make_uint4(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
+                           pack_bf16x2(acc[4 % VEC], acc[5 % VEC]), pack_bf16x2(acc[6 % VEC], acc[7 % VEC]));
+        } else {
+            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(Z) + o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        }
+    }
+}
+
 // Long runs: Z[s] = invc_s * sum of the run's unit partials.  One thread per float4.
 template <bool BF16>
 __global__ void k_run_mean_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
@@ -1016,6 +1094,27 @@ int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, i
     const int lpr = pow2_at_least((d + vec - 1) / vec);
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the run-mean kernel", d);
     const kge_heavy_index &hx = p->hv_seg;
+    if (p->n_edge < 3 * S && lpr >= 8) {
+        // mostly very short runs: several runs per wavefront; the unit wavefronts of the general kernel
+        // still take the heavy runs (it is launched with no light rows)
+        constexpr int RPW = 8;
+        KGE_PROF("run_mean", st);
+        const unsigned gridm = (unsigned)cdiv(cdiv(S, RPW), WPB);
+#define RMM_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, H, d, Z, active
+        if (bf16) { DISPATCH_LPR(lpr, (k_run_mean_multi<true, (L < 8 ? 8 : L), RPW><<<gridm, 64 * WPB, 0, st>>>(RMM_ARGS))); }
+        else { DISPATCH_LPR(lpr, (k_run_mean_multi<false, (L < 8 ? 8 : L), RPW><<<gridm, 64 * WPB, 0, st>>>(RMM_ARGS))); }
+#undef RMM_ARGS
+        KGE_LAUNCH_CHECK();
+        if (hx.n_units > 0) {
+            const unsigned gridu = (unsigned)cdiv(hx.n_units, WPB);
+#define RMU_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, (int64_t)0, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, \
+                 H, d, Z, partial, active
+            if (bf16) { DISPATCH_LPR(lpr, (k_run_mean<true, L><<<gridu, 64 * WPB, 0, st>>>(RMU_ARGS))); }
+            else { DISPATCH_LPR(lpr, (k_run_mean<false, L><<<gridu, 64 * WPB, 0, st>>>(RMU_ARGS))); }
+#undef RMU_ARGS
+            KGE_LAUNCH_CHECK();
+        }
+    } else {
     const unsigned grid = (unsigned)cdiv(S + hx.n_units, WPB);
     {
         KGE_PROF("run_mean", st);
@@ -1026,6 +1125,7 @@ int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, i
 #undef RM_ARGS
     }
     KGE_LAUNCH_CHECK();
+    }
     if (hx.n_hv > 0) {
         KGE_PROF("run_mean_fin", st);
         const int64_t n = (int64_t)hx.n_hv * (d / 4);
