@@ -291,9 +291,14 @@ int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_ent
  *               destination) run in the partition's run order (valid after forward)
  *   KGE_WS_Y    aggregate-first layer l: y [N][B*d_in] float of the last such layer forward has
  *               processed (the buffer is shared between layers)
- * KGE_WS_P exists only for project-first layers, KGE_WS_Z / KGE_WS_Y only for aggregate-first ones.
+ *   KGE_WS_U    relation-weight layers: one buffer shared by all of them, msg_dtype elements.  After
+ *               forward it holds u [S][d_out] of the last layer (the per-run products z W_r); after
+ *               backward dz [S][d_in] of the last layer that produced an input gradient.  The slice
+ *               is sized for the wider of the two.
+ * KGE_WS_P exists only for project-first layers, KGE_WS_Y only for aggregate-first ones, KGE_WS_Z for
+ * both orders that sum first, KGE_WS_U and no KGE_WS_DP contents beyond G for relation-weight layers.
  */
-enum { KGE_WS_P = 0, KGE_WS_H = 1, KGE_WS_G = 2, KGE_WS_DP = 3, KGE_WS_DH = 4, KGE_WS_Z = 5, KGE_WS_Y = 6 };
+enum { KGE_WS_P = 0, KGE_WS_H = 1, KGE_WS_G = 2, KGE_WS_DP = 3, KGE_WS_DH = 4, KGE_WS_Z = 5, KGE_WS_Y = 6, KGE_WS_U = 7 };
 int kge_workspace_slice(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
                         int32_t msg_dtype, int32_t which, int32_t layer, size_t *offset,
                         size_t *bytes);

@@ -162,3 +162,34 @@ def coeff_grad_relations_runs(part, rels, Z_of, V, G):
             acc += np.einsum("sk,bkc,sc->b", z, V, g)
         out[int(r)] = acc
     return out
+
+
+def transposed_column(ev: EdgeView, a, b, G_col):
+    """dP[:, b, col] for every source: sum over its out-edges of a_rb (1/c) G[dst][col], given column
+    `col` of G as a vector over vertices."""
+    a = np.asarray(a, np.float64)
+    w = a[ev.rel, b] * ev.invc * np.asarray(G_col, np.float64)[ev.dst]
+    return np.bincount(ev.src, weights=w, minlength=ev.n_vert)
+
+
+def relation_weight(a, V, r):
+    """W_r = sum_b a_rb V_b (Eq. 2)."""
+    return np.einsum("b,bkc->kc", np.asarray(a, np.float64)[r], np.asarray(V, np.float64))
+
+
+def relation_product_rows(part, runs, Z_of, a, V, bf16=False):
+    """u_s = z_s W_{rel(s)} for the listed runs; with bf16, W_r is rounded first (z comes as stored)."""
+    z = np.asarray(Z_of(runs), np.float64)
+    out = np.zeros((len(runs), np.shape(V)[2]))
+    for k, s in enumerate(runs):
+        W = relation_weight(a, V, part["seg_rel"][s])
+        out[k] = z[k] @ (round_bf16(W) if bf16 else W)
+    return out
+
+
+def relation_product_t_rows(part, runs, G, a, V):
+    """dz_s = G_{dst(s)} W_{rel(s)}^T for the listed runs (chain rule on u_s = z_s W_r)."""
+    out = np.zeros((len(runs), np.shape(V)[1]))
+    for k, s in enumerate(runs):
+        out[k] = np.asarray(G[part["seg_dst"][s]], np.float64) @ relation_weight(a, V, part["seg_rel"][s]).T
+    return out

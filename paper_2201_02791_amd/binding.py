@@ -274,7 +274,7 @@ def profile_collect() -> dict:
     return {arr[i].name.decode(): (float(arr[i].total_ms), int(arr[i].calls)) for i in range(n.value)}
 
 
-WS_P, WS_H, WS_G, WS_DP, WS_DH, WS_Z, WS_Y = 0, 1, 2, 3, 4, 5, 6
+WS_P, WS_H, WS_G, WS_DP, WS_DH, WS_Z, WS_Y, WS_U = 0, 1, 2, 3, 4, 5, 6, 7
 
 
 def workspace_slice(part: Partition, layers: Sequence[dict], which: int, layer: int,

@@ -227,6 +227,9 @@ extern "C" int kge_workspace_slice(const kge_partition *p, const kge_layer *laye
     case KGE_WS_Z:
         KGE_REQUIRE(L.order != KGE_ORDER_PROJECT_FIRST, KGE_EINVAL, "a project-first layer keeps no run means");
         *offset = w.off_Z[layer]; *bytes = (size_t)p->n_seg * L.d_in * ep; break;
+    case KGE_WS_U:
+        KGE_REQUIRE(L.order == KGE_ORDER_RELATION_WEIGHTS, KGE_EINVAL, "only relation-weight layers have per-run products");
+        *offset = w.off_U; *bytes = (size_t)p->n_seg * (size_t)(L.d_in > L.d_out ? L.d_in : L.d_out) * ep; break;
     case KGE_WS_Y:
         KGE_REQUIRE(L.order == KGE_ORDER_AGGREGATE_FIRST, KGE_EINVAL, "only aggregate-first layers have Y");
         *offset = w.off_Y;

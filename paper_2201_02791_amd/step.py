@@ -63,8 +63,10 @@ class TrainStep:
         torch = self.torch
         off, nbytes = kb.workspace_slice(self.part, self.layers, which, layer, self.msg_dtype)
         raw = self.workspace[off:off + nbytes]
-        bf = self.msg_dtype == kb.MSG_BF16 and which in (kb.WS_P, kb.WS_DP, kb.WS_Z, kb.WS_Y)
+        bf = self.msg_dtype == kb.MSG_BF16 and which in (kb.WS_P, kb.WS_DP, kb.WS_Z, kb.WS_Y, kb.WS_U)
         t = raw.view(torch.bfloat16 if bf else torch.float32)
+        if which == kb.WS_U:          # flat: the caller reshapes to [S, d_out] (u) or [S, d_in] (dz)
+            return t
         return t.view(self.part.n_seg if which == kb.WS_Z else self.part.n_vert, -1)
 
     # --- the four per-step calls, in Algorithm 1's order

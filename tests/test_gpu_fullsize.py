@@ -10,9 +10,10 @@ at any size, all evaluated from the GPU's own stored layer inputs:
   transposed gather sampled rows of dP              input_grad         sampled rows of dH_1 (and dH0)
   weight_grad       dW0 whole; dV sampled columns; Euler identity     coefficients  rare relations; Euler
 
-The aggregate-first variants run on the batch's computational sub-graph, as bench.py does by default:
-sampled run means z and per-basis sums y replace the projected rows, forward rows are sampled from
-the active sets, and the sub-graph flags and counts are compared bit-exactly.
+The aggregate-first and relation-weight variants run on the batch's computational sub-graph (bench.py's
+default is the relation-weight order on the sub-graph): sampled run means z and per-basis sums y, or
+per-run products u = z W_r and their transposes dz, replace the projected rows; forward rows are
+sampled from the active sets, and the sub-graph flags and counts are compared bit-exactly.
 """
 import sys
 import time
@@ -55,7 +56,9 @@ def pick_rows(rng, deg, edge_budget, n_max, allowed=None):
     return np.array(sorted(set(rows)), np.int64)
 
 
-def run_full_size(kb, orc, cfg, agg=False):
+def run_full_size(kb, orc, cfg, order="project"):
+    agg = order != "project"          # both orders that sum first run on the sub-graph here
+    relw = order == "relation"
     import torch
     from oracle import sampled
     from paper_2201_02791_amd.step import TrainStep
@@ -77,9 +80,21 @@ def run_full_size(kb, orc, cfg, agg=False):
     pos = synth.make_batch(spec, gp.n_core)
     need_dH0 = not spec.fixed_features
     ts = TrainStep(gp, params, spec.acts, kb.MSG_BF16 if bf else kb.MSG_F32, need_dH0=need_dH0, cone=agg,
-                   order=kb.ORDER_AGGREGATE_FIRST if agg else kb.ORDER_PROJECT_FIRST)
-    mode = (2 if agg else 1) if bf else 0          # the oracle's rounding points for this pipeline
+                   order={"project": kb.ORDER_PROJECT_FIRST, "aggregate": kb.ORDER_AGGREGATE_FIRST,
+                          "relation": kb.ORDER_RELATION_WEIGHTS}[order])
+    mode = {"project": 1, "aggregate": 2, "relation": 3}[order] if bf else 0     # the oracle's rounding points
     ts.set_batch(pos, spec.n_neg)
+    u_check = None
+    if relw:       # the per-run products of the last layer share their buffer with dz: look after forward only
+        ts.sample(spec.neg_mode, SEED, STEP); ts.compute_graph(); ts.forward()
+        torch.cuda.synchronize()
+        lens_all = np.diff(op["seg_ptr"])
+        act_last = orc.compute_graph(op, pos, orc.sample_negatives(op, pos, spec.n_neg, spec.neg_mode, SEED, STEP)[0], 2)[1]
+        okr = np.nonzero(act_last[op["seg_dst"]].astype(bool) & (lens_all <= 2000))[0]
+        uruns = np.random.default_rng(7).permutation(okr)[:120].astype(np.int64)
+        tr = torch.from_numpy(uruns).to(ts.dev)
+        u_check = (uruns, ts.view(kb.WS_U, 1)[:gp.n_seg * d].view(gp.n_seg, d)[tr].float().cpu().numpy(),
+                   ts.view(kb.WS_Z, 1)[tr].float().cpu().numpy())
     ts.run(spec.neg_mode, SEED, STEP)
     torch.cuda.synchronize()
     say("gpu step done (%.0f s)" % (time.time() - t0))
@@ -107,6 +122,8 @@ def run_full_size(kb, orc, cfg, agg=False):
         assert not Hout[~active[1]].any() and not H1[~active[0]].any()
     if mode == 2:      # the oracle's regrouped evaluation costs (B + 1) d^2 per ROW and d per edge
         budget = 4e6
+    elif mode == 3:    # and B d^2 per RUN where it writes W_r out on the spot
+        budget = 1.5e10 / (B * d * d)
     else:
         budget = 1.4e10 / (B * d * d)      # oracle cost per edge: B d^2 multiply-adds
     rows1 = pick_rows(rng, deg_in, budget, 300, None if active is None else active[0])
@@ -133,9 +150,14 @@ def run_full_size(kb, orc, cfg, agg=False):
                 assert not c(ts.view(kb.WS_Z, l)[torch.from_numpy(gone).to(ts.dev)]).any()
         Zv = ts.view(kb.WS_Z, 1)
         Z_of = lambda ids: c(Zv[torch.from_numpy(np.asarray(ids, np.int64)).to(ts.dev)])
-        yw = sampled.basis_sum_rows(op, rows2, L[1]["a"], Z_of)
-        yg = c(ts.view(kb.WS_Y, 1)[torch.from_numpy(rows2).to(ts.dev)])[:, :B * d].reshape(len(rows2), B, d)
-        errs["y_2 rows"] = (rel_err(yg, yw), tol_v)
+        if relw:
+            uruns, ug, zg_u = u_check
+            uw = sampled.relation_product_rows(op, uruns, lambda ids: zg_u, L[1]["a"], L[1]["V"], bf16=bf)
+            errs["u_2 runs"] = (rel_err(ug, uw), tol_v)
+        else:
+            yw = sampled.basis_sum_rows(op, rows2, L[1]["a"], Z_of)
+            yg = c(ts.view(kb.WS_Y, 1)[torch.from_numpy(rows2).to(ts.dev)])[:, :B * d].reshape(len(rows2), B, d)
+            errs["y_2 rows"] = (rel_err(yg, yw), tol_v)
     else:
         trows = torch.from_numpy(rows1).to(ts.dev)
         P1 = c(ts.view(kb.WS_P, 0)[trows]).reshape(len(rows1), B, d)
@@ -165,9 +187,19 @@ def run_full_size(kb, orc, cfg, agg=False):
     G1 = c(ts.view(kb.WS_G, 0))
     np.testing.assert_array_equal(G1[srows], dH1 * (H1[srows] > 0))
     # layer 1 transposed gather from the GPU's own G1
-    X1 = ts.view(kb.WS_DP, 0)
-    dP1 = c(X1[tsrows])[:, :B * d].reshape(len(srows), B, d)
-    errs["dP_1 rows"] = (rel_err(dP1, sampled.transposed_rows(ev, srows, L[0]["a"], G1)), tol_g)
+    dP1w = sampled.transposed_rows(ev, srows, L[0]["a"], G1)
+    if relw:
+        # no dP in this order: the transposed per-run products dz of the last layer that produced an
+        # input gradient are in the shared buffer
+        lz, Gz = (0, G1) if need_dH0 else (1, G2)
+        zruns = np.random.default_rng(11).permutation(op["n_seg"])[:120].astype(np.int64)
+        dzg = c(ts.view(kb.WS_U, lz)[:gp.n_seg * d].view(gp.n_seg, d)[torch.from_numpy(zruns).to(ts.dev)])
+        errs["dz_%d runs" % (lz + 1)] = (rel_err(dzg, sampled.relation_product_t_rows(op, zruns, Gz, L[lz]["a"], L[lz]["V"])), tol_g)
+        dP1 = dP1w
+    else:
+        X1 = ts.view(kb.WS_DP, 0)
+        dP1 = c(X1[tsrows])[:, :B * d].reshape(len(srows), B, d)
+        errs["dP_1 rows"] = (rel_err(dP1, dP1w), tol_g)
     if need_dH0:
         errs["dH0 rows"] = (rel_err(c(ts.dH0[tsrows]), sampled.input_grad_rows(dP1, G1[srows], L[0]["V"], L[0]["W0"])), tol_g)
     # self-loop weight gradients, whole
@@ -176,7 +208,7 @@ def run_full_size(kb, orc, cfg, agg=False):
     # basis gradients of layer 1: sampled columns
     dV1 = c(ts.grads[0]["dV"])
     for (b, col) in [(0, 0), (B - 1, d - 1), (B // 2, d // 3)]:
-        colv = c(X1[:, b * d + col])
+        colv = sampled.transposed_column(ev, L[0]["a"], b, G1[:, col])        # dP_1[:, b, col] by definition
         want = sampled.basis_weight_grad_column(H0, colv)
         errs["dV_1[%d][:,%d]" % (b, col)] = (float(np.abs(dV1[b][:, col] - want).max() / np.abs(dV1[b]).max()), tol_g)
     # Euler identity for both layers: sum a*da = sum V*dV = sum <pre - h W0, G>
@@ -228,13 +260,24 @@ def test_config3_full_size(kb, orc):
 
 def test_config3_full_size_aggregate_first_subgraph(kb, orc):
     """The same workload in the aggregate-first order on the batch's computational sub-graph."""
-    run_full_size(kb, orc, 3, agg=True)
+    run_full_size(kb, orc, 3, order="aggregate")
 
 
 def test_config4_full_size_aggregate_first_subgraph(kb, orc):
     """configs[4] as a bf16 pipeline in the aggregate-first order (the oracle rounds at the same
     points: inputs, run means, per-basis sums, weights) on the batch's computational sub-graph."""
-    run_full_size(kb, orc, 4, agg=True)
+    run_full_size(kb, orc, 4, order="aggregate")
+
+
+def test_config3_full_size_relation_weights_subgraph(kb, orc):
+    """The launch configuration bench.py times by default: relation-weight order on the sub-graph."""
+    run_full_size(kb, orc, 3, order="relation")
+
+
+def test_config4_full_size_relation_weights_subgraph(kb, orc):
+    """configs[4] as the bf16 relation-weight pipeline (the oracle rounds inputs, run means, W_r, the
+    per-run products and W_0) on the batch's computational sub-graph."""
+    run_full_size(kb, orc, 4, order="relation")
 
 
 def test_config4_full_size(kb, orc):

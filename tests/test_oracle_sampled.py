@@ -70,3 +70,30 @@ def test_regrouped_helpers_match_the_whole_step(case, orc):
     pre_q = np.einsum("nbk,bkc->nc", Yq, sampled.round_bf16(lay["V"])) + sampled.round_bf16(H0) @ sampled.round_bf16(lay["W0"])
     want, _ = orc.layer_forward(part, lay["V"], lay["a"], lay["W0"], 1, H0, msg_bf16=2)
     np.testing.assert_allclose(pre_q, want, rtol=1e-10, atol=1e-12)
+
+
+def test_relation_weight_helpers_match_the_whole_step(case, orc):
+    sampled, part, layers, H0, res, ev = case
+    lay, g = layers[0], res["grads"][0]
+    S = part["n_seg"]; runs = np.arange(S)
+    Z = sampled.run_mean_rows(part, runs, H0)
+    U = sampled.relation_product_rows(part, runs, lambda ids: Z[ids], lay["a"], lay["V"])
+    pre = H0 @ lay["W0"]
+    np.add.at(pre, part["seg_dst"], U)
+    np.testing.assert_allclose(pre, res["pres"][0], rtol=1e-10, atol=1e-12)
+    # dP column and, through it, a column of dV
+    col = sampled.transposed_column(ev, lay["a"], 1, g["Gpre"][:, 2])
+    np.testing.assert_allclose(col, g["dP"][:, 1, 2], rtol=1e-11, atol=1e-13)
+    # dz and the input gradient it gives: dH_j = sum_{e out of j} dz_run(e) / c + G_j W_0^T
+    dZ = sampled.relation_product_t_rows(part, runs, g["Gpre"], lay["a"], lay["V"])
+    lens = np.diff(part["seg_ptr"]); run_of_edge = np.repeat(runs, lens)
+    dH = g["Gpre"] @ lay["W0"].T
+    np.add.at(dH, part["col_src"], dZ[run_of_edge] / lens[run_of_edge][:, None])
+    np.testing.assert_allclose(dH, g["dH"], rtol=1e-10, atol=1e-12)
+    # bf16: rounded W_r and rounded products reproduce the oracle's mode 3
+    Zq = sampled.round_bf16(sampled.run_mean_rows(part, runs, H0, bf16=True))
+    Uq = sampled.round_bf16(sampled.relation_product_rows(part, runs, lambda ids: Zq[ids], lay["a"], lay["V"], bf16=True))
+    pre_q = sampled.round_bf16(H0) @ sampled.round_bf16(lay["W0"])
+    np.add.at(pre_q, part["seg_dst"], Uq)
+    want, _ = orc.layer_forward(part, lay["V"], lay["a"], lay["W0"], 1, H0, msg_bf16=3)
+    np.testing.assert_allclose(pre_q, want, rtol=1e-10, atol=1e-12)
