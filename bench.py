@@ -35,7 +35,7 @@ def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None, spec_order=
     gemm_flops = 2.0 * N * d * (B + 1) * d
     if cone is not None and name in ("gather_fwd", "coeff_seg", "gather_t"):
         tot = 0.0
-        for nv, ne, ns in cone:
+        for nv, ne, ns, _ in cone:
             if name == "gather_fwd":   # inactive rows: flag + ptr read, zero row written
                 tot += ne * (B * d * ep + 12.0) + N * (5.0 + 4.0 * d) + nv * 4.0 * d + R2 * B * 4.0
             elif name == "coeff_seg":  # inactive runs: dst + flag read, B zeros written
@@ -61,7 +61,11 @@ def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None, spec_order=
     if name == "sum_runs":     # per run: u row + run id; per vertex: ptr + Self read + output write
         return "hbm", ns_mean * (ep * d + 4.0) + N * (5.0 + 4.0 * d) + nv_mean * 4.0 * d
     if name == "sum_edges_out":  # per edge: dz row + (run id, 1/c); per vertex: ptr + Self read + output write
-        return "hbm", E * (ep * d + 8.0) + N * (4.0 + 8.0 * d)
+        # rows outside the previous layer's active set are skipped (zero rows written); the first
+        # layer's input gradient, when wanted, covers every vertex
+        eo = E if cone is None else (sum(c[3] for c in cone[:-1]) + (0 if spec.fixed_features else E)) / max(
+            len(cone) - (1 if spec.fixed_features else 0), 1)
+        return "hbm", eo * (ep * d + 8.0) + N * (4.0 + 8.0 * d)
     if name in ("apply_rel", "apply_rel_t"):    # one (d x d) product per run
         return "mfma", 2.0 * S * d * d
     if name == "rel_weights" or name == "basis_grad":
@@ -247,7 +251,7 @@ def main():
                       "positives": n_pos, "negatives_per_positive": n_neg, "parallelism": "1 partition on 1 GPU",
                       "propagation": "whole partition" if cone is None else "batch computational sub-graph",
                       "order": {"project": "project-first", "aggregate": "aggregate-first", "relation": "relation-weight"}[args.order],
-                      "subgraph_vertices_edges_runs_per_layer": cone},
+                      "subgraph_vertices_edgesin_runs_edgesout_per_layer": cone},
            "triples_per_s": T / (dt / args.steps), "loss": loss,
            "roofline": roof, "cpu_baseline": base, "kernels": kernels}
     print(json.dumps(out))

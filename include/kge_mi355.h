@@ -179,8 +179,8 @@ size_t kge_workspace_bytes(const kge_partition *p, const kge_layer *layers, int3
  *   neg_ent      : device int32 [n_neg_entries] local vertex ids (as written by
  *                  kge_sample_negatives, n_neg_entries = n_pos * n_neg), or NULL with 0
  * kge_cgraph_export (synchronises the device) copies the flags to HOST uint8 [L][N] and/or, per
- * layer, three counts to HOST int64 [L][3]: active vertices, message edges into them, and
- * (relation, destination) runs into them; either pointer may be NULL.
+ * layer, four counts to HOST int64 [L][4]: active vertices, message edges into them,
+ * (relation, destination) runs into them, and message edges out of them; either pointer may be NULL.
  */
 int kge_cgraph_create(const kge_partition *p, int32_t n_layers, kge_cgraph **out);
 void kge_cgraph_destroy(kge_cgraph *cg);

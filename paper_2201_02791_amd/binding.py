@@ -200,9 +200,9 @@ class ComputeGraph:
         return self._h
 
     def export(self):
-        """(active uint8 [n_layers][N], counts int64 [n_layers][3] = vertices, edges, runs)."""
+        """(active uint8 [n_layers][N], counts int64 [n_layers][4] = vertices, edges in, runs, edges out)."""
         active = np.zeros((self.n_layers, self.n_vert), np.uint8)
-        stats = np.zeros((self.n_layers, 3), np.int64)
+        stats = np.zeros((self.n_layers, 4), np.int64)
         _check(load().kge_cgraph_export(self._h, active.ctypes.data_as(C.c_void_p),
                                         stats.ctypes.data_as(C.c_void_p)))
         return active, stats

@@ -15,7 +15,7 @@ struct kge_cgraph {
     int64_t N, stride;      // vertices; bytes between the layers' flag rows
     int32_t n_layers;
     uint8_t *active;        // [n_layers][stride]
-    unsigned long long *stats;   // [n_layers][3]: active vertices, edges into them, runs into them
+    unsigned long long *stats;   // [n_layers][4]: active vertices, edges into them, runs into them, edges out of them
 };
 
 namespace {
@@ -48,37 +48,41 @@ __global__ __launch_bounds__(256) void k_cg_expand(const int32_t *__restrict__ d
     for (int32_t e = dm_ptr[i] + lane; e < end; e += 64) below[dm_src[e]] = 1;
 }
 
-__device__ __forceinline__ void block_add3(unsigned long long a, unsigned long long b, unsigned long long c,
-                                           unsigned long long *out)
+__device__ __forceinline__ void block_add4(unsigned long long a, unsigned long long b, unsigned long long c,
+                                           unsigned long long e, unsigned long long *out)
 {
-    __shared__ unsigned long long red[3][4];
+    __shared__ unsigned long long red[4][4];
     for (int off = 32; off > 0; off >>= 1) {
         a += __shfl_xor(a, off, 64); b += __shfl_xor(b, off, 64); c += __shfl_xor(c, off, 64);
+        e += __shfl_xor(e, off, 64);
     }
     const int wv = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { red[0][wv] = a; red[1][wv] = b; red[2][wv] = c; }
+    if ((threadIdx.x & 63) == 0) { red[0][wv] = a; red[1][wv] = b; red[2][wv] = c; red[3][wv] = e; }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned long long sa = 0, sb = 0, sc = 0;
-        for (int k = 0; k < 4; ++k) { sa += red[0][k]; sb += red[1][k]; sc += red[2][k]; }
-        if (sa) atomicAdd(out + 0, sa);
-        if (sb) atomicAdd(out + 1, sb);
-        if (sc) atomicAdd(out + 2, sc);
+    if (threadIdx.x < 4) {
+        unsigned long long sum = 0;
+        for (int k = 0; k < 4; ++k) sum += red[threadIdx.x][k];
+        if (sum) atomicAdd(out + threadIdx.x, sum);
     }
 }
 
 // counts of one layer: active vertices and edges (over vertices), active runs (over runs)
-__global__ __launch_bounds__(256) void k_cg_stats(const int32_t *__restrict__ dm_ptr, int64_t N,
+__global__ __launch_bounds__(256) void k_cg_stats(const int32_t *__restrict__ dm_ptr,
+                                                  const int32_t *__restrict__ sm_ptr, int64_t N,
                                                   const int32_t *__restrict__ seg_dst, int64_t S,
                                                   const uint8_t *__restrict__ act, unsigned long long *out)
 {
-    unsigned long long nv = 0, ne = 0, ns = 0;
+    unsigned long long nv = 0, ne = 0, ns = 0, no = 0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += stride)
-        if (act[i]) { nv += 1; ne += (unsigned long long)(dm_ptr[i + 1] - dm_ptr[i]); }
+        if (act[i]) {
+            nv += 1;
+            ne += (unsigned long long)(dm_ptr[i + 1] - dm_ptr[i]);
+            no += (unsigned long long)(sm_ptr[i + 1] - sm_ptr[i]);
+        }
     for (int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; s < S; s += stride)
         if (act[seg_dst[s]]) ns += 1;
-    block_add3(nv, ne, ns, out);
+    block_add4(nv, ne, ns, no, out);
 }
 
 }  // namespace
@@ -96,9 +100,9 @@ extern "C" int kge_cgraph_create(const kge_partition *p, int32_t n_layers, kge_c
     cg->active = nullptr;
     cg->stats = nullptr;
     hipError_t e = hipMalloc((void **)&cg->active, (size_t)cg->stride * n_layers);
-    if (e == hipSuccess) e = hipMalloc((void **)&cg->stats, sizeof(unsigned long long) * 3 * n_layers);
+    if (e == hipSuccess) e = hipMalloc((void **)&cg->stats, sizeof(unsigned long long) * 4 * n_layers);
     if (e == hipSuccess) e = hipMemset(cg->active, 0, (size_t)cg->stride * n_layers);
-    if (e == hipSuccess) e = hipMemset(cg->stats, 0, sizeof(unsigned long long) * 3 * n_layers);
+    if (e == hipSuccess) e = hipMemset(cg->stats, 0, sizeof(unsigned long long) * 4 * n_layers);
     if (e != hipSuccess) {
         kge_set_error("allocating the sub-graph flags failed: %s", hipGetErrorString(e));
         if (cg->active) (void)hipFree(cg->active);
@@ -133,7 +137,7 @@ extern "C" int kge_compute_graph(const kge_partition *p, kge_cgraph *cg, const i
     KGE_PROF("compute_graph", st);
     int rc = launch_fill_zero(cg->active, (size_t)cg->stride * L, st);
     if (rc != KGE_OK) return rc;
-    rc = launch_fill_zero(cg->stats, sizeof(unsigned long long) * 3 * L, st);
+    rc = launch_fill_zero(cg->stats, sizeof(unsigned long long) * 4 * L, st);
     if (rc != KGE_OK) return rc;
     if (p->n_vert == 0) return KGE_OK;
     const int64_t n_mark = n_pos + n_neg_entries;
@@ -150,8 +154,8 @@ extern "C" int kge_compute_graph(const kge_partition *p, kge_cgraph *cg, const i
         KGE_LAUNCH_CHECK();
     }
     for (int l = 0; l < L; ++l) {
-        k_cg_stats<<<1024, 256, 0, st>>>(p->dm_ptr, p->n_vert, p->seg_dst, p->n_seg,
-                                         cg->active + (size_t)l * cg->stride, cg->stats + 3 * l);
+        k_cg_stats<<<1024, 256, 0, st>>>(p->dm_ptr, p->sm_ptr, p->n_vert, p->seg_dst, p->n_seg,
+                                         cg->active + (size_t)l * cg->stride, cg->stats + 4 * l);
         KGE_LAUNCH_CHECK();
     }
     return KGE_OK;
@@ -166,9 +170,9 @@ extern "C" int kge_cgraph_export(const kge_cgraph *cg, uint8_t *host_active, int
             KGE_HIP(hipMemcpy(host_active + (size_t)l * cg->N, cg->active + (size_t)l * cg->stride, (size_t)cg->N,
                               hipMemcpyDeviceToHost));
     if (host_stats) {
-        unsigned long long tmp[48];
-        KGE_HIP(hipMemcpy(tmp, cg->stats, sizeof(unsigned long long) * 3 * cg->n_layers, hipMemcpyDeviceToHost));
-        for (int k = 0; k < 3 * cg->n_layers; ++k) host_stats[k] = (int64_t)tmp[k];
+        unsigned long long tmp[64];
+        KGE_HIP(hipMemcpy(tmp, cg->stats, sizeof(unsigned long long) * 4 * cg->n_layers, hipMemcpyDeviceToHost));
+        for (int k = 0; k < 4 * cg->n_layers; ++k) host_stats[k] = (int64_t)tmp[k];
     }
     return KGE_OK;
 }

@@ -35,6 +35,7 @@ def check_flags(orc, ts, opart, pos, res, n_layers):
         assert stats[l, 0] == int(want[l].sum())
         assert stats[l, 1] == int(want[l][dst_of_edge].sum())
         assert stats[l, 2] == int(want[l][opart["seg_dst"]].sum())
+        assert stats[l, 3] == int(want[l][opart["col_src"]].sum())
     return want, stats
 
 
