@@ -88,9 +88,9 @@ __device__ __forceinline__ RowWork row_work(int64_t wid, const int32_t *__restri
 
 // ------------------------------------------------------------------ forward
 //   out[i][:] = act( sum_e invc_e sum_b a[rel_e][b] P[src_e][b][:] + Self[i][:] )
-// With a == null (and B = 1) the sum is plain: out[i] = act( sum_e w_e P[idx_e] + Self[i] ), w = 1 if
-// dm_invc is null; dm_rel may then be null too.
-template <bool BF16, int LPR>
+// PLAIN (B = 1, no coefficient table, dm_rel unused): out[i] = act( sum_e w_e P[idx_e] + Self[i] ),
+// w = 1 if dm_invc is null.
+template <bool BF16, int LPR, bool PLAIN>
 __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
     const int32_t *__restrict__ dm_ptr, const int32_t *__restrict__ dm_src,
     const int32_t *__restrict__ dm_rel, const float *__restrict__ dm_invc, int64_t N,
@@ -134,8 +134,12 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
         float my_w = 0.f;
         if (lane < cnt) {
             my_src = dm_src[e0 + lane];
-            my_rel = dm_rel ? dm_rel[e0 + lane] : 0;
-            my_w = dm_invc ? dm_invc[e0 + lane] : 1.f;
+            if (PLAIN) {
+                my_w = dm_invc ? dm_invc[e0 + lane] : 1.f;
+            } else {
+                my_rel = dm_rel[e0 + lane];
+                my_w = dm_invc[e0 + lane];
+            }
         }
         const int erounds = (cnt + GE - 1) / GE;        // uniform trip counts for all lanes
         const int items = erounds * nb;
@@ -155,7 +159,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
                 coef[u] = 0.f;
                 raw[u] = make_uint4(0u, 0u, 0u, 0u);
                 if (ok) {
-                    coef[u] = a ? a[(int64_t)rel * B + b] * w : w;
+                    coef[u] = PLAIN ? w : a[(int64_t)rel * B + b] * w;
                     if (kact) raw[u] = MsgRow<BF16>::load_raw(P, ((int64_t)src * B + b) * d + kl * VEC);
                 }
                 if (++bi == nb) { bi = 0; ++er; }
@@ -856,8 +860,8 @@ int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, c
         KGE_PROF("gather_fwd", st);
 #define GF_ARGS p->dm_ptr, p->dm_src, p->dm_rel, p->dm_invc, N, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, \
                 P, a, B, d, gbc, Self, act, out, out2, partial, active
-        if (msg_bf16) { DISPATCH_LPR(lpr, (k_gather_fwd<true, L><<<grid, 64 * WPB, 0, st>>>(GF_ARGS))); }
-        else { DISPATCH_LPR(lpr, (k_gather_fwd<false, L><<<grid, 64 * WPB, 0, st>>>(GF_ARGS))); }
+        if (msg_bf16) { DISPATCH_LPR(lpr, (k_gather_fwd<true, L, false><<<grid, 64 * WPB, 0, st>>>(GF_ARGS))); }
+        else { DISPATCH_LPR(lpr, (k_gather_fwd<false, L, false><<<grid, 64 * WPB, 0, st>>>(GF_ARGS))); }
 #undef GF_ARGS
     }
     KGE_LAUNCH_CHECK();
@@ -886,8 +890,8 @@ static int launch_row_sum(const int32_t *ptr, const int32_t *idx, const float *w
         KGE_PROF(name, st);
 #define RS_ARGS ptr, idx, nullptr, w, n_rows, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, X, nullptr, 1, d, 1, \
                 Self, act, out, out2, partial, active
-        if (x_bf16) { DISPATCH_LPR(lpr, (k_gather_fwd<true, L><<<grid, 64 * WPB, 0, st>>>(RS_ARGS))); }
-        else { DISPATCH_LPR(lpr, (k_gather_fwd<false, L><<<grid, 64 * WPB, 0, st>>>(RS_ARGS))); }
+        if (x_bf16) { DISPATCH_LPR(lpr, (k_gather_fwd<true, L, true><<<grid, 64 * WPB, 0, st>>>(RS_ARGS))); }
+        else { DISPATCH_LPR(lpr, (k_gather_fwd<false, L, true><<<grid, 64 * WPB, 0, st>>>(RS_ARGS))); }
 #undef RS_ARGS
     }
     KGE_LAUNCH_CHECK();
