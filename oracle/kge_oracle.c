@@ -751,3 +751,34 @@ void orc_compute_graph(int64_t N, int64_t S, const int32_t *seg_ptr, const int32
                 for (int32_t e = seg_ptr[s]; e < seg_ptr[s + 1]; ++e) below[col_src[e]] = 1;
     }
 }
+
+/* ------------------------------------------------------------------ */
+/* Optimizer step (Algorithm 1, "optimizer.step()")                    */
+/* ------------------------------------------------------------------ */
+/*
+ * The paper trains with synchronous gradient descent at learning rate 0.01 and does not name the
+ * update rule; two are provided.
+ *   kind 0, plain gradient descent:  p <- p - lr g
+ *   kind 1, Adam (Kingma & Ba 2015), t = 1, 2, ... the number of this step:
+ *       m <- b1 m + (1 - b1) g,   v <- b2 v + (1 - b2) g^2
+ *       p <- p - lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)
+ * Row form: the tensor is [n_rows][d] and only rows with row_mask[i] != 0 are touched (an embedding
+ * table of which a step reaches few rows; moments of the other rows stay as they are, and the bias
+ * correction still uses the global t).  row_mask NULL = every row.
+ */
+void orc_optimizer_step(int32_t kind, double *p, const double *g, double *m, double *v, int64_t n_rows,
+                        int64_t d, const uint8_t *row_mask, double lr, double b1, double b2, double eps,
+                        int64_t t)
+{
+    double c1 = 1.0 - pow(b1, (double)t), c2 = 1.0 - pow(b2, (double)t);
+    for (int64_t i = 0; i < n_rows; ++i) {
+        if (row_mask && !row_mask[i]) continue;
+        for (int64_t k = 0; k < d; ++k) {
+            size_t q = (size_t)i * d + k;
+            if (kind == 0) { p[q] -= lr * g[q]; continue; }
+            m[q] = b1 * m[q] + (1.0 - b1) * g[q];
+            v[q] = b2 * v[q] + (1.0 - b2) * g[q] * g[q];
+            p[q] -= lr * (m[q] / c1) / (sqrt(v[q] / c2) + eps);
+        }
+    }
+}

@@ -232,6 +232,24 @@ def compute_graph(part, pos_core_idx, neg_ent, n_layers):
     return active
 
 
+def optimizer_step(kind, p, g, m, v, lr=0.01, b1=0.9, b2=0.999, eps=1e-8, t=1, row_mask=None):
+    """One optimizer step in place on float64 arrays (Algorithm 1, "optimizer.step()").  kind 0: plain
+    gradient descent; 1: Adam.  row_mask (uint8 per row of a 2-D tensor): only those rows are touched."""
+    assert p.dtype == np.float64 and p.flags.c_contiguous
+    g = _d(g)
+    if kind == 1:
+        assert m.dtype == np.float64 and v.dtype == np.float64 and m.flags.c_contiguous and v.flags.c_contiguous
+    if row_mask is None:
+        n_rows, d, mk = 1, p.size, None
+    else:
+        n_rows, d = p.shape[0], p.size // max(p.shape[0], 1)
+        mk = np.ascontiguousarray(row_mask, np.uint8)
+    lib().orc_optimizer_step(C.c_int32(kind), _p(p, _F64), _p(g, _F64),
+                             _p(m, _F64) if kind == 1 else None, _p(v, _F64) if kind == 1 else None,
+                             C.c_int64(n_rows), C.c_int64(d), _p(mk, _U8) if mk is not None else None,
+                             C.c_double(lr), C.c_double(b1), C.c_double(b2), C.c_double(eps), C.c_int64(t))
+
+
 def train_step(part, layers, H0, M, pos_core_idx, n_neg, mode, seed, step, need_dH0=True,
                msg_bf16=False):
     """One whole step: encoder forward, negatives, score + loss, encoder backward."""
