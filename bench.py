@@ -70,6 +70,10 @@ def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None, spec_order=
         return "mfma", 2.0 * S * d * d
     if name == "rel_weights" or name == "basis_grad":
         return "alu", 2.0 * R2 * B * d * d
+    if name == "optimizer":    # dense tensors: p, g, m, v read, p, m, v written; small here, no figure given
+        return "hbm", 0.0
+    if name == "optimizer_rows":   # the entity table: gradient row read for every vertex, 28 B per touched element
+        return "hbm", N * d * 4.0 + nv_mean * d * 24.0
     if name == "combine":
         return "mfma", gemm_flops
     if name == "rel_outer":    # C_r = sum_runs z^T G: 2 S d^2 flops; bytes S (2 d) 4
@@ -142,6 +146,8 @@ def main():
     ap.add_argument("--order", choices=["project", "aggregate", "relation"], default="relation",
                     help="order of Eq. 1-2: project-first (P = H V_b, then the neighbour sum), aggregate-first "
                          "(run means, per-basis sums, one contraction) or relation-weight (run means times W_r)")
+    ap.add_argument("--no-optimizer", action="store_true",
+                    help="leave the optimizer step (Adam, lr 0.01) out of the timed step")
     ap.add_argument("--whole-partition", action="store_true",
                     help="propagate every vertex of the partition instead of the batch's computational sub-graph")
     ap.add_argument("--calibrate", action="store_true",
@@ -187,13 +193,18 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for w in range(args.warmup):
-        ts.run(spec.neg_mode, 1234, w)
+    def one_step(i):          # Algorithm 1, one mini-batch: negatives, sub-graph, forward, loss, backward, update
+        ts.run(spec.neg_mode, 1234, i)
+        if not args.no_optimizer:
+            ts.optimizer_step(kb.OPT_ADAM, 0.01)
+
+    for w in range(max(args.warmup, 1) if not args.no_optimizer else args.warmup):
+        one_step(w)           # (the first optimizer step allocates the Adam moments: never inside the timed region)
     torch.cuda.synchronize()
     kb.profile_enable(True)
     t0 = time.perf_counter()
     for k in range(args.steps):
-        ts.run(spec.neg_mode, 1234, args.warmup + k)
+        one_step(args.warmup + k)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     kb.profile_enable(False)
@@ -250,6 +261,7 @@ def main():
                       "relations_with_inverses": 2 * spec.n_relations, "layers": spec.n_layers,
                       "positives": n_pos, "negatives_per_positive": n_neg, "parallelism": "1 partition on 1 GPU",
                       "propagation": "whole partition" if cone is None else "batch computational sub-graph",
+                      "optimizer": None if args.no_optimizer else "adam, lr 0.01 (inside the timed step)",
                       "order": {"project": "project-first", "aggregate": "aggregate-first", "relation": "relation-weight"}[args.order],
                       "subgraph_vertices_edgesin_runs_edgesout_per_layer": cone},
            "triples_per_s": T / (dt / args.steps), "loss": loss,

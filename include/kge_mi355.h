@@ -16,6 +16,7 @@
  *   kge_distmult_score_loss  Eq. 4 (DistMult) and Eq. 3 (cross entropy), with
  *                            the gradients with respect to embeddings and M_r
  *   kge_rgcn_backward        chain rule on Eq. 1-2 (Algorithm 1, "backward")
+ *   kge_optimizer_step       Algorithm 1, "optimizer.step()"
  *
  * General rules
  *  - Every function returns KGE_OK (0) or a negative kge_status; on error no
@@ -259,6 +260,30 @@ int kge_distmult_score_loss(const kge_partition *p, const float *H, const float 
                             const int32_t *pos_core_idx, int64_t n_pos, const int32_t *neg_ent,
                             const uint8_t *neg_side, int32_t n_neg, float *scores, float *loss,
                             float *dH, float *dM, void *stream);
+
+/*
+ * Optimizer step (Algorithm 1, "optimizer.step()"; learning rate 0.01 in the paper's large-graph
+ * setting).  The paper speaks of synchronous gradient descent and does not name the update rule:
+ *   KGE_OPT_SGD   p <- p - lr g
+ *   KGE_OPT_ADAM  m <- beta1 m + (1 - beta1) g;  v <- beta2 v + (1 - beta2) g^2;
+ *                 p <- p - lr (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps),  t = 1, 2, ...
+ * kge_optimizer_step updates n elements of one tensor in place; param, grad, m, v are device float
+ * arrays (m, v: Adam only, zero before the first step).  kge_optimizer_step_rows treats the tensors as
+ * [n_rows][d] (d a multiple of 4, 16-byte aligned) and leaves a row - parameters and moments - as it
+ * is when row_mask[row] == 0 (device uint8 [n_rows]) or, with row_mask NULL, when the row's gradient is
+ * all zeros: the update for an embedding table of which a step reaches few rows.  The bias correction
+ * uses the global t for every row.  Asynchronous on `stream`, no allocation.
+ */
+enum { KGE_OPT_SGD = 0, KGE_OPT_ADAM = 1 };
+typedef struct kge_opt {
+    int32_t kind;      /* KGE_OPT_*                                   */
+    float lr, beta1, beta2, eps;
+    int64_t t;         /* number of this step, starting at 1 (Adam)   */
+} kge_opt;
+int kge_optimizer_step(const kge_opt *opt, float *param, const float *grad, float *m, float *v,
+                       int64_t n, void *stream);
+int kge_optimizer_step_rows(const kge_opt *opt, float *param, const float *grad, float *m, float *v,
+                            int64_t n_rows, int32_t d, const uint8_t *row_mask, void *stream);
 
 /*
  * Per-kernel timing for benchmarks (not part of the training path).  While enabled, every

@@ -20,10 +20,12 @@ EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_partition_destroy", "kge_workspace_bytes", "kge_workspace_slice", "kge_rgcn_forward",
             "kge_rgcn_backward", "kge_sample_negatives", "kge_distmult_score_loss",
             "kge_profile_enable", "kge_profile_collect", "kge_last_error", "kge_cgraph_create",
-            "kge_cgraph_destroy", "kge_compute_graph", "kge_cgraph_export"]
+            "kge_cgraph_destroy", "kge_compute_graph", "kge_cgraph_export", "kge_optimizer_step",
+            "kge_optimizer_step_rows"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
 ORDER_PROJECT_FIRST, ORDER_AGGREGATE_FIRST, ORDER_RELATION_WEIGHTS = 0, 1, 2
+OPT_SGD, OPT_ADAM = 0, 1
 MSG_F32, MSG_BF16 = 0, 1
 NEG_TAIL, NEG_HEAD_OR_TAIL = 0, 1
 DOMAIN_CORE, DOMAIN_ALL = 0, 1
@@ -60,6 +62,11 @@ class _Layer(C.Structure):
 
 class _LayerGrad(C.Structure):
     _fields_ = [("dV", C.c_void_p), ("da", C.c_void_p), ("dW0", C.c_void_p)]
+
+
+class _Opt(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("t", C.c_int64)]
 
 
 class _ProfEntry(C.Structure):
@@ -284,3 +291,16 @@ def workspace_slice(part: Partition, layers: Sequence[dict], which: int, layer: 
     _check(load().kge_workspace_slice(part.handle, _layers(layers), C.c_int32(len(layers)), C.c_int32(msg_dtype),
                                       C.c_int32(which), C.c_int32(layer), C.byref(off), C.byref(nbytes)))
     return int(off.value), int(nbytes.value)
+
+
+def optimizer_step(kind: int, param, grad, m=None, v=None, lr=0.01, beta1=0.9, beta2=0.999, eps=1e-8, t=1,
+                   rows: bool = False, row_mask=None, stream=None):
+    """One optimizer step in place on device tensors.  rows=True: the row form on a 2-D tensor."""
+    o = _Opt(kind, lr, beta1, beta2, eps, t)
+    if rows:
+        _check(load().kge_optimizer_step_rows(C.byref(o), _ptr(param), _ptr(grad), _ptr(m), _ptr(v),
+                                              C.c_int64(param.shape[0]), C.c_int32(param.shape[1]),
+                                              _ptr(row_mask), _stream(stream)))
+    else:
+        _check(load().kge_optimizer_step(C.byref(o), _ptr(param), _ptr(grad), _ptr(m), _ptr(v),
+                                         C.c_int64(param.numel()), _stream(stream)))

@@ -95,3 +95,25 @@ class TrainStep:
         self.forward(stream)
         self.score_loss(stream)
         self.backward(stream)
+
+    # --- Algorithm 1, "optimizer.step()": every parameter the step has a gradient for
+    def optimizer_step(self, kind: int = kb.OPT_ADAM, lr: float = 0.01, beta1: float = 0.9, beta2: float = 0.999,
+                       eps: float = 1e-8, stream=None):
+        torch = self.torch
+        if not hasattr(self, "opt_t"):
+            self.opt_t = 0
+            self.opt_state = {}
+        self.opt_t += 1
+        pairs = [("M", self.M, self.dM, False)]
+        for l, (lay, g) in enumerate(zip(self.layers, self.grads)):
+            pairs += [("V%d" % l, lay["V"], g["dV"], False), ("a%d" % l, lay["a"], g["da"], False),
+                      ("W0%d" % l, lay["W0"], g["dW0"], False)]
+        if self.dH0 is not None:
+            pairs.append(("H0", self.H0, self.dH0, True))      # entity embeddings: only rows the step reached
+        for name, p, g, rows in pairs:
+            m = v = None
+            if kind == kb.OPT_ADAM:
+                if name not in self.opt_state:
+                    self.opt_state[name] = (torch.zeros_like(p), torch.zeros_like(p))
+                m, v = self.opt_state[name]
+            kb.optimizer_step(kind, p, g, m, v, lr, beta1, beta2, eps, self.opt_t, rows=rows, stream=stream)
