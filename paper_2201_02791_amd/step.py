@@ -99,21 +99,26 @@ class TrainStep:
     # --- Algorithm 1, "optimizer.step()": every parameter the step has a gradient for
     def optimizer_step(self, kind: int = kb.OPT_ADAM, lr: float = 0.01, beta1: float = 0.9, beta2: float = 0.999,
                        eps: float = 1e-8, stream=None):
-        torch = self.torch
         if not hasattr(self, "opt_t"):
-            self.opt_t = 0
-            self.opt_state = {}
+            self.init_optimizer(kind)
         self.opt_t += 1
+        for name, p, g, rows in self._opt_pairs():
+            m, v = self.opt_state.get(name, (None, None)) if kind == kb.OPT_ADAM else (None, None)
+            kb.optimizer_step(kind, p, g, m, v, lr, beta1, beta2, eps, self.opt_t, rows=rows, stream=stream)
+
+    def _opt_pairs(self):
         pairs = [("M", self.M, self.dM, False)]
         for l, (lay, g) in enumerate(zip(self.layers, self.grads)):
             pairs += [("V%d" % l, lay["V"], g["dV"], False), ("a%d" % l, lay["a"], g["da"], False),
                       ("W0%d" % l, lay["W0"], g["dW0"], False)]
         if self.dH0 is not None:
             pairs.append(("H0", self.H0, self.dH0, True))      # entity embeddings: only rows the step reached
-        for name, p, g, rows in pairs:
-            m = v = None
-            if kind == kb.OPT_ADAM:
-                if name not in self.opt_state:
-                    self.opt_state[name] = (torch.zeros_like(p), torch.zeros_like(p))
-                m, v = self.opt_state[name]
-            kb.optimizer_step(kind, p, g, m, v, lr, beta1, beta2, eps, self.opt_t, rows=rows, stream=stream)
+        return pairs
+
+    def init_optimizer(self, kind: int = kb.OPT_ADAM):
+        """Allocate (zeroed) Adam moments for every parameter, so that no step allocates."""
+        self.opt_t = 0
+        self.opt_state = {}
+        if kind == kb.OPT_ADAM:
+            for name, p, _, _ in self._opt_pairs():
+                self.opt_state[name] = (self.torch.zeros_like(p), self.torch.zeros_like(p))
