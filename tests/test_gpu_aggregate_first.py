@@ -216,3 +216,30 @@ def test_bf16_aggregate_first_intermediates(kb, orc):
     # one bf16 unit in the last place at most (fp32 vs fp64 sums can land on different sides of a tie)
     assert np.all(np.abs(got - Z) <= np.abs(Z) * 2.0 ** -8 + 1e-30)
     assert np.mean(got == bf(Z)) > 0.999
+
+
+@pytest.mark.parametrize("order", [pytest.param(0, id="project_first")] + ORDERS)
+@pytest.mark.parametrize("dims,bf16", [((128, 32, 32), False), ((48, 96, 24), False), ((128, 32, 32), True),
+                                       ((64, 128, 64), True)],
+                         ids=["f32_128_32_32", "f32_48_96_24", "bf16_128_32_32", "bf16_64_128_64"])
+def test_feature_layer_with_different_widths(kb, orc, order, dims, bf16):
+    """A feature-input layer whose width differs from the embedding width (the paper's large-graph
+    setting: 128-d features, 32-d embeddings), and a widening layer, in every order."""
+    say("d_in != d_out, order", order, dims, bf16)
+    n, R, m, B = 700, 4, 6000, 3
+    spec = synth.scaled(synth.WORKLOADS[4 if bf16 else 0], name="widths", seed=9, n_entities=n, n_relations=R,
+                        n_triples=m, d=dims[2], n_bases=B, n_pos=150, n_neg=2, neg_mode=1, n_parts=1, part_id=0,
+                        acts=[0, 0] if bf16 else [1, 0], feature_std=0.5)
+    head, rel, tail = random_graph(41, n, R, m)
+    rng = np.random.default_rng(5)
+    g = lambda *shape: (rng.uniform(-1, 1, shape) * np.sqrt(6.0 / (shape[-2] + shape[-1]))).astype(np.float32)
+    opart = orc.build_partition(head, rel, tail, n, R, 1, 0, 2, spec.neg_domain)
+    params = dict(V=[g(B, dims[0], dims[1]), g(B, dims[1], dims[2])], a=[g(2 * R, B), g(2 * R, B)],
+                  W0=[g(dims[0], dims[1]), g(dims[1], dims[2])],
+                  M=(rng.standard_normal((R, dims[2])) * 0.1).astype(np.float32),
+                  H0=(rng.standard_normal((opart["n_vert"], dims[0])) * 0.5).astype(np.float32))
+    gp, ts, _, pos = gpu_step(spec, head, rel, tail, params=params, order=order)
+    mode = {0: 1, AGG: 2, RELW: 3}[order] if bf16 else False
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos, msg_bf16=mode)
+    tol = (TOL_BF16, TOL_BF16) if bf16 else (TOL_VAL, TOL_GRAD)
+    assert_step_close(ts, res, *tol)
