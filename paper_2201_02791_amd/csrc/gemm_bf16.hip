@@ -30,10 +30,7 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int TM = 128, TN = 256, TK = 32, LDK = TK + 8, NT = 256;
-constexpr int EPI_LD = 128;                           // floats per staged row: 4 x 32 x 128 x 4 B = 64 KB
-constexpr int LDS_MAIN = (TM + TN) * LDK * 2;         // bytes
-constexpr int LDS_EPI = 4 * 32 * EPI_LD * 4;          // bytes: 4 wavefronts x 32 rows
+constexpr int TM = 128, TN = 256, TK = 32, NT = 256;
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)   // two fp32 -> packed bf16x2, nearest even
 {
@@ -151,10 +148,14 @@ __device__ __forceinline__ void transpose_pairs(const uint32_t (&pr)[8], uint4 &
 
 // KC = true : C[m][n] = sum_k A[m][k] B[n][k]   (A.oct(m, k), B.oct(n, k))
 // KC = false: C[m][n] = sum_k A[k][m] B[k][n]   (A.pair(k, m), B.pair(k, n))
-template <bool KC, class EPI>
 // Split s contracts [s*kchunk, min((s+1)*kchunk, K)), or, in a grouped launch (g_beg non-null),
 // [g_beg[s], g_end[s]) with the epilogue bound to group g_id[s].
-__global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, int64_t K, int64_t kchunk,
+// TNt: columns of the block tile, 256 (a wavefront owns 64 x 128: 128 accumulator registers, two blocks
+// per CU) or 128 (64 x 64: four blocks per CU, for contractions too short to hide their own latency).
+// TKt: contraction depth of a tile, 32 or (k-contiguous operands only) 64: with 64 a row's piece of a
+// tile is a whole 128-byte line, and one tile instead of two is in flight in registers.
+template <bool KC, class EPI, int TNt = TN, int TKt = TK>
+__global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, int64_t K, int64_t kchunk,
                                                      int32_t tiles_m, int32_t tiles_n, int32_t n_splits,
                                                      const int32_t *__restrict__ g_id,
                                                      const int32_t *__restrict__ g_beg,
@@ -163,9 +164,15 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
                                                      const int32_t *__restrict__ mt_beg,
                                                      const int32_t *__restrict__ mt_end, int64_t b_group_stride)
 {
+    constexpr int NJ = TNt / 64;                 // 32-column MFMA tiles per wavefront
+    constexpr int LDKt = TKt == 32 ? 40 : 88;    // LDS row pitch in elements: 80 / 176 bytes, so that the 16-byte
+                                                 // operand reads of 8 consecutive rows fall in 8 different bank groups
+    constexpr int TPR = TKt / 8, RPP = NT / TPR; // k-contiguous loads: threads per row, rows per pass
+    constexpr int PF = TKt == TK ? 2 : 1;        // tiles in flight in registers
+    static_assert(KC || TKt == TK, "k-strided operands use the 32-deep tile");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint16_t (*As)[LDK] = reinterpret_cast<uint16_t (*)[LDK]>(smem);
-    uint16_t (*Bs)[LDK] = reinterpret_cast<uint16_t (*)[LDK]>(smem + TM * LDK * 2);
+    uint16_t (*As)[LDKt] = reinterpret_cast<uint16_t (*)[LDKt]>(smem);
+    uint16_t (*Bs)[LDKt] = reinterpret_cast<uint16_t (*)[LDKt]>(smem + TM * LDKt * 2);
 
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int wm = w >> 1, wn = w & 1;
@@ -196,16 +203,16 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
         if (KC) A.rows = m_end;
         B.p += (int64_t)mt_id[tm] * b_group_stride;
     }
-    const int32_t n0 = tn * TN;
+    const int32_t n0 = tn * TNt;
     int64_t kbeg = bid * kchunk;
     int64_t kend = (kbeg + kchunk < K) ? kbeg + kchunk : K;
     if (g_beg) { kbeg = g_beg[bid]; kend = g_end[bid]; epi.bind(g_id[bid]); }
 
-    floatx16 acc[2][4];
+    floatx16 acc[2][NJ];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
@@ -214,8 +221,8 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
     // transposed only when they are written to LDS, so that nothing waits for a load before the
     // matrix-core loop.  Rows picked through an index list have their indices fetched one tile
     // earlier still, which keeps the row loads themselves independent.
-    struct Regs { uint4 a[2], b[4]; uint32_t pa[8], pb[2][8]; };
-    Regs rg[2];
+    struct Regs { uint4 a[KC ? TM / RPP : 1], b[KC ? TNt / RPP : 1]; uint32_t pa[KC ? 1 : 8], pb[KC ? 1 : NJ / 2][KC ? 1 : 8]; };
+    Regs rg[PF];
     int32_t brow[8];          // KC = false: stored rows of B for the tile that is loaded next
 
     auto load_rows = [&](int64_t k0) {
@@ -228,23 +235,33 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
             }
         }
     };
+    // k-contiguous A through an index list: the stored rows of this thread's tile rows, fetched once
+    int64_t arow[KC ? TM / RPP : 1];
+    if constexpr (KC) {
+#pragma unroll
+        for (int ps = 0; ps < TM / RPP; ++ps) {
+            const int64_t r = m0 + t / TPR + ps * RPP;
+            arow[ps] = r < A.rows ? (A.idx ? (int64_t)A.idx[r] : r) : -1;
+        }
+    }
     auto load_tile = [&](int64_t k0, Regs &R) {
-        if (KC) {
-            const int row = t >> 2, ko = (t & 3) * 8;
+        if constexpr (KC) {
+            const int row = t / TPR, ko = (t % TPR) * 8;
             const bool kok = k0 + ko < kend;
 #pragma unroll
-            for (int ps = 0; ps < 2; ++ps)
-                R.a[ps] = kok ? A.oct(m0 + row + ps * 64, (int32_t)(k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
+            for (int ps = 0; ps < TM / RPP; ++ps)
+                R.a[ps] = (kok && arow[ps] >= 0 && k0 + ko < A.cols)
+                              ? *reinterpret_cast<const uint4 *>(A.p + arow[ps] * A.ld + (k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-            for (int ps = 0; ps < 4; ++ps)
-                R.b[ps] = kok ? B.oct(n0 + row + ps * 64, (int32_t)(k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
+            for (int ps = 0; ps < TNt / RPP; ++ps)
+                R.b[ps] = kok ? B.oct(n0 + row + ps * RPP, (int32_t)(k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
         } else {
             const int cp = t & 63, ko = (t >> 6) * 8;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk)
                 R.pa[kk] = (k0 + ko + kk < kend) ? A.pair(k0 + ko + kk, (int32_t)(m0 + 2 * cp)) : 0u;
 #pragma unroll
-            for (int ps = 0; ps < 2; ++ps)
+            for (int ps = 0; ps < NJ / 2; ++ps)
 #pragma unroll
                 for (int kk = 0; kk < 8; ++kk) {
                     const int32_t c = n0 + 2 * (cp + ps * 64);
@@ -254,12 +271,12 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
         }
     };
     auto store_tile = [&](Regs &R) {
-        if (KC) {
-            const int row = t >> 2, ko = (t & 3) * 8;
+        if constexpr (KC) {
+            const int row = t / TPR, ko = (t % TPR) * 8;
 #pragma unroll
-            for (int ps = 0; ps < 2; ++ps) *reinterpret_cast<uint4 *>(&As[row + ps * 64][ko]) = R.a[ps];
+            for (int ps = 0; ps < TM / RPP; ++ps) *reinterpret_cast<uint4 *>(&As[row + ps * RPP][ko]) = R.a[ps];
 #pragma unroll
-            for (int ps = 0; ps < 4; ++ps) *reinterpret_cast<uint4 *>(&Bs[row + ps * 64][ko]) = R.b[ps];
+            for (int ps = 0; ps < TNt / RPP; ++ps) *reinterpret_cast<uint4 *>(&Bs[row + ps * RPP][ko]) = R.b[ps];
         } else {
             const int cp = t & 63, ko = (t >> 6) * 8;
             uint4 c0, c1;
@@ -267,7 +284,7 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
             *reinterpret_cast<uint4 *>(&As[2 * cp][ko]) = c0;
             *reinterpret_cast<uint4 *>(&As[2 * cp + 1][ko]) = c1;
 #pragma unroll
-            for (int ps = 0; ps < 2; ++ps) {
+            for (int ps = 0; ps < NJ / 2; ++ps) {
                 transpose_pairs(R.pb[ps], c0, c1);
                 *reinterpret_cast<uint4 *>(&Bs[2 * (cp + ps * 64)][ko]) = c0;
                 *reinterpret_cast<uint4 *>(&Bs[2 * (cp + ps * 64) + 1][ko]) = c1;
@@ -276,19 +293,19 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
     };
     auto mma_tile = [&]() {
 #pragma unroll
-        for (int ks = 0; ks < TK; ks += 16) {
+        for (int ks = 0; ks < TKt; ks += 16) {
             const int kc = ks + 8 * (lane >> 5);
-            bf16x8 af[2], bfr[4];
+            bf16x8 af[2], bfr[NJ];
 #pragma unroll
             for (int i = 0; i < 2; ++i)
                 af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[wm * 64 + i * 32 + (lane & 31)][kc]));
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                bfr[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[wn * 128 + j * 32 + (lane & 31)][kc]));
+            for (int j = 0; j < NJ; ++j)
+                bfr[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[wn * (TNt / 2) + j * 32 + (lane & 31)][kc]));
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < NJ; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
         }
     };
@@ -297,50 +314,56 @@ __global__ __launch_bounds__(NT, 2) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, 
         __syncthreads();                 // previous tile fully consumed
         store_tile(R);
         __syncthreads();
-        if (k0 + 2 * TK < kend) { load_tile(k0 + 2 * TK, R); load_rows(k0 + 3 * TK); }
+        if (k0 + PF * TKt < kend) { load_tile(k0 + PF * TKt, R); load_rows(k0 + (PF + 1) * TKt); }
         mma_tile();
     };
 
     if (kbeg < kend) {
         load_rows(kbeg);
         load_tile(kbeg, rg[0]);
-        load_rows(kbeg + TK);
-        if (kbeg + TK < kend) { load_tile(kbeg + TK, rg[1]); load_rows(kbeg + 2 * TK); }
+        load_rows(kbeg + TKt);
+        if (PF == 2 && kbeg + TKt < kend) { load_tile(kbeg + TKt, rg[1]); load_rows(kbeg + 2 * TKt); }
     }
-    for (int64_t k0 = kbeg; k0 < kend; k0 += 2 * TK) {
-        step(k0, rg[0]);
-        if (k0 + TK < kend) step(k0 + TK, rg[1]);
+    if constexpr (PF == 2) {
+        for (int64_t k0 = kbeg; k0 < kend; k0 += 2 * TKt) {
+            step(k0, rg[0]);
+            if (k0 + TKt < kend) step(k0 + TKt, rg[1]);
+        }
+    } else {
+        for (int64_t k0 = kbeg; k0 < kend; k0 += TKt) step(k0, rg[0]);
     }
     // D register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 tile
     if (EPI::staged) {
-        float *stage = reinterpret_cast<float *>(smem) + w * 32 * EPI_LD;   // 32 rows x 128 columns per wavefront
+        constexpr int ELD = TNt / 2;               // floats per staged row: one wavefront's columns
+        float *stage = reinterpret_cast<float *>(smem) + w * 32 * ELD;   // 32 rows x 128 columns per wavefront
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             __syncthreads();             // operand tiles (or the previous row group) no longer needed
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    stage[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * EPI_LD + j * 32 + (lane & 31)] = acc[i][j][v];
+                    stage[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * ELD + j * 32 + (lane & 31)] = acc[i][j][v];
             __syncthreads();
+            constexpr int LPRW = NJ * 4;             // lanes across a wavefront's row of NJ * 32 columns, 8 each
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {
-                const int row = it * 4 + (lane >> 4), c8 = (lane & 15) * 8;
-                const float4 x = *reinterpret_cast<const float4 *>(&stage[row * EPI_LD + c8]);
-                const float4 y = *reinterpret_cast<const float4 *>(&stage[row * EPI_LD + c8 + 4]);
+            for (int it = 0; it < 32 / (64 / LPRW); ++it) {
+                const int row = it * (64 / LPRW) + lane / LPRW, c8 = (lane % LPRW) * 8;
+                const float4 x = *reinterpret_cast<const float4 *>(&stage[row * ELD + c8]);
+                const float4 y = *reinterpret_cast<const float4 *>(&stage[row * ELD + c8 + 4]);
                 if (m0 + wm * 64 + i * 32 + row < m_end || !mt_beg)
-                    epi.store8(m0 + wm * 64 + i * 32 + row, n0 + wn * 128 + c8, x, y);
+                    epi.store8(m0 + wm * 64 + i * 32 + row, n0 + wn * (TNt / 2) + c8, x, y);
             }
         }
     } else {
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                    const int col = wn * 128 + j * 32 + (lane & 31);
+                    const int col = wn * (TNt / 2) + j * 32 + (lane & 31);
                     if (m0 + row < m_end || !mt_beg) epi.store(m0 + row, n0 + col, acc[i][j][v]);
                 }
     }
@@ -425,7 +448,7 @@ __global__ __launch_bounds__(256) void k_cvt_group_mats(const float *__restrict_
     }
 }
 
-template <bool KC, class EPI>
+template <bool KC, class EPI, int TNt = TN, int TKt = TK>
 int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64_t kchunk, int32_t tiles_m,
                 int32_t tiles_n, int64_t splits, hipStream_t st, const int32_t *g_id = nullptr,
                 const int32_t *g_beg = nullptr, const int32_t *g_end = nullptr, const int32_t *mt_id = nullptr,
@@ -435,14 +458,15 @@ int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64
     const int64_t n_patches = cdiv(splits * tiles_m, pm) * cdiv(tiles_n, pn);
     const int64_t blocks = cdiv(n_patches, 8) * 8 * 64;
     KGE_REQUIRE(blocks < 0x7fffffffLL, KGE_ERANGE, "grid too large");
-    const size_t lds = EPI::staged ? (LDS_EPI > LDS_MAIN ? LDS_EPI : LDS_MAIN) : LDS_MAIN;
+    const size_t lds_main = (size_t)(TM + TNt) * (TKt == 32 ? 40 : 88) * 2, lds_epi = (size_t)4 * 32 * (TNt / 2) * 4;
+    const size_t lds = EPI::staged ? (lds_epi > lds_main ? lds_epi : lds_main) : lds_main;
     static bool attr_set = false;
     if (!attr_set) {
-        KGE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<KC, EPI>),
+        KGE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<KC, EPI, TNt, TKt>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    k_gemm_bf16<KC, EPI><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n, (int32_t)splits,
+    k_gemm_bf16<KC, EPI, TNt, TKt><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n, (int32_t)splits,
                                                             g_id, g_beg, g_end, mt_id, mt_beg, mt_end, b_group_stride);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
@@ -599,7 +623,7 @@ int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, 
     MatBF Bm{reinterpret_cast<const uint16_t *>(WbT), d_out, d_in, d_in, nullptr};
     EpiRowsBF16Staged ep{reinterpret_cast<uint16_t *>(U), p->n_seg, d_out};
     KGE_PROF("apply_rel", st);
-    return launch_gemm<true, EpiRowsBF16Staged>(A, Bm, ep, d_in, cdiv(d_in, TK) * TK, p->n_relt, tiles_n, 1, st, nullptr,
+    return launch_gemm<true, EpiRowsBF16Staged, TN, 64>(A, Bm, ep, d_in, cdiv(d_in, TK) * TK, p->n_relt, tiles_n, 1, st, nullptr,
                                                 nullptr, nullptr, p->relt_rel, p->relt_beg, p->relt_end,
                                                 (int64_t)d_in * d_out);
 }
