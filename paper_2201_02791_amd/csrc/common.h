@@ -61,7 +61,7 @@ struct kge_partition {
     // the runs grouped by destination (order dst, rel): dr_seg = run id, dr_rel = its relation
     int32_t *dr_ptr, *dr_seg, *dr_rel;
     kge_heavy_index hv_dr;
-    // each relation's run range cut into chunks of at most KGE_REL_CHUNK runs
+    // each relation's run range cut into chunks of KGE_REL_CHUNK .. 8 KGE_REL_CHUNK runs (about 2048 chunks in all)
     int32_t n_relc;
     int32_t *relc_rel, *relc_beg, *relc_end;
     // and into row tiles of at most KGE_REL_TILE runs

@@ -710,10 +710,15 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
         const int64_t R2 = 2 * (int64_t)n_rel;
         std::vector<int32_t> h_rel_ptr((size_t)R2 + 1), c_rel, c_beg, c_end, t_rel, t_beg, t_end;
         KGE_HIP(hipMemcpy(h_rel_ptr.data(), p->rel_ptr, sizeof(int32_t) * (size_t)(R2 + 1), hipMemcpyDeviceToHost));
+        // chunk length: about 2048 chunks over all runs (every chunk ends in one atomic accumulation of a
+        // whole d_in x d_out tile, so fewer, longer chunks are cheaper as long as the chip stays full)
+        int32_t chunk = (int32_t)((S / 2048 + 31) / 32 * 32);
+        if (chunk < KGE_REL_CHUNK) chunk = KGE_REL_CHUNK;
+        if (chunk > 8 * KGE_REL_CHUNK) chunk = 8 * KGE_REL_CHUNK;
         for (int64_t r = 0; r < R2; ++r)
-            for (int32_t b = h_rel_ptr[r]; b < h_rel_ptr[r + 1]; b += KGE_REL_CHUNK) {
+            for (int32_t b = h_rel_ptr[r]; b < h_rel_ptr[r + 1]; b += chunk) {
                 c_rel.push_back((int32_t)r); c_beg.push_back(b);
-                c_end.push_back(b + KGE_REL_CHUNK < h_rel_ptr[r + 1] ? b + KGE_REL_CHUNK : h_rel_ptr[r + 1]);
+                c_end.push_back(b + chunk < h_rel_ptr[r + 1] ? b + chunk : h_rel_ptr[r + 1]);
             }
         // and into row tiles of at most KGE_REL_TILE runs (one output tile of the per-relation products)
         for (int64_t r = 0; r < R2; ++r)
