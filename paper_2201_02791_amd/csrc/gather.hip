@@ -105,10 +105,23 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
     constexpr int U = 8;
     const int lane = threadIdx.x & 63;
     const int64_t wid = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
+    const int kl = lane % LPR, g = lane / LPR;
+    if (active && wid >= n_units && wid - n_units < N && !active[wid - n_units]) {
+        // a row outside the batch's sub-graph, seen before its edge range is even fetched: a zero row
+        // (a heavy row's zeros are written once more by the finishing kernel)
+        if (g == 0 && kl * VEC < d) {
+            const int64_t o = (wid - n_units) * d + kl * VEC;
+#pragma unroll
+            for (int v4 = 0; v4 < VEC; v4 += 4) {
+                *reinterpret_cast<float4 *>(out + o + v4) = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (out2) *reinterpret_cast<float4 *>(out2 + o + v4) = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+        return;
+    }
     const RowWork rw = row_work(wid, dm_ptr, N, n_units, hv_row, hv_unit_ptr, unit_hv);
     if (rw.row < 0) return;                             // whole wavefront leaves together
-    const int kl = lane % LPR, g = lane / LPR;
-    if (active && !active[rw.row]) {                    // outside the batch's sub-graph: a zero row
+    if (active && !active[rw.row]) {                    // a unit of a heavy row outside the sub-graph
         if (rw.unit < 0 && g == 0 && kl * VEC < d) {
             const int64_t o = rw.row * d + kl * VEC;
 #pragma unroll
