@@ -782,3 +782,36 @@ void orc_optimizer_step(int32_t kind, double *p, const double *g, double *m, dou
         }
     }
 }
+
+/* ------------------------------------------------------------------ */
+/* Dropout on a layer's input                                          */
+/* ------------------------------------------------------------------ */
+/*
+ * The paper's large-graph setting uses dropout 0.2 and does not say where; it is applied here to the
+ * features a layer reads (neighbour messages and self-loop alike), in the usual inverted form:
+ *   out[i][k] = keep ? H[i][k] / (1 - p) : 0
+ * The decision for element (i, k) of layer `layer` at training step `step` is counter-based, like the
+ * negative sampler:  x = Philox4x32-10(counter = (i, k / 4, step lo, step hi),
+ *                                       key = (seed lo, seed hi xor (layer + 1)))
+ * keep iff x[k mod 4] >= floor(p * 2^32).  mask (optional) receives 1 for kept elements.
+ * p = 0 keeps everything.
+ */
+void orc_dropout(int64_t N, int32_t d, double p, uint64_t seed, uint64_t step, int32_t layer,
+                 const double *H, double *out, uint8_t *mask)
+{
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) ^ (uint32_t)(layer + 1) };
+    uint32_t thr = (uint32_t)(p * 4294967296.0);
+    double scale = 1.0 / (1.0 - p);
+    for (int64_t i = 0; i < N; ++i)
+        for (int32_t g = 0; g < (d + 3) / 4; ++g) {
+            uint32_t ctr[4] = { (uint32_t)i, (uint32_t)g, (uint32_t)step, (uint32_t)(step >> 32) };
+            uint32_t x[4];
+            orc_philox4x32_10(ctr, key, x);
+            for (int32_t q = 0; q < 4 && 4 * g + q < d; ++q) {
+                size_t e = (size_t)i * d + 4 * g + q;
+                int keep = p <= 0.0 || x[q] >= thr;
+                out[e] = keep ? H[e] * scale : 0.0;
+                if (mask) mask[e] = (uint8_t)keep;
+            }
+        }
+}

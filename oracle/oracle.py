@@ -106,15 +106,31 @@ def layer_forward(part, V, a, W0, act, H, msg_bf16=False):
     return pre, out
 
 
-def rgcn_forward(part, layers: Sequence[dict], H0, msg_bf16=False):
+def dropout(H, p, seed, step, layer):
+    """Inverted dropout on a layer's input with a counter-based mask.  Returns (dropped H, keep mask)."""
+    H = _d(H)
+    out = np.zeros_like(H); mask = np.zeros(H.shape, np.uint8)
+    lib().orc_dropout(C.c_int64(H.shape[0]), C.c_int32(H.shape[1]), C.c_double(p), C.c_uint64(seed),
+                      C.c_uint64(step), C.c_int32(layer), _p(H, _F64), _p(out, _F64), _p(mask, _U8))
+    return out, mask
+
+
+def rgcn_forward(part, layers: Sequence[dict], H0, msg_bf16=False, drop=None):
     """All layers.  ``layers[l]`` has V [B,d,d], a [2R,B], W0 [d,d], act.  Returns the list of
-    layer inputs/outputs ``Hs`` (len L+1, Hs[0] = H0) and pre-activations ``pres`` (len L)."""
-    Hs, pres = [_d(H0)], []
-    for lay in layers:
+    layer inputs/outputs ``Hs`` (len L+1, Hs[0] = H0) and pre-activations ``pres`` (len L).
+
+    ``drop = (p, seed, step)`` applies :func:`dropout` to every layer's input; ``Hs[l]`` is then
+    the input as the layer saw it (after dropout) for l < L, and the third result lists the keep
+    masks."""
+    Hs, pres, masks = [_d(H0)], [], []
+    for l, lay in enumerate(layers):
+        if drop is not None:
+            Hs[-1], m = dropout(Hs[-1], drop[0], drop[1], drop[2], l)
+            masks.append(m)
         pre, out = layer_forward(part, lay["V"], lay["a"], lay["W0"], lay["act"], Hs[-1], msg_bf16)
         pres.append(pre)
         Hs.append(out)
-    return Hs, pres
+    return (Hs, pres, masks) if drop is not None else (Hs, pres)
 
 
 def layer_backward(part, V, a, W0, act, H, pre, dHout, need_dH=True, msg_bf16=False):
@@ -137,8 +153,10 @@ def layer_backward(part, V, a, W0, act, H, pre, dHout, need_dH=True, msg_bf16=Fa
     return dict(dV=dV, da=da, dW0=dW0, dH=dH, dP=dP, Gpre=G)
 
 
-def rgcn_backward(part, layers, Hs, pres, dH_out, need_dH0=True, msg_bf16=False):
-    """Reverse of :func:`rgcn_forward`. Returns per-layer grads (list) and dH0 (or None)."""
+def rgcn_backward(part, layers, Hs, pres, dH_out, need_dH0=True, msg_bf16=False, drop=None, masks=None):
+    """Reverse of :func:`rgcn_forward`. Returns per-layer grads (list) and dH0 (or None).  With
+    dropout (``drop`` and the forward's ``masks``) the gradient handed to the layer below, and dH0,
+    is the one with respect to the input before dropout."""
     grads: List[Optional[dict]] = [None] * len(layers)
     g = _d(dH_out)
     for l in range(len(layers) - 1, -1, -1):
@@ -147,6 +165,8 @@ def rgcn_backward(part, layers, Hs, pres, dH_out, need_dH0=True, msg_bf16=False)
         r = layer_backward(part, lay["V"], lay["a"], lay["W0"], lay["act"], Hs[l], pres[l], g, need, msg_bf16)
         grads[l] = r
         g = r["dH"]
+        if drop is not None and g is not None:
+            g = g * masks[l] / (1.0 - drop[0])
     return grads, g
 
 
