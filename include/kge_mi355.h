@@ -90,6 +90,15 @@ typedef struct kge_layer {
     const float *V;    /* [n_bases][d_in][d_out]   basis matrices V_b                          */
     const float *a;    /* [2R][n_bases]            coefficients a_rb                           */
     const float *W0;   /* [d_in][d_out]            self-loop weight                            */
+    /* Dropout on the layer's input (training setting of Sec. 4: 0.2 on the large graphs), inverted
+     * form: every element the layer reads - for the neighbour messages, the self-loop and the weight
+     * gradients - is zeroed with probability `dropout` and scaled by 1 / (1 - dropout) otherwise.
+     * Element (i, k) is kept iff word (k mod 4) of Philox4x32-10(counter = (i, k / 4, step lo, step hi),
+     * key = (seed lo, seed hi xor (layer index + 1))) is >= floor(dropout * 2^32).  0 = off (the three
+     * fields are then ignored); must be in [0, 1).  kge_rgcn_backward must see the same three values
+     * as the forward call it follows; change drop_step between training steps for a fresh mask. */
+    float dropout;
+    uint64_t drop_seed, drop_step;
 } kge_layer;
 
 /* Gradients of one layer; device pointers, caller owned, overwritten. */
@@ -316,6 +325,9 @@ int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_ent
  *               destination) run in the partition's run order (valid after forward)
  *   KGE_WS_Y    aggregate-first layer l: y [N][B*d_in] float of the last such layer forward has
  *               processed (the buffer is shared between layers)
+ *   KGE_WS_HD   layer l's input after dropout [N][d_in] float (valid after forward; only for layers
+ *               with dropout > 0; with dropout, KGE_WS_DH is the gradient with respect to the
+ *               input BEFORE dropout)
  *   KGE_WS_U    relation-weight layers: one buffer shared by all of them, msg_dtype elements.  After
  *               forward it holds u [S][d_out] of the last layer (the per-run products z W_r); after
  *               backward dz [S][d_in] of the last layer that produced an input gradient.  The slice
@@ -323,7 +335,8 @@ int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_ent
  * KGE_WS_P exists only for project-first layers, KGE_WS_Y only for aggregate-first ones, KGE_WS_Z for
  * both orders that sum first, KGE_WS_U and no KGE_WS_DP contents beyond G for relation-weight layers.
  */
-enum { KGE_WS_P = 0, KGE_WS_H = 1, KGE_WS_G = 2, KGE_WS_DP = 3, KGE_WS_DH = 4, KGE_WS_Z = 5, KGE_WS_Y = 6, KGE_WS_U = 7 };
+enum { KGE_WS_P = 0, KGE_WS_H = 1, KGE_WS_G = 2, KGE_WS_DP = 3, KGE_WS_DH = 4, KGE_WS_Z = 5, KGE_WS_Y = 6, KGE_WS_U = 7,
+       KGE_WS_HD = 8 };
 int kge_workspace_slice(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
                         int32_t msg_dtype, int32_t which, int32_t layer, size_t *offset,
                         size_t *bytes);

@@ -795,9 +795,13 @@ void orc_optimizer_step(int32_t kind, double *p, const double *g, double *m, dou
  *                                       key = (seed lo, seed hi xor (layer + 1)))
  * keep iff x[k mod 4] >= floor(p * 2^32).  mask (optional) receives 1 for kept elements.
  * p = 0 keeps everything.
+ * product_f32 != 0: the scaled value is the single-precision product of the single-precision values
+ * of h and 1 / (1 - p).  The bf16 pipelines round the dropped input to bf16 next; that rounding is a
+ * decision taken from a floating-point value, so the value it is taken from is formed in the
+ * precision the kernels use (the paper fixes none).
  */
 void orc_dropout(int64_t N, int32_t d, double p, uint64_t seed, uint64_t step, int32_t layer,
-                 const double *H, double *out, uint8_t *mask)
+                 int32_t product_f32, const double *H, double *out, uint8_t *mask)
 {
     uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) ^ (uint32_t)(layer + 1) };
     uint32_t thr = (uint32_t)(p * 4294967296.0);
@@ -810,7 +814,9 @@ void orc_dropout(int64_t N, int32_t d, double p, uint64_t seed, uint64_t step, i
             for (int32_t q = 0; q < 4 && 4 * g + q < d; ++q) {
                 size_t e = (size_t)i * d + 4 * g + q;
                 int keep = p <= 0.0 || x[q] >= thr;
-                out[e] = keep ? H[e] * scale : 0.0;
+                if (!keep) out[e] = 0.0;
+                else if (product_f32) out[e] = (double)((float)H[e] * (float)scale);
+                else out[e] = H[e] * scale;
                 if (mask) mask[e] = (uint8_t)keep;
             }
         }

@@ -106,12 +106,14 @@ def layer_forward(part, V, a, W0, act, H, msg_bf16=False):
     return pre, out
 
 
-def dropout(H, p, seed, step, layer):
-    """Inverted dropout on a layer's input with a counter-based mask.  Returns (dropped H, keep mask)."""
+def dropout(H, p, seed, step, layer, product_f32=False):
+    """Inverted dropout on a layer's input with a counter-based mask.  Returns (dropped H, keep mask).
+    product_f32: form h / (1 - p) as a single-precision product (what the bf16 pipelines round next)."""
     H = _d(H)
     out = np.zeros_like(H); mask = np.zeros(H.shape, np.uint8)
     lib().orc_dropout(C.c_int64(H.shape[0]), C.c_int32(H.shape[1]), C.c_double(p), C.c_uint64(seed),
-                      C.c_uint64(step), C.c_int32(layer), _p(H, _F64), _p(out, _F64), _p(mask, _U8))
+                      C.c_uint64(step), C.c_int32(layer), C.c_int32(int(product_f32)), _p(H, _F64), _p(out, _F64),
+                      _p(mask, _U8))
     return out, mask
 
 
@@ -125,7 +127,7 @@ def rgcn_forward(part, layers: Sequence[dict], H0, msg_bf16=False, drop=None):
     Hs, pres, masks = [_d(H0)], [], []
     for l, lay in enumerate(layers):
         if drop is not None:
-            Hs[-1], m = dropout(Hs[-1], drop[0], drop[1], drop[2], l)
+            Hs[-1], m = dropout(Hs[-1], drop[0], drop[1], drop[2], l, bool(msg_bf16))
             masks.append(m)
         pre, out = layer_forward(part, lay["V"], lay["a"], lay["W0"], lay["act"], Hs[-1], msg_bf16)
         pres.append(pre)
@@ -271,11 +273,17 @@ def optimizer_step(kind, p, g, m, v, lr=0.01, b1=0.9, b2=0.999, eps=1e-8, t=1, r
 
 
 def train_step(part, layers, H0, M, pos_core_idx, n_neg, mode, seed, step, need_dH0=True,
-               msg_bf16=False):
-    """One whole step: encoder forward, negatives, score + loss, encoder backward."""
-    Hs, pres = rgcn_forward(part, layers, H0, msg_bf16)
+               msg_bf16=False, dropout=0.0):
+    """One whole step: encoder forward, negatives, score + loss, encoder backward.  With
+    ``dropout`` > 0 every layer's input is dropped with masks keyed by the step's (seed, step)."""
+    drop = (float(dropout), seed, step) if dropout > 0 else None
+    masks = None
+    if drop is None:
+        Hs, pres = rgcn_forward(part, layers, H0, msg_bf16)
+    else:
+        Hs, pres, masks = rgcn_forward(part, layers, H0, msg_bf16, drop)
     ne, ns = sample_negatives(part, pos_core_idx, n_neg, mode, seed, step)
     sl = distmult_score_loss(part, Hs[-1], M, pos_core_idx, ne, ns)
-    grads, dH0 = rgcn_backward(part, layers, Hs, pres, sl["dH"], need_dH0, msg_bf16)
+    grads, dH0 = rgcn_backward(part, layers, Hs, pres, sl["dH"], need_dH0, msg_bf16, drop, masks)
     return dict(Hs=Hs, pres=pres, neg_ent=ne, neg_side=ns, scores=sl["scores"], loss=sl["loss"],
-                dH_out=sl["dH"], dM=sl["dM"], grads=grads, dH0=dH0)
+                dH_out=sl["dH"], dM=sl["dM"], grads=grads, dH0=dH0, masks=masks, drop=drop)

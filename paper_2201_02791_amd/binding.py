@@ -57,7 +57,8 @@ class _PartInfo(C.Structure):
 
 class _Layer(C.Structure):
     _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("n_bases", C.c_int32), ("act", C.c_int32),
-                ("order", C.c_int32), ("V", C.c_void_p), ("a", C.c_void_p), ("W0", C.c_void_p)]
+                ("order", C.c_int32), ("V", C.c_void_p), ("a", C.c_void_p), ("W0", C.c_void_p),
+                ("dropout", C.c_float), ("drop_seed", C.c_uint64), ("drop_step", C.c_uint64)]
 
 
 class _LayerGrad(C.Structure):
@@ -183,6 +184,8 @@ def _layers(layers: Sequence[dict]):
         arr[i].act = int(l["act"])
         arr[i].order = int(l.get("order", ORDER_PROJECT_FIRST))
         arr[i].V, arr[i].a, arr[i].W0 = V.data_ptr(), a.data_ptr(), W0.data_ptr()
+        arr[i].dropout = float(l.get("dropout", 0.0))
+        arr[i].drop_seed, arr[i].drop_step = int(l.get("drop_seed", 0)), int(l.get("drop_step", 0))
     return arr
 
 
@@ -281,7 +284,7 @@ def profile_collect() -> dict:
     return {arr[i].name.decode(): (float(arr[i].total_ms), int(arr[i].calls)) for i in range(n.value)}
 
 
-WS_P, WS_H, WS_G, WS_DP, WS_DH, WS_Z, WS_Y, WS_U = 0, 1, 2, 3, 4, 5, 6, 7
+WS_P, WS_H, WS_G, WS_DP, WS_DH, WS_Z, WS_Y, WS_U, WS_HD = 0, 1, 2, 3, 4, 5, 6, 7, 8
 
 
 def workspace_slice(part: Partition, layers: Sequence[dict], which: int, layer: int,

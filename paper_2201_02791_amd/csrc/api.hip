@@ -78,6 +78,7 @@ struct WsLayout {
     // orientations; U / dZ [S][max(d_in, d_out)] (shared)
     std::vector<size_t> off_Wrel, off_Wrb, off_WrbT;
     size_t off_U = 0;
+    std::vector<size_t> off_Hd;         // layers with dropout: the input as the layer reads it, fp32 [N][d_in]
     size_t off_self = 0, off_G = 0, off_dP = 0, off_dHa = 0, off_dHb = 0, off_seg = 0, off_part = 0, total = 0;
 };
 
@@ -98,6 +99,7 @@ int check_layers(const kge_partition *p, const kge_layer *layers, int32_t n_laye
         KGE_REQUIRE(L.d_out <= dmax && L.d_in <= 512, KGE_EINVAL,
                     "layer %d: d_out must be at most %d and d_in at most 512", l, dmax);
         KGE_REQUIRE(L.act == KGE_ACT_IDENTITY || L.act == KGE_ACT_RELU, KGE_EINVAL, "layer %d: bad act", l);
+        KGE_REQUIRE(L.dropout >= 0.0f && L.dropout < 1.0f, KGE_EINVAL, "layer %d: dropout must be in [0, 1)", l);
         KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.order == KGE_ORDER_AGGREGATE_FIRST ||
                         L.order == KGE_ORDER_RELATION_WEIGHTS, KGE_EINVAL, "layer %d: bad order", l);
         KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.d_in <= dmax, KGE_EINVAL,
@@ -122,6 +124,7 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
     size_t max_u = 0;
     size_t max_y = 0, max_c = 0, max_zd = 0;
     w->off_Hbf.assign(n_layers, 0); w->off_Wbf.assign(n_layers, 0); w->off_WbfT.assign(n_layers, 0);
+    w->off_Hd.assign(n_layers, 0);
     for (int l = 0; l < n_layers; ++l) {
         const kge_layer &L = layers[l];
         const bool agg = L.order == KGE_ORDER_AGGREGATE_FIRST;
@@ -152,6 +155,7 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
             w->off_P[l] = cur; cur = align_up(cur + N * L.n_bases * L.d_out * ep, 256);
         }
         w->off_H[l] = cur; cur = align_up(cur + N * L.d_out * 4, 256);
+        if (L.dropout > 0.0f) { w->off_Hd[l] = cur; cur = align_up(cur + N * L.d_in * 4, 256); }
         if ((size_t)L.d_out > max_dout) max_dout = L.d_out;
         if ((size_t)L.d_in > max_din) max_din = L.d_in;
         if ((size_t)L.n_bases * L.d_out > max_bd) max_bd = (size_t)L.n_bases * L.d_out;
@@ -236,6 +240,9 @@ extern "C" int kge_workspace_slice(const kge_partition *p, const kge_layer *laye
         *bytes = msg_dtype == KGE_MSG_BF16 ? N * (size_t)(L.n_bases + 1) * L.d_in * 2 : N * (size_t)L.n_bases * L.d_in * 4;
         break;
     case KGE_WS_H: *offset = w.off_H[layer]; *bytes = N * L.d_out * 4; break;
+    case KGE_WS_HD:
+        KGE_REQUIRE(L.dropout > 0.0f, KGE_EINVAL, "layer %d has no dropout", layer);
+        *offset = w.off_Hd[layer]; *bytes = N * L.d_in * 4; break;
     case KGE_WS_G: *offset = w.off_G; *bytes = N * L.d_out * 4; break;
     case KGE_WS_DP:
         *offset = w.off_dP;
@@ -270,6 +277,12 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
         const kge_layer &L = layers[l];
         void *P = ws + w.off_P[l];
         float *Hl = (float *)(ws + w.off_H[l]);
+        if (L.dropout > 0.0f) {      // everything below reads the dropped copy; backward regenerates the mask
+            float *Hd = (float *)(ws + w.off_Hd[l]);
+            rc = launch_dropout(Hin, p->n_vert, L.d_in, L.dropout, L.drop_seed, L.drop_step, l, Hd, st);
+            if (rc != KGE_OK) return rc;
+            Hin = Hd;
+        }
         if (L.order == KGE_ORDER_RELATION_WEIGHTS) {
             void *Z = ws + w.off_Z[l], *U = ws + w.off_U;
             float *Wrel = (float *)(ws + w.off_Wrel[l]);
@@ -385,7 +398,8 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
         const kge_layer &L = layers[l];
         const void *P = ws + w.off_P[l];
         const float *Hl = (const float *)(ws + w.off_H[l]);
-        const float *Hprev = l > 0 ? (const float *)(ws + w.off_H[l - 1]) : H0;
+        const float *Hprev = L.dropout > 0.0f ? (const float *)(ws + w.off_Hd[l])
+                                              : l > 0 ? (const float *)(ws + w.off_H[l - 1]) : H0;
         const float *Gl = gin;
         if (L.act != KGE_ACT_IDENTITY) {
             rc = launch_act_backward(gin, Hl, L.act, p->n_vert * (int64_t)L.d_out, G, st);
@@ -433,6 +447,10 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
                 if (rc != KGE_OK) return rc;
                 rc = launch_sum_edges_out(p, dZ, bf, L.d_in, Self, dst, part, l > 0 ? kge_cgraph_layer(cg, l - 1) : nullptr, st);
                 if (rc != KGE_OK) return rc;
+                if (L.dropout > 0.0f) {
+                    rc = launch_dropout(dst, p->n_vert, L.d_in, L.dropout, L.drop_seed, L.drop_step, l, dst, st);
+                    if (rc != KGE_OK) return rc;
+                }
                 gin = dst;
             }
             continue;
@@ -470,6 +488,10 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
             if (bf) rc = launch_input_grad_bf16(dP, p->n_vert, L.d_in, L.d_out, L.n_bases, ws + w.off_Wbf[l], dst, st);
             else rc = launch_input_grad((const float *)dP, Gl, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, dst, st);
             if (rc != KGE_OK) return rc;
+            if (L.dropout > 0.0f) {      // chain rule through out = mask * h / (1 - p): the same mask and scale
+                rc = launch_dropout(dst, p->n_vert, L.d_in, L.dropout, L.drop_seed, L.drop_step, l, dst, st);
+                if (rc != KGE_OK) return rc;
+            }
             gin = dst;
         }
     }

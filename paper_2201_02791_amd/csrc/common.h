@@ -212,3 +212,8 @@ int launch_distmult(const kge_partition *p, const float *H, const float *M, int3
                     const uint8_t *neg_side, int32_t n_neg, float *scores, float *loss, float *dH,
                     float *dM, hipStream_t st);
 int launch_fill_zero(void *ptr, size_t bytes, hipStream_t st);
+
+// dst = dropout(src) on [n_rows][d] floats (d a multiple of 4), inverted scaling, Philox mask keyed by
+// (seed, step, layer, row, column); src == dst is allowed.  p == 0 copies.
+int launch_dropout(const float *src, int64_t n_rows, int32_t d, float p, uint64_t seed, uint64_t step, int32_t layer,
+                   float *dst, hipStream_t st);

@@ -16,7 +16,8 @@ from . import binding as kb
 class TrainStep:
     def __init__(self, part: kb.Partition, params: Dict[str, object], acts: Sequence[int],
                  msg_dtype: int = kb.MSG_F32, need_dH0: bool = True, device: str = "cuda:0",
-                 keep_scores: bool = True, cone: bool = False, order: int = kb.ORDER_PROJECT_FIRST):
+                 keep_scores: bool = True, cone: bool = False, order: int = kb.ORDER_PROJECT_FIRST,
+                 dropout: float = 0.0):
         import torch
         self.torch = torch
         self.part = part
@@ -25,7 +26,8 @@ class TrainStep:
         t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(self.dev)
         self.layers: List[dict] = []
         for V, a, W0, act in zip(params["V"], params["a"], params["W0"], acts):
-            self.layers.append(dict(V=t(V), a=t(a), W0=t(W0), act=int(act), order=int(order)))
+            self.layers.append(dict(V=t(V), a=t(a), W0=t(W0), act=int(act), order=int(order),
+                                    dropout=float(dropout), drop_seed=0, drop_step=0))
         self.M = t(params["M"])
         self.H0 = t(params["H0"])
         N = part.n_vert
@@ -89,7 +91,14 @@ class TrainStep:
         kb.rgcn_backward(self.part, self.layers, self.H0, self.workspace, self.dH_out, self.grads,
                          self.dH0, self.msg_dtype, stream, self.cg)
 
+    def set_dropout_state(self, seed: int, step: int):
+        """Seed and step of the dropout masks (Sec. 4 training setting); forward and backward of one
+        step must see the same pair."""
+        for lay in self.layers:
+            lay["drop_seed"], lay["drop_step"] = int(seed), int(step)
+
     def run(self, mode: int, seed: int, step: int, stream=None):
+        self.set_dropout_state(seed, step)
         self.sample(mode, seed, step, stream)
         self.compute_graph(stream)
         self.forward(stream)

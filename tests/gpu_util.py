@@ -21,7 +21,7 @@ def layers_of(params, acts):
             for l in range(len(acts))]
 
 
-def gpu_step(spec, head, rel, tail, params=None, pos=None, need_dH0=True, cone=False, order=0):
+def gpu_step(spec, head, rel, tail, params=None, pos=None, need_dH0=True, cone=False, order=0, dropout=0.0):
     """Build the partition and run one step on the GPU. Returns (part, step object, params, pos)."""
     from paper_2201_02791_amd import binding as kb
     from paper_2201_02791_amd.step import TrainStep
@@ -33,20 +33,21 @@ def gpu_step(spec, head, rel, tail, params=None, pos=None, need_dH0=True, cone=F
     if pos is None:
         pos = synth.make_batch(spec, part.n_core)
     msg = kb.MSG_BF16 if spec.msg_dtype == "bf16" else kb.MSG_F32
-    ts = TrainStep(part, params, spec.acts, msg, need_dH0=need_dH0, cone=cone, order=order)
+    ts = TrainStep(part, params, spec.acts, msg, need_dH0=need_dH0, cone=cone, order=order, dropout=dropout)
     ts.set_batch(pos, spec.n_neg)
     ts.run(spec.neg_mode, SEED, STEP)
     torch.cuda.synchronize()
     return part, ts, params, pos
 
 
-def oracle_step(orc, spec, head, rel, tail, params, pos, need_dH0=True, msg_bf16=None):
+def oracle_step(orc, spec, head, rel, tail, params, pos, need_dH0=True, msg_bf16=None, dropout=0.0):
     """msg_bf16 None: the oracle stores messages the way the workload says (bf16 or exact)."""
     part = orc.build_partition(head, rel, tail, spec.n_entities, spec.n_relations, spec.n_parts,
                                spec.part_id, spec.n_hops, spec.neg_domain)
     res = orc.train_step(part, layers_of(params, spec.acts), params["H0"], params["M"], pos,
                          spec.n_neg, spec.neg_mode, SEED, STEP, need_dH0,
-                         msg_bf16=(spec.msg_dtype == "bf16") if msg_bf16 is None else msg_bf16)
+                         msg_bf16=(spec.msg_dtype == "bf16") if msg_bf16 is None else msg_bf16,
+                         dropout=float(np.float32(dropout)))      # the rate as the library's float field holds it
     return part, res
 
 
@@ -122,6 +123,7 @@ def align_mask_decisions(orc, ts, opart, res, params, acts, need_dH0, msg_bf16, 
         pres[l][flip] = np.where(hg[flip] > 0, tiny, -tiny)
     if n_flip == 0:
         return 0, res
-    grads, dH0 = orc.rgcn_backward(opart, layers_of(params, acts), res["Hs"], pres, res["dH_out"], need_dH0, msg_bf16)
+    grads, dH0 = orc.rgcn_backward(opart, layers_of(params, acts), res["Hs"], pres, res["dH_out"], need_dH0, msg_bf16,
+                                   res.get("drop"), res.get("masks"))
     out = dict(res); out["grads"] = grads; out["dH0"] = dH0
     return n_flip, out

@@ -40,7 +40,8 @@ def test_library_exports_every_declared_symbol(kb):
 
 
 def test_struct_layouts_match_the_header(kb):
-    assert C.sizeof(kb._Layer) == 5 * 4 + 4 + 3 * 8        # five int32, padding, three pointers
+    # five int32, padding, three pointers, the dropout rate, padding, its seed and step
+    assert C.sizeof(kb._Layer) == 5 * 4 + 4 + 3 * 8 + 4 + 4 + 2 * 8
     assert C.sizeof(kb._LayerGrad) == 3 * 8
     assert C.sizeof(kb._PartInfo) == 6 * 8 + 8 * 4
 

@@ -56,7 +56,7 @@ def pick_rows(rng, deg, edge_budget, n_max, allowed=None):
     return np.array(sorted(set(rows)), np.int64)
 
 
-def run_full_size(kb, orc, cfg, order="project"):
+def run_full_size(kb, orc, cfg, order="project", dropout=0.0):
     agg = order != "project"          # both orders that sum first run on the sub-graph here
     relw = order == "relation"
     import torch
@@ -81,11 +81,12 @@ def run_full_size(kb, orc, cfg, order="project"):
     need_dH0 = not spec.fixed_features
     ts = TrainStep(gp, params, spec.acts, kb.MSG_BF16 if bf else kb.MSG_F32, need_dH0=need_dH0, cone=agg,
                    order={"project": kb.ORDER_PROJECT_FIRST, "aggregate": kb.ORDER_AGGREGATE_FIRST,
-                          "relation": kb.ORDER_RELATION_WEIGHTS}[order])
+                          "relation": kb.ORDER_RELATION_WEIGHTS}[order], dropout=dropout)
     mode = {"project": 1, "aggregate": 2, "relation": 3}[order] if bf else 0     # the oracle's rounding points
     ts.set_batch(pos, spec.n_neg)
     u_check = None
     if relw:       # the per-run products of the last layer share their buffer with dz: look after forward only
+        ts.set_dropout_state(SEED, STEP)
         ts.sample(spec.neg_mode, SEED, STEP); ts.compute_graph(); ts.forward()
         torch.cuda.synchronize()
         lens_all = np.diff(op["seg_ptr"])
@@ -102,6 +103,24 @@ def run_full_size(kb, orc, cfg, order="project"):
     L = [dict(V=params["V"][l], a=params["a"][l], W0=params["W0"][l], act=spec.acts[l]) for l in range(2)]
     H0 = params["H0"]
     H1 = c(ts.view(kb.WS_H, 0)); Hout = c(ts.H_out)
+    # what each layer read: its input, or with dropout the dropped copy - every element of it against the
+    # oracle's mask (bit-exact zero pattern) and scaling, from the GPU's own layer outputs
+    Hin0, Hin1, keep0, keep1, inv_keep = H0, H1, None, None, 1.0
+    if dropout > 0:
+        pf = float(np.float32(dropout))
+        inv_keep = 1.0 / (1.0 - pf)
+        Hin0, Hin1 = c(ts.view(kb.WS_HD, 0)), c(ts.view(kb.WS_HD, 1))
+        for l, (src, got) in enumerate(((H0, Hin0), (H1, Hin1))):
+            want, keep = orc.dropout(src, pf, SEED, STEP, l)
+            np.testing.assert_array_equal(got != 0, (keep > 0) & (np.asarray(src) != 0))
+            assert rel_err(got, want) <= 1e-6
+            assert abs(keep.mean() - (1 - pf)) < 5 * np.sqrt(pf * (1 - pf) / keep.size)
+            if l == 0:
+                keep0 = keep
+            else:
+                keep1 = keep
+            del want
+        say("dropout masks checked (%.0f s)" % (time.time() - t0))
     ev = sampled.EdgeView(op)
     rng = np.random.default_rng(123)
     deg_in = np.diff(gp.export("dm_ptr")); deg_out = np.diff(gp.export("sm_ptr"))
@@ -130,15 +149,15 @@ def run_full_size(kb, orc, cfg, order="project"):
     rows2 = pick_rows(rng, deg_in, budget, 300, None if active is None else active[1])
     say("forward rows:", len(rows1), len(rows2), "edges:", int(deg_in[rows1].sum()), int(deg_in[rows2].sum()),
         "max deg:", int(deg_in[rows1].max()), int(deg_in[rows2].max()))
-    _, want1 = orc.layer_rows(op, rows1, L[0]["V"], L[0]["a"], L[0]["W0"], L[0]["act"], H0, msg_bf16=mode)
+    _, want1 = orc.layer_rows(op, rows1, L[0]["V"], L[0]["a"], L[0]["W0"], L[0]["act"], Hin0, msg_bf16=mode)
     errs["H1 rows"] = (rel_err(H1[rows1], want1), tol_v)
-    _, want2 = orc.layer_rows(op, rows2, L[1]["V"], L[1]["a"], L[1]["W0"], L[1]["act"], H1, msg_bf16=mode)
+    _, want2 = orc.layer_rows(op, rows2, L[1]["V"], L[1]["a"], L[1]["W0"], L[1]["act"], Hin1, msg_bf16=mode)
     errs["H_out rows"] = (rel_err(Hout[rows2], want2), tol_v)
     if agg:
         # run means of both layers on sampled runs into active destinations, and the per-basis sums
         # of the last layer (the y buffer is shared) on its sampled rows, from the GPU's own z
         run_len = np.diff(op["seg_ptr"])
-        for l, Hin in ((0, H0), (1, H1)):
+        for l, Hin in ((0, Hin0), (1, Hin1)):
             ok = active[l][op["seg_dst"]] & (run_len <= 2000)
             runs = rng.permutation(np.nonzero(ok)[0])[:400]
             runs = np.concatenate([runs, np.nonzero(ok & (run_len >= 256))[0][:2]]).astype(np.int64)
@@ -161,9 +180,9 @@ def run_full_size(kb, orc, cfg, order="project"):
     else:
         trows = torch.from_numpy(rows1).to(ts.dev)
         P1 = c(ts.view(kb.WS_P, 0)[trows]).reshape(len(rows1), B, d)
-        errs["P1 rows"] = (rel_err(P1, sampled.project_rows(H0[rows1], L[0]["V"])), tol_v)
+        errs["P1 rows"] = (rel_err(P1, sampled.project_rows(Hin0[rows1], L[0]["V"])), tol_v)
         P2 = c(ts.view(kb.WS_P, 1)[trows]).reshape(len(rows1), B, d)
-        errs["P2 rows"] = (rel_err(P2, sampled.project_rows(H1[rows1], L[1]["V"])), tol_v)
+        errs["P2 rows"] = (rel_err(P2, sampled.project_rows(Hin1[rows1], L[1]["V"])), tol_v)
     say("forward checked (%.0f s)" % (time.time() - t0), errs)
 
     # ---- scoring: everything
@@ -182,6 +201,8 @@ def run_full_size(kb, orc, cfg, order="project"):
     # layer 2 input gradient (dH_1) by definition from G2, and the activation backward
     dP2 = sampled.transposed_rows(ev, srows, L[1]["a"], G2)
     want = sampled.input_grad_rows(dP2, G2[srows], L[1]["V"], L[1]["W0"])
+    if dropout > 0:        # chain rule through the dropped copy: the same mask and scale
+        want = want * keep1[srows] * inv_keep
     dH1 = c(ts.view(kb.WS_DH, 1)[tsrows])
     errs["dH_1 rows"] = (rel_err(dH1, want), tol_g)
     G1 = c(ts.view(kb.WS_G, 0))
@@ -201,19 +222,22 @@ def run_full_size(kb, orc, cfg, order="project"):
         dP1 = c(X1[tsrows])[:, :B * d].reshape(len(srows), B, d)
         errs["dP_1 rows"] = (rel_err(dP1, dP1w), tol_g)
     if need_dH0:
-        errs["dH0 rows"] = (rel_err(c(ts.dH0[tsrows]), sampled.input_grad_rows(dP1, G1[srows], L[0]["V"], L[0]["W0"])), tol_g)
+        want = sampled.input_grad_rows(dP1, G1[srows], L[0]["V"], L[0]["W0"])
+        if dropout > 0:
+            want = want * keep0[srows] * inv_keep
+        errs["dH0 rows"] = (rel_err(c(ts.dH0[tsrows]), want), tol_g)
     # self-loop weight gradients, whole
-    errs["dW0_2"] = (rel_err(c(ts.grads[1]["dW0"]), sampled.self_weight_grad(H1, G2)), tol_g)
-    errs["dW0_1"] = (rel_err(c(ts.grads[0]["dW0"]), sampled.self_weight_grad(H0, G1)), tol_g)
+    errs["dW0_2"] = (rel_err(c(ts.grads[1]["dW0"]), sampled.self_weight_grad(Hin1, G2)), tol_g)
+    errs["dW0_1"] = (rel_err(c(ts.grads[0]["dW0"]), sampled.self_weight_grad(Hin0, G1)), tol_g)
     # basis gradients of layer 1: sampled columns
     dV1 = c(ts.grads[0]["dV"])
     for (b, col) in [(0, 0), (B - 1, d - 1), (B // 2, d // 3)]:
         colv = sampled.transposed_column(ev, L[0]["a"], b, G1[:, col])        # dP_1[:, b, col] by definition
-        want = sampled.basis_weight_grad_column(H0, colv)
+        want = sampled.basis_weight_grad_column(Hin0, colv)
         errs["dV_1[%d][:,%d]" % (b, col)] = (float(np.abs(dV1[b][:, col] - want).max() / np.abs(dV1[b]).max()), tol_g)
     # Euler identity for both layers: sum a*da = sum V*dV = sum <pre - h W0, G>
     tol_q = 5e-2 if bf else 2e-3
-    for l, (pre, Hin, G) in enumerate([(H1, H0, G1), (Hout, H1, G2)]):
+    for l, (pre, Hin, G) in enumerate([(H1, Hin0, G1), (Hout, Hin1, G2)]):
         q = sampled.euler_quantity(pre, Hin, L[l]["W0"], G)
         qa = float(np.sum(L[l]["a"].astype(np.float64) * c(ts.grads[l]["da"])))
         qv = float(np.sum(L[l]["V"].astype(np.float64) * c(ts.grads[l]["dV"])))
@@ -284,3 +308,8 @@ def test_config4_full_size(kb, orc):
     """Partition 0 of 4 of the 1 M-entity / 20 M-triple / 1,000-relation graph, d = 256, 64 bases,
     bf16 messages (the oracle stores messages the way the workload says)."""
     run_full_size(kb, orc, 4)
+
+
+def test_config4_full_size_relation_weights_subgraph_dropout(kb, orc):
+    """The benchmark's launch configuration with the large-graph setting's dropout of 0.2."""
+    run_full_size(kb, orc, 4, order="relation", dropout=0.2)
