@@ -295,6 +295,58 @@ int kge_optimizer_step_rows(const kge_opt *opt, float *param, const float *grad,
                             int64_t n_rows, int32_t d, const uint8_t *row_mask, void *stream);
 
 /*
+ * Link-prediction evaluation ("Evaluation Metrics" section: filtered setting, MRR Eq. 5, Hits@k Eq. 6).
+ *
+ * A query fixes one entity and a relation and asks for the other entity of a test triple (h, r, t):
+ * the tail query fixes h (answer t), the head query fixes t (answer h).  DistMult (Eq. 4) is symmetric
+ * in its entities, so a candidate e scores  sum_k H[fixed][k] M[r][k] H[e][k]  in both directions.
+ * Candidates are all entities except the answer; with a filter, also except every entity whose triple
+ * with the query's (fixed entity, relation) is among the filter's known triples.  Per query the calls
+ * return `higher` = candidates scoring strictly above the answer and `equal` = candidates scoring
+ * exactly the same (fp32 scores); the answer's rank in the list sorted by descending score is
+ * 1 + higher with ties placed first, 1 + higher + equal with ties placed last.  kge_eval_metrics uses
+ * rank = 1 + higher + equal / 2 (the mean position over all orders of the ties; the paper leaves the
+ * order of equal scores open).
+ *
+ * kge_eval_filter_create: head, rel, tail are HOST int32 [n_known] (the triples whose corruptions are
+ *   dropped: the training triples in the paper's setting); ids must be in range (KGE_ERANGE).  Sorts
+ *   and de-duplicates on the host and keeps two device tables.  Synchronous; free with _destroy.
+ * kge_eval_rank_all: H DEVICE float [n_entities][d] (d a multiple of 4, <= 1024, 16-byte aligned),
+ *   M DEVICE float [n_relations][d], test_h/r/t DEVICE int32 [n_test]; filter may be NULL (raw setting)
+ *   and must have been built for the same n_entities / n_relations.  higher, equal: DEVICE int32
+ *   [2 n_test], tail queries first, then head queries.  workspace: DEVICE, 256-byte aligned, at least
+ *   kge_eval_workspace_bytes(2 n_test, d) bytes.  Scores are an (2 n_test x d) by (d x n_entities)
+ *   product on the fp32 matrix cores that is compared and counted tile by tile, never stored.
+ * kge_eval_rank_candidates: every query brings its own list cand[q][0..n_cand) (DEVICE int32; the
+ *   setting of the large citation graph, which ships a fixed number of negative targets per test edge);
+ *   fixed, rel, answer: DEVICE int32 [n_queries]; an entry equal to the answer is skipped.
+ * kge_eval_metrics: out DEVICE double [1 + n_ks] = MRR, Hits@ks[0], ..; ks HOST int32 [n_ks], n_ks <= 8.
+ * All three are asynchronous on `stream`, allocate nothing, and return KGE_EINVAL on bad arguments;
+ * entity / relation ids inside the device arrays are the caller's responsibility.
+ */
+typedef struct kge_eval_filter kge_eval_filter;
+int kge_eval_filter_create(const int32_t *head, const int32_t *rel, const int32_t *tail, int64_t n_known,
+                           int32_t n_entities, int32_t n_relations, kge_eval_filter **out);
+void kge_eval_filter_destroy(kge_eval_filter *f);
+size_t kge_eval_workspace_bytes(int64_t n_queries, int32_t d);
+int kge_eval_rank_all(const kge_eval_filter *filter, const float *H, int64_t n_entities, int32_t d,
+                      const float *M, int32_t n_relations, const int32_t *test_h, const int32_t *test_r,
+                      const int32_t *test_t, int64_t n_test, void *workspace, size_t ws_bytes,
+                      int32_t *higher, int32_t *equal, void *stream);
+int kge_eval_rank_candidates(const float *H, int64_t n_entities, int32_t d, const float *M,
+                             int32_t n_relations, const int32_t *fixed, const int32_t *rel,
+                             const int32_t *answer, int64_t n_queries, const int32_t *cand, int32_t n_cand,
+                             void *workspace, size_t ws_bytes, int32_t *higher, int32_t *equal, void *stream);
+int kge_eval_metrics(const int32_t *higher, const int32_t *equal, int64_t n_queries, const int32_t *ks,
+                     int32_t n_ks, double *out, void *stream);
+/* Test hook: the fp32 scores kge_eval_rank_all compares, written out: scores DEVICE float
+ * [2 n_test][n_entities] from the tile kernel, answer_score DEVICE float [2 n_test] from the per-query
+ * kernel (the two kernels must agree bit for bit on the same pair).  Small inputs only. */
+int kge_eval_debug_scores(const float *H, int64_t n_entities, int32_t d, const float *M, int32_t n_relations,
+                          const int32_t *test_h, const int32_t *test_r, const int32_t *test_t, int64_t n_test,
+                          void *workspace, size_t ws_bytes, float *scores, float *answer_score, void *stream);
+
+/*
  * Per-kernel timing for benchmarks (not part of the training path).  While enabled, every
  * kernel launch of the per-step calls is bracketed by two HIP events recorded on the launch
  * stream.  kge_profile_collect waits for the recorded events, sums the elapsed time per

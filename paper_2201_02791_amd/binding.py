@@ -21,7 +21,9 @@ EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_rgcn_backward", "kge_sample_negatives", "kge_distmult_score_loss",
             "kge_profile_enable", "kge_profile_collect", "kge_last_error", "kge_cgraph_create",
             "kge_cgraph_destroy", "kge_compute_graph", "kge_cgraph_export", "kge_optimizer_step",
-            "kge_optimizer_step_rows"]
+            "kge_optimizer_step_rows", "kge_eval_filter_create", "kge_eval_filter_destroy",
+            "kge_eval_workspace_bytes", "kge_eval_rank_all", "kge_eval_rank_candidates", "kge_eval_metrics",
+            "kge_eval_debug_scores"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
 ORDER_PROJECT_FIRST, ORDER_AGGREGATE_FIRST, ORDER_RELATION_WEIGHTS = 0, 1, 2
@@ -89,6 +91,8 @@ def load():
         lib.kge_workspace_bytes.restype = C.c_size_t
         lib.kge_partition_destroy.restype = None
         lib.kge_cgraph_destroy.restype = None
+        lib.kge_eval_filter_destroy.restype = None
+        lib.kge_eval_workspace_bytes.restype = C.c_size_t
         _lib = lib
     return _lib
 
@@ -307,3 +311,103 @@ def optimizer_step(kind: int, param, grad, m=None, v=None, lr=0.01, beta1=0.9, b
     else:
         _check(load().kge_optimizer_step(C.byref(o), _ptr(param), _ptr(grad), _ptr(m), _ptr(v),
                                          C.c_int64(param.numel()), _stream(stream)))
+
+
+# ---- link-prediction evaluation (filtered ranks, MRR, Hits@k) ----------------------------------
+
+class EvalFilter:
+    """Owner of a ``kge_eval_filter*``: the known triples whose corruptions the filtered setting drops."""
+
+    def __init__(self, head, rel, tail, n_entities: int, n_relations: int):
+        head = np.ascontiguousarray(head, np.int32)
+        rel = np.ascontiguousarray(rel, np.int32)
+        tail = np.ascontiguousarray(tail, np.int32)
+        assert len(head) == len(rel) == len(tail)
+        out = C.c_void_p()
+        _check(load().kge_eval_filter_create(head.ctypes.data_as(C.c_void_p), rel.ctypes.data_as(C.c_void_p),
+                                             tail.ctypes.data_as(C.c_void_p), C.c_int64(len(head)),
+                                             C.c_int32(n_entities), C.c_int32(n_relations), C.byref(out)))
+        self._h = C.c_void_p(out.value)
+
+    @property
+    def handle(self):
+        return self._h
+
+    def destroy(self):
+        if self._h is not None and self._h.value:
+            load().kge_eval_filter_destroy(self._h)
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def eval_workspace_bytes(n_queries: int, d: int) -> int:
+    n = load().kge_eval_workspace_bytes(C.c_int64(n_queries), C.c_int32(d))
+    if n == 0:
+        raise KgeError(-1, load().kge_last_error().decode())
+    return int(n)
+
+
+def _eval_ws(n_queries, d, device, workspace):
+    import torch
+    need = eval_workspace_bytes(n_queries, d)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace
+
+
+def eval_rank_all(H, M, test_h, test_r, test_t, filt: EvalFilter = None, workspace=None, stream=None):
+    """(higher, equal) int32 [2 n_test] on the device: tail queries of all test triples, then head queries."""
+    import torch
+    n_test = test_h.numel()
+    ws = _eval_ws(2 * n_test, H.shape[1], H.device, workspace)
+    higher = torch.empty(2 * n_test, dtype=torch.int32, device=H.device)
+    equal = torch.empty_like(higher)
+    _check(load().kge_eval_rank_all(filt.handle if filt is not None else C.c_void_p(0), _ptr(H), C.c_int64(H.shape[0]),
+                                    C.c_int32(H.shape[1]), _ptr(M), C.c_int32(M.shape[0]), _ptr(test_h), _ptr(test_r),
+                                    _ptr(test_t), C.c_int64(n_test), _ptr(ws), C.c_size_t(ws.numel()), _ptr(higher),
+                                    _ptr(equal), _stream(stream)))
+    return higher, equal
+
+
+def eval_rank_candidates(H, M, fixed, rel, answer, cand, workspace=None, stream=None):
+    """(higher, equal) int32 [n_queries] against each query's own candidate list cand [n_queries, n_cand]."""
+    import torch
+    nq = fixed.numel()
+    ws = _eval_ws(nq, H.shape[1], H.device, workspace)
+    higher = torch.empty(nq, dtype=torch.int32, device=H.device)
+    equal = torch.empty_like(higher)
+    _check(load().kge_eval_rank_candidates(_ptr(H), C.c_int64(H.shape[0]), C.c_int32(H.shape[1]), _ptr(M),
+                                           C.c_int32(M.shape[0]), _ptr(fixed), _ptr(rel), _ptr(answer), C.c_int64(nq),
+                                           _ptr(cand), C.c_int32(cand.shape[1] if cand.dim() == 2 else 0), _ptr(ws),
+                                           C.c_size_t(ws.numel()), _ptr(higher), _ptr(equal), _stream(stream)))
+    return higher, equal
+
+
+def eval_metrics(higher, equal, ks=(1, 3, 10), stream=None):
+    """Device tensor of doubles: MRR, then Hits@k for each k."""
+    import torch
+    out = torch.empty(1 + len(ks), dtype=torch.float64, device=higher.device)
+    karr = (C.c_int32 * max(len(ks), 1))(*ks)
+    _check(load().kge_eval_metrics(_ptr(higher), _ptr(equal), C.c_int64(higher.numel()), karr, C.c_int32(len(ks)),
+                                   _ptr(out), _stream(stream)))
+    return out
+
+
+def eval_debug_scores(H, M, test_h, test_r, test_t, stream=None):
+    """Test hook: (scores [2 n_test, n_entities] from the tile kernel, answer scores [2 n_test] from the
+    per-query kernel)."""
+    import torch
+    n_test = test_h.numel()
+    ws = _eval_ws(2 * n_test, H.shape[1], H.device, None)
+    scores = torch.empty((2 * n_test, H.shape[0]), dtype=torch.float32, device=H.device)
+    ans = torch.empty(2 * n_test, dtype=torch.float32, device=H.device)
+    _check(load().kge_eval_debug_scores(_ptr(H), C.c_int64(H.shape[0]), C.c_int32(H.shape[1]), _ptr(M),
+                                        C.c_int32(M.shape[0]), _ptr(test_h), _ptr(test_r), _ptr(test_t),
+                                        C.c_int64(n_test), _ptr(ws), C.c_size_t(ws.numel()), _ptr(scores), _ptr(ans),
+                                        _stream(stream)))
+    return scores, ans
