@@ -138,6 +138,94 @@ def cpu_baseline(spec, cfg_index):
                                                                       small.n_bases, dt)}
 
 
+def run_eval(args):
+    """--eval: filtered link-prediction ranking ("Evaluation Metrics": MRR Eq. 5, Hits@k Eq. 6) instead of
+    the training step.  all: every test triple's two queries against every entity of the workload's graph,
+    known triples = the workload's training triples.  candidates: the large citation graph's setting, 1000
+    given candidates per query.  Embeddings are random (no trained weights exist here): the arithmetic and
+    the data movement are those of a trained model, the metric values are not."""
+    import numpy as np
+    import torch
+    from paper_2201_02791_amd import binding as kb, synth
+    kb.load()
+    assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU fallback)"
+    spec = synth.WORKLOADS[args.config]
+    log = lambda *a: print("[bench]", *a, file=sys.stderr, flush=True)
+    N, R, d = spec.n_entities, spec.n_relations, spec.d
+    rng = np.random.default_rng(spec.seed + 77)
+    n_test = args.eval_triples
+    H = torch.from_numpy(rng.normal(0, 0.5, (N, d)).astype(np.float32)).cuda()
+    M = torch.from_numpy(rng.normal(0, 1.0, (R, d)).astype(np.float32)).cuda()
+    head, rel, tail = synth.make_triples(spec)
+    pick = rng.permutation(len(head))[:n_test]       # test triples drawn like the graph's own
+    th, tr, tt = (torch.from_numpy(np.ascontiguousarray(x[pick])).cuda() for x in (head, rel, tail))
+    nq = 2 * n_test
+    if args.eval == "all":
+        t0 = time.time()
+        filt = kb.EvalFilter(head, rel, tail, N, R)
+        log("filter tables of %d known triples built in %.1f s (host sort, once per evaluation)" % (len(head), time.time() - t0))
+        ws = torch.empty(kb.eval_workspace_bytes(nq, d), dtype=torch.uint8, device="cuda")
+        step = lambda: kb.eval_rank_all(H, M, th, tr, tt, filt, ws)
+        work_name, flops = "eval_count", 2.0 * nq * N * d
+    else:
+        n_cand = 1000
+        fixed = torch.cat([th, tt]); rr = torch.cat([tr, tr]); ans = torch.cat([tt, th])
+        cand = torch.from_numpy(rng.integers(0, N, (nq, n_cand)).astype(np.int32)).cuda()
+        ws = torch.empty(kb.eval_workspace_bytes(nq, d), dtype=torch.uint8, device="cuda")
+        step = lambda: kb.eval_rank_candidates(H, M, fixed, rr, ans, cand, ws)
+        work_name, flops = "eval_cand", None
+    del head, rel, tail
+    for _ in range(args.warmup):
+        hi, eq = step()
+    torch.cuda.synchronize()
+    kb.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        hi, eq = step()
+        met = kb.eval_metrics(hi, eq, (1, 3, 10))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kb.profile_enable(False)
+    prof = kb.profile_collect()
+    for name, (tot, calls) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
+        log("%-13s %9.3f ms/step  %4.1f launches" % (name, tot / args.steps, calls / args.steps))
+    avg_ms = prof[work_name][0] / max(prof[work_name][1], 1)
+    if flops is not None:        # dense contraction on the fp32 matrix cores
+        roof = {"kernel": work_name, "bound": "mfma", "achieved": flops / (avg_ms * 1e-3) / 1e12,
+                "peak": PEAK_F32_MFMA_TFLOPS, "unit": "TFLOP/s", "traffic": None, "avg_launch_ms": avg_ms}
+    else:                        # gathers one entity row per (query, candidate)
+        nbytes = nq * (1000 + 1) * (d * 4.0 + 4.0)
+        roof = {"kernel": work_name, "bound": "hbm", "achieved": nbytes / (avg_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                "unit": "GB/s", "traffic": None, "avg_launch_ms": avg_ms}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    base = None
+    if not args.no_cpu_baseline:
+        from oracle import eval_oracle as evo
+        Hc, Mc = H.cpu().numpy(), M.cpu().numpy()
+        k = max(1, min(n_test, int(2e10 / (2.0 * N * d * 8))))      # about 10-30 s of fp64 matrix-vector products
+        t0 = time.perf_counter()
+        if args.eval == "all":
+            evo.filtered_counts(Hc, Mc, th[:k].cpu().numpy(), tr[:k].cpu().numpy(), tt[:k].cpu().numpy())
+        else:
+            evo.candidate_counts(Hc, Mc, fixed[:2 * k].cpu().numpy(), rr[:2 * k].cpu().numpy(), ans[:2 * k].cpu().numpy(),
+                                 cand[:2 * k].cpu().numpy())
+        dtc = time.perf_counter() - t0
+        base = {"value": 2 * k / dtc, "unit": "queries/s", "cores": 1, "kind": "oracle", "host_cores": os.cpu_count(),
+                "sample": "%d of the %d queries (raw setting), %.1f s" % (2 * k, nq, dtc)}
+    m = met.cpu().numpy()
+    out = {"metric": "link-prediction ranking queries/s (filtered, DistMult) on 1 GPU", "value": nq / (dt / args.steps),
+           "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "evaluation on configs[%d] %s" % (args.config, spec.name), "mode": args.eval,
+                      "entities": N, "relations": R, "d": d, "test_triples": n_test, "queries": nq,
+                      "known_triples": spec.n_triples if args.eval == "all" else 0,
+                      "candidates_per_query": N - 1 if args.eval == "all" else 1000},
+           "mrr_of_random_embeddings": float(m[0]), "hits_at_1_3_10": [float(x) for x in m[1:]],
+           "roofline": roof, "cpu_baseline": base}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -156,6 +244,9 @@ def main():
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout rate on every layer's input (the paper's large-graph setting uses 0.2); "
                          "default 0: the benchmark's workload is quoted without it")
+    ap.add_argument("--eval", choices=["all", "candidates"], default=None,
+                    help="time the link-prediction evaluation (filtered ranks, MRR, Hits@k) instead of the training step")
+    ap.add_argument("--eval-triples", type=int, default=10000, help="test triples of --eval (two queries each)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -163,6 +254,10 @@ def main():
         print("bench.py: this build runs on ONE GPU (one partition per GPU, no collectives); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+
+    if args.eval:
+        run_eval(args)
+        return
 
     import torch
     from paper_2201_02791_amd import binding as kb, synth

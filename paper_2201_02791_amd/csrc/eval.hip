@@ -91,15 +91,12 @@ struct FilterTables {
     const int64_t *key[2]; const int32_t *val[2]; int64_t n[2]; int64_t N; int32_t R;
 };
 
-// One wavefront per query: the answer's score, then the query's list (FILTER: the known answers of its
-// (fixed entity, relation); otherwise its candidate list) 32 entities at a time.  Counts the entries other
-// than the answer that score above / exactly at the answer.
-template <bool FILTER>
+// One wavefront per query: the answer's score, then the known answers of the query's (fixed entity,
+// relation) 32 entities at a time.  Counts those other than the answer that score above / exactly at it.
 __global__ __launch_bounds__(256) void k_eval_pairs(const float *__restrict__ Q, const float *__restrict__ H,
                                                     int32_t d, int64_t nq, int64_t n_test,
                                                     const int32_t *__restrict__ fixed, const int32_t *__restrict__ rel,
                                                     const int32_t *__restrict__ answer, FilterTables ft,
-                                                    const int32_t *__restrict__ cand, int32_t n_cand,
                                                     float *__restrict__ s_answer, int32_t *__restrict__ out_gt,
                                                     int32_t *__restrict__ out_eq)
 {
@@ -110,18 +107,11 @@ __global__ __launch_bounds__(256) void k_eval_pairs(const float *__restrict__ Q,
     const int32_t ans = answer[q];
     float st = pair_scores(qrow, H, (lane & 31) == 0 ? ans : -1, d, lane);
     st = __shfl(st, 0, 64);
-    const int32_t *list;
-    int64_t lo, hi;
-    if (FILTER) {
-        const int side = q >= n_test ? 1 : 0;
-        const int64_t base = ((int64_t)fixed[q] * ft.R + rel[q]) * ft.N;
-        lo = lower_bound_i64(ft.key[side], ft.n[side], base);
-        hi = lower_bound_i64(ft.key[side], ft.n[side], base + ft.N);
-        list = ft.val[side];
-    } else {
-        list = cand + q * n_cand;
-        lo = 0; hi = n_cand;
-    }
+    const int side = q >= n_test ? 1 : 0;
+    const int64_t base = ((int64_t)fixed[q] * ft.R + rel[q]) * ft.N;
+    const int64_t lo = lower_bound_i64(ft.key[side], ft.n[side], base);
+    const int64_t hi = lower_bound_i64(ft.key[side], ft.n[side], base + ft.N);
+    const int32_t *list = ft.val[side];
     int gt = 0, eq = 0;
     for (int64_t b = lo; b < hi; b += 32) {                 // bounds are the same in every lane
         const int64_t i = b + (lane & 31);
@@ -133,9 +123,72 @@ __global__ __launch_bounds__(256) void k_eval_pairs(const float *__restrict__ Q,
         eq += __popc((unsigned)me);
     }
     if (lane == 0) {
-        if (s_answer) s_answer[q] = st;
+        s_answer[q] = st;
         out_gt[q] = gt; out_eq[q] = eq;
     }
+}
+
+// Candidate lists: one wavefront per query, LPR lanes per entity row (LPR * 4 >= min(d, 256) columns at a
+// time), 64 / LPR rows side by side and UN such groups in flight.  A score is the row's fp32 dot product
+// with the query vector summed in a fixed order (per lane over its column pieces, then a butterfly over the
+// row's lanes), the answer's score included, so equal rows give equal scores.
+template <int LPR, int NP>
+__device__ __forceinline__ float row_dot(const float4 *__restrict__ hrow, const float4 (&q4)[NP], int32_t d4, int sub)
+{
+    float4 h[NP];
+#pragma unroll
+    for (int j = 0; j < NP; ++j) h[j] = sub + j * LPR < d4 ? hrow[sub + j * LPR] : make_float4(0.f, 0.f, 0.f, 0.f);
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+        s = fmaf(h[j].x, q4[j].x, s); s = fmaf(h[j].y, q4[j].y, s); s = fmaf(h[j].z, q4[j].z, s); s = fmaf(h[j].w, q4[j].w, s);
+    }
+    return s;
+}
+
+// NP: column pieces per lane, LPR * NP * 4 >= d
+template <int LPR, int NP>
+__global__ __launch_bounds__(256) void k_eval_candidates(const float4 *__restrict__ Q, const float4 *__restrict__ H,
+                                                         int32_t d4, int64_t nq, const int32_t *__restrict__ answer,
+                                                         const int32_t *__restrict__ cand, int32_t n_cand,
+                                                         int32_t *__restrict__ out_gt, int32_t *__restrict__ out_eq)
+{
+    constexpr int RPP = 64 / LPR, UN = NP > 2 ? 2 : 4;         // rows per pass, passes in flight
+    const int lane = threadIdx.x & 63, sub = lane % LPR, grp = lane / LPR;
+    const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (q >= nq) return;                                    // whole wavefronts leave
+    float4 q4[NP];
+#pragma unroll
+    for (int j = 0; j < NP; ++j) q4[j] = sub + j * LPR < d4 ? Q[q * d4 + sub + j * LPR] : make_float4(0.f, 0.f, 0.f, 0.f);
+    const int32_t ans = answer[q];
+    auto reduce = [&](float s) {
+#pragma unroll
+        for (int off = LPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        return s;
+    };
+    const float st = reduce(row_dot<LPR, NP>(H + (int64_t)ans * d4, q4, d4, sub));
+    const int32_t *list = cand + q * n_cand;
+    int gt = 0, eq = 0;
+    for (int32_t b = 0; b < n_cand; b += RPP * UN) {         // bounds are the same in every lane
+        int32_t e[UN];
+        float s[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int32_t i = b + u * RPP + grp;
+            e[u] = i < n_cand ? list[i] : -1;
+            if (e[u] == ans) e[u] = -1;
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) s[u] = row_dot<LPR, NP>(H + (int64_t)(e[u] < 0 ? 0 : e[u]) * d4, q4, d4, sub);
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const float r = reduce(s[u]);
+            if (sub == 0 && e[u] >= 0) { gt += r > st ? 1 : 0; eq += r == st ? 1 : 0; }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) { gt += __shfl_xor(gt, off, 64); eq += __shfl_xor(eq, off, 64); }
+    if (lane == 0) { out_gt[q] = gt; out_eq[q] = eq; }
 }
 
 // ---- all entities: 128 queries x 128 entities per tile, 4 wavefronts in a 2 x 2 grid, each with 2 x 2
@@ -390,8 +443,8 @@ int rank_all(const kge_eval_filter *f, const float *H, int64_t N, int32_t d, con
             ft.key[sde] = f ? f->key[sde] : nullptr; ft.val[sde] = f ? f->val[sde] : nullptr; ft.n[sde] = f ? f->n[sde] : 0;
         }
         ft.N = N; ft.R = R;
-        k_eval_pairs<true><<<(unsigned)cdiv(nq, 4), 256, 0, st>>>(Q, H, d, nq, n_test, fixed, rel, answer, ft, nullptr, 0,
-                                                                 dump_answer ? dump_answer : s, sub_gt, sub_eq);
+        k_eval_pairs<<<(unsigned)cdiv(nq, 4), 256, 0, st>>>(Q, H, d, nq, n_test, fixed, rel, answer, ft,
+                                                           dump_answer ? dump_answer : s, sub_gt, sub_eq);
         KGE_LAUNCH_CHECK();
     }
     {
@@ -507,10 +560,16 @@ extern "C" int kge_eval_rank_candidates(const float *H, int64_t n_entities, int3
                                                                              n_queries, d / 4, (float4 *)Q);
         KGE_LAUNCH_CHECK();
     }
-    KGE_PROF("eval_pairs", st);
-    FilterTables ft = {};
-    k_eval_pairs<false><<<(unsigned)cdiv(n_queries, 4), 256, 0, st>>>(Q, H, d, n_queries, n_queries, fixed, rel, answer, ft,
-                                                                     cand, n_cand, nullptr, higher, equal);
+    KGE_PROF("eval_cand", st);
+    const unsigned grid = (unsigned)cdiv(n_queries, 4);
+    const int32_t d4 = d / 4;
+    const float4 *Q4 = (const float4 *)Q, *H4 = (const float4 *)H;
+    if (d4 <= 8) k_eval_candidates<8, 1><<<grid, 256, 0, st>>>(Q4, H4, d4, n_queries, answer, cand, n_cand, higher, equal);
+    else if (d4 <= 16) k_eval_candidates<16, 1><<<grid, 256, 0, st>>>(Q4, H4, d4, n_queries, answer, cand, n_cand, higher, equal);
+    else if (d4 <= 32) k_eval_candidates<32, 1><<<grid, 256, 0, st>>>(Q4, H4, d4, n_queries, answer, cand, n_cand, higher, equal);
+    else if (d4 <= 64) k_eval_candidates<64, 1><<<grid, 256, 0, st>>>(Q4, H4, d4, n_queries, answer, cand, n_cand, higher, equal);
+    else if (d4 <= 128) k_eval_candidates<64, 2><<<grid, 256, 0, st>>>(Q4, H4, d4, n_queries, answer, cand, n_cand, higher, equal);
+    else k_eval_candidates<64, 4><<<grid, 256, 0, st>>>(Q4, H4, d4, n_queries, answer, cand, n_cand, higher, equal);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }

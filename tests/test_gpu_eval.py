@@ -142,12 +142,14 @@ def test_filtered_counts_on_real_embeddings(kb, n, R, d, n_test):
     assert abs(got[0] - mrr) <= 1e-3 * mrr
 
 
-@pytest.mark.parametrize("n_cand", [1000, 33, 1])
-def test_candidate_lists(kb, n_cand):
-    """The large citation graph's setting: every query ranks its answer against its own list."""
-    say("candidates", n_cand)
+@pytest.mark.parametrize("n_cand,d", [(1000, 128), (33, 128), (1, 128), (100, 8), (77, 48), (50, 200), (40, 400),
+                                      (19, 1024)])
+def test_candidate_lists(kb, n_cand, d):
+    """The large citation graph's setting: every query ranks its answer against its own list.  The widths
+    cover every lanes-per-row / pieces-per-lane form of the kernel."""
+    say("candidates", n_cand, d)
     import torch
-    n, R, d, nq = 4000, 1, 128, 300
+    n, R, nq = 4000, 1, 300
     rng = np.random.default_rng(21)
     fixed = rng.integers(0, n, nq).astype(np.int32); rel = np.zeros(nq, np.int32)
     answer = rng.integers(0, n, nq).astype(np.int32)
