@@ -196,46 +196,57 @@ __global__ __launch_bounds__(256) void k_eval_candidates(const float4 *__restric
 // consecutive entity tiles and keeps its counts in registers: one packed word per accumulator row
 // (low half: entries above the answer, high half: entries equal to it).
 constexpr int EBM = 128, EBN = 128, EBK = 16, EPAD = 4;
+constexpr int ETR = EBK / 4, ERP = 256 / ETR, ENP = EBM / ERP;      // threads per row piece, rows per pass, passes
 
 template <bool DUMP>
-__global__ __launch_bounds__(256) void k_eval_count(const float *__restrict__ Q, int64_t nq,
+__global__ __launch_bounds__(256, 2) void k_eval_count(const float *__restrict__ Q, int64_t nq,
                                                     const float *__restrict__ H, int64_t N, int32_t d,
                                                     const float *__restrict__ s_answer, int32_t tiles_per_block,
-                                                    int32_t n_col_tiles, unsigned *__restrict__ cnt_gt,
+                                                    int32_t n_col_tiles, int32_t n_row_tiles, int32_t n_col_chunks,
+                                                    unsigned *__restrict__ cnt_gt,
                                                     unsigned *__restrict__ cnt_eq, float *__restrict__ dump)
 {
     __shared__ __attribute__((aligned(16))) float As[EBK][EBM + EPAD];
     __shared__ __attribute__((aligned(16))) float Bs[EBK][EBN + EPAD];
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int wm = w >> 1, wn = w & 1, half = lane >> 5;
-    const int64_t m0 = (int64_t)blockIdx.x * EBM;
+    // block id -> (query tile, chunk of entity tiles).  Workgroup i runs on XCD i % 8, each with its own L2.
+    // The (query tile, chunk) space is cut into 8 x 8 patches; a patch goes to one XCD and is what that XCD
+    // runs at a time (64 blocks), so its L2 holds 8 query tiles, re-read at every entity tile, and 8 streams
+    // of entity tiles, each shared by 8 blocks - instead of 64 unrelated query tiles that do not fit.
+    const int64_t slot = blockIdx.x / 8, xcd = blockIdx.x % 8;
+    const int64_t patch = (slot / 64) * 8 + xcd;
+    const int r64 = (int)(slot % 64);
+    const int64_t patches_r = (n_row_tiles + 7) / 8;
+    const int64_t row_tile = (patch % patches_r) * 8 + r64 % 8;
+    const int64_t chunk = (patch / patches_r) * 8 + r64 / 8;
+    if (row_tile >= n_row_tiles || chunk >= n_col_chunks) return;      // padding blocks of the edge patches
+    const int64_t m0 = row_tile * EBM;
 
     // D register v of lane l of accumulator (i, j): row 32 i + 8 (v / 4) + 4 (l / 32) + v % 4, column 32 j + l % 32
-    float thr[2][16];
+    // the answers' scores of the tile's queries wait in LDS for the comparisons (rows past the end: +inf)
+    __shared__ float thr_s[EBM];
+    if (t < EBM) thr_s[t] = m0 + t < nq ? s_answer[m0 + t] : INFINITY;
     unsigned cnt[2][16];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int64_t row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-            thr[i][v] = row < nq ? s_answer[row] : INFINITY;
-            cnt[i][v] = 0u;
-        }
+        for (int v = 0; v < 16; ++v) cnt[i][v] = 0u;
 
-    const int32_t ct_beg = blockIdx.y * tiles_per_block;
+    const int32_t ct_beg = (int32_t)chunk * tiles_per_block;
     const int32_t ct_end = ct_beg + tiles_per_block < n_col_tiles ? ct_beg + tiles_per_block : n_col_tiles;
     const int32_t nk = (d + EBK - 1) / EBK;
     const int64_t n_it = (int64_t)(ct_end - ct_beg) * nk;      // k chunks of all tiles, in one sequence
 
-    // operand pieces of this thread: rows r_ld and r_ld + 64 of the tile, 4 consecutive k from k_ld
-    const int r_ld = t >> 2, k_ld = (t & 3) * 4;
-    float4 ra[2], rb[2];
+    // operand pieces of this thread: rows r_ld + ERP * pass of the tile, 4 consecutive k from k_ld
+    const int r_ld = t / ETR, k_ld = (t % ETR) * 4;
+    float4 ra[ENP], rb[ENP];
     auto fetch = [&](int32_t ct, int32_t kc) {
         const int32_t k = kc * EBK + k_ld;
         const int64_t n0 = (int64_t)ct * EBN;
 #pragma unroll
-        for (int ps = 0; ps < 2; ++ps) {
-            const int64_t m = m0 + r_ld + ps * 64, n = n0 + r_ld + ps * 64;
+        for (int ps = 0; ps < ENP; ++ps) {
+            const int64_t m = m0 + r_ld + ps * ERP, n = n0 + r_ld + ps * ERP;
             ra[ps] = (m < nq && k < d) ? *reinterpret_cast<const float4 *>(Q + m * d + k) : make_float4(0.f, 0.f, 0.f, 0.f);
             rb[ps] = (n < N && k < d) ? *reinterpret_cast<const float4 *>(H + n * d + k) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
@@ -255,8 +266,8 @@ __global__ __launch_bounds__(256) void k_eval_count(const float *__restrict__ Q,
         }
         __syncthreads();                  // the previous chunk has been consumed
 #pragma unroll
-        for (int ps = 0; ps < 2; ++ps) {
-            const int r = r_ld + ps * 64;
+        for (int ps = 0; ps < ENP; ++ps) {
+            const int r = r_ld + ps * ERP;
             As[k_ld + 0][r] = ra[ps].x; As[k_ld + 1][r] = ra[ps].y; As[k_ld + 2][r] = ra[ps].z; As[k_ld + 3][r] = ra[ps].w;
             Bs[k_ld + 0][r] = rb[ps].x; Bs[k_ld + 1][r] = rb[ps].y; Bs[k_ld + 2][r] = rb[ps].z; Bs[k_ld + 3][r] = rb[ps].w;
         }
@@ -284,7 +295,8 @@ __global__ __launch_bounds__(256) void k_eval_count(const float *__restrict__ Q,
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
                             const float s = acc[i][j][v];
-                            cnt[i][v] += s > thr[i][v] ? 1u : (s == thr[i][v] ? 65536u : 0u);
+                            const float th = thr_s[wm * 64 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3)];
+                            cnt[i][v] += s > th ? 1u : (s == th ? 65536u : 0u);
                             if (DUMP) {
                                 const int64_t row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
                                 if (row < nq) dump[row * N + col] = s;
@@ -389,17 +401,23 @@ int launch_count(const float *Q, int64_t nq, const float *H, int64_t N, int32_t 
                  unsigned *cnt_gt, unsigned *cnt_eq, float *dump, hipStream_t st)
 {
     const int64_t row_tiles = cdiv(nq, EBM), col_tiles = cdiv(N, EBN);
-    // about 4096 blocks (16 per compute unit) when there is that much work; a block's packed counters hold 512 tiles
-    int64_t tpb = cdiv(row_tiles * col_tiles, 4096);
-    if (tpb < 1) tpb = 1;
+    // about 4096 blocks (16 per compute unit) when there is that much work, the chunk count a multiple of
+    // the patch width when it exceeds it; a block's packed counters hold 512 tiles
+    int64_t col_chunks = cdiv(4096, row_tiles);
+    if (col_chunks > 8) col_chunks = cdiv(col_chunks, 8) * 8;
+    if (col_chunks > col_tiles) col_chunks = col_tiles;
+    int64_t tpb = cdiv(col_tiles, col_chunks);
     if (tpb > 512) tpb = 512;
-    const int64_t col_chunks = cdiv(col_tiles, tpb);
-    KGE_REQUIRE(row_tiles <= 0x7FFFFFFFll && col_chunks <= 65535, KGE_ERANGE, "evaluation grid too large");
-    dim3 grid((unsigned)row_tiles, (unsigned)col_chunks);
+    col_chunks = cdiv(col_tiles, tpb);
+    const int64_t patches = cdiv(row_tiles, 8) * cdiv(col_chunks, 8);
+    const int64_t blocks = cdiv(patches, 8) * 8 * 64;        // whole rounds of 8 patches, 64 blocks each
+    KGE_REQUIRE(blocks <= 0x7FFFFFFFll, KGE_ERANGE, "evaluation grid too large");
     if (dump)
-        k_eval_count<true><<<grid, 256, 0, st>>>(Q, nq, H, N, d, s_answer, (int32_t)tpb, (int32_t)col_tiles, cnt_gt, cnt_eq, dump);
+        k_eval_count<true><<<(unsigned)blocks, 256, 0, st>>>(Q, nq, H, N, d, s_answer, (int32_t)tpb, (int32_t)col_tiles,
+                                                            (int32_t)row_tiles, (int32_t)col_chunks, cnt_gt, cnt_eq, dump);
     else
-        k_eval_count<false><<<grid, 256, 0, st>>>(Q, nq, H, N, d, s_answer, (int32_t)tpb, (int32_t)col_tiles, cnt_gt, cnt_eq, nullptr);
+        k_eval_count<false><<<(unsigned)blocks, 256, 0, st>>>(Q, nq, H, N, d, s_answer, (int32_t)tpb, (int32_t)col_tiles,
+                                                             (int32_t)row_tiles, (int32_t)col_chunks, cnt_gt, cnt_eq, nullptr);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
