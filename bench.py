@@ -202,7 +202,7 @@ def run_eval(args):
     if not args.no_cpu_baseline:
         from oracle import eval_oracle as evo
         Hc, Mc = H.cpu().numpy(), M.cpu().numpy()
-        k = max(1, min(n_test, int(2e10 / (2.0 * N * d * 8))))      # about 10-30 s of fp64 matrix-vector products
+        k = max(1, min(n_test, int(2e11 / (2.0 * N * d * 8))))      # about 10-30 s of fp64 matrix-vector products
         t0 = time.perf_counter()
         if args.eval == "all":
             evo.filtered_counts(Hc, Mc, th[:k].cpu().numpy(), tr[:k].cpu().numpy(), tt[:k].cpu().numpy())
