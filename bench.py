@@ -25,7 +25,7 @@ PEAK_F32_MFMA_TFLOPS = 157.3
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 
 
-def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None, spec_order="project"):
+def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None, spec_order="project", single_runs=0):
     """Algorithmic bytes / flops of ONE launch of a kernel (what the method itself must move
     or compute in this formulation).  Returns (bound, work).  cone: None, or the per-layer counts
     (active vertices, edges into them, runs into them) of the batch's computational sub-graph;
@@ -55,7 +55,10 @@ def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None, spec_order=
     ns_mean = S if cone is None else sum(c[2] for c in cone) / len(cone)
     nv_mean = N if cone is None else sum(c[0] for c in cone) / len(cone)
     if name == "run_mean":     # per edge: source id + input row; per run: ptr/dst/1/c + z row written
-        return "hbm", ne_mean * (ep * d + 4.0) + S * 12.0 + S * ep * d
+        # single_runs: runs of one edge that the bf16 relation-weight pipeline neither reads nor writes
+        # (their mean is the source's input row, read in place by the products), scaled to the sub-graph
+        skip = single_runs * (ne_mean / max(E, 1))
+        return "hbm", (ne_mean - skip) * (ep * d + 4.0) + S * 12.0 + (S - single_runs) * ep * d
     if name == "aggregate":    # per run: z row + (run id, relation); per vertex: ptr + y row written
         return "hbm", ns_mean * (ep * d + 8.0) + N * 4.0 + nv_mean * B * d * ep + R2 * B * 4.0
     if name == "sum_runs":     # per run: u row + run id; per vertex: ptr + Self read + output write
@@ -320,12 +323,16 @@ def main():
 
     ms_per_step = 1e3 * dt / args.steps
     E = part.n_edge
+    single_runs = 0
+    if args.order == "relation" and spec.msg_dtype == "bf16":
+        import numpy as np
+        single_runs = int((np.diff(part.export("seg_ptr")) == 1).sum())
     n_pos, n_neg = len(pos), spec.n_neg
     T = n_pos * (1 + n_neg)
     ep = 2 if spec.msg_dtype == "bf16" else 4
     kernels = {}
     for name, (tot_ms, calls) in prof.items():
-        bound, work = kernel_work(name, part, spec, spec.d, spec.n_bases, ep, n_pos, n_neg, cone, args.order)
+        bound, work = kernel_work(name, part, spec, spec.d, spec.n_bases, ep, n_pos, n_neg, cone, args.order, single_runs)
         avg_ms = tot_ms / max(calls, 1)
         if bound == "hbm":
             ach, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"

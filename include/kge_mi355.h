@@ -374,7 +374,9 @@ int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_ent
  *               bf16, is appended behind the B blocks)
  *   KGE_WS_DH   gradient with respect to layer l's INPUT, l >= 1, [N][d_in] float (after backward)
  *   KGE_WS_Z    aggregate-first or relation-weight layer l: run means z [S][d_in], one row per (relation,
- *               destination) run in the partition's run order (valid after forward)
+ *               destination) run in the partition's run order (valid after forward).  A relation-weight
+ *               layer with bf16 messages leaves the rows of single-edge runs unwritten: such a run's mean
+ *               is its source's row of the layer input, which the layer reads in place
  *   KGE_WS_Y    aggregate-first layer l: y [N][B*d_in] float of the last such layer forward has
  *               processed (the buffer is shared between layers)
  *   KGE_WS_HD   layer l's input after dropout [N][d_in] float (valid after forward; only for layers

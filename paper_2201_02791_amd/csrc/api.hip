@@ -130,6 +130,9 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
         const bool agg = L.order == KGE_ORDER_AGGREGATE_FIRST;
         if (L.order == KGE_ORDER_RELATION_WEIGHTS) {
             const size_t dd = (size_t)L.d_in * L.d_out, R2 = (size_t)2 * p->n_relations;
+            // bf16: the run means follow the bf16 copy of the layer input without a gap, so that the two are
+            // one matrix [X; Z] whose rows the partition's seg_zrow addresses
+            if (bf) { w->off_Hbf[l] = cur; cur += N * L.d_in * 2; }
             w->off_Z[l] = cur; cur = align_up(cur + (size_t)p->n_seg * L.d_in * ep, 256);
             w->off_Wrel[l] = cur; cur = align_up(cur + R2 * dd * 4, 256);
             if (bf) {
@@ -163,7 +166,7 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
         const size_t nc = (size_t)(L.n_bases + 1) * L.d_out;
         if (nc > max_nc) max_nc = nc;
         if (bf) {
-            w->off_Hbf[l] = cur; cur = align_up(cur + N * L.d_in * 2, 256);
+            if (L.order != KGE_ORDER_RELATION_WEIGHTS) { w->off_Hbf[l] = cur; cur = align_up(cur + N * L.d_in * 2, 256); }
             w->off_Wbf[l] = cur; cur = align_up(cur + nc * L.d_in * 2, 256);
             w->off_WbfT[l] = cur; cur = align_up(cur + nc * L.d_in * 2, 256);
         }
@@ -299,13 +302,16 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
                 if (rc != KGE_OK) return rc;
                 rc = launch_cvt_relation_weights_bf16(Wrel, R2, L.d_in, L.d_out, ws + w.off_Wrb[l], ws + w.off_WrbT[l], st);
                 if (rc != KGE_OK) return rc;
-                rc = launch_run_mean(p, Hbf, L.d_in, Z, 1, part, act_l, st);
+                // a run of one edge has its source's row of Hbf as its mean: those rows of Z are neither written
+                // nor read (Hbf and Z are adjacent, seg_zrow says which row of [Hbf; Z] holds run s)
+                const int32_t *zrow = p->seg_zrow;
+                rc = launch_run_mean(p, Hbf, L.d_in, Z, 1, part, act_l, zrow != nullptr, st);
                 if (rc != KGE_OK) return rc;
-                rc = launch_apply_relation_weights_bf16(p, Z, ws + w.off_WrbT[l], L.d_in, L.d_out, U, st);
+                rc = launch_apply_relation_weights_bf16(p, zrow ? Hbf : Z, zrow, ws + w.off_WrbT[l], L.d_in, L.d_out, U, st);
                 if (rc != KGE_OK) return rc;
                 rc = launch_project_bf16(Hbf, p->n_vert, L.d_in, L.d_out, 0, WbfT, nullptr, Self, st);
             } else {
-                rc = launch_run_mean(p, Hin, L.d_in, Z, 0, part, act_l, st);
+                rc = launch_run_mean(p, Hin, L.d_in, Z, 0, part, act_l, 0, st);
                 if (rc != KGE_OK) return rc;
                 rc = launch_apply_relation_weights(p, (const float *)Z, Wrel, L.d_in, L.d_out, (float *)U, st);
                 if (rc != KGE_OK) return rc;
@@ -330,7 +336,7 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
                 if (rc != KGE_OK) return rc;
                 rc = launch_cvt_wstack_bf16(L.V, L.W0, L.d_in, L.d_out, L.n_bases, WstT, st);
                 if (rc != KGE_OK) return rc;
-                rc = launch_run_mean(p, Hbf, L.d_in, Z, 1, part, act_l, st);
+                rc = launch_run_mean(p, Hbf, L.d_in, Z, 1, part, act_l, 0, st);
                 if (rc != KGE_OK) return rc;
                 rc = launch_aggregate_runs(p, Z, L.a, L.n_bases, L.d_in, Y, (int64_t)(L.n_bases + 1) * L.d_in, 1, part, act_l, st);
                 if (rc != KGE_OK) return rc;
@@ -338,7 +344,7 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
                 if (rc != KGE_OK) return rc;
                 rc = launch_combine_bf16(Y, p->n_vert, L.d_in, L.d_out, L.n_bases, WstT, L.act, act_l, Hl, out2, st);
             } else {
-                rc = launch_run_mean(p, Hin, L.d_in, Z, 0, part, act_l, st);
+                rc = launch_run_mean(p, Hin, L.d_in, Z, 0, part, act_l, 0, st);
                 if (rc != KGE_OK) return rc;
                 rc = launch_aggregate_runs(p, Z, L.a, L.n_bases, L.d_in, Y, (int64_t)L.n_bases * L.d_in, 0, part, act_l, st);
                 if (rc != KGE_OK) return rc;
@@ -421,7 +427,7 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
             if (bf) {
                 rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, 0, dP, st);          // Gbf [N][d_out]
                 if (rc != KGE_OK) return rc;
-                rc = launch_rel_outer_bf16(p, Z, dP, L.d_out, L.d_in, L.d_out, C, st);
+                rc = launch_rel_outer_bf16(p, p->seg_zrow ? ws + w.off_Hbf[l] : Z, p->seg_zrow, dP, L.d_out, L.d_in, L.d_out, C, st);
             } else {
                 rc = launch_rel_outer(p, (const float *)Z, Gl, L.d_in, L.d_out, C, st);
             }
@@ -471,7 +477,7 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
             rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, L.n_bases, dP, st);
             if (rc != KGE_OK) return rc;
             if (agg) {       // the coefficient gradient reads the bf16 copy of G that was just appended
-                rc = launch_rel_outer_bf16(p, ws + w.off_Z[l], (const uint16_t *)dP + bd, bd + L.d_out, L.d_in, L.d_out, C, st);
+                rc = launch_rel_outer_bf16(p, ws + w.off_Z[l], nullptr, (const uint16_t *)dP + bd, bd + L.d_out, L.d_in, L.d_out, C, st);
                 if (rc != KGE_OK) return rc;
                 rc = launch_coeff_contract(p, C, L.V, L.d_in, L.d_out, L.n_bases, grads[l].da, st);
                 if (rc != KGE_OK) return rc;

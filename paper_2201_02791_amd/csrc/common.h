@@ -67,6 +67,10 @@ struct kge_partition {
     // and into row tiles of at most KGE_REL_TILE runs
     int32_t n_relt;
     int32_t *relt_rel, *relt_beg, *relt_end;
+    // where the mean of run s can be read when the layer input X [N][d] and the run means Z [S][d] are one
+    // matrix [X; Z]: a run of a single edge has its source's row of X as its mean (row col_src), any other
+    // run row N + s.  NULL if N + S does not fit 31 bits.
+    int32_t *seg_zrow;
 };
 #define KGE_REL_CHUNK 2048
 #define KGE_REL_TILE 128
@@ -141,8 +145,9 @@ int kge_cgraph_check(const kge_partition *p, const kge_cgraph *cg, int32_t n_lay
 // gather.hip, aggregate-first order ------------------------------------------
 // Z[s][:] = invc_s sum_{j in run s} H[j][:]  ([S][d]; H and Z both fp32 or, with bf16 != 0, both bf16;
 // sums in fp32); runs into inactive destinations get zeros; `partial`: [hv_seg.n_units][d] floats
+// skip_single: runs of one edge are left unwritten (their mean is their source's row of H, see seg_zrow)
 int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, int bf16, float *partial,
-                    const uint8_t *active, hipStream_t st);
+                    const uint8_t *active, int skip_single, hipStream_t st);
 // Y[i][b][:] = sum_{runs (r,i) of i} a[r][b] Z[run][:]; rows are `ld` elements apart; rows with
 // row_active[i] == 0 are left unwritten; `partial`: [hv_dr.n_units][B*d] floats
 // (Z and Y are fp32, or both bf16 when msg_bf16 != 0)
@@ -174,9 +179,10 @@ int launch_apply_relation_weights_t(const kge_partition *p, const float *G, cons
 // bf16 copies of Wrel: Wb [2R][d_in][d_out] and WbT [2R][d_out][d_in]
 int launch_cvt_relation_weights_bf16(const float *Wrel, int32_t R2, int32_t d_in, int32_t d_out, void *Wb, void *WbT,
                                      hipStream_t st);
-// the same two products from bf16 operands, bf16 results; Gbf rows are ldg elements apart
-int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, const void *WbT, int32_t d_in,
-                                       int32_t d_out, void *U, hipStream_t st);
+// the same two products from bf16 operands, bf16 results; Gbf rows are ldg elements apart.  zrow (may be
+// NULL): Zbf is then the matrix [X; Z] and run s reads its row zrow[s]
+int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, const int32_t *zrow, const void *WbT,
+                                       int32_t d_in, int32_t d_out, void *U, hipStream_t st);
 int launch_apply_relation_weights_t_bf16(const kge_partition *p, const void *Gbf, int64_t ldg, const void *Wb,
                                          int32_t d_in, int32_t d_out, void *dZ, hipStream_t st);
 
@@ -199,9 +205,10 @@ int launch_cvt_wstack_bf16(const float *V, const float *W0, int32_t d_in, int32_
 // out = act(X WstT^T), X = [Y | Hbf] bf16 [N][(B+1) d_in]; zero rows where row_active[i] == 0
 int launch_combine_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const void *WstT,
                         int act, const uint8_t *row_active, float *out, float *out2, hipStream_t st);
-// the same C from bf16 operands: Zbf [S][d_in]; Gbf rows of d_out elements, ldg elements apart
-int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const void *Gbf, int64_t ldg, int32_t d_in,
-                          int32_t d_out, float *C, hipStream_t st);
+// the same C from bf16 operands: Zbf [S][d_in] (or, with zrow, the matrix [X; Z] read through zrow); Gbf rows
+// of d_out elements, ldg elements apart
+int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const int32_t *zrow, const void *Gbf, int64_t ldg,
+                          int32_t d_in, int32_t d_out, float *C, hipStream_t st);
 
 // sampler_score.hip --------------------------------------------------------
 int launch_sample_negatives(const kge_partition *p, const int32_t *pos, int64_t n_pos, int32_t n_neg,

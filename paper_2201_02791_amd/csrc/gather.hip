@@ -538,7 +538,7 @@ __global__ __launch_bounds__(64 * WPB) void k_run_mean(
     const float *__restrict__ inv_c, const int32_t *__restrict__ col_src, int64_t S,
     int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
     const int32_t *__restrict__ unit_hv, const void *__restrict__ H, int32_t d,
-    void *__restrict__ Z, float *__restrict__ partial, const uint8_t *__restrict__ active)
+    void *__restrict__ Z, float *__restrict__ partial, const uint8_t *__restrict__ active, int skip_single)
 {
     constexpr int VEC = MsgRow<BF16>::VEC;
     constexpr int NG = 64 / LPR;
@@ -547,6 +547,7 @@ __global__ __launch_bounds__(64 * WPB) void k_run_mean(
     const int64_t wid = (int64_t)blockIdx.x * WPB + (threadIdx.x >> 6);
     const RowWork rw = row_work(wid, seg_ptr, S, n_units, hv_row, hv_unit_ptr, unit_hv);
     if (rw.row < 0) return;
+    if (skip_single && rw.unit < 0 && rw.end - rw.beg == 1) return;    // read in place by the consumer
     const int kl = lane % LPR, g = lane / LPR;
     const bool kact = kl * VEC < d;
     float acc[VEC];
@@ -607,7 +608,7 @@ template <bool BF16, int LPR, int RPW>
 __global__ __launch_bounds__(64 * WPB) void k_run_mean_multi(
     const int32_t *__restrict__ seg_ptr, const int32_t *__restrict__ seg_dst,
     const float *__restrict__ inv_c, const int32_t *__restrict__ col_src, int64_t S,
-    const void *__restrict__ H, int32_t d, void *__restrict__ Z, const uint8_t *__restrict__ active)
+    const void *__restrict__ H, int32_t d, void *__restrict__ Z, const uint8_t *__restrict__ active, int skip_single)
 {
     constexpr int VEC = MsgRow<BF16>::VEC;
     constexpr int NG = 64 / LPR;
@@ -633,6 +634,7 @@ __global__ __launch_bounds__(64 * WPB) void k_run_mean_multi(
         w[i] = 0.f;
         src0[i] = 0;
         if (len[i] >= KGE_HEAVY) len[i] = -1;              // written by the finishing kernel
+        if (skip_single && len[i] == 1) len[i] = -1;       // read in place by the consumer
         if (len[i] > 0) {
             if (active && !active[seg_dst[sr]]) len[i] = 0;            // outside the sub-graph: a zero row
             else { w[i] = inv_c[sr]; src0[i] = col_src[b]; }
@@ -1103,7 +1105,7 @@ int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const
 
 // Z[s][:] = invc_s * sum_{j in run s} H[j][:]; H and Z fp32, or both bf16; `partial`: [hv_seg.n_units][d] floats
 int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, int bf16, float *partial,
-                    const uint8_t *active, hipStream_t st)
+                    const uint8_t *active, int skip_single, hipStream_t st)
 {
     const int64_t S = p->n_seg;
     if (S == 0) return KGE_OK;
@@ -1117,7 +1119,7 @@ int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, i
         constexpr int RPW = 8;
         KGE_PROF("run_mean", st);
         const unsigned gridm = (unsigned)cdiv(cdiv(S, RPW), WPB);
-#define RMM_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, H, d, Z, active
+#define RMM_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, H, d, Z, active, skip_single
         if (bf16) { DISPATCH_LPR(lpr, (k_run_mean_multi<true, (L < 8 ? 8 : L), RPW><<<gridm, 64 * WPB, 0, st>>>(RMM_ARGS))); }
         else { DISPATCH_LPR(lpr, (k_run_mean_multi<false, (L < 8 ? 8 : L), RPW><<<gridm, 64 * WPB, 0, st>>>(RMM_ARGS))); }
 #undef RMM_ARGS
@@ -1125,7 +1127,7 @@ int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, i
         if (hx.n_units > 0) {
             const unsigned gridu = (unsigned)cdiv(hx.n_units, WPB);
 #define RMU_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, (int64_t)0, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, \
-                 H, d, Z, partial, active
+                 H, d, Z, partial, active, 0
             if (bf16) { DISPATCH_LPR(lpr, (k_run_mean<true, L><<<gridu, 64 * WPB, 0, st>>>(RMU_ARGS))); }
             else { DISPATCH_LPR(lpr, (k_run_mean<false, L><<<gridu, 64 * WPB, 0, st>>>(RMU_ARGS))); }
 #undef RMU_ARGS
@@ -1136,7 +1138,7 @@ int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, i
     {
         KGE_PROF("run_mean", st);
 #define RM_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, \
-                H, d, Z, partial, active
+                H, d, Z, partial, active, skip_single
         if (bf16) { DISPATCH_LPR(lpr, (k_run_mean<true, L><<<grid, 64 * WPB, 0, st>>>(RM_ARGS))); }
         else { DISPATCH_LPR(lpr, (k_run_mean<false, L><<<grid, 64 * WPB, 0, st>>>(RM_ARGS))); }
 #undef RM_ARGS

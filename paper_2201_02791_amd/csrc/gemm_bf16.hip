@@ -223,7 +223,7 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
     // earlier still, which keeps the row loads themselves independent.
     struct Regs { uint4 a[KC ? TM / RPP : 1], b[KC ? TNt / RPP : 1]; uint32_t pa[KC ? 1 : 8], pb[KC ? 1 : NJ / 2][KC ? 1 : 8]; };
     Regs rg[PF];
-    int32_t brow[8];          // KC = false: stored rows of B for the tile that is loaded next
+    int32_t brow[8], akrow[8];          // KC = false: stored rows of B and of A for the tile that is loaded next
 
     auto load_rows = [&](int64_t k0) {
         if (!KC) {
@@ -232,6 +232,7 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             for (int kk = 0; kk < 8; ++kk) {
                 const int64_t r = k0 + ko + kk;
                 brow[kk] = (r < kend && r < B.rows) ? (B.idx ? B.idx[r] : (int32_t)r) : -1;
+                akrow[kk] = (r < kend && r < A.rows) ? (A.idx ? A.idx[r] : (int32_t)r) : -1;
             }
         }
     };
@@ -258,8 +259,11 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
         } else {
             const int cp = t & 63, ko = (t >> 6) * 8;
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                R.pa[kk] = (k0 + ko + kk < kend) ? A.pair(k0 + ko + kk, (int32_t)(m0 + 2 * cp)) : 0u;
+            for (int kk = 0; kk < 8; ++kk) {
+                const int32_t c = (int32_t)(m0 + 2 * cp);
+                R.pa[kk] = (akrow[kk] >= 0 && c < A.cols)
+                               ? *reinterpret_cast<const uint32_t *>(A.p + (int64_t)akrow[kk] * A.ld + c) : 0u;
+            }
 #pragma unroll
             for (int ps = 0; ps < NJ / 2; ++ps)
 #pragma unroll
@@ -584,15 +588,15 @@ int launch_combine_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out, i
 
 // C[r] (d_in x d_out, fp32, zeroed here) = sum_{runs s of relation r} Zbf[s]^T Gbf[seg_dst[s]]
 // Gbf: bf16 rows of d_out elements, `ldg` elements apart (the G block appended behind dP)
-int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const void *Gbf, int64_t ldg, int32_t d_in,
-                          int32_t d_out, float *C, hipStream_t st)
+int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const int32_t *zrow, const void *Gbf, int64_t ldg,
+                          int32_t d_in, int32_t d_out, float *C, hipStream_t st)
 {
     const int64_t R2 = 2 * (int64_t)p->n_relations;
     int rc = launch_fill_zero(C, sizeof(float) * (size_t)R2 * d_in * d_out, st);
     if (rc != KGE_OK) return rc;
     if (p->n_seg == 0 || p->n_relc == 0) return KGE_OK;
     const int32_t tiles_m = (int32_t)cdiv(d_in, TM), tiles_n = (int32_t)cdiv(d_out, TN);
-    MatBF A{reinterpret_cast<const uint16_t *>(Zbf), p->n_seg, d_in, d_in, nullptr};
+    MatBF A{reinterpret_cast<const uint16_t *>(Zbf), p->n_seg, d_in, d_in, zrow};
     MatBF Bm{reinterpret_cast<const uint16_t *>(Gbf), p->n_seg, d_out, ldg, p->seg_dst};
     EpiRelOuterAtomic ep{C, d_in, d_out, 0};
     KGE_PROF("rel_outer", st);
@@ -614,12 +618,12 @@ int launch_cvt_relation_weights_bf16(const float *Wrel, int32_t R2, int32_t d_in
 }
 
 // U[s] = Zbf[s] Wrel[rel(s)]   bf16 in, bf16 out; WbT: bf16 [2R][d_out][d_in]
-int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, const void *WbT, int32_t d_in,
-                                       int32_t d_out, void *U, hipStream_t st)
+int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, const int32_t *zrow, const void *WbT,
+                                       int32_t d_in, int32_t d_out, void *U, hipStream_t st)
 {
     if (p->n_relt == 0) return KGE_OK;
     const int32_t tiles_n = (int32_t)cdiv(d_out, TN);
-    MatBF A{reinterpret_cast<const uint16_t *>(Zbf), p->n_seg, d_in, d_in, nullptr};
+    MatBF A{reinterpret_cast<const uint16_t *>(Zbf), p->n_seg, d_in, d_in, zrow};
     MatBF Bm{reinterpret_cast<const uint16_t *>(WbT), d_out, d_in, d_in, nullptr};
     EpiRowsBF16Staged ep{reinterpret_cast<uint16_t *>(U), p->n_seg, d_out};
     KGE_PROF("apply_rel", st);

@@ -372,6 +372,14 @@ __global__ void k_seg_emit(const uint64_t *keys, const uint32_t *vals, int64_t E
     }
 }
 
+__global__ void k_seg_zrow(const int32_t *seg_ptr, const int32_t *col_src, int64_t S, int32_t N, int32_t *zrow)
+{
+    int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= S) return;
+    const int32_t b = seg_ptr[s];
+    zrow[s] = seg_ptr[s + 1] - b == 1 ? col_src[b] : N + (int32_t)s;
+}
+
 __global__ void k_inv_c(const int32_t *seg_ptr, int64_t S, float *inv_c)
 {
     int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -655,6 +663,11 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
     KGE_HIP(hipMemcpyAsync(p->seg_ptr + S, &E_i32, sizeof(int32_t), hipMemcpyHostToDevice, st));
     KGE_HIP(hipStreamSynchronize(st));
     if (S > 0) { k_inv_c<<<grid_for(S), TB, 0, st>>>(p->seg_ptr, S, p->inv_c); KGE_LAUNCH_CHECK(); }
+    if (S > 0 && N + S < 0x7FFFFFFFll) {
+        TRY(palloc(&p->seg_zrow, S));
+        k_seg_zrow<<<grid_for(S), TB, 0, st>>>(p->seg_ptr, p->col_src, S, (int32_t)N, p->seg_zrow);
+        KGE_LAUNCH_CHECK();
+    }
     TRY(palloc(&p->rel_ptr, (size_t)2 * n_rel + 1));
     k_ptr_from_sorted<int32_t><<<grid_for(S + 1), TB, 0, st>>>(p->seg_rel, S, 2 * (int64_t)n_rel, p->rel_ptr);
     KGE_LAUNCH_CHECK();
@@ -774,7 +787,8 @@ extern "C" void kge_partition_destroy(kge_partition *p)
                     p->hv_sm.hv_row, p->hv_sm.hv_unit_ptr, p->hv_sm.unit_hv,
                     p->hv_seg.hv_row, p->hv_seg.hv_unit_ptr, p->hv_seg.unit_hv,
                     p->dr_ptr, p->dr_seg, p->dr_rel, p->hv_dr.hv_row, p->hv_dr.hv_unit_ptr, p->hv_dr.unit_hv,
-                    p->relc_rel, p->relc_beg, p->relc_end, p->sm_seg, p->relt_rel, p->relt_beg, p->relt_end};
+                    p->relc_rel, p->relc_beg, p->relc_end, p->sm_seg, p->relt_rel, p->relt_beg, p->relt_end,
+                    p->seg_zrow};
     for (void *q : arrs) if (q) (void)hipFree(q);
     delete p;
 }

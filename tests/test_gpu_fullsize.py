@@ -157,20 +157,28 @@ def run_full_size(kb, orc, cfg, order="project", dropout=0.0):
         # run means of both layers on sampled runs into active destinations, and the per-basis sums
         # of the last layer (the y buffer is shared) on its sampled rows, from the GPU's own z
         run_len = np.diff(op["seg_ptr"])
+        # the bf16 relation-weight pipeline keeps no mean for a run of one edge (it reads the source's row of
+        # the layer input in place, which is that mean): those rows of z are sampled from longer runs only
+        alias = relw and bf
         for l, Hin in ((0, Hin0), (1, Hin1)):
-            ok = active[l][op["seg_dst"]] & (run_len <= 2000)
+            ok = active[l][op["seg_dst"]] & (run_len <= 2000) & ((run_len > 1) | (not alias))
             runs = rng.permutation(np.nonzero(ok)[0])[:400]
             runs = np.concatenate([runs, np.nonzero(ok & (run_len >= 256))[0][:2]]).astype(np.int64)
             zg = c(ts.view(kb.WS_Z, l)[torch.from_numpy(runs).to(ts.dev)])
             zw = sampled.run_mean_rows(op, runs, Hin, bf16=bf)
             errs["z_%d runs" % (l + 1)] = (rel_err(zg, zw), tol_v)
-            gone = np.nonzero(~active[l][op["seg_dst"]])[0][:50]          # runs outside the sub-graph: zero rows
+            gone = np.nonzero(~active[l][op["seg_dst"]] & ((run_len > 1) | (not alias)))[0][:50]   # runs outside the sub-graph: zero rows
             if len(gone):
                 assert not c(ts.view(kb.WS_Z, l)[torch.from_numpy(gone).to(ts.dev)]).any()
         Zv = ts.view(kb.WS_Z, 1)
         Z_of = lambda ids: c(Zv[torch.from_numpy(np.asarray(ids, np.int64)).to(ts.dev)])
         if relw:
             uruns, ug, zg_u = u_check
+            if alias:       # single-edge runs: the operand is the bf16 copy of the source's input row
+                one = run_len[uruns] == 1
+                assert one.any() and not one.all()
+                zg_u = zg_u.copy()
+                zg_u[one] = sampled.round_bf16(Hin1[op["col_src"][op["seg_ptr"][uruns[one]]]])
             uw = sampled.relation_product_rows(op, uruns, lambda ids: zg_u, L[1]["a"], L[1]["V"], bf16=bf)
             errs["u_2 runs"] = (rel_err(ug, uw), tol_v)
         else:
@@ -252,7 +260,15 @@ def run_full_size(kb, orc, cfg, order="project", dropout=0.0):
         for l, G in ((0, G1), (1, G2)):
             if agg:
                 Zl = ts.view(kb.WS_Z, l)
-                Zl_of = lambda ids: c(Zl[torch.from_numpy(np.asarray(ids, np.int64)).to(ts.dev)])
+                Hin_l = Hin0 if l == 0 else Hin1
+
+                def Zl_of(ids, Zl=Zl, Hin_l=Hin_l):
+                    ids = np.asarray(ids, np.int64)
+                    z = c(Zl[torch.from_numpy(ids).to(ts.dev)])
+                    if relw and bf:      # single-edge runs keep no mean: it is the bf16 copy of the source's input row
+                        one = np.diff(op["seg_ptr"])[ids] == 1
+                        z[one] = sampled.round_bf16(Hin_l[op["col_src"][op["seg_ptr"][ids[one]]]])
+                    return z
                 want = sampled.coeff_grad_relations_runs(op, rels, Zl_of, L[l]["V"], G)
             else:
                 Pv = ts.view(kb.WS_P, l)
