@@ -449,14 +449,47 @@ int launch_coeff_contract(const kge_partition *p, const float *C, const float *V
 namespace {
 
 // out[i][x] = sum_k coef(i, k) M[k][x],  coef(i, k) = TRANS ? c[k][i] : c[i][k]   (c is [ni][nk], or [nk][ni])
-// One block: 16 rows i, 1024 columns x; M is read once per 16 rows.
-template <bool TRANS>
+// One block: 16 rows i, 256 CPT columns x (CPT = 4 or 1 per thread); M is read once per 16 rows.  A long sum
+// over few rows (the basis gradient: nk = 2R, ni = B) takes CPT = 1: four times the blocks, each walking k
+// with several row loads in flight.
+template <bool TRANS, int CPT>
 __global__ __launch_bounds__(256) void k_lincomb(const float *__restrict__ c, int32_t ni, int32_t nk,
                                                  const float *__restrict__ M, int64_t nx, float *__restrict__ out)
 {
     __shared__ float sc[16][64];
     const int i0 = blockIdx.y * 16;
-    const int64_t x = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    const int64_t x = ((int64_t)blockIdx.x * 256 + threadIdx.x) * CPT;
+    if constexpr (CPT == 1) {
+        float acc1[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc1[j] = 0.f;
+        for (int k0 = 0; k0 < nk; k0 += 64) {
+            __syncthreads();
+            for (int q = threadIdx.x; q < 16 * 64; q += 256) {
+                const int j = q >> 6, kk = q & 63;
+                const int i = i0 + j, k = k0 + kk;
+                sc[j][kk] = (i < ni && k < nk) ? (TRANS ? c[(int64_t)k * ni + i] : c[(int64_t)i * nk + k]) : 0.f;
+            }
+            __syncthreads();
+            if (x < nx) {
+                float m[8];
+#pragma unroll
+                for (int kb = 0; kb < 64; kb += 8) {       // rows past nk carry a zero coefficient: read row nk - 1 instead
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) m[u] = M[(int64_t)min(k0 + kb + u, nk - 1) * nx + x];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) acc1[j] = fmaf(sc[j][kb + u], m[u], acc1[j]);
+                }
+            }
+        }
+        if (x < nx)
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (i0 + j < ni) out[(int64_t)(i0 + j) * nx + x] = acc1[j];
+        return;
+    }
     float4 acc[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -495,7 +528,7 @@ int launch_relation_weights(const float *a, int32_t R2, int32_t B, const float *
     if (R2 == 0) return KGE_OK;
     dim3 grid((unsigned)cdiv(dd, 1024), (unsigned)cdiv(R2, 16), 1);
     KGE_PROF("rel_weights", st);
-    k_lincomb<false><<<grid, 256, 0, st>>>(a, R2, B, V, dd, Wrel);
+    k_lincomb<false, 4><<<grid, 256, 0, st>>>(a, R2, B, V, dd, Wrel);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
@@ -504,9 +537,10 @@ int launch_relation_weights(const float *a, int32_t R2, int32_t B, const float *
 int launch_basis_grad_from_relations(const float *a, int32_t R2, int32_t B, const float *C, int64_t dd, float *dV,
                                      hipStream_t st)
 {
-    dim3 grid((unsigned)cdiv(dd, 1024), (unsigned)cdiv(B, 16), 1);
+    if (R2 == 0) return launch_fill_zero(dV, sizeof(float) * (size_t)B * dd, st);
+    dim3 grid((unsigned)cdiv(dd, 256), (unsigned)cdiv(B, 16), 1);
     KGE_PROF("basis_grad", st);
-    k_lincomb<true><<<grid, 256, 0, st>>>(a, B, R2, C, dd, dV);
+    k_lincomb<true, 1><<<grid, 256, 0, st>>>(a, B, R2, C, dd, dV);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
