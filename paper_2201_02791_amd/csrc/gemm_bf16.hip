@@ -34,10 +34,11 @@ constexpr int TM = 128, TN = 256, TK = 32, NT = 256;
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)   // two fp32 -> packed bf16x2, nearest even
 {
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a = ((a & 0x7fffffffu) > 0x7f800000u) ? ((a >> 16) | 0x40u) : ((a + 0x7fffu + ((a >> 16) & 1u)) >> 16);
-    b = ((b & 0x7fffffffu) > 0x7f800000u) ? ((b >> 16) | 0x40u) : ((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
-    return (a & 0xffffu) | (b << 16);
+    // one v_cvt_pk_bf16_f32 on gfx950
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float floatx2_t __attribute__((ext_vector_type(2)));
+    const floatx2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // Row-major bf16 matrix.  oct: 8 consecutive elements (16 bytes); pair: 2 (4 bytes).  Out of range -> 0.
