@@ -224,16 +224,24 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
     // earlier still, which keeps the row loads themselves independent.
     struct Regs { uint4 a[KC ? TM / RPP : 1], b[KC ? TNt / RPP : 1]; uint32_t pa[KC ? 1 : 8], pb[KC ? 1 : NJ / 2][KC ? 1 : 8]; };
     Regs rg[PF];
-    int32_t brow[8], akrow[8];          // KC = false: stored rows of B and of A for the tile that is loaded next
+    // KC = false: stored rows of B and of A for the tile that is loaded next.  A k past the range's end takes
+    // the range's last row instead (kend <= rows of both operands) and clears its bit in kmask: every load is
+    // then unconditional - no divergent branch per load - and only A's pairs are zeroed for such a k, which
+    // makes the product vanish whatever finite row B repeats.
+    int32_t brow[8], akrow[8];
+    uint32_t kmask = 0u;
 
     auto load_rows = [&](int64_t k0) {
         if (!KC) {
             const int ko = (t >> 6) * 8;
+            kmask = 0u;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
                 const int64_t r = k0 + ko + kk;
-                brow[kk] = (r < kend && r < B.rows) ? (B.idx ? B.idx[r] : (int32_t)r) : -1;
-                akrow[kk] = (r < kend && r < A.rows) ? (A.idx ? A.idx[r] : (int32_t)r) : -1;
+                const int64_t rc = r < kend ? r : kend - 1;
+                kmask |= (r < kend ? 1u : 0u) << kk;
+                brow[kk] = B.idx ? B.idx[rc] : (int32_t)rc;
+                akrow[kk] = A.idx ? A.idx[rc] : (int32_t)rc;
             }
         }
     };
@@ -258,21 +266,23 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             for (int ps = 0; ps < TNt / RPP; ++ps)
                 R.b[ps] = kok ? B.oct(n0 + row + ps * RPP, (int32_t)(k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
         } else {
-            const int cp = t & 63, ko = (t >> 6) * 8;
+            // columns past the matrix read its last pair: they only feed outputs the epilogue drops
+            const int cp = t & 63;
+            const int32_t ca0 = (int32_t)(m0 + 2 * cp), ca = ca0 < A.cols ? ca0 : A.cols - 2;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                const int32_t c = (int32_t)(m0 + 2 * cp);
-                R.pa[kk] = (akrow[kk] >= 0 && c < A.cols)
-                               ? *reinterpret_cast<const uint32_t *>(A.p + (int64_t)akrow[kk] * A.ld + c) : 0u;
+                const uint32_t v = *reinterpret_cast<const uint32_t *>(A.p + (int64_t)akrow[kk] * A.ld + ca);
+                R.pa[kk] = (kmask >> kk) & 1u ? v : 0u;
             }
 #pragma unroll
-            for (int ps = 0; ps < NJ / 2; ++ps)
+            for (int kk = 0; kk < 8; ++kk) {
+                const uint16_t *brp = B.p + (int64_t)brow[kk] * B.ld;
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk) {
-                    const int32_t c = n0 + 2 * (cp + ps * 64);
-                    R.pb[ps][kk] = (brow[kk] >= 0 && c < B.cols)
-                                       ? *reinterpret_cast<const uint32_t *>(B.p + (int64_t)brow[kk] * B.ld + c) : 0u;
+                for (int ps = 0; ps < NJ / 2; ++ps) {
+                    const int32_t cb0 = n0 + 2 * (cp + ps * 64), cb = cb0 < B.cols ? cb0 : B.cols - 2;
+                    R.pb[ps][kk] = *reinterpret_cast<const uint32_t *>(brp + cb);
                 }
+            }
         }
     };
     auto store_tile = [&](Regs &R) {
