@@ -245,26 +245,35 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             }
         }
     };
-    // k-contiguous A through an index list: the stored rows of this thread's tile rows, fetched once
-    int64_t arow[KC ? TM / RPP : 1];
+    // k-contiguous operands: the stored rows of this thread's tile rows (through the index lists), fetched
+    // once.  Rows past an operand's end repeat its last row: they only feed outputs the epilogue drops, and
+    // every load stays unconditional.
+    int64_t arow[KC ? TM / RPP : 1], bcrow[KC ? TNt / RPP : 1];
     if constexpr (KC) {
 #pragma unroll
         for (int ps = 0; ps < TM / RPP; ++ps) {
-            const int64_t r = m0 + t / TPR + ps * RPP;
-            arow[ps] = r < A.rows ? (A.idx ? (int64_t)A.idx[r] : r) : -1;
+            const int64_t r = m0 + t / TPR + ps * RPP, rc = r < A.rows ? r : A.rows - 1;
+            arow[ps] = A.idx ? (int64_t)A.idx[rc] : rc;
+        }
+#pragma unroll
+        for (int ps = 0; ps < TNt / RPP; ++ps) {
+            const int64_t r = n0 + t / TPR + ps * RPP, rc = r < B.rows ? r : B.rows - 1;
+            bcrow[ps] = B.idx ? (int64_t)B.idx[rc] : rc;
         }
     }
     auto load_tile = [&](int64_t k0, Regs &R) {
         if constexpr (KC) {
-            const int row = t / TPR, ko = (t % TPR) * 8;
-            const bool kok = k0 + ko < kend;
+            // an octet past the contraction range reads octet 0 instead, and A's copy of it is zeroed
+            const int ko = (t % TPR) * 8;
+            const bool kok = k0 + ko < kend && k0 + ko < A.cols;
+            const int64_t kc = kok ? k0 + ko : 0;
 #pragma unroll
-            for (int ps = 0; ps < TM / RPP; ++ps)
-                R.a[ps] = (kok && arow[ps] >= 0 && k0 + ko < A.cols)
-                              ? *reinterpret_cast<const uint4 *>(A.p + arow[ps] * A.ld + (k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
+            for (int ps = 0; ps < TM / RPP; ++ps) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(A.p + arow[ps] * A.ld + kc);
+                R.a[ps] = kok ? v : make_uint4(0u, 0u, 0u, 0u);
+            }
 #pragma unroll
-            for (int ps = 0; ps < TNt / RPP; ++ps)
-                R.b[ps] = kok ? B.oct(n0 + row + ps * RPP, (int32_t)(k0 + ko)) : make_uint4(0u, 0u, 0u, 0u);
+            for (int ps = 0; ps < TNt / RPP; ++ps) R.b[ps] = *reinterpret_cast<const uint4 *>(B.p + bcrow[ps] * B.ld + kc);
         } else {
             // columns past the matrix read its last pair: they only feed outputs the epilogue drops
             const int cp = t & 63;
