@@ -233,15 +233,18 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
 
     auto load_rows = [&](int64_t k0) {
         if (!KC) {
-            const int ko = (t >> 6) * 8;
+            // a wavefront's 8 rows are the same in every lane: lane kk fetches row kk's indices, and reading
+            // them back lane by lane leaves them in scalar registers, so that the row addresses are scalar
+            // arithmetic and the loads take a scalar base plus the lane's column offset
+            const int ko = __builtin_amdgcn_readfirstlane((t >> 6) * 8);
+            const int64_t rl = k0 + ko + (lane & 7), rcl = rl < kend ? rl : kend - 1;
+            const int32_t bi = B.idx ? B.idx[rcl] : (int32_t)rcl, ai = A.idx ? A.idx[rcl] : (int32_t)rcl;
             kmask = 0u;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                const int64_t r = k0 + ko + kk;
-                const int64_t rc = r < kend ? r : kend - 1;
-                kmask |= (r < kend ? 1u : 0u) << kk;
-                brow[kk] = B.idx ? B.idx[rc] : (int32_t)rc;
-                akrow[kk] = A.idx ? A.idx[rc] : (int32_t)rc;
+                kmask |= (k0 + ko + kk < kend ? 1u : 0u) << kk;
+                brow[kk] = __builtin_amdgcn_readlane(bi, kk);
+                akrow[kk] = __builtin_amdgcn_readlane(ai, kk);
             }
         }
     };
