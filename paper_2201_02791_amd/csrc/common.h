@@ -71,6 +71,10 @@ struct kge_partition {
     // matrix [X; Z]: a run of a single edge has its source's row of X as its mean (row col_src), any other
     // run row N + s.  NULL if N + S does not fit 31 bits.
     int32_t *seg_zrow;
+    // the runs of two or more edges, ascending (the only ones whose mean is computed when single-edge runs
+    // are read in place); allocated together with seg_zrow
+    int64_t n_mrun;
+    int32_t *mrun;
 };
 #define KGE_REL_CHUNK 2048
 #define KGE_REL_TILE 128

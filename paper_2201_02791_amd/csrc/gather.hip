@@ -609,8 +609,10 @@ template <bool BF16, int LPR, int RPW>
 __global__ __launch_bounds__(64 * WPB) void k_run_mean_multi(
     const int32_t *__restrict__ seg_ptr, const int32_t *__restrict__ seg_dst,
     const float *__restrict__ inv_c, const int32_t *__restrict__ col_src, int64_t S,
-    const void *__restrict__ H, int32_t d, void *__restrict__ Z, const uint8_t *__restrict__ active, int skip_single)
+    const void *__restrict__ H, int32_t d, void *__restrict__ Z, const uint8_t *__restrict__ active, int skip_single,
+    const int32_t *__restrict__ run_list)
 {
+    // run_list (optional): the wavefronts walk runs run_list[0 .. S) instead of runs 0 .. S
     constexpr int VEC = MsgRow<BF16>::VEC;
     constexpr int NG = 64 / LPR;
     constexpr int PER = RPW / NG;                          // runs per lane group
@@ -620,18 +622,26 @@ __global__ __launch_bounds__(64 * WPB) void k_run_mean_multi(
     if (s0 >= S) return;
     const int kl = lane % LPR, g = lane / LPR;
     const bool kact = kl * VEC < d;
-    // bounds of the RPW runs: lanes 0 .. RPW hold seg_ptr[s0 + lane]
-    int32_t pv = 0;
-    if (lane <= RPW) pv = seg_ptr[min(s0 + lane, S)];
-    int32_t beg[PER], len[PER], src0[PER];
+    // bounds of the RPW runs: lanes 0 .. RPW hold seg_ptr[s0 + lane]; with a list, lane r holds its run's
+    // id and both of its bounds
+    int32_t pv = 0, pe = 0, pid = 0;
+    if (run_list) {
+        if (lane < RPW && s0 + lane < S) { pid = run_list[s0 + lane]; pv = seg_ptr[pid]; pe = seg_ptr[pid + 1]; }
+    } else if (lane <= RPW) {
+        pv = seg_ptr[min(s0 + lane, S)];
+    }
+    int32_t beg[PER], len[PER], src0[PER], rid[PER];
     float w[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
         const int r = i * NG + g;
-        const int32_t b = __shfl(pv, r, 64), e = __shfl(pv, r + 1, 64);
-        const int64_t sr = s0 + r;
+        const int32_t b = __shfl(pv, r, 64), e1 = __shfl(pv, r + 1, 64), e2 = __shfl(pe, r, 64), id = __shfl(pid, r, 64);
+        const int32_t e = run_list ? e2 : e1;
+        const bool exists = s0 + r < S;
+        const int64_t sr = run_list ? (int64_t)id : s0 + r;
+        rid[i] = (int32_t)sr;
         beg[i] = b;
-        len[i] = sr < S ? e - b : -1;                      // -1: no such run
+        len[i] = exists ? e - b : -1;                      // -1: no such run
         w[i] = 0.f;
         src0[i] = 0;
         if (len[i] >= KGE_HEAVY) len[i] = -1;              // written by the finishing kernel
@@ -667,7 +677,7 @@ __global__ __launch_bounds__(64 * WPB) void k_run_mean_multi(
             for (int v = 0; v < VEC; ++v) acc[v] += va[v] + vb[v];
         }
         if (!kact) continue;
-        const int64_t o = (s0 + i * NG + g) * d + kl * VEC;
+        const int64_t o = (int64_t)rid[i] * d + kl * VEC;
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] *= w[i];
         if (BF16) {
@@ -1110,6 +1120,9 @@ int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, i
 {
     const int64_t S = p->n_seg;
     if (S == 0) return KGE_OK;
+    // single-edge runs skipped: only the listed runs of two or more edges are visited
+    const int32_t *run_list = skip_single && p->mrun ? p->mrun : nullptr;
+    const int64_t n_visit = run_list ? p->n_mrun : S;
     const int vec = bf16 ? 8 : 4;
     const int lpr = pow2_at_least((d + vec - 1) / vec);
     KGE_REQUIRE(lpr <= 64, KGE_EINVAL, "feature width %d too large for the run-mean kernel", d);
@@ -1119,8 +1132,8 @@ int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, i
         // still take the heavy runs (it is launched with no light rows)
         constexpr int RPW = 8;
         KGE_PROF("run_mean", st);
-        const unsigned gridm = (unsigned)cdiv(cdiv(S, RPW), WPB);
-#define RMM_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, H, d, Z, active, skip_single
+        const unsigned gridm = (unsigned)cdiv(cdiv(n_visit, RPW), WPB);
+#define RMM_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, n_visit, H, d, Z, active, skip_single, run_list
         if (bf16) { DISPATCH_LPR(lpr, (k_run_mean_multi<true, (L < 8 ? 8 : L), RPW><<<gridm, 64 * WPB, 0, st>>>(RMM_ARGS))); }
         else { DISPATCH_LPR(lpr, (k_run_mean_multi<false, (L < 8 ? 8 : L), RPW><<<gridm, 64 * WPB, 0, st>>>(RMM_ARGS))); }
 #undef RMM_ARGS

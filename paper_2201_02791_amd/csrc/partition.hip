@@ -380,6 +380,18 @@ __global__ void k_seg_zrow(const int32_t *seg_ptr, const int32_t *col_src, int64
     zrow[s] = seg_ptr[s + 1] - b == 1 ? col_src[b] : N + (int32_t)s;
 }
 
+__global__ void k_multi_flag(const int32_t *seg_ptr, int64_t S, uint32_t *flag)
+{
+    int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s < S) flag[s] = seg_ptr[s + 1] - seg_ptr[s] >= 2 ? 1u : 0u;
+}
+
+__global__ void k_multi_emit(const uint32_t *flag, const uint32_t *pos, int64_t S, int32_t *mrun)
+{
+    int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s < S && flag[s]) mrun[pos[s]] = (int32_t)s;
+}
+
 __global__ void k_inv_c(const int32_t *seg_ptr, int64_t S, float *inv_c)
 {
     int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -667,6 +679,16 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
         TRY(palloc(&p->seg_zrow, S));
         k_seg_zrow<<<grid_for(S), TB, 0, st>>>(p->seg_ptr, p->col_src, S, (int32_t)N, p->seg_zrow);
         KGE_LAUNCH_CHECK();
+        uint32_t *mflag, *mpos;
+        TRY(tmp.alloc(&mflag, S)); TRY(tmp.alloc(&mpos, (size_t)S + 1));
+        k_multi_flag<<<grid_for(S), TB, 0, st>>>(p->seg_ptr, S, mflag);
+        KGE_LAUNCH_CHECK();
+        TRY(exclusive_scan(mflag, mpos, S, st));
+        uint32_t n_multi = 0;
+        KGE_HIP(hipMemcpy(&n_multi, mpos + S, sizeof(uint32_t), hipMemcpyDeviceToHost));
+        p->n_mrun = n_multi;
+        TRY(palloc(&p->mrun, n_multi));
+        if (n_multi > 0) { k_multi_emit<<<grid_for(S), TB, 0, st>>>(mflag, mpos, S, p->mrun); KGE_LAUNCH_CHECK(); }
     }
     TRY(palloc(&p->rel_ptr, (size_t)2 * n_rel + 1));
     k_ptr_from_sorted<int32_t><<<grid_for(S + 1), TB, 0, st>>>(p->seg_rel, S, 2 * (int64_t)n_rel, p->rel_ptr);
@@ -788,7 +810,7 @@ extern "C" void kge_partition_destroy(kge_partition *p)
                     p->hv_seg.hv_row, p->hv_seg.hv_unit_ptr, p->hv_seg.unit_hv,
                     p->dr_ptr, p->dr_seg, p->dr_rel, p->hv_dr.hv_row, p->hv_dr.hv_unit_ptr, p->hv_dr.unit_hv,
                     p->relc_rel, p->relc_beg, p->relc_end, p->sm_seg, p->relt_rel, p->relt_beg, p->relt_end,
-                    p->seg_zrow};
+                    p->seg_zrow, p->mrun};
     for (void *q : arrs) if (q) (void)hipFree(q);
     delete p;
 }
