@@ -165,17 +165,16 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
             for (int u = 0; u < U; ++u) {
                 const int el = er * GE + ge;
                 const int b = bi * GB + gb;
+                // a slot past the end repeats the chunk's first edge with coefficient 0, and a lane past the
+                // row's width reads its start: every load is unconditional (no divergent branch around it)
                 const bool ok = (q0 + u < items) && el < cnt && b < B;
-                const int els = ok ? el : 0;
+                const int els = ok ? el : 0, bs = ok ? b : 0;
                 const int32_t src = __shfl(my_src, els, 64);
                 const int32_t rel = __shfl(my_rel, els, 64);
                 const float w = __shfl(my_w, els, 64);
-                coef[u] = 0.f;
-                raw[u] = make_uint4(0u, 0u, 0u, 0u);
-                if (ok) {
-                    coef[u] = PLAIN ? w : a[(int64_t)rel * B + b] * w;
-                    if (kact) raw[u] = MsgRow<BF16>::load_raw(P, ((int64_t)src * B + b) * d + kl * VEC);
-                }
+                const float cf = PLAIN ? w : a[(int64_t)rel * B + bs] * w;
+                coef[u] = ok ? cf : 0.f;
+                raw[u] = MsgRow<BF16>::load_raw(P, ((int64_t)src * B + bs) * d + (kact ? kl * VEC : 0));
                 if (++bi == nb) { bi = 0; ++er; }
             }
 #pragma unroll
