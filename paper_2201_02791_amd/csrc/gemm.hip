@@ -219,9 +219,9 @@ __global__ __launch_bounds__(GT) void k_gemm(SA srcA, SB srcB, EPI epi, int64_t 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
-        // ---- global -> registers
-        float4 ra[2], rb[2];
+    // ---- global -> registers: the chunk after the one being multiplied is always in flight
+    float4 ra[2], rb[2];
+    auto fetch = [&](int64_t k0) {
 #pragma unroll
         for (int ps = 0; ps < 2; ++ps) {
             if (A_KCONTIG) {
@@ -239,6 +239,9 @@ __global__ __launch_bounds__(GT) void k_gemm(SA srcA, SB srcB, EPI epi, int64_t 
                 rb[ps] = (k0 + k < kend) ? srcB.load4(k0 + k, n0 + n4) : make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
+    };
+    if (kbeg < kend) fetch(kbeg);
+    for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
         __syncthreads();      // previous tile fully consumed
 #pragma unroll
         for (int ps = 0; ps < 2; ++ps) {
@@ -260,6 +263,7 @@ __global__ __launch_bounds__(GT) void k_gemm(SA srcA, SB srcB, EPI epi, int64_t 
             }
         }
         __syncthreads();
+        if (k0 + BK < kend) fetch(k0 + BK);
         // ---- LDS -> matrix cores.  32x32x2: lane l supplies A[m = l%32][k = l/32], B[k = l/32][n = l%32]
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
