@@ -220,8 +220,9 @@ def test_bf16_aggregate_first_intermediates(kb, orc):
 
 @pytest.mark.parametrize("order", [pytest.param(0, id="project_first")] + ORDERS)
 @pytest.mark.parametrize("dims,bf16", [((128, 32, 32), False), ((48, 96, 24), False), ((128, 32, 32), True),
-                                       ((64, 128, 64), True)],
-                         ids=["f32_128_32_32", "f32_48_96_24", "bf16_128_32_32", "bf16_64_128_64"])
+                                       ((64, 128, 64), True), ((200, 40, 72), True), ((8, 248, 16), True)],
+                         ids=["f32_128_32_32", "f32_48_96_24", "bf16_128_32_32", "bf16_64_128_64",
+                              "bf16_200_40_72_ragged_tiles", "bf16_8_248_16_ragged_tiles"])
 def test_feature_layer_with_different_widths(kb, orc, order, dims, bf16):
     """A feature-input layer whose width differs from the embedding width (the paper's large-graph
     setting: 128-d features, 32-d embeddings), and a widening layer, in every order."""
