@@ -278,22 +278,29 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
 #pragma unroll
             for (int ps = 0; ps < TNt / RPP; ++ps) R.b[ps] = *reinterpret_cast<const uint4 *>(B.p + bcrow[ps] * B.ld + kc);
         } else {
-            // columns past the matrix read its last pair: they only feed outputs the epilogue drops
+            // columns past the matrix read its last pair: they only feed outputs the epilogue drops.  The row
+            // bases are scalar (see load_rows); the column offsets are unsigned 32-bit byte offsets, so the
+            // loads take the scalar-base form and need no address arithmetic of their own
             const int cp = t & 63;
-            const int32_t ca0 = (int32_t)(m0 + 2 * cp), ca = ca0 < A.cols ? ca0 : A.cols - 2;
+            const int32_t ca0 = (int32_t)(m0 + 2 * cp);
+            const uint32_t ca_b = (uint32_t)(ca0 < A.cols ? ca0 : A.cols - 2) * 2u;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                const uint32_t v = *reinterpret_cast<const uint32_t *>(A.p + (int64_t)akrow[kk] * A.ld + ca);
+                const char *arp = reinterpret_cast<const char *>(A.p + (int64_t)akrow[kk] * A.ld);
+                const uint32_t v = *reinterpret_cast<const uint32_t *>(arp + ca_b);
                 R.pa[kk] = (kmask >> kk) & 1u ? v : 0u;
+            }
+            uint32_t cb_b[NJ / 2];
+#pragma unroll
+            for (int ps = 0; ps < NJ / 2; ++ps) {
+                const int32_t cb0 = n0 + 2 * (cp + ps * 64);
+                cb_b[ps] = (uint32_t)(cb0 < B.cols ? cb0 : B.cols - 2) * 2u;
             }
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                const uint16_t *brp = B.p + (int64_t)brow[kk] * B.ld;
+                const char *brp = reinterpret_cast<const char *>(B.p + (int64_t)brow[kk] * B.ld);
 #pragma unroll
-                for (int ps = 0; ps < NJ / 2; ++ps) {
-                    const int32_t cb0 = n0 + 2 * (cp + ps * 64), cb = cb0 < B.cols ? cb0 : B.cols - 2;
-                    R.pb[ps][kk] = *reinterpret_cast<const uint32_t *>(brp + cb);
-                }
+                for (int ps = 0; ps < NJ / 2; ++ps) R.pb[ps][kk] = *reinterpret_cast<const uint32_t *>(brp + cb_b[ps]);
             }
         }
     };
