@@ -27,7 +27,8 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0
 
 def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None, spec_order="project", single_runs=0):
     """Algorithmic bytes / flops of ONE launch of a kernel (what the method itself must move
-    or compute in this formulation).  Returns (bound, work).  cone: None, or the per-layer counts
+    or compute in this formulation).  Returns (bound, work); the grouped contractions return
+    ("mfma", flops, bytes) and the caller reports whichever ceiling binds.  cone: None, or the per-layer counts
     (active vertices, edges into them, runs into them) of the batch's computational sub-graph;
     the figure is then the mean over the layers' launches."""
     N, E, S = part.n_vert, part.n_edge, part.n_seg
@@ -69,8 +70,8 @@ def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None, spec_order=
         eo = E if cone is None else (sum(c[3] for c in cone[:-1]) + (0 if spec.fixed_features else E)) / max(
             len(cone) - (1 if spec.fixed_features else 0), 1)
         return "hbm", eo * (ep * d + 8.0) + N * (4.0 + 8.0 * d)
-    if name in ("apply_rel", "apply_rel_t"):    # one (d x d) product per run
-        return "mfma", 2.0 * S * d * d
+    if name in ("apply_rel", "apply_rel_t"):    # one (d x d) product per run: a row read and a row written per run
+        return "mfma", 2.0 * S * d * d, S * 2.0 * d * ep + R2 * d * d * ep
     if name == "rel_weights" or name == "basis_grad":
         return "alu", 2.0 * R2 * B * d * d
     if name == "optimizer":    # dense tensors: p, g, m, v read, p, m, v written; small here, no figure given
@@ -79,8 +80,8 @@ def kernel_work(name, part, spec, d, B, ep, n_pos, n_neg, cone=None, spec_order=
         return "hbm", N * d * 4.0 + nv_mean * d * 24.0
     if name == "combine":
         return "mfma", gemm_flops
-    if name == "rel_outer":    # C_r = sum_runs z^T G: 2 S d^2 flops; bytes S (2 d) 4
-        return "mfma", 2.0 * S * d * d
+    if name == "rel_outer":    # C_r = sum_runs z^T G: 2 S d^2 flops; two rows read per run, C_r accumulated once
+        return "mfma", 2.0 * S * d * d, S * 2.0 * d * ep + R2 * d * d * 4.0
     if name == "coeff_contract":
         return "mfma", 2.0 * R2 * d * d * B
     if spec_order == "relation":      # only the self-loop term W_0 goes through these
@@ -332,8 +333,17 @@ def main():
     ep = 2 if spec.msg_dtype == "bf16" else 4
     kernels = {}
     for name, (tot_ms, calls) in prof.items():
-        bound, work = kernel_work(name, part, spec, spec.d, spec.n_bases, ep, n_pos, n_neg, cone, args.order, single_runs)
+        kw = kernel_work(name, part, spec, spec.d, spec.n_bases, ep, n_pos, n_neg, cone, args.order, single_runs)
+        bound, work = kw[0], kw[1]
         avg_ms = tot_ms / max(calls, 1)
+        mfma_frac = None
+        if len(kw) == 3:
+            # a contraction with a byte figure: the roofline that binds is the one that takes longer at its peak
+            # (flops / matrix-core peak against bytes / HBM peak), i.e. HBM below the ridge intensity
+            peak_t = (PEAK_BF16_MFMA_TFLOPS if ep == 2 else PEAK_F32_MFMA_TFLOPS) * 1e12
+            mfma_frac = kw[1] / (avg_ms * 1e-3) / peak_t
+            if kw[2] / (PEAK_HBM_GBS * 1e9) > kw[1] / peak_t:
+                bound, work = "hbm", kw[2]
         if bound == "hbm":
             ach, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
         elif bound == "alu":
@@ -344,6 +354,8 @@ def main():
         kernels[name] = {"ms_per_step": tot_ms / args.steps, "launches_per_step": calls / args.steps,
                          "avg_ms": avg_ms, "bound": bound, "achieved": ach, "peak": peak, "unit": unit,
                          "frac": ach / peak if peak else None}
+        if mfma_frac is not None:
+            kernels[name]["frac_of_mfma_peak"] = mfma_frac
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"]) if kernels else None
     roof = None
     if dominant:
@@ -351,6 +363,8 @@ def main():
         traffic = measured_traffic(args.config, dominant)
         roof = {"kernel": dominant, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
                 "unit": kd["unit"], "frac": kd["frac"], "traffic": traffic, "avg_launch_ms": kd["avg_ms"]}
+        if "frac_of_mfma_peak" in kd:
+            roof["frac_of_mfma_peak"] = kd["frac_of_mfma_peak"]
         if traffic and kd["bound"] != "hbm":
             # a contraction under the matrix cores' ridge: its measured traffic at the HBM peak, for comparison
             roof["hbm_floor_ms"] = traffic / (PEAK_HBM_GBS * 1e9) * 1e3
