@@ -326,25 +326,26 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t(
                     rel = __shfl(my_rel, els, 64);
                     ww = __shfl(my_w, els, 64);
                 }
+                // a slot without an edge (or an edge into a row outside the sub-graph) reads row 0 with weight 0,
+                // a lane past the row's width its start: the load itself is unconditional
                 const bool live = ok && dst >= 0;
                 w[u] = live ? ww : 0.f;
                 arow[u] = a + (int64_t)rel * B;
-                gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (live && kact) {
-                    if (GIN) {
-                        const uint2 x = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(Gv) + (int64_t)dst * d + kl * 4);
-                        gv[u] = make_float4(__uint_as_float(x.x << 16), __uint_as_float(x.x & 0xffff0000u),
-                                            __uint_as_float(x.y << 16), __uint_as_float(x.y & 0xffff0000u));
-                    } else {
-                        gv[u] = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(Gv) + (int64_t)dst * d + kl * 4);
-                    }
+                const int64_t goff = (int64_t)(live ? dst : 0) * d + (kact ? kl * 4 : 0);
+                if (GIN) {
+                    const uint2 x = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(Gv) + goff);
+                    gv[u] = make_float4(__uint_as_float(x.x << 16), __uint_as_float(x.x & 0xffff0000u),
+                                        __uint_as_float(x.y << 16), __uint_as_float(x.y & 0xffff0000u));
+                } else {
+                    gv[u] = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(Gv) + goff);
                 }
             }
 #pragma unroll
             for (int u = 0; u < UE; ++u)
 #pragma unroll
                 for (int n = 0; n < NB; ++n) {
-                    const float c = (b0 + n < B) ? arow[u][b0 + n] * w[u] : 0.f;
+                    const float cv = arow[u][b0 + n < B ? b0 + n : B - 1];
+                    const float c = (b0 + n < B) ? cv * w[u] : 0.f;
                     acc[n][0] = fmaf(c, gv[u].x, acc[n][0]); acc[n][1] = fmaf(c, gv[u].y, acc[n][1]);
                     acc[n][2] = fmaf(c, gv[u].z, acc[n][2]); acc[n][3] = fmaf(c, gv[u].w, acc[n][3]);
                 }
