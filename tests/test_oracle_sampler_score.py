@@ -24,6 +24,19 @@ def test_philox_matches_an_independent_library_engine(orc, aten_philox):
         np.testing.assert_array_equal(orc.philox4x32_10(ctr, key), aten_philox(seed, subseq, off))
 
 
+def test_philox_published_known_answers(orc):
+    """The generator's published known-answer vectors (tests/golden/philox4x32_10_kat.txt)."""
+    n = 0
+    for line in open(os.path.join(HERE, "golden", "philox4x32_10_kat.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        w = [int(x, 16) for x in line.split()]
+        assert len(w) == 10
+        np.testing.assert_array_equal(orc.philox4x32_10(w[0:4], w[4:6]), np.array(w[6:10], np.uint32))
+        n += 1
+    assert n == 3
+
+
 def test_philox_avalanche_and_bit_balance(orc):
     # A one-bit change of counter or key flips about half of the 128 output bits.
     rng = np.random.default_rng(1)
