@@ -7,8 +7,8 @@ import numpy as np
 import pytest
 
 from paper_2201_02791_amd import synth
-from gpu_util import (SEED, STEP, assert_partition_equal, assert_step_close, gpu_step, layers_of,
-                      oracle_step, rel_err)
+from gpu_util import (SEED, STEP, align_mask_decisions, assert_partition_equal, assert_step_close, gpu_step,
+                      layers_of, oracle_step, rel_err)
 
 pytestmark = pytest.mark.gpu
 
@@ -232,6 +232,37 @@ def test_config0_tiny_whole_step(kb, orc):
     assert (gp.n_vert, gp.n_edge) == (1000, 10000)
     assert_partition_equal(gp, op)
     assert_step_close(ts, res, TOL_VAL, TOL_GRAD)
+
+
+@pytest.fixture(scope="module")
+def config1_oracle(orc):
+    """configs[1] (the whole 14,541-entity graph as one partition, 30,000 positives x 10 negatives):
+    the oracle's whole step, computed once for the three evaluation orders."""
+    spec = synth.WORKLOADS[1]
+    head, rel, tail = synth.make_triples(spec)
+    op = orc.build_partition(head, rel, tail, spec.n_entities, spec.n_relations, spec.n_parts, spec.part_id,
+                             spec.n_hops, spec.neg_domain)
+    params = synth.make_params(spec, op["n_vert"])
+    pos = synth.make_batch(spec, op["n_core"])
+    say("config 1 oracle step")
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
+    return spec, (head, rel, tail), params, pos, op, res
+
+
+@pytest.mark.parametrize("order", [0, 1, 2], ids=["project_first", "aggregate_first", "relation_weights"])
+def test_config1_mid_whole_graph_step(kb, orc, config1_oracle, order):
+    spec, (head, rel, tail), params, pos, op, res = config1_oracle
+    say("config 1", spec.name, "order", order)
+    gp, ts, _, _ = gpu_step(spec, head, rel, tail, params=params, pos=pos, order=order)
+    assert (gp.n_vert, gp.n_core) == (14541, 272115)       # one partition = the whole graph
+    assert_partition_equal(gp, op)
+    # 2.9 M pre-activations: one within fp32 rounding of zero (|pre| < 1e-5 of the largest) may take the
+    # other side in the kernel's fp32 sum; the ReLU decision is then taken in the kernel's precision
+    n_adopted, res = align_mask_decisions(orc, ts, op, res, params, spec.acts, True, 0, thresh=1e-5)
+    say("config 1 adopted ReLU decisions", n_adopted)
+    assert n_adopted <= 8
+    errs = assert_step_close(ts, res, TOL_VAL, TOL_GRAD)
+    say("config 1 errs", errs)
 
 
 def test_config2_mid_partition_whole_step(kb, orc):
