@@ -156,13 +156,18 @@ __device__ __forceinline__ void transpose_pairs(const uint32_t (&pr)[8], uint4 &
 // per CU) or 128 (64 x 64: four blocks per CU, for contractions too short to hide their own latency).
 // TKt: contraction depth of a tile, 32 or (k-contiguous operands only) 64: with 64 a row's piece of a
 // tile is a whole 128-byte line, and one tile instead of two is in flight in registers.
+// TR (k-strided operands only): tiles go to LDS as they lie in memory, k-major, by 16-byte loads and stores, and
+// the matrix-core operands are fetched with the transposing LDS read of gfx950 (ds_read_b64_tr_b16: within 16
+// lanes, lane l receives the l-th 16-bit column of the 4 x 16 block whose four rows lanes 0-3, 4-7, 8-11 and
+// 12-15 address 4 columns at a time).  No transposes in registers, a quarter of the load instructions.  The
+// launcher checks that columns and pitches are multiples of 8 elements.
 // MT (k-contiguous operands with a tile list only): a block takes `tpb` consecutive row tiles of the list
 // (`tiles_m` then counts such groups and `n_mt` the tiles), and the first loads of the next tile are issued in
 // place of the refills that the current tile's last steps have no use for, so that they are in flight while the
 // current tile's results go out.  Its loads carry no clamps: the launcher checks that the contraction is a whole
 // number of PF * TKt deep rounds over all of A's columns, that B is un-indexed with a multiple of RPP rows in one
 // column tile, and that A's (indexed) rows are below 2^31.
-template <bool KC, class EPI, int TNt = TN, int TKt = TK, bool MT = false>
+template <bool KC, class EPI, int TNt = TN, int TKt = TK, bool MT = false, bool TR = false>
 __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, int64_t K, int64_t kchunk,
                                                      int32_t tiles_m, int32_t tiles_n, int32_t n_splits,
                                                      const int32_t *__restrict__ g_id,
@@ -180,6 +185,13 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
     constexpr int PF = TKt == TK ? 2 : 1;        // tiles in flight in registers
     static_assert(KC || TKt == TK, "k-strided operands use the 32-deep tile");
     static_assert(KC || !MT, "several row tiles per block: k-contiguous operands only");
+    static_assert(!KC || !TR, "transposing LDS reads: k-strided operands only");
+    // TR: LDS rows of TM + 32 and TNt + 32 elements (pitches of 64 bytes modulo 256: the four rows that 16 lanes
+    // read at once fall in four different quarters of the banks)
+    constexpr int PA = TM + 32, PB = TNt + 32;
+    constexpr int LRA = TM / 8, LRB = TNt / 8;             // lanes per tile row, 8 elements each
+    constexpr int RA = NT / LRA, RB = NT / LRB;            // tile rows per pass of the block
+    constexpr int NLA = TR ? TK / RA : 1, NLB = TR ? TK / RB : 1;   // loads per thread and tile
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint16_t (*As)[LDKt] = reinterpret_cast<uint16_t (*)[LDKt]>(smem);
     uint16_t (*Bs)[LDKt] = reinterpret_cast<uint16_t (*)[LDKt]>(smem + TM * LDKt * 2);
@@ -229,7 +241,10 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
     // matrix-core loop.  Rows picked through an index list have their indices fetched one tile
     // earlier still, which keeps the row loads themselves independent.
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));     // 16 bytes as a plain vector value
-    struct Regs { u32x4 a[KC ? TM / RPP : 1], b[KC ? TNt / RPP : 1]; uint32_t pa[KC ? 1 : 8], pb[KC ? 1 : NJ / 2][KC ? 1 : 8]; };
+    struct Regs {
+        u32x4 a[KC ? TM / RPP : NLA], b[KC ? TNt / RPP : NLB];
+        uint32_t pa[KC || TR ? 1 : 8], pb[KC || TR ? 1 : NJ / 2][KC || TR ? 1 : 8];
+    };
     Regs rg[PF];
     // KC = false: stored rows of B and of A for the tile that is loaded next.  A k past the range's end takes
     // the range's last row instead (kend <= rows of both operands) and clears its bit in kmask: every load is
@@ -237,9 +252,24 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
     // makes the product vanish whatever finite row B repeats.
     int32_t brow[8], akrow[8];
     uint32_t kmask = 0u;
+    int32_t tai[NLA], tbi[NLB];      // TR: the same, per load of this thread (16 or 32 lanes share a row)
+    uint16_t *As2 = reinterpret_cast<uint16_t *>(smem), *Bs2 = As2 + TK * PA;
 
     auto load_rows = [&](int64_t k0) __attribute__((always_inline)) {
-        if (!KC) {
+        if constexpr (TR) {
+            kmask = 0u;
+#pragma unroll
+            for (int i = 0; i < NLA; ++i) {
+                const int64_t rl = k0 + t / LRA + RA * i, rcl = rl < kend ? rl : kend - 1;
+                tai[i] = A.idx ? A.idx[rcl] : (int32_t)rcl;
+                kmask |= (rl < kend ? 1u : 0u) << i;
+            }
+#pragma unroll
+            for (int i = 0; i < NLB; ++i) {
+                const int64_t rl = k0 + t / LRB + RB * i, rcl = rl < kend ? rl : kend - 1;
+                tbi[i] = B.idx ? B.idx[rcl] : (int32_t)rcl;
+            }
+        } else if (!KC) {
             // a wavefront's 8 rows are the same in every lane: lane kk fetches row kk's indices, and reading
             // them back lane by lane leaves them in scalar registers, so that the row addresses are scalar
             // arithmetic and the loads take a scalar base plus the lane's column offset
@@ -311,6 +341,17 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             }
 #pragma unroll
             for (int ps = 0; ps < TNt / RPP; ++ps) R.b[ps] = *reinterpret_cast<const u32x4 *>(Bp + bcrow[ps] * B.ld + kc);
+        } else if constexpr (TR) {
+            // 8 consecutive columns of one row per load; an octet past the matrix reads its last octet instead
+            const int32_t ca0 = (int32_t)m0 + (t % LRA) * 8, ca = ca0 + 8 <= A.cols ? ca0 : A.cols - 8;
+            const int32_t cb0 = n0 + (t % LRB) * 8, cb = cb0 + 8 <= B.cols ? cb0 : B.cols - 8;
+#pragma unroll
+            for (int i = 0; i < NLA; ++i) {
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(A.p + (int64_t)tai[i] * A.ld + ca);
+                R.a[i] = (kmask >> i) & 1u ? v : u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int i = 0; i < NLB; ++i) R.b[i] = *reinterpret_cast<const u32x4 *>(Bp + (int64_t)tbi[i] * B.ld + cb);
         } else {
             // columns past the matrix read its last pair: they only feed outputs the epilogue drops.  The row
             // bases are scalar (see load_rows); the column offsets are unsigned 32-bit byte offsets, so the
@@ -345,6 +386,13 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             for (int ps = 0; ps < TM / RPP; ++ps) *reinterpret_cast<u32x4 *>(&As[row + ps * RPP][ko]) = R.a[ps];
 #pragma unroll
             for (int ps = 0; ps < TNt / RPP; ++ps) *reinterpret_cast<u32x4 *>(&Bs[row + ps * RPP][ko]) = R.b[ps];
+        } else if constexpr (TR) {
+#pragma unroll
+            for (int i = 0; i < NLA; ++i)
+                *reinterpret_cast<u32x4 *>(&As2[(t / LRA + RA * i) * PA + (t % LRA) * 8]) = R.a[i];
+#pragma unroll
+            for (int i = 0; i < NLB; ++i)
+                *reinterpret_cast<u32x4 *>(&Bs2[(t / LRB + RB * i) * PB + (t % LRB) * 8]) = R.b[i];
         } else {
             const int cp = t & 63, ko = (t >> 6) * 8;
             uint4 c0, c1;
@@ -360,6 +408,33 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
         }
     };
     auto mma_tile = [&]() __attribute__((always_inline)) {
+        if constexpr (TR) {
+            typedef short s16x4 __attribute__((ext_vector_type(4)));
+            // lane -> (row lane % 32 of the 32-row operand tile, k-group lane / 32); as an addressing lane of its
+            // group of 16 it points at k-row (lane % 16) / 4 of the group's four and at columns 4 (lane % 4) ...
+            const int l16 = lane & 15, kr0 = 8 * (lane >> 5) + (l16 >> 2), mc = 16 * ((lane >> 4) & 1) + 4 * (l16 & 3);
+            auto frag = [&](const uint16_t *tile, int pitch, int kr, int col) __attribute__((always_inline)) {
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (s16x4 __attribute__((address_space(3))) *)(tile + kr * pitch + col));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (s16x4 __attribute__((address_space(3))) *)(tile + (kr + 4) * pitch + col));
+                return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            };
+#pragma unroll
+            for (int ks = 0; ks < TKt; ks += 16) {
+                bf16x8 af[2], bfr[NJ];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) af[i] = frag(As2, PA, ks + kr0, wm * 64 + i * 32 + mc);
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) bfr[j] = frag(Bs2, PB, ks + kr0, wn * (TNt / 2) + j * 32 + mc);
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            }
+            return;
+        }
 #pragma unroll
         for (int ks = 0; ks < TKt; ks += 16) {
             const int kc = ks + 8 * (lane >> 5);
@@ -545,7 +620,7 @@ __global__ __launch_bounds__(256) void k_cvt_group_mats(const float *__restrict_
     }
 }
 
-template <bool KC, class EPI, int TNt = TN, int TKt = TK, bool MT = false>
+template <bool KC, class EPI, int TNt = TN, int TKt = TK, bool MT = false, bool TR = false>
 int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64_t kchunk, int32_t tiles_m,
                 int32_t tiles_n, int64_t splits, hipStream_t st, const int32_t *g_id = nullptr,
                 const int32_t *g_beg = nullptr, const int32_t *g_end = nullptr, const int32_t *mt_id = nullptr,
@@ -564,19 +639,30 @@ int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64
     const int64_t n_patches = cdiv(splits * tiles_m, pm) * cdiv(tiles_n, pn);
     const int64_t blocks = cdiv(n_patches, 8) * 8 * 64;
     KGE_REQUIRE(blocks < 0x7fffffffLL, KGE_ERANGE, "grid too large");
-    const size_t lds_main = (size_t)(TM + TNt) * (TKt == 32 ? 40 : 88) * 2, lds_epi = (size_t)4 * 32 * (TNt / 2) * 4;
+    if (TR)
+        KGE_REQUIRE(A.cols >= 8 && B.cols >= 8 && A.cols % 8 == 0 && B.cols % 8 == 0 && A.ld % 8 == 0 && B.ld % 8 == 0 &&
+                        reinterpret_cast<uintptr_t>(A.p) % 16 == 0 && reinterpret_cast<uintptr_t>(B.p) % 16 == 0 &&
+                        b_group_stride % 8 == 0,
+                    KGE_EINVAL, "shape not supported by the 16-byte k-strided loader");
+    const size_t lds_main = TR ? (size_t)TK * (TM + 32 + TNt + 32) * 2 : (size_t)(TM + TNt) * (TKt == 32 ? 40 : 88) * 2, lds_epi = (size_t)4 * 32 * (TNt / 2) * 4;
     const size_t lds = EPI::staged ? (lds_epi > lds_main ? lds_epi : lds_main) : lds_main;
     static bool attr_set = false;
     if (!attr_set) {
-        KGE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<KC, EPI, TNt, TKt, MT>),
+        KGE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<KC, EPI, TNt, TKt, MT, TR>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    k_gemm_bf16<KC, EPI, TNt, TKt, MT><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n,
+    k_gemm_bf16<KC, EPI, TNt, TKt, MT, TR><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n,
                                                                 (int32_t)splits, g_id, g_beg, g_end, mt_id, mt_beg, mt_end,
                                                                 b_group_stride, tpb, n_mt);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
+}
+
+// rows that 16-byte loads can walk: whole octets, 16-byte aligned (the k-strided loader with transposing LDS reads)
+bool octet_rows(const MatBF &M)
+{
+    return M.cols >= 8 && M.cols % 8 == 0 && M.ld % 8 == 0 && reinterpret_cast<uintptr_t>(M.p) % 16 == 0;
 }
 
 }  // namespace
@@ -648,6 +734,8 @@ int launch_weight_grad_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_
     MatBF Bm{reinterpret_cast<const uint16_t *>(X), N, nc, nc, nullptr};
     EpiWeightGradAtomic ep{dV, dW0, d_in, d_out, B};
     KGE_PROF("weight_grad", st);
+    if (octet_rows(A) && octet_rows(Bm))
+        return launch_gemm<false, EpiWeightGradAtomic, TN, TK, false, true>(A, Bm, ep, N, kchunk, tiles_m, tiles_n, splits, st);
     return launch_gemm<false, EpiWeightGradAtomic>(A, Bm, ep, N, kchunk, tiles_m, tiles_n, splits, st);
 }
 
@@ -703,6 +791,9 @@ int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const int32_t
     MatBF Bm{reinterpret_cast<const uint16_t *>(Gbf), p->n_seg, d_out, ldg, p->seg_dst};
     EpiRelOuterAtomic ep{C, d_in, d_out, 0};
     KGE_PROF("rel_outer", st);
+    if (octet_rows(A) && octet_rows(Bm))
+        return launch_gemm<false, EpiRelOuterAtomic, TN, TK, false, true>(A, Bm, ep, p->n_seg, 0, tiles_m, tiles_n, p->n_relc,
+                                                                         st, p->relc_rel, p->relc_beg, p->relc_end);
     return launch_gemm<false, EpiRelOuterAtomic>(A, Bm, ep, p->n_seg, 0, tiles_m, tiles_n, p->n_relc, st,
                                                  p->relc_rel, p->relc_beg, p->relc_end);
 }
