@@ -61,7 +61,7 @@ struct MatBF {
 };
 
 struct EpiProjectStaged {     // columns < bd -> P (bf16), the rest -> Self (fp32); through LDS
-    static constexpr bool staged = true;
+    static constexpr bool staged = true, packed = false;
     uint16_t *P; float *Self; int64_t rows; int32_t d_out, bd;
     __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store8(int64_t m, int32_t n, const float4 &x, const float4 &y) const
@@ -79,7 +79,7 @@ struct EpiProjectStaged {     // columns < bd -> P (bf16), the rest -> Self (fp3
     __device__ __forceinline__ void store(int64_t, int32_t, float) const {}
 };
 struct EpiWeightGradAtomic {
-    static constexpr bool staged = false;
+    static constexpr bool staged = false, packed = false;
     float *dV, *dW0; int32_t d_in, d_out, B;
     __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
@@ -93,7 +93,7 @@ struct EpiWeightGradAtomic {
     __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
 };
 struct EpiRowMajorF32 {
-    static constexpr bool staged = false;
+    static constexpr bool staged = false, packed = false;
     float *out; int64_t rows; int32_t cols;
     __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
@@ -102,20 +102,25 @@ struct EpiRowMajorF32 {
     }
     __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
 };
-struct EpiRowsBF16Staged {    // out[m][n] as bf16, rows below `rows` only; through LDS for 16-byte stores
-    static constexpr bool staged = true;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));     // 16 bytes as a plain vector value
+
+// out[m][n] as bf16, rows below `rows` only.  `packed`: the kernel forms the product transposed (operands
+// swapped), so that a lane's accumulators hold 4 consecutive columns of one row; they are rounded to bf16 in
+// registers, staged through LDS by 8-byte writes and leave as 16-byte row-contiguous stores.
+struct EpiRowsBF16Staged {
+    static constexpr bool staged = true, packed = true;
     uint16_t *out; int64_t rows; int32_t cols;
     __device__ __forceinline__ void bind(int32_t) {}
-    __device__ __forceinline__ void store8(int64_t m, int32_t n, const float4 &x, const float4 &y) const
+    __device__ __forceinline__ void store_packed(int64_t m, int32_t n, const u32x4 &v) const    // 8 columns from n
     {
         if (m >= rows || n >= cols) return;
-        *reinterpret_cast<uint4 *>(out + m * cols + n) =
-            make_uint4(pack2(x.x, x.y), pack2(x.z, x.w), pack2(y.x, y.y), pack2(y.z, y.w));
+        *reinterpret_cast<u32x4 *>(out + m * cols + n) = v;
     }
+    __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
     __device__ __forceinline__ void store(int64_t, int32_t, float) const {}
 };
 struct EpiActF32 {            // activation, zero rows outside the sub-graph, optional second copy
-    static constexpr bool staged = false;
+    static constexpr bool staged = false, packed = false;
     float *out, *out2; int64_t rows; int32_t cols; int act; const uint8_t *row_active;
     __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
@@ -129,7 +134,7 @@ struct EpiActF32 {            // activation, zero rows outside the sub-graph, op
     __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
 };
 struct EpiRelOuterAtomic {    // C[group] (d_in x d_out) accumulates the chunks of one relation
-    static constexpr bool staged = false;
+    static constexpr bool staged = false, packed = false;
     float *C; int32_t d_in, d_out; int32_t group;
     __device__ __forceinline__ void bind(int32_t g) { group = g; }
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
@@ -240,7 +245,6 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
     // transposed only when they are written to LDS, so that nothing waits for a load before the
     // matrix-core loop.  Rows picked through an index list have their indices fetched one tile
     // earlier still, which keeps the row loads themselves independent.
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));     // 16 bytes as a plain vector value
     struct Regs {
         u32x4 a[KC ? TM / RPP : NLA], b[KC ? TNt / RPP : NLB];
         uint32_t pa[KC || TR ? 1 : 8], pb[KC || TR ? 1 : NJ / 2][KC || TR ? 1 : 8];
@@ -449,7 +453,8 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = EPI::packed ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0)
+                                            : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
         }
     };
     // one step of the pipeline: tile k0 (held in R) goes to LDS and is multiplied; R is refilled with tile
@@ -497,7 +502,31 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
         for (int64_t k0 = kbeg; k0 < kend; k0 += TKt) step(k0, rg[0]);
     }
     // D register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 tile
-    if (EPI::staged) {
+    if constexpr (EPI::packed) {
+        // transposed product: register v of lane l is row l%32, column 8*(v/4) + 4*(l/32) + v%4 of the tile
+        constexpr int SP = TNt / 2 + 8;            // staged row pitch, bf16 elements (16-byte multiple)
+        uint16_t *stage = reinterpret_cast<uint16_t *>(smem) + w * 32 * SP;     // 32 rows per wavefront
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            __syncthreads();             // operand tiles (or the previous row group) no longer needed
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<uint2 *>(&stage[(lane & 31) * SP + j * 32 + 8 * q + 4 * (lane >> 5)]) =
+                        make_uint2(pack2(acc[i][j][4 * q], acc[i][j][4 * q + 1]),
+                                   pack2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
+            __syncthreads();
+            constexpr int LPRW = NJ * 4;             // lanes across a wavefront's row of NJ * 32 columns, 8 each
+#pragma unroll
+            for (int it = 0; it < 32 / (64 / LPRW); ++it) {
+                const int row = it * (64 / LPRW) + lane / LPRW, c8 = (lane % LPRW) * 8;
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(&stage[row * SP + c8]);
+                if (m0 + wm * 64 + i * 32 + row < m_end || !mt_beg)
+                    epi.store_packed(m0 + wm * 64 + i * 32 + row, n0 + wn * (TNt / 2) + c8, v);
+            }
+        }
+    } else if (EPI::staged) {
         constexpr int ELD = TNt / 2;               // floats per staged row: one wavefront's columns
         float *stage = reinterpret_cast<float *>(smem) + w * 32 * ELD;   // 32 rows x 128 columns per wavefront
 #pragma unroll
@@ -644,7 +673,7 @@ int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64
                         reinterpret_cast<uintptr_t>(A.p) % 16 == 0 && reinterpret_cast<uintptr_t>(B.p) % 16 == 0 &&
                         b_group_stride % 8 == 0,
                     KGE_EINVAL, "shape not supported by the 16-byte k-strided loader");
-    const size_t lds_main = TR ? (size_t)TK * (TM + 32 + TNt + 32) * 2 : (size_t)(TM + TNt) * (TKt == 32 ? 40 : 88) * 2, lds_epi = (size_t)4 * 32 * (TNt / 2) * 4;
+    const size_t lds_main = TR ? (size_t)TK * (TM + 32 + TNt + 32) * 2 : (size_t)(TM + TNt) * (TKt == 32 ? 40 : 88) * 2, lds_epi = EPI::packed ? (size_t)4 * 32 * (TNt / 2 + 8) * 2 : (size_t)4 * 32 * (TNt / 2) * 4;
     const size_t lds = EPI::staged ? (lds_epi > lds_main ? lds_epi : lds_main) : lds_main;
     static bool attr_set = false;
     if (!attr_set) {
