@@ -248,6 +248,8 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
     struct Regs {
         u32x4 a[KC ? TM / RPP : NLA], b[KC ? TNt / RPP : NLB];
         uint32_t pa[KC || TR ? 1 : 8], pb[KC || TR ? 1 : NJ / 2][KC || TR ? 1 : 8];
+        uint32_t keep;      // which of a[] are inside the contraction range: applied when the tile goes to LDS, so
+                            // that nothing touches the loaded registers (and waits for them) before that
     };
     Regs rg[PF];
     // KC = false: stored rows of B and of A for the tile that is loaded next.  A k past the range's end takes
@@ -339,10 +341,9 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             const bool kok = k0 + ko < kend && k0 + ko < A.cols;
             const int64_t kc = kok ? k0 + ko : 0;
 #pragma unroll
-            for (int ps = 0; ps < TM / RPP; ++ps) {
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(A.p + (int64_t)arow[ps] * A.ld + kc);
-                R.a[ps] = kok ? v : u32x4{0u, 0u, 0u, 0u};
-            }
+            for (int ps = 0; ps < TM / RPP; ++ps)
+                R.a[ps] = *reinterpret_cast<const u32x4 *>(A.p + (int64_t)arow[ps] * A.ld + kc);
+            R.keep = kok ? 1u : 0u;
 #pragma unroll
             for (int ps = 0; ps < TNt / RPP; ++ps) R.b[ps] = *reinterpret_cast<const u32x4 *>(Bp + bcrow[ps] * B.ld + kc);
         } else if constexpr (TR) {
@@ -350,10 +351,9 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             const int32_t ca0 = (int32_t)m0 + (t % LRA) * 8, ca = ca0 + 8 <= A.cols ? ca0 : A.cols - 8;
             const int32_t cb0 = n0 + (t % LRB) * 8, cb = cb0 + 8 <= B.cols ? cb0 : B.cols - 8;
 #pragma unroll
-            for (int i = 0; i < NLA; ++i) {
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(A.p + (int64_t)tai[i] * A.ld + ca);
-                R.a[i] = (kmask >> i) & 1u ? v : u32x4{0u, 0u, 0u, 0u};
-            }
+            for (int i = 0; i < NLA; ++i)
+                R.a[i] = *reinterpret_cast<const u32x4 *>(A.p + (int64_t)tai[i] * A.ld + ca);
+            R.keep = kmask;
 #pragma unroll
             for (int i = 0; i < NLB; ++i) R.b[i] = *reinterpret_cast<const u32x4 *>(Bp + (int64_t)tbi[i] * B.ld + cb);
         } else {
@@ -387,13 +387,15 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
         if constexpr (KC) {
             const int row = t / TPR, ko = (t % TPR) * 8;
 #pragma unroll
-            for (int ps = 0; ps < TM / RPP; ++ps) *reinterpret_cast<u32x4 *>(&As[row + ps * RPP][ko]) = R.a[ps];
+            for (int ps = 0; ps < TM / RPP; ++ps)
+                *reinterpret_cast<u32x4 *>(&As[row + ps * RPP][ko]) = (MT || R.keep) ? R.a[ps] : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int ps = 0; ps < TNt / RPP; ++ps) *reinterpret_cast<u32x4 *>(&Bs[row + ps * RPP][ko]) = R.b[ps];
         } else if constexpr (TR) {
 #pragma unroll
             for (int i = 0; i < NLA; ++i)
-                *reinterpret_cast<u32x4 *>(&As2[(t / LRA + RA * i) * PA + (t % LRA) * 8]) = R.a[i];
+                *reinterpret_cast<u32x4 *>(&As2[(t / LRA + RA * i) * PA + (t % LRA) * 8]) =
+                    (R.keep >> i) & 1u ? R.a[i] : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int i = 0; i < NLB; ++i)
                 *reinterpret_cast<u32x4 *>(&Bs2[(t / LRB + RB * i) * PB + (t % LRB) * 8]) = R.b[i];
@@ -741,7 +743,7 @@ int launch_project_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out,
     MatBF Bm{reinterpret_cast<const uint16_t *>(WbfT), nc, d_in, d_in, nullptr};
     EpiProjectStaged ep{reinterpret_cast<uint16_t *>(P), Self, N, d_out, B * d_out};
     KGE_PROF("project", st);
-    return launch_gemm<true, EpiProjectStaged>(A, Bm, ep, d_in, cdiv(d_in, TK) * TK, tiles_m, tiles_n, 1, st);
+    return launch_gemm<true, EpiProjectStaged, TN, 64>(A, Bm, ep, d_in, cdiv(d_in, TK) * TK, tiles_m, tiles_n, 1, st);
 }
 
 // d[V | W0] = Hbf^T X     X: bf16 [N][nc] = [dP | G]
@@ -779,7 +781,7 @@ int launch_input_grad_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out
     MatBF Bm{reinterpret_cast<const uint16_t *>(Wbf), d_in, nc, nc, nullptr};
     EpiRowMajorF32 ep{dH, N, d_in};
     KGE_PROF("input_grad", st);
-    return launch_gemm<true, EpiRowMajorF32>(A, Bm, ep, nc, cdiv(nc, TK) * TK, tiles_m, tiles_n, 1, st);
+    return launch_gemm<true, EpiRowMajorF32, TN, 64>(A, Bm, ep, nc, cdiv(nc, TK) * TK, tiles_m, tiles_n, 1, st);
 }
 
 int launch_cvt_wstack_bf16(const float *V, const float *W0, int32_t d_in, int32_t d_out, int32_t B, void *WstT,
@@ -803,7 +805,7 @@ int launch_combine_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out, i
     MatBF Bm{reinterpret_cast<const uint16_t *>(WstT), d_out, K, K, nullptr};
     EpiActF32 ep{out, out2, N, d_out, act, row_active};
     KGE_PROF("combine", st);
-    return launch_gemm<true, EpiActF32>(A, Bm, ep, K, cdiv(K, TK) * TK, tiles_m, tiles_n, 1, st);
+    return launch_gemm<true, EpiActF32, TN, 64>(A, Bm, ep, K, cdiv(K, TK) * TK, tiles_m, tiles_n, 1, st);
 }
 
 // C[r] (d_in x d_out, fp32, zeroed here) = sum_{runs s of relation r} Zbf[s]^T Gbf[seg_dst[s]]
