@@ -61,7 +61,7 @@ struct MatBF {
 };
 
 struct EpiProjectStaged {     // columns < bd -> P (bf16), the rest -> Self (fp32); through LDS
-    static constexpr bool staged = true, packed = false;
+    static constexpr bool staged = true, packed = false, swapped = false;
     uint16_t *P; float *Self; int64_t rows; int32_t d_out, bd;
     __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store8(int64_t m, int32_t n, const float4 &x, const float4 &y) const
@@ -79,7 +79,7 @@ struct EpiProjectStaged {     // columns < bd -> P (bf16), the rest -> Self (fp3
     __device__ __forceinline__ void store(int64_t, int32_t, float) const {}
 };
 struct EpiWeightGradAtomic {
-    static constexpr bool staged = false, packed = false;
+    static constexpr bool staged = false, packed = false, swapped = false;
     float *dV, *dW0; int32_t d_in, d_out, B;
     __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
@@ -92,8 +92,26 @@ struct EpiWeightGradAtomic {
     }
     __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
 };
+// The same sums with the operands' roles exchanged: A = X (its columns are the tile's rows), B = H.  Every
+// column block of X is then read by one block only (X is the big operand, (B+1) d_out columns; H has d_in), and
+// with the matrix-core operands swapped as well a lane's neighbours still hold neighbouring columns of X, so the
+// atomics of a wavefront instruction stay contiguous.
+struct EpiWeightGradAtomicT {
+    static constexpr bool staged = false, packed = false, swapped = true;
+    float *dV, *dW0; int32_t d_in, d_out, B;
+    __device__ __forceinline__ void bind(int32_t) {}
+    __device__ __forceinline__ void store(int64_t xc, int32_t hc, float v) const   // column of X, column of H
+    {
+        const int32_t bd = B * d_out;
+        if (xc >= bd + d_out || hc >= d_in) return;
+        const int32_t b = (int32_t)xc / d_out, c = (int32_t)xc - b * d_out;
+        float *dst = b < B ? dV + ((int64_t)b * d_in + hc) * d_out + c : dW0 + (int64_t)hc * d_out + c;
+        unsafeAtomicAdd(dst, v);
+    }
+    __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
+};
 struct EpiRowMajorF32 {
-    static constexpr bool staged = false, packed = false;
+    static constexpr bool staged = false, packed = false, swapped = false;
     float *out; int64_t rows; int32_t cols;
     __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
@@ -108,7 +126,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));     // 16 bytes as a
 // swapped), so that a lane's accumulators hold 4 consecutive columns of one row; they are rounded to bf16 in
 // registers, staged through LDS by 8-byte writes and leave as 16-byte row-contiguous stores.
 struct EpiRowsBF16Staged {
-    static constexpr bool staged = true, packed = true;
+    static constexpr bool staged = true, packed = true, swapped = true;
     uint16_t *out; int64_t rows; int32_t cols;
     __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store_packed(int64_t m, int32_t n, const u32x4 &v) const    // 8 columns from n
@@ -120,7 +138,7 @@ struct EpiRowsBF16Staged {
     __device__ __forceinline__ void store(int64_t, int32_t, float) const {}
 };
 struct EpiActF32 {            // activation, zero rows outside the sub-graph, optional second copy
-    static constexpr bool staged = false, packed = false;
+    static constexpr bool staged = false, packed = false, swapped = false;
     float *out, *out2; int64_t rows; int32_t cols; int act; const uint8_t *row_active;
     __device__ __forceinline__ void bind(int32_t) {}
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
@@ -134,7 +152,7 @@ struct EpiActF32 {            // activation, zero rows outside the sub-graph, op
     __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
 };
 struct EpiRelOuterAtomic {    // C[group] (d_in x d_out) accumulates the chunks of one relation
-    static constexpr bool staged = false, packed = false;
+    static constexpr bool staged = false, packed = false, swapped = false;
     float *C; int32_t d_in, d_out; int32_t group;
     __device__ __forceinline__ void bind(int32_t g) { group = g; }
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
@@ -437,7 +455,8 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int j = 0; j < NJ; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = EPI::swapped ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0)
+                                                 : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
             }
             return;
         }
@@ -455,7 +474,7 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
-                    acc[i][j] = EPI::packed ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0)
+                    acc[i][j] = EPI::swapped ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0)
                                             : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
         }
     };
@@ -557,8 +576,10 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int row = wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                    const int col = wn * (TNt / 2) + j * 32 + (lane & 31);
+                    // swapped operands: the lane runs along the tile's rows and the registers along its columns
+                    const int rr = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), cc = lane & 31;
+                    const int row = wm * 64 + i * 32 + (EPI::swapped ? cc : rr);
+                    const int col = wn * (TNt / 2) + j * 32 + (EPI::swapped ? rr : cc);
                     if (m0 + row < m_end || !mt_beg) epi.store(m0 + row, n0 + col, acc[i][j][v]);
                 }
     }
@@ -765,8 +786,16 @@ int launch_weight_grad_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_
     MatBF Bm{reinterpret_cast<const uint16_t *>(X), N, nc, nc, nullptr};
     EpiWeightGradAtomic ep{dV, dW0, d_in, d_out, B};
     KGE_PROF("weight_grad", st);
-    if (octet_rows(A) && octet_rows(Bm))
-        return launch_gemm<false, EpiWeightGradAtomic, TN, TK, false, true>(A, Bm, ep, N, kchunk, tiles_m, tiles_n, splits, st);
+    if (octet_rows(A) && octet_rows(Bm)) {
+        // X as the row operand: 128 of its columns per block against all (up to 256) columns of H at a time
+        const int32_t tm = (int32_t)cdiv(nc, TM), tn = (int32_t)cdiv(d_in, TN);
+        int64_t sp = cdiv(2048, (int64_t)tm * tn);
+        int64_t kc = cdiv(cdiv(N, sp), TK) * TK;
+        if (kc < 8 * TK) kc = 8 * TK;
+        sp = cdiv(N, kc);
+        EpiWeightGradAtomicT ept{dV, dW0, d_in, d_out, B};
+        return launch_gemm<false, EpiWeightGradAtomicT, TN, TK, false, true>(Bm, A, ept, N, kc, tm, tn, sp, st);
+    }
     return launch_gemm<false, EpiWeightGradAtomic>(A, Bm, ep, N, kchunk, tiles_m, tiles_n, splits, st);
 }
 
