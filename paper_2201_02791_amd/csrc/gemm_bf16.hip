@@ -4,11 +4,11 @@
 // Every operand is a plain row-major bf16 matrix by the time it reaches a GEMM: small
 // conversion kernels write a bf16 copy of the layer input, of [V_1..V_B | W_0] (row-major and
 // transposed), and append the upstream gradient G to the dP buffer, so that X = [dP | G] is one
-// matrix.  The GEMM loaders are then bare 16-byte (or 4-byte) loads.
+// matrix.  The GEMM loaders are then bare 16-byte loads.
 //
 //   project      [P | Self] = Hbf  (N x K)  *  WbfT^T   both operands k-contiguous
 //   input_grad   dH         = X    (N x nc) *  Wbf^T    both operands k-contiguous
-//   weight_grad  d[V | W0]  = Hbf^T * X                 both operands k-strided (k = vertex)
+//   weight_grad  d[V | W0]  = Hbf^T * X                 both operands k-strided (k = vertex); formed as (X^T Hbf)^T
 //
 // and for layers that aggregate before they project:
 //
@@ -16,13 +16,13 @@
 //   rel_outer    C_r = sum_{runs s of r} Zbf[s]^T Gbf[dst(s)]   k-strided (k = run), grouped by relation,
 //                                                        B rows picked through the run -> destination list
 //
-// Block tile 128 x 256 x 32, 4 wavefronts in a 2 x 2 grid, each owning 64 x 128 = 2 x 4 MFMA
-// tiles (128 accumulator registers, two blocks per CU).  LDS holds A as [m][k] and B as [n][k],
-// k contiguous, rows padded to 80 bytes so the 16-byte operand reads of a half-wavefront touch
-// every bank once.  A lane feeds the matrix core 8 consecutive k values of one row; k-strided
-// sources are transposed in registers (8 k x 2 columns per thread) before the LDS write.  The
-// next tile's global loads are issued before the MFMA loop of the current tile.  The projection's
-// epilogue goes through LDS so that P is written as 16-byte bf16 vectors, 256 bytes per row.
+// Block tile 128 x 256 x 32 (or x 64), 4 wavefronts in a 2 x 2 grid, each owning 64 x 128 = 2 x 4 MFMA
+// tiles (128 accumulator registers, two blocks per CU).  k-contiguous operands: LDS holds A as [m][k] and B
+// as [n][k], k contiguous, rows padded to 80 (176) bytes so the 16-byte operand reads of a half-wavefront
+// touch every bank once; a lane feeds the matrix core 8 consecutive k values of one row.  k-strided operands
+// stay k-major in LDS ([k][m], [k][n], as they lie in memory) and the operands are fetched with the
+// transposing LDS read of gfx950.  The next tile's global loads are issued before the MFMA loop of the
+// current tile.  bf16 outputs go through LDS so that they are written as 16-byte vectors, row-contiguous.
 #include "common.h"
 #include <type_traits>
 
@@ -42,22 +42,9 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)   // two fp32 -> p
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
-// Row-major bf16 matrix.  oct: 8 consecutive elements (16 bytes); pair: 2 (4 bytes).  Out of range -> 0.
-// `idx` (optional): logical row r is stored row idx[r].
+// Row-major bf16 matrix, rows `ld` elements apart.  `idx` (optional): logical row r is stored row idx[r].
 struct MatBF {
     const uint16_t *p; int64_t rows; int32_t cols; int64_t ld; const int32_t *idx;
-    __device__ __forceinline__ uint4 oct(int64_t r, int32_t c) const
-    {
-        if (r >= rows || c >= cols) return make_uint4(0u, 0u, 0u, 0u);
-        const int64_t rr = idx ? (int64_t)idx[r] : r;
-        return *reinterpret_cast<const uint4 *>(p + rr * ld + c);
-    }
-    __device__ __forceinline__ uint32_t pair(int64_t r, int32_t c) const
-    {
-        if (r >= rows || c >= cols) return 0u;
-        const int64_t rr = idx ? (int64_t)idx[r] : r;
-        return *reinterpret_cast<const uint32_t *>(p + rr * ld + c);
-    }
 };
 
 struct EpiProjectStaged {     // columns < bd -> P (bf16), the rest -> Self (fp32); through LDS
@@ -78,24 +65,10 @@ struct EpiProjectStaged {     // columns < bd -> P (bf16), the rest -> Self (fp3
     }
     __device__ __forceinline__ void store(int64_t, int32_t, float) const {}
 };
-struct EpiWeightGradAtomic {
-    static constexpr bool staged = false, packed = false, swapped = false;
-    float *dV, *dW0; int32_t d_in, d_out, B;
-    __device__ __forceinline__ void bind(int32_t) {}
-    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
-    {
-        const int32_t bd = B * d_out;
-        if (m >= d_in || n >= bd + d_out) return;
-        const int32_t b = n / d_out, c = n - b * d_out;
-        float *dst = b < B ? dV + ((int64_t)b * d_in + m) * d_out + c : dW0 + m * d_out + c;
-        unsafeAtomicAdd(dst, v);
-    }
-    __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
-};
-// The same sums with the operands' roles exchanged: A = X (its columns are the tile's rows), B = H.  Every
-// column block of X is then read by one block only (X is the big operand, (B+1) d_out columns; H has d_in), and
-// with the matrix-core operands swapped as well a lane's neighbours still hold neighbouring columns of X, so the
-// atomics of a wavefront instruction stay contiguous.
+// d[V | W0] = H^T X accumulated with atomics, computed as (X^T H)^T: A = X (its columns are the tile's rows),
+// B = H.  Every column block of X is then read by one block only (X is the big operand, (B+1) d_out columns; H
+// has d_in), and with the matrix-core operands swapped as well a lane's neighbours hold neighbouring columns of
+// X, so the atomics of a wavefront instruction stay contiguous.
 struct EpiWeightGradAtomicT {
     static constexpr bool staged = false, packed = false, swapped = true;
     float *dV, *dW0; int32_t d_in, d_out, B;
@@ -162,35 +135,26 @@ struct EpiRelOuterAtomic {    // C[group] (d_in x d_out) accumulates the chunks 
     __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
 };
 
-// eight packed pairs (k = 0..7, columns x and x+1) -> the k-octets of column x and of column x+1
-__device__ __forceinline__ void transpose_pairs(const uint32_t (&pr)[8], uint4 &c0, uint4 &c1)
-{
-    c0.x = (pr[0] & 0xffffu) | (pr[1] << 16); c0.y = (pr[2] & 0xffffu) | (pr[3] << 16);
-    c0.z = (pr[4] & 0xffffu) | (pr[5] << 16); c0.w = (pr[6] & 0xffffu) | (pr[7] << 16);
-    c1.x = (pr[0] >> 16) | (pr[1] & 0xffff0000u); c1.y = (pr[2] >> 16) | (pr[3] & 0xffff0000u);
-    c1.z = (pr[4] >> 16) | (pr[5] & 0xffff0000u); c1.w = (pr[6] >> 16) | (pr[7] & 0xffff0000u);
-}
-
-// KC = true : C[m][n] = sum_k A[m][k] B[n][k]   (A.oct(m, k), B.oct(n, k))
-// KC = false: C[m][n] = sum_k A[k][m] B[k][n]   (A.pair(k, m), B.pair(k, n))
+// KC = true : C[m][n] = sum_k A[m][k] B[n][k]   (k-contiguous operands)
+// KC = false: C[m][n] = sum_k A[k][m] B[k][n]   (k-strided operands: the contraction index is the row of both)
 // Split s contracts [s*kchunk, min((s+1)*kchunk, K)), or, in a grouped launch (g_beg non-null),
 // [g_beg[s], g_end[s]) with the epilogue bound to group g_id[s].
 // TNt: columns of the block tile, 256 (a wavefront owns 64 x 128: 128 accumulator registers, two blocks
 // per CU) or 128 (64 x 64: four blocks per CU, for contractions too short to hide their own latency).
 // TKt: contraction depth of a tile, 32 or (k-contiguous operands only) 64: with 64 a row's piece of a
 // tile is a whole 128-byte line, and one tile instead of two is in flight in registers.
-// TR (k-strided operands only): tiles go to LDS as they lie in memory, k-major, by 16-byte loads and stores, and
+// k-strided operands (TR in the code): tiles go to LDS as they lie in memory, k-major, by 16-byte loads and stores, and
 // the matrix-core operands are fetched with the transposing LDS read of gfx950 (ds_read_b64_tr_b16: within 16
 // lanes, lane l receives the l-th 16-bit column of the 4 x 16 block whose four rows lanes 0-3, 4-7, 8-11 and
 // 12-15 address 4 columns at a time).  No transposes in registers, a quarter of the load instructions.  The
-// launcher checks that columns and pitches are multiples of 8 elements.
+// launcher checks that columns and pitches are multiples of 8 elements (bf16 layers have such widths).
 // MT (k-contiguous operands with a tile list only): a block takes `tpb` consecutive row tiles of the list
 // (`tiles_m` then counts such groups and `n_mt` the tiles), and the first loads of the next tile are issued in
 // place of the refills that the current tile's last steps have no use for, so that they are in flight while the
 // current tile's results go out.  Its loads carry no clamps: the launcher checks that the contraction is a whole
 // number of PF * TKt deep rounds over all of A's columns, that B is un-indexed with a multiple of RPP rows in one
 // column tile, and that A's (indexed) rows are below 2^31.
-template <bool KC, class EPI, int TNt = TN, int TKt = TK, bool MT = false, bool TR = false>
+template <bool KC, class EPI, int TNt = TN, int TKt = TK, bool MT = false>
 __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, MatBF B, EPI epi, int64_t K, int64_t kchunk,
                                                      int32_t tiles_m, int32_t tiles_n, int32_t n_splits,
                                                      const int32_t *__restrict__ g_id,
@@ -208,7 +172,7 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
     constexpr int PF = TKt == TK ? 2 : 1;        // tiles in flight in registers
     static_assert(KC || TKt == TK, "k-strided operands use the 32-deep tile");
     static_assert(KC || !MT, "several row tiles per block: k-contiguous operands only");
-    static_assert(!KC || !TR, "transposing LDS reads: k-strided operands only");
+    constexpr bool TR = !KC;
     // TR: LDS rows of TM + 32 and TNt + 32 elements (pitches of 64 bytes modulo 256: the four rows that 16 lanes
     // read at once fall in four different quarters of the banks)
     constexpr int PA = TM + 32, PB = TNt + 32;
@@ -259,24 +223,21 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
     floatx16 acc[2][NJ];
 
     // Two tiles are in flight in registers while a third is multiplied out of LDS (24 registers per
-    // tile): k-contiguous operands as 16-byte octets, k-strided ones as raw 4-byte pairs that are
-    // transposed only when they are written to LDS, so that nothing waits for a load before the
-    // matrix-core loop.  Rows picked through an index list have their indices fetched one tile
-    // earlier still, which keeps the row loads themselves independent.
+    // tile, 16-byte octets), so that nothing waits for a load before the matrix-core loop.  Rows picked
+    // through an index list have their indices fetched one tile earlier still, which keeps the row loads
+    // themselves independent.
     struct Regs {
         u32x4 a[KC ? TM / RPP : NLA], b[KC ? TNt / RPP : NLB];
-        uint32_t pa[KC || TR ? 1 : 8], pb[KC || TR ? 1 : NJ / 2][KC || TR ? 1 : 8];
         uint32_t keep;      // which of a[] are inside the contraction range: applied when the tile goes to LDS, so
                             // that nothing touches the loaded registers (and waits for them) before that
     };
     Regs rg[PF];
-    // KC = false: stored rows of B and of A for the tile that is loaded next.  A k past the range's end takes
-    // the range's last row instead (kend <= rows of both operands) and clears its bit in kmask: every load is
-    // then unconditional - no divergent branch per load - and only A's pairs are zeroed for such a k, which
-    // makes the product vanish whatever finite row B repeats.
-    int32_t brow[8], akrow[8];
+    // KC = false: stored rows of A and of B for this thread's loads of the tile that is loaded next (16 or 32
+    // lanes share a row).  A k past the range's end takes the range's last row instead (kend <= rows of both
+    // operands) and clears its bit in kmask: every load is then unconditional - no divergent branch per load -
+    // and only A's octets are zeroed for such a k, which makes the product vanish whatever finite row B repeats.
     uint32_t kmask = 0u;
-    int32_t tai[NLA], tbi[NLB];      // TR: the same, per load of this thread (16 or 32 lanes share a row)
+    int32_t tai[NLA], tbi[NLB];
     uint16_t *As2 = reinterpret_cast<uint16_t *>(smem), *Bs2 = As2 + TK * PA;
 
     auto load_rows = [&](int64_t k0) __attribute__((always_inline)) {
@@ -292,20 +253,6 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             for (int i = 0; i < NLB; ++i) {
                 const int64_t rl = k0 + t / LRB + RB * i, rcl = rl < kend ? rl : kend - 1;
                 tbi[i] = B.idx ? B.idx[rcl] : (int32_t)rcl;
-            }
-        } else if (!KC) {
-            // a wavefront's 8 rows are the same in every lane: lane kk fetches row kk's indices, and reading
-            // them back lane by lane leaves them in scalar registers, so that the row addresses are scalar
-            // arithmetic and the loads take a scalar base plus the lane's column offset
-            const int ko = __builtin_amdgcn_readfirstlane((t >> 6) * 8);
-            const int64_t rl = k0 + ko + (lane & 7), rcl = rl < kend ? rl : kend - 1;
-            const int32_t bi = B.idx ? B.idx[rcl] : (int32_t)rcl, ai = A.idx ? A.idx[rcl] : (int32_t)rcl;
-            kmask = 0u;
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                kmask |= (k0 + ko + kk < kend ? 1u : 0u) << kk;
-                brow[kk] = __builtin_amdgcn_readlane(bi, kk);
-                akrow[kk] = __builtin_amdgcn_readlane(ai, kk);
             }
         }
     };
@@ -374,31 +321,6 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             R.keep = kmask;
 #pragma unroll
             for (int i = 0; i < NLB; ++i) R.b[i] = *reinterpret_cast<const u32x4 *>(Bp + (int64_t)tbi[i] * B.ld + cb);
-        } else {
-            // columns past the matrix read its last pair: they only feed outputs the epilogue drops.  The row
-            // bases are scalar (see load_rows); the column offsets are unsigned 32-bit byte offsets, so the
-            // loads take the scalar-base form and need no address arithmetic of their own
-            const int cp = t & 63;
-            const int32_t ca0 = (int32_t)(m0 + 2 * cp);
-            const uint32_t ca_b = (uint32_t)(ca0 < A.cols ? ca0 : A.cols - 2) * 2u;
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const char *arp = reinterpret_cast<const char *>(A.p + (int64_t)akrow[kk] * A.ld);
-                const uint32_t v = *reinterpret_cast<const uint32_t *>(arp + ca_b);
-                R.pa[kk] = (kmask >> kk) & 1u ? v : 0u;
-            }
-            uint32_t cb_b[NJ / 2];
-#pragma unroll
-            for (int ps = 0; ps < NJ / 2; ++ps) {
-                const int32_t cb0 = n0 + 2 * (cp + ps * 64);
-                cb_b[ps] = (uint32_t)(cb0 < B.cols ? cb0 : B.cols - 2) * 2u;
-            }
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const char *brp = reinterpret_cast<const char *>(Bp + (int64_t)brow[kk] * B.ld);
-#pragma unroll
-                for (int ps = 0; ps < NJ / 2; ++ps) R.pb[ps][kk] = *reinterpret_cast<const uint32_t *>(brp + cb_b[ps]);
-            }
         }
     };
     auto store_tile = [&](Regs &R) __attribute__((always_inline)) {
@@ -417,18 +339,6 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
 #pragma unroll
             for (int i = 0; i < NLB; ++i)
                 *reinterpret_cast<u32x4 *>(&Bs2[(t / LRB + RB * i) * PB + (t % LRB) * 8]) = R.b[i];
-        } else {
-            const int cp = t & 63, ko = (t >> 6) * 8;
-            uint4 c0, c1;
-            transpose_pairs(R.pa, c0, c1);
-            *reinterpret_cast<uint4 *>(&As[2 * cp][ko]) = c0;
-            *reinterpret_cast<uint4 *>(&As[2 * cp + 1][ko]) = c1;
-#pragma unroll
-            for (int ps = 0; ps < NJ / 2; ++ps) {
-                transpose_pairs(R.pb[ps], c0, c1);
-                *reinterpret_cast<uint4 *>(&Bs[2 * (cp + ps * 64)][ko]) = c0;
-                *reinterpret_cast<uint4 *>(&Bs[2 * (cp + ps * 64) + 1][ko]) = c1;
-            }
         }
     };
     auto mma_tile = [&]() __attribute__((always_inline)) {
@@ -672,7 +582,7 @@ __global__ __launch_bounds__(256) void k_cvt_group_mats(const float *__restrict_
     }
 }
 
-template <bool KC, class EPI, int TNt = TN, int TKt = TK, bool MT = false, bool TR = false>
+template <bool KC, class EPI, int TNt = TN, int TKt = TK, bool MT = false>
 int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64_t kchunk, int32_t tiles_m,
                 int32_t tiles_n, int64_t splits, hipStream_t st, const int32_t *g_id = nullptr,
                 const int32_t *g_beg = nullptr, const int32_t *g_end = nullptr, const int32_t *mt_id = nullptr,
@@ -691,6 +601,7 @@ int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64
     const int64_t n_patches = cdiv(splits * tiles_m, pm) * cdiv(tiles_n, pn);
     const int64_t blocks = cdiv(n_patches, 8) * 8 * 64;
     KGE_REQUIRE(blocks < 0x7fffffffLL, KGE_ERANGE, "grid too large");
+    constexpr bool TR = !KC;
     if (TR)
         KGE_REQUIRE(A.cols >= 8 && B.cols >= 8 && A.cols % 8 == 0 && B.cols % 8 == 0 && A.ld % 8 == 0 && B.ld % 8 == 0 &&
                         reinterpret_cast<uintptr_t>(A.p) % 16 == 0 && reinterpret_cast<uintptr_t>(B.p) % 16 == 0 &&
@@ -700,21 +611,15 @@ int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64
     const size_t lds = EPI::staged ? (lds_epi > lds_main ? lds_epi : lds_main) : lds_main;
     static bool attr_set = false;
     if (!attr_set) {
-        KGE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<KC, EPI, TNt, TKt, MT, TR>),
+        KGE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<KC, EPI, TNt, TKt, MT>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    k_gemm_bf16<KC, EPI, TNt, TKt, MT, TR><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n,
+    k_gemm_bf16<KC, EPI, TNt, TKt, MT><<<(unsigned)blocks, NT, lds, st>>>(A, B, epi, K, kchunk, tiles_m, tiles_n,
                                                                 (int32_t)splits, g_id, g_beg, g_end, mt_id, mt_beg, mt_end,
                                                                 b_group_stride, tpb, n_mt);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
-}
-
-// rows that 16-byte loads can walk: whole octets, 16-byte aligned (the k-strided loader with transposing LDS reads)
-bool octet_rows(const MatBF &M)
-{
-    return M.cols >= 8 && M.cols % 8 == 0 && M.ld % 8 == 0 && reinterpret_cast<uintptr_t>(M.p) % 16 == 0;
 }
 
 }  // namespace
@@ -777,26 +682,17 @@ int launch_weight_grad_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_
     if (rc != KGE_OK) return rc;
     if (N == 0) return KGE_OK;
     const int32_t nc = (B + 1) * d_out;
-    const int32_t tiles_m = (int32_t)cdiv(d_in, TM), tiles_n = (int32_t)cdiv(nc, TN);
+    // X as the row operand: 128 of its columns per block against all (up to 256) columns of H at a time
+    const int32_t tiles_m = (int32_t)cdiv(nc, TM), tiles_n = (int32_t)cdiv(d_in, TN);
     int64_t splits = cdiv(2048, (int64_t)tiles_m * tiles_n);
     int64_t kchunk = cdiv(cdiv(N, splits), TK) * TK;
     if (kchunk < 8 * TK) kchunk = 8 * TK;
     splits = cdiv(N, kchunk);
-    MatBF A{reinterpret_cast<const uint16_t *>(Hbf), N, d_in, d_in, nullptr};
-    MatBF Bm{reinterpret_cast<const uint16_t *>(X), N, nc, nc, nullptr};
-    EpiWeightGradAtomic ep{dV, dW0, d_in, d_out, B};
+    MatBF Xm{reinterpret_cast<const uint16_t *>(X), N, nc, nc, nullptr};
+    MatBF Hm{reinterpret_cast<const uint16_t *>(Hbf), N, d_in, d_in, nullptr};
+    EpiWeightGradAtomicT ep{dV, dW0, d_in, d_out, B};
     KGE_PROF("weight_grad", st);
-    if (octet_rows(A) && octet_rows(Bm)) {
-        // X as the row operand: 128 of its columns per block against all (up to 256) columns of H at a time
-        const int32_t tm = (int32_t)cdiv(nc, TM), tn = (int32_t)cdiv(d_in, TN);
-        int64_t sp = cdiv(2048, (int64_t)tm * tn);
-        int64_t kc = cdiv(cdiv(N, sp), TK) * TK;
-        if (kc < 8 * TK) kc = 8 * TK;
-        sp = cdiv(N, kc);
-        EpiWeightGradAtomicT ept{dV, dW0, d_in, d_out, B};
-        return launch_gemm<false, EpiWeightGradAtomicT, TN, TK, false, true>(Bm, A, ept, N, kc, tm, tn, sp, st);
-    }
-    return launch_gemm<false, EpiWeightGradAtomic>(A, Bm, ep, N, kchunk, tiles_m, tiles_n, splits, st);
+    return launch_gemm<false, EpiWeightGradAtomicT>(Xm, Hm, ep, N, kchunk, tiles_m, tiles_n, splits, st);
 }
 
 // dH = X [V | W0]^T        Wbf: bf16 [d_in][nc]
@@ -851,9 +747,6 @@ int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const int32_t
     MatBF Bm{reinterpret_cast<const uint16_t *>(Gbf), p->n_seg, d_out, ldg, p->seg_dst};
     EpiRelOuterAtomic ep{C, d_in, d_out, 0};
     KGE_PROF("rel_outer", st);
-    if (octet_rows(A) && octet_rows(Bm))
-        return launch_gemm<false, EpiRelOuterAtomic, TN, TK, false, true>(A, Bm, ep, p->n_seg, 0, tiles_m, tiles_n, p->n_relc,
-                                                                         st, p->relc_rel, p->relc_beg, p->relc_end);
     return launch_gemm<false, EpiRelOuterAtomic>(A, Bm, ep, p->n_seg, 0, tiles_m, tiles_n, p->n_relc, st,
                                                  p->relc_rel, p->relc_beg, p->relc_end);
 }
