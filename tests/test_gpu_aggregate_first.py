@@ -218,6 +218,25 @@ def test_bf16_aggregate_first_intermediates(kb, orc):
     assert np.mean(got == bf(Z)) > 0.999
 
 
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("d", [64, 72])
+def test_bf16_many_small_relations(kb, orc, order, d):
+    """800 relation ids over 5,000 runs: every row tile of the run list is a ragged handful of runs, a block's
+    consecutive tiles belong to different relations (a new weight matrix per tile), and the per-relation
+    contraction ranges of the outer products are one to a few runs long.  d = 64 takes the multi-tile form of
+    the per-run products, d = 72 the one-tile form."""
+    say("bf16, many small relations, order", order, d)
+    spec = synth.scaled(synth.WORKLOADS[4], name="bf16-manyrel", seed=13, n_entities=1500, n_relations=400,
+                        n_triples=4000, d=d, n_bases=4, n_pos=200, n_neg=3, n_parts=1, part_id=0, acts=[0, 0])
+    head, rel, tail = random_graph(77, 1500, 400, 4000)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=order)
+    assert gp.n_seg > 4000 and len(np.unique(gp.export("seg_rel"))) > 700
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos, msg_bf16=BF16_MODE[order])
+    assert_partition_equal(gp, op)
+    errs = assert_step_close(ts, res, TOL_BF16, TOL_BF16)
+    say("errs", errs)
+
+
 @pytest.mark.parametrize("order", [pytest.param(0, id="project_first")] + ORDERS)
 @pytest.mark.parametrize("dims,bf16", [((128, 32, 32), False), ((48, 96, 24), False), ((128, 32, 32), True),
                                        ((64, 128, 64), True), ((200, 40, 72), True), ((8, 248, 16), True)],
