@@ -31,7 +31,11 @@
  *    Relation ids 0..R-1 are the given direction, R..2R-1 the inverses; the
  *    self-loop is the dense W_0 term, not an edge.
  *  - All matrices are dense row-major.  Feature widths must be multiples of 4
- *    (of 8 when msg_dtype = KGE_MSG_BF16) and at most 256 (512 for bf16).
+ *    (of 8 when msg_dtype = KGE_MSG_BF16).  Per layer and order:
+ *      project-first     d_in <= 512, d_out <= 256
+ *      aggregate-first   d_in <= 256, d_out <= 256
+ *      relation-weight   d_in, d_out <= 256 (512 with bf16 messages)
+ *    A wider layer is refused with KGE_EINVAL before anything runs.
  */
 #ifndef KGE_MI355_H
 #define KGE_MI355_H

@@ -98,12 +98,18 @@ int check_layers(const kge_partition *p, const kge_layer *layers, int32_t n_laye
                     "layer %d: d_in and d_out must be multiples of %d", l, mult);
         KGE_REQUIRE(L.d_out <= dmax && L.d_in <= 512, KGE_EINVAL,
                     "layer %d: d_out must be at most %d and d_in at most 512", l, dmax);
+        // the transposed gather of the project-first order holds a row of d_out floats in one wavefront's lanes
+        KGE_REQUIRE(L.order != KGE_ORDER_PROJECT_FIRST || L.d_out <= 256, KGE_EINVAL,
+                    "layer %d: the project-first order needs d_out <= 256", l);
         KGE_REQUIRE(L.act == KGE_ACT_IDENTITY || L.act == KGE_ACT_RELU, KGE_EINVAL, "layer %d: bad act", l);
         KGE_REQUIRE(L.dropout >= 0.0f && L.dropout < 1.0f, KGE_EINVAL, "layer %d: dropout must be in [0, 1)", l);
         KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.order == KGE_ORDER_AGGREGATE_FIRST ||
                         L.order == KGE_ORDER_RELATION_WEIGHTS, KGE_EINVAL, "layer %d: bad order", l);
-        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.d_in <= dmax, KGE_EINVAL,
-                    "layer %d: the aggregate-first order needs d_in <= %d", l, dmax);
+        // so do the per-basis sums over runs of the aggregate-first order, forward (rows of d_in) and backward
+        KGE_REQUIRE(L.order != KGE_ORDER_AGGREGATE_FIRST || (L.d_in <= 256 && L.d_out <= 256), KGE_EINVAL,
+                    "layer %d: the aggregate-first order needs d_in <= 256 and d_out <= 256", l);
+        KGE_REQUIRE(L.order != KGE_ORDER_RELATION_WEIGHTS || L.d_in <= dmax, KGE_EINVAL,
+                    "layer %d: the relation-weight order needs d_in <= %d", l, dmax);
         KGE_REQUIRE(l == 0 || L.d_in == layers[l - 1].d_out, KGE_EINVAL,
                     "layer %d: d_in does not match the previous layer's d_out", l);
         KGE_REQUIRE(((uintptr_t)L.V % 16) == 0 && ((uintptr_t)L.W0 % 16) == 0, KGE_EINVAL,

@@ -239,9 +239,13 @@ def test_bf16_many_small_relations(kb, orc, order, d):
 
 @pytest.mark.parametrize("order", [pytest.param(0, id="project_first")] + ORDERS)
 @pytest.mark.parametrize("dims,bf16", [((128, 32, 32), False), ((48, 96, 24), False), ((128, 32, 32), True),
-                                       ((64, 128, 64), True), ((200, 40, 72), True), ((8, 248, 16), True)],
+                                       ((64, 128, 64), True), ((200, 40, 72), True), ((8, 248, 16), True),
+                                       ((512, 256, 256), False), ((256, 256, 256), False), ((512, 320, 512), True),
+                                       ((256, 256, 512), True)],
                          ids=["f32_128_32_32", "f32_48_96_24", "bf16_128_32_32", "bf16_64_128_64",
-                              "bf16_200_40_72_ragged_tiles", "bf16_8_248_16_ragged_tiles"])
+                              "bf16_200_40_72_ragged_tiles", "bf16_8_248_16_ragged_tiles",
+                              "f32_512_256_256_widest", "f32_256_256_256_widest", "bf16_512_320_512_widest",
+                              "bf16_256_256_512_widest"])
 def test_feature_layer_with_different_widths(kb, orc, order, dims, bf16):
     """A feature-input layer whose width differs from the embedding width (the paper's large-graph
     setting: 128-d features, 32-d embeddings), and a widening layer, in every order."""
@@ -251,6 +255,19 @@ def test_feature_layer_with_different_widths(kb, orc, order, dims, bf16):
                         n_triples=m, d=dims[2], n_bases=B, n_pos=150, n_neg=2, neg_mode=1, n_parts=1, part_id=0,
                         acts=[0, 0] if bf16 else [1, 0], feature_std=0.5)
     head, rel, tail = random_graph(41, n, R, m)
+    too_wide = ("d_out <= 256" if order == 0 and max(dims[1:]) > 256 else
+                "d_in <= 256 and d_out <= 256" if order == AGG and max(dims) > 256 else
+                "d_in <= 256" if order == RELW and not bf16 and max(dims[:2]) > 256 else None)
+    if too_wide:
+        # wider than the order's kernels take (see the header): a clean error before anything runs, not a fault
+        part = kb.build_partition(head, rel, tail, n, R, 1, 0, 2, spec.neg_domain)
+        with pytest.raises(kb.KgeError, match=too_wide):
+            gpu_step(spec, head, rel, tail, params=dict(
+                V=[np.zeros((B, dims[0], dims[1]), np.float32), np.zeros((B, dims[1], dims[2]), np.float32)],
+                a=[np.zeros((2 * R, B), np.float32)] * 2,
+                W0=[np.zeros((dims[0], dims[1]), np.float32), np.zeros((dims[1], dims[2]), np.float32)],
+                M=np.zeros((R, dims[2]), np.float32), H0=np.zeros((part.n_vert, dims[0]), np.float32)), order=order)
+        return
     rng = np.random.default_rng(5)
     g = lambda *shape: (rng.uniform(-1, 1, shape) * np.sqrt(6.0 / (shape[-2] + shape[-1]))).astype(np.float32)
     opart = orc.build_partition(head, rel, tail, n, R, 1, 0, 2, spec.neg_domain)
@@ -262,4 +279,10 @@ def test_feature_layer_with_different_widths(kb, orc, order, dims, bf16):
     mode = {0: 1, AGG: 2, RELW: 3}[order] if bf16 else False
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos, msg_bf16=mode)
     tol = (TOL_BF16, TOL_BF16) if bf16 else (TOL_VAL, TOL_GRAD)
+    if not bf16:
+        # a pre-activation within fp32 rounding of zero (|pre| < 1e-5 of the largest) may take the other side in
+        # the kernel's fp32 sum over up to 512 terms; the ReLU decision is then taken in the kernel's precision
+        n_adopted, res = align_mask_decisions(orc, ts, op, res, params, spec.acts, True, False, thresh=1e-5)
+        say("adopted ReLU decisions", n_adopted)
+        assert n_adopted <= 4
     assert_step_close(ts, res, *tol)
