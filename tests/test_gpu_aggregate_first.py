@@ -69,6 +69,7 @@ SHAPES = [
     ("d16_B20", 250, 9, 2200, 16, 20, 128, 2, 0, 2, [1, 0]),
     ("d96_B40_matrix_core_sum", 300, 12, 2600, 96, 40, 150, 3, 1, 1, [1, 0]),
     ("d160_B70", 200, 5, 1500, 160, 70, 64, 2, 1, 2, [1, 1]),
+    ("d32_B256_most_bases", 150, 4, 1200, 32, 256, 64, 2, 1, 1, [1, 0]),
     ("many_relations_few_runs", 400, 300, 3000, 32, 6, 100, 2, 1, 1, [1, 0]),
     ("one_relation_many_chunks", 9000, 1, 40000, 16, 2, 300, 1, 1, 1, [1, 0]),
 ]
