@@ -370,7 +370,9 @@ int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_ent
  * tests; the layout is fixed by the partition, the layer list and msg_dtype).  Writes the byte
  * offset and size of one slice:
  *   KGE_WS_P    layer l's projected messages P_l [N][B*d_out], msg_dtype (valid after forward)
- *   KGE_WS_H    layer l's output H_l [N][d_out] float (valid after forward)
+ *   KGE_WS_H    layer l's output H_l [N][d_out] float (valid after forward; the last layer's
+ *               output is the call's H_out, and this copy of it is written only when that
+ *               layer has ReLU)
  *   KGE_WS_G    G = dL/d(pre) [N][d_out] float of the last ReLU layer backward has processed
  *               (a layer with identity activation uses its incoming gradient in place)
  *   KGE_WS_DP   dP of the last layer backward has processed: [N][ld] msg_dtype with

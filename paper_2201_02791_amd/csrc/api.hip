@@ -286,6 +286,11 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
         const kge_layer &L = layers[l];
         void *P = ws + w.off_P[l];
         float *Hl = (float *)(ws + w.off_H[l]);
+        // The last layer's output goes to the caller's H_out; the workspace keeps a copy of it only when
+        // backward reads it (the ReLU mask).
+        const bool last = l == n_layers - 1;
+        float *out1 = last && L.act == KGE_ACT_IDENTITY ? H_out : Hl;
+        float *out2 = last && L.act != KGE_ACT_IDENTITY ? H_out : nullptr;
         if (L.dropout > 0.0f) {      // everything below reads the dropped copy; backward regenerates the mask
             float *Hd = (float *)(ws + w.off_Hd[l]);
             rc = launch_dropout(Hin, p->n_vert, L.d_in, L.dropout, L.drop_seed, L.drop_step, l, Hd, st);
@@ -295,7 +300,6 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
         if (L.order == KGE_ORDER_RELATION_WEIGHTS) {
             void *Z = ws + w.off_Z[l], *U = ws + w.off_U;
             float *Wrel = (float *)(ws + w.off_Wrel[l]);
-            float *out2 = l == n_layers - 1 ? H_out : nullptr;
             const uint8_t *act_l = kge_cgraph_layer(cg, l);
             const int32_t R2 = 2 * p->n_relations;
             rc = launch_relation_weights(L.a, R2, L.n_bases, L.V, (int64_t)L.d_in * L.d_out, Wrel, st);
@@ -324,7 +328,7 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
                 rc = launch_project(Hin, p->n_vert, L.d_in, L.d_out, 0, L.V, L.W0, nullptr, Self, st);
             }
             if (rc != KGE_OK) return rc;
-            rc = launch_sum_runs(p, U, bf, L.d_out, Self, L.act, Hl, out2, part, act_l, st);
+            rc = launch_sum_runs(p, U, bf, L.d_out, Self, L.act, out1, out2, part, act_l, st);
             if (rc != KGE_OK) return rc;
             Hin = Hl;
             continue;
@@ -332,7 +336,6 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
         if (L.order == KGE_ORDER_AGGREGATE_FIRST) {
             void *Z = ws + w.off_Z[l];
             void *Y = ws + w.off_Y;
-            float *out2 = l == n_layers - 1 ? H_out : nullptr;
             const uint8_t *act_l = kge_cgraph_layer(cg, l);
             if (bf) {
                 void *Hbf = ws + w.off_Hbf[l], *Wbf = ws + w.off_Wbf[l], *WbfT = ws + w.off_WbfT[l], *WstT = ws + w.off_Wst[l];
@@ -348,14 +351,14 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
                 if (rc != KGE_OK) return rc;
                 rc = launch_append_g_bf16(Hin, p->n_vert, L.d_in, L.n_bases, Y, st);      // X = [Y | Hbf]
                 if (rc != KGE_OK) return rc;
-                rc = launch_combine_bf16(Y, p->n_vert, L.d_in, L.d_out, L.n_bases, WstT, L.act, act_l, Hl, out2, st);
+                rc = launch_combine_bf16(Y, p->n_vert, L.d_in, L.d_out, L.n_bases, WstT, L.act, act_l, out1, out2, st);
             } else {
                 rc = launch_run_mean(p, Hin, L.d_in, Z, 0, part, act_l, 0, st);
                 if (rc != KGE_OK) return rc;
                 rc = launch_aggregate_runs(p, Z, L.a, L.n_bases, L.d_in, Y, (int64_t)L.n_bases * L.d_in, 0, part, act_l, st);
                 if (rc != KGE_OK) return rc;
                 rc = launch_combine((const float *)Y, Hin, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, L.act, act_l,
-                                    Hl, out2, st);
+                                    out1, out2, st);
             }
             if (rc != KGE_OK) return rc;
             Hin = Hl;
@@ -372,8 +375,8 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
             rc = launch_project(Hin, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, (float *)P, Self, st);
         }
         if (rc != KGE_OK) return rc;
-        rc = launch_gather_forward(p, P, bf, L.a, L.n_bases, L.d_out, Self, L.act, Hl,
-                                   l == n_layers - 1 ? H_out : nullptr, part, kge_cgraph_layer(cg, l), st);
+        rc = launch_gather_forward(p, P, bf, L.a, L.n_bases, L.d_out, Self, L.act, out1, out2, part,
+                                   kge_cgraph_layer(cg, l), st);
         if (rc != KGE_OK) return rc;
         Hin = Hl;
     }
