@@ -343,6 +343,22 @@ int kge_eval_rank_candidates(const float *H, int64_t n_entities, int32_t d, cons
                              void *workspace, size_t ws_bytes, int32_t *higher, int32_t *equal, void *stream);
 int kge_eval_metrics(const int32_t *higher, const int32_t *equal, int64_t n_queries, const int32_t *ks,
                      int32_t n_ks, double *out, void *stream);
+/*
+ * kge_eval_rank_all for callers that cannot allocate device memory and have no workspace to hand over:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * (minus the workspace), same kernels, same results; the scratch (query vectors, answer scores,
+ * per-query counters) lives in a static device array of KGE_EVAL_STATIC_BYTES inside the library, one
+ * copy per GPU, held until the process ends.  The call allocates nothing and never synchronises.
+ *   Limit: kge_eval_workspace_bytes(2 n_test, d) <= KGE_EVAL_STATIC_BYTES (about 15,000 test triples at
+ *   d = 256, 28,000 at d = 128); beyond it the call returns KGE_ENOMEM and nothing runs.
+ *   All calls on one GPU share that GPU's array: two calls that overlap in time (different streams or
+ *   threads) race on it; calls on one stream are ordered and safe.  The counters are cleared by a fill
+ *   kernel at the start of every call, so a call never sees the previous call's contents.
+ */
+#define KGE_EVAL_STATIC_BYTES (32u << 20)
+int kge_eval_rank_all_static(const kge_eval_filter *filter, const float *H, int64_t n_entities, int32_t d,
+                             const float *M, int32_t n_relations, const int32_t *test_h, const int32_t *test_r,
+                             const int32_t *test_t, int64_t n_test, int32_t *higher, int32_t *equal, void *stream);
 /* Test hook: the fp32 scores kge_eval_rank_all compares, written out: scores DEVICE float
  * [2 n_test][n_entities] from the tile kernel, answer_score DEVICE float [2 n_test] from the per-query
  * kernel (the two kernels must agree bit for bit on the same pair).  Small inputs only. */

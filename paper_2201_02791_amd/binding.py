@@ -23,7 +23,7 @@ EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_cgraph_destroy", "kge_compute_graph", "kge_cgraph_export", "kge_optimizer_step",
             "kge_optimizer_step_rows", "kge_eval_filter_create", "kge_eval_filter_destroy",
             "kge_eval_workspace_bytes", "kge_eval_rank_all", "kge_eval_rank_candidates", "kge_eval_metrics",
-            "kge_eval_debug_scores"]
+            "kge_eval_debug_scores", "kge_eval_rank_all_static"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
 ORDER_PROJECT_FIRST, ORDER_AGGREGATE_FIRST, ORDER_RELATION_WEIGHTS = 0, 1, 2
@@ -31,6 +31,7 @@ OPT_SGD, OPT_ADAM = 0, 1
 MSG_F32, MSG_BF16 = 0, 1
 NEG_TAIL, NEG_HEAD_OR_TAIL = 0, 1
 DOMAIN_CORE, DOMAIN_ALL = 0, 1
+EVAL_STATIC_BYTES = 32 << 20      # KGE_EVAL_STATIC_BYTES
 
 ARRAYS = {"vert_gid": (0, np.int32), "core_eid": (1, np.int32), "core_h": (2, np.int32),
           "core_r": (3, np.int32), "core_t": (4, np.int32), "seg_ptr": (5, np.int32),
@@ -372,6 +373,14 @@ def eval_rank_all(H, M, test_h, test_r, test_t, filt: EvalFilter = None, workspa
                                     _ptr(test_t), C.c_int64(n_test), _ptr(ws), C.c_size_t(ws.numel()), _ptr(higher),
                                     _ptr(equal), _stream(stream)))
     return higher, equal
+
+
+def eval_rank_all_static(H, M, test_h, test_r, test_t, higher, equal, filt: EvalFilter = None, stream=None):
+    """kge_eval_rank_all_static: the caller brings the outputs (int32 [2 n_test] each); nothing is allocated."""
+    _check(load().kge_eval_rank_all_static(filt.handle if filt is not None else C.c_void_p(0), _ptr(H),
+                                           C.c_int64(H.shape[0]), C.c_int32(H.shape[1]), _ptr(M), C.c_int32(M.shape[0]),
+                                           _ptr(test_h), _ptr(test_r), _ptr(test_t), C.c_int64(test_h.numel()),
+                                           _ptr(higher), _ptr(equal), _stream(stream)))
 
 
 def eval_rank_candidates(H, M, fixed, rel, answer, cand, workspace=None, stream=None):

@@ -14,7 +14,13 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <vector>
+
+// Scratch of kge_eval_rank_all_static: device memory that lives in the library's code object, one copy
+// per GPU, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the address kernels and fills may use is static_scratch_ptr()'s result.
+static __device__ __align__(256) unsigned char scratch[KGE_EVAL_STATIC_BYTES];
 
 struct kge_eval_filter {
     int device;
@@ -545,6 +551,47 @@ extern "C" int kge_eval_rank_all(const kge_eval_filter *filter, const float *H, 
     KGE_REQUIRE(n_test <= 0 || (higher && equal), KGE_EINVAL, "higher or equal is NULL");
     return rank_all(filter, H, n_entities, d, M, n_relations, test_h, test_r, test_t, n_test, workspace, ws_bytes,
                     higher, equal, nullptr, nullptr, (hipStream_t)stream);
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices];      // per device: where that GPU's copy of `scratch` lives
+
+// Address of the current device's copy of `scratch`, looked up once per device with that device current.
+int static_scratch_ptr(void **out)
+{
+    int dev = -1;
+    KGE_HIP(hipGetDevice(&dev));
+    KGE_REQUIRE(dev >= 0 && dev < kMaxDevices, KGE_EINVAL, "device index %d is outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        KGE_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        KGE_REQUIRE(ptr && ((uintptr_t)ptr % 256) == 0, KGE_EHIP, "the static scratch array has no usable device address");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return KGE_OK;
+}
+}  // namespace
+
+extern "C" int kge_eval_rank_all_static(const kge_eval_filter *filter, const float *H, int64_t n_entities, int32_t d,
+                                        const float *M, int32_t n_relations, const int32_t *test_h,
+                                        const int32_t *test_r, const int32_t *test_t, int64_t n_test,
+                                        int32_t *higher, int32_t *equal, void *stream)
+{
+    KGE_REQUIRE(n_test <= 0 || (higher && equal), KGE_EINVAL, "higher or equal is NULL");
+    KGE_REQUIRE(n_test >= 0 && n_test <= 0x3FFFFFFFll && d > 0, KGE_EINVAL, "n_test or d out of range");
+    const size_t need = eval_layout(2 * n_test, d).total;
+    KGE_REQUIRE(need <= (size_t)KGE_EVAL_STATIC_BYTES, KGE_ENOMEM,
+                "%lld test triples of width %d need %zu bytes of scratch; the static buffer holds %zu "
+                "(use kge_eval_rank_all with a workspace)", (long long)n_test, d, need, (size_t)KGE_EVAL_STATIC_BYTES);
+    void *ptr = nullptr;
+    int rc = static_scratch_ptr(&ptr);
+    if (rc != KGE_OK) return rc;
+    return rank_all(filter, H, n_entities, d, M, n_relations, test_h, test_r, test_t, n_test, ptr,
+                    (size_t)KGE_EVAL_STATIC_BYTES, higher, equal, nullptr, nullptr, (hipStream_t)stream);
 }
 
 extern "C" int kge_eval_debug_scores(const float *H, int64_t n_entities, int32_t d, const float *M, int32_t n_relations,
