@@ -220,26 +220,9 @@ void orc_partition_copy(const orc_partition *p, int32_t which, void *dst)
 static double act_fwd(int act, double x) { return act == 1 ? (x > 0.0 ? x : 0.0) : x; }
 static double act_grad(int act, double pre) { return act == 1 ? (pre > 0.0 ? 1.0 : 0.0) : 1.0; }
 
-/* Rounding to bfloat16 for workloads that run the projections as a bf16 contraction and keep
- * the projected messages in bf16: the operands (layer input, V_b, W_0) are rounded before they
- * are multiplied, products are summed exactly (double), and a message is rounded once more when
- * it is stored.  To float first, then to the nearest bfloat16, ties to even. */
-static double round_msg(double x, int32_t msg_bf16)
-{
-    if (!msg_bf16) return x;
-    float f = (float)x;
-    uint32_t u;
-    memcpy(&u, &f, 4);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return x;            /* NaN */
-    uint32_t lower = u & 0xffffu, keep = u & 0xffff0000u;
-    if (lower > 0x8000u || (lower == 0x8000u && (keep & 0x10000u))) keep += 0x10000u;
-    memcpy(&f, &keep, 4);
-    return (double)f;
-}
-
 /* P[j][b][:] = h_j V_b  — the B projections of every vertex (Eq. 2 applied to h_j). */
 static void project_all(int64_t N, int32_t d_in, int32_t d_out, int32_t B,
-                        const double *V, const double *H, double *P, int32_t msg_bf16)
+                        const double *V, const double *H, double *P)
 {
     memset(P, 0, sizeof(double) * (size_t)N * (size_t)B * (size_t)d_out);
     for (int64_t j = 0; j < N; ++j)
@@ -247,159 +230,35 @@ static void project_all(int64_t N, int32_t d_in, int32_t d_out, int32_t B,
             double *out = P + ((size_t)j * B + b) * d_out;
             const double *Vb = V + (size_t)b * d_in * d_out;
             for (int32_t k = 0; k < d_in; ++k) {
-                double h = round_msg(H[(size_t)j * d_in + k], msg_bf16);
+                double h = H[(size_t)j * d_in + k];
                 const double *vrow = Vb + (size_t)k * d_out;
-                for (int32_t o = 0; o < d_out; ++o) out[o] += h * round_msg(vrow[o], msg_bf16);
+                for (int32_t o = 0; o < d_out; ++o) out[o] += h * vrow[o];
             }
-            if (msg_bf16) for (int32_t o = 0; o < d_out; ++o) out[o] = round_msg(out[o], 1);
         }
-}
-
-/*
- * The rounding points of a bf16 pipeline that sums neighbours before it applies weights
- * (msg_bf16 == 2).  Eq. 1-2 regrouped, nothing else:
- *   z_{i,r} = (1/c_{i,r}) sum_{j in N_i^r} h_j          per (relation, destination) run
- *   y_{i,b} = sum_r a_rb z_{i,r}
- *   pre_i   = sum_b y_{i,b} V_b + h_i W_0
- * with h, z, y, V_b, W_0 each rounded to bf16 where they enter the next step and every sum exact.
- * zq_out (optional) receives the rounded z, [S][d_in].
- */
-static void forward_aggregate_first_bf16(int64_t N, int64_t S, const int32_t *seg_ptr,
-                                         const int32_t *seg_rel, const int32_t *seg_dst,
-                                         const int32_t *col_src, int32_t d_in, int32_t d_out, int32_t B,
-                                         const double *V, const double *a, const double *W0,
-                                         const double *H, double *pre, double *zq_out)
-{
-    double *y = (double *)calloc((size_t)N * B * d_in, sizeof(double));
-    double *z = (double *)malloc(sizeof(double) * (size_t)d_in);
-    for (int64_t s = 0; s < S; ++s) {
-        int32_t r = seg_rel[s], i = seg_dst[s];
-        double c = (double)(seg_ptr[s + 1] - seg_ptr[s]);
-        for (int32_t k = 0; k < d_in; ++k) z[k] = 0.0;
-        for (int32_t e = seg_ptr[s]; e < seg_ptr[s + 1]; ++e) {
-            const double *hj = H + (size_t)col_src[e] * d_in;
-            for (int32_t k = 0; k < d_in; ++k) z[k] += round_msg(hj[k], 1);
-        }
-        for (int32_t k = 0; k < d_in; ++k) z[k] = round_msg(z[k] / c, 1);
-        if (zq_out) memcpy(zq_out + (size_t)s * d_in, z, sizeof(double) * (size_t)d_in);
-        for (int32_t b = 0; b < B; ++b) {
-            double w = a[(size_t)r * B + b];
-            double *yb = y + ((size_t)i * B + b) * d_in;
-            for (int32_t k = 0; k < d_in; ++k) yb[k] += w * z[k];
-        }
-    }
-    for (int64_t i = 0; i < N; ++i) {
-        double *o = pre + (size_t)i * d_out;
-        for (int32_t c = 0; c < d_out; ++c) o[c] = 0.0;
-        for (int32_t k = 0; k < d_in; ++k) {
-            double h = round_msg(H[(size_t)i * d_in + k], 1);
-            const double *w = W0 + (size_t)k * d_out;
-            for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(w[c], 1);
-        }
-        for (int32_t b = 0; b < B; ++b)
-            for (int32_t k = 0; k < d_in; ++k) {
-                double yq = round_msg(y[((size_t)i * B + b) * d_in + k], 1);
-                const double *v = V + ((size_t)b * d_in + k) * d_out;
-                for (int32_t c = 0; c < d_out; ++c) o[c] += yq * round_msg(v[c], 1);
-            }
-    }
-    free(z);
-    free(y);
-}
-
-/*
- * The rounding points of a bf16 pipeline that writes Eq. 2 out per relation (msg_bf16 == 3):
- *   W_r     = sum_b a_rb V_b                            (Eq. 2), rounded to bf16
- *   z_{i,r} = (1/c_{i,r}) sum_{j in N_i^r} h_j          h and z rounded to bf16
- *   u_{i,r} = z_{i,r} W_r                               rounded to bf16 when stored
- *   pre_i   = sum_r u_{i,r} + h_i W_0                   W_0 rounded to bf16
- * every sum exact.  zq_out (optional) receives the rounded z, [S][d_in].
- */
-static void forward_relation_weights_bf16(int64_t N, int64_t S, const int32_t *seg_ptr,
-                                          const int32_t *seg_rel, const int32_t *seg_dst,
-                                          const int32_t *col_src, int32_t d_in, int32_t d_out, int32_t B,
-                                          int32_t n_rel2, const double *V, const double *a, const double *W0,
-                                          const double *H, double *pre, double *zq_out)
-{
-    size_t dd = (size_t)d_in * d_out;
-    double *Wr = (double *)calloc((size_t)n_rel2 * dd, sizeof(double));
-    double *z = (double *)malloc(sizeof(double) * (size_t)d_in);
-    double *u = (double *)malloc(sizeof(double) * (size_t)d_out);
-    for (int32_t r = 0; r < n_rel2; ++r) {
-        for (int32_t b = 0; b < B; ++b)
-            for (size_t x = 0; x < dd; ++x) Wr[(size_t)r * dd + x] += a[(size_t)r * B + b] * V[(size_t)b * dd + x];
-        for (size_t x = 0; x < dd; ++x) Wr[(size_t)r * dd + x] = round_msg(Wr[(size_t)r * dd + x], 1);
-    }
-    for (int64_t i = 0; i < N; ++i) {
-        double *o = pre + (size_t)i * d_out;
-        for (int32_t c = 0; c < d_out; ++c) o[c] = 0.0;
-        for (int32_t k = 0; k < d_in; ++k) {
-            double h = round_msg(H[(size_t)i * d_in + k], 1);
-            const double *w = W0 + (size_t)k * d_out;
-            for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(w[c], 1);
-        }
-    }
-    for (int64_t s = 0; s < S; ++s) {
-        int32_t r = seg_rel[s], i = seg_dst[s];
-        double cnt = (double)(seg_ptr[s + 1] - seg_ptr[s]);
-        for (int32_t k = 0; k < d_in; ++k) z[k] = 0.0;
-        for (int32_t e = seg_ptr[s]; e < seg_ptr[s + 1]; ++e) {
-            const double *hj = H + (size_t)col_src[e] * d_in;
-            for (int32_t k = 0; k < d_in; ++k) z[k] += round_msg(hj[k], 1);
-        }
-        for (int32_t k = 0; k < d_in; ++k) z[k] = round_msg(z[k] / cnt, 1);
-        if (zq_out) memcpy(zq_out + (size_t)s * d_in, z, sizeof(double) * (size_t)d_in);
-        for (int32_t c = 0; c < d_out; ++c) u[c] = 0.0;
-        for (int32_t k = 0; k < d_in; ++k) {
-            const double *w = Wr + (size_t)r * dd + (size_t)k * d_out;
-            for (int32_t c = 0; c < d_out; ++c) u[c] += z[k] * w[c];
-        }
-        double *o = pre + (size_t)i * d_out;
-        for (int32_t c = 0; c < d_out; ++c) o[c] += round_msg(u[c], 1);
-    }
-    free(u);
-    free(z);
-    free(Wr);
 }
 
 /*
  * One layer forward over the whole partition:
  *   pre_i = sum_r sum_{j in N_i^r} (1/c_{i,r}) h_j W_r + h_i W_0,   W_r = sum_b a_rb V_b
  *   h'_i  = act(pre_i)                        act: 0 identity, 1 ReLU
- * P_scratch is [N][B][d_out] doubles.  msg_bf16 != 0 models a workload whose projections are
- * a bf16 contraction with bf16 message storage (see round_msg); 2 models the bf16 pipeline that
- * sums neighbours first (forward_aggregate_first_bf16); 3 the one that writes Eq. 2 out per relation
- * (forward_relation_weights_bf16); 0 keeps everything exact.
+ * P_scratch is [N][B][d_out] doubles.  Everything is exact double arithmetic: workloads that keep
+ * messages in bf16 are compared with these values under their wider tolerance.
  */
 void orc_rgcn_layer_forward(int64_t N, int64_t S, const int32_t *seg_ptr, const int32_t *seg_rel,
                             const int32_t *seg_dst, const int32_t *col_src,
                             int32_t d_in, int32_t d_out, int32_t B,
                             const double *V, const double *a, const double *W0, int32_t act,
-                            int32_t msg_bf16,
                             const double *H, double *P_scratch, double *pre, double *Hout)
 {
-    if (msg_bf16 == 3) {
-        int32_t n_rel2 = 0;
-        for (int64_t s = 0; s < S; ++s) if (seg_rel[s] + 1 > n_rel2) n_rel2 = seg_rel[s] + 1;
-        forward_relation_weights_bf16(N, S, seg_ptr, seg_rel, seg_dst, col_src, d_in, d_out, B, n_rel2, V, a, W0, H,
-                                      pre, NULL);
-        for (size_t q = 0; q < (size_t)N * d_out; ++q) Hout[q] = act_fwd(act, pre[q]);
-        return;
-    }
-    if (msg_bf16 == 2) {
-        forward_aggregate_first_bf16(N, S, seg_ptr, seg_rel, seg_dst, col_src, d_in, d_out, B, V, a, W0, H, pre, NULL);
-        for (size_t q = 0; q < (size_t)N * d_out; ++q) Hout[q] = act_fwd(act, pre[q]);
-        return;
-    }
-    project_all(N, d_in, d_out, B, V, H, P_scratch, msg_bf16);
+    project_all(N, d_in, d_out, B, V, H, P_scratch);
     /* self-loop: h_i W_0 */
     for (int64_t i = 0; i < N; ++i) {
         double *o = pre + (size_t)i * d_out;
         for (int32_t c = 0; c < d_out; ++c) o[c] = 0.0;
         for (int32_t k = 0; k < d_in; ++k) {
-            double h = round_msg(H[(size_t)i * d_in + k], msg_bf16);
+            double h = H[(size_t)i * d_in + k];
             const double *w = W0 + (size_t)k * d_out;
-            for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(w[c], msg_bf16);
+            for (int32_t c = 0; c < d_out; ++c) o[c] += h * w[c];
         }
     }
     /* neighbours, one (relation, destination) run at a time */
@@ -429,74 +288,17 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
                          const int64_t *row_seg, const int32_t *seg_ptr, const int32_t *seg_rel,
                          const int32_t *col_src, int32_t d_in, int32_t d_out, int32_t B,
                          const double *V, const double *a, const double *W0, int32_t act,
-                         int32_t msg_bf16,
                          const float *H /* [N][d_in], the layer input as stored */,
                          double *pre_rows, double *out_rows)
 {
     double *pj = (double *)malloc(sizeof(double) * (size_t)d_out);
-    double *yrow = (double *)malloc(sizeof(double) * (size_t)B * d_in);
-    double *zrow = (double *)malloc(sizeof(double) * (size_t)d_in);
     for (int64_t q = 0; q < n_rows; ++q) {
         int32_t i = rows[q];
         double *o = pre_rows + (size_t)q * d_out;
         for (int32_t c = 0; c < d_out; ++c) o[c] = 0.0;
-        if (msg_bf16 == 3) {      /* Eq. 2 written out per relation, see forward_relation_weights_bf16 */
-            for (int32_t k = 0; k < d_in; ++k) {
-                double h = round_msg((double)H[(size_t)i * d_in + k], 1);
-                for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(W0[(size_t)k * d_out + c], 1);
-            }
-            for (int64_t t = row_seg_ptr[q]; t < row_seg_ptr[q + 1]; ++t) {
-                int64_t s = row_seg[t];
-                int32_t r = seg_rel[s];
-                double cnt = (double)(seg_ptr[s + 1] - seg_ptr[s]);
-                for (int32_t k = 0; k < d_in; ++k) zrow[k] = 0.0;
-                for (int32_t e = seg_ptr[s]; e < seg_ptr[s + 1]; ++e)
-                    for (int32_t k = 0; k < d_in; ++k)
-                        zrow[k] += round_msg((double)H[(size_t)col_src[e] * d_in + k], 1);
-                for (int32_t k = 0; k < d_in; ++k) zrow[k] = round_msg(zrow[k] / cnt, 1);
-                for (int32_t c = 0; c < d_out; ++c) pj[c] = 0.0;
-                for (int32_t k = 0; k < d_in; ++k)
-                    for (int32_t c = 0; c < d_out; ++c) {
-                        double wr = 0.0;                       /* W_r[k][c], rounded */
-                        for (int32_t b = 0; b < B; ++b)
-                            wr += a[(size_t)r * B + b] * V[((size_t)b * d_in + k) * d_out + c];
-                        pj[c] += zrow[k] * round_msg(wr, 1);
-                    }
-                for (int32_t c = 0; c < d_out; ++c) o[c] += round_msg(pj[c], 1);
-            }
-            for (int32_t c = 0; c < d_out; ++c) out_rows[(size_t)q * d_out + c] = act_fwd(act, o[c]);
-            continue;
-        }
-        if (msg_bf16 == 2) {      /* the regrouped evaluation, see forward_aggregate_first_bf16 */
-            for (size_t x = 0; x < (size_t)B * d_in; ++x) yrow[x] = 0.0;
-            for (int64_t t = row_seg_ptr[q]; t < row_seg_ptr[q + 1]; ++t) {
-                int64_t s = row_seg[t];
-                double cnt = (double)(seg_ptr[s + 1] - seg_ptr[s]);
-                for (int32_t k = 0; k < d_in; ++k) zrow[k] = 0.0;
-                for (int32_t e = seg_ptr[s]; e < seg_ptr[s + 1]; ++e)
-                    for (int32_t k = 0; k < d_in; ++k)
-                        zrow[k] += round_msg((double)H[(size_t)col_src[e] * d_in + k], 1);
-                for (int32_t k = 0; k < d_in; ++k) zrow[k] = round_msg(zrow[k] / cnt, 1);
-                for (int32_t b = 0; b < B; ++b)
-                    for (int32_t k = 0; k < d_in; ++k)
-                        yrow[(size_t)b * d_in + k] += a[(size_t)seg_rel[s] * B + b] * zrow[k];
-            }
-            for (int32_t k = 0; k < d_in; ++k) {
-                double h = round_msg((double)H[(size_t)i * d_in + k], 1);
-                for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(W0[(size_t)k * d_out + c], 1);
-            }
-            for (int32_t b = 0; b < B; ++b)
-                for (int32_t k = 0; k < d_in; ++k) {
-                    double yq = round_msg(yrow[(size_t)b * d_in + k], 1);
-                    for (int32_t c = 0; c < d_out; ++c)
-                        o[c] += yq * round_msg(V[((size_t)b * d_in + k) * d_out + c], 1);
-                }
-            for (int32_t c = 0; c < d_out; ++c) out_rows[(size_t)q * d_out + c] = act_fwd(act, o[c]);
-            continue;
-        }
         for (int32_t k = 0; k < d_in; ++k) {
-            double h = round_msg((double)H[(size_t)i * d_in + k], msg_bf16);
-            for (int32_t c = 0; c < d_out; ++c) o[c] += h * round_msg(W0[(size_t)k * d_out + c], msg_bf16);
+            double h = (double)H[(size_t)i * d_in + k];
+            for (int32_t c = 0; c < d_out; ++c) o[c] += h * W0[(size_t)k * d_out + c];
         }
         for (int64_t t = row_seg_ptr[q]; t < row_seg_ptr[q + 1]; ++t) {
             int64_t s = row_seg[t];
@@ -508,20 +310,17 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
                     const double *Vb = V + (size_t)b * d_in * d_out;
                     for (int32_t c = 0; c < d_out; ++c) pj[c] = 0.0;
                     for (int32_t k = 0; k < d_in; ++k) {
-                        double h = round_msg((double)H[(size_t)j * d_in + k], msg_bf16);
-                        for (int32_t c = 0; c < d_out; ++c)
-                            pj[c] += h * round_msg(Vb[(size_t)k * d_out + c], msg_bf16);
+                        double h = (double)H[(size_t)j * d_in + k];
+                        for (int32_t c = 0; c < d_out; ++c) pj[c] += h * Vb[(size_t)k * d_out + c];
                     }
                     double w = a[(size_t)r * B + b] * invc;
-                    for (int32_t c = 0; c < d_out; ++c) o[c] += w * round_msg(pj[c], msg_bf16);
+                    for (int32_t c = 0; c < d_out; ++c) o[c] += w * pj[c];
                 }
             }
         }
         for (int32_t c = 0; c < d_out; ++c) out_rows[(size_t)q * d_out + c] = act_fwd(act, o[c]);
     }
     free(pj);
-    free(yrow);
-    free(zrow);
 }
 
 /*
@@ -533,23 +332,18 @@ void orc_rgcn_layer_rows(int64_t n_rows, const int32_t *rows, const int64_t *row
  *       dP[j][b][:] += a_rb w Gpre_i
  *   dV_b = H^T dP_b,                dH_j  += sum_b dP[j][b][:] V_b^T
  * P_scratch and dP_scratch are [N][B][d_out]; dH_in may be NULL.
- * msg_bf16 == 1: the projected messages h_j V_b in da are the rounded ones the forward pass kept.
- * msg_bf16 == 2: da_rb = sum_runs <z_{i,r} V_b, Gpre_i> with the rounded run means z the regrouped
- * forward pass kept (the same sum, since sum_j (1/c) h_j V_b = z V_b); msg_bf16 == 3 likewise.
- * All else is exact.
  */
 void orc_rgcn_layer_backward(int64_t N, int64_t S, const int32_t *seg_ptr, const int32_t *seg_rel,
                              const int32_t *seg_dst, const int32_t *col_src,
                              int32_t d_in, int32_t d_out, int32_t B, int32_t n_rel2,
                              const double *V, const double *a, const double *W0, int32_t act,
-                             int32_t msg_bf16,
                              const double *H, const double *pre, const double *dHout,
                              double *P_scratch, double *dP_scratch, double *Gpre,
                              double *dV, double *da, double *dW0, double *dH_in)
 {
     size_t nd_out = (size_t)N * d_out;
     for (size_t q = 0; q < nd_out; ++q) Gpre[q] = dHout[q] * act_grad(act, pre[q]);
-    project_all(N, d_in, d_out, B, V, H, P_scratch, msg_bf16 >= 2 ? 0 : msg_bf16);
+    project_all(N, d_in, d_out, B, V, H, P_scratch);
     memset(dP_scratch, 0, sizeof(double) * (size_t)N * B * d_out);
     memset(dV, 0, sizeof(double) * (size_t)B * d_in * d_out);
     memset(da, 0, sizeof(double) * (size_t)n_rel2 * B);
@@ -579,31 +373,9 @@ void orc_rgcn_layer_backward(int64_t N, int64_t S, const int32_t *seg_ptr, const
                 double *dpj = dP_scratch + ((size_t)j * B + b) * d_out;
                 double dot = 0.0, w = a[(size_t)r * B + b] * invc;
                 for (int32_t c = 0; c < d_out; ++c) { dot += pj[c] * g[c]; dpj[c] += w * g[c]; }
-                if (msg_bf16 < 2) da[(size_t)r * B + b] += invc * dot;
+                da[(size_t)r * B + b] += invc * dot;
             }
         }
-    }
-    if (msg_bf16 >= 2) {
-        double *zq = (double *)malloc(sizeof(double) * (size_t)(S > 0 ? S : 1) * d_in);
-        double *scratch_pre = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1) * d_out);
-        forward_aggregate_first_bf16(N, S, seg_ptr, seg_rel, seg_dst, col_src, d_in, d_out, B, V, a, W0, H,
-                                     scratch_pre, zq);
-        for (int64_t s = 0; s < S; ++s) {
-            const double *g = Gpre + (size_t)seg_dst[s] * d_out;
-            const double *z = zq + (size_t)s * d_in;
-            for (int32_t b = 0; b < B; ++b) {
-                double dot = 0.0;
-                for (int32_t k = 0; k < d_in; ++k) {
-                    const double *v = V + ((size_t)b * d_in + k) * d_out;
-                    double t = 0.0;
-                    for (int32_t c = 0; c < d_out; ++c) t += v[c] * g[c];
-                    dot += z[k] * t;
-                }
-                da[(size_t)seg_rel[s] * B + b] += dot;
-            }
-        }
-        free(scratch_pre);
-        free(zq);
     }
     for (int64_t j = 0; j < N; ++j)
         for (int32_t b = 0; b < B; ++b) {
@@ -795,13 +567,9 @@ void orc_optimizer_step(int32_t kind, double *p, const double *g, double *m, dou
  *                                       key = (seed lo, seed hi xor (layer + 1)))
  * keep iff x[k mod 4] >= floor(p * 2^32).  mask (optional) receives 1 for kept elements.
  * p = 0 keeps everything.
- * product_f32 != 0: the scaled value is the single-precision product of the single-precision values
- * of h and 1 / (1 - p).  The bf16 pipelines round the dropped input to bf16 next; that rounding is a
- * decision taken from a floating-point value, so the value it is taken from is formed in the
- * precision the kernels use (the paper fixes none).
  */
 void orc_dropout(int64_t N, int32_t d, double p, uint64_t seed, uint64_t step, int32_t layer,
-                 int32_t product_f32, const double *H, double *out, uint8_t *mask)
+                 const double *H, double *out, uint8_t *mask)
 {
     uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) ^ (uint32_t)(layer + 1) };
     uint32_t thr = (uint32_t)(p * 4294967296.0);
@@ -814,9 +582,7 @@ void orc_dropout(int64_t N, int32_t d, double p, uint64_t seed, uint64_t step, i
             for (int32_t q = 0; q < 4 && 4 * g + q < d; ++q) {
                 size_t e = (size_t)i * d + 4 * g + q;
                 int keep = p <= 0.0 || x[q] >= thr;
-                if (!keep) out[e] = 0.0;
-                else if (product_f32) out[e] = (double)((float)H[e] * (float)scale);
-                else out[e] = H[e] * scale;
+                out[e] = keep ? H[e] * scale : 0.0;
                 if (mask) mask[e] = (uint8_t)keep;
             }
         }

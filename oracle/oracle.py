@@ -85,9 +85,7 @@ def _d(x):
     return np.ascontiguousarray(x, np.float64)
 
 
-# msg_bf16: False/0 exact; True/1 bf16 projections with bf16 message storage (project-first pipeline);
-# 2 the bf16 pipeline that sums neighbours first (run means, per-basis sums and weights rounded).
-def layer_forward(part, V, a, W0, act, H, msg_bf16=False):
+def layer_forward(part, V, a, W0, act, H):
     """One RGCN layer over the whole partition (Eq. 1-2). Returns (pre, H') in float64."""
     L = lib()
     V, a, W0, H = _d(V), _d(a), _d(W0), _d(H)
@@ -101,23 +99,20 @@ def layer_forward(part, V, a, W0, act, H, msg_bf16=False):
                              _p(part["seg_rel"], _I32), _p(part["seg_dst"], _I32),
                              _p(part["col_src"], _I32), C.c_int32(d_in), C.c_int32(d_out),
                              C.c_int32(B), _p(V, _F64), _p(a, _F64), _p(W0, _F64), C.c_int32(act),
-                             C.c_int32(int(msg_bf16)),
                              _p(H, _F64), _p(P, _F64), _p(pre, _F64), _p(out, _F64))
     return pre, out
 
 
-def dropout(H, p, seed, step, layer, product_f32=False):
-    """Inverted dropout on a layer's input with a counter-based mask.  Returns (dropped H, keep mask).
-    product_f32: form h / (1 - p) as a single-precision product (what the bf16 pipelines round next)."""
+def dropout(H, p, seed, step, layer):
+    """Inverted dropout on a layer's input with a counter-based mask.  Returns (dropped H, keep mask)."""
     H = _d(H)
     out = np.zeros_like(H); mask = np.zeros(H.shape, np.uint8)
     lib().orc_dropout(C.c_int64(H.shape[0]), C.c_int32(H.shape[1]), C.c_double(p), C.c_uint64(seed),
-                      C.c_uint64(step), C.c_int32(layer), C.c_int32(int(product_f32)), _p(H, _F64), _p(out, _F64),
-                      _p(mask, _U8))
+                      C.c_uint64(step), C.c_int32(layer), _p(H, _F64), _p(out, _F64), _p(mask, _U8))
     return out, mask
 
 
-def rgcn_forward(part, layers: Sequence[dict], H0, msg_bf16=False, drop=None):
+def rgcn_forward(part, layers: Sequence[dict], H0, drop=None):
     """All layers.  ``layers[l]`` has V [B,d,d], a [2R,B], W0 [d,d], act.  Returns the list of
     layer inputs/outputs ``Hs`` (len L+1, Hs[0] = H0) and pre-activations ``pres`` (len L).
 
@@ -127,15 +122,15 @@ def rgcn_forward(part, layers: Sequence[dict], H0, msg_bf16=False, drop=None):
     Hs, pres, masks = [_d(H0)], [], []
     for l, lay in enumerate(layers):
         if drop is not None:
-            Hs[-1], m = dropout(Hs[-1], drop[0], drop[1], drop[2], l, bool(msg_bf16))
+            Hs[-1], m = dropout(Hs[-1], drop[0], drop[1], drop[2], l)
             masks.append(m)
-        pre, out = layer_forward(part, lay["V"], lay["a"], lay["W0"], lay["act"], Hs[-1], msg_bf16)
+        pre, out = layer_forward(part, lay["V"], lay["a"], lay["W0"], lay["act"], Hs[-1])
         pres.append(pre)
         Hs.append(out)
     return (Hs, pres, masks) if drop is not None else (Hs, pres)
 
 
-def layer_backward(part, V, a, W0, act, H, pre, dHout, need_dH=True, msg_bf16=False):
+def layer_backward(part, V, a, W0, act, H, pre, dHout, need_dH=True):
     L = lib()
     V, a, W0, H, pre, dHout = _d(V), _d(a), _d(W0), _d(H), _d(pre), _d(dHout)
     B, d_in, d_out = V.shape
@@ -147,15 +142,14 @@ def layer_backward(part, V, a, W0, act, H, pre, dHout, need_dH=True, msg_bf16=Fa
                               _p(part["seg_rel"], _I32), _p(part["seg_dst"], _I32),
                               _p(part["col_src"], _I32), C.c_int32(d_in), C.c_int32(d_out),
                               C.c_int32(B), C.c_int32(a.shape[0]), _p(V, _F64), _p(a, _F64),
-                              _p(W0, _F64), C.c_int32(act), C.c_int32(int(msg_bf16)),
-                              _p(H, _F64), _p(pre, _F64),
+                              _p(W0, _F64), C.c_int32(act), _p(H, _F64), _p(pre, _F64),
                               _p(dHout, _F64), _p(P, _F64), _p(dP, _F64), _p(G, _F64),
                               _p(dV, _F64), _p(da, _F64), _p(dW0, _F64),
                               _p(dH, _F64) if need_dH else None)
     return dict(dV=dV, da=da, dW0=dW0, dH=dH, dP=dP, Gpre=G)
 
 
-def rgcn_backward(part, layers, Hs, pres, dH_out, need_dH0=True, msg_bf16=False, drop=None, masks=None):
+def rgcn_backward(part, layers, Hs, pres, dH_out, need_dH0=True, drop=None, masks=None):
     """Reverse of :func:`rgcn_forward`. Returns per-layer grads (list) and dH0 (or None).  With
     dropout (``drop`` and the forward's ``masks``) the gradient handed to the layer below, and dH0,
     is the one with respect to the input before dropout."""
@@ -164,7 +158,7 @@ def rgcn_backward(part, layers, Hs, pres, dH_out, need_dH0=True, msg_bf16=False,
     for l in range(len(layers) - 1, -1, -1):
         lay = layers[l]
         need = need_dH0 or l > 0
-        r = layer_backward(part, lay["V"], lay["a"], lay["W0"], lay["act"], Hs[l], pres[l], g, need, msg_bf16)
+        r = layer_backward(part, lay["V"], lay["a"], lay["W0"], lay["act"], Hs[l], pres[l], g, need)
         grads[l] = r
         g = r["dH"]
         if drop is not None and g is not None:
@@ -172,7 +166,7 @@ def rgcn_backward(part, layers, Hs, pres, dH_out, need_dH0=True, msg_bf16=False,
     return grads, g
 
 
-def layer_rows(part, rows, V, a, W0, act, H_f32, msg_bf16=False):
+def layer_rows(part, rows, V, a, W0, act, H_f32):
     """Layer output for the listed destination rows only, from the stored float32 input."""
     L = lib()
     rows = np.ascontiguousarray(rows, np.int32)
@@ -191,8 +185,7 @@ def layer_rows(part, rows, V, a, W0, act, H_f32, msg_bf16=False):
     L.orc_rgcn_layer_rows(C.c_int64(len(rows)), _p(rows, _I32), _p(ptr, _I64), _p(segs, _I64),
                           _p(part["seg_ptr"], _I32), _p(part["seg_rel"], _I32),
                           _p(part["col_src"], _I32), C.c_int32(d_in), C.c_int32(d_out), C.c_int32(B),
-                          _p(V, _F64), _p(a, _F64), _p(W0, _F64), C.c_int32(act),
-                          C.c_int32(int(msg_bf16)), _p(H_f32, _F32),
+                          _p(V, _F64), _p(a, _F64), _p(W0, _F64), C.c_int32(act), _p(H_f32, _F32),
                           _p(pre, _F64), _p(out, _F64))
     return pre, out
 
@@ -272,18 +265,17 @@ def optimizer_step(kind, p, g, m, v, lr=0.01, b1=0.9, b2=0.999, eps=1e-8, t=1, r
                              C.c_double(lr), C.c_double(b1), C.c_double(b2), C.c_double(eps), C.c_int64(t))
 
 
-def train_step(part, layers, H0, M, pos_core_idx, n_neg, mode, seed, step, need_dH0=True,
-               msg_bf16=False, dropout=0.0):
+def train_step(part, layers, H0, M, pos_core_idx, n_neg, mode, seed, step, need_dH0=True, dropout=0.0):
     """One whole step: encoder forward, negatives, score + loss, encoder backward.  With
     ``dropout`` > 0 every layer's input is dropped with masks keyed by the step's (seed, step)."""
     drop = (float(dropout), seed, step) if dropout > 0 else None
     masks = None
     if drop is None:
-        Hs, pres = rgcn_forward(part, layers, H0, msg_bf16)
+        Hs, pres = rgcn_forward(part, layers, H0)
     else:
-        Hs, pres, masks = rgcn_forward(part, layers, H0, msg_bf16, drop)
+        Hs, pres, masks = rgcn_forward(part, layers, H0, drop)
     ne, ns = sample_negatives(part, pos_core_idx, n_neg, mode, seed, step)
     sl = distmult_score_loss(part, Hs[-1], M, pos_core_idx, ne, ns)
-    grads, dH0 = rgcn_backward(part, layers, Hs, pres, sl["dH"], need_dH0, msg_bf16, drop, masks)
+    grads, dH0 = rgcn_backward(part, layers, Hs, pres, sl["dH"], need_dH0, drop, masks)
     return dict(Hs=Hs, pres=pres, neg_ent=ne, neg_side=ns, scores=sl["scores"], loss=sl["loss"],
                 dH_out=sl["dH"], dM=sl["dM"], grads=grads, dH0=dH0, masks=masks, drop=drop)

@@ -111,23 +111,12 @@ def euler_quantity(pre, H_in, W0, G, chunk=1 << 18):
 
 
 # ---- the regrouped evaluation of Eq. 1-2 (run means z, per-basis sums y), sampled ----------------
-def round_bf16(x):
-    """float -> nearest bfloat16 (ties to even), returned as float64.  Bit arithmetic on the float32
-    pattern: add half a unit of the kept part, plus its lowest bit for ties, and drop 16 bits."""
-    u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
-    r = ((u + 0x7fff + ((u >> 16) & 1)) & 0xffff0000).astype(np.uint32)
-    return r.view(np.float32).astype(np.float64).reshape(np.shape(x))
-
-
-def run_mean_rows(part, runs, H, bf16=False):
-    """z_s = (1/c_s) sum_{j in run s} h_j for the listed runs; with bf16, inputs are rounded first."""
+def run_mean_rows(part, runs, H):
+    """z_s = (1/c_s) sum_{j in run s} h_j for the listed runs."""
     out = np.zeros((len(runs), H.shape[1]))
     for k, s in enumerate(runs):
         src = part["col_src"][part["seg_ptr"][s]:part["seg_ptr"][s + 1]]
-        rows = np.asarray(H[src], np.float64)
-        if bf16:
-            rows = round_bf16(rows)
-        out[k] = rows.sum(0) / len(src)
+        out[k] = np.asarray(H[src], np.float64).sum(0) / len(src)
     return out
 
 
@@ -177,13 +166,12 @@ def relation_weight(a, V, r):
     return np.einsum("b,bkc->kc", np.asarray(a, np.float64)[r], np.asarray(V, np.float64))
 
 
-def relation_product_rows(part, runs, Z_of, a, V, bf16=False):
-    """u_s = z_s W_{rel(s)} for the listed runs; with bf16, W_r is rounded first (z comes as stored)."""
+def relation_product_rows(part, runs, Z_of, a, V):
+    """u_s = z_s W_{rel(s)} for the listed runs (z as Z_of returns it)."""
     z = np.asarray(Z_of(runs), np.float64)
     out = np.zeros((len(runs), np.shape(V)[2]))
     for k, s in enumerate(runs):
-        W = relation_weight(a, V, part["seg_rel"][s])
-        out[k] = z[k] @ (round_bf16(W) if bf16 else W)
+        out[k] = z[k] @ relation_weight(a, V, part["seg_rel"][s])
     return out
 
 
@@ -193,3 +181,34 @@ def relation_product_t_rows(part, runs, G, a, V):
     for k, s in enumerate(runs):
         out[k] = np.asarray(G[part["seg_dst"][s]], np.float64) @ relation_weight(a, V, part["seg_rel"][s]).T
     return out
+
+
+# ---- reductions over every vertex or edge, at any size ----------------------------------------------
+def basis_weight_grad_projection(ev: EdgeView, a, H_in, G, x, y):
+    """x^T dV_b y for every basis b, where dV_b = H^T dP_b and dP[j][b][:] = sum over edges j -> i under r
+    of a_rb (1/c_{i,r}) G_i (chain rule on Eq. 1-2):
+        x^T dV_b y = sum_e (h_{src(e)} . x) a_{rel(e), b} (1/c_e) (G_{dst(e)} . y)
+    One pass over the edges whatever the sizes; checks every element of dV_b in one random direction."""
+    a = np.asarray(a, np.float64)
+    hx = np.asarray(H_in, np.float64) @ np.asarray(x, np.float64)        # [N]
+    gy = np.asarray(G, np.float64) @ np.asarray(y, np.float64)           # [N]
+    w = hx[ev.src] * ev.invc * gy[ev.dst]                                # one term per edge
+    per_rel = np.bincount(ev.rel, weights=w, minlength=a.shape[0])       # sum over the edges of a relation
+    return per_rel @ a                                                   # [B]
+
+
+def coeff_grad_relation_edges(ev: EdgeView, r, H_in, G, V, chunk=1 << 18):
+    """da[r][b] for every basis b of ONE relation, however many edges it has:
+        da_rb = sum over edges j -> i under r of (1/c_{i,r}) <h_j V_b, G_i> = <C_r, V_b>,
+        C_r = sum_e (1/c_e) h_{src(e)}^T G_{dst(e)}     (d_in x d_out, a dense product chunk by chunk)."""
+    V = np.asarray(V, np.float64)
+    live = np.zeros(ev.n_vert, bool)                 # edges into rows whose gradient is zero add nothing
+    for s in range(0, ev.n_vert, 1 << 20):
+        live[s:s + (1 << 20)] = np.abs(G[s:s + (1 << 20)]).max(axis=1) > 0
+    e = np.nonzero((ev.rel == r) & live[ev.dst])[0]
+    C = np.zeros(V.shape[1:])
+    for s in range(0, len(e), chunk):
+        ee = e[s:s + chunk]
+        g = np.asarray(G[ev.dst[ee]], np.float64) * ev.invc[ee][:, None]
+        C += np.asarray(H_in[ev.src[ee]], np.float64).T @ g
+    return np.einsum("kc,bkc->b", C, V)

@@ -49,6 +49,7 @@ class WorkloadSpec:
     neg_mode: int             # 0 tail only, 1 head-or-tail with p = 0.5
     neg_domain: int = 0       # 0 endpoints of core edges, 1 all partition vertices
     acts: List[int] = field(default_factory=lambda: [1, 0])   # ReLU then identity
+    d_in: Optional[int] = None   # width of the layer-1 input when it differs from d (fixed features)
 
 
 def _w(name, seed, n, r, m, hd, he, hc, td, te, tc, rz, P, pid, d, B, dt, fstd, fixed,
@@ -61,7 +62,7 @@ def _w(name, seed, n, r, m, hd, he, hc, td, te, tc, rz, P, pid, d, B, dt, fstd, 
                         n_pos=npos, n_neg=nneg, neg_mode=mode)
 
 
-#: The five benchmark workloads, index = config number.
+#: The five benchmark workloads, index = config number.  (PAPER_LARGE below is a sixth, outside the list.)
 WORKLOADS: List[WorkloadSpec] = [
     _w("tiny-kg", 0, 1_000, 10, 5_000, "uniform", 0, 0, "uniform", 0, 0, 1.1,
        1, 0, 32, 4, "f32", 0.1, False, 1_024, 1, 0),
@@ -76,6 +77,13 @@ WORKLOADS: List[WorkloadSpec] = [
        "uniform", 0, 0, 1.1,
        4, 0, 256, 64, "bf16", 0.1, False, 65_536, 64, 1),
 ]
+
+
+def paper_large_setting() -> WorkloadSpec:
+    """The citation-shaped workload with the hyper-parameters the paper trains its large graph with
+    (Sec. 4): 128 fixed input features, 32-wide embeddings, 2 bases, 1 negative per positive; dropout 0.2
+    is a run-time setting of the step.  Same graph, partition and batch as WORKLOADS[3]."""
+    return scaled(WORKLOADS[3], name="citation-part0of16-paper-setting", d=32, d_in=128, n_bases=2, n_neg=1)
 
 
 def scaled(spec: WorkloadSpec, **kw) -> WorkloadSpec:
@@ -133,21 +141,24 @@ def make_params(spec: WorkloadSpec, n_vertices: int) -> Dict[str, object]:
     ``n_vertices`` local vertices.
 
     Returns dict with ``H0`` [N,d], per-layer lists ``V`` [B,d,d], ``a`` [2R,B],
-    ``W0`` [d,d], and ``M`` [R,d] (the decoder's diagonals), all float32."""
+    ``W0`` [d,d], and ``M`` [R,d] (the decoder's diagonals), all float32; with ``spec.d_in`` set the
+    layer-1 input and the first layer's V, W0 have that many rows."""
     rng = np.random.default_rng(spec.seed + 1_000_003)
     d, B, R2 = spec.d, spec.n_bases, 2 * spec.n_relations
+    d0 = spec.d_in if spec.d_in else d
     out: Dict[str, object] = {"V": [], "a": [], "W0": []}
-    for _ in range(spec.n_layers):
-        out["V"].append(_glorot(rng, (B, d, d), d, d))
+    for l in range(spec.n_layers):
+        di = d0 if l == 0 else d
+        out["V"].append(_glorot(rng, (B, di, d), di, d))
         out["a"].append(_glorot(rng, (R2, B), R2, B))
-        out["W0"].append(_glorot(rng, (d, d), d, d))
+        out["W0"].append(_glorot(rng, (di, d), di, d))
     out["M"] = (rng.standard_normal((spec.n_relations, d)) * 0.1).astype(np.float32)
     # Row-chunked so the float64 temporaries of the big workloads stay small.
-    H0 = np.empty((n_vertices, d), dtype=np.float32)
+    H0 = np.empty((n_vertices, d0), dtype=np.float32)
     step = 1 << 18
     for s in range(0, n_vertices, step):
         e = min(n_vertices, s + step)
-        H0[s:e] = rng.standard_normal((e - s, d), dtype=np.float32) * np.float32(spec.feature_std)
+        H0[s:e] = rng.standard_normal((e - s, d0), dtype=np.float32) * np.float32(spec.feature_std)
     out["H0"] = H0
     return out
 

@@ -7,7 +7,8 @@ import numpy as np
 import pytest
 
 from paper_2201_02791_amd import synth
-from gpu_util import (SEED, STEP, assert_partition_equal, assert_step_close, gpu_step, oracle_step)
+from gpu_util import (SEED, STEP, align_mask_decisions, assert_partition_equal, assert_step_close, gpu_step,
+                      oracle_step)
 
 pytestmark = pytest.mark.gpu
 TOL_VAL, TOL_GRAD, TOL_BF16 = 1e-4, 1e-3, 2e-2
@@ -99,6 +100,9 @@ def test_cone_bf16_messages(kb, orc):
     gp, ts, params, pos = gpu_step(spec, head, rel, tail, cone=True)
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
     check_flags(orc, ts, op, pos, res, 2)
+    active = orc.compute_graph(op, pos, res["neg_ent"], 2)
+    n_adopted, res = align_mask_decisions(orc, ts, op, res, params, spec.acts, True, True, rows=active)
+    say("mask decisions inside the rounding band, taken as the kernel took them:", n_adopted)
     assert_step_close(ts, res, TOL_BF16, TOL_BF16, batch_rows=orc.batch_vertices(op, pos, res["neg_ent"]))
 
 

@@ -15,7 +15,6 @@ TOL_VAL, TOL_GRAD, TOL_BF16 = 1e-4, 1e-3, 2e-2
 PROJ, AGG, RELW = 0, 1, 2
 ORDERS = [pytest.param(PROJ, id="project_first"), pytest.param(AGG, id="aggregate_first"),
           pytest.param(RELW, id="relation_weights")]
-BF16_MODE = {PROJ: 1, AGG: 2, RELW: 3}
 
 
 def say(*a):
@@ -74,7 +73,7 @@ def test_step_with_dropout(kb, orc, order, cone):
     gp, ts, params, pos = gpu_step(spec, head, rel, tail, cone=cone, order=order, dropout=0.2)
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos, dropout=0.2)
     rows = orc.compute_graph(op, pos, res["neg_ent"], 2) if cone else None
-    n_flip, res = align_mask_decisions(orc, ts, op, res, params, spec.acts, True, 0, rows=rows)
+    n_flip, res = align_mask_decisions(orc, ts, op, res, params, spec.acts, True, False, rows=rows)
     assert n_flip <= 8
     assert_step_close(ts, res, TOL_VAL, TOL_GRAD,
                       batch_rows=orc.batch_vertices(op, pos, res["neg_ent"]) if cone else None)
@@ -87,16 +86,11 @@ def test_step_with_dropout_bf16_messages(kb, orc, order):
                         d=64, n_bases=6, n_pos=200, n_neg=3, n_parts=1, part_id=0, acts=[1, 0])
     head, rel, tail = synth.make_triples(spec)
     gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=order, dropout=0.2)
-    mode = BF16_MODE[order]
-    op, res = oracle_step(orc, spec, head, rel, tail, params, pos, msg_bf16=mode, dropout=0.2)
-    # project-first stores every projected message in bf16, and that stored value differs by one bf16
-    # unit wherever the fp32 and fp64 sums fall on different sides of a rounding boundary: there a
-    # pre-activation within bf16 rounding of zero can take either sign.  The other two orders keep
-    # their sums in fp32 up to the activation.
-    n_flip, res = align_mask_decisions(orc, ts, op, res, params, spec.acts, True, mode,
-                                       thresh=1e-2 if order == PROJ else 1e-4)
-    say("mask decisions adopted from the kernel:", n_flip)
-    assert n_flip <= (64 if order == PROJ else 8)
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos, dropout=0.2)
+    # against the exact oracle; ReLU decisions inside the rounding band of their own sum (asserted, and few)
+    # are taken as the kernel took them
+    n_flip, res = align_mask_decisions(orc, ts, op, res, params, spec.acts, True, True)
+    say("mask decisions inside the rounding band, taken as the kernel took them:", n_flip)
     assert_step_close(ts, res, TOL_BF16, TOL_BF16)
 
 

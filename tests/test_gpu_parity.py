@@ -141,12 +141,10 @@ def test_hub_vertex_and_isolated_rows(kb, orc):
                                           ([0, 0], 900, 9000, 96, 40)],
                          ids=["identity", "relu", "identity_B40_d96"])
 def test_bf16_messages_small(kb, orc, acts, n, m, d, B):
-    """Messages stored as bf16 (fp32 accumulation), tolerance 2e-2.
-    The ReLU mask of layer 1 is a decision taken from floating-point values: a pre-activation
-    within bf16 rounding of zero flips it, and each flip changes layer-1 gradients by whole
-    terms.  So the full comparison is against the oracle that stores messages in bf16 as the
-    workload specifies (both sides then take the mask decision in the same precision), and the
-    outputs that do not depend on that decision are also held to 2e-2 against the exact oracle."""
+    """Messages stored as bf16 (fp32 accumulation): every output against the exact oracle at 2e-2.
+    The ReLU mask of layer 1 is a decision taken from floating-point values; where a pre-activation
+    lies inside the rounding band of its own sum the decision is the kernel's (align_mask_decisions
+    asserts the band and that such elements are few), everything else is the oracle's arithmetic."""
     say("bf16 small", acts, n, m, d, B)
     spec = synth.scaled(synth.WORKLOADS[4], name="bf16-small", seed=3, n_entities=n, n_relations=20,
                         n_triples=m, d=d, n_bases=B, n_pos=256, n_neg=4, n_parts=2, part_id=0, acts=acts)
@@ -154,18 +152,10 @@ def test_bf16_messages_small(kb, orc, acts, n, m, d, B):
     gp, ts, params, pos = gpu_step(spec, head, rel, tail)
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
     assert_partition_equal(gp, op)
+    n_adopted, res = align_mask_decisions(orc, ts, op, res, params, acts, True, True)
+    say("mask decisions inside the rounding band, taken as the kernel took them:", n_adopted)
     errs = assert_step_close(ts, res, TOL_BF16, TOL_BF16)
-    say("bf16 errs vs bf16-storage oracle", errs)
-    _, exact = oracle_step(orc, spec, head, rel, tail, params, pos, msg_bf16=False)
-    c = lambda t: t.detach().cpu().numpy()
-    assert rel_err(c(ts.H_out), exact["Hs"][-1]) <= TOL_BF16
-    assert rel_err(c(ts.scores), exact["scores"]) <= TOL_BF16
-    assert abs(float(c(ts.loss)[0]) - exact["loss"]) <= TOL_BF16 * exact["loss"]
-    last = len(acts) - 1
-    for k in ("dV", "da", "dW0"):
-        assert rel_err(c(ts.grads[last][k]), exact["grads"][last][k]) <= TOL_BF16, k
-    if acts == [0, 0]:       # no mask anywhere: everything also matches the exact oracle
-        assert_step_close(ts, exact, TOL_BF16, TOL_BF16)
+    say("bf16 errs vs the exact oracle", errs)
 
 
 def test_zero_negatives_and_empty_batch(kb, orc):
@@ -257,9 +247,9 @@ def test_config1_mid_whole_graph_step(kb, orc, config1_oracle, order):
     gp, ts, _, _ = gpu_step(spec, head, rel, tail, params=params, pos=pos, order=order)
     assert (gp.n_vert, gp.n_core) == (14541, 272115)       # one partition = the whole graph
     assert_partition_equal(gp, op)
-    # 2.9 M pre-activations: one within fp32 rounding of zero (|pre| < 1e-5 of the largest) may take the
-    # other side in the kernel's fp32 sum; the ReLU decision is then taken in the kernel's precision
-    n_adopted, res = align_mask_decisions(orc, ts, op, res, params, spec.acts, True, 0, thresh=1e-5)
+    # 2.9 M pre-activations: one within fp32 rounding of zero may take the other side in the kernel's
+    # fp32 sum; the ReLU decision is then taken in the kernel's precision
+    n_adopted, res = align_mask_decisions(orc, ts, op, res, params, spec.acts, True, False)
     say("config 1 adopted ReLU decisions", n_adopted)
     assert n_adopted <= 8
     errs = assert_step_close(ts, res, TOL_VAL, TOL_GRAD)

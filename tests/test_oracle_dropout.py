@@ -29,19 +29,6 @@ def test_rate_zero_is_the_identity(orc):
     assert mask.all()
 
 
-def test_single_precision_product(orc):
-    """The variant the bf16 pipelines use: same mask, values equal to numpy's float32 product."""
-    H = np.random.default_rng(5).normal(size=(40, 12)).astype(np.float32)
-    p = float(np.float32(0.2))
-    out64, m64 = orc.dropout(H, p, 3, 1, 0)
-    out32, m32 = orc.dropout(H, p, 3, 1, 0, product_f32=True)
-    np.testing.assert_array_equal(m32, m64)
-    want = np.where(m64 > 0, H * np.float32(1.0 / (1.0 - p)), np.float32(0))
-    assert want.dtype == np.float32
-    np.testing.assert_array_equal(out32, want.astype(np.float64))
-    assert np.abs(out32 - out64).max() <= 2.0 ** -23 * np.abs(out64).max()
-
-
 @pytest.mark.parametrize("p", [0.2, 0.5])
 def test_keep_rate_and_independence(orc, p):
     H = np.ones((4000, 64))

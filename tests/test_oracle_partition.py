@@ -10,8 +10,28 @@ def tiny_graph(seed, n=40, R=3, m=120):
             rng.integers(0, n, m).astype(np.int32), n, R)
 
 
+def test_head_hash_values_worked_by_hand(orc):
+    """part = ((head * 0x9E3779B1 mod 2^32) >> 8) mod P, worked out digit by digit:
+      head 0: the product is 0                                           -> 0 for every P
+      head 1: 0x9E3779B1 >> 8 = 0x9E3779; its last hex digits 0x79 = 0b0111_1001   -> mod 4 = 1, mod 8 = 1
+      head 2: 2 * 0x9E3779B1 = 0x1_3C6EF362, low 32 bits 0x3C6EF362, >> 8 = 0x3C6EF3, 0xF3 = 0b1111_0011
+                                                                         -> mod 4 = 3, mod 16 = 3
+      head 3: 3 * 0x9E3779B1 = 0x1_DAA66D13, low 32 bits 0xDAA66D13, >> 8 = 0xDAA66D, 0x6D = 0b0110_1101
+                                                                         -> mod 4 = 1, mod 8 = 5
+              0xDAA66D = 14,329,453, digit sum 31                        -> mod 3 = 1
+      head 1, P = 3: 0x9E3779 = 10,368,889, digit sum 52                 -> mod 3 = 1
+    The multiplication wraps at 32 bits (head 2 and 3 overflow) and the low 8 bits are dropped."""
+    for P in (1, 2, 3, 4, 7, 16):
+        assert orc.part_of_head(0, P) == 0
+    assert orc.part_of_head(1, 4) == 1 and orc.part_of_head(1, 8) == 1 and orc.part_of_head(1, 3) == 1
+    assert orc.part_of_head(2, 4) == 3 and orc.part_of_head(2, 16) == 3
+    assert orc.part_of_head(3, 4) == 1 and orc.part_of_head(3, 8) == 5 and orc.part_of_head(3, 3) == 1
+    assert orc.part_of_head(1, 1 << 24) == 0x9E3779          # all 24 kept bits
+    assert orc.part_of_head(2, 1 << 24) == 0x3C6EF3
+
+
 def brute_partition(orc, head, rel, tail, n, R, P, pid, L, neg_domain):
-    """Python sets and sorted tuples; shares nothing with the C code but the hash."""
+    """Python sets and sorted tuples; the hash is the oracle's (pinned by hand-worked values above)."""
     M = len(head)
     core = [i for i in range(M) if orc.part_of_head(int(head[i]), P) == pid]
     S0 = set()

@@ -153,159 +153,3 @@ def test_layer_rows_matches_whole_layer(orc):
     rpre, rout = orc.layer_rows(part, rows, lay["V"], lay["a"], lay["W0"], 1, H)
     np.testing.assert_allclose(rpre, pre[rows], rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(rout, out[rows], rtol=1e-12, atol=1e-13)
-
-
-def test_bf16_message_storage_rounds_like_a_library_conversion(orc):
-    """msg_bf16 rounds each projected message once to bfloat16 (nearest, ties to even).  With one
-    basis, V = I, a = 1, W_0 = 0 and a single in-edge, the layer output IS the rounded message,
-    which must equal PyTorch's float32 -> bfloat16 conversion, ties included."""
-    import torch
-    d = 256
-    head = np.array([0], np.int32); rel = np.array([0], np.int32); tail = np.array([1], np.int32)
-    part = orc.build_partition(head, rel, tail, 2, 1, 1, 0, 1, 0)
-    rng = np.random.default_rng(0)
-    h = (rng.standard_normal(d) * 10.0 ** rng.integers(-6, 6, d)).astype(np.float32)
-    # exact ties: low 16 bits = 0x8000 with even and odd kept parts
-    ties = np.array([0x3F808000, 0x3F818000, 0xBF808000, 0x40FF8000, 0x3F807FFF, 0x3F808001], np.uint32)
-    h[:len(ties)] = ties.view(np.float32)
-    H = np.zeros((2, d)); H[0] = h
-    _, out = orc.layer_forward(part, np.eye(d)[None], np.ones((2, 1)), np.zeros((d, d)), 0, H, msg_bf16=True)
-    want = torch.from_numpy(h).to(torch.bfloat16).to(torch.float64).numpy()
-    np.testing.assert_array_equal(out[1], want)
-    _, exact = orc.layer_forward(part, np.eye(d)[None], np.ones((2, 1)), np.zeros((d, d)), 0, H)
-    np.testing.assert_array_equal(exact[1], h.astype(np.float64))
-
-
-# ------------------------------------------------------------------ aggregate-first bf16 rounding (msg_bf16 = 2)
-def _bf(x):
-    import torch
-    return torch.from_numpy(np.asarray(x, np.float64)).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
-
-
-def _small_case(orc, seed, n=60, R=3, m=400, d_in=12, d_out=8, B=3):
-    rng = np.random.default_rng(seed)
-    head = rng.integers(0, n, m).astype(np.int32); rel = rng.integers(0, R, m).astype(np.int32)
-    tail = rng.integers(0, n, m).astype(np.int32)
-    part = orc.build_partition(head, rel, tail, n, R, 1, 0, 2, 0)
-    V = rng.normal(0, 0.4, (B, d_in, d_out)); a = rng.normal(0, 1, (2 * R, B)); W0 = rng.normal(0, 0.4, (d_in, d_out))
-    H = rng.normal(0, 1, (part["n_vert"], d_in)).astype(np.float32).astype(np.float64)
-    return part, V, a, W0, H
-
-
-def test_aggregate_first_bf16_mode_matches_a_numpy_emulation(orc):
-    """Eq. 1-2 regrouped (run means z, per-basis sums y, one contraction with the stacked weights),
-    every operand rounded with PyTorch's bfloat16 conversion, sums in float64."""
-    part, V, a, W0, H = _small_case(orc, 4)
-    S, N = part["n_seg"], part["n_vert"]
-    lens = np.diff(part["seg_ptr"])
-    run = np.repeat(np.arange(S), lens)
-    Hq = _bf(H)
-    Z = np.zeros((S, H.shape[1])); np.add.at(Z, run, Hq[part["col_src"]])
-    Zq = _bf(Z / lens[:, None])
-    Y = np.zeros((N, V.shape[0], H.shape[1]))
-    np.add.at(Y, part["seg_dst"], a[part["seg_rel"]][:, :, None] * Zq[:, None, :])
-    want = np.einsum("nbk,bkc->nc", _bf(Y), _bf(V)) + Hq @ _bf(W0)
-    pre, out = orc.layer_forward(part, V, a, W0, 1, H, msg_bf16=2)
-    np.testing.assert_allclose(pre, want, rtol=1e-11, atol=1e-12)
-    np.testing.assert_array_equal(out, np.maximum(pre, 0))
-    exact, _ = orc.layer_forward(part, V, a, W0, 1, H)
-    err = np.abs(pre - exact).max() / np.abs(exact).max()
-    assert 0 < err < 2e-2                                       # rounded, and only by bf16 amounts
-    rows = np.array([0, 7, N - 1], np.int32)
-    rpre, rout = orc.layer_rows(part, rows, V, a, W0, 1, H.astype(np.float32), msg_bf16=2)
-    np.testing.assert_allclose(rpre, pre[rows], rtol=1e-11, atol=1e-12)
-
-
-def test_aggregate_first_bf16_mode_is_exact_on_bf16_representable_inputs(orc):
-    """Small integers, power-of-two run lengths: no rounding point changes anything, so the regrouped
-    evaluation must reproduce the exact layer (a regrouping mistake would not)."""
-    n, R, d_in, d_out, B = 20, 2, 4, 4, 2
-    rng = np.random.default_rng(1)
-    # every (relation, destination) run gets 1, 2 or 4 edges
-    head, rel, tail = [], [], []
-    for t in range(n):
-        for r in range(R):
-            for j in rng.choice(n, size=int(rng.choice([1, 2, 4])), replace=False):
-                head.append(j); rel.append(r); tail.append(t)
-    head, rel, tail = (np.asarray(x, np.int32) for x in (head, rel, tail))
-    part = orc.build_partition(head, rel, tail, n, R, 1, 0, 1, 0)
-    lens = np.diff(part["seg_ptr"])
-    fwd = part["seg_rel"] < R                       # inverse runs have arbitrary lengths: give them weight 0
-    a = np.zeros((2 * R, B)); a[:R] = rng.integers(-2, 3, (R, B))
-    assert set(lens[fwd]) <= {1, 2, 4}
-    V = rng.integers(-2, 3, (B, d_in, d_out)).astype(np.float64)
-    W0 = rng.integers(-2, 3, (d_in, d_out)).astype(np.float64)
-    H = rng.integers(-4, 5, (part["n_vert"], d_in)).astype(np.float64)
-    exact, _ = orc.layer_forward(part, V, a, W0, 0, H)
-    got, _ = orc.layer_forward(part, V, a, W0, 0, H, msg_bf16=2)
-    np.testing.assert_array_equal(got, exact)
-
-
-def test_aggregate_first_bf16_backward(orc):
-    """Mode 2 changes only da (through the rounded run means); every other gradient is the exact one."""
-    part, V, a, W0, H = _small_case(orc, 9)
-    pre, out = orc.layer_forward(part, V, a, W0, 1, H, msg_bf16=2)
-    rng = np.random.default_rng(2)
-    dH = rng.normal(0, 1, out.shape)
-    g2 = orc.layer_backward(part, V, a, W0, 1, H, pre, dH, True, msg_bf16=2)
-    g0 = orc.layer_backward(part, V, a, W0, 1, H, pre, dH, True, msg_bf16=0)
-    for k in ("dV", "dW0", "dH", "dP", "Gpre"):
-        np.testing.assert_array_equal(g2[k], g0[k])
-    S = part["n_seg"]; lens = np.diff(part["seg_ptr"]); run = np.repeat(np.arange(S), lens)
-    Z = np.zeros((S, H.shape[1])); np.add.at(Z, run, _bf(H)[part["col_src"]])
-    Zq = _bf(Z / lens[:, None])
-    G = g0["Gpre"][part["seg_dst"]]                                  # [S][d_out]
-    per_run = np.einsum("sk,bkc,sc->sb", Zq, V, G)
-    want = np.zeros_like(a); np.add.at(want, part["seg_rel"], per_run)
-    np.testing.assert_allclose(g2["da"], want, rtol=1e-10, atol=1e-12)
-    assert 0 < np.abs(g2["da"] - g0["da"]).max() / np.abs(g0["da"]).max() < 2e-2
-
-
-# ------------------------------------------------------------------ relation-weight bf16 rounding (msg_bf16 = 3)
-def test_relation_weight_bf16_mode_matches_a_numpy_emulation(orc):
-    """Eq. 2 written out (W_r = sum_b a_rb V_b, rounded), run means z (rounded), one product z W_r per
-    run (rounded when stored), summed per destination with the self-loop term."""
-    part, V, a, W0, H = _small_case(orc, 14)
-    S, N = part["n_seg"], part["n_vert"]
-    lens = np.diff(part["seg_ptr"])
-    run = np.repeat(np.arange(S), lens)
-    Hq = _bf(H)
-    Z = np.zeros((S, H.shape[1])); np.add.at(Z, run, Hq[part["col_src"]])
-    Zq = _bf(Z / lens[:, None])
-    Wr = _bf(np.einsum("rb,bkc->rkc", a, V))
-    U = _bf(np.einsum("sk,skc->sc", Zq, Wr[part["seg_rel"]]))
-    want = Hq @ _bf(W0)
-    np.add.at(want, part["seg_dst"], U)
-    pre, out = orc.layer_forward(part, V, a, W0, 1, H, msg_bf16=3)
-    np.testing.assert_allclose(pre, want, rtol=1e-11, atol=1e-12)
-    np.testing.assert_array_equal(out, np.maximum(pre, 0))
-    exact, _ = orc.layer_forward(part, V, a, W0, 1, H)
-    assert 0 < np.abs(pre - exact).max() / np.abs(exact).max() < 2e-2
-    rows = np.array([0, 7, N - 1], np.int32)
-    rpre, _ = orc.layer_rows(part, rows, V, a, W0, 1, H.astype(np.float32), msg_bf16=3)
-    np.testing.assert_allclose(rpre, pre[rows], rtol=1e-11, atol=1e-12)
-    # backward: only da differs from the exact one, and it is the mode-2 value (same rounded run means)
-    dH = np.random.default_rng(3).normal(0, 1, out.shape)
-    g3 = orc.layer_backward(part, V, a, W0, 1, H, pre, dH, True, msg_bf16=3)
-    g2 = orc.layer_backward(part, V, a, W0, 1, H, pre, dH, True, msg_bf16=2)
-    for k in ("dV", "dW0", "dH", "dP", "Gpre", "da"):
-        np.testing.assert_array_equal(g3[k], g2[k])
-
-
-def test_relation_weight_bf16_mode_is_exact_on_bf16_representable_inputs(orc):
-    n, R, d_in, d_out, B = 20, 2, 4, 4, 2
-    rng = np.random.default_rng(1)
-    head, rel, tail = [], [], []
-    for t in range(n):
-        for r in range(R):
-            for j in rng.choice(n, size=int(rng.choice([1, 2, 4])), replace=False):
-                head.append(j); rel.append(r); tail.append(t)
-    head, rel, tail = (np.asarray(x, np.int32) for x in (head, rel, tail))
-    part = orc.build_partition(head, rel, tail, n, R, 1, 0, 1, 0)
-    a = np.zeros((2 * R, B)); a[:R] = rng.integers(-2, 3, (R, B))      # inverse runs (any length) get weight 0
-    V = rng.integers(-2, 3, (B, d_in, d_out)).astype(np.float64)
-    W0 = rng.integers(-2, 3, (d_in, d_out)).astype(np.float64)
-    H = rng.integers(-4, 5, (part["n_vert"], d_in)).astype(np.float64)
-    exact, _ = orc.layer_forward(part, V, a, W0, 0, H)
-    got, _ = orc.layer_forward(part, V, a, W0, 0, H, msg_bf16=3)
-    np.testing.assert_array_equal(got, exact)

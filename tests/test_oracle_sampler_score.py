@@ -71,7 +71,6 @@ def test_negative_draws_are_uniform_and_the_coin_is_fair(orc):
     head, rel, tail, n, R = tiny_graph(3, n=64, R=2, m=400)
     part = orc.build_partition(head, rel, tail, n, R, 1, 0, 2, 1)
     n_cand = part["n_cand"]
-    pos = (np.arange(20000) % part["n_core"]).astype(np.int32)
     pos = np.arange(20000, dtype=np.int32)           # counter word only; indices need not exist
     ne, ns = orc.sample_negatives(part, pos, 50, 1, 99, 0)
     counts = np.bincount(ne.ravel(), minlength=part["n_vert"])[part["cand"]]
