@@ -201,6 +201,15 @@ void kge_cgraph_destroy(kge_cgraph *cg);
 int kge_compute_graph(const kge_partition *p, kge_cgraph *cg, const int32_t *pos_core_idx,
                       int64_t n_pos, const int32_t *neg_ent, int64_t n_neg_entries, void *stream);
 int kge_cgraph_export(const kge_cgraph *cg, uint8_t *host_active, int64_t *host_stats);
+/* The rows of the first layer's INPUT that the batch filled in by kge_compute_graph reads: active_0 united with
+ * the sources of all message edges into active_0 (one hop beyond the first layer's outputs).  With learned
+ * entity embeddings as that input these are exactly the rows the step produces a gradient for (Algorithm 1's
+ * update touches no other row): pass *device_flags (device uint8 [N], owned by cg, valid until the next
+ * kge_compute_graph on it or its destruction) as row_mask to kge_optimizer_step_rows.  host_flags (HOST uint8
+ * [N]) and host_count (HOST, number of flagged rows) synchronise the device when given; any of the three may
+ * be NULL. */
+int kge_cgraph_input_rows(const kge_cgraph *cg, const uint8_t **device_flags, uint8_t *host_flags,
+                          int64_t *host_count);
 
 /*
  * Encoder forward (Eq. 1-2), for l = 1..n_layers:

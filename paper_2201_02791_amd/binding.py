@@ -23,7 +23,7 @@ EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_cgraph_destroy", "kge_compute_graph", "kge_cgraph_export", "kge_optimizer_step",
             "kge_optimizer_step_rows", "kge_eval_filter_create", "kge_eval_filter_destroy",
             "kge_eval_workspace_bytes", "kge_eval_rank_all", "kge_eval_rank_candidates", "kge_eval_metrics",
-            "kge_eval_debug_scores", "kge_eval_rank_all_static"]
+            "kge_eval_debug_scores", "kge_eval_rank_all_static", "kge_cgraph_input_rows"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
 ORDER_PROJECT_FIRST, ORDER_AGGREGATE_FIRST, ORDER_RELATION_WEIGHTS = 0, 1, 2
@@ -222,6 +222,19 @@ class ComputeGraph:
                                         stats.ctypes.data_as(C.c_void_p)))
         return active, stats
 
+    def input_rows_ptr(self) -> int:
+        """Device address of the flags (uint8 [N]) of the first layer's input rows the batch reads."""
+        ptr = C.c_void_p()
+        _check(load().kge_cgraph_input_rows(self._h, C.byref(ptr), None, None))
+        return ptr.value
+
+    def input_rows(self):
+        """(flags uint8 [N] on the host, their count): the first layer's input rows the batch reads."""
+        flags = np.zeros(self.n_vert, np.uint8)
+        count = C.c_int64()
+        _check(load().kge_cgraph_input_rows(self._h, None, flags.ctypes.data_as(C.c_void_p), C.byref(count)))
+        return flags, int(count.value)
+
     def destroy(self):
         if self._h is not None and self._h.value:
             load().kge_cgraph_destroy(self._h)
@@ -306,9 +319,10 @@ def optimizer_step(kind: int, param, grad, m=None, v=None, lr=0.01, beta1=0.9, b
     """One optimizer step in place on device tensors.  rows=True: the row form on a 2-D tensor."""
     o = _Opt(kind, lr, beta1, beta2, eps, t)
     if rows:
+        mask = C.c_void_p(row_mask) if isinstance(row_mask, int) else _ptr(row_mask)     # raw device address or tensor
         _check(load().kge_optimizer_step_rows(C.byref(o), _ptr(param), _ptr(grad), _ptr(m), _ptr(v),
                                               C.c_int64(param.shape[0]), C.c_int32(param.shape[1]),
-                                              _ptr(row_mask), _stream(stream)))
+                                              mask, _stream(stream)))
     else:
         _check(load().kge_optimizer_step(C.byref(o), _ptr(param), _ptr(grad), _ptr(m), _ptr(v),
                                          C.c_int64(param.numel()), _stream(stream)))

@@ -460,7 +460,7 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
                                                          (float *)dZ, st);
                 }
                 if (rc != KGE_OK) return rc;
-                rc = launch_sum_edges_out(p, dZ, bf, L.d_in, Self, dst, part, l > 0 ? kge_cgraph_layer(cg, l - 1) : nullptr, st);
+                rc = launch_sum_edges_out(p, dZ, bf, L.d_in, Self, dst, part, kge_cgraph_layer(cg, l - 1), st);
                 if (rc != KGE_OK) return rc;
                 if (L.dropout > 0.0f) {
                     rc = launch_dropout(dst, p->n_vert, L.d_in, L.dropout, L.drop_seed, L.drop_step, l, dst, st);

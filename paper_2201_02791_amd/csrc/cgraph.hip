@@ -14,8 +14,8 @@ struct kge_cgraph {
     int device;
     int64_t N, stride;      // vertices; bytes between the layers' flag rows
     int32_t n_layers;
-    uint8_t *active;        // [n_layers][stride]
-    unsigned long long *stats;   // [n_layers][4]: active vertices, edges into them, runs into them, edges out of them
+    uint8_t *active;        // [n_layers + 1][stride]; row n_layers: the rows of the first layer's INPUT the step reads
+    unsigned long long *stats;   // [n_layers + 1][4]: active vertices, edges into them, runs into them, edges out of them
 };
 
 namespace {
@@ -99,10 +99,10 @@ extern "C" int kge_cgraph_create(const kge_partition *p, int32_t n_layers, kge_c
     cg->n_layers = n_layers;
     cg->active = nullptr;
     cg->stats = nullptr;
-    hipError_t e = hipMalloc((void **)&cg->active, (size_t)cg->stride * n_layers);
-    if (e == hipSuccess) e = hipMalloc((void **)&cg->stats, sizeof(unsigned long long) * 4 * n_layers);
-    if (e == hipSuccess) e = hipMemset(cg->active, 0, (size_t)cg->stride * n_layers);
-    if (e == hipSuccess) e = hipMemset(cg->stats, 0, sizeof(unsigned long long) * 4 * n_layers);
+    hipError_t e = hipMalloc((void **)&cg->active, (size_t)cg->stride * (n_layers + 1));
+    if (e == hipSuccess) e = hipMalloc((void **)&cg->stats, sizeof(unsigned long long) * 4 * (n_layers + 1));
+    if (e == hipSuccess) e = hipMemset(cg->active, 0, (size_t)cg->stride * (n_layers + 1));
+    if (e == hipSuccess) e = hipMemset(cg->stats, 0, sizeof(unsigned long long) * 4 * (n_layers + 1));
     if (e != hipSuccess) {
         kge_set_error("allocating the sub-graph flags failed: %s", hipGetErrorString(e));
         if (cg->active) (void)hipFree(cg->active);
@@ -135,9 +135,9 @@ extern "C" int kge_compute_graph(const kge_partition *p, kge_cgraph *cg, const i
     hipStream_t st = (hipStream_t)stream;
     const int L = cg->n_layers;
     KGE_PROF("compute_graph", st);
-    int rc = launch_fill_zero(cg->active, (size_t)cg->stride * L, st);
+    int rc = launch_fill_zero(cg->active, (size_t)cg->stride * (L + 1), st);
     if (rc != KGE_OK) return rc;
-    rc = launch_fill_zero(cg->stats, sizeof(unsigned long long) * 4 * L, st);
+    rc = launch_fill_zero(cg->stats, sizeof(unsigned long long) * 4 * (L + 1), st);
     if (rc != KGE_OK) return rc;
     if (p->n_vert == 0) return KGE_OK;
     const int64_t n_mark = n_pos + n_neg_entries;
@@ -153,10 +153,33 @@ extern "C" int kge_compute_graph(const kge_partition *p, kge_cgraph *cg, const i
                                                                  cg->active + (size_t)(l - 1) * cg->stride);
         KGE_LAUNCH_CHECK();
     }
-    for (int l = 0; l < L; ++l) {
+    // one hop further: the rows of the first layer's input that layer reads (its active destinations and the
+    // sources of every edge into them) - the embedding rows this step has a gradient for
+    k_cg_expand<<<(unsigned)cdiv(p->n_vert, 4), 256, 0, st>>>(p->dm_ptr, p->dm_src, p->n_vert, cg->active,
+                                                             cg->active + (size_t)L * cg->stride);
+    KGE_LAUNCH_CHECK();
+    for (int l = 0; l <= L; ++l) {
         k_cg_stats<<<1024, 256, 0, st>>>(p->dm_ptr, p->sm_ptr, p->n_vert, p->seg_dst, p->n_seg,
                                          cg->active + (size_t)l * cg->stride, cg->stats + 4 * l);
         KGE_LAUNCH_CHECK();
+    }
+    return KGE_OK;
+}
+
+extern "C" int kge_cgraph_input_rows(const kge_cgraph *cg, const uint8_t **device_flags, uint8_t *host_flags,
+                                     int64_t *host_count)
+{
+    KGE_REQUIRE(cg, KGE_EINVAL, "NULL sub-graph object");
+    const uint8_t *row = cg->active + (size_t)cg->n_layers * cg->stride;
+    if (device_flags) *device_flags = row;
+    if (host_flags || host_count) {
+        KGE_HIP(hipDeviceSynchronize());
+        if (host_flags) KGE_HIP(hipMemcpy(host_flags, row, (size_t)cg->N, hipMemcpyDeviceToHost));
+        if (host_count) {
+            unsigned long long n = 0;
+            KGE_HIP(hipMemcpy(&n, cg->stats + 4 * cg->n_layers, sizeof n, hipMemcpyDeviceToHost));
+            *host_count = (int64_t)n;
+        }
     }
     return KGE_OK;
 }
@@ -179,7 +202,9 @@ extern "C" int kge_cgraph_export(const kge_cgraph *cg, uint8_t *host_active, int
 
 const uint8_t *kge_cgraph_layer(const kge_cgraph *cg, int32_t layer)
 {
-    return cg ? cg->active + (size_t)layer * cg->stride : nullptr;
+    if (!cg) return nullptr;
+    // layer -1: the rows of the first layer's input the batch reads (kept behind the layers' rows)
+    return cg->active + (size_t)(layer < 0 ? cg->n_layers : layer) * cg->stride;
 }
 
 int kge_cgraph_check(const kge_partition *p, const kge_cgraph *cg, int32_t n_layers)

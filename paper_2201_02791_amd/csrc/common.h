@@ -142,7 +142,7 @@ int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const
                       const uint8_t *active, hipStream_t st);
 
 // cgraph.hip: per-batch computational sub-graph ------------------------------
-// flag row of layer `layer` (device pointer), or null when cg is null
+// flag row of layer `layer` (device pointer; -1: the first layer's input rows the batch reads), or null when cg is null
 const uint8_t *kge_cgraph_layer(const kge_cgraph *cg, int32_t layer);
 int kge_cgraph_check(const kge_partition *p, const kge_cgraph *cg, int32_t n_layers);
 

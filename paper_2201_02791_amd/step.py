@@ -60,6 +60,17 @@ class TrainStep:
         self.scores = (torch.empty((n_pos, 1 + n_neg), dtype=torch.float32, device=self.dev)
                        if self.keep_scores else None)
 
+    def stage_batches(self, batches):
+        """Copy several mini-batches (equal-length index arrays) to the device ahead of a loop; returns the
+        tensor [n_batches, n_pos] whose rows `use_batch` takes."""
+        torch = self.torch
+        return torch.from_numpy(np.ascontiguousarray(np.stack(batches), np.int32)).to(self.dev)
+
+    def use_batch(self, pos_dev):
+        """Switch to another mini-batch of the size set_batch was given (a device tensor; nothing is allocated)."""
+        assert pos_dev.numel() == self.pos.numel() and pos_dev.dtype == self.pos.dtype
+        self.pos = pos_dev
+
     def view(self, which: int, layer: int):
         """Torch view [N, width] of one intermediate inside the workspace (see kge_workspace_slice)."""
         torch = self.torch
@@ -111,9 +122,13 @@ class TrainStep:
         if not hasattr(self, "opt_t"):
             self.init_optimizer(kind)
         self.opt_t += 1
+        # the entity table: only the rows the step read (flags of the sub-graph's input rows; without a
+        # sub-graph the kernel skips rows whose gradient is all zero)
+        mask = self.cg.input_rows_ptr() if self.cg is not None else None
         for name, p, g, rows in self._opt_pairs():
             m, v = self.opt_state.get(name, (None, None)) if kind == kb.OPT_ADAM else (None, None)
-            kb.optimizer_step(kind, p, g, m, v, lr, beta1, beta2, eps, self.opt_t, rows=rows, stream=stream)
+            kb.optimizer_step(kind, p, g, m, v, lr, beta1, beta2, eps, self.opt_t, rows=rows,
+                              row_mask=mask if rows else None, stream=stream)
 
     def _opt_pairs(self):
         pairs = [("M", self.M, self.dM, False)]

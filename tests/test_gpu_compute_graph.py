@@ -37,6 +37,11 @@ def check_flags(orc, ts, opart, pos, res, n_layers):
         assert stats[l, 1] == int(want[l][dst_of_edge].sum())
         assert stats[l, 2] == int(want[l][opart["seg_dst"]].sum())
         assert stats[l, 3] == int(want[l][opart["col_src"]].sum())
+    # the rows of the first layer's input the batch reads: one hop beyond its active destinations
+    flags, count = ts.cg.input_rows()
+    want_in = orc.compute_graph(opart, pos, res["neg_ent"], n_layers + 1)[0]
+    np.testing.assert_array_equal(flags, want_in)
+    assert count == int(want_in.sum())
     return want, stats
 
 
