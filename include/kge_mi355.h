@@ -74,6 +74,7 @@ enum { KGE_ORDER_PROJECT_FIRST = 0, KGE_ORDER_AGGREGATE_FIRST = 1, KGE_ORDER_REL
 
 typedef struct kge_partition kge_partition;      /* opaque; device resident; library owned    */
 typedef struct kge_cgraph kge_cgraph;            /* opaque; one batch's computational sub-graph */
+typedef struct kge_score_index kge_score_index;  /* opaque; scratch of the atomic-free scoring call    */
 
 typedef struct kge_part_info {
     int64_t n_vert;        /* N: vertices after expansion (numerator term of Eq. 7)            */
@@ -274,12 +275,31 @@ int kge_sample_negatives(const kge_partition *p, const int32_t *pos_core_idx, in
  *   neg_ent / neg_side : as written by kge_sample_negatives, entries in [0, N)
  *   scores : device float [n_pos][1+n_neg] or NULL
  *   loss   : device float [1]
- *   dH     : device float [N][d], zeroed by this call, then accumulated
- *   dM     : device float [R][d], zeroed by this call, then accumulated
- * Accumulation uses fp32 atomics, so low-order bits can differ from run to run.
+ *   dH     : device float [N][d], overwritten (every row; rows no triple names become zero)
+ *   dM     : device float [R][d], overwritten
+ *   index  : NULL, or scratch from kge_score_index_create.
+ *     NULL : rows are added into dH with fp32 atomics as the triples are scored; low-order bits of dH can
+ *            differ from run to run.
+ *     else : the atomic-free form.  The rows every scored triple adds into dH (one per negative, to the
+ *            corrupting entity; two per positive, to its head and tail) are sorted by entity with a stable
+ *            radix sort inside the call, the triples are scored, and one wavefront per entity adds up its rows
+ *            in the order of the batch: every row of dH is written once and the result repeats bit for bit.
+ *            H, M and dH must then be 16-byte aligned.  An id outside [0, n_core) / [0, N) never becomes an
+ *            address in this form: it is replaced by 0 and counted (kge_score_index_bad_ids; outputs of such
+ *            a call are meaningless).
+ *   dM and the loss are accumulated with fp32 atomics in both forms.
+ *
+ * kge_score_index_create allocates the scratch for batches of at most max_pos positives with at most max_neg
+ * negatives each and embedding width d (about (n_neg + 2) x 36 bytes + 8 d bytes per positive, plus 4 N bytes);
+ * once per trainer, synchronous; free with kge_score_index_destroy.  kge_score_index_bad_ids (synchronises)
+ * writes to *host_count how many out-of-range ids the calls with this index have seen so far.
  */
-int kge_distmult_score_loss(const kge_partition *p, const float *H, const float *M, int32_t d,
-                            const int32_t *pos_core_idx, int64_t n_pos, const int32_t *neg_ent,
+int kge_score_index_create(const kge_partition *p, int64_t max_pos, int32_t max_neg, int32_t d,
+                           kge_score_index **out);
+void kge_score_index_destroy(kge_score_index *index);
+int kge_score_index_bad_ids(const kge_score_index *index, int64_t *host_count);
+int kge_distmult_score_loss(const kge_partition *p, kge_score_index *index, const float *H, const float *M,
+                            int32_t d, const int32_t *pos_core_idx, int64_t n_pos, const int32_t *neg_ent,
                             const uint8_t *neg_side, int32_t n_neg, float *scores, float *loss,
                             float *dH, float *dM, void *stream);
 

@@ -23,7 +23,8 @@ EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_cgraph_destroy", "kge_compute_graph", "kge_cgraph_export", "kge_optimizer_step",
             "kge_optimizer_step_rows", "kge_eval_filter_create", "kge_eval_filter_destroy",
             "kge_eval_workspace_bytes", "kge_eval_rank_all", "kge_eval_rank_candidates", "kge_eval_metrics",
-            "kge_eval_debug_scores", "kge_eval_rank_all_static", "kge_cgraph_input_rows"]
+            "kge_eval_debug_scores", "kge_eval_rank_all_static", "kge_cgraph_input_rows", "kge_score_index_create", "kge_score_index_destroy",
+            "kge_score_index_bad_ids"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
 ORDER_PROJECT_FIRST, ORDER_AGGREGATE_FIRST, ORDER_RELATION_WEIGHTS = 0, 1, 2
@@ -92,6 +93,7 @@ def load():
         lib.kge_workspace_bytes.restype = C.c_size_t
         lib.kge_partition_destroy.restype = None
         lib.kge_cgraph_destroy.restype = None
+        lib.kge_score_index_destroy.restype = None
         lib.kge_eval_filter_destroy.restype = None
         lib.kge_eval_workspace_bytes.restype = C.c_size_t
         _lib = lib
@@ -282,9 +284,40 @@ def sample_negatives(part: Partition, pos_core_idx, n_neg: int, mode: int, seed:
                                        _ptr(neg_ent), _ptr(neg_side), _stream(stream)))
 
 
+class ScoreIndex:
+    """Owner of a ``kge_score_index*``: scratch of the atomic-free scoring call for batches up to a given size."""
+
+    def __init__(self, part: Partition, max_pos: int, max_neg: int, d: int):
+        out = C.c_void_p()
+        _check(load().kge_score_index_create(part.handle, C.c_int64(max_pos), C.c_int32(max_neg), C.c_int32(d),
+                                             C.byref(out)))
+        self._h = C.c_void_p(out.value)
+
+    @property
+    def handle(self):
+        return self._h
+
+    def bad_ids(self) -> int:
+        n = C.c_int64()
+        _check(load().kge_score_index_bad_ids(self._h, C.byref(n)))
+        return int(n.value)
+
+    def destroy(self):
+        if self._h is not None and self._h.value:
+            load().kge_score_index_destroy(self._h)
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
 def distmult_score_loss(part: Partition, H, M, pos_core_idx, neg_ent, neg_side, n_neg: int, scores, loss,
-                        dH, dM, stream=None):
-    _check(load().kge_distmult_score_loss(part.handle, _ptr(H), _ptr(M), C.c_int32(H.shape[1]),
+                        dH, dM, stream=None, index: "ScoreIndex" = None):
+    _check(load().kge_distmult_score_loss(part.handle, index.handle if index is not None else C.c_void_p(0),
+                                          _ptr(H), _ptr(M), C.c_int32(H.shape[1]),
                                           _ptr(pos_core_idx), C.c_int64(pos_core_idx.numel()),
                                           _ptr(neg_ent), _ptr(neg_side), C.c_int32(n_neg), _ptr(scores),
                                           _ptr(loss), _ptr(dH), _ptr(dM), _stream(stream)))

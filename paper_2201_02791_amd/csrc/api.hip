@@ -525,8 +525,8 @@ extern "C" int kge_sample_negatives(const kge_partition *p, const int32_t *pos_c
                                    (hipStream_t)stream);
 }
 
-extern "C" int kge_distmult_score_loss(const kge_partition *p, const float *H, const float *M, int32_t d,
-                                       const int32_t *pos_core_idx, int64_t n_pos, const int32_t *neg_ent,
+extern "C" int kge_distmult_score_loss(const kge_partition *p, kge_score_index *index, const float *H, const float *M,
+                                       int32_t d, const int32_t *pos_core_idx, int64_t n_pos, const int32_t *neg_ent,
                                        const uint8_t *neg_side, int32_t n_neg, float *scores, float *loss,
                                        float *dH, float *dM, void *stream)
 {
@@ -538,6 +538,9 @@ extern "C" int kge_distmult_score_loss(const kge_partition *p, const float *H, c
     KGE_REQUIRE(n_pos == 0 || p->n_core > 0, KGE_EINVAL, "the partition has no core edge to score");
     KGE_REQUIRE(((uintptr_t)dH % 4) == 0 && ((uintptr_t)dM % 4) == 0 && ((uintptr_t)loss % 4) == 0, KGE_EINVAL,
                 "misaligned output");
+    if (index)
+        return launch_distmult_indexed(p, index, H, M, d, pos_core_idx, n_pos, neg_ent, neg_side, n_neg, scores, loss,
+                                       dH, dM, (hipStream_t)stream);
     return launch_distmult(p, H, M, d, pos_core_idx, n_pos, neg_ent, neg_side, n_neg, scores, loss, dH, dM,
                            (hipStream_t)stream);
 }

@@ -222,6 +222,9 @@ int launch_distmult(const kge_partition *p, const float *H, const float *M, int3
                     const int32_t *pos, int64_t n_pos, const int32_t *neg_ent,
                     const uint8_t *neg_side, int32_t n_neg, float *scores, float *loss, float *dH,
                     float *dM, hipStream_t st);
+int launch_distmult_indexed(const kge_partition *p, kge_score_index *x, const float *H, const float *M, int32_t d,
+                            const int32_t *pos, int64_t n_pos, const int32_t *neg_ent, const uint8_t *neg_side,
+                            int32_t n_neg, float *scores, float *loss, float *dH, float *dM, hipStream_t st);
 int launch_fill_zero(void *ptr, size_t bytes, hipStream_t st);
 
 // dst = dropout(src) on [n_rows][d] floats (d a multiple of 4), inverted scaling, Philox mask keyed by

@@ -10,14 +10,9 @@
 #include <vector>
 
 #include "common.h"
+#include "sort_scan.h"
 
 namespace {
-
-constexpr int TB = 256;              // threads per block (4 wavefronts of 64)
-constexpr int SCAN_ITEMS = 8;        // items per thread in the scan kernels
-constexpr int SCAN_TILE = TB * SCAN_ITEMS;
-constexpr int SORT_ROWS = 8;         // 64-element rows per wavefront in a sort tile
-constexpr int SORT_TILE = TB * SORT_ROWS;
 
 __device__ __forceinline__ uint32_t part_of_head(int32_t head, uint32_t n_parts)
 {
@@ -56,122 +51,29 @@ __global__ void k_expand(const int32_t *head, const int32_t *tail, int64_t M, co
     if (prev[s]) cur[t] = 1u;
 }
 
-// ---------------------------------------------------------------- scan
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
-{
-    int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        uint32_t o = __shfl_up(v, off, 64);
-        if (lane >= off) v += o;
-    }
-    return v;
-}
-
-// Inclusive scan of one value per thread across the block; returns the exclusive prefix of
-// this thread and the block total.
-__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *total)
-{
-    __shared__ uint32_t wsum[TB / 64];
-    int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    uint32_t inc = wave_incl_scan(v);
-    if (lane == 63) wsum[w] = inc;
-    __syncthreads();
-    uint32_t base = 0, tot = 0;
-#pragma unroll
-    for (int k = 0; k < TB / 64; ++k) {
-        uint32_t s = wsum[k];
-        if (k < w) base += s;
-        tot += s;
-    }
-    __syncthreads();
-    *total = tot;
-    return base + inc - v;
-}
-
-__global__ void k_scan_reduce(const uint32_t *in, int64_t n, uint32_t *block_sums)
-{
-    int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
-    uint32_t s = 0;
-#pragma unroll
-    for (int k = 0; k < SCAN_ITEMS; ++k)
-        if (base + k < n) s += in[base + k];
-    uint32_t tot;
-    block_excl_scan(s, &tot);
-    if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
-}
-
-__global__ void k_scan_apply(const uint32_t *in, int64_t n, const uint32_t *block_offs, uint32_t *out)
-{
-    int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
-    uint32_t v[SCAN_ITEMS], s = 0;
-#pragma unroll
-    for (int k = 0; k < SCAN_ITEMS; ++k) {
-        v[k] = (base + k < n) ? in[base + k] : 0u;
-        s += v[k];
-    }
-    uint32_t tot;
-    uint32_t run = block_excl_scan(s, &tot) + block_offs[blockIdx.x];
-#pragma unroll
-    for (int k = 0; k < SCAN_ITEMS; ++k) {
-        if (base + k < n) out[base + k] = run;
-        run += v[k];
-    }
-}
-
-// Single block: exclusive scan of up to any n (loops), writes total to out[n].
-__global__ void k_scan_small(const uint32_t *in, int64_t n, uint32_t *out)
-{
-    __shared__ uint32_t carry;
-    if (threadIdx.x == 0) carry = 0;
-    __syncthreads();
-    for (int64_t start = 0; start < n; start += SCAN_TILE) {
-        int64_t base = start + (int64_t)threadIdx.x * SCAN_ITEMS;
-        uint32_t v[SCAN_ITEMS], s = 0;
-#pragma unroll
-        for (int k = 0; k < SCAN_ITEMS; ++k) {
-            v[k] = (base + k < n) ? in[base + k] : 0u;
-            s += v[k];
-        }
-        uint32_t tot;
-        uint32_t run = block_excl_scan(s, &tot) + carry;
-#pragma unroll
-        for (int k = 0; k < SCAN_ITEMS; ++k) {
-            if (base + k < n) out[base + k] = run;
-            run += v[k];
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) carry += tot;
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) out[n] = carry;
-}
-
-// out[0..n) = exclusive prefix sums of in[0..n), out[n] = total.  out has n+1 entries and may
-// not alias in.  Temporary block sums are allocated here (build time only).
+// Build-time wrappers: the scratch of the scan and of the sort is allocated here (nothing in this file is
+// in the timed training step).
 int exclusive_scan(const uint32_t *in, uint32_t *out, int64_t n, hipStream_t st)
 {
-    if (n <= 4 * SCAN_TILE) {
-        k_scan_small<<<1, TB, 0, st>>>(in, n, out);
-        KGE_LAUNCH_CHECK();
-        return KGE_OK;
-    }
-    int64_t nb = cdiv(n, SCAN_TILE);
-    uint32_t *sums = nullptr, *offs = nullptr;
-    KGE_HIP(hipMalloc(&sums, sizeof(uint32_t) * (nb + 1)));
-    KGE_HIP(hipMalloc(&offs, sizeof(uint32_t) * (nb + 1)));
-    k_scan_reduce<<<(unsigned)nb, TB, 0, st>>>(in, n, sums);
-    KGE_LAUNCH_CHECK();
-    int rc = exclusive_scan(sums, offs, nb, st);
-    if (rc == KGE_OK) {
-        k_scan_apply<<<(unsigned)nb, TB, 0, st>>>(in, n, offs, out);
-        KGE_LAUNCH_CHECK();
-        // total = offs[nb]
-        KGE_HIP(hipMemcpyAsync(out + n, offs + nb, sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
-    }
-    KGE_HIP(hipStreamSynchronize(st));
-    (void)hipFree(sums);
-    (void)hipFree(offs);
+    uint32_t *scratch = nullptr;
+    const size_t words = scan_scratch_words(n);
+    if (words) KGE_HIP(hipMalloc(&scratch, sizeof(uint32_t) * words));
+    int rc = exclusive_scan_ws(in, out, n, scratch, st);
+    if (rc == KGE_OK && hipStreamSynchronize(st) != hipSuccess) { kge_set_error("scan failed"); rc = KGE_EHIP; }
+    if (scratch) (void)hipFree(scratch);
+    return rc;
+}
+
+template <typename K>
+int radix_sort(K **keys, uint32_t **vals, K **keys_alt, uint32_t **vals_alt, int64_t n, int bits,
+               hipStream_t st)
+{
+    if (n == 0) return KGE_OK;
+    uint32_t *scratch = nullptr;
+    KGE_HIP(hipMalloc(&scratch, sizeof(uint32_t) * radix_scratch_words(n)));
+    int rc = radix_sort_ws<K>(keys, vals, keys_alt, vals_alt, n, bits, scratch, st);
+    (void)hipStreamSynchronize(st);
+    (void)hipFree(scratch);
     return rc;
 }
 
@@ -231,118 +133,6 @@ __global__ void k_edge_emit(const int32_t *head, const int32_t *rel, const int32
     uint32_t q = epos[e];
     keys[q] = (r << (2 * vbits)) | (dst << vbits) | src;
     vals[q] = (uint32_t)e;
-}
-
-// ---------------------------------------------------------------- radix sort
-// Stable LSD radix sort, 8 bits per pass.  A tile of SORT_TILE elements is split so that
-// wavefront w owns the contiguous chunk [w*512, (w+1)*512): ascending index order is then
-// (wavefront, row, lane), which is the order ranks are handed out in.
-template <typename K>
-__global__ void k_radix_hist(const K *keys, int64_t n, int shift, uint32_t *hist, int64_t nblk)
-{
-    __shared__ uint32_t h[256];
-    h[threadIdx.x] = 0;
-    __syncthreads();
-    int64_t base = (int64_t)blockIdx.x * SORT_TILE;
-#pragma unroll
-    for (int k = 0; k < SORT_ROWS; ++k) {
-        int64_t idx = base + (int64_t)k * TB + threadIdx.x;
-        if (idx < n) atomicAdd(&h[(uint32_t)(keys[idx] >> shift) & 255u], 1u);
-    }
-    __syncthreads();
-    hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
-}
-
-template <typename K>
-__global__ void k_radix_scatter(const K *keys_in, const uint32_t *vals_in, K *keys_out,
-                                uint32_t *vals_out, int64_t n, int shift, const uint32_t *offs,
-                                int64_t nblk)
-{
-    __shared__ uint32_t cnt[TB / 64][256];
-    __shared__ uint32_t base[TB / 64][256];
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-#pragma unroll
-    for (int k = 0; k < TB / 64; ++k) cnt[k][threadIdx.x] = 0;
-    __syncthreads();
-
-    const int64_t start = (int64_t)blockIdx.x * SORT_TILE + (int64_t)w * (64 * SORT_ROWS);
-    K key[SORT_ROWS];
-    uint32_t val[SORT_ROWS], rank[SORT_ROWS];
-#pragma unroll
-    for (int it = 0; it < SORT_ROWS; ++it) {
-        int64_t idx = start + it * 64 + lane;
-        bool valid = idx < n;
-        key[it] = valid ? keys_in[idx] : (K)0;
-        val[it] = valid ? vals_in[idx] : 0u;
-        uint32_t digit = (uint32_t)(key[it] >> shift) & 255u;
-        unsigned long long mask = __ballot(valid);
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            bool bit = (digit >> b) & 1u;
-            unsigned long long bal = __ballot(valid && bit);
-            mask &= bit ? bal : ~bal;
-        }
-        // mask: valid lanes of this row holding the same digit as this lane
-        uint32_t below = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-        uint32_t same = (uint32_t)__popcll(mask);
-        uint32_t prev = 0;
-        if (valid && below == 0) {          // lowest lane of its digit group updates the counter
-            prev = cnt[w][digit];
-            cnt[w][digit] = prev + same;
-        }
-        int leader = valid ? (__ffsll((long long)mask) - 1) : lane;
-        prev = __shfl(prev, leader, 64);
-        rank[it] = prev + below;
-        __builtin_amdgcn_wave_barrier();
-    }
-    __syncthreads();
-    {
-        uint32_t run = offs[(int64_t)threadIdx.x * nblk + blockIdx.x];
-#pragma unroll
-        for (int k = 0; k < TB / 64; ++k) {
-            base[k][threadIdx.x] = run;
-            run += cnt[k][threadIdx.x];
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int it = 0; it < SORT_ROWS; ++it) {
-        int64_t idx = start + it * 64 + lane;
-        if (idx < n) {
-            uint32_t digit = (uint32_t)(key[it] >> shift) & 255u;
-            uint32_t pos = base[w][digit] + rank[it];
-            keys_out[pos] = key[it];
-            vals_out[pos] = val[it];
-        }
-    }
-}
-
-// Sort (keys, vals) by the low `bits` bits of the key, stable.  Buffers ping-pong; on return
-// *keys / *vals point at the sorted data (either the original or the alternate buffers).
-template <typename K>
-int radix_sort(K **keys, uint32_t **vals, K **keys_alt, uint32_t **vals_alt, int64_t n, int bits,
-               hipStream_t st)
-{
-    if (n == 0) return KGE_OK;
-    int64_t nblk = cdiv(n, SORT_TILE);
-    uint32_t *hist = nullptr, *offs = nullptr;
-    KGE_HIP(hipMalloc(&hist, sizeof(uint32_t) * (256 * nblk + 1)));
-    KGE_HIP(hipMalloc(&offs, sizeof(uint32_t) * (256 * nblk + 1)));
-    int rc = KGE_OK;
-    for (int shift = 0; shift < bits && rc == KGE_OK; shift += 8) {
-        k_radix_hist<K><<<(unsigned)nblk, TB, 0, st>>>(*keys, n, shift, hist, nblk);
-        rc = exclusive_scan(hist, offs, 256 * nblk, st);
-        if (rc != KGE_OK) break;
-        k_radix_scatter<K><<<(unsigned)nblk, TB, 0, st>>>(*keys, *vals, *keys_alt, *vals_alt, n,
-                                                         shift, offs, nblk);
-        if (hipGetLastError() != hipSuccess) { kge_set_error("radix scatter launch failed"); rc = KGE_EHIP; }
-        K *tk = *keys; *keys = *keys_alt; *keys_alt = tk;
-        uint32_t *tv = *vals; *vals = *vals_alt; *vals_alt = tv;
-    }
-    (void)hipStreamSynchronize(st);
-    (void)hipFree(hist);
-    (void)hipFree(offs);
-    return rc;
 }
 
 // ---------------------------------------------------------------- runs and views
@@ -422,17 +212,6 @@ __global__ void k_view_emit(const uint32_t *pos_sorted, int64_t E, const uint64_
     o_rel[q] = (int32_t)(k >> (2 * vbits));
     o_invc[q] = inv_c[edge_seg[e]];
     if (o_seg) o_seg[q] = (int32_t)edge_seg[e];
-}
-
-// ptr[v] = first position q with sorted[q] >= v, for v in [0, nv]; ptr[nv] = n.
-template <typename T>
-__global__ void k_ptr_from_sorted(const T *sorted, int64_t n, int64_t nv, int32_t *ptr)
-{
-    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (q > n) return;
-    int64_t lo = (q == 0) ? 0 : (int64_t)sorted[q - 1] + 1;
-    int64_t hi = (q == n) ? nv : (int64_t)sorted[q];
-    for (int64_t v = lo; v <= hi; ++v) ptr[v] = (int32_t)q;
 }
 
 // keys[s] = destination of run s, vals[s] = s

@@ -17,7 +17,7 @@ class TrainStep:
     def __init__(self, part: kb.Partition, params: Dict[str, object], acts: Sequence[int],
                  msg_dtype: int = kb.MSG_F32, need_dH0: bool = True, device: str = "cuda:0",
                  keep_scores: bool = True, cone: bool = False, order: int = kb.ORDER_PROJECT_FIRST,
-                 dropout: float = 0.0):
+                 dropout: float = 0.0, score_index: bool = True):
         import torch
         self.torch = torch
         self.part = part
@@ -49,6 +49,9 @@ class TrainStep:
         self.pos = None
         self.neg_ent = self.neg_side = self.scores = None
         self.n_neg = 0
+        # score_index: the atomic-free form of the scoring call (its scratch is allocated with the batch)
+        self.want_index = score_index
+        self.index = None
 
     def set_batch(self, pos_core_idx: np.ndarray, n_neg: int):
         torch = self.torch
@@ -59,6 +62,8 @@ class TrainStep:
         self.neg_side = torch.empty((n_pos, max(n_neg, 1)), dtype=torch.uint8, device=self.dev)
         self.scores = (torch.empty((n_pos, 1 + n_neg), dtype=torch.float32, device=self.dev)
                        if self.keep_scores else None)
+        self.index = (kb.ScoreIndex(self.part, max(n_pos, 1), self.n_neg, self.H_out.shape[1])
+                      if self.want_index else None)
 
     def stage_batches(self, batches):
         """Copy several mini-batches (equal-length index arrays) to the device ahead of a loop; returns the
@@ -96,7 +101,7 @@ class TrainStep:
 
     def score_loss(self, stream=None):
         kb.distmult_score_loss(self.part, self.H_out, self.M, self.pos, self.neg_ent, self.neg_side,
-                               self.n_neg, self.scores, self.loss, self.dH_out, self.dM, stream)
+                               self.n_neg, self.scores, self.loss, self.dH_out, self.dM, stream, self.index)
 
     def backward(self, stream=None):
         kb.rgcn_backward(self.part, self.layers, self.H0, self.workspace, self.dH_out, self.grads,

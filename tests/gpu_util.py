@@ -21,7 +21,8 @@ def layers_of(params, acts):
             for l in range(len(acts))]
 
 
-def gpu_step(spec, head, rel, tail, params=None, pos=None, need_dH0=True, cone=False, order=0, dropout=0.0):
+def gpu_step(spec, head, rel, tail, params=None, pos=None, need_dH0=True, cone=False, order=0, dropout=0.0,
+             score_index=True):
     """Build the partition and run one step on the GPU. Returns (part, step object, params, pos)."""
     from paper_2201_02791_amd import binding as kb
     from paper_2201_02791_amd.step import TrainStep
@@ -33,7 +34,8 @@ def gpu_step(spec, head, rel, tail, params=None, pos=None, need_dH0=True, cone=F
     if pos is None:
         pos = synth.make_batch(spec, part.n_core)
     msg = kb.MSG_BF16 if spec.msg_dtype == "bf16" else kb.MSG_F32
-    ts = TrainStep(part, params, spec.acts, msg, need_dH0=need_dH0, cone=cone, order=order, dropout=dropout)
+    ts = TrainStep(part, params, spec.acts, msg, need_dH0=need_dH0, cone=cone, order=order, dropout=dropout,
+                   score_index=score_index)
     ts.set_batch(pos, spec.n_neg)
     ts.run(spec.neg_mode, SEED, STEP)
     torch.cuda.synchronize()

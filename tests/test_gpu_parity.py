@@ -158,6 +158,87 @@ def test_bf16_messages_small(kb, orc, acts, n, m, d, B):
     say("bf16 errs vs the exact oracle", errs)
 
 
+# ------------------------------------------------------------------ the scoring call alone, both forms
+@pytest.mark.parametrize("indexed", [True, False], ids=["atomic_free", "atomics"])
+@pytest.mark.parametrize("d,n_pos,n_neg,mode", [(4, 50, 3, 1), (72, 300, 5, 1), (200, 700, 9, 1), (256, 260, 64, 1),
+                                                (260, 90, 2, 0), (512, 130, 7, 1), (32, 400, 0, 1), (64, 1, 1, 1)])
+def test_scoring_call_alone(kb, orc, d, n_pos, n_neg, mode, indexed):
+    """kge_distmult_score_loss on random embeddings against the oracle: scores, loss, dH, dM; widths that leave
+    lanes idle, one and two 16-byte pieces per lane, negative counts that are not multiples of 4, no negatives,
+    a single positive, and a hub entity that most triples name (a long occurrence list)."""
+    import torch
+    say("scoring alone", d, n_pos, n_neg, mode, "indexed" if indexed else "atomics")
+    n, R, m = 900, 7, 6000
+    head, rel, tail = random_graph(d + n_pos, n, R, m)
+    head[: m // 3] = 5                                   # vertex 5 heads a third of the triples
+    gp = kb.build_partition(head, rel, tail, n, R, 1, 0, 2, 0)
+    op = orc.build_partition(head, rel, tail, n, R, 1, 0, 2, 0)
+    rng = np.random.default_rng(d)
+    H = rng.normal(0, 0.5, (gp.n_vert, d)).astype(np.float32)
+    M = rng.normal(0, 0.5, (R, d)).astype(np.float32)
+    pos = rng.permutation(gp.n_core)[:n_pos].astype(np.int32)
+    ne, ns = orc.sample_negatives(op, pos, n_neg, mode, SEED, STEP)
+    want = orc.distmult_score_loss(op, H, M, pos, ne, ns)
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    dH = torch.full((gp.n_vert, d), 7.0, device="cuda"); dM = torch.full((R, d), 7.0, device="cuda")
+    scores = torch.empty((n_pos, 1 + n_neg), device="cuda"); loss = torch.full((1,), 7.0, device="cuda")
+    idx = kb.ScoreIndex(gp, n_pos, n_neg, d) if indexed else None
+    args = (gp, t(H), t(M), t(pos), t(ne.reshape(n_pos, -1)) if n_neg else None, t(ns.reshape(n_pos, -1)) if n_neg else None,
+            n_neg, scores, loss, dH, dM)
+    kb.distmult_score_loss(*args, index=idx)
+    torch.cuda.synchronize()
+    assert rel_err(scores.cpu().numpy(), want["scores"]) <= TOL_VAL
+    assert abs(float(loss.cpu()[0]) - want["loss"]) <= TOL_VAL * want["loss"]
+    assert rel_err(dH.cpu().numpy(), want["dH"]) <= TOL_GRAD
+    assert rel_err(dM.cpu().numpy(), want["dM"]) <= TOL_GRAD
+    untouched = np.abs(want["dH"]).max(axis=1) == 0
+    assert untouched.any() or n_pos * (2 + n_neg) > 2000
+    assert not dH.cpu().numpy()[untouched].any()
+    if indexed:
+        assert idx.bad_ids() == 0
+        first = dH.clone()
+        dH.fill_(3.0)
+        kb.distmult_score_loss(*args, index=idx)
+        torch.cuda.synchronize()
+        assert torch.equal(first, dH), "the atomic-free form must repeat bit for bit"
+
+
+def test_scoring_index_counts_ids_outside_the_partition(kb, orc):
+    """With the index no id becomes an address unchecked: an entity or core-edge index outside the partition is
+    replaced and counted (the call's outputs are then meaningless, but nothing is read or written out of bounds)."""
+    import torch
+    say("scoring index, ids out of range")
+    n, R, m, d, n_pos, n_neg = 300, 3, 2000, 32, 40, 4
+    head, rel, tail = random_graph(5, n, R, m)
+    gp = kb.build_partition(head, rel, tail, n, R, 1, 0, 2, 0)
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    rng = np.random.default_rng(1)
+    H = t(rng.normal(size=(gp.n_vert, d)).astype(np.float32)); M = t(rng.normal(size=(R, d)).astype(np.float32))
+    pos = rng.permutation(gp.n_core)[:n_pos].astype(np.int32)
+    ne = rng.integers(0, gp.n_vert, (n_pos, n_neg)).astype(np.int32); ns = np.zeros((n_pos, n_neg), np.uint8)
+    pos[3] = gp.n_core + 5; pos[7] = -1                 # two bad core-edge indices
+    ne[0, 0] = gp.n_vert; ne[9, 2] = -4; ne[11, 3] = 2 ** 31 - 1      # three bad entities
+    idx = kb.ScoreIndex(gp, n_pos, n_neg, d)
+    dH = torch.empty((gp.n_vert, d), device="cuda"); dM = torch.empty((R, d), device="cuda")
+    loss = torch.empty(1, device="cuda")
+    kb.distmult_score_loss(gp, H, M, t(pos), t(ne), t(ns), n_neg, None, loss, dH, dM, index=idx)
+    torch.cuda.synchronize()
+    assert idx.bad_ids() == 5
+    with pytest.raises(kb.KgeError):                     # a batch larger than the index was made for
+        kb.distmult_score_loss(gp, H, M, t(np.zeros(n_pos + 1, np.int32)), None, None, 0, None, loss, dH, dM, index=idx)
+
+
+def test_step_with_atomic_scoring(kb, orc):
+    """The whole step with the scoring call's atomic form (no index)."""
+    say("step, atomic scoring")
+    spec = synth.scaled(synth.WORKLOADS[0], name="atomic", seed=17, n_entities=400, n_relations=6, n_triples=3000,
+                        d=200, n_bases=10, n_pos=333, n_neg=5, neg_mode=1, feature_std=0.5)
+    head, rel, tail = random_graph(3, 400, 6, 3000)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, score_index=False)
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
+    assert_step_close(ts, res, TOL_VAL, TOL_GRAD)
+
+
 def test_zero_negatives_and_empty_batch(kb, orc):
     say("n_neg = 0 / n_pos = 0")
     spec = synth.scaled(synth.WORKLOADS[0], n_entities=200, n_triples=900, n_pos=50, n_neg=0)
