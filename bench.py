@@ -305,7 +305,7 @@ class Graphs:
         self.parts.pop(cfg, None)
 
 
-ORDER_NAMES = {"project": "project-first", "aggregate": "aggregate-first", "relation": "relation-weight"}
+ORDER_NAMES = {"project": "project-first", "relation": "relation-weight"}
 
 
 def run_workload(graphs, cfg, order="relation", whole=False, dropout=0.0, steps=10, warmup=2, paper_setting=False,
@@ -325,8 +325,8 @@ def run_workload(graphs, cfg, order="relation", whole=False, dropout=0.0, steps=
     lr = lr if lr is not None else DEFAULT_LR.get(cfg, 0.01)
     ts = TrainStep(part, params, spec.acts, msg, need_dH0=not spec.fixed_features, keep_scores=True,
                    cone=not whole,
-                   order={"project": kb.ORDER_PROJECT_FIRST, "aggregate": kb.ORDER_AGGREGATE_FIRST,
-                          "relation": kb.ORDER_RELATION_WEIGHTS}[order], dropout=dropout)
+                   order={"project": kb.ORDER_PROJECT_FIRST, "relation": kb.ORDER_RELATION_WEIGHTS}[order],
+                   dropout=dropout)
     del params
     batches = [synth.make_batch(synth.scaled(spec, seed=spec.seed + 101 * i), part.n_core) for i in range(warmup + steps)]
     ts.set_batch(batches[0], spec.n_neg)
@@ -462,10 +462,10 @@ def main():
     ap.add_argument("--config", type=int, default=4,
                     help="index into the workload list (0..4); default: the largest single-GPU workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--order", choices=["project", "aggregate", "relation"], default="relation",
+    ap.add_argument("--order", choices=["project", "relation"], default="relation",
                     help="order of Eq. 1-2: project-first (P = H V_b, then the neighbour sum; the order the step is "
-                         "named in), aggregate-first (run means, per-basis sums, one contraction) or relation-weight "
-                         "(run means times W_r; the default, the fastest with the same results)")
+                         "named in) or relation-weight (run means times W_r; the default, the library's product path, "
+                         "same results)")
     ap.add_argument("--no-optimizer", action="store_true",
                     help="leave the optimizer step (Adam) out of the timed step")
     ap.add_argument("--lr", type=float, default=None, help="Adam's learning rate (default 0.01; 0.001 at configs[4])")

@@ -33,7 +33,6 @@
  *  - All matrices are dense row-major.  Feature widths must be multiples of 4
  *    (of 8 when msg_dtype = KGE_MSG_BF16).  Per layer and order:
  *      project-first     d_in <= 512, d_out <= 256
- *      aggregate-first   d_in <= 256, d_out <= 256
  *      relation-weight   d_in, d_out <= 256 (512 with bf16 messages)
  *    A wider layer is refused with KGE_EINVAL before anything runs.
  */
@@ -60,17 +59,17 @@ enum { KGE_MSG_F32 = 0, KGE_MSG_BF16 = 1 };      /* storage type of projected me
 enum { KGE_NEG_TAIL = 0, KGE_NEG_HEAD_OR_TAIL = 1 };
 enum { KGE_DOMAIN_CORE = 0, KGE_DOMAIN_ALL = 1 };
 /* Order in which a layer applies Eq. 1-2 (the results are the same up to rounding):
- *   KGE_ORDER_PROJECT_FIRST    P[j][b] = h_j V_b for every vertex, then the neighbour sum over
- *                              projected messages: (B+1) d_out values move per edge.
- *   KGE_ORDER_AGGREGATE_FIRST  z_{i,r} = (1/c_ir) sum_{j in N_i^r} h_j per (relation,
- *                              destination) run, y_{i,b} = sum_r a_rb z_{i,r}, then
- *                              pre_i = sum_b y_{i,b} V_b + h_i W_0: d_in values move per edge.
- *   KGE_ORDER_RELATION_WEIGHTS the same run means z_{i,r}, then Eq. 2 written out, W_r = sum_b a_rb
- *                              V_b for every relation, and pre_i = sum_r z_{i,r} W_r + h_i W_0 as one
- *                              product per (relation, destination) run, grouped by relation over the
- *                              (relation, destination)-sorted runs.  S d_in d_out multiply-adds instead
- *                              of N B d_in d_out: cheaper when a vertex has fewer runs than bases. */
-enum { KGE_ORDER_PROJECT_FIRST = 0, KGE_ORDER_AGGREGATE_FIRST = 1, KGE_ORDER_RELATION_WEIGHTS = 2 };
+ *   KGE_ORDER_PROJECT_FIRST    the order the step is usually written in: P[j][b] = h_j V_b for every vertex,
+ *                              then the neighbour sum over projected messages.  (B+1) d_out values move
+ *                              per edge.
+ *   KGE_ORDER_RELATION_WEIGHTS the library's product path (what the benchmark times): run means
+ *                              z_{i,r} = (1/c_ir) sum_{j in N_i^r} h_j per (relation, destination) run, then
+ *                              Eq. 2 written out, W_r = sum_b a_rb V_b for every relation, and
+ *                              pre_i = sum_r z_{i,r} W_r + h_i W_0 as one product per run, grouped by relation
+ *                              over the (relation, destination)-sorted runs.  d_in values move per edge and
+ *                              S d_in d_out multiply-adds replace N B d_in d_out.
+ * (Value 1 belonged to a third order that was removed; it is refused.) */
+enum { KGE_ORDER_PROJECT_FIRST = 0, KGE_ORDER_RELATION_WEIGHTS = 2 };
 
 typedef struct kge_partition kge_partition;      /* opaque; device resident; library owned    */
 typedef struct kge_cgraph kge_cgraph;            /* opaque; one batch's computational sub-graph */
@@ -424,12 +423,10 @@ int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_ent
  *               ld = B*d_out (fp32 messages) or (B+1)*d_out (bf16 messages: G, rounded to
  *               bf16, is appended behind the B blocks)
  *   KGE_WS_DH   gradient with respect to layer l's INPUT, l >= 1, [N][d_in] float (after backward)
- *   KGE_WS_Z    aggregate-first or relation-weight layer l: run means z [S][d_in], one row per (relation,
+ *   KGE_WS_Z    relation-weight layer l: run means z [S][d_in], one row per (relation,
  *               destination) run in the partition's run order (valid after forward).  A relation-weight
  *               layer with bf16 messages leaves the rows of single-edge runs unwritten: such a run's mean
  *               is its source's row of the layer input, which the layer reads in place
- *   KGE_WS_Y    aggregate-first layer l: y [N][B*d_in] float of the last such layer forward has
- *               processed (the buffer is shared between layers)
  *   KGE_WS_HD   layer l's input after dropout [N][d_in] float (valid after forward; only for layers
  *               with dropout > 0; with dropout, KGE_WS_DH is the gradient with respect to the
  *               input BEFORE dropout)
@@ -437,11 +434,10 @@ int kge_profile_collect(kge_prof_entry *out, int32_t max_entries, int32_t *n_ent
  *               forward it holds u [S][d_out] of the last layer (the per-run products z W_r); after
  *               backward dz [S][d_in] of the last layer that produced an input gradient.  The slice
  *               is sized for the wider of the two.
- * KGE_WS_P exists only for project-first layers, KGE_WS_Y only for aggregate-first ones, KGE_WS_Z for
- * both orders that sum first, KGE_WS_U and no KGE_WS_DP contents beyond G for relation-weight layers.
+ * KGE_WS_P exists only for project-first layers; KGE_WS_Z, KGE_WS_U and no KGE_WS_DP contents beyond G for
+ * relation-weight layers.
  */
-enum { KGE_WS_P = 0, KGE_WS_H = 1, KGE_WS_G = 2, KGE_WS_DP = 3, KGE_WS_DH = 4, KGE_WS_Z = 5, KGE_WS_Y = 6, KGE_WS_U = 7,
-       KGE_WS_HD = 8 };
+enum { KGE_WS_P = 0, KGE_WS_H = 1, KGE_WS_G = 2, KGE_WS_DP = 3, KGE_WS_DH = 4, KGE_WS_Z = 5, KGE_WS_U = 7, KGE_WS_HD = 8 };
 int kge_workspace_slice(const kge_partition *p, const kge_layer *layers, int32_t n_layers,
                         int32_t msg_dtype, int32_t which, int32_t layer, size_t *offset,
                         size_t *bytes);

@@ -27,7 +27,7 @@ EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_score_index_bad_ids"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
-ORDER_PROJECT_FIRST, ORDER_AGGREGATE_FIRST, ORDER_RELATION_WEIGHTS = 0, 1, 2
+ORDER_PROJECT_FIRST, ORDER_RELATION_WEIGHTS = 0, 2
 OPT_SGD, OPT_ADAM = 0, 1
 MSG_F32, MSG_BF16 = 0, 1
 NEG_TAIL, NEG_HEAD_OR_TAIL = 0, 1
@@ -335,7 +335,7 @@ def profile_collect() -> dict:
     return {arr[i].name.decode(): (float(arr[i].total_ms), int(arr[i].calls)) for i in range(n.value)}
 
 
-WS_P, WS_H, WS_G, WS_DP, WS_DH, WS_Z, WS_Y, WS_U, WS_HD = 0, 1, 2, 3, 4, 5, 6, 7, 8
+WS_P, WS_H, WS_G, WS_DP, WS_DH, WS_Z, WS_U, WS_HD = 0, 1, 2, 3, 4, 5, 7, 8
 
 
 def workspace_slice(part: Partition, layers: Sequence[dict], which: int, layer: int,

@@ -72,8 +72,8 @@ namespace {
 struct WsLayout {
     std::vector<size_t> off_P, off_H;   // per layer: projected messages, layer output
     std::vector<size_t> off_Hbf, off_Wbf, off_WbfT;   // bf16 workloads: bf16 copies of layer input and weights
-    std::vector<size_t> off_Z, off_Wst; // aggregate-first layers: run means [S][d_in]; bf16: stacked weights, transposed
-    size_t off_Y = 0, off_C = 0;        // aggregate-first layers: Y [N][B*d_in], C [2R][d_in*d_out] (shared)
+    std::vector<size_t> off_Z;          // relation-weight layers: run means [S][d_in]
+    size_t off_C = 0;                   // relation-weight layers: C [2R][d_in*d_out] (shared)
     // relation-weight layers: W_r fp32 [2R][d_in*d_out] and, for bf16 workloads, its bf16 copies in both
     // orientations; U / dZ [S][max(d_in, d_out)] (shared)
     std::vector<size_t> off_Wrel, off_Wrb, off_WrbT;
@@ -103,11 +103,8 @@ int check_layers(const kge_partition *p, const kge_layer *layers, int32_t n_laye
                     "layer %d: the project-first order needs d_out <= 256", l);
         KGE_REQUIRE(L.act == KGE_ACT_IDENTITY || L.act == KGE_ACT_RELU, KGE_EINVAL, "layer %d: bad act", l);
         KGE_REQUIRE(L.dropout >= 0.0f && L.dropout < 1.0f, KGE_EINVAL, "layer %d: dropout must be in [0, 1)", l);
-        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.order == KGE_ORDER_AGGREGATE_FIRST ||
-                        L.order == KGE_ORDER_RELATION_WEIGHTS, KGE_EINVAL, "layer %d: bad order", l);
-        // so do the per-basis sums over runs of the aggregate-first order, forward (rows of d_in) and backward
-        KGE_REQUIRE(L.order != KGE_ORDER_AGGREGATE_FIRST || (L.d_in <= 256 && L.d_out <= 256), KGE_EINVAL,
-                    "layer %d: the aggregate-first order needs d_in <= 256 and d_out <= 256", l);
+        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST || L.order == KGE_ORDER_RELATION_WEIGHTS, KGE_EINVAL,
+                    "layer %d: bad order", l);
         KGE_REQUIRE(L.order != KGE_ORDER_RELATION_WEIGHTS || L.d_in <= dmax, KGE_EINVAL,
                     "layer %d: the relation-weight order needs d_in <= %d", l, dmax);
         KGE_REQUIRE(l == 0 || L.d_in == layers[l - 1].d_out, KGE_EINVAL,
@@ -125,15 +122,13 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
     const bool bf = msg_dtype == KGE_MSG_BF16;
     size_t max_nc = 0;
     w->off_P.assign(n_layers, 0); w->off_H.resize(n_layers); w->off_Z.assign(n_layers, 0);
-    w->off_Wst.assign(n_layers, 0);
     w->off_Wrel.assign(n_layers, 0); w->off_Wrb.assign(n_layers, 0); w->off_WrbT.assign(n_layers, 0);
     size_t max_u = 0;
-    size_t max_y = 0, max_c = 0, max_zd = 0;
+    size_t max_c = 0, max_zd = 0;
     w->off_Hbf.assign(n_layers, 0); w->off_Wbf.assign(n_layers, 0); w->off_WbfT.assign(n_layers, 0);
     w->off_Hd.assign(n_layers, 0);
     for (int l = 0; l < n_layers; ++l) {
         const kge_layer &L = layers[l];
-        const bool agg = L.order == KGE_ORDER_AGGREGATE_FIRST;
         if (L.order == KGE_ORDER_RELATION_WEIGHTS) {
             const size_t dd = (size_t)L.d_in * L.d_out, R2 = (size_t)2 * p->n_relations;
             // bf16: the run means follow the bf16 copy of the layer input without a gap, so that the two are
@@ -150,16 +145,6 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
             if (R2 * dd * 4 > max_c) max_c = R2 * dd * 4;
             if ((size_t)L.d_in > max_zd) max_zd = L.d_in;
             if ((size_t)L.d_in > max_dout) max_dout = L.d_in;      // Self also holds the self-loop part of dH
-        } else if (agg) {
-            w->off_Z[l] = cur; cur = align_up(cur + (size_t)p->n_seg * L.d_in * ep, 256);
-            // fp32: Y [N][B d_in]; bf16: X = [Y | Hbf] [N][(B+1) d_in]
-            const size_t yb = bf ? N * (L.n_bases + 1) * L.d_in * 2 : N * L.n_bases * L.d_in * 4;
-            if (yb > max_y) max_y = yb;
-            if (bf) { w->off_Wst[l] = cur; cur = align_up(cur + (size_t)(L.n_bases + 1) * L.d_in * L.d_out * 2, 256); }
-            const size_t cb = (size_t)2 * p->n_relations * L.d_in * L.d_out * 4;
-            if (cb > max_c) max_c = cb;
-            if ((size_t)L.d_in > max_zd) max_zd = L.d_in;
-            if ((size_t)L.n_bases * L.d_in > max_bd) max_bd = (size_t)L.n_bases * L.d_in;   // partials of Y
         } else {
             w->off_P[l] = cur; cur = align_up(cur + N * L.n_bases * L.d_out * ep, 256);
         }
@@ -177,7 +162,6 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
             w->off_WbfT[l] = cur; cur = align_up(cur + nc * L.d_in * 2, 256);
         }
     }
-    w->off_Y = cur; cur = align_up(cur + max_y, 256);
     w->off_C = cur; cur = align_up(cur + max_c, 256);
     w->off_U = cur; cur = align_up(cur + max_u, 256);
     w->off_self = cur; cur = align_up(cur + N * max_dout * 4, 256);
@@ -192,7 +176,6 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
     if ((size_t)p->hv_sm.n_units * max_bd > part) part = (size_t)p->hv_sm.n_units * max_bd;
     if ((size_t)p->hv_seg.n_units * max_B > part) part = (size_t)p->hv_seg.n_units * max_B;
     if ((size_t)p->hv_seg.n_units * max_zd > part) part = (size_t)p->hv_seg.n_units * max_zd;
-    if (max_y > 0 && (size_t)p->hv_dr.n_units * max_bd > part) part = (size_t)p->hv_dr.n_units * max_bd;
     if (max_u > 0 && (size_t)p->hv_dr.n_units * max_dout > part) part = (size_t)p->hv_dr.n_units * max_dout;
     if (max_u > 0 && (size_t)p->hv_sm.n_units * max_dout > part) part = (size_t)p->hv_sm.n_units * max_dout;
     w->off_part = cur; cur = align_up(cur + part * 4, 256);
@@ -235,7 +218,7 @@ extern "C" int kge_workspace_slice(const kge_partition *p, const kge_layer *laye
     const kge_layer &L = layers[layer];
     switch (which) {
     case KGE_WS_P:
-        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST, KGE_EINVAL, "an aggregate-first layer keeps no projected messages");
+        KGE_REQUIRE(L.order == KGE_ORDER_PROJECT_FIRST, KGE_EINVAL, "a relation-weight layer keeps no projected messages");
         *offset = w.off_P[layer]; *bytes = N * L.n_bases * L.d_out * ep; break;
     case KGE_WS_Z:
         KGE_REQUIRE(L.order != KGE_ORDER_PROJECT_FIRST, KGE_EINVAL, "a project-first layer keeps no run means");
@@ -243,11 +226,6 @@ extern "C" int kge_workspace_slice(const kge_partition *p, const kge_layer *laye
     case KGE_WS_U:
         KGE_REQUIRE(L.order == KGE_ORDER_RELATION_WEIGHTS, KGE_EINVAL, "only relation-weight layers have per-run products");
         *offset = w.off_U; *bytes = (size_t)p->n_seg * (size_t)(L.d_in > L.d_out ? L.d_in : L.d_out) * ep; break;
-    case KGE_WS_Y:
-        KGE_REQUIRE(L.order == KGE_ORDER_AGGREGATE_FIRST, KGE_EINVAL, "only aggregate-first layers have Y");
-        *offset = w.off_Y;
-        *bytes = msg_dtype == KGE_MSG_BF16 ? N * (size_t)(L.n_bases + 1) * L.d_in * 2 : N * (size_t)L.n_bases * L.d_in * 4;
-        break;
     case KGE_WS_H: *offset = w.off_H[layer]; *bytes = N * L.d_out * 4; break;
     case KGE_WS_HD:
         KGE_REQUIRE(L.dropout > 0.0f, KGE_EINVAL, "layer %d has no dropout", layer);
@@ -333,37 +311,6 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
             Hin = Hl;
             continue;
         }
-        if (L.order == KGE_ORDER_AGGREGATE_FIRST) {
-            void *Z = ws + w.off_Z[l];
-            void *Y = ws + w.off_Y;
-            const uint8_t *act_l = kge_cgraph_layer(cg, l);
-            if (bf) {
-                void *Hbf = ws + w.off_Hbf[l], *Wbf = ws + w.off_Wbf[l], *WbfT = ws + w.off_WbfT[l], *WstT = ws + w.off_Wst[l];
-                rc = launch_cvt_rows_bf16(Hin, p->n_vert * (int64_t)L.d_in, Hbf, st);
-                if (rc != KGE_OK) return rc;
-                rc = launch_cvt_weights_bf16(L.V, L.W0, L.d_in, L.d_out, L.n_bases, Wbf, WbfT, st);   // backward reads Wbf
-                if (rc != KGE_OK) return rc;
-                rc = launch_cvt_wstack_bf16(L.V, L.W0, L.d_in, L.d_out, L.n_bases, WstT, st);
-                if (rc != KGE_OK) return rc;
-                rc = launch_run_mean(p, Hbf, L.d_in, Z, 1, part, act_l, 0, st);
-                if (rc != KGE_OK) return rc;
-                rc = launch_aggregate_runs(p, Z, L.a, L.n_bases, L.d_in, Y, (int64_t)(L.n_bases + 1) * L.d_in, 1, part, act_l, st);
-                if (rc != KGE_OK) return rc;
-                rc = launch_append_g_bf16(Hin, p->n_vert, L.d_in, L.n_bases, Y, st);      // X = [Y | Hbf]
-                if (rc != KGE_OK) return rc;
-                rc = launch_combine_bf16(Y, p->n_vert, L.d_in, L.d_out, L.n_bases, WstT, L.act, act_l, out1, out2, st);
-            } else {
-                rc = launch_run_mean(p, Hin, L.d_in, Z, 0, part, act_l, 0, st);
-                if (rc != KGE_OK) return rc;
-                rc = launch_aggregate_runs(p, Z, L.a, L.n_bases, L.d_in, Y, (int64_t)L.n_bases * L.d_in, 0, part, act_l, st);
-                if (rc != KGE_OK) return rc;
-                rc = launch_combine((const float *)Y, Hin, p->n_vert, L.d_in, L.d_out, L.n_bases, L.V, L.W0, L.act, act_l,
-                                    out1, out2, st);
-            }
-            if (rc != KGE_OK) return rc;
-            Hin = Hl;
-            continue;
-        }
         if (bf) {
             void *Hbf = ws + w.off_Hbf[l], *Wbf = ws + w.off_Wbf[l], *WbfT = ws + w.off_WbfT[l];
             rc = launch_cvt_rows_bf16(Hin, p->n_vert * (int64_t)L.d_in, Hbf, st);
@@ -421,7 +368,6 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
             if (rc != KGE_OK) return rc;
             Gl = G;
         }
-        const bool agg = L.order == KGE_ORDER_AGGREGATE_FIRST;
         float *C = (float *)(ws + w.off_C);
         if (L.order == KGE_ORDER_RELATION_WEIGHTS) {
             // W_r = sum_b a_rb V_b was applied per (relation, destination) run: dW_r = C_r = sum_runs z^T G,
@@ -470,13 +416,7 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
             }
             continue;
         }
-        if (agg && !bf) {
-            rc = launch_rel_outer(p, (const float *)(ws + w.off_Z[l]), Gl, L.d_in, L.d_out, C, st);
-            if (rc != KGE_OK) return rc;
-            rc = launch_coeff_contract(p, C, L.V, L.d_in, L.d_out, L.n_bases, grads[l].da, st);
-        } else if (!agg) {
-            rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, part, grads[l].da, kge_cgraph_layer(cg, l), st);
-        }
+        rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, part, grads[l].da, kge_cgraph_layer(cg, l), st);
         if (rc != KGE_OK) return rc;
         const int64_t bd = (int64_t)L.n_bases * L.d_out;
         rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf ? bd + L.d_out : bd, bf, part,
@@ -485,12 +425,6 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
         if (bf) {
             rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, L.n_bases, dP, st);
             if (rc != KGE_OK) return rc;
-            if (agg) {       // the coefficient gradient reads the bf16 copy of G that was just appended
-                rc = launch_rel_outer_bf16(p, ws + w.off_Z[l], nullptr, (const uint16_t *)dP + bd, bd + L.d_out, L.d_in, L.d_out, C, st);
-                if (rc != KGE_OK) return rc;
-                rc = launch_coeff_contract(p, C, L.V, L.d_in, L.d_out, L.n_bases, grads[l].da, st);
-                if (rc != KGE_OK) return rc;
-            }
             rc = launch_weight_grad_bf16(ws + w.off_Hbf[l], p->n_vert, L.d_in, L.d_out, L.n_bases, dP,
                                          grads[l].dV, grads[l].dW0, st);
         } else {

@@ -146,19 +146,12 @@ int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const
 const uint8_t *kge_cgraph_layer(const kge_cgraph *cg, int32_t layer);
 int kge_cgraph_check(const kge_partition *p, const kge_cgraph *cg, int32_t n_layers);
 
-// gather.hip, aggregate-first order ------------------------------------------
+// gather.hip, run means (relation-weight order) -----------------------------
 // Z[s][:] = invc_s sum_{j in run s} H[j][:]  ([S][d]; H and Z both fp32 or, with bf16 != 0, both bf16;
 // sums in fp32); runs into inactive destinations get zeros; `partial`: [hv_seg.n_units][d] floats
 // skip_single: runs of one edge are left unwritten (their mean is their source's row of H, see seg_zrow)
 int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, int bf16, float *partial,
                     const uint8_t *active, int skip_single, hipStream_t st);
-// Y[i][b][:] = sum_{runs (r,i) of i} a[r][b] Z[run][:]; rows are `ld` elements apart; rows with
-// row_active[i] == 0 are left unwritten; `partial`: [hv_dr.n_units][B*d] floats
-// (Z and Y are fp32, or both bf16 when msg_bf16 != 0)
-int launch_aggregate_runs(const kge_partition *p, const void *Z, const float *a, int32_t B, int32_t d,
-                          void *Y, int64_t ld, int msg_bf16, float *partial, const uint8_t *row_active,
-                          hipStream_t st);
-
 // gather.hip, relation-weight order ------------------------------------------
 // out[i] = act( sum over the runs (r, i) of destination i of U[run][:] + Self[i] ); U [S][d] fp32 or bf16;
 // zero rows where active[i] == 0; `partial`: [hv_dr.n_units][d] floats
@@ -190,11 +183,7 @@ int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, 
 int launch_apply_relation_weights_t_bf16(const kge_partition *p, const void *Gbf, int64_t ldg, const void *Wb,
                                          int32_t d_in, int32_t d_out, void *dZ, hipStream_t st);
 
-// gemm.hip, aggregate-first order ---------------------------------------------
-// out[i][:] = act( sum_b Y[i][b][:] V_b + H[i][:] W0 ), zero rows where row_active[i] == 0; out2 optional copy
-int launch_combine(const float *Y, const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
-                   const float *V, const float *W0, int act, const uint8_t *row_active, float *out,
-                   float *out2, hipStream_t st);
+// gemm.hip, relation-weight order (coefficient gradient) ---------------------
 // C[r] (d_in x d_out; [2R][d_in*d_out] floats, zeroed inside) = sum_{runs s of relation r} Z[s]^T G[seg_dst[s]]
 int launch_rel_outer(const kge_partition *p, const float *Z, const float *G, int32_t d_in, int32_t d_out,
                      float *C, hipStream_t st);
@@ -202,13 +191,7 @@ int launch_rel_outer(const kge_partition *p, const float *Z, const float *G, int
 int launch_coeff_contract(const kge_partition *p, const float *C, const float *V, int32_t d_in, int32_t d_out,
                           int32_t B, float *da, hipStream_t st);
 
-// gemm_bf16.hip, aggregate-first order ----------------------------------------
-// [V_1; ..; V_B; W0] -> WstT bf16 [d_out][(B+1) d_in]
-int launch_cvt_wstack_bf16(const float *V, const float *W0, int32_t d_in, int32_t d_out, int32_t B, void *WstT,
-                           hipStream_t st);
-// out = act(X WstT^T), X = [Y | Hbf] bf16 [N][(B+1) d_in]; zero rows where row_active[i] == 0
-int launch_combine_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const void *WstT,
-                        int act, const uint8_t *row_active, float *out, float *out2, hipStream_t st);
+// gemm_bf16.hip ----------------------------------------------------------------
 // the same C from bf16 operands: Zbf [S][d_in] (or, with zrow, the matrix [X; Z] read through zrow); Gbf rows
 // of d_out elements, ldg elements apart
 int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const int32_t *zrow, const void *Gbf, int64_t ldg,

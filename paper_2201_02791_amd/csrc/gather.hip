@@ -1050,15 +1050,6 @@ int launch_gather_transpose(const kge_partition *p, const float *G, const float 
     return launch_tview(vw, G, 0, a, B, d, dP, ld, msg_bf16, partial, active, nullptr, st);
 }
 
-// Y[i][b][:] = sum over the runs (r, i) of destination i of a[r][b] Z[run][:]
-int launch_aggregate_runs(const kge_partition *p, const void *Z, const float *a, int32_t B, int32_t d,
-                          void *Y, int64_t ld, int msg_bf16, float *partial, const uint8_t *row_active,
-                          hipStream_t st)
-{
-    const TView vw{p->dr_ptr, p->dr_seg, p->dr_rel, nullptr, p->n_vert, &p->hv_dr, "aggregate"};
-    return launch_tview(vw, Z, msg_bf16, a, B, d, Y, ld, msg_bf16, partial, nullptr, row_active, st);
-}
-
 template <bool BF16, int LPR>
 static int launch_coeff_seg(const kge_partition *p, const void *P, const float *G, int32_t B, int32_t d,
                             int gbc, float *seg_scratch, float *partial, const uint8_t *active, hipStream_t st)

@@ -5,9 +5,8 @@
 //   weight_grad  d[V_1 .. V_B | W_0] = H^T [dP | G]            (d_in x N) (N x (B+1)d_out)
 //   input_grad   dH = [dP | G] [V_1 .. V_B | W_0]^T            (N x (B+1)d_out) ((B+1)d_out x d_in)
 //
-// and, for layers that aggregate before they project,
+// and, for layers that apply W_r per (relation, destination) run,
 //
-//   combine      H' = act([Y | H] [V_1; ..; V_B; W_0])          (N x (B+1)d_in) ((B+1)d_in x d_out)
 //   rel_outer    C_r = sum_{runs s of r} Z_s^T G_{dst(s)}        grouped over relations, (d_in x d_out) each
 //   coeff        da = C Vflat^T                                  (2R x d_in d_out) (d_in d_out x B)
 //
@@ -67,20 +66,6 @@ struct SrcXcat {
         if (r >= rows || c >= bd + d_out) return make_float4(0.f, 0.f, 0.f, 0.f);
         if (c >= bd) return *reinterpret_cast<const float4 *>(G + r * d_out + (c - bd));
         return *reinterpret_cast<const float4 *>(dP + r * bd + c);
-    }
-};
-
-// [V_1; ..; V_B; W0] viewed as a ((B+1) d_in x d_out) matrix (V's own memory order, then W0)
-struct SrcWstack {
-    const float *V, *W0; int32_t d_in, d_out, B;
-    __device__ __forceinline__ void limit_rows(int64_t) {}
-    __device__ __forceinline__ void bind(int32_t) {}
-    __device__ __forceinline__ float4 load4(int64_t k, int32_t c) const
-    {
-        const int64_t bk = (int64_t)B * d_in;
-        if (k >= bk + d_in || c >= d_out) return make_float4(0.f, 0.f, 0.f, 0.f);
-        const float *base = k < bk ? V + k * d_out : W0 + (k - bk) * d_out;
-        return *reinterpret_cast<const float4 *>(base + c);
     }
 };
 
@@ -153,20 +138,6 @@ struct EpiRowMajorAtomic {      // split-K partial tiles
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
         if (m < rows && n < cols) unsafeAtomicAdd(out + m * cols + n, v);
-    }
-};
-
-struct EpiAct {                 // activation, zero rows outside the sub-graph, optional second copy
-    float *out, *out2; int64_t rows; int32_t cols; int act; const uint8_t *row_active;
-    __device__ __forceinline__ void bind(int32_t) {}
-    __device__ __forceinline__ void limit_rows(int64_t) {}
-    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
-    {
-        if (m >= rows || n >= cols) return;
-        float r = act == KGE_ACT_RELU ? fmaxf(v, 0.f) : v;
-        if (row_active && !row_active[m]) r = 0.f;
-        out[m * cols + n] = r;
-        if (out2) out2[m * cols + n] = r;
     }
 };
 
@@ -382,22 +353,6 @@ int launch_input_grad(const float *dP, const float *G, int64_t N, int32_t d_in,
     KGE_PROF("input_grad", st);
     SrcXcat sa{dP, G, N, d_out, B};
     k_gemm<SrcXcat, true, SrcWcat, true, EpiRowMajor><<<grid, GT, 0, st>>>(sa, sb, ep, nc, nc);
-    KGE_LAUNCH_CHECK();
-    return KGE_OK;
-}
-
-int launch_combine(const float *Y, const float *H, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
-                   const float *V, const float *W0, int act, const uint8_t *row_active, float *out,
-                   float *out2, hipStream_t st)
-{
-    if (N == 0) return KGE_OK;
-    const int64_t K = (int64_t)(B + 1) * d_in;
-    dim3 grid((unsigned)cdiv(N, BM), (unsigned)cdiv(d_out, BN), 1);
-    SrcXcat sa{Y, H, N, d_in, B};                 // [Y | H]: B blocks of d_in columns, then d_in more
-    SrcWstack sb{V, W0, d_in, d_out, B};
-    EpiAct ep{out, out2, N, d_out, act, row_active};
-    KGE_PROF("combine", st);
-    k_gemm<SrcXcat, true, SrcWstack, false, EpiAct><<<grid, GT, 0, st>>>(sa, sb, ep, K, K);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }

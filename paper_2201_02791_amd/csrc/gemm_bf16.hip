@@ -10,9 +10,8 @@
 //   input_grad   dH         = X    (N x nc) *  Wbf^T    both operands k-contiguous
 //   weight_grad  d[V | W0]  = Hbf^T * X                 both operands k-strided (k = vertex); formed as (X^T Hbf)^T
 //
-// and for layers that aggregate before they project:
+// and for layers that apply W_r per (relation, destination) run:
 //
-//   combine      H' = act([Y | Hbf] * WstT^T)             both operands k-contiguous, K = (B+1) d_in
 //   rel_outer    C_r = sum_{runs s of r} Zbf[s]^T Gbf[dst(s)]   k-strided (k = run), grouped by relation,
 //                                                        B rows picked through the run -> destination list
 //
@@ -109,20 +108,6 @@ struct EpiRowsBF16Staged {
     }
     __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
     __device__ __forceinline__ void store(int64_t, int32_t, float) const {}
-};
-struct EpiActF32 {            // activation, zero rows outside the sub-graph, optional second copy
-    static constexpr bool staged = false, packed = false, swapped = false;
-    float *out, *out2; int64_t rows; int32_t cols; int act; const uint8_t *row_active;
-    __device__ __forceinline__ void bind(int32_t) {}
-    __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
-    {
-        if (m >= rows || n >= cols) return;
-        float r = act == KGE_ACT_RELU ? fmaxf(v, 0.f) : v;
-        if (row_active && !row_active[m]) r = 0.f;
-        out[m * cols + n] = r;
-        if (out2) out2[m * cols + n] = r;
-    }
-    __device__ __forceinline__ void store8(int64_t, int32_t, const float4 &, const float4 &) const {}
 };
 struct EpiRelOuterAtomic {    // C[group] (d_in x d_out) accumulates the chunks of one relation
     static constexpr bool staged = false, packed = false, swapped = false;
@@ -544,19 +529,6 @@ __global__ void k_cvt_weights(const float *__restrict__ V, const float *__restri
     WbfT[(int64_t)n * d_in + k] = h;
 }
 
-// [V_1; ..; V_B; W0] (fp32, ((B+1) d_in x d_out)) -> WstT [d_out][(B+1) d_in], bf16
-__global__ void k_cvt_wstack_t(const float *__restrict__ V, const float *__restrict__ W0, int32_t d_in,
-                               int32_t d_out, int32_t B, uint16_t *__restrict__ WstT)
-{
-    const int64_t K = (int64_t)(B + 1) * d_in;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // = kk * d_out + c (coalesced reads)
-    if (idx >= K * d_out) return;
-    const int64_t kk = idx / d_out;
-    const int32_t c = (int32_t)(idx - kk * d_out);
-    const float v = kk < (int64_t)B * d_in ? V[idx] : W0[(kk - (int64_t)B * d_in) * d_out + c];
-    WstT[(int64_t)c * K + kk] = (uint16_t)(pack2(v, 0.f) & 0xffffu);
-}
-
 // Wrel (fp32 [G][rows][cols]) -> bf16 copies in both orientations: Wb[g][r][c] and WbT[g][c][r]
 __global__ __launch_bounds__(256) void k_cvt_group_mats(const float *__restrict__ W, int32_t rows, int32_t cols,
                                                         uint16_t *__restrict__ Wb, uint16_t *__restrict__ WbT)
@@ -707,30 +679,6 @@ int launch_input_grad_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out
     EpiRowMajorF32 ep{dH, N, d_in};
     KGE_PROF("input_grad", st);
     return launch_gemm<true, EpiRowMajorF32, TN, 64>(A, Bm, ep, nc, cdiv(nc, TK) * TK, tiles_m, tiles_n, 1, st);
-}
-
-int launch_cvt_wstack_bf16(const float *V, const float *W0, int32_t d_in, int32_t d_out, int32_t B, void *WstT,
-                           hipStream_t st)
-{
-    const int64_t n = (int64_t)(B + 1) * d_in * d_out;
-    KGE_PROF("cvt_weights", st);
-    k_cvt_wstack_t<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(V, W0, d_in, d_out, B, reinterpret_cast<uint16_t *>(WstT));
-    KGE_LAUNCH_CHECK();
-    return KGE_OK;
-}
-
-// out = act(X WstT^T)      X: bf16 [N][(B+1) d_in] = [Y | Hbf]; WstT: bf16 [d_out][(B+1) d_in]
-int launch_combine_bf16(const void *X, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const void *WstT,
-                        int act, const uint8_t *row_active, float *out, float *out2, hipStream_t st)
-{
-    if (N == 0) return KGE_OK;
-    const int32_t K = (B + 1) * d_in;
-    const int32_t tiles_m = (int32_t)cdiv(N, TM), tiles_n = (int32_t)cdiv(d_out, TN);
-    MatBF A{reinterpret_cast<const uint16_t *>(X), N, K, K, nullptr};
-    MatBF Bm{reinterpret_cast<const uint16_t *>(WstT), d_out, K, K, nullptr};
-    EpiActF32 ep{out, out2, N, d_out, act, row_active};
-    KGE_PROF("combine", st);
-    return launch_gemm<true, EpiActF32, TN, 64>(A, Bm, ep, K, cdiv(K, TK) * TK, tiles_m, tiles_n, 1, st);
 }
 
 // C[r] (d_in x d_out, fp32, zeroed here) = sum_{runs s of relation r} Zbf[s]^T Gbf[seg_dst[s]]

@@ -81,7 +81,7 @@ class TrainStep:
         torch = self.torch
         off, nbytes = kb.workspace_slice(self.part, self.layers, which, layer, self.msg_dtype)
         raw = self.workspace[off:off + nbytes]
-        bf = self.msg_dtype == kb.MSG_BF16 and which in (kb.WS_P, kb.WS_DP, kb.WS_Z, kb.WS_Y, kb.WS_U)
+        bf = self.msg_dtype == kb.MSG_BF16 and which in (kb.WS_P, kb.WS_DP, kb.WS_Z, kb.WS_U)
         t = raw.view(torch.bfloat16 if bf else torch.float32)
         if which == kb.WS_U:          # flat: the caller reshapes to [S, d_out] (u) or [S, d_in] (dz)
             return t

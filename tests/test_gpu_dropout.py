@@ -1,6 +1,6 @@
 """GPU parity of dropout on the layer inputs (training setting of Sec. 4: rate 0.2 on the large
 graphs): the keep decisions are bit-exact against the oracle's counter-based mask, and a whole step
-with dropout matches the oracle in all three evaluation orders, with and without the per-batch
+with dropout matches the oracle in both evaluation orders, with and without the per-batch
 sub-graph, in fp32 and with bf16 messages."""
 import sys
 
@@ -12,9 +12,8 @@ from gpu_util import (SEED, STEP, align_mask_decisions, assert_step_close, gpu_s
 
 pytestmark = pytest.mark.gpu
 TOL_VAL, TOL_GRAD, TOL_BF16 = 1e-4, 1e-3, 2e-2
-PROJ, AGG, RELW = 0, 1, 2
-ORDERS = [pytest.param(PROJ, id="project_first"), pytest.param(AGG, id="aggregate_first"),
-          pytest.param(RELW, id="relation_weights")]
+PROJ, RELW = 0, 2
+ORDERS = [pytest.param(PROJ, id="project_first"), pytest.param(RELW, id="relation_weights")]
 
 
 def say(*a):

@@ -288,6 +288,9 @@ def test_argument_errors(kb):
     bad[1]["V"] = torch.zeros((4, 16, 16), device=dev)       # d_in mismatch with layer 0's d_out
     with pytest.raises(kb.KgeError) as e:
         kb.workspace_bytes(part, bad)
+    gone = [dict(layers[0], order=1), dict(layers[1], order=1)]      # the value of a removed evaluation order
+    with pytest.raises(kb.KgeError, match="bad order"):
+        kb.workspace_bytes(part, gone)
     odd = [dict(V=torch.zeros((2, 6, 6), device=dev), a=layers[0]["a"][:, :2].contiguous(),
                 W0=torch.zeros((6, 6), device=dev), act=0)]
     with pytest.raises(kb.KgeError):
@@ -309,7 +312,7 @@ def test_config0_tiny_whole_step(kb, orc):
 @pytest.fixture(scope="module")
 def config1_oracle(orc):
     """configs[1] (the whole 14,541-entity graph as one partition, 30,000 positives x 10 negatives):
-    the oracle's whole step, computed once for the three evaluation orders."""
+    the oracle's whole step, computed once for both evaluation orders."""
     spec = synth.WORKLOADS[1]
     head, rel, tail = synth.make_triples(spec)
     op = orc.build_partition(head, rel, tail, spec.n_entities, spec.n_relations, spec.n_parts, spec.part_id,
@@ -321,7 +324,7 @@ def config1_oracle(orc):
     return spec, (head, rel, tail), params, pos, op, res
 
 
-@pytest.mark.parametrize("order", [0, 1, 2], ids=["project_first", "aggregate_first", "relation_weights"])
+@pytest.mark.parametrize("order", [0, 2], ids=["project_first", "relation_weights"])
 def test_config1_mid_whole_graph_step(kb, orc, config1_oracle, order):
     spec, (head, rel, tail), params, pos, op, res = config1_oracle
     say("config 1", spec.name, "order", order)

@@ -1,8 +1,7 @@
-"""GPU parity of the two orders of Eq. 1-2 that sum neighbours before they apply weights -
-aggregate-first (run means z, per-basis sums y, one contraction with [V_1; ..; V_B; W_0]) and
-relation-weight (run means z, W_r = sum_b a_rb V_b written out, one product z W_r per run) -
-against the same oracle as the project-first order: the orders are algebraically identical, so
-every output is held to the same tolerances."""
+"""GPU parity of the relation-weight order of Eq. 1-2, the library's product path (run means z,
+W_r = sum_b a_rb V_b written out, one product z W_r per run), against the same oracle as the
+project-first order: the orders are algebraically identical, so every output is held to the same
+tolerances."""
 import sys
 
 import numpy as np
@@ -14,8 +13,8 @@ from gpu_util import (SEED, STEP, align_mask_decisions, assert_partition_equal, 
 
 pytestmark = pytest.mark.gpu
 TOL_VAL, TOL_GRAD = 1e-4, 1e-3
-AGG, RELW = 1, 2
-ORDERS = [pytest.param(AGG, id="aggregate_first"), pytest.param(RELW, id="relation_weights")]
+RELW = 2
+ORDERS = [pytest.param(RELW, id="relation_weights")]
 
 
 def say(*a):
@@ -76,7 +75,7 @@ SHAPES = [
 
 @pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("shape", SHAPES, ids=[s[0] for s in SHAPES])
-def test_step_aggregate_first(kb, orc, shape, order):
+def test_step_relation_weights(kb, orc, shape, order):
     name, n, R, m, d, B, n_pos, n_neg, mode, P, acts = shape
     say("step, order", order, shape)
     spec = synth.scaled(synth.WORKLOADS[0], name=name, seed=17, n_entities=n, n_relations=R, n_triples=m,
@@ -89,14 +88,14 @@ def test_step_aggregate_first(kb, orc, shape, order):
     assert_step_close(ts, res, TOL_VAL, TOL_GRAD)
 
 
-def test_intermediates_z_and_y(kb, orc):
-    """z (run means) and y (per-basis sums) of the LAST layer against their definitions in fp64."""
-    say("z / y")
+def test_intermediate_run_means(kb, orc):
+    """z (run means) of the LAST layer against their definition in fp64."""
+    say("z")
     n, R, m, d, B = 600, 6, 7000, 64, 5
     spec = synth.scaled(synth.WORKLOADS[0], name="zy", seed=3, n_entities=n, n_relations=R, n_triples=m,
                         d=d, n_bases=B, n_pos=50, n_neg=1, feature_std=0.5)
     head, rel, tail = random_graph(77, n, R, m)
-    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=AGG)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=RELW)
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
     H1 = res["Hs"][1]                       # input of the last layer
     lens = np.diff(op["seg_ptr"])
@@ -105,14 +104,10 @@ def test_intermediates_z_and_y(kb, orc):
     np.add.at(Z, run_of_edge, H1[op["col_src"]])
     Z /= lens[:, None]
     assert rel_err(ts.view(kb.WS_Z, 1).cpu().numpy(), Z) <= TOL_VAL
-    a = np.asarray(params["a"][1], np.float64)
-    Y = np.zeros((op["n_vert"], B, d))
-    np.add.at(Y, op["seg_dst"], a[op["seg_rel"]][:, :, None] * Z[:, None, :])
-    assert rel_err(ts.view(kb.WS_Y, 1).cpu().numpy().reshape(-1, B, d), Y) <= TOL_VAL
 
 
 @pytest.mark.parametrize("order", ORDERS)
-def test_hub_rows_aggregate_first(kb, orc, order):
+def test_hub_rows_relation_weights(kb, orc, order):
     """A run of 600 edges (split into units), a destination and a source with > 256 edges."""
     say("hub, order", order)
     n, R = 700, 2
@@ -146,7 +141,7 @@ def test_many_runs_per_destination(kb, orc, order):
 
 
 @pytest.mark.parametrize("order", ORDERS)
-def test_aggregate_first_with_compute_graph(kb, orc, order):
+def test_relation_weights_with_compute_graph(kb, orc, order):
     say("sub-graph, order", order)
     n, R, m = 4000, 5, 14000
     spec = synth.scaled(synth.WORKLOADS[0], name="aggcone", seed=23, n_entities=n, n_relations=R, n_triples=m,
@@ -167,10 +162,10 @@ TOL_BF16 = 2e-2
 @pytest.mark.parametrize("acts,n,m,d,B,cone", [([0, 0], 600, 6000, 64, 8, False), ([1, 0], 6000, 90000, 64, 8, False),
                                                ([0, 0], 900, 9000, 96, 40, False), ([1, 0], 5000, 60000, 128, 6, True)],
                          ids=["identity", "relu", "identity_B40_d96", "relu_subgraph"])
-def test_bf16_aggregate_first(kb, orc, acts, n, m, d, B, cone, order):
-    """bf16 pipelines of the two orders that sum first (inputs, run means, per-basis sums or W_r and the
-    per-run products, and the weights are bf16 operands; sums fp32): every output against the exact
-    oracle at 2e-2, ReLU decisions inside the rounding band taken as the kernel took them."""
+def test_bf16_relation_weights(kb, orc, acts, n, m, d, B, cone, order):
+    """The bf16 pipeline of the relation-weight order (inputs, run means, W_r, the per-run products and W_0 are
+    bf16 operands; sums fp32): every output against the exact oracle at 2e-2, ReLU decisions inside the
+    rounding band taken as the kernel took them."""
     say("bf16, order", order, acts, n, m, d, B, cone)
     spec = synth.scaled(synth.WORKLOADS[4], name="bf16-agg", seed=3, n_entities=n, n_relations=20,
                         n_triples=m, d=d, n_bases=B, n_pos=24 if cone else 256, n_neg=4, n_parts=2, part_id=0, acts=acts)
@@ -186,15 +181,16 @@ def test_bf16_aggregate_first(kb, orc, acts, n, m, d, B, cone, order):
     say("errs vs the exact oracle", errs)
 
 
-def test_bf16_aggregate_first_intermediates(kb, orc):
+def test_bf16_run_means(kb, orc):
     """Run means z of the first layer (stored in bf16) against the exact means: each element within two
-    bf16 roundings (of the input, of the mean) of mean|h| over its run, and 2e-2 as a tensor."""
+    bf16 roundings (of the input, of the mean) of mean|h| over its run, and 2e-2 as a tensor.  Runs of one edge
+    keep no stored mean in this pipeline (the products read the source's row in place)."""
     say("bf16 z")
     import torch
     spec = synth.scaled(synth.WORKLOADS[4], name="bf16-z", seed=4, n_entities=800, n_relations=10, n_triples=9000,
                         d=64, n_bases=4, n_pos=64, n_neg=2, n_parts=1, part_id=0, acts=[1, 0])
     head, rel, tail = synth.make_triples(spec)
-    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=AGG)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=RELW)
     op = orc.build_partition(head, rel, tail, spec.n_entities, spec.n_relations, 1, 0, 2, spec.neg_domain)
     H0 = np.asarray(params["H0"], np.float64)
     lens = np.diff(op["seg_ptr"]); run = np.repeat(np.arange(op["n_seg"]), lens)
@@ -202,8 +198,10 @@ def test_bf16_aggregate_first_intermediates(kb, orc):
     Zabs = np.zeros_like(Z); np.add.at(Zabs, run, np.abs(H0[op["col_src"]]))
     Z /= lens[:, None]; Zabs /= lens[:, None]
     got = ts.view(kb.WS_Z, 0).to(torch.float64).cpu().numpy()
-    assert np.all(np.abs(got - Z) <= 2.0 * 2.0 ** -8 * Zabs + 1e-30)
-    assert rel_err(got, Z) <= TOL_BF16
+    multi = lens > 1
+    assert multi.sum() > 100
+    assert np.all(np.abs(got[multi] - Z[multi]) <= 2.0 * 2.0 ** -8 * Zabs[multi] + 1e-30)
+    assert rel_err(got[multi], Z[multi]) <= TOL_BF16
 
 
 @pytest.mark.parametrize("order", ORDERS)
@@ -244,7 +242,6 @@ def test_feature_layer_with_different_widths(kb, orc, order, dims, bf16):
                         acts=[0, 0] if bf16 else [1, 0], feature_std=0.5)
     head, rel, tail = random_graph(41, n, R, m)
     too_wide = ("d_out <= 256" if order == 0 and max(dims[1:]) > 256 else
-                "d_in <= 256 and d_out <= 256" if order == AGG and max(dims) > 256 else
                 "d_in <= 256" if order == RELW and not bf16 and max(dims[:2]) > 256 else None)
     if too_wide:
         # wider than the order's kernels take (see the header): a clean error before anything runs, not a fault
