@@ -225,10 +225,10 @@ def test_bf16_many_small_relations(kb, orc, order, d):
 
 @pytest.mark.parametrize("order", [pytest.param(0, id="project_first")] + ORDERS)
 @pytest.mark.parametrize("dims,bf16", [((128, 32, 32), False), ((48, 96, 24), False), ((128, 32, 32), True),
-                                       ((64, 128, 64), True), ((200, 40, 72), True), ((8, 248, 16), True),
+                                       ((64, 128, 64), True), ((192, 64, 264), True), ((200, 40, 72), True), ((8, 248, 16), True),
                                        ((512, 256, 256), False), ((256, 256, 256), False), ((512, 320, 512), True),
                                        ((256, 256, 512), True)],
-                         ids=["f32_128_32_32", "f32_48_96_24", "bf16_128_32_32", "bf16_64_128_64",
+                         ids=["f32_128_32_32", "f32_48_96_24", "bf16_128_32_32", "bf16_64_128_64", "bf16_192_64_264_three_chunks_ragged_columns",
                               "bf16_200_40_72_ragged_tiles", "bf16_8_248_16_ragged_tiles",
                               "f32_512_256_256_widest", "f32_256_256_256_widest", "bf16_512_320_512_widest",
                               "bf16_256_256_512_widest"])
