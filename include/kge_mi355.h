@@ -166,6 +166,14 @@ int kge_build_partition(const int32_t *head, const int32_t *rel, const int32_t *
 
 int kge_partition_info(const kge_partition *p, kge_part_info *out);
 
+/* Ids inside device arrays (core-edge indices in pos_core_idx, entities in neg_ent) cannot be checked by the
+ * host without a synchronisation, so the kernels of kge_compute_graph and kge_distmult_score_loss check them:
+ * an id outside [0, n_core) / [0, N) is counted in the partition and skipped or replaced by 0 - it never becomes
+ * an address - and the outputs of that call are meaningless.  This call (it synchronises the device) writes to
+ * *host_count how many such ids the partition's calls have met since it was built; a caller that cannot vouch
+ * for its ids reads it once per epoch and treats a non-zero count as KGE_ERANGE. */
+int kge_partition_bad_ids(const kge_partition *p, int64_t *host_count);
+
 /* Copy one array to HOST memory `host_dst` of `bytes` bytes (must equal 4 * its length).
  * Synchronous. */
 int kge_partition_export(const kge_partition *p, int32_t which, void *host_dst, int64_t bytes);
@@ -189,7 +197,7 @@ size_t kge_workspace_bytes(const kge_partition *p, const kge_layer *layers, int3
  * kge_cgraph_create allocates the flags for a partition and a layer count (once per trainer;
  * synchronous); kge_cgraph_destroy frees them.  kge_compute_graph fills them for one batch:
  * asynchronous on `stream`, no allocation, no host synchronisation.
- *   pos_core_idx : device int32 [n_pos], each in [0, n_core)
+ *   pos_core_idx : device int32 [n_pos], each in [0, n_core) (checked on the device, see kge_partition_bad_ids)
  *   neg_ent      : device int32 [n_neg_entries] local vertex ids (as written by
  *                  kge_sample_negatives, n_neg_entries = n_pos * n_neg), or NULL with 0
  * kge_cgraph_export (synchronises the device) copies the flags to HOST uint8 [L][N] and/or, per
@@ -283,20 +291,17 @@ int kge_sample_negatives(const kge_partition *p, const int32_t *pos_core_idx, in
  *            corrupting entity; two per positive, to its head and tail) are sorted by entity with a stable
  *            radix sort inside the call, the triples are scored, and one wavefront per entity adds up its rows
  *            in the order of the batch: every row of dH is written once and the result repeats bit for bit.
- *            H, M and dH must then be 16-byte aligned.  An id outside [0, n_core) / [0, N) never becomes an
- *            address in this form: it is replaced by 0 and counted (kge_score_index_bad_ids; outputs of such
- *            a call are meaningless).
+ *            H, M and dH must then be 16-byte aligned.
+ *   In both forms an id outside [0, n_core) / [0, N) is replaced by 0 and counted (kge_partition_bad_ids).
  *   dM and the loss are accumulated with fp32 atomics in both forms.
  *
  * kge_score_index_create allocates the scratch for batches of at most max_pos positives with at most max_neg
  * negatives each and embedding width d (about (n_neg + 2) x 36 bytes + 8 d bytes per positive, plus 4 N bytes);
- * once per trainer, synchronous; free with kge_score_index_destroy.  kge_score_index_bad_ids (synchronises)
- * writes to *host_count how many out-of-range ids the calls with this index have seen so far.
+ * once per trainer, synchronous; free with kge_score_index_destroy.
  */
 int kge_score_index_create(const kge_partition *p, int64_t max_pos, int32_t max_neg, int32_t d,
                            kge_score_index **out);
 void kge_score_index_destroy(kge_score_index *index);
-int kge_score_index_bad_ids(const kge_score_index *index, int64_t *host_count);
 int kge_distmult_score_loss(const kge_partition *p, kge_score_index *index, const float *H, const float *M,
                             int32_t d, const int32_t *pos_core_idx, int64_t n_pos, const int32_t *neg_ent,
                             const uint8_t *neg_side, int32_t n_neg, float *scores, float *loss,

@@ -24,7 +24,7 @@ EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_optimizer_step_rows", "kge_eval_filter_create", "kge_eval_filter_destroy",
             "kge_eval_workspace_bytes", "kge_eval_rank_all", "kge_eval_rank_candidates", "kge_eval_metrics",
             "kge_eval_debug_scores", "kge_eval_rank_all_static", "kge_cgraph_input_rows", "kge_score_index_create", "kge_score_index_destroy",
-            "kge_score_index_bad_ids"]
+            "kge_partition_bad_ids"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
 ORDER_PROJECT_FIRST, ORDER_RELATION_WEIGHTS = 0, 2
@@ -132,6 +132,12 @@ class Partition:
 
     def export(self, name: str) -> np.ndarray:
         return partition_export(self, name)
+
+    def bad_ids(self) -> int:
+        """Ids outside the partition that the per-step kernels have met (and not used) so far; synchronises."""
+        n = C.c_int64()
+        _check(load().kge_partition_bad_ids(self._h, C.byref(n)))
+        return int(n.value)
 
     def destroy(self):
         if self._h is not None and self._h.value:
@@ -296,11 +302,6 @@ class ScoreIndex:
     @property
     def handle(self):
         return self._h
-
-    def bad_ids(self) -> int:
-        n = C.c_int64()
-        _check(load().kge_score_index_bad_ids(self._h, C.byref(n)))
-        return int(n.value)
 
     def destroy(self):
         if self._h is not None and self._h.value:

@@ -23,15 +23,19 @@ namespace {
 __global__ void k_cg_mark_batch(const int32_t *__restrict__ core_h, const int32_t *__restrict__ core_t,
                                 const int32_t *__restrict__ pos, int64_t n_pos,
                                 const int32_t *__restrict__ neg_ent, int64_t n_neg_entries,
+                                uint32_t n_vert, uint32_t n_core, uint32_t *__restrict__ bad,
                                 uint8_t *__restrict__ top)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n_pos) {
-        const int32_t c = pos[i];
+        const uint32_t c = (uint32_t)pos[i];
+        if (c >= n_core) { atomicAdd(bad, 1u); return; }      // outside the partition: counted, never an address
         top[core_h[c]] = 1;
         top[core_t[c]] = 1;
     } else if (i - n_pos < n_neg_entries) {
-        top[neg_ent[i - n_pos]] = 1;
+        const uint32_t e = (uint32_t)neg_ent[i - n_pos];
+        if (e >= n_vert) { atomicAdd(bad, 1u); return; }
+        top[e] = 1;
     }
 }
 
@@ -143,7 +147,8 @@ extern "C" int kge_compute_graph(const kge_partition *p, kge_cgraph *cg, const i
     const int64_t n_mark = n_pos + n_neg_entries;
     if (n_mark > 0) {
         k_cg_mark_batch<<<(unsigned)cdiv(n_mark, 256), 256, 0, st>>>(p->core_h, p->core_t, pos_core_idx, n_pos,
-                                                                    neg_ent, n_neg_entries,
+                                                                    neg_ent, n_neg_entries, (uint32_t)p->n_vert,
+                                                                    (uint32_t)p->n_core, p->bad_ids,
                                                                     cg->active + (size_t)(L - 1) * cg->stride);
         KGE_LAUNCH_CHECK();
     }

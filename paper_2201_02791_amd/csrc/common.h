@@ -75,6 +75,9 @@ struct kge_partition {
     // are read in place); allocated together with seg_zrow
     int64_t n_mrun;
     int32_t *mrun;
+    // [1] how many ids outside the partition (core-edge indices, entities) the per-step kernels have met so far:
+    // such an id is counted and replaced or skipped, never used as an address (kge_partition_bad_ids)
+    uint32_t *bad_ids;
 };
 #define KGE_REL_CHUNK 2048
 #define KGE_REL_TILE 128

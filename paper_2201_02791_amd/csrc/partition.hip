@@ -589,7 +589,7 @@ extern "C" void kge_partition_destroy(kge_partition *p)
                     p->hv_seg.hv_row, p->hv_seg.hv_unit_ptr, p->hv_seg.unit_hv,
                     p->dr_ptr, p->dr_seg, p->dr_rel, p->hv_dr.hv_row, p->hv_dr.hv_unit_ptr, p->hv_dr.unit_hv,
                     p->relc_rel, p->relc_beg, p->relc_end, p->sm_seg, p->relt_rel, p->relt_beg, p->relt_end,
-                    p->seg_zrow, p->mrun};
+                    p->seg_zrow, p->mrun, p->bad_ids};
     for (void *q : arrs) if (q) (void)hipFree(q);
     delete p;
 }
@@ -617,7 +617,24 @@ extern "C" int kge_build_partition(const int32_t *head, const int32_t *rel, cons
     int rc = build_impl(head, rel, tail, n_triples, n_entities, n_relations, n_parts, part_id,
                         n_hops, neg_domain, p);
     if (rc != KGE_OK) { kge_partition_destroy(p); return rc; }
+    hipError_t e = hipMalloc((void **)&p->bad_ids, sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMemset(p->bad_ids, 0, sizeof(uint32_t));
+    if (e != hipSuccess) {
+        kge_set_error("allocating the partition's id counter failed: %s", hipGetErrorString(e));
+        kge_partition_destroy(p);
+        return KGE_ENOMEM;
+    }
     *out = p;
+    return KGE_OK;
+}
+
+extern "C" int kge_partition_bad_ids(const kge_partition *p, int64_t *host_count)
+{
+    KGE_REQUIRE(p && host_count, KGE_EINVAL, "NULL argument");
+    uint32_t n = 0;
+    KGE_HIP(hipDeviceSynchronize());
+    KGE_HIP(hipMemcpy(&n, p->bad_ids, sizeof n, hipMemcpyDeviceToHost));
+    *host_count = (int64_t)n;
     return KGE_OK;
 }
 

@@ -23,7 +23,6 @@ struct kge_score_index {
                                    // -1 - (row of rows[]) for a positive's own end; y = relation; z = bits of delta
     uint32_t *pkeys[2], *pvals[2]; // [max_pos] the batch's positives sorted by relation (ping-pong buffers)
     float *rows;                   // [2 max_pos][d] per positive q: the summed rows for its head (2q) and its tail (2q+1)
-    uint32_t *bad;                 // [1] ids outside the partition seen so far (replaced, never used as addresses)
 };
 
 namespace {
@@ -91,6 +90,7 @@ __global__ __launch_bounds__(64 * DM_WAVES) void k_distmult(
     const int32_t *__restrict__ core_h, const int32_t *__restrict__ core_r,
     const int32_t *__restrict__ core_t, const int32_t *__restrict__ pos, int64_t n_pos, int32_t per_wave,
     const int32_t *__restrict__ neg_ent, const uint8_t *__restrict__ neg_side, int32_t n_neg,
+    uint32_t n_vert, uint32_t n_core, uint32_t *__restrict__ bad,
     float inv_T, float *__restrict__ scores, float *__restrict__ loss, float *__restrict__ dH,
     float *__restrict__ dM)
 {
@@ -109,7 +109,11 @@ __global__ __launch_bounds__(64 * DM_WAVES) void k_distmult(
     float lsum = 0.f;
 
     for (int64_t q = q_beg; q < q_end; ++q) {
-        const int32_t c = pos[q];
+        uint32_t c = (uint32_t)pos[q];
+        if (c >= n_core) {                // an index outside the partition never becomes an address: counted, replaced
+            c = 0;
+            if (lane == 0) atomicAdd(bad, 1u);
+        }
         const int32_t s = core_h[c], r = core_r[c], t = core_t[c];
         if (r != r_cur) {                 // uniform: flush the relation gradient of the finished run
             if (r_cur >= 0) {
@@ -154,6 +158,10 @@ __global__ __launch_bounds__(64 * DM_WAVES) void k_distmult(
             for (int z = 0; z < 4; ++z) {
                 const bool ok = k0 + z < n_neg;
                 ent[z] = ok ? neg_ent[q * n_neg + k0 + z] : 0;
+                if ((uint32_t)ent[z] >= n_vert) {
+                    ent[z] = 0;
+                    if (lane == 0) atomicAdd(bad, 1u);
+                }
                 side[z] = ok ? (int)neg_side[q * n_neg + k0 + z] : 0;
 #pragma unroll
                 for (int u = 0; u < NCH; ++u) {
@@ -625,8 +633,6 @@ extern "C" int kge_score_index_create(const kge_partition *p, int64_t max_pos, i
     take((void **)&x->recs, 16 * (size_t)max_occ);
     for (int k = 0; k < 2; ++k) { take((void **)&x->pkeys[k], 4 * (size_t)max_pos); take((void **)&x->pvals[k], 4 * (size_t)max_pos); }
     take((void **)&x->rows, 4 * (size_t)2 * max_pos * d);
-    take((void **)&x->bad, 4);
-    if (e == hipSuccess) e = hipMemset(x->bad, 0, 4);
     if (e != hipSuccess) {
         kge_set_error("allocating the scoring index failed: %s", hipGetErrorString(e));
         kge_score_index_destroy(x);
@@ -640,19 +646,9 @@ extern "C" void kge_score_index_destroy(kge_score_index *x)
 {
     if (!x) return;
     void *all[] = {x->keys[0], x->keys[1], x->vals[0], x->vals[1], x->sort_ws, x->ent_ptr, x->slot_of, x->recs,
-                   x->pkeys[0], x->pkeys[1], x->pvals[0], x->pvals[1], x->rows, x->bad};
+                   x->pkeys[0], x->pkeys[1], x->pvals[0], x->pvals[1], x->rows};
     for (void *q : all) if (q) (void)hipFree(q);
     delete x;
-}
-
-extern "C" int kge_score_index_bad_ids(const kge_score_index *x, int64_t *host_count)
-{
-    KGE_REQUIRE(x && host_count, KGE_EINVAL, "NULL argument");
-    uint32_t n = 0;
-    KGE_HIP(hipDeviceSynchronize());
-    KGE_HIP(hipMemcpy(&n, x->bad, 4, hipMemcpyDeviceToHost));
-    *host_count = (int64_t)n;
-    return KGE_OK;
 }
 
 // The atomic-free form: sort the batch's occurrences by entity (stable, so ties keep occurrence order), score
@@ -680,7 +676,7 @@ int launch_distmult_indexed(const kge_partition *p, kge_score_index *x, const fl
     {
         KGE_PROF("score_index", st);
         k_score_keys<<<(unsigned)cdiv(n_occ, 256), 256, 0, st>>>(p->core_h, p->core_t, pos, n_pos, neg_ent, n_neg,
-                                                                (uint32_t)p->n_vert, (uint32_t)p->n_core, keys, vals, x->bad);
+                                                                (uint32_t)p->n_vert, (uint32_t)p->n_core, keys, vals, p->bad_ids);
         KGE_LAUNCH_CHECK();
         int bits = 1;
         while (bits < 32 && ((int64_t)1 << bits) < p->n_vert) ++bits;
@@ -747,7 +743,8 @@ int launch_distmult(const kge_partition *p, const float *H, const float *M, int3
 #define DM_CALL(NCHV)                                                                                \
     k_distmult<NCHV><<<grid, 64 * DM_WAVES, 0, st>>>(H, M, d, p->core_h, p->core_r, p->core_t, pos,  \
                                                     n_pos, (int32_t)per_wave, neg_ent, neg_side,     \
-                                                    n_neg, inv_T, scores, loss, dH, dM)
+                                                    n_neg, (uint32_t)p->n_vert, (uint32_t)p->n_core, \
+                                                    p->bad_ids, inv_T, scores, loss, dH, dM)
     if (d <= 64) DM_CALL(1);
     else if (d <= 128) DM_CALL(2);
     else if (d <= 256) DM_CALL(4);

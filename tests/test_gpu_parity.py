@@ -194,8 +194,8 @@ def test_scoring_call_alone(kb, orc, d, n_pos, n_neg, mode, indexed):
     untouched = np.abs(want["dH"]).max(axis=1) == 0
     assert untouched.any() or n_pos * (2 + n_neg) > 2000
     assert not dH.cpu().numpy()[untouched].any()
+    assert gp.bad_ids() == 0
     if indexed:
-        assert idx.bad_ids() == 0
         first = dH.clone()
         dH.fill_(3.0)
         kb.distmult_score_loss(*args, index=idx)
@@ -203,11 +203,13 @@ def test_scoring_call_alone(kb, orc, d, n_pos, n_neg, mode, indexed):
         assert torch.equal(first, dH), "the atomic-free form must repeat bit for bit"
 
 
-def test_scoring_index_counts_ids_outside_the_partition(kb, orc):
-    """With the index no id becomes an address unchecked: an entity or core-edge index outside the partition is
-    replaced and counted (the call's outputs are then meaningless, but nothing is read or written out of bounds)."""
+@pytest.mark.parametrize("indexed", [False, True], ids=["atomic", "indexed"])
+def test_ids_outside_the_partition_are_counted_and_never_addresses(kb, orc, indexed):
+    """No id read from a device array becomes an address unchecked, in the sub-graph call or in either form of
+    the scoring call: an entity or core-edge index outside the partition is skipped or replaced, and counted in
+    the partition (the outputs of such a call are meaningless, but nothing is read or written out of bounds)."""
     import torch
-    say("scoring index, ids out of range")
+    say("ids out of range", indexed)
     n, R, m, d, n_pos, n_neg = 300, 3, 2000, 32, 40, 4
     head, rel, tail = random_graph(5, n, R, m)
     gp = kb.build_partition(head, rel, tail, n, R, 1, 0, 2, 0)
@@ -216,16 +218,29 @@ def test_scoring_index_counts_ids_outside_the_partition(kb, orc):
     H = t(rng.normal(size=(gp.n_vert, d)).astype(np.float32)); M = t(rng.normal(size=(R, d)).astype(np.float32))
     pos = rng.permutation(gp.n_core)[:n_pos].astype(np.int32)
     ne = rng.integers(0, gp.n_vert, (n_pos, n_neg)).astype(np.int32); ns = np.zeros((n_pos, n_neg), np.uint8)
+    good_pos, good_ne = pos.copy(), ne.copy()
     pos[3] = gp.n_core + 5; pos[7] = -1                 # two bad core-edge indices
     ne[0, 0] = gp.n_vert; ne[9, 2] = -4; ne[11, 3] = 2 ** 31 - 1      # three bad entities
-    idx = kb.ScoreIndex(gp, n_pos, n_neg, d)
+    idx = kb.ScoreIndex(gp, n_pos, n_neg, d) if indexed else None
     dH = torch.empty((gp.n_vert, d), device="cuda"); dM = torch.empty((R, d), device="cuda")
     loss = torch.empty(1, device="cuda")
+    assert gp.bad_ids() == 0
     kb.distmult_score_loss(gp, H, M, t(pos), t(ne), t(ns), n_neg, None, loss, dH, dM, index=idx)
-    torch.cuda.synchronize()
-    assert idx.bad_ids() == 5
-    with pytest.raises(kb.KgeError):                     # a batch larger than the index was made for
-        kb.distmult_score_loss(gp, H, M, t(np.zeros(n_pos + 1, np.int32)), None, None, 0, None, loss, dH, dM, index=idx)
+    assert gp.bad_ids() == 5
+    # the sub-graph call skips the same five and flags exactly what the good ids reach
+    cg = kb.ComputeGraph(gp, 2)
+    kb.compute_graph(gp, cg, t(pos), t(ne))
+    assert gp.bad_ids() == 10
+    got = cg.export()
+    keep = np.ones(n_pos, bool); keep[[3, 7]] = False
+    kb.compute_graph(gp, cg, t(good_pos[keep]), t(np.where(ne == good_ne, ne, good_ne[1, 1])))
+    assert gp.bad_ids() == 10
+    want = cg.export()
+    np.testing.assert_array_equal(got[0], want[0])
+    np.testing.assert_array_equal(got[1], want[1])
+    if indexed:
+        with pytest.raises(kb.KgeError):                 # a batch larger than the index was made for
+            kb.distmult_score_loss(gp, H, M, t(np.zeros(n_pos + 1, np.int32)), None, None, 0, None, loss, dH, dM, index=idx)
 
 
 def test_step_with_atomic_scoring(kb, orc):
