@@ -67,6 +67,9 @@ struct kge_partition {
     // and into row tiles of at most KGE_REL_TILE runs
     int32_t n_relt;
     int32_t *relt_rel, *relt_beg, *relt_end;
+    // and into ranges of at most KGE_REL_RANGE runs (what one block of the bf16 per-run products takes)
+    int32_t n_relr;
+    int32_t *relr_rel, *relr_beg, *relr_end;
     // where the mean of run s can be read when the layer input X [N][d] and the run means Z [S][d] are one
     // matrix [X; Z]: a run of a single edge has its source's row of X as its mean (row col_src), any other
     // run row N + s.  NULL if N + S does not fit 31 bits.
@@ -81,6 +84,7 @@ struct kge_partition {
 };
 #define KGE_REL_CHUNK 2048
 #define KGE_REL_TILE 128
+#define KGE_REL_RANGE 4096
 
 // Optional per-kernel timing with HIP events on the launch stream (kge_profile_enable).
 struct KgeProfScope {
@@ -181,6 +185,9 @@ int launch_cvt_relation_weights_bf16(const float *Wrel, int32_t R2, int32_t d_in
                                      hipStream_t st);
 // the same two products from bf16 operands, bf16 results; Gbf rows are ldg elements apart.  zrow (may be
 // NULL): Zbf is then the matrix [X; Z] and run s reads its row zrow[s]
+bool rel_rows_bf16_supported(int32_t K, int32_t N);
+int launch_rel_rows_bf16(const kge_partition *p, const void *A, int64_t lda, const int32_t *aidx, const void *Wk,
+                         int32_t K, int32_t N, void *out, hipStream_t st);
 int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, const int32_t *zrow, const void *WbT,
                                        int32_t d_in, int32_t d_out, void *U, hipStream_t st);
 int launch_apply_relation_weights_t_bf16(const kge_partition *p, const void *Gbf, int64_t ldg, const void *Wb,

@@ -712,8 +712,10 @@ int launch_cvt_relation_weights_bf16(const float *Wrel, int32_t R2, int32_t d_in
     return KGE_OK;
 }
 
-// Row tiles of the run list that one block of the per-run products takes in turn (the next tile's first loads
-// overlap the current tile's stores).  Measured at 25 M runs, d = 256: 1 -> 6.4 ms, 2 -> 6.3, 4 and 8 -> 6.2.
+// The per-run products take the kernel of rel_rows_bf16.hip when it supports the layer's widths (64, 128 or 256
+// in, a multiple of 32 up to 256 out); the rest runs here as a grouped GEMM over row tiles of the run list.
+// Row tiles that one block takes in turn (the next tile's first loads overlap the current tile's stores);
+// measured at 25 M runs, d = 256: 1 -> 6.4 ms, 2 -> 6.3, 4 and 8 -> 6.2 (the other kernel: 5.3).
 constexpr int32_t ROW_TILES_PER_BLOCK = 4;
 
 // U[s] = Zbf[s] Wrel[rel(s)]   bf16 in, bf16 out; WbT: bf16 [2R][d_out][d_in]
@@ -726,6 +728,8 @@ int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, 
     MatBF Bm{reinterpret_cast<const uint16_t *>(WbT), d_out, d_in, d_in, nullptr};
     EpiRowsBF16Staged ep{reinterpret_cast<uint16_t *>(U), p->n_seg, d_out};
     KGE_PROF("apply_rel", st);
+    if (rel_rows_bf16_supported(d_in, d_out))
+        return launch_rel_rows_bf16(p, Zbf, d_in, zrow, WbT, d_in, d_out, U, st);
     if (tiles_n == 1 && d_in % 64 == 0 && d_out % 32 == 0)   // several row tiles per block, the next one's first loads under the current one's stores
         return launch_gemm<true, EpiRowsBF16Staged, TN, 64, true>(A, Bm, ep, d_in, cdiv(d_in, TK) * TK, p->n_relt, tiles_n, 1,
                                                                   st, nullptr, nullptr, nullptr, p->relt_rel, p->relt_beg,
@@ -745,6 +749,8 @@ int launch_apply_relation_weights_t_bf16(const kge_partition *p, const void *Gbf
     MatBF Bm{reinterpret_cast<const uint16_t *>(Wb), d_in, d_out, d_out, nullptr};
     EpiRowsBF16Staged ep{reinterpret_cast<uint16_t *>(dZ), p->n_seg, d_in};
     KGE_PROF("apply_rel_t", st);
+    if (rel_rows_bf16_supported(d_out, d_in))
+        return launch_rel_rows_bf16(p, Gbf, ldg, p->seg_dst, Wb, d_out, d_in, dZ, st);
     if (tiles_n == 1 && d_out % 64 == 0 && d_in % 64 == 0)   // two tiles in flight: the contraction must be whole pairs of them
         return launch_gemm<true, EpiRowsBF16Staged, TN, 64, true>(A, Bm, ep, d_out, cdiv(d_out, TK) * TK, p->n_relt, tiles_n, 1,
                                                                   st, nullptr, nullptr, nullptr, p->relt_rel, p->relt_beg,

@@ -540,6 +540,22 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
                 t_rel.push_back((int32_t)r); t_beg.push_back(b);
                 t_end.push_back(b + KGE_REL_TILE < h_rel_ptr[r + 1] ? b + KGE_REL_TILE : h_rel_ptr[r + 1]);
             }
+        {
+            std::vector<int32_t> g_rel, g_beg, g_end;
+            const int32_t RANGE = KGE_REL_RANGE;
+            for (int64_t r = 0; r < R2; ++r)
+                for (int32_t b = h_rel_ptr[r]; b < h_rel_ptr[r + 1]; b += RANGE) {
+                    g_rel.push_back((int32_t)r); g_beg.push_back(b);
+                    g_end.push_back(b + RANGE < h_rel_ptr[r + 1] ? b + RANGE : h_rel_ptr[r + 1]);
+                }
+            p->n_relr = (int32_t)g_rel.size();
+            TRY(palloc(&p->relr_rel, g_rel.size())); TRY(palloc(&p->relr_beg, g_rel.size())); TRY(palloc(&p->relr_end, g_rel.size()));
+            if (!g_rel.empty()) {
+                KGE_HIP(hipMemcpy(p->relr_rel, g_rel.data(), sizeof(int32_t) * g_rel.size(), hipMemcpyHostToDevice));
+                KGE_HIP(hipMemcpy(p->relr_beg, g_beg.data(), sizeof(int32_t) * g_beg.size(), hipMemcpyHostToDevice));
+                KGE_HIP(hipMemcpy(p->relr_end, g_end.data(), sizeof(int32_t) * g_end.size(), hipMemcpyHostToDevice));
+            }
+        }
         p->n_relt = (int32_t)t_rel.size();
         TRY(palloc(&p->relt_rel, t_rel.size())); TRY(palloc(&p->relt_beg, t_rel.size())); TRY(palloc(&p->relt_end, t_rel.size()));
         if (!t_rel.empty()) {
@@ -589,7 +605,7 @@ extern "C" void kge_partition_destroy(kge_partition *p)
                     p->hv_seg.hv_row, p->hv_seg.hv_unit_ptr, p->hv_seg.unit_hv,
                     p->dr_ptr, p->dr_seg, p->dr_rel, p->hv_dr.hv_row, p->hv_dr.hv_unit_ptr, p->hv_dr.unit_hv,
                     p->relc_rel, p->relc_beg, p->relc_end, p->sm_seg, p->relt_rel, p->relt_beg, p->relt_end,
-                    p->seg_zrow, p->mrun, p->bad_ids};
+                    p->relr_rel, p->relr_beg, p->relr_end, p->seg_zrow, p->mrun, p->bad_ids};
     for (void *q : arrs) if (q) (void)hipFree(q);
     delete p;
 }
