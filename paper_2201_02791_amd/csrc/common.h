@@ -188,6 +188,8 @@ int launch_cvt_relation_weights_bf16(const float *Wrel, int32_t R2, int32_t d_in
 bool rel_rows_bf16_supported(int32_t K, int32_t N);
 int launch_rel_rows_bf16(const kge_partition *p, const void *A, int64_t lda, const int32_t *aidx, const void *Wk,
                          int32_t K, int32_t N, void *out, hipStream_t st);
+int launch_all_rows_bf16(const void *A, int64_t rows, const void *Wk, int32_t n_groups, int32_t K, int32_t N,
+                         void *out, hipStream_t st);
 int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, const int32_t *zrow, const void *WbT,
                                        int32_t d_in, int32_t d_out, void *U, hipStream_t st);
 int launch_apply_relation_weights_t_bf16(const kge_partition *p, const void *Gbf, int64_t ldg, const void *Wb,

@@ -635,6 +635,18 @@ int launch_project_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out,
                         void *P, float *Self, hipStream_t st)
 {
     if (N == 0) return KGE_OK;
+    if (B > 0 && rel_rows_bf16_supported(d_in, d_out)) {
+        // the B basis projections: every V_b held in registers while the input rows stream past (rel_rows_bf16.hip);
+        // the self-loop product (fp32 out) stays on the grouped GEMM below
+        int rc;
+        {
+            KGE_PROF("project", st);
+            rc = launch_all_rows_bf16(Hbf, N, WbfT, B, d_in, d_out, P, st);
+        }
+        if (rc != KGE_OK || !Self) return rc;
+        return launch_project_bf16(Hbf, N, d_in, d_out, 0, reinterpret_cast<const uint16_t *>(WbfT) + (int64_t)B * d_out * d_in,
+                                   nullptr, Self, st);
+    }
     const int32_t nc = (B + 1) * d_out;
     const int32_t tiles_m = (int32_t)cdiv(N, TM), tiles_n = (int32_t)cdiv(nc, TN);
     MatBF A{reinterpret_cast<const uint16_t *>(Hbf), N, d_in, d_in, nullptr};

@@ -44,8 +44,9 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)   // two fp32 -> p
 template <int NP>
 __global__ __launch_bounds__(RNT) void k_rel_rows_bf16(
     const uint16_t *__restrict__ A, int64_t lda, const int32_t *__restrict__ aidx,
-    const uint16_t *__restrict__ Wk, int64_t w_stride, int32_t N, uint16_t *__restrict__ out,
+    const uint16_t *__restrict__ Wk, int64_t w_stride, int32_t N, uint16_t *__restrict__ out, int64_t ldo,
     const int32_t *__restrict__ r_rel, const int32_t *__restrict__ r_beg, const int32_t *__restrict__ r_end,
+    int32_t n_groups, int64_t rows_total,   // without a range list: block i takes range i / n_groups of group i % n_groups
     int32_t pitch)                          // LDS row pitch in elements: max(K, N) + 8
 {
     constexpr int K = 32 * NP, KS = 2 * NP;      // contraction width, matrix-core steps of 16
@@ -57,7 +58,18 @@ __global__ __launch_bounds__(RNT) void k_rel_rows_bf16(
 
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int lrow = lane & 31, half = lane >> 5;
-    const int64_t m_beg = r_beg[blockIdx.x], m_end = r_end[blockIdx.x];
+    int64_t m_beg, m_end;
+    int32_t group;
+    if (r_beg) {
+        m_beg = r_beg[blockIdx.x]; m_end = r_end[blockIdx.x]; group = r_rel[blockIdx.x];
+    } else {
+        // every matrix over every range of rows, the groups of one range next to each other: they are dispatched
+        // together (round-robin over the eight L2s), so a range's rows come from HBM once and from cache after that
+        group = (int32_t)(blockIdx.x % (uint32_t)n_groups);
+        m_beg = (int64_t)(blockIdx.x / (uint32_t)n_groups) * KGE_REL_RANGE;
+        m_end = m_beg + KGE_REL_RANGE < rows_total ? m_beg + KGE_REL_RANGE : rows_total;
+        out += (int64_t)group * N;               // group g owns columns [g N, (g + 1) N) of the output rows
+    }
     if (m_beg >= m_end) return;                  // uniform over the block
     const int32_t n_tiles = (int32_t)((m_end - m_beg + RT - 1) / RT);
     const bool cols = 32 * w < N;                // this wavefront has output columns (uniform per wavefront)
@@ -65,7 +77,7 @@ __global__ __launch_bounds__(RNT) void k_rel_rows_bf16(
     // the relation's matrix: this wavefront's 32 columns as row operands, all K
     bf16x8 wreg[KS];
     {
-        const uint16_t *Wr = Wk + (int64_t)r_rel[blockIdx.x] * w_stride;
+        const uint16_t *Wr = Wk + (int64_t)group * w_stride;
         const int32_t n = 32 * w + lrow;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -153,15 +165,15 @@ __global__ __launch_bounds__(RNT) void k_rel_rows_bf16(
         for (int row = srow; row < RT; row += RNT / NC8) {      // NC8 divides the block size: 4, 8, .. 32
             if (m0 + row < m_end) {
                 const u32x4 v = *reinterpret_cast<const u32x4 *>(cur + (size_t)row * pitch + c8 * 8);
-                *reinterpret_cast<u32x4 *>(out + (m0 + row) * N + c8 * 8) = v;
+                *reinterpret_cast<u32x4 *>(out + (m0 + row) * ldo + c8 * 8) = v;
             }
         }
     }
 }
 
 template <int NP>
-int launch_np(const kge_partition *p, const void *A, int64_t lda, const int32_t *aidx, const void *Wk, int32_t N,
-              void *out, hipStream_t st)
+int launch_np(const kge_partition *p, int32_t n_groups, int64_t rows_total, const void *A, int64_t lda,
+              const int32_t *aidx, const void *Wk, int32_t N, void *out, int64_t ldo, hipStream_t st)
 {
     const int32_t K = 32 * NP;
     const int32_t pitch = (K > N ? K : N) + 8;
@@ -172,9 +184,12 @@ int launch_np(const kge_partition *p, const void *A, int64_t lda, const int32_t 
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)((size_t)2 * RT * (256 + 8) * 2)));
         attr_set = true;
     }
-    k_rel_rows_bf16<NP><<<(unsigned)p->n_relr, RNT, lds, st>>>(
+    const int64_t blocks = p ? p->n_relr : n_groups * cdiv(rows_total, KGE_REL_RANGE);
+    KGE_REQUIRE(blocks < (1ll << 31), KGE_ERANGE, "per-run product: too many blocks");
+    k_rel_rows_bf16<NP><<<(unsigned)blocks, RNT, lds, st>>>(
         reinterpret_cast<const uint16_t *>(A), lda, aidx, reinterpret_cast<const uint16_t *>(Wk), (int64_t)N * K, N,
-        reinterpret_cast<uint16_t *>(out), p->relr_rel, p->relr_beg, p->relr_end, pitch);
+        reinterpret_cast<uint16_t *>(out), ldo, p ? p->relr_rel : nullptr, p ? p->relr_beg : nullptr,
+        p ? p->relr_end : nullptr, n_groups, rows_total, pitch);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
@@ -196,8 +211,27 @@ int launch_rel_rows_bf16(const kge_partition *p, const void *A, int64_t lda, con
                 KGE_EINVAL, "per-run product: operands must be 16-byte aligned");
     if (p->n_relr == 0) return KGE_OK;
     switch (K) {
-    case 64: return launch_np<2>(p, A, lda, aidx, Wk, N, out, st);
-    case 128: return launch_np<4>(p, A, lda, aidx, Wk, N, out, st);
-    default: return launch_np<8>(p, A, lda, aidx, Wk, N, out, st);
+    case 64: return launch_np<2>(p, 0, 0, A, lda, aidx, Wk, N, out, N, st);
+    case 128: return launch_np<4>(p, 0, 0, A, lda, aidx, Wk, N, out, N, st);
+    default: return launch_np<8>(p, 0, 0, A, lda, aidx, Wk, N, out, N, st);
+    }
+}
+
+// out[i][g N .. (g + 1) N) = A[i] * Wk[g]^T for every row i < rows and every matrix g < n_groups (the basis
+// projections of Eq. 2: A = the layer input, Wk[g] = V_g^T):  A: bf16 [rows][K], Wk: bf16 [n_groups][N][K],
+// out: bf16 [rows][n_groups N].
+int launch_all_rows_bf16(const void *A, int64_t rows, const void *Wk, int32_t n_groups, int32_t K, int32_t N,
+                         void *out, hipStream_t st)
+{
+    KGE_REQUIRE(rel_rows_bf16_supported(K, N), KGE_EINVAL, "projection: shape not supported by this kernel");
+    KGE_REQUIRE(((uintptr_t)A % 16) == 0 && ((uintptr_t)Wk % 16) == 0 && ((uintptr_t)out % 16) == 0, KGE_EINVAL,
+                "projection: operands must be 16-byte aligned");
+    KGE_REQUIRE(rows < (1ll << 31), KGE_ERANGE, "projection: too many rows");
+    if (rows == 0 || n_groups == 0) return KGE_OK;
+    const int64_t ldo = (int64_t)n_groups * N;
+    switch (K) {
+    case 64: return launch_np<2>(nullptr, n_groups, rows, A, K, nullptr, Wk, N, out, ldo, st);
+    case 128: return launch_np<4>(nullptr, n_groups, rows, A, K, nullptr, Wk, N, out, ldo, st);
+    default: return launch_np<8>(nullptr, n_groups, rows, A, K, nullptr, Wk, N, out, ldo, st);
     }
 }
