@@ -385,6 +385,11 @@ def run_workload(graphs, cfg, order="relation", whole=False, dropout=0.0, steps=
         # its algorithmic bytes are those of the whole call, so the three are reported as one entry
         tot = sum(prof.pop(k)[0] for k in ("score_index", "distmult", "distmult_gather") if k in prof)
         prof["distmult"] = (tot, steps)
+    if "project_self" in prof:
+        # the projections of a bf16 layer with bases are two launches (the B basis products, then the self-loop
+        # product): one entry, one launch pair per layer
+        tot, calls = prof["project"]
+        prof["project"] = (tot + prof.pop("project_self")[0], calls)
     for name, (tot_ms, calls) in prof.items():
         avg_ms = tot_ms / max(calls, 1)
         rec = {"ms_per_step": tot_ms / steps, "launches_per_step": calls / steps, "avg_ms": avg_ms}

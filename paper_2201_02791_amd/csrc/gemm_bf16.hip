@@ -631,28 +631,37 @@ int launch_cvt_weights_bf16(const float *V, const float *W0, int32_t d_in, int32
 }
 
 // [P | Self] = Hbf * [V | W0]      Hbf: bf16 [N][d_in]; WbfT: bf16 [nc][d_in]
+static int project_gemm(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const void *WbfT, void *P,
+                        float *Self, const char *prof_name, hipStream_t st);
+
 int launch_project_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const void *WbfT,
                         void *P, float *Self, hipStream_t st)
 {
     if (N == 0) return KGE_OK;
     if (B > 0 && rel_rows_bf16_supported(d_in, d_out)) {
         // the B basis projections: every V_b held in registers while the input rows stream past (rel_rows_bf16.hip);
-        // the self-loop product (fp32 out) stays on the grouped GEMM below
+        // the self-loop product (fp32 out) stays on the GEMM
         int rc;
         {
             KGE_PROF("project", st);
             rc = launch_all_rows_bf16(Hbf, N, WbfT, B, d_in, d_out, P, st);
         }
         if (rc != KGE_OK || !Self) return rc;
-        return launch_project_bf16(Hbf, N, d_in, d_out, 0, reinterpret_cast<const uint16_t *>(WbfT) + (int64_t)B * d_out * d_in,
-                                   nullptr, Self, st);
+        return project_gemm(Hbf, N, d_in, d_out, 0, reinterpret_cast<const uint16_t *>(WbfT) + (int64_t)B * d_out * d_in,
+                            nullptr, Self, "project_self", st);
     }
+    return project_gemm(Hbf, N, d_in, d_out, B, WbfT, P, Self, "project", st);
+}
+
+static int project_gemm(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out, int32_t B, const void *WbfT, void *P,
+                        float *Self, const char *prof_name, hipStream_t st)
+{
     const int32_t nc = (B + 1) * d_out;
     const int32_t tiles_m = (int32_t)cdiv(N, TM), tiles_n = (int32_t)cdiv(nc, TN);
     MatBF A{reinterpret_cast<const uint16_t *>(Hbf), N, d_in, d_in, nullptr};
     MatBF Bm{reinterpret_cast<const uint16_t *>(WbfT), nc, d_in, d_in, nullptr};
     EpiProjectStaged ep{reinterpret_cast<uint16_t *>(P), Self, N, d_out, B * d_out};
-    KGE_PROF("project", st);
+    KGE_PROF(prof_name, st);
     return launch_gemm<true, EpiProjectStaged, TN, 64>(A, Bm, ep, d_in, cdiv(d_in, TK) * TK, tiles_m, tiles_n, 1, st);
 }
 

@@ -23,6 +23,9 @@ struct kge_score_index {
                                    // -1 - (row of rows[]) for a positive's own end; y = relation; z = bits of delta
     uint32_t *pkeys[2], *pvals[2]; // [max_pos] the batch's positives sorted by relation (ping-pong buffers)
     float *rows;                   // [2 max_pos][d] per positive q: the summed rows for its head (2q) and its tail (2q+1)
+    float *dm_part;                // [KGE_SCORE_MAX_BLOCKS][d] one partial relation-gradient row per scoring block,
+    int32_t *dm_rel;               // [KGE_SCORE_MAX_BLOCKS] its relation (-1: none, the block used atomics),
+    float *loss_part;              // [KGE_SCORE_MAX_BLOCKS] and the block's loss terms
 };
 
 namespace {
@@ -75,6 +78,7 @@ __device__ __forceinline__ float sigmoid_f(float x)
     return x >= 0.f ? 1.f / (1.f + expf(-x)) : expf(x) / (1.f + expf(x));
 }
 
+constexpr int KGE_SCORE_MAX_BLOCKS = 4096;   // the scoring kernel runs at most 16384 wavefronts, four per block
 constexpr int DM_WAVES = 16;     // wavefronts per block of the scoring kernel
 
 // Each wavefront takes a contiguous chunk of positives; for each, lane l holds elements
@@ -342,10 +346,13 @@ __global__ __launch_bounds__(64 * DS_WAVES) void k_distmult_score(
     int64_t n_pos, int32_t per_wave,
     const int32_t *__restrict__ neg_ent, const uint8_t *__restrict__ neg_side, int32_t n_neg,
     uint32_t n_vert, uint32_t n_core,
-    float inv_T, float *__restrict__ scores, float *__restrict__ loss, float *__restrict__ dM,
-    const uint32_t *__restrict__ slot_of, int4 *__restrict__ recs, float4 *__restrict__ rows)
+    float inv_T, float *__restrict__ scores, float *__restrict__ dM,
+    const uint32_t *__restrict__ slot_of, int4 *__restrict__ recs, float4 *__restrict__ rows,
+    float4 *__restrict__ dm_part, int32_t *__restrict__ dm_rel, float *__restrict__ loss_part)
 {
     __shared__ float loss_of_wave[DS_WAVES];
+    __shared__ int32_t rel_of_wave[DS_WAVES];
+    __shared__ float4 part_of_wave[DS_WAVES][64 * NV];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t wave_id = (int64_t)blockIdx.x * DS_WAVES + w;
     const int64_t q_beg = wave_id * per_wave;
@@ -503,15 +510,86 @@ __global__ __launch_bounds__(64 * DS_WAVES) void k_distmult_score(
                 rows[(2 * q + 1) * d4 + lane + 64 * u] = aT[u];
             }
     }
-    if (r_cur >= 0) flush_rel(r_cur);
+    // What is still in registers - the relation gradient of the wavefront's last relation and its loss terms -
+    // leaves as one partial per BLOCK when the block's wavefronts ended on the same relation (the usual case:
+    // the positives are walked in relation order), and k_score_finish adds the partials up.  Thousands of
+    // wavefronts adding to the same few rows of dM (one relation, or a few) would otherwise queue up on the
+    // same addresses.
     lsum = wave_sum(lsum);
-    if (lane == 0) loss_of_wave[w] = lsum;
+    if (lane == 0) { loss_of_wave[w] = lsum; rel_of_wave[w] = r_cur; }
+#pragma unroll
+    for (int u = 0; u < NV; ++u) part_of_wave[w][lane + 64 * u] = aM[u];
     __syncthreads();
+    int32_t r0 = -1;
+    bool same = true;
+#pragma unroll
+    for (int x = 0; x < DS_WAVES; ++x) {
+        const int32_t r = rel_of_wave[x];
+        if (r >= 0) {
+            if (r0 < 0) r0 = r;
+            else if (r != r0) same = false;
+        }
+    }
+    if (same) {
+        if (w == 0) {
+#pragma unroll
+            for (int u = 0; u < NV; ++u) {
+                if (!ok[u]) continue;
+                float4 t4 = part_of_wave[0][lane + 64 * u];
+#pragma unroll
+                for (int x = 1; x < DS_WAVES; ++x) {      // a wavefront without positives holds zeros
+                    const float4 y = part_of_wave[x][lane + 64 * u];
+                    t4.x += y.x; t4.y += y.y; t4.z += y.z; t4.w += y.w;
+                }
+                dm_part[(int64_t)blockIdx.x * d4 + lane + 64 * u] = t4;
+            }
+        }
+    } else if (r_cur >= 0) {
+        flush_rel(r_cur);
+    }
     if (threadIdx.x == 0) {
+        dm_rel[blockIdx.x] = same ? r0 : -1;
         float t = 0.f;
 #pragma unroll
         for (int x = 0; x < DS_WAVES; ++x) t += loss_of_wave[x];
-        unsafeAtomicAdd(loss, t * inv_T);
+        loss_part[blockIdx.x] = t;
+    }
+}
+
+// loss = (sum of the blocks' loss terms) / T, in a fixed order; dM[r] += the blocks' partial rows of relation r.
+// Block c walks the c-th range of the scoring blocks (they are in relation order, so a relation's partials are
+// consecutive) and adds a run of equal relations in registers before it touches dM.
+__global__ __launch_bounds__(256) void k_score_finish(const float *__restrict__ dm_part, const int32_t *__restrict__ dm_rel,
+                                                      const float *__restrict__ loss_part, int32_t n_blocks, int32_t len,
+                                                      int32_t d, float inv_T, float *__restrict__ dM, float *__restrict__ loss)
+{
+    __shared__ float red[256];
+    const int32_t b0 = blockIdx.x * len, b1 = b0 + len < n_blocks ? b0 + len : n_blocks;
+    for (int32_t k = threadIdx.x; k < d; k += 256) {
+        float acc = 0.f;
+        int32_t r_acc = -1;
+        for (int32_t b = b0; b < b1; ++b) {
+            const int32_t r = dm_rel[b];
+            if (r < 0) continue;
+            if (r != r_acc) {
+                if (r_acc >= 0) unsafeAtomicAdd(dM + (int64_t)r_acc * d + k, acc);
+                acc = 0.f;
+                r_acc = r;
+            }
+            acc += dm_part[(int64_t)b * d + k];
+        }
+        if (r_acc >= 0) unsafeAtomicAdd(dM + (int64_t)r_acc * d + k, acc);
+    }
+    if (blockIdx.x == 0) {
+        float t = 0.f;
+        for (int32_t b = threadIdx.x; b < n_blocks; b += 256) t += loss_part[b];
+        red[threadIdx.x] = t;
+        __syncthreads();
+        for (int off = 128; off > 0; off >>= 1) {
+            if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) loss[0] = red[0] * inv_T;
     }
 }
 
@@ -633,6 +711,9 @@ extern "C" int kge_score_index_create(const kge_partition *p, int64_t max_pos, i
     take((void **)&x->recs, 16 * (size_t)max_occ);
     for (int k = 0; k < 2; ++k) { take((void **)&x->pkeys[k], 4 * (size_t)max_pos); take((void **)&x->pvals[k], 4 * (size_t)max_pos); }
     take((void **)&x->rows, 4 * (size_t)2 * max_pos * d);
+    take((void **)&x->dm_part, 4 * (size_t)KGE_SCORE_MAX_BLOCKS * d);
+    take((void **)&x->dm_rel, 4 * (size_t)KGE_SCORE_MAX_BLOCKS);
+    take((void **)&x->loss_part, 4 * (size_t)KGE_SCORE_MAX_BLOCKS);
     if (e != hipSuccess) {
         kge_set_error("allocating the scoring index failed: %s", hipGetErrorString(e));
         kge_score_index_destroy(x);
@@ -646,7 +727,7 @@ extern "C" void kge_score_index_destroy(kge_score_index *x)
 {
     if (!x) return;
     void *all[] = {x->keys[0], x->keys[1], x->vals[0], x->vals[1], x->sort_ws, x->ent_ptr, x->slot_of, x->recs,
-                   x->pkeys[0], x->pkeys[1], x->pvals[0], x->pvals[1], x->rows};
+                   x->pkeys[0], x->pkeys[1], x->pvals[0], x->pvals[1], x->rows, x->dm_part, x->dm_rel, x->loss_part};
     for (void *q : all) if (q) (void)hipFree(q);
     delete x;
 }
@@ -703,9 +784,15 @@ int launch_distmult_indexed(const kge_partition *p, kge_score_index *x, const fl
 #define DMS_CALL(NVV)                                                                                               \
         k_distmult_score<NVV><<<grid, 64 * DS_WAVES, 0, st>>>((const float4 *)H, (const float4 *)M, d4, p->core_h,  \
             p->core_r, p->core_t, pos, pvals, n_pos, (int32_t)per_wave, neg_ent, neg_side, n_neg,                  \
-            (uint32_t)p->n_vert, (uint32_t)p->n_core, inv_T, scores, loss, dM, x->slot_of, x->recs, (float4 *)x->rows)
+            (uint32_t)p->n_vert, (uint32_t)p->n_core, inv_T, scores, dM, x->slot_of, x->recs, (float4 *)x->rows,  \
+            (float4 *)x->dm_part, x->dm_rel, x->loss_part)
+        KGE_REQUIRE(grid <= KGE_SCORE_MAX_BLOCKS, KGE_ERANGE, "scoring: more blocks than the index has partial rows for");
         if (d4 <= 64) DMS_CALL(1); else DMS_CALL(2);
 #undef DMS_CALL
+        KGE_LAUNCH_CHECK();
+        const int32_t n_chunks = grid < 64 ? (int32_t)grid : 64, len = (int32_t)cdiv(grid, n_chunks);
+        k_score_finish<<<(unsigned)cdiv(grid, len), 256, 0, st>>>(x->dm_part, x->dm_rel, x->loss_part, (int32_t)grid, len, d,
+                                                                   inv_T, dM, loss);
         KGE_LAUNCH_CHECK();
     }
     {
