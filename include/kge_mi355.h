@@ -392,12 +392,6 @@ int kge_eval_metrics(const int32_t *higher, const int32_t *equal, int64_t n_quer
 int kge_eval_rank_all_static(const kge_eval_filter *filter, const float *H, int64_t n_entities, int32_t d,
                              const float *M, int32_t n_relations, const int32_t *test_h, const int32_t *test_r,
                              const int32_t *test_t, int64_t n_test, int32_t *higher, int32_t *equal, void *stream);
-/* Test hook: the fp32 scores kge_eval_rank_all compares, written out: scores DEVICE float
- * [2 n_test][n_entities] from the tile kernel, answer_score DEVICE float [2 n_test] from the per-query
- * kernel (the two kernels must agree bit for bit on the same pair).  Small inputs only. */
-int kge_eval_debug_scores(const float *H, int64_t n_entities, int32_t d, const float *M, int32_t n_relations,
-                          const int32_t *test_h, const int32_t *test_r, const int32_t *test_t, int64_t n_test,
-                          void *workspace, size_t ws_bytes, float *scores, float *answer_score, void *stream);
 
 /*
  * Per-kernel timing for benchmarks (not part of the training path).  While enabled, every

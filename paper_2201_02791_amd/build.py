@@ -30,7 +30,8 @@ def _stale(target, deps):
 
 def build(force: bool = False, verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    headers = [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "sort_scan.h"), os.path.join(ROOT, "include", "kge_mi355.h")]
+    headers = [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "sort_scan.h"), os.path.join(ROOT, "include", "kge_mi355.h"),
+               os.path.join(ROOT, "include", "kge_mi355_testing.h")]
 
     def compile_one(src):
         s = os.path.join(CSRC, src)

@@ -5,6 +5,7 @@
 #include <stdio.h>
 
 #include "kge_mi355.h"
+#include "kge_mi355_testing.h"
 
 void kge_set_error(const char *fmt, ...);
 
