@@ -221,23 +221,28 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
     // lanes share a row).  A k past the range's end takes the range's last row instead (kend <= rows of both
     // operands) and clears its bit in kmask: every load is then unconditional - no divergent branch per load -
     // and only A's octets are zeroed for such a k, which makes the product vanish whatever finite row B repeats.
-    uint32_t kmask = 0u;
-    int32_t tai[NLA], tbi[NLB];
+    // Two sets of them, used in turn: the rows of tile j + 3 are fetched (into the set tile j + 1 no longer needs)
+    // AHEAD of the loads of tile j + 2.  A wavefront's memory operations retire in order, so waiting for indices
+    // that were issued behind a tile's loads would wait for those loads too, and nothing would stay in flight
+    // across a step.
+    struct RowSet { int32_t tai[NLA], tbi[NLB]; uint32_t kmask; };
+    RowSet rs[2];
+    rs[0].kmask = rs[1].kmask = 0u;
     uint16_t *As2 = reinterpret_cast<uint16_t *>(smem), *Bs2 = As2 + TK * PA;
 
-    auto load_rows = [&](int64_t k0) __attribute__((always_inline)) {
+    auto load_rows = [&](int64_t k0, RowSet &S) __attribute__((always_inline)) {
         if constexpr (TR) {
-            kmask = 0u;
+            S.kmask = 0u;
 #pragma unroll
             for (int i = 0; i < NLA; ++i) {
                 const int64_t rl = k0 + t / LRA + RA * i, rcl = rl < kend ? rl : kend - 1;
-                tai[i] = A.idx ? A.idx[rcl] : (int32_t)rcl;
-                kmask |= (rl < kend ? 1u : 0u) << i;
+                S.tai[i] = A.idx ? A.idx[rcl] : (int32_t)rcl;
+                S.kmask |= (rl < kend ? 1u : 0u) << i;
             }
 #pragma unroll
             for (int i = 0; i < NLB; ++i) {
                 const int64_t rl = k0 + t / LRB + RB * i, rcl = rl < kend ? rl : kend - 1;
-                tbi[i] = B.idx ? B.idx[rcl] : (int32_t)rcl;
+                S.tbi[i] = B.idx ? B.idx[rcl] : (int32_t)rcl;
             }
         }
     };
@@ -265,7 +270,7 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             bcrow[ps] = B.idx ? (int64_t)B.idx[rc] : rc;
         }
     }
-    auto load_tile = [&](int64_t k0, Regs &R, const arow_t *arow, const uint16_t *Bp) __attribute__((always_inline)) {
+    auto load_tile = [&](int64_t k0, Regs &R, const arow_t *arow, const uint16_t *Bp, const RowSet &S) __attribute__((always_inline)) {
         if constexpr (MT) {
             // the launcher guarantees whole tiles along k, an un-indexed B and B.rows a multiple of RPP: no clamps.
             // B rows: one 32-bit lane offset behind a scalar base per pass; A rows: the address is rebuilt from
@@ -302,10 +307,10 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
             const int32_t cb0 = n0 + (t % LRB) * 8, cb = cb0 + 8 <= B.cols ? cb0 : B.cols - 8;
 #pragma unroll
             for (int i = 0; i < NLA; ++i)
-                R.a[i] = *reinterpret_cast<const u32x4 *>(A.p + (int64_t)tai[i] * A.ld + ca);
-            R.keep = kmask;
+                R.a[i] = *reinterpret_cast<const u32x4 *>(A.p + (int64_t)S.tai[i] * A.ld + ca);
+            R.keep = S.kmask;
 #pragma unroll
-            for (int i = 0; i < NLB; ++i) R.b[i] = *reinterpret_cast<const u32x4 *>(Bp + (int64_t)tbi[i] * B.ld + cb);
+            for (int i = 0; i < NLB; ++i) R.b[i] = *reinterpret_cast<const u32x4 *>(Bp + (int64_t)S.tbi[i] * B.ld + cb);
         }
     };
     auto store_tile = [&](Regs &R) __attribute__((always_inline)) {
@@ -377,21 +382,40 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
     // k0 + PF TK, or (MT) with the same-numbered early tile of the block's next row tile
     bool has_next = false;
     const int64_t kwrap = (kend - kbeg + TKt - 1) / TKt * TKt;   // MT: a whole number of PF-tile rounds (kbeg = 0)
-    auto step = [&](int64_t k0, Regs &R) __attribute__((always_inline)) {
+    // S: the rows of the tile that refills R (fetched a step ago); Sn: where the rows of the tile after it go
+    auto step = [&](int64_t k0, Regs &R, RowSet &S, RowSet &Sn) __attribute__((always_inline)) {
         __syncthreads();                 // previous tile fully consumed
         store_tile(R);
         __syncthreads();
         const int64_t kn = k0 + PF * TKt;
-        if (kn < kend) { load_tile(kn, R, arow, Bp); load_rows(kn + TKt); }
-        else if (MT && has_next) load_tile(kn - kwrap, R, arow_n, Bp_n);
+        if (kn < kend) { load_rows(kn + TKt, Sn); load_tile(kn, R, arow, Bp, S); }
+        else if (MT && has_next) load_tile(kn - kwrap, R, arow_n, Bp_n, S);
         mma_tile();
     };
 
-    if (kbeg < kend) {
-        load_rows(kbeg);
-        load_tile(kbeg, rg[0], arow, Bp);
-        load_rows(kbeg + TKt);
-        if (PF == 2 && kbeg + TKt < kend) { load_tile(kbeg + TKt, rg[1], arow, Bp); load_rows(kbeg + 2 * TKt); }
+    // The same step where the refill is known to lie inside the range: no condition around the loads, so that the
+    // compiler can count the memory operations issued after the tile it is about to use and waits for that tile
+    // only (behind a condition it has to assume the fewest and waits for everything in flight).
+    auto step_full = [&](int64_t k0, Regs &R, RowSet &S, RowSet &Sn) __attribute__((always_inline)) {
+        __syncthreads();
+        store_tile(R);
+        __syncthreads();
+        load_rows(k0 + (PF + 1) * TKt, Sn);
+        load_tile(k0 + PF * TKt, R, arow, Bp, S);
+        mma_tile();
+    };
+    const bool long_range = PF == 2 && !MT && kend - kbeg >= 4 * TKt;    // uniform over the block
+    if (long_range) {
+        load_rows(kbeg, rs[0]);
+        load_rows(kbeg + TKt, rs[1]);
+        load_tile(kbeg, rg[0], arow, Bp, rs[0]);
+        load_rows(kbeg + 2 * TKt, rs[0]);
+        load_tile(kbeg + TKt, rg[1], arow, Bp, rs[1]);
+    } else if (kbeg < kend) {
+        load_rows(kbeg, rs[0]);
+        load_rows(kbeg + TKt, rs[1]);
+        load_tile(kbeg, rg[0], arow, Bp, rs[0]);
+        if (PF == 2 && kbeg + TKt < kend) { load_rows(kbeg + 2 * TKt, rs[0]); load_tile(kbeg + TKt, rg[1], arow, Bp, rs[1]); }
     }
     for (int32_t ti = 0; ti < t_cnt; ++ti) {
     if constexpr (MT) {
@@ -410,12 +434,19 @@ __global__ __launch_bounds__(NT, TNt == TN ? 2 : 4) void k_gemm_bf16(MatBF A, Ma
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     if constexpr (PF == 2) {
-        for (int64_t k0 = kbeg; k0 < kend; k0 += 2 * TKt) {
-            step(k0, rg[0]);
-            if (k0 + TKt < kend) step(k0 + TKt, rg[1]);
+        int64_t k0 = kbeg;
+        if (long_range) {
+            for (; k0 + 4 * TKt <= kend; k0 += 2 * TKt) {     // both refills of the pair lie inside the range
+                step_full(k0, rg[0], rs[0], rs[1]);
+                step_full(k0 + TKt, rg[1], rs[1], rs[0]);
+            }
+        }
+        for (; k0 < kend; k0 += 2 * TKt) {
+            step(k0, rg[0], rs[0], rs[1]);
+            if (k0 + TKt < kend) step(k0 + TKt, rg[1], rs[1], rs[0]);
         }
     } else {
-        for (int64_t k0 = kbeg; k0 < kend; k0 += TKt) step(k0, rg[0]);
+        for (int64_t k0 = kbeg; k0 < kend; k0 += TKt) step(k0, rg[0], rs[0], rs[0]);
     }
     // D register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 tile
     if constexpr (EPI::packed) {
