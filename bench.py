@@ -60,7 +60,9 @@ def kernel_work(name, part, spec, dims, B, ep, n_pos, n_neg, cone=None, order="p
         elif name == "coeff_seg":  # per edge: P row + src; per run: ptr/dst/1/c + G row + B outputs
             w = {"bytes": ne * (B * do * ep + 4.0) + ns * (8.0 + 4.0 * do) + S * ((5.0 if inactive else 4.0) + 4.0 * B)}
         elif name == "gather_t":   # per edge: G row + (dst, rel, 1/c); per vertex: ptr + dP row write
-            w = {"bytes": ne * 4.0 * do + E * (13.0 if inactive else 12.0) + N * (4.0 + B * do * ep) + R2 * B * 4.0}
+            # the bf16 matrix-core form (>= 32 bases, width a multiple of 32) gathers the bf16 copy of G
+            g_el = 2.0 if (ep == 2 and B >= 32 and do % 32 == 0) else 4.0
+            w = {"bytes": ne * g_el * do + E * (13.0 if inactive else 12.0) + N * (4.0 + B * do * ep) + R2 * B * 4.0}
         elif name == "run_mean":   # per edge: source id + input row; per run: ptr/dst/1/c + z row written
             # single_runs: runs of one edge that the bf16 relation-weight pipeline neither reads nor writes
             # (their mean is the source's input row, read in place by the products), scaled to the sub-graph

@@ -419,12 +419,21 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
         rc = launch_coeff_grad(p, P, bf, Gl, L.n_bases, L.d_out, seg, part, grads[l].da, kge_cgraph_layer(cg, l), st);
         if (rc != KGE_OK) return rc;
         const int64_t bd = (int64_t)L.n_bases * L.d_out;
-        rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf ? bd + L.d_out : bd, bf, part,
-                                     kge_cgraph_layer(cg, l), st);
-        if (rc != KGE_OK) return rc;
-        if (bf) {
+        if (bf && gather_transpose_bf16_supported(L.n_bases, L.d_out)) {
+            // the bf16 copy of G first (behind the dP columns of the same matrix): the transposed sums gather it
             rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, L.n_bases, dP, st);
             if (rc != KGE_OK) return rc;
+            rc = launch_gather_transpose_bf16(p, (const uint16_t *)dP + bd, bd + L.d_out, L.a, L.n_bases, L.d_out, dP,
+                                              bd + L.d_out, part, kge_cgraph_layer(cg, l), st);
+            if (rc != KGE_OK) return rc;
+        } else {
+            rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf ? bd + L.d_out : bd, bf, part,
+                                         kge_cgraph_layer(cg, l), st);
+            if (rc != KGE_OK) return rc;
+            if (bf) rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, L.n_bases, dP, st);
+            if (rc != KGE_OK) return rc;
+        }
+        if (bf) {
             rc = launch_weight_grad_bf16(ws + w.off_Hbf[l], p->n_vert, L.d_in, L.d_out, L.n_bases, dP,
                                          grads[l].dV, grads[l].dW0, st);
         } else {

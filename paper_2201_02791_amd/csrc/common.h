@@ -140,6 +140,9 @@ int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t 
 // dP[j][b][:] = sum_{e out of j} a[rel_e][b] invc_e G[dst_e][:]
 // `partial`: [hv_sm.n_units][B*d] floats of scratch
 // dP rows are `ld` elements apart (B*d, or (B+1)*d when G is appended behind them)
+bool gather_transpose_bf16_supported(int32_t B, int32_t d);
+int launch_gather_transpose_bf16(const kge_partition *p, const void *Gbf, int64_t ldg, const float *a, int32_t B,
+                                 int32_t d, void *dP, int64_t ld, float *partial, const uint8_t *active, hipStream_t st);
 int launch_gather_transpose(const kge_partition *p, const float *G, const float *a, int32_t B,
                             int32_t d, void *dP, int64_t ld, int msg_bf16, float *partial,
                             const uint8_t *active, hipStream_t st);

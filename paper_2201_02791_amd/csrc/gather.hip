@@ -500,6 +500,139 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_t_mfma(
         }
 }
 
+// The same per-source product for workloads that keep messages in bf16, on v_mfma_f32_32x32x16_bf16:
+//   dP[j] (B x d, bf16) = W^T (B x deg) * Gg (deg x d),  W[e][b] = a[rel_e][b] invc_e (rounded to bf16),  Gg[e] = Gbf[dst_e].
+// One block of four wavefronts per (source or heavy unit, chunk of 64 bases, chunk of 256 columns).  The block
+// stages up to 32 edges at a time in LDS, as they lie in memory and with 16-byte loads: the gathered rows of G
+// ([edge][column]) and the coefficient rows ([edge][base], multiplied by 1/c and rounded on the way).  The edge is
+// the contraction index of both, so the matrix-core operands are fetched with the transposing LDS read, two per
+// operand; wavefront w owns bases 32 (w / 2) .. and columns 128 (w % 2) ..: one coefficient operand feeds four
+// products.  Sixteen edges per matrix-core instruction instead of two, and the gathered rows are read once per
+// block instead of once per wavefront.
+constexpr int GTB_EP = 32;                 // edges per pass
+constexpr int GTB_PG = 256 + 32;           // LDS pitches, elements: 64 bytes modulo 256 (the four rows that 16
+constexpr int GTB_PC = 64 + 96;            // lanes read at once fall in different quarters of the banks)
+
+__global__ __launch_bounds__(256) void k_gather_t_bf16(
+    const int32_t *__restrict__ sm_ptr, const int32_t *__restrict__ sm_dst,
+    const int32_t *__restrict__ sm_rel, const float *__restrict__ sm_invc, int64_t N,
+    int32_t n_units, const int32_t *__restrict__ hv_row, const int32_t *__restrict__ hv_unit_ptr,
+    const int32_t *__restrict__ unit_hv,
+    const uint16_t *__restrict__ Gbf, int64_t ldg, const float *__restrict__ a, int32_t B, int32_t d,
+    int32_t n_bchunks, int32_t n_cchunks, uint16_t *__restrict__ dP, int64_t ld, float *__restrict__ partial,
+    const uint8_t *__restrict__ active)
+{
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 gtb_bf16x8 __attribute__((ext_vector_type(8)));
+    __shared__ __attribute__((aligned(16))) uint16_t Gs[GTB_EP * GTB_PG];     // 18,432 B; the epilogue's staging too
+    __shared__ __attribute__((aligned(16))) uint16_t Cs[GTB_EP * GTB_PC];     // 10,240 B
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int n_chunks = n_bchunks * n_cchunks;
+    const int64_t wid = (int64_t)blockIdx.x / n_chunks;
+    const int chunk = (int)((int64_t)blockIdx.x - wid * n_chunks);
+    const int bbase = (chunk / n_cchunks) * 64, cbase = (chunk % n_cchunks) * 256;
+    const RowWork rw = row_work(wid, sm_ptr, N, n_units, hv_row, hv_unit_ptr, unit_hv);
+    if (rw.row < 0) return;                               // uniform over the block
+    const int wm = w >> 1, wn = w & 1;
+
+    gt_floatx16 acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+
+    // this thread's part of a pass: edge t / 8; of its G row the 16-byte chunks (t % 8) + 8 p, of its coefficient
+    // row the 8 bases from 8 (t % 8)
+    const int el = t >> 3, sub = t & 7;
+    const int l16 = lane & 15, kr0 = 8 * (lane >> 5) + (l16 >> 2), mc = 16 * ((lane >> 4) & 1) + 4 * (l16 & 3);
+    auto frag = [&](const uint16_t *tile, int pitch, int kr, int col) __attribute__((always_inline)) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3))) *)(tile + kr * pitch + col));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3))) *)(tile + (kr + 4) * pitch + col));
+        return __builtin_bit_cast(gtb_bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+
+    for (int32_t e0 = rw.beg; e0 < rw.end; e0 += GTB_EP) {
+        const int cnt = min(GTB_EP, rw.end - e0);
+        int32_t dst = -1, rel = 0;
+        float wgt = 0.f;
+        if (el < cnt) {
+            dst = sm_dst[e0 + el]; rel = sm_rel[e0 + el]; wgt = sm_invc ? sm_invc[e0 + el] : 1.f;
+            if (active && !active[dst]) dst = -1;         // destination outside the sub-graph: its G row is zero
+        }
+        uint4 gq[4];
+        float cf[8];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int col = cbase + 8 * (sub + 8 * p);
+            gq[p] = make_uint4(0u, 0u, 0u, 0u);
+            if (dst >= 0 && col < d) gq[p] = *reinterpret_cast<const uint4 *>(Gbf + (int64_t)dst * ldg + col);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int b = bbase + 8 * sub + q;
+            cf[q] = (dst >= 0 && b < B) ? a[(int64_t)rel * B + b] * wgt : 0.f;
+        }
+        __syncthreads();                                  // the previous pass's operands are consumed
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            *reinterpret_cast<uint4 *>(&Gs[el * GTB_PG + 8 * (sub + 8 * p)]) = gq[p];
+        *reinterpret_cast<uint4 *>(&Cs[el * GTB_PC + 8 * sub]) =
+            make_uint4(pack_bf16x2(cf[0], cf[1]), pack_bf16x2(cf[2], cf[3]), pack_bf16x2(cf[4], cf[5]), pack_bf16x2(cf[6], cf[7]));
+        __syncthreads();
+        if (bbase + 32 * wm < B) {                        // uniform per wavefront
+#pragma unroll
+            for (int ks = 0; ks < GTB_EP; ks += 16) {
+                if (ks >= cnt) break;                     // uniform
+                const gtb_bf16x8 af = frag(Cs, GTB_PC, ks + kr0, 32 * wm + mc);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (cbase + 128 * wn + 32 * c >= d) continue;     // uniform
+                    const gtb_bf16x8 bfr = frag(Gs, GTB_PG, ks + kr0, 128 * wn + 32 * c + mc);
+                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[c], 0, 0, 0);
+                }
+            }
+        }
+    }
+    __syncthreads();                                      // Gs is free: each wavefront stages its tiles in its quarter
+    // D register v of lane l: base 8*(v/4) + 4*(l/32) + v%4, column l%32 of its tile
+    const int h = lane >> 5, l32 = lane & 31;
+    float (*stage)[36] = reinterpret_cast<float (*)[36]>(reinterpret_cast<float *>(Gs) + w * 32 * 36);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int tb = bbase + 32 * wm, tc = cbase + 128 * wn + 32 * c;
+        if (tb >= B || tc >= d) continue;                 // uniform
+        if (rw.unit >= 0) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int b = tb + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (b < B) partial[((int64_t)rw.unit * B + b) * d + tc + l32] = acc[c][v];
+            }
+        } else {
+            // through LDS so that each lane writes 16 consecutive bf16 of one base row
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int v = 0; v < 16; ++v) stage[8 * (v >> 2) + 4 * h + (v & 3)][l32] = acc[c][v];
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const int br = lane >> 1, c16 = (lane & 1) * 16;
+            const float4 x0 = *reinterpret_cast<const float4 *>(&stage[br][c16]);
+            const float4 x1 = *reinterpret_cast<const float4 *>(&stage[br][c16 + 4]);
+            const float4 x2 = *reinterpret_cast<const float4 *>(&stage[br][c16 + 8]);
+            const float4 x3 = *reinterpret_cast<const float4 *>(&stage[br][c16 + 12]);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            if (tb + br < B) {
+                uint16_t *q = dP + (int64_t)rw.row * ld + (int64_t)(tb + br) * d + tc + c16;
+                *reinterpret_cast<uint4 *>(q) = make_uint4(pack_bf16x2(x0.x, x0.y), pack_bf16x2(x0.z, x0.w),
+                                                           pack_bf16x2(x1.x, x1.y), pack_bf16x2(x1.z, x1.w));
+                *reinterpret_cast<uint4 *>(q + 8) = make_uint4(pack_bf16x2(x2.x, x2.y), pack_bf16x2(x2.z, x2.w),
+                                                               pack_bf16x2(x3.x, x3.y), pack_bf16x2(x3.z, x3.w));
+            }
+        }
+    }
+}
+
 // Heavy sources: dP[j] = sum of the row's unit partials.  One thread per float4 of a [B*d] row.
 template <bool BF16>
 __global__ void k_gather_t_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
@@ -1048,6 +1181,40 @@ int launch_gather_transpose(const kge_partition *p, const float *G, const float 
 {
     const TView vw{p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, p->n_vert, &p->hv_sm, "gather_t"};
     return launch_tview(vw, G, 0, a, B, d, dP, ld, msg_bf16, partial, active, nullptr, st);
+}
+
+// The bf16 form: Gbf = the bf16 copy of G, rows `ldg` elements apart.  Takes the matrix-core kernel above when the
+// layer has at least 32 bases and a width that is a multiple of 32; other shapes convert nothing and go the
+// general way from the fp32 G.
+bool gather_transpose_bf16_supported(int32_t B, int32_t d) { return B >= 32 && d % 32 == 0 && d >= 32; }
+
+int launch_gather_transpose_bf16(const kge_partition *p, const void *Gbf, int64_t ldg, const float *a, int32_t B,
+                                 int32_t d, void *dP, int64_t ld, float *partial, const uint8_t *active, hipStream_t st)
+{
+    KGE_REQUIRE(gather_transpose_bf16_supported(B, d), KGE_EINVAL, "transposed aggregation: shape not supported by the bf16 kernel");
+    KGE_REQUIRE(ldg % 8 == 0 && ((uintptr_t)Gbf % 16) == 0 && ld % 8 == 0 && ((uintptr_t)dP % 16) == 0, KGE_EINVAL,
+                "transposed aggregation: rows must be 16-byte aligned");
+    const kge_heavy_index &hx = p->hv_sm;
+    if (p->n_vert == 0) return KGE_OK;
+    const int n_bchunks = (B + 63) / 64, n_cchunks = (d + 255) / 256;
+    const int64_t blocks = ((int64_t)p->n_vert + hx.n_units) * n_bchunks * n_cchunks;
+    KGE_REQUIRE(blocks < 0x7fffffffLL, KGE_ERANGE, "grid too large");
+    {
+        KGE_PROF("gather_t", st);
+        k_gather_t_bf16<<<(unsigned)blocks, 256, 0, st>>>(p->sm_ptr, p->sm_dst, p->sm_rel, p->sm_invc, p->n_vert, hx.n_units,
+                                                         hx.hv_row, hx.hv_unit_ptr, hx.unit_hv,
+                                                         reinterpret_cast<const uint16_t *>(Gbf), ldg, a, B, d, n_bchunks,
+                                                         n_cchunks, reinterpret_cast<uint16_t *>(dP), ld, partial, active);
+        KGE_LAUNCH_CHECK();
+    }
+    if (hx.n_hv > 0) {
+        KGE_PROF("gather_t_fin", st);
+        const int bd = B * d;
+        const int64_t n = (int64_t)hx.n_hv * (bd / 4);
+        k_gather_t_finish<true><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, bd, dP, ld, nullptr);
+        KGE_LAUNCH_CHECK();
+    }
+    return KGE_OK;
 }
 
 template <bool BF16, int LPR>

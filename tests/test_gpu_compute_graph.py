@@ -97,10 +97,11 @@ def test_cone_with_hub_rows(kb, orc):
         assert_step_close(ts, res, TOL_VAL, TOL_GRAD, batch_rows=orc.batch_vertices(op, pos, res["neg_ent"]))
 
 
-def test_cone_bf16_messages(kb, orc):
-    say("cone bf16")
+@pytest.mark.parametrize("d,B", [(64, 8), (96, 40)], ids=["d64_B8", "d96_B40_matrix_core_transposed_sums"])
+def test_cone_bf16_messages(kb, orc, d, B):
+    say("cone bf16", d, B)
     spec = synth.scaled(synth.WORKLOADS[4], name="bf16cone", n_entities=5000, n_relations=20, n_triples=40000,
-                        d=64, n_bases=8, n_pos=12, n_neg=4, n_parts=1, part_id=0, acts=[1, 0])
+                        d=d, n_bases=B, n_pos=12, n_neg=4, n_parts=1, part_id=0, acts=[1, 0])
     head, rel, tail = synth.make_triples(spec)
     gp, ts, params, pos = gpu_step(spec, head, rel, tail, cone=True)
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos)

@@ -138,8 +138,10 @@ def test_hub_vertex_and_isolated_rows(kb, orc):
 
 
 @pytest.mark.parametrize("acts,n,m,d,B", [([0, 0], 600, 6000, 64, 8), ([1, 0], 6000, 90000, 64, 8),
-                                          ([0, 0], 900, 9000, 96, 40)],
-                         ids=["identity", "relu", "identity_B40_d96"])
+                                          ([0, 0], 900, 9000, 96, 40), ([1, 0], 3000, 70000, 128, 64),
+                                          ([1, 0], 2000, 30000, 224, 70)],
+                         ids=["identity", "relu", "identity_B40_d96", "relu_B64_d128_hub_sources",
+                              "relu_B70_d224_two_base_chunks"])
 def test_bf16_messages_small(kb, orc, acts, n, m, d, B):
     """Messages stored as bf16 (fp32 accumulation): every output against the exact oracle at 2e-2.
     The ReLU mask of layer 1 is a decision taken from floating-point values; where a pre-activation
@@ -152,6 +154,8 @@ def test_bf16_messages_small(kb, orc, acts, n, m, d, B):
     gp, ts, params, pos = gpu_step(spec, head, rel, tail)
     op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
     assert_partition_equal(gp, op)
+    if B == 64:
+        assert gp.max_out_degree >= 256, "this case is meant to have sources whose out-edges are cut into units"
     n_adopted, res = align_mask_decisions(orc, ts, op, res, params, acts, True, True)
     say("mask decisions inside the rounding band, taken as the kernel took them:", n_adopted)
     errs = assert_step_close(ts, res, TOL_BF16, TOL_BF16)
