@@ -81,7 +81,10 @@ def kernel_work(name, part, spec, dims, B, ep, n_pos, n_neg, cone=None, order="p
             w = {"flops": 2.0 * S * di * do, "bytes": S * (di + do) * ep + R2 * di * do * ep, "unit": "mfma"}
         elif name == "rel_outer":  # C_r = sum_runs z^T G: two rows read per run, C_r accumulated once
             w = {"flops": 2.0 * S * di * do, "bytes": S * (di + do) * ep + R2 * di * do * 4.0, "unit": "mfma"}
-        elif name in ("rel_weights", "basis_grad"):   # (2R x B) by (B x d_in d_out) on the vector ALUs
+        elif name == "rel_weights":  # (2R x B) by (B x d_in d_out) on the vector ALUs; bf16: written in both orientations
+            w = {"flops": 2.0 * R2 * B * di * do, "unit": "alu",
+                 "bytes": B * di * do * 4.0 + R2 * di * do * (4.0 if ep == 4 else 2.0 * ep)}
+        elif name == "basis_grad":   # the transposed product: C read once, dV written
             w = {"flops": 2.0 * R2 * B * di * do, "bytes": (R2 + B) * di * do * 4.0, "unit": "alu"}
         elif name == "coeff_contract":   # da_rb = <C_r, V_b>: C and V read once
             w = {"flops": 2.0 * R2 * di * do * B, "bytes": (R2 + B) * di * do * 4.0, "unit": "mfma", "f32": True}

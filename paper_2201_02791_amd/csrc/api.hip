@@ -135,8 +135,9 @@ void layout(const kge_partition *p, const kge_layer *layers, int32_t n_layers, i
             // one matrix [X; Z] whose rows the partition's seg_zrow addresses
             if (bf) { w->off_Hbf[l] = cur; cur += N * L.d_in * 2; }
             w->off_Z[l] = cur; cur = align_up(cur + (size_t)p->n_seg * L.d_in * ep, 256);
-            w->off_Wrel[l] = cur; cur = align_up(cur + R2 * dd * 4, 256);
-            if (bf) {
+            if (!bf) {
+                w->off_Wrel[l] = cur; cur = align_up(cur + R2 * dd * 4, 256);
+            } else {
                 w->off_Wrb[l] = cur; cur = align_up(cur + R2 * dd * 2, 256);
                 w->off_WrbT[l] = cur; cur = align_up(cur + R2 * dd * 2, 256);
             }
@@ -280,15 +281,15 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
             float *Wrel = (float *)(ws + w.off_Wrel[l]);
             const uint8_t *act_l = kge_cgraph_layer(cg, l);
             const int32_t R2 = 2 * p->n_relations;
-            rc = launch_relation_weights(L.a, R2, L.n_bases, L.V, (int64_t)L.d_in * L.d_out, Wrel, st);
+            // bf16 messages: the relation matrices are rounded as they are summed; the fp32 ones are never stored
+            if (bf) rc = launch_relation_weights_bf16(L.a, R2, L.n_bases, L.V, L.d_in, L.d_out, ws + w.off_Wrb[l], ws + w.off_WrbT[l], st);
+            else rc = launch_relation_weights(L.a, R2, L.n_bases, L.V, (int64_t)L.d_in * L.d_out, Wrel, st);
             if (rc != KGE_OK) return rc;
             if (bf) {
                 void *Hbf = ws + w.off_Hbf[l], *Wbf = ws + w.off_Wbf[l], *WbfT = ws + w.off_WbfT[l];
                 rc = launch_cvt_rows_bf16(Hin, p->n_vert * (int64_t)L.d_in, Hbf, st);
                 if (rc != KGE_OK) return rc;
                 rc = launch_cvt_weights_bf16(L.V, L.W0, L.d_in, L.d_out, 0, Wbf, WbfT, st);     // W0 alone, both orientations
-                if (rc != KGE_OK) return rc;
-                rc = launch_cvt_relation_weights_bf16(Wrel, R2, L.d_in, L.d_out, ws + w.off_Wrb[l], ws + w.off_WrbT[l], st);
                 if (rc != KGE_OK) return rc;
                 // a run of one edge has its source's row of Hbf as its mean: those rows of Z are neither written
                 // nor read (Hbf and Z are adjacent, seg_zrow says which row of [Hbf; Z] holds run s)

@@ -177,6 +177,9 @@ int launch_sum_edges_out(const kge_partition *p, const void *dZ, int z_bf16, int
 int launch_relation_weights(const float *a, int32_t R2, int32_t B, const float *V, int64_t dd, float *Wrel,
                             hipStream_t st);
 // dV[b] = sum_r a[r][b] C[r]   (overwrites dV)
+// the same matrices summed in fp32 and stored as bf16 only: Wb [2R][d_in][d_out] and WbT [2R][d_out][d_in]
+int launch_relation_weights_bf16(const float *a, int32_t R2, int32_t B, const float *V, int32_t d_in, int32_t d_out,
+                                 void *Wb, void *WbT, hipStream_t st);
 int launch_basis_grad_from_relations(const float *a, int32_t R2, int32_t B, const float *C, int64_t dd, float *dV,
                                      hipStream_t st);
 // U[s] = Z[s] Wrel[rel(s)]  and  dZ[s] = G[dst(s)] Wrel[rel(s)]^T   (fp32)
@@ -184,9 +187,6 @@ int launch_apply_relation_weights(const kge_partition *p, const float *Z, const 
                                   int32_t d_out, float *U, hipStream_t st);
 int launch_apply_relation_weights_t(const kge_partition *p, const float *G, const float *Wrel, int32_t d_in,
                                     int32_t d_out, float *dZ, hipStream_t st);
-// bf16 copies of Wrel: Wb [2R][d_in][d_out] and WbT [2R][d_out][d_in]
-int launch_cvt_relation_weights_bf16(const float *Wrel, int32_t R2, int32_t d_in, int32_t d_out, void *Wb, void *WbT,
-                                     hipStream_t st);
 // the same two products from bf16 operands, bf16 results; Gbf rows are ldg elements apart.  zrow (may be
 // NULL): Zbf is then the matrix [X; Z] and run s reads its row zrow[s]
 bool rel_rows_bf16_supported(int32_t K, int32_t N);

@@ -407,48 +407,14 @@ int launch_coeff_contract(const kge_partition *p, const float *C, const float *V
 // ---- relation-weight order ------------------------------------------------------------------
 namespace {
 
-// out[i][x] = sum_k coef(i, k) M[k][x],  coef(i, k) = TRANS ? c[k][i] : c[i][k]   (c is [ni][nk], or [nk][ni])
-// One block: 16 rows i, 256 CPT columns x (CPT = 4 or 1 per thread); M is read once per 16 rows.  A long sum
-// over few rows (the basis gradient: nk = 2R, ni = B) takes CPT = 1: four times the blocks, each walking k
-// with several row loads in flight.
-template <bool TRANS, int CPT>
+// out[i][x] = sum_k c[i][k] M[k][x]   (c is [ni][nk])
+// One block: 16 rows i, 1024 columns x (4 per thread); M is read once per 16 rows.
 __global__ __launch_bounds__(256) void k_lincomb(const float *__restrict__ c, int32_t ni, int32_t nk,
                                                  const float *__restrict__ M, int64_t nx, float *__restrict__ out)
 {
     __shared__ float sc[16][64];
     const int i0 = blockIdx.y * 16;
-    const int64_t x = ((int64_t)blockIdx.x * 256 + threadIdx.x) * CPT;
-    if constexpr (CPT == 1) {
-        float acc1[16];
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc1[j] = 0.f;
-        for (int k0 = 0; k0 < nk; k0 += 64) {
-            __syncthreads();
-            for (int q = threadIdx.x; q < 16 * 64; q += 256) {
-                const int j = q >> 6, kk = q & 63;
-                const int i = i0 + j, k = k0 + kk;
-                sc[j][kk] = (i < ni && k < nk) ? (TRANS ? c[(int64_t)k * ni + i] : c[(int64_t)i * nk + k]) : 0.f;
-            }
-            __syncthreads();
-            if (x < nx) {
-                float m[8];
-#pragma unroll
-                for (int kb = 0; kb < 64; kb += 8) {       // rows past nk carry a zero coefficient: read row nk - 1 instead
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) m[u] = M[(int64_t)min(k0 + kb + u, nk - 1) * nx + x];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-#pragma unroll
-                        for (int j = 0; j < 16; ++j) acc1[j] = fmaf(sc[j][kb + u], m[u], acc1[j]);
-                }
-            }
-        }
-        if (x < nx)
-#pragma unroll
-            for (int j = 0; j < 16; ++j)
-                if (i0 + j < ni) out[(int64_t)(i0 + j) * nx + x] = acc1[j];
-        return;
-    }
+    const int64_t x = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     float4 acc[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -457,7 +423,7 @@ __global__ __launch_bounds__(256) void k_lincomb(const float *__restrict__ c, in
         for (int q = threadIdx.x; q < 16 * 64; q += 256) {
             const int j = q >> 6, kk = q & 63;
             const int i = i0 + j, k = k0 + kk;
-            sc[j][kk] = (i < ni && k < nk) ? (TRANS ? c[(int64_t)k * ni + i] : c[(int64_t)i * nk + k]) : 0.f;
+            sc[j][kk] = (i < ni && k < nk) ? c[(int64_t)i * nk + k] : 0.f;
         }
         __syncthreads();
         const int kn = min(64, nk - k0);
@@ -487,21 +453,89 @@ int launch_relation_weights(const float *a, int32_t R2, int32_t B, const float *
     if (R2 == 0) return KGE_OK;
     dim3 grid((unsigned)cdiv(dd, 1024), (unsigned)cdiv(R2, 16), 1);
     KGE_PROF("rel_weights", st);
-    k_lincomb<false, 4><<<grid, 256, 0, st>>>(a, R2, B, V, dd, Wrel);
+    k_lincomb<<<grid, 256, 0, st>>>(a, R2, B, V, dd, Wrel);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
 
+namespace {
+
+// dV[b][x] += sum_{r in this block's chunk} a[r][b] C[r][x] for BB bases b at once: the block's 256 columns of C
+// are read once for all of them (C, one matrix per relation, is the big operand).  A row's BB coefficients are
+// uniform over the block and contiguous: they arrive through scalar loads and enter the multiply-adds as scalar
+// operands.
+template <int BB>
+__global__ __launch_bounds__(256) void k_basis_grad_cols(const float *__restrict__ a, int32_t R2, int32_t B,
+                                                         int32_t b_base, const float *__restrict__ C, int64_t nx,
+                                                         int32_t rchunk, float *__restrict__ dV)
+{
+    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int b0 = b_base + blockIdx.z * BB;
+    const int rb = blockIdx.y * rchunk, re = min(rb + rchunk, R2);
+    const bool in = x < nx;
+    const float *cp = C + (in ? x : 0);
+    float acc[BB];
+#pragma unroll
+    for (int j = 0; j < BB; ++j) acc[j] = 0.f;
+    int r = rb;
+    for (; r + 4 <= re; r += 4) {
+        float c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) c[u] = cp[(int64_t)(r + u) * nx];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float *ar = a + (int64_t)(r + u) * B + b0;
+#pragma unroll
+            for (int j = 0; j < BB; ++j) acc[j] = fmaf(ar[j], c[u], acc[j]);
+        }
+    }
+    for (; r < re; ++r) {
+        const float c = cp[(int64_t)r * nx];
+        const float *ar = a + (int64_t)r * B + b0;
+#pragma unroll
+        for (int j = 0; j < BB; ++j) acc[j] = fmaf(ar[j], c, acc[j]);
+    }
+    if (in)
+#pragma unroll
+        for (int j = 0; j < BB; ++j) atomicAdd(dV + (int64_t)(b0 + j) * nx + x, acc[j]);
+}
+
+template <int BB>
+int basis_grad_groups(const float *a, int32_t R2, int32_t B, int32_t &b_done, const float *C, int64_t dd, float *dV,
+                      hipStream_t st)
+{
+    const int64_t zb = (B - b_done) / BB;
+    if (zb == 0) return KGE_OK;
+    // the sum over relations is cut into chunks so that about 1536 blocks run (six per compute unit are resident
+    // at once: one round of blocks, no tail); their partial sums meet in dV
+    const int64_t xb = cdiv(dd, 256);
+    int64_t chunks = cdiv(1536, xb * zb);
+    if (chunks > cdiv(R2, 16)) chunks = cdiv(R2, 16);
+    const int32_t rchunk = (int32_t)cdiv(R2, chunks);
+    KGE_REQUIRE(xb <= 0x7fffffffLL && zb <= 65535, KGE_ERANGE, "basis gradient: too many columns or bases");
+    dim3 grid((unsigned)xb, (unsigned)cdiv(R2, rchunk), (unsigned)zb);
+    k_basis_grad_cols<BB><<<grid, 256, 0, st>>>(a, R2, B, b_done, C, dd, rchunk, dV);
+    KGE_LAUNCH_CHECK();
+    b_done += (int32_t)zb * BB;
+    return KGE_OK;
+}
+
+}  // namespace
+
 // dV_b = sum_r a[r][b] C[r]   (the chain rule on Wrel[r] = sum_b a[r][b] V_b with dWrel = C)
+// Groups of 64 bases per block, then what is left in groups of 16, 4 and 1.
 int launch_basis_grad_from_relations(const float *a, int32_t R2, int32_t B, const float *C, int64_t dd, float *dV,
                                      hipStream_t st)
 {
-    if (R2 == 0) return launch_fill_zero(dV, sizeof(float) * (size_t)B * dd, st);
-    dim3 grid((unsigned)cdiv(dd, 256), (unsigned)cdiv(B, 16), 1);
+    int rc = launch_fill_zero(dV, sizeof(float) * (size_t)B * dd, st);
+    if (rc != KGE_OK || R2 == 0 || B == 0) return rc;
     KGE_PROF("basis_grad", st);
-    k_lincomb<true, 1><<<grid, 256, 0, st>>>(a, B, R2, C, dd, dV);
-    KGE_LAUNCH_CHECK();
-    return KGE_OK;
+    int32_t b_done = 0;
+    rc = basis_grad_groups<64>(a, R2, B, b_done, C, dd, dV, st);
+    if (rc == KGE_OK) rc = basis_grad_groups<16>(a, R2, B, b_done, C, dd, dV, st);
+    if (rc == KGE_OK) rc = basis_grad_groups<4>(a, R2, B, b_done, C, dd, dV, st);
+    if (rc == KGE_OK) rc = basis_grad_groups<1>(a, R2, B, b_done, C, dd, dV, st);
+    return rc;
 }
 
 // U[s] = Z[s] Wrel[rel(s)]   (S x d_in) -> (S x d_out), one row tile per (relation, <= 128 runs)

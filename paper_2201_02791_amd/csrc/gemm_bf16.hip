@@ -560,31 +560,6 @@ __global__ void k_cvt_weights(const float *__restrict__ V, const float *__restri
     WbfT[(int64_t)n * d_in + k] = h;
 }
 
-// Wrel (fp32 [G][rows][cols]) -> bf16 copies in both orientations: Wb[g][r][c] and WbT[g][c][r]
-__global__ __launch_bounds__(256) void k_cvt_group_mats(const float *__restrict__ W, int32_t rows, int32_t cols,
-                                                        uint16_t *__restrict__ Wb, uint16_t *__restrict__ WbT)
-{
-    __shared__ uint16_t tile[32][33];
-    const int64_t g = blockIdx.z;
-    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 x 8
-    const float *Wg = W + g * rows * cols;
-    for (int rr = ty; rr < 32; rr += 8) {
-        const int r = r0 + rr, c = c0 + tx;
-        uint16_t h = 0;
-        if (r < rows && c < cols) {
-            h = (uint16_t)(pack2(Wg[(int64_t)r * cols + c], 0.f) & 0xffffu);
-            Wb[g * rows * cols + (int64_t)r * cols + c] = h;
-        }
-        tile[rr][tx] = h;
-    }
-    __syncthreads();
-    for (int cc = ty; cc < 32; cc += 8) {
-        const int c = c0 + cc, r = r0 + tx;
-        if (r < rows && c < cols) WbT[g * rows * cols + (int64_t)c * rows + r] = tile[tx][cc];
-    }
-}
-
 template <bool KC, class EPI, int TNt = TN, int TKt = TK, bool MT = false>
 int launch_gemm(const MatBF &A, const MatBF &B, const EPI &epi, int64_t K, int64_t kchunk, int32_t tiles_m,
                 int32_t tiles_n, int64_t splits, hipStream_t st, const int32_t *g_id = nullptr,
@@ -751,15 +726,90 @@ int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const int32_t
                                                  p->relc_rel, p->relc_beg, p->relc_end);
 }
 
-int launch_cvt_relation_weights_bf16(const float *Wrel, int32_t R2, int32_t d_in, int32_t d_out, void *Wb, void *WbT,
-                                     hipStream_t st)
+// Wb[r][k][n] and WbT[r][n][k] = bf16(sum_b a[r][b] V[b][k][n]): Eq. 2 written out for every relation, summed in
+// fp32 in the order of b and rounded once, in the two orientations the per-run products read; the fp32 matrices
+// are never stored.  One block: a 32 x 32 tile of (k, n) for RB relations.  A thread owns four neighbouring n of
+// one k (one 16-byte load of V per basis, served by L2: the blocks that share a tile are neighbours in the
+// grid); the coefficients are uniform over the block and come through scalar loads.  The transposed copy goes
+// through LDS.  d_in and d_out are multiples of 4 here.
+template <int RB>
+__global__ __launch_bounds__(256) void k_relation_weights_bf16(const float *__restrict__ a, int32_t R2, int32_t B,
+                                                               const float *__restrict__ V, int32_t d_in,
+                                                               int32_t d_out, uint16_t *__restrict__ Wb,
+                                                               uint16_t *__restrict__ WbT)
+{
+    constexpr int PT = 36;                       // tile pitch in elements: rows 8-byte aligned
+    __shared__ uint16_t tile[RB][32][PT];
+    const int r0 = blockIdx.x * RB;
+    const int tiles_n = (d_out + 31) >> 5;
+    const int k0 = (int)(blockIdx.y / tiles_n) * 32, n0 = (int)(blockIdx.y % tiles_n) * 32;
+    const int kk = threadIdx.x >> 3, c4 = (threadIdx.x & 7) * 4;
+    const int64_t dd = (int64_t)d_in * d_out;
+    const bool in = k0 + kk < d_in && n0 + c4 < d_out;
+    const float *vp = V + (in ? (int64_t)(k0 + kk) * d_out + n0 + c4 : 0);
+    const float *ar[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j) ar[j] = a + (int64_t)min(r0 + j, R2 - 1) * B;
+    float4 acc[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    int b = 0;
+    for (; b + 4 <= B; b += 4) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4 *>(vp + (b + u) * dd);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                const float c = ar[j][b + u];
+                acc[j].x = fmaf(c, v[u].x, acc[j].x); acc[j].y = fmaf(c, v[u].y, acc[j].y);
+                acc[j].z = fmaf(c, v[u].z, acc[j].z); acc[j].w = fmaf(c, v[u].w, acc[j].w);
+            }
+    }
+    for (; b < B; ++b) {
+        const float4 v = *reinterpret_cast<const float4 *>(vp + b * dd);
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            const float c = ar[j][b];
+            acc[j].x = fmaf(c, v.x, acc[j].x); acc[j].y = fmaf(c, v.y, acc[j].y);
+            acc[j].z = fmaf(c, v.z, acc[j].z); acc[j].w = fmaf(c, v.w, acc[j].w);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+        const uint2 h = make_uint2(pack2(acc[j].x, acc[j].y), pack2(acc[j].z, acc[j].w));
+        if (in && r0 + j < R2)
+            *reinterpret_cast<uint2 *>(Wb + (int64_t)(r0 + j) * dd + (int64_t)(k0 + kk) * d_out + n0 + c4) = h;
+        *reinterpret_cast<uint2 *>(&tile[j][kk][c4]) = h;
+    }
+    __syncthreads();
+    // transposed: this thread now owns four neighbouring k (c4 ..) of one n (kk)
+    if (n0 + kk < d_out && k0 + c4 < d_in) {
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            if (r0 + j >= R2) break;
+            const uint32_t e0 = tile[j][c4][kk], e1 = tile[j][c4 + 1][kk], e2 = tile[j][c4 + 2][kk],
+                           e3 = tile[j][c4 + 3][kk];
+            *reinterpret_cast<uint2 *>(WbT + (int64_t)(r0 + j) * dd + (int64_t)(n0 + kk) * d_in + k0 + c4) =
+                make_uint2(e0 | (e1 << 16), e2 | (e3 << 16));
+        }
+    }
+}
+
+// The relation matrices of Eq. 2 straight to bf16: Wb [2R][d_in][d_out] and WbT [2R][d_out][d_in]
+int launch_relation_weights_bf16(const float *a, int32_t R2, int32_t B, const float *V, int32_t d_in, int32_t d_out,
+                                 void *Wb, void *WbT, hipStream_t st)
 {
     if (R2 == 0) return KGE_OK;
-    KGE_REQUIRE(R2 <= 65535, KGE_ERANGE, "too many relations for one conversion launch");
-    dim3 grid((unsigned)cdiv(d_out, 32), (unsigned)cdiv(d_in, 32), (unsigned)R2);
-    KGE_PROF("cvt_weights", st);
-    k_cvt_group_mats<<<grid, 256, 0, st>>>(Wrel, d_in, d_out, reinterpret_cast<uint16_t *>(Wb),
-                                          reinterpret_cast<uint16_t *>(WbT));
+    constexpr int RB = 16;
+    const int64_t tiles = cdiv(d_in, 32) * cdiv(d_out, 32);
+    KGE_REQUIRE(d_in % 4 == 0 && d_out % 4 == 0 && tiles <= 65535, KGE_EINVAL,
+                "relation weights in bf16: widths must be multiples of 4");
+    dim3 grid((unsigned)cdiv(R2, RB), (unsigned)tiles, 1);
+    KGE_PROF("rel_weights", st);
+    k_relation_weights_bf16<RB><<<grid, 256, 0, st>>>(a, R2, B, V, d_in, d_out, reinterpret_cast<uint16_t *>(Wb),
+                                                     reinterpret_cast<uint16_t *>(WbT));
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
