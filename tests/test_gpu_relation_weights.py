@@ -160,8 +160,9 @@ TOL_BF16 = 2e-2
 
 @pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("acts,n,m,d,B,cone", [([0, 0], 600, 6000, 64, 8, False), ([1, 0], 6000, 90000, 64, 8, False),
-                                               ([0, 0], 900, 9000, 96, 40, False), ([1, 0], 5000, 60000, 128, 6, True)],
-                         ids=["identity", "relu", "identity_B40_d96", "relu_subgraph"])
+                                               ([0, 0], 900, 9000, 96, 40, False), ([1, 0], 5000, 60000, 128, 6, True),
+                                               ([1, 0], 700, 7000, 40, 70, False)],
+                         ids=["identity", "relu", "identity_B40_d96", "relu_subgraph", "relu_B70_d40_ragged_tiles"])
 def test_bf16_relation_weights(kb, orc, acts, n, m, d, B, cone, order):
     """The bf16 pipeline of the relation-weight order (inputs, run means, W_r, the per-run products and W_0 are
     bf16 operands; sums fp32): every output against the exact oracle at 2e-2, ReLU decisions inside the
