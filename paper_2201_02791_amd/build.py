@@ -15,7 +15,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(PKG, "libkge_mi355.so")
-SOURCES = ["partition.hip", "gemm.hip", "gemm_bf16.hip", "rel_rows_bf16.hip", "gather.hip", "sampler_score.hip", "cgraph.hip", "optimizer.hip", "dropout.hip", "eval.hip", "api.hip"]
+SOURCES = ["partition.hip", "gemm.hip", "gemm_bf16.hip", "rel_rows_bf16.hip", "rel_outer_bf16.hip", "gather.hip", "sampler_score.hip", "cgraph.hip", "optimizer.hip", "dropout.hip", "eval.hip", "api.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wall", "-Wno-unused-function"]

@@ -140,6 +140,10 @@ int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t 
 // dP[j][b][:] = sum_{e out of j} a[rel_e][b] invc_e G[dst_e][:]
 // `partial`: [hv_sm.n_units][B*d] floats of scratch
 // dP rows are `ld` elements apart (B*d, or (B+1)*d when G is appended behind them)
+// rel_outer_bf16.hip: C[r] += sum over relation r's runs of X[xidx ? xidx[s] : s]^T G[seg_dst[s]] (bf16 rows, fp32 C)
+bool rel_outer_bf16_supported(int32_t d_in, int32_t d_out);
+int launch_rel_outer_rows_bf16(const kge_partition *p, const void *X, int64_t ldx, const int32_t *xidx, const void *G,
+                               int64_t ldg, int32_t d_in, int32_t d_out, float *C, hipStream_t st);
 bool gather_transpose_bf16_supported(int32_t B, int32_t d);
 int launch_gather_transpose_bf16(const kge_partition *p, const void *Gbf, int64_t ldg, const float *a, int32_t B,
                                  int32_t d, void *dP, int64_t ld, float *partial, const uint8_t *active, hipStream_t st);

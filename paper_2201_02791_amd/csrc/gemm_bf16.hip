@@ -717,6 +717,10 @@ int launch_rel_outer_bf16(const kge_partition *p, const void *Zbf, const int32_t
     int rc = launch_fill_zero(C, sizeof(float) * (size_t)R2 * d_in * d_out, st);
     if (rc != KGE_OK) return rc;
     if (p->n_seg == 0 || p->n_relc == 0) return KGE_OK;
+    if (rel_outer_bf16_supported(d_in, d_out)) {     // the row-streaming kernel of rel_outer_bf16.hip
+        KGE_PROF("rel_outer", st);
+        return launch_rel_outer_rows_bf16(p, Zbf, d_in, zrow, Gbf, ldg, d_in, d_out, C, st);
+    }
     const int32_t tiles_m = (int32_t)cdiv(d_in, TM), tiles_n = (int32_t)cdiv(d_out, TN);
     MatBF A{reinterpret_cast<const uint16_t *>(Zbf), p->n_seg, d_in, d_in, zrow};
     MatBF Bm{reinterpret_cast<const uint16_t *>(Gbf), p->n_seg, d_out, ldg, p->seg_dst};

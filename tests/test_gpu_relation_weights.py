@@ -182,6 +182,24 @@ def test_bf16_relation_weights(kb, orc, acts, n, m, d, B, cone, order):
     say("errs vs the exact oracle", errs)
 
 
+@pytest.mark.parametrize("d_in,d", [(256, 128), (128, 256)], ids=["256_to_128", "128_to_256"])
+def test_bf16_relation_weights_mixed_widths(kb, orc, d_in, d):
+    """Layers whose input and output widths differ, at the widths the row-streaming kernels of the relation
+    gradient and of the per-run products take (128 and 256): layer 1 is d_in -> d, layer 2 d -> d; relation chunks
+    of every length (one run to several tiles).  Everything against the exact oracle at 2e-2."""
+    say("bf16 relation order, widths", d_in, d)
+    spec = synth.scaled(synth.WORKLOADS[4], name="bf16-mixed", seed=9, n_entities=500, n_relations=12, n_triples=5000,
+                        d=d, d_in=d_in, n_bases=8, n_pos=128, n_neg=4, n_parts=2, part_id=0, acts=[1, 0])
+    head, rel, tail = synth.make_triples(spec)
+    gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=RELW)
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
+    assert_partition_equal(gp, op)
+    n_adopted, res = align_mask_decisions(orc, ts, op, res, params, [1, 0], True, True)
+    say("mask decisions inside the rounding band, taken as the kernel took them:", n_adopted)
+    errs = assert_step_close(ts, res, TOL_BF16, TOL_BF16)
+    say("errs vs the exact oracle", errs)
+
+
 def test_bf16_run_means(kb, orc):
     """Run means z of the first layer (stored in bf16) against the exact means: each element within two
     bf16 roundings (of the input, of the mean) of mean|h| over its run, and 2e-2 as a tensor.  Runs of one edge
