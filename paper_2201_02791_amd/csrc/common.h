@@ -144,6 +144,9 @@ int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t 
 bool rel_outer_bf16_supported(int32_t d_in, int32_t d_out);
 int launch_rel_outer_rows_bf16(const kge_partition *p, const void *X, int64_t ldx, const int32_t *xidx, const void *G,
                                int64_t ldg, int32_t d_in, int32_t d_out, float *C, hipStream_t st);
+// C[g] += X^T Y_g for every d_out-wide column block g of Y's rows; the last block's sum to C_last when non-null
+int launch_col_blocks_outer_bf16(const void *X, int64_t rows, const void *Y, int64_t ldy, int32_t n_groups,
+                                 int32_t d_in, int32_t d_out, float *C, float *C_last, hipStream_t st);
 bool gather_transpose_bf16_supported(int32_t B, int32_t d);
 int launch_gather_transpose_bf16(const kge_partition *p, const void *Gbf, int64_t ldg, const float *a, int32_t B,
                                  int32_t d, void *dP, int64_t ld, float *partial, const uint8_t *active, hipStream_t st);

@@ -681,6 +681,10 @@ int launch_weight_grad_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_
     if (rc != KGE_OK) return rc;
     if (N == 0) return KGE_OK;
     const int32_t nc = (B + 1) * d_out;
+    if (rel_outer_bf16_supported(d_in, d_out)) {     // the row-streaming kernel of rel_outer_bf16.hip
+        KGE_PROF("weight_grad", st);
+        return launch_col_blocks_outer_bf16(Hbf, N, X, nc, B + 1, d_in, d_out, dV, dW0, st);
+    }
     // X as the row operand: 128 of its columns per block against all (up to 256) columns of H at a time
     const int32_t tiles_m = (int32_t)cdiv(nc, TM), tiles_n = (int32_t)cdiv(d_in, TN);
     int64_t splits = cdiv(2048, (int64_t)tiles_m * tiles_n);

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(ONT) void k_rel_outer_bf16(
     const uint16_t *__restrict__ X, int64_t ldx, const int32_t *__restrict__ xidx,
     const uint16_t *__restrict__ G, int64_t ldg, const int32_t *__restrict__ gidx,
     const int32_t *__restrict__ c_rel, const int32_t *__restrict__ c_beg, const int32_t *__restrict__ c_end,
-    float *__restrict__ C)
+    float *__restrict__ C, int32_t n_groups, int32_t rows_total, int32_t chunk_rows, float *__restrict__ C_last)
 {
     constexpr int BX = 2 * DI, BG = 2 * DO;              // bytes of a row of X, of G
     constexpr int LX = BX / 16, LG = BG / 16;            // lanes (16-byte chunks) per row
@@ -72,7 +72,17 @@ __global__ __launch_bounds__(ONT) void k_rel_outer_bf16(
 
     const int t = threadIdx.x, lane = t & 63;
     const int w = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int32_t m_beg = c_beg[blockIdx.x], m_end = c_end[blockIdx.x], rel = c_rel[blockIdx.x];
+    int32_t m_beg, m_end, rel;
+    if (c_beg) {
+        m_beg = c_beg[blockIdx.x]; m_end = c_end[blockIdx.x]; rel = c_rel[blockIdx.x];
+    } else {
+        // without a chunk list: every group (a block of DO columns of G's rows) over every chunk of all rows, the
+        // groups of one chunk next to each other in the grid, so that the chunk's rows of X come from HBM once
+        rel = (int32_t)(blockIdx.x % (uint32_t)n_groups);
+        m_beg = (int32_t)(blockIdx.x / (uint32_t)n_groups) * chunk_rows;
+        m_end = m_beg + chunk_rows < rows_total ? m_beg + chunk_rows : rows_total;
+        G += (int64_t)rel * DO;
+    }
     if (m_beg >= m_end) return;                          // uniform over the block
     const int32_t n_tiles = (m_end - m_beg + RT - 1) / RT;
 
@@ -87,7 +97,7 @@ __global__ __launch_bounds__(ONT) void k_rel_outer_bf16(
             for (int q = 0; q < 8; ++q) {
                 const int32_t r = r0 + q < last ? r0 + q : last;       // past the chunk: its last run again
                 xi[q] = xidx ? xidx[r] : r;
-                gi[q] = gidx[r];
+                gi[q] = gidx ? gidx[r] : r;
             }
             unsigned char *bx = smem + (ti & (NB - 1)) * TB + 8 * mw * BX;
             unsigned char *bg = smem + (ti & (NB - 1)) * TB + RT * BX + 8 * mw * BG;
@@ -186,7 +196,7 @@ __global__ __launch_bounds__(ONT) void k_rel_outer_bf16(
         block_barrier();
     }
     // register v of lane l: row 8 (v / 4) + 4 (l / 32) + v % 4 and column l % 32 of the 32 x 32 block
-    float *Cr = C + (int64_t)rel * DI * DO;
+    float *Cr = (C_last && rel == n_groups - 1) ? C_last : C + (int64_t)rel * DI * DO;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -199,9 +209,14 @@ __global__ __launch_bounds__(ONT) void k_rel_outer_bf16(
             }
 }
 
+struct OuterArgs {
+    const void *X; int64_t ldx; const int32_t *xidx; const void *G; int64_t ldg; const int32_t *gidx;
+    const int32_t *c_rel, *c_beg, *c_end; int64_t blocks; float *C;
+    int32_t n_groups, rows_total, chunk_rows; float *C_last;
+};
+
 template <int DI, int DO>
-int launch_shape(const kge_partition *p, const void *X, int64_t ldx, const int32_t *xidx, const void *G, int64_t ldg,
-                 float *C, hipStream_t st)
+int launch_shape(const OuterArgs &a, hipStream_t st)
 {
     constexpr size_t lds = (size_t)NB * RT * 2 * (DI + DO);
     static bool attr_set = false;
@@ -210,11 +225,26 @@ int launch_shape(const kge_partition *p, const void *X, int64_t ldx, const int32
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    k_rel_outer_bf16<DI, DO><<<(unsigned)p->n_relc, ONT, lds, st>>>(
-        reinterpret_cast<const uint16_t *>(X), ldx, xidx, reinterpret_cast<const uint16_t *>(G), ldg, p->seg_dst,
-        p->relc_rel, p->relc_beg, p->relc_end, C);
+    KGE_REQUIRE(a.blocks < (1ll << 31), KGE_ERANGE, "outer-product sums: too many blocks");
+    k_rel_outer_bf16<DI, DO><<<(unsigned)a.blocks, ONT, lds, st>>>(
+        reinterpret_cast<const uint16_t *>(a.X), a.ldx, a.xidx, reinterpret_cast<const uint16_t *>(a.G), a.ldg, a.gidx,
+        a.c_rel, a.c_beg, a.c_end, a.C, a.n_groups, a.rows_total, a.chunk_rows, a.C_last);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
+}
+
+int launch_any(const OuterArgs &a, int32_t d_in, int32_t d_out, hipStream_t st)
+{
+    KGE_REQUIRE(rel_outer_bf16_supported(d_in, d_out), KGE_EINVAL, "outer-product sums: shape not supported by this kernel");
+    KGE_REQUIRE(a.ldx % 8 == 0 && a.ldg % 8 == 0 && a.ldx >= d_in && a.ldg >= d_out && ((uintptr_t)a.X % 16) == 0 &&
+                    ((uintptr_t)a.G % 16) == 0,
+                KGE_EINVAL, "outer-product sums: rows must be 16-byte aligned");
+    if (d_in == 256) {
+        if (d_out == 256) return launch_shape<256, 256>(a, st);
+        return launch_shape<256, 128>(a, st);
+    }
+    if (d_out == 256) return launch_shape<128, 256>(a, st);
+    return launch_shape<128, 128>(a, st);
 }
 
 }  // namespace
@@ -229,15 +259,24 @@ bool rel_outer_bf16_supported(int32_t d_in, int32_t d_out)
 int launch_rel_outer_rows_bf16(const kge_partition *p, const void *X, int64_t ldx, const int32_t *xidx, const void *G,
                                int64_t ldg, int32_t d_in, int32_t d_out, float *C, hipStream_t st)
 {
-    KGE_REQUIRE(rel_outer_bf16_supported(d_in, d_out), KGE_EINVAL, "relation gradient: shape not supported by this kernel");
-    KGE_REQUIRE(ldx % 8 == 0 && ldg % 8 == 0 && ldx >= d_in && ldg >= d_out && ((uintptr_t)X % 16) == 0 &&
-                    ((uintptr_t)G % 16) == 0,
-                KGE_EINVAL, "relation gradient: rows must be 16-byte aligned");
     if (p->n_relc == 0) return KGE_OK;
-    if (d_in == 256) {
-        if (d_out == 256) return launch_shape<256, 256>(p, X, ldx, xidx, G, ldg, C, st);
-        return launch_shape<256, 128>(p, X, ldx, xidx, G, ldg, C, st);
-    }
-    if (d_out == 256) return launch_shape<128, 256>(p, X, ldx, xidx, G, ldg, C, st);
-    return launch_shape<128, 128>(p, X, ldx, xidx, G, ldg, C, st);
+    const OuterArgs a{X, ldx, xidx, G, ldg, p->seg_dst, p->relc_rel, p->relc_beg, p->relc_end, p->n_relc, C, 0, 0, 0, nullptr};
+    return launch_any(a, d_in, d_out, st);
+}
+
+// C[g] (d_in x d_out fp32, zeroed by the caller) += X^T Y_g for every column block g < n_groups of Y's rows
+// (Y: bf16 [rows][ldy], block g = columns [g d_out, (g + 1) d_out)); the last block's sum goes to C_last when that is
+// non-null (the weight gradients of Eq. 2: X = the layer input, Y = [dP | G], C = dV, C_last = dW_0).
+int launch_col_blocks_outer_bf16(const void *X, int64_t rows, const void *Y, int64_t ldy, int32_t n_groups,
+                                 int32_t d_in, int32_t d_out, float *C, float *C_last, hipStream_t st)
+{
+    if (rows == 0 || n_groups == 0) return KGE_OK;
+    KGE_REQUIRE(rows < (1ll << 31) - 65536 && ldy >= (int64_t)n_groups * d_out, KGE_ERANGE, "outer-product sums: bad row count or pitch");
+    // every chunk ends in one atomic accumulation of a whole d_in x d_out tile: long chunks, as long as about two
+    // blocks per compute unit are left
+    int32_t chunk = 8192;
+    while (chunk > 2048 && cdiv(rows, chunk) * n_groups < 512) chunk /= 2;
+    const OuterArgs a{X, d_in, nullptr, Y, ldy, nullptr, nullptr, nullptr, nullptr, cdiv(rows, chunk) * n_groups, C,
+                      n_groups, (int32_t)rows, chunk, C_last};
+    return launch_any(a, d_in, d_out, st);
 }
