@@ -1227,7 +1227,10 @@ static int launch_coeff_seg(const kge_partition *p, const void *P, const float *
     const int nb = (B + gbc - 1) / gbc;
 #define CS_ARGS p->seg_ptr, p->seg_dst, p->inv_c, p->col_src, S, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, \
                 P, G, B, d, gbc, seg_scratch, partial, active
-    if (nb >= 4) k_coeff_seg<BF16, LPR, 4, 2><<<grid, 64 * WPB, 0, st>>>(CS_ARGS);
+    // base slots x edges in flight per wavefront: with many bases, eight slots of one edge at a time (most runs
+    // have one edge; 212 against 225 ms per launch at 25 M runs, 64 bases, d = 256; 4 x 1: 221, 8 x 2: 220, 16 x 1: 215)
+    if (nb >= 8) k_coeff_seg<BF16, LPR, 8, 1><<<grid, 64 * WPB, 0, st>>>(CS_ARGS);
+    else if (nb >= 4) k_coeff_seg<BF16, LPR, 4, 2><<<grid, 64 * WPB, 0, st>>>(CS_ARGS);
     else if (nb >= 2) k_coeff_seg<BF16, LPR, 2, 4><<<grid, 64 * WPB, 0, st>>>(CS_ARGS);
     else k_coeff_seg<BF16, LPR, 1, 8><<<grid, 64 * WPB, 0, st>>>(CS_ARGS);
 #undef CS_ARGS
