@@ -364,8 +364,15 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
         const float *Hprev = L.dropout > 0.0f ? (const float *)(ws + w.off_Hd[l])
                                               : l > 0 ? (const float *)(ws + w.off_H[l - 1]) : H0;
         const float *Gl = gin;
+        bool g_bf = false;           // the bf16 copy of G is already behind dP's columns
         if (L.act != KGE_ACT_IDENTITY) {
-            rc = launch_act_backward(gin, Hl, L.act, p->n_vert * (int64_t)L.d_out, G, st);
+            if (bf) {
+                rc = launch_act_backward_append_bf16(gin, Hl, L.act, p->n_vert, L.d_out,
+                                                     L.order == KGE_ORDER_RELATION_WEIGHTS ? 0 : L.n_bases, G, dP, st);
+                g_bf = true;
+            } else {
+                rc = launch_act_backward(gin, Hl, L.act, p->n_vert * (int64_t)L.d_out, G, st);
+            }
             if (rc != KGE_OK) return rc;
             Gl = G;
         }
@@ -381,7 +388,7 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
             const bool need_in = l > 0 || dH0;
             float *dst = l > 0 ? dHbuf[l & 1] : dH0;
             if (bf) {
-                rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, 0, dP, st);          // Gbf [N][d_out]
+                if (!g_bf) rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, 0, dP, st);          // Gbf [N][d_out]
                 if (rc != KGE_OK) return rc;
                 rc = launch_rel_outer_bf16(p, p->seg_zrow ? ws + w.off_Hbf[l] : Z, p->seg_zrow, dP, L.d_out, L.d_in, L.d_out, C, st);
             } else {
@@ -422,7 +429,7 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
         const int64_t bd = (int64_t)L.n_bases * L.d_out;
         if (bf && gather_transpose_bf16_supported(L.n_bases, L.d_out)) {
             // the bf16 copy of G first (behind the dP columns of the same matrix): the transposed sums gather it
-            rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, L.n_bases, dP, st);
+            if (!g_bf) rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, L.n_bases, dP, st);
             if (rc != KGE_OK) return rc;
             rc = launch_gather_transpose_bf16(p, (const uint16_t *)dP + bd, bd + L.d_out, L.a, L.n_bases, L.d_out, dP,
                                               bd + L.d_out, part, kge_cgraph_layer(cg, l), st);
@@ -431,7 +438,7 @@ extern "C" int kge_rgcn_backward(const kge_partition *p, const kge_cgraph *cg, c
             rc = launch_gather_transpose(p, Gl, L.a, L.n_bases, L.d_out, dP, bf ? bd + L.d_out : bd, bf, part,
                                          kge_cgraph_layer(cg, l), st);
             if (rc != KGE_OK) return rc;
-            if (bf) rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, L.n_bases, dP, st);
+            if (bf && !g_bf) rc = launch_append_g_bf16(Gl, p->n_vert, L.d_out, L.n_bases, dP, st);
             if (rc != KGE_OK) return rc;
         }
         if (bf) {

@@ -118,6 +118,9 @@ int launch_cvt_weights_bf16(const float *V, const float *W0, int32_t d_in, int32
                             void *Wbf /*[d_in][nc]*/, void *WbfT /*[nc][d_in]*/, hipStream_t st);
 // G (fp32 [N][d_out]) -> last d_out columns of X (bf16 [N][(B+1) d_out])
 int launch_append_g_bf16(const float *G, int64_t N, int32_t d_out, int32_t B, void *X, hipStream_t st);
+// G = act'(Hout) * dHout in fp32 and, in the same pass, its bf16 copy behind the B d_out columns of X
+int launch_act_backward_append_bf16(const float *dHout, const float *Hout, int act, int64_t N, int32_t d_out, int32_t B,
+                                    float *G, void *X, hipStream_t st);
 int launch_project_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out, int32_t B,
                         const void *WbfT, void *P, float *Self, hipStream_t st);
 int launch_weight_grad_bf16(const void *Hbf, int64_t N, int32_t d_in, int32_t d_out, int32_t B,

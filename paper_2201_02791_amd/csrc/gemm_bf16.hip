@@ -545,6 +545,29 @@ __global__ void k_append_g(const float4 *__restrict__ G, int64_t N, int32_t d_ou
     }
 }
 
+// The activation's backward pass with both outputs: G = dH (masked by Hout > 0 for ReLU) in fp32, and its bf16
+// copy behind the B d_out columns of dP in X (one pass over dH and Hout instead of a second one over G)
+__global__ void k_act_backward_append(const float4 *__restrict__ dH, const float4 *__restrict__ Hout, int act,
+                                      int64_t N, int32_t d_out, int32_t bd, int32_t nc, float4 *__restrict__ G,
+                                      uint16_t *__restrict__ X)
+{
+    const int d4 = d_out >> 2;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x, n4 = N * d4;
+    for (; i < n4; i += stride) {
+        const int64_t r = i / d4;
+        const int c = (int)(i - r * d4) * 4;
+        float4 g = dH[i];
+        if (act == KGE_ACT_RELU) {
+            const float4 h = Hout[i];
+            g.x = h.x > 0.f ? g.x : 0.f; g.y = h.y > 0.f ? g.y : 0.f;
+            g.z = h.z > 0.f ? g.z : 0.f; g.w = h.w > 0.f ? g.w : 0.f;
+        }
+        G[i] = g;
+        *reinterpret_cast<uint2 *>(X + r * nc + bd + c) = make_uint2(pack2(g.x, g.y), pack2(g.z, g.w));
+    }
+}
+
 // [V_1 .. V_B | W0] (fp32) -> Wbf [d_in][nc] and WbfT [nc][d_in], bf16
 __global__ void k_cvt_weights(const float *__restrict__ V, const float *__restrict__ W0, int32_t d_in,
                               int32_t d_out, int32_t B, uint16_t *__restrict__ Wbf, uint16_t *__restrict__ WbfT)
@@ -621,6 +644,22 @@ int launch_append_g_bf16(const float *G, int64_t N, int32_t d_out, int32_t B, vo
     KGE_PROF("append_g", st);
     k_append_g<<<(unsigned)blocks, 256, 0, st>>>(reinterpret_cast<const float4 *>(G), N, d_out, B * d_out,
                                                  (B + 1) * d_out, reinterpret_cast<uint16_t *>(X));
+    KGE_LAUNCH_CHECK();
+    return KGE_OK;
+}
+
+int launch_act_backward_append_bf16(const float *dHout, const float *Hout, int act, int64_t N, int32_t d_out, int32_t B,
+                                    float *G, void *X, hipStream_t st)
+{
+    const int64_t n4 = N * (d_out / 4);
+    if (n4 == 0) return KGE_OK;
+    int64_t blocks = cdiv(n4, 256);
+    if (blocks > 65536) blocks = 65536;
+    KGE_PROF("act_bwd", st);
+    k_act_backward_append<<<(unsigned)blocks, 256, 0, st>>>(reinterpret_cast<const float4 *>(dHout),
+                                                            reinterpret_cast<const float4 *>(Hout), act, N, d_out,
+                                                            B * d_out, (B + 1) * d_out, reinterpret_cast<float4 *>(G),
+                                                            reinterpret_cast<uint16_t *>(X));
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
