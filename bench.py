@@ -106,7 +106,7 @@ def kernel_work(name, part, spec, dims, B, ep, n_pos, n_neg, cone=None, order="p
         elif name == "act_bwd":
             if spec.acts[l] == 0:
                 continue
-            w = {"bytes": 12.0 * N * do}
+            w = {"bytes": (12.0 + (2.0 if ep == 2 else 0.0)) * N * do}   # dH and H read, G written (bf16 messages: its bf16 copy too)
         elif name == "coeff_reduce":
             w = {"bytes": 4.0 * S * B}
         if w is not None:
