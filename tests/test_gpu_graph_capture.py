@@ -17,14 +17,15 @@ def say(*a):
     print("[gpu-case]", *a, file=sys.stderr, flush=True)
 
 
-@pytest.mark.parametrize("order,bf16,cone", [(0, False, False), (2, False, True), (2, True, True), (0, True, False)],
+@pytest.mark.parametrize("order,bf16,cone,d", [(0, False, False, 64), (2, False, True, 64), (2, True, True, 64),
+                                               (0, True, False, 64), (2, True, True, 128), (0, True, False, 128)],
                          ids=["project_first_f32", "relation_weights_f32_subgraph", "relation_weights_bf16_subgraph",
-                              "project_first_bf16"])
-def test_step_replays_from_a_hip_graph(order, bf16, cone):
+                              "project_first_bf16", "relation_weights_bf16_subgraph_d128", "project_first_bf16_d128"])
+def test_step_replays_from_a_hip_graph(order, bf16, cone, d):
     import torch
-    say("graph capture, order", order, "bf16", bf16, "sub-graph", cone)
+    say("graph capture, order", order, "bf16", bf16, "sub-graph", cone, "d", d)
     spec = synth.scaled(synth.WORKLOADS[4 if bf16 else 0], name="graph", seed=31, n_entities=3000, n_relations=12,
-                        n_triples=20000, d=64, n_bases=4, n_pos=300, n_neg=4, neg_mode=1, n_parts=2, part_id=0,
+                        n_triples=20000, d=d, n_bases=4, n_pos=300, n_neg=4, neg_mode=1, n_parts=2, part_id=0,
                         acts=[1, 0], feature_std=0.5)
     head, rel, tail = synth.make_triples(spec)
     gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=order, cone=cone)     # eager step
