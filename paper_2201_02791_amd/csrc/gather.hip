@@ -962,27 +962,52 @@ __global__ void k_coeff_finish(int32_t n_hv, const int32_t *__restrict__ hv_row,
     seg_out[row * B + b] = inv_c[row] * s;
 }
 
-// da[r][b] += sum of seg_out[s][b] over a strided share of relation r's runs.
-// grid = (2R, n_split); block = 256 threads laid out as (256 / BP) run slots x BP bases.
-__global__ __launch_bounds__(256) void k_coeff_reduce(const int32_t *__restrict__ rel_ptr,
-                                                      const float *__restrict__ seg_out, int32_t B,
-                                                      int32_t BP, float *__restrict__ da)
+// da[r][b] += sum of seg_out[s][b] over one chunk of relation r's runs (the partition's chunk list: every chunk lies
+// in one relation).  A run's B values are covered by TPR threads of V floats each (V = 4 when B is a multiple
+// of 4); the block's 256 / TPR run slots walk the chunk with four rows in flight per thread.
+template <int V>
+__global__ __launch_bounds__(256) void k_coeff_reduce(const int32_t *__restrict__ c_rel, const int32_t *__restrict__ c_beg,
+                                                      const int32_t *__restrict__ c_end,
+                                                      const float *__restrict__ seg_out, int32_t B, int32_t TPR,
+                                                      float *__restrict__ da)
 {
-    __shared__ float red[256];
-    const int r = blockIdx.x;
-    const int slots = 256 / BP;
-    const int b = threadIdx.x % BP, slot = threadIdx.x / BP;
-    const int64_t beg = rel_ptr[r], end = rel_ptr[r + 1];
-    float acc = 0.f;
-    if (b < B)
-        for (int64_t s = beg + (int64_t)blockIdx.y * slots + slot; s < end; s += (int64_t)gridDim.y * slots)
-            acc += seg_out[s * B + b];
-    red[threadIdx.x] = acc;
+    __shared__ float red[256 * V];
+    const int r = c_rel[blockIdx.x];
+    const int64_t beg = c_beg[blockIdx.x], end = c_end[blockIdx.x];
+    const int slots = 256 / TPR;
+    const int b = (threadIdx.x % TPR) * V, slot = threadIdx.x / TPR;
+    float acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.f;
+    if (b < B) {
+        int64_t s = beg + slot;
+        for (; s + 3 * slots < end; s += 4 * slots) {
+            float x[4][V];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float *q = seg_out + (s + (int64_t)u * slots) * B + b;
+                if (V == 4) { const float4 t4 = *reinterpret_cast<const float4 *>(q); x[u][0] = t4.x; x[u][1 % V] = t4.y; x[u][2 % V] = t4.z; x[u][3 % V] = t4.w; }
+                else x[u][0] = q[0];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[v] += x[u][v];
+        }
+        for (; s < end; s += slots)
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[v] += seg_out[s * B + b + v];
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) red[threadIdx.x * V + v] = acc[v];
     __syncthreads();
     if (slot == 0 && b < B) {
-        float t = 0.f;
-        for (int k = 0; k < slots; ++k) t += red[k * BP + b];
-        if (t != 0.f) unsafeAtomicAdd(&da[(int64_t)r * B + b], t);
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            float t = 0.f;
+            for (int k = 0; k < slots; ++k) t += red[(k * TPR + threadIdx.x) * V + v];
+            if (t != 0.f) unsafeAtomicAdd(&da[(int64_t)r * B + b + v], t);
+        }
     }
 }
 
@@ -1265,12 +1290,12 @@ int launch_coeff_grad(const kge_partition *p, const void *P, int msg_bf16, const
         k_coeff_finish<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, p->inv_c, B, seg_scratch, p->seg_dst, active);
         KGE_LAUNCH_CHECK();
     }
-    const int BP = pow2_at_least(B);
-    int n_split = (int)(S / 65536) + 1;       // enough blocks for the most frequent relation
-    if (n_split > 256) n_split = 256;
-    dim3 rgrid((unsigned)R2, (unsigned)n_split, 1);
+    if (p->n_relc == 0) return KGE_OK;
     KGE_PROF("coeff_reduce", st);
-    k_coeff_reduce<<<rgrid, 256, 0, st>>>(p->rel_ptr, seg_scratch, B, BP, da);
+    if (B % 4 == 0) k_coeff_reduce<4><<<(unsigned)p->n_relc, 256, 0, st>>>(p->relc_rel, p->relc_beg, p->relc_end, seg_scratch, B,
+                                                                    pow2_at_least(B / 4), da);
+    else k_coeff_reduce<1><<<(unsigned)p->n_relc, 256, 0, st>>>(p->relc_rel, p->relc_beg, p->relc_end, seg_scratch, B,
+                                                                pow2_at_least(B), da);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
