@@ -159,7 +159,7 @@ __global__ __launch_bounds__(RNT) void k_rel_rows_bf16(
                 for (int row = srow; row < RT; row += GT / NC8) {
                     if (m0 + row < m_end) {
                         const u32x4 v = *reinterpret_cast<const u32x4 *>(sb + (size_t)row * PS + c8 * 8);
-                        *reinterpret_cast<u32x4 *>(out + (m0 + row) * ldo + c8 * 8) = v;
+                        __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(out + (m0 + row) * ldo + c8 * 8));
                     }
                 }
             }
