@@ -71,6 +71,10 @@ struct kge_partition {
     // and into ranges of at most KGE_REL_RANGE runs (what one block of the bf16 per-run products takes)
     int32_t n_relr;
     int32_t *relr_rel, *relr_beg, *relr_end;
+    // the same kind of ranges ordered by slab of the destination range first (KGE_REL_SLAB vertices), relation
+    // second: the order in which the transposed per-run products gather the output-gradient rows
+    int32_t n_rels;
+    int32_t *rels_rel, *rels_beg, *rels_end;
     // where the mean of run s can be read when the layer input X [N][d] and the run means Z [S][d] are one
     // matrix [X; Z]: a run of a single edge has its source's row of X as its mean (row col_src), any other
     // run row N + s.  NULL if N + S does not fit 31 bits.
@@ -86,6 +90,8 @@ struct kge_partition {
 #define KGE_REL_CHUNK 2048
 #define KGE_REL_TILE 128
 #define KGE_REL_RANGE 4096
+// vertices per slab of the destination range by which those ranges are ordered
+#define KGE_REL_SLAB 262144
 
 // Optional per-kernel timing with HIP events on the launch stream (kge_profile_enable).
 struct KgeProfScope {
@@ -201,7 +207,7 @@ int launch_apply_relation_weights_t(const kge_partition *p, const float *G, cons
 // NULL): Zbf is then the matrix [X; Z] and run s reads its row zrow[s]
 bool rel_rows_bf16_supported(int32_t K, int32_t N);
 int launch_rel_rows_bf16(const kge_partition *p, const void *A, int64_t lda, const int32_t *aidx, const void *Wk,
-                         int32_t K, int32_t N, void *out, hipStream_t st);
+                         int32_t K, int32_t N, void *out, hipStream_t st, bool by_dst_slab = false);
 int launch_all_rows_bf16(const void *A, int64_t rows, const void *Wk, int32_t n_groups, int32_t K, int32_t N,
                          void *out, hipStream_t st);
 int launch_apply_relation_weights_bf16(const kge_partition *p, const void *Zbf, const int32_t *zrow, const void *WbT,

@@ -899,7 +899,7 @@ int launch_apply_relation_weights_t_bf16(const kge_partition *p, const void *Gbf
     EpiRowsBF16Staged ep{reinterpret_cast<uint16_t *>(dZ), p->n_seg, d_in};
     KGE_PROF("apply_rel_t", st);
     if (rel_rows_bf16_supported(d_out, d_in))
-        return launch_rel_rows_bf16(p, Gbf, ldg, p->seg_dst, Wb, d_out, d_in, dZ, st);
+        return launch_rel_rows_bf16(p, Gbf, ldg, p->seg_dst, Wb, d_out, d_in, dZ, st, true);
     if (tiles_n == 1 && d_out % 64 == 0 && d_in % 64 == 0)   // two tiles in flight: the contraction must be whole pairs of them
         return launch_gemm<true, EpiRowsBF16Staged, TN, 64, true>(A, Bm, ep, d_out, cdiv(d_out, TK) * TK, p->n_relt, tiles_n, 1,
                                                                   st, nullptr, nullptr, nullptr, p->relt_rel, p->relt_beg,

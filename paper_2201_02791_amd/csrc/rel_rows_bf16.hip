@@ -214,8 +214,10 @@ __global__ __launch_bounds__(RNT) void k_rel_rows_bf16(
     }
 }
 
+struct RangeList { int32_t n; const int32_t *rel, *beg, *end; };
+
 template <int NP>
-int launch_np(const kge_partition *p, int32_t n_groups, int64_t rows_total, const void *A, int64_t lda,
+int launch_np(const RangeList *p, int32_t n_groups, int64_t rows_total, const void *A, int64_t lda,
               const int32_t *aidx, const void *Wk, int32_t N, void *out, int64_t ldo, hipStream_t st)
 {
     const int32_t K = 32 * NP;
@@ -226,12 +228,12 @@ int launch_np(const kge_partition *p, int32_t n_groups, int64_t rows_total, cons
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)((size_t)2 * RT * (K + 8 + 256 + 8) * 2)));
         attr_set = true;
     }
-    const int64_t blocks = p ? p->n_relr : n_groups * cdiv(rows_total, KGE_REL_RANGE);
+    const int64_t blocks = p ? p->n : n_groups * cdiv(rows_total, KGE_REL_RANGE);
     KGE_REQUIRE(blocks < (1ll << 31), KGE_ERANGE, "per-run product: too many blocks");
     k_rel_rows_bf16<NP><<<(unsigned)blocks, RNT, lds, st>>>(
         reinterpret_cast<const uint16_t *>(A), lda, aidx, reinterpret_cast<const uint16_t *>(Wk), (int64_t)N * K, N,
-        reinterpret_cast<uint16_t *>(out), ldo, p ? p->relr_rel : nullptr, p ? p->relr_beg : nullptr,
-        p ? p->relr_end : nullptr, n_groups, rows_total);
+        reinterpret_cast<uint16_t *>(out), ldo, p ? p->rel : nullptr, p ? p->beg : nullptr,
+        p ? p->end : nullptr, n_groups, rows_total);
     KGE_LAUNCH_CHECK();
     return KGE_OK;
 }
@@ -245,17 +247,21 @@ bool rel_rows_bf16_supported(int32_t K, int32_t N)
 
 // out[s] = A[aidx ? aidx[s] : s] * Wk[rel(s)]^T for every run s;  A rows `lda` elements apart (16-byte aligned),
 // Wk: bf16 [2R][N][K], out: bf16 [S][N].  Shapes outside rel_rows_bf16_supported are the caller's to route elsewhere.
+// by_dst_slab: walk the ranges in the order of the destination slabs (for rows gathered by destination)
 int launch_rel_rows_bf16(const kge_partition *p, const void *A, int64_t lda, const int32_t *aidx, const void *Wk,
-                         int32_t K, int32_t N, void *out, hipStream_t st)
+                         int32_t K, int32_t N, void *out, hipStream_t st, bool by_dst_slab)
 {
     KGE_REQUIRE(rel_rows_bf16_supported(K, N), KGE_EINVAL, "per-run product: shape not supported by this kernel");
     KGE_REQUIRE(lda % 8 == 0 && ((uintptr_t)A % 16) == 0 && ((uintptr_t)Wk % 16) == 0 && ((uintptr_t)out % 16) == 0,
                 KGE_EINVAL, "per-run product: operands must be 16-byte aligned");
     if (p->n_relr == 0) return KGE_OK;
+    const RangeList plain{p->n_relr, p->relr_rel, p->relr_beg, p->relr_end};
+    const RangeList slabs{p->n_rels, p->rels_rel, p->rels_beg, p->rels_end};
+    const RangeList *rl = by_dst_slab ? &slabs : &plain;
     switch (K) {
-    case 64: return launch_np<2>(p, 0, 0, A, lda, aidx, Wk, N, out, N, st);
-    case 128: return launch_np<4>(p, 0, 0, A, lda, aidx, Wk, N, out, N, st);
-    default: return launch_np<8>(p, 0, 0, A, lda, aidx, Wk, N, out, N, st);
+    case 64: return launch_np<2>(rl, 0, 0, A, lda, aidx, Wk, N, out, N, st);
+    case 128: return launch_np<4>(rl, 0, 0, A, lda, aidx, Wk, N, out, N, st);
+    default: return launch_np<8>(rl, 0, 0, A, lda, aidx, Wk, N, out, N, st);
     }
 }
 
