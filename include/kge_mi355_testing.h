@@ -21,6 +21,13 @@ int kge_eval_debug_scores(const float *H, int64_t n_entities, int32_t d, const f
                           const int32_t *test_h, const int32_t *test_r, const int32_t *test_t, int64_t n_test,
                           void *workspace, size_t ws_bytes, float *scores, float *answer_score, void *stream);
 
+/* Partitions built after this call order the run ranges of the transposed per-run products by slabs of
+ * `vertices` destinations and cut a relation's runs at slab borders once it has `min_runs` runs or more (the
+ * library's own values: 262,144 vertices, two full ranges of runs; <= 0 restores them).  It lets a small graph
+ * take the code path that otherwise only a partition of more than 262,144 vertices takes.  Process-wide, not
+ * thread-safe. */
+void kge_test_set_rel_slab(int32_t vertices, int32_t min_runs);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ EXPORTED = ["kge_build_partition", "kge_partition_info", "kge_partition_export",
             "kge_optimizer_step_rows", "kge_eval_filter_create", "kge_eval_filter_destroy",
             "kge_eval_workspace_bytes", "kge_eval_rank_all", "kge_eval_rank_candidates", "kge_eval_metrics",
             "kge_eval_debug_scores", "kge_eval_rank_all_static", "kge_cgraph_input_rows", "kge_score_index_create", "kge_score_index_destroy",
-            "kge_partition_bad_ids"]
+            "kge_partition_bad_ids", "kge_test_set_rel_slab"]
 
 ACT_IDENTITY, ACT_RELU = 0, 1
 ORDER_PROJECT_FIRST, ORDER_RELATION_WEIGHTS = 0, 2
@@ -149,6 +149,12 @@ class Partition:
             self.destroy()
         except Exception:
             pass
+
+
+def set_rel_slab_for_tests(vertices: int, min_runs: int = 0):
+    """Test hook: slab size (destinations) and cutting threshold (runs) of the range order that partitions built
+    afterwards give the transposed per-run products; (0, 0) restores the library's values."""
+    load().kge_test_set_rel_slab(C.c_int32(vertices), C.c_int32(min_runs))
 
 
 def build_partition(head, rel, tail, n_entities: int, n_relations: int, n_parts: int = 1,

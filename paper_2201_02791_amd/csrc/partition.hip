@@ -13,6 +13,9 @@
 #include <algorithm>
 #include "sort_scan.h"
 
+// slab of the destination range by which the transposed products' ranges are ordered (a test hook can shrink it)
+static int64_t g_rel_slab = KGE_REL_SLAB, g_rel_min_runs = 0;
+
 namespace {
 
 __device__ __forceinline__ uint32_t part_of_head(int32_t head, uint32_t n_parts)
@@ -543,7 +546,7 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
         // bf16 rows at d = 256): the transposed products 4.95 -> 4.68 ms per launch at 25 M runs with four slabs.  A relation with fewer than two ranges' worth of runs stays whole, in the
         // first slab's group: cutting it would only make blocks with little to do (with those cut as well the
         // forward products lost what the transposed ones gained).
-        const int64_t n_slabs = N > KGE_REL_SLAB ? cdiv(N, KGE_REL_SLAB) : 1;
+        const int64_t n_slabs = N > g_rel_slab ? cdiv(N, g_rel_slab) : 1;
         const int64_t slab = cdiv(N, n_slabs);
         std::vector<int32_t> h_dst;
         if (n_slabs > 1) {
@@ -557,7 +560,7 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
                 int32_t *c = cut.data() + r * (n_slabs + 1);
                 c[0] = h_rel_ptr[r];
                 c[n_slabs] = h_rel_ptr[r + 1];
-                const bool whole = (int64_t)h_rel_ptr[r + 1] - h_rel_ptr[r] < 2 * (int64_t)piece;
+                const bool whole = (int64_t)h_rel_ptr[r + 1] - h_rel_ptr[r] < (g_rel_min_runs > 0 ? g_rel_min_runs : 2 * (int64_t)piece);
                 for (int64_t k = 1; k < n_slabs; ++k) {
                     if (whole) { c[k] = h_rel_ptr[r + 1]; continue; }
                     const int32_t *b0 = h_dst.data() + h_rel_ptr[r], *b1 = h_dst.data() + h_rel_ptr[r + 1];
@@ -634,6 +637,12 @@ int build_impl(const int32_t *h_head, const int32_t *h_rel, const int32_t *h_tai
 }  // namespace
 
 // ------------------------------------------------------------------ ABI
+extern "C" void kge_test_set_rel_slab(int32_t vertices, int32_t min_runs)
+{
+    g_rel_slab = vertices > 0 ? vertices : KGE_REL_SLAB;
+    g_rel_min_runs = min_runs > 0 ? min_runs : 0;
+}
+
 static thread_local char g_err[512] = "";
 
 void kge_set_error(const char *fmt, ...)

@@ -200,6 +200,28 @@ def test_bf16_relation_weights_mixed_widths(kb, orc, d_in, d):
     say("errs vs the exact oracle", errs)
 
 
+def test_bf16_ranges_ordered_by_destination_slab(kb, orc):
+    """The transposed per-run products walk run ranges that are ordered by slab of the destination range and cut
+    at slab borders; only a partition of more than 262,144 vertices gets more than one slab.  With the test hook a
+    small graph gets eleven slabs and every relation is cut: the step must come out as without slabs (every run in
+    exactly one range), to the bf16 tolerance against the exact oracle."""
+    say("bf16 relation order with destination slabs")
+    spec = synth.scaled(synth.WORKLOADS[4], name="bf16-slabs", seed=13, n_entities=2100, n_relations=3, n_triples=24000,
+                        d=128, n_bases=4, n_pos=128, n_neg=4, n_parts=1, part_id=0, acts=[1, 0])
+    head, rel, tail = synth.make_triples(spec)
+    kb.set_rel_slab_for_tests(200, 40)
+    try:
+        gp, ts, params, pos = gpu_step(spec, head, rel, tail, order=RELW)
+    finally:
+        kb.set_rel_slab_for_tests(0, 0)
+    op, res = oracle_step(orc, spec, head, rel, tail, params, pos)
+    assert_partition_equal(gp, op)
+    n_adopted, res = align_mask_decisions(orc, ts, op, res, params, [1, 0], True, True)
+    say("mask decisions inside the rounding band, taken as the kernel took them:", n_adopted)
+    errs = assert_step_close(ts, res, TOL_BF16, TOL_BF16)
+    say("errs vs the exact oracle", errs)
+
+
 def test_bf16_run_means(kb, orc):
     """Run means z of the first layer (stored in bf16) against the exact means: each element within two
     bf16 roundings (of the input, of the mean) of mean|h| over its run, and 2e-2 as a tensor.  Runs of one edge
