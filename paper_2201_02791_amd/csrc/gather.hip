@@ -141,6 +141,16 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
     float acc[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+    // the row's self-loop part is fetched ahead of the edges (it is only needed at the end; loaded there it would
+    // add one more memory round trip to every wavefront)
+    float4 selfv[VEC / 4];
+#pragma unroll
+    for (int v4 = 0; v4 < VEC / 4; ++v4) selfv[v4] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (g == 0 && kact && rw.unit < 0) {
+#pragma unroll
+        for (int v4 = 0; v4 < VEC / 4; ++v4)
+            selfv[v4] = *reinterpret_cast<const float4 *>(Self + rw.row * d + kl * VEC + 4 * v4);
+    }
 
     for (int32_t e0 = rw.beg; e0 < rw.end; e0 += 64) {
         const int cnt = min(64, rw.end - e0);
@@ -203,7 +213,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
         const int64_t o = rw.row * d + kl * VEC;
 #pragma unroll
         for (int v4 = 0; v4 < VEC; v4 += 4) {
-            float4 s = *reinterpret_cast<const float4 *>(Self + o + v4);
+            const float4 s = selfv[v4 / 4];
             float4 r = make_float4(act_apply(act, acc[v4] + s.x), act_apply(act, acc[v4 + 1] + s.y),
                                    act_apply(act, acc[v4 + 2] + s.z), act_apply(act, acc[v4 + 3] + s.w));
             *reinterpret_cast<float4 *>(out + o + v4) = r;
