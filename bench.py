@@ -33,7 +33,7 @@ DEFAULT_LR = {4: 1e-3}
 
 
 def kernel_work(name, part, spec, dims, B, ep, n_pos, n_neg, cone=None, order="project", single_runs=0,
-                n_input_rows=None):
+                n_input_rows=None, dropout=0.0):
     """Algorithmic work of ONE launch of a kernel: what the method itself must move or compute in this
     formulation, as the mean over the layers that launch it.  Returns a dict with "bytes" and / or "flops"
     (a contraction has both and the caller reports whichever ceiling takes longer at its peak), "unit"
@@ -70,6 +70,8 @@ def kernel_work(name, part, spec, dims, B, ep, n_pos, n_neg, cone=None, order="p
             w = {"bytes": (ne - skip) * (ep * di + 4.0) + S * 12.0 + (S - single_runs) * ep * di}
         elif name == "sum_runs":   # per run: u row + run id; per vertex: ptr + Self read + output write
             w = {"bytes": ns * (ep * do + 4.0) + N * (5.0 + 4.0 * do) + nv * 4.0 * do}
+            if ep == 2 and l + 1 < len(spec.acts) and dropout == 0.0:   # it also writes the next layer's bf16 input
+                w["bytes"] += N * 2.0 * do
         elif name == "sum_edges_out":  # per edge: dz row + (run id, 1/c); per vertex: ptr + Self read + output write
             if l == 0 and spec.fixed_features:
                 continue               # no gradient with respect to fixed features
@@ -399,7 +401,7 @@ def run_workload(graphs, cfg, order="relation", whole=False, dropout=0.0, steps=
         avg_ms = tot_ms / max(calls, 1)
         rec = {"ms_per_step": tot_ms / steps, "launches_per_step": calls / steps, "avg_ms": avg_ms}
         roof = roof_of(kernel_work(name, part, spec, dims, spec.n_bases, ep, n_pos, n_neg, cone, order, single_runs,
-                                   n_input_rows), avg_ms, ep)
+                                   n_input_rows, dropout), avg_ms, ep)
         if roof:
             rec.update(roof)
             if roof["frac"] > 1.0:

@@ -261,6 +261,7 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
     const float *Hin = H0;
     float *Self = (float *)(ws + w.off_self);
     float *part = (float *)(ws + w.off_part);
+    bool hbf_written = false;        // the previous layer has written this layer's bf16 input already
     for (int l = 0; l < n_layers; ++l) {
         const kge_layer &L = layers[l];
         void *P = ws + w.off_P[l];
@@ -287,7 +288,7 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
             if (rc != KGE_OK) return rc;
             if (bf) {
                 void *Hbf = ws + w.off_Hbf[l], *Wbf = ws + w.off_Wbf[l], *WbfT = ws + w.off_WbfT[l];
-                rc = launch_cvt_rows_bf16(Hin, p->n_vert * (int64_t)L.d_in, Hbf, st);
+                if (!hbf_written) rc = launch_cvt_rows_bf16(Hin, p->n_vert * (int64_t)L.d_in, Hbf, st);
                 if (rc != KGE_OK) return rc;
                 rc = launch_cvt_weights_bf16(L.V, L.W0, L.d_in, L.d_out, 0, Wbf, WbfT, st);     // W0 alone, both orientations
                 if (rc != KGE_OK) return rc;
@@ -307,7 +308,11 @@ extern "C" int kge_rgcn_forward(const kge_partition *p, const kge_cgraph *cg, co
                 rc = launch_project(Hin, p->n_vert, L.d_in, L.d_out, 0, L.V, L.W0, nullptr, Self, st);
             }
             if (rc != KGE_OK) return rc;
-            rc = launch_sum_runs(p, U, bf, L.d_out, Self, L.act, out1, out2, part, act_l, st);
+            // the next layer's bf16 input is written by this layer's sums when that layer reads this output as
+            // it is (same order, no dropout in between)
+            hbf_written = bf && !last && layers[l + 1].order == KGE_ORDER_RELATION_WEIGHTS && layers[l + 1].dropout == 0.0f;
+            rc = launch_sum_runs(p, U, bf, L.d_out, Self, L.act, out1, out2, hbf_written ? ws + w.off_Hbf[l + 1] : nullptr,
+                                 part, act_l, st);
             if (rc != KGE_OK) return rc;
             Hin = Hl;
             continue;

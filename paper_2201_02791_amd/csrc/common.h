@@ -181,9 +181,9 @@ int launch_run_mean(const kge_partition *p, const void *H, int32_t d, void *Z, i
                     const uint8_t *active, int skip_single, hipStream_t st);
 // gather.hip, relation-weight order ------------------------------------------
 // out[i] = act( sum over the runs (r, i) of destination i of U[run][:] + Self[i] ); U [S][d] fp32 or bf16;
-// zero rows where active[i] == 0; `partial`: [hv_dr.n_units][d] floats
+// zero rows where active[i] == 0; out_bf16 (optional): a bf16 copy of the same rows; `partial`: [hv_dr.n_units][d] floats
 int launch_sum_runs(const kge_partition *p, const void *U, int u_bf16, int32_t d, const float *Self, int act,
-                    float *out, float *out2, float *partial, const uint8_t *active, hipStream_t st);
+                    float *out, float *out2, void *out_bf16, float *partial, const uint8_t *active, hipStream_t st);
 // out[j] = sum over the edges e out of j of (1/c_e) dZ[run(e)][:] + Self[j]; `partial`: [hv_sm.n_units][d] floats
 int launch_sum_edges_out(const kge_partition *p, const void *dZ, int z_bf16, int32_t d, const float *Self,
                          float *out, float *partial, const uint8_t *active, hipStream_t st);

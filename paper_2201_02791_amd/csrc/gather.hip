@@ -99,8 +99,10 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
     const int32_t *__restrict__ unit_hv,
     const void *__restrict__ P, const float *__restrict__ a, int32_t B, int32_t d, int32_t gb_count,
     const float *__restrict__ Self, int act, float *__restrict__ out, float *__restrict__ out2,
-    float *__restrict__ partial, const uint8_t *__restrict__ active)
+    uint16_t *__restrict__ outbf, float *__restrict__ partial, const uint8_t *__restrict__ active)
 {
+    // outbf (optional): a bf16 copy of the output rows (the next layer's bf16 input, written here instead of by a
+    // conversion pass over `out`)
     constexpr int VEC = MsgRow<BF16>::VEC;
     constexpr int G = 64 / LPR;
     constexpr int U = 8;
@@ -116,6 +118,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
             for (int v4 = 0; v4 < VEC; v4 += 4) {
                 *reinterpret_cast<float4 *>(out + o + v4) = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (out2) *reinterpret_cast<float4 *>(out2 + o + v4) = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (outbf) *reinterpret_cast<uint2 *>(outbf + o + v4) = make_uint2(0u, 0u);
             }
         }
         return;
@@ -129,6 +132,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
             for (int v4 = 0; v4 < VEC; v4 += 4) {
                 *reinterpret_cast<float4 *>(out + o + v4) = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (out2) *reinterpret_cast<float4 *>(out2 + o + v4) = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (outbf) *reinterpret_cast<uint2 *>(outbf + o + v4) = make_uint2(0u, 0u);
             }
         }
         return;
@@ -218,6 +222,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gather_fwd(
                                    act_apply(act, acc[v4 + 2] + s.z), act_apply(act, acc[v4 + 3] + s.w));
             *reinterpret_cast<float4 *>(out + o + v4) = r;
             if (out2) *reinterpret_cast<float4 *>(out2 + o + v4) = r;
+            if (outbf) *reinterpret_cast<uint2 *>(outbf + o + v4) = make_uint2(pack_bf16x2(r.x, r.y), pack_bf16x2(r.z, r.w));
         }
     }
 }
@@ -227,7 +232,7 @@ __global__ void k_gather_fwd_finish(int32_t n_hv, const int32_t *__restrict__ hv
                                     const int32_t *__restrict__ hv_unit_ptr, const float *__restrict__ partial,
                                     int32_t d, const float *__restrict__ Self, int act,
                                     float *__restrict__ out, float *__restrict__ out2,
-                                    const uint8_t *__restrict__ active)
+                                    uint16_t *__restrict__ outbf, const uint8_t *__restrict__ active)
 {
     const int d4 = d >> 2;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -239,6 +244,7 @@ __global__ void k_gather_fwd_finish(int32_t n_hv, const int32_t *__restrict__ hv
         const int64_t oz = (int64_t)hv_row[h] * d + k4;
         *reinterpret_cast<float4 *>(out + oz) = s;
         if (out2) *reinterpret_cast<float4 *>(out2 + oz) = s;
+        if (outbf) *reinterpret_cast<uint2 *>(outbf + oz) = make_uint2(0u, 0u);
         return;
     }
     for (int32_t u = hv_unit_ptr[h]; u < hv_unit_ptr[h + 1]; ++u) {
@@ -251,6 +257,7 @@ __global__ void k_gather_fwd_finish(int32_t n_hv, const int32_t *__restrict__ hv
                                  act_apply(act, s.z + sf.z), act_apply(act, s.w + sf.w));
     *reinterpret_cast<float4 *>(out + o) = r;
     if (out2) *reinterpret_cast<float4 *>(out2 + o) = r;
+    if (outbf) *reinterpret_cast<uint2 *>(outbf + o) = make_uint2(pack_bf16x2(r.x, r.y), pack_bf16x2(r.z, r.w));
 }
 
 // ------------------------------------------------------------------ activation backward
@@ -1053,7 +1060,7 @@ int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, c
     {
         KGE_PROF("gather_fwd", st);
 #define GF_ARGS p->dm_ptr, p->dm_src, p->dm_rel, p->dm_invc, N, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, \
-                P, a, B, d, gbc, Self, act, out, out2, partial, active
+                P, a, B, d, gbc, Self, act, out, out2, nullptr, partial, active
         if (msg_bf16) { DISPATCH_LPR(lpr, (k_gather_fwd<true, L, false><<<grid, 64 * WPB, 0, st>>>(GF_ARGS))); }
         else { DISPATCH_LPR(lpr, (k_gather_fwd<false, L, false><<<grid, 64 * WPB, 0, st>>>(GF_ARGS))); }
 #undef GF_ARGS
@@ -1063,7 +1070,7 @@ int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, c
         KGE_PROF("gather_fwd_fin", st);
         const int64_t n = (int64_t)hx.n_hv * (d / 4);
         k_gather_fwd_finish<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, d,
-                                                                   Self, act, out, out2, active);
+                                                                   Self, act, out, out2, nullptr, active);
         KGE_LAUNCH_CHECK();
     }
     return KGE_OK;
@@ -1072,7 +1079,7 @@ int launch_gather_forward(const kge_partition *p, const void *P, int msg_bf16, c
 // out[i] = act( sum_{q in row i of the view} w_q X[idx_q][:] + Self[i] ),  X rows of d elements (fp32 or bf16)
 static int launch_row_sum(const int32_t *ptr, const int32_t *idx, const float *w, int64_t n_rows,
                           const kge_heavy_index &hx, const char *name, const void *X, int x_bf16, int32_t d,
-                          const float *Self, int act, float *out, float *out2, float *partial,
+                          const float *Self, int act, float *out, float *out2, uint16_t *outbf, float *partial,
                           const uint8_t *active, hipStream_t st)
 {
     if (n_rows == 0) return KGE_OK;
@@ -1083,7 +1090,7 @@ static int launch_row_sum(const int32_t *ptr, const int32_t *idx, const float *w
     {
         KGE_PROF(name, st);
 #define RS_ARGS ptr, idx, nullptr, w, n_rows, hx.n_units, hx.hv_row, hx.hv_unit_ptr, hx.unit_hv, X, nullptr, 1, d, 1, \
-                Self, act, out, out2, partial, active
+                Self, act, out, out2, outbf, partial, active
         if (x_bf16) { DISPATCH_LPR(lpr, (k_gather_fwd<true, L, true><<<grid, 64 * WPB, 0, st>>>(RS_ARGS))); }
         else { DISPATCH_LPR(lpr, (k_gather_fwd<false, L, true><<<grid, 64 * WPB, 0, st>>>(RS_ARGS))); }
 #undef RS_ARGS
@@ -1093,7 +1100,7 @@ static int launch_row_sum(const int32_t *ptr, const int32_t *idx, const float *w
         KGE_PROF("gather_fwd_fin", st);
         const int64_t n = (int64_t)hx.n_hv * (d / 4);
         k_gather_fwd_finish<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(hx.n_hv, hx.hv_row, hx.hv_unit_ptr, partial, d,
-                                                                   Self, act, out, out2, active);
+                                                                   Self, act, out, out2, outbf, active);
         KGE_LAUNCH_CHECK();
     }
     return KGE_OK;
@@ -1101,10 +1108,10 @@ static int launch_row_sum(const int32_t *ptr, const int32_t *idx, const float *w
 
 // out[i] = act( sum over the runs (r, i) of destination i of U[run][:] + Self[i] )
 int launch_sum_runs(const kge_partition *p, const void *U, int u_bf16, int32_t d, const float *Self, int act,
-                    float *out, float *out2, float *partial, const uint8_t *active, hipStream_t st)
+                    float *out, float *out2, void *out_bf16, float *partial, const uint8_t *active, hipStream_t st)
 {
     return launch_row_sum(p->dr_ptr, p->dr_seg, nullptr, p->n_vert, p->hv_dr, "sum_runs", U, u_bf16, d, Self, act,
-                          out, out2, partial, active, st);
+                          out, out2, reinterpret_cast<uint16_t *>(out_bf16), partial, active, st);
 }
 
 // dH[j] = sum over the edges e out of j of invc_e dZ[run(e)][:] + Self[j]
@@ -1112,7 +1119,7 @@ int launch_sum_edges_out(const kge_partition *p, const void *dZ, int z_bf16, int
                          float *out, float *partial, const uint8_t *active, hipStream_t st)
 {
     return launch_row_sum(p->sm_ptr, p->sm_seg, p->sm_invc, p->n_vert, p->hv_sm, "sum_edges_out", dZ, z_bf16, d, Self,
-                          KGE_ACT_IDENTITY, out, nullptr, partial, active, st);
+                          KGE_ACT_IDENTITY, out, nullptr, nullptr, partial, active, st);
 }
 
 int launch_act_backward(const float *dHout, const float *Hout, int act, int64_t n, float *G, hipStream_t st)
