@@ -831,9 +831,10 @@ __global__ __launch_bounds__(64 * WPB) void k_run_mean_multi(
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] *= w[i];
         if (BF16) {
-            *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(Z) + o) =
-                make_uint4(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
-                           pack_bf16x2(acc[4 % VEC], acc[5 % VEC]), pack_bf16x2(acc[6 % VEC], acc[7 % VEC]));
+            typedef uint32_t rm_u32x4 __attribute__((ext_vector_type(4)));
+            __builtin_nontemporal_store(rm_u32x4{pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
+                                                 pack_bf16x2(acc[4 % VEC], acc[5 % VEC]), pack_bf16x2(acc[6 % VEC], acc[7 % VEC])},
+                                        reinterpret_cast<rm_u32x4 *>(reinterpret_cast<uint16_t *>(Z) + o));
         } else {
             *reinterpret_cast<float4 *>(reinterpret_cast<float *>(Z) + o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
         }
