@@ -746,8 +746,9 @@ __global__ __launch_bounds__(64 * WPB) void k_run_mean(
             make_uint4(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
                        pack_bf16x2(acc[4 % VEC], acc[5 % VEC]), pack_bf16x2(acc[6 % VEC], acc[7 % VEC]));
     } else {
-        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(Z) + rw.row * d + kl * VEC) =
-            make_float4(acc[0], acc[1], acc[2], acc[3]);
+        typedef float rm_f32x4 __attribute__((ext_vector_type(4)));
+        __builtin_nontemporal_store(rm_f32x4{acc[0], acc[1], acc[2], acc[3]},
+                                    reinterpret_cast<rm_f32x4 *>(reinterpret_cast<float *>(Z) + rw.row * d + kl * VEC));
     }
 }
 

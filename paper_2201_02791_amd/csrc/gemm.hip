@@ -127,7 +127,7 @@ struct EpiRowMajor {
     __device__ __forceinline__ void limit_rows(int64_t e) { if (e < rows) rows = e; }
     __device__ __forceinline__ void store(int64_t m, int32_t n, float v) const
     {
-        if (m < rows && n < cols) out[m * cols + n] = v;
+        if (m < rows && n < cols) __builtin_nontemporal_store(v, out + m * cols + n);
     }
 };
 
